@@ -1,0 +1,137 @@
+"""ctypes front-end of the CPU oracle (oracle/knn_softmax_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's CPU-baseline
+leg.  The product package never imports this module, and this module never imports the product.
+All arrays are numpy; floating-point results are fp64.
+"""
+from __future__ import annotations
+
+import ctypes as ct
+import os
+
+import numpy as np
+
+from .build import LIB, build as _build
+
+_lib = None
+
+ORC_OK, ORC_BAD_ARG, ORC_BAD_LABEL, ORC_BAD_GRAPH_ID = 0, 1, 2, 3
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build(force=False) if not os.path.exists(LIB) else LIB
+        _lib = ct.CDLL(path)
+        _lib.orc_num_threads.restype = ct.c_int
+        for name in ("orc_graph_bruteforce", "orc_select_active", "orc_knn_softmax_fwd_bwd",
+                     "orc_full_softmax_fwd_bwd", "orc_apply_weight_grad"):
+            getattr(_lib, name).restype = ct.c_int
+    return _lib
+
+
+def _p(a, typ):
+    return None if a is None else a.ctypes.data_as(ct.POINTER(typ))
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def graph_bruteforce(W, K: int, rows=None):
+    """Exact K nearest neighbours (inner product, self excluded, ties to the lowest id) of `rows`
+    (all rows when None).  Returns (graph int32 [n,K], sims fp64 [n,K])."""
+    W = _f32(W)
+    C, D = W.shape
+    rows_a = None if rows is None else _i32(rows)
+    n = C if rows is None else rows_a.shape[0]
+    graph = np.empty((n, K), dtype=np.int32)
+    sims = np.empty((n, K), dtype=np.float64)
+    rc = lib().orc_graph_bruteforce(_p(W, ct.c_float), ct.c_int64(C), ct.c_int(D), ct.c_int(K),
+                                    _p(rows_a, ct.c_int32), ct.c_int64(n), _p(graph, ct.c_int32),
+                                    _p(sims, ct.c_double))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_graph_bruteforce failed with code {rc}")
+    return graph, sims
+
+
+def select_active(labels, G, C: int, M: int):
+    """Algorithm 1 without the random fill-up.  Returns (active int32 [M] padded with -1, n_active,
+    target_pos int32 [B])."""
+    labels = _i32(labels)
+    G = _i32(G)
+    B = labels.shape[0]
+    K = G.shape[1] if G.ndim == 2 else 0
+    active = np.empty(M, dtype=np.int32)
+    n_active = ct.c_int32(0)
+    target_pos = np.empty(B, dtype=np.int32)
+    rc = lib().orc_select_active(_p(labels, ct.c_int32), ct.c_int(B), _p(G, ct.c_int32), ct.c_int64(C),
+                                 ct.c_int(K), ct.c_int(M), _p(active, ct.c_int32), ct.byref(n_active),
+                                 _p(target_pos, ct.c_int32))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_select_active failed with code {rc}")
+    return active, int(n_active.value), target_pos
+
+
+def knn_softmax_fwd_bwd(W, X, active, target_pos, scale: float, grad_scale: float = 1.0,
+                        want_P: bool = False):
+    """Softmax/CE forward and backward on the active columns.  `active` holds exactly the A valid ids.
+    Returns dict(loss_i [B], loss, dX [B,D], dWA [A,D], lse [B], P [B,A] or None), all fp64."""
+    W, X = _f32(W), _f32(X)
+    active, target_pos = _i32(active), _i32(target_pos)
+    A, (B, D) = active.shape[0], X.shape
+    loss_i = np.empty(B, dtype=np.float64)
+    loss = ct.c_double(0.0)
+    dX = np.empty((B, D), dtype=np.float64)
+    dWA = np.empty((A, D), dtype=np.float64)
+    lse = np.empty(B, dtype=np.float64)
+    P = np.empty((B, A), dtype=np.float64) if want_P else None
+    rc = lib().orc_knn_softmax_fwd_bwd(_p(W, ct.c_float), _p(X, ct.c_float), _p(active, ct.c_int32),
+                                       ct.c_int(A), _p(target_pos, ct.c_int32), ct.c_int(B), ct.c_int(D),
+                                       ct.c_double(scale), ct.c_double(grad_scale), _p(loss_i, ct.c_double),
+                                       ct.byref(loss), _p(dX, ct.c_double), _p(dWA, ct.c_double),
+                                       _p(P, ct.c_double), _p(lse, ct.c_double))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_knn_softmax_fwd_bwd failed with code {rc}")
+    return dict(loss_i=loss_i, loss=float(loss.value), dX=dX, dWA=dWA, lse=lse, P=P)
+
+
+def full_softmax_fwd_bwd(W, X, labels, scale: float, grad_scale: float = 1.0):
+    """Full softmax over all classes.  Returns dict(loss_i, loss, dX [B,D], dW [C,D]), fp64."""
+    W, X, labels = _f32(W), _f32(X), _i32(labels)
+    (C, D), B = W.shape, X.shape[0]
+    loss_i = np.empty(B, dtype=np.float64)
+    loss = ct.c_double(0.0)
+    dX = np.empty((B, D), dtype=np.float64)
+    dW = np.empty((C, D), dtype=np.float64)
+    rc = lib().orc_full_softmax_fwd_bwd(_p(W, ct.c_float), _p(X, ct.c_float), _p(labels, ct.c_int32),
+                                        ct.c_int64(C), ct.c_int(B), ct.c_int(D), ct.c_double(scale),
+                                        ct.c_double(grad_scale), _p(loss_i, ct.c_double), ct.byref(loss),
+                                        _p(dX, ct.c_double), _p(dW, ct.c_double))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_full_softmax_fwd_bwd failed with code {rc}")
+    return dict(loss_i=loss_i, loss=float(loss.value), dX=dX, dW=dW)
+
+
+def apply_weight_grad(W_master, idx, dW, alpha: float, want_bf16: bool = True):
+    """W[c] += alpha * sum of the rows of dW addressed to c.  Returns (new fp32 master copy, bf16 bit
+    patterns uint16 of the touched rows written into a copy that is zero elsewhere, or None).  The input
+    array is not modified."""
+    Wm = _f32(W_master).copy()
+    idx, dW = _i32(idx), _f32(dW)
+    C, D = Wm.shape
+    n = idx.shape[0]
+    Wb = np.zeros((C, D), dtype=np.uint16) if want_bf16 else None
+    rc = lib().orc_apply_weight_grad(_p(Wm, ct.c_float), _p(Wb, ct.c_uint16), _p(idx, ct.c_int32), ct.c_int(n),
+                                     _p(dW, ct.c_float), ct.c_double(alpha), ct.c_int64(C), ct.c_int(D))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_apply_weight_grad failed with code {rc}")
+    return Wm, Wb

@@ -1,0 +1,342 @@
+/*
+ * CPU oracle for the KNN-softmax output layer (paper: "Large-Scale Training System for 100-Million
+ * Classification at Alibaba", Section 3.2 "KNN Softmax", Algorithm 1, Section 3.1 steps 3-6).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, obviously-correct statement of
+ * what the GPU path must compute: fp32 storage of inputs, every accumulation in fp64, no blocking, no
+ * fusion, no BLAS.  It shares no code with the HIP library and is only called from tests, from the
+ * smoke check and from the benchmark's CPU-baseline leg.
+ *
+ * Every function below is pinned by tests that do not go through this file's own formulas
+ * (full-softmax equality when K spans all classes, a library cross-entropy in fp64, closed forms,
+ * finite differences, set-based selection, argsort-based neighbour search, dense index_add).
+ *
+ * Readings taken where the paper is silent (each is also listed in the design notes):
+ *   - logits are scale * <x, w> with the scale given by the caller; no margin;
+ *   - X and W are used as given (callers pass L2-normalised rows); gradients are w.r.t. the given rows;
+ *   - neighbour lists hold K classes other than the class itself; selection always adds the label
+ *     itself with rank 0 (same set as the paper's lists, in which the class itself is ranked first);
+ *   - "ranking score" used to cut the set down to M = best (smallest) position of the class in any
+ *     contributing list, ties to the lowest class id; the active list is emitted in ascending id;
+ *   - similarity for ranking neighbours = sum over d ascending of (double)w_id * (double)w_jd;
+ *     ties go to the lowest class id; lists are in descending similarity;
+ *   - loss is the mean over the batch; grad_scale multiplies gradients only;
+ *   - the weight update is W[c] += alpha * (sum of the gradient rows addressed to c).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <limits.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_OK 0
+#define ORC_BAD_ARG 1
+#define ORC_BAD_LABEL 2
+#define ORC_BAD_GRAPH_ID 3
+
+int orc_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Section 3.2.2 (graph building by linear search): similarity of two weight rows is their inner
+ * product.  Canonical arithmetic: fp64, one term at a time, d ascending.
+ * ------------------------------------------------------------------------------------------- */
+static double row_similarity(const float *wi, const float *wj, int D) {
+    double acc = 0.0;
+    for (int d = 0; d < D; ++d) acc += (double)wi[d] * (double)wj[d];
+    return acc;
+}
+
+/* is candidate (s, j) ranked before (t, k)?  higher similarity first, then lower class id */
+static int ranks_before(double s, int32_t j, double t, int32_t k) {
+    if (s > t) return 1;
+    if (s < t) return 0;
+    return j < k;
+}
+
+/*
+ * Brute-force K nearest neighbours (Section 3.2.2: "linear search", exact) of the rows listed in
+ * `rows` (or of every row when rows == NULL) among all C rows of W, the row itself excluded.
+ * graph_out [n_rows, K] int32, sims_out [n_rows, K] fp64 (may be NULL), both in rank order.
+ */
+int orc_graph_bruteforce(const float *W, int64_t C, int D, int K, const int32_t *rows, int64_t n_rows,
+                         int32_t *graph_out, double *sims_out) {
+    if (!W || !graph_out || C < 2 || D < 1 || K < 1 || K > C - 1) return ORC_BAD_ARG;
+    if (!rows) n_rows = C;
+    int bad = 0;
+#pragma omp parallel for schedule(dynamic, 4) reduction(| : bad)
+    for (int64_t r = 0; r < n_rows; ++r) {
+        int64_t i = rows ? rows[r] : r;
+        if (i < 0 || i >= C) { bad = 1; continue; }
+        double *best_s = (double *)malloc(sizeof(double) * (size_t)K);
+        int32_t *best_j = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
+        int n = 0;
+        for (int64_t j = 0; j < C; ++j) {
+            if (j == i) continue;
+            double s = row_similarity(W + i * D, W + j * D, D);
+            if (n == K && !ranks_before(s, (int32_t)j, best_s[K - 1], best_j[K - 1])) continue;
+            /* insert into the sorted list of the best so far */
+            int pos = (n < K) ? n : K - 1;
+            while (pos > 0 && ranks_before(s, (int32_t)j, best_s[pos - 1], best_j[pos - 1])) {
+                best_s[pos] = best_s[pos - 1];
+                best_j[pos] = best_j[pos - 1];
+                --pos;
+            }
+            best_s[pos] = s;
+            best_j[pos] = (int32_t)j;
+            if (n < K) ++n;
+        }
+        for (int k = 0; k < K; ++k) {
+            graph_out[r * K + k] = best_j[k];
+            if (sims_out) sims_out[r * K + k] = best_s[k];
+        }
+        free(best_s);
+        free(best_j);
+    }
+    return bad ? ORC_BAD_ARG : ORC_OK;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Algorithm 1 (KNN graph-based active classes selection), without the random fill-up branch:
+ * the union of the labels' neighbour lists (each list headed by the label itself), duplicates
+ * removed; when more than M classes remain, the M with the best ranking score are kept.
+ *   active [M]   ascending class ids, first *n_active valid, the rest set to -1
+ *   target_pos[B] position of label i inside active
+ * Graph entries equal to -1 are empty slots.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct { int32_t score; int32_t cls; } scored_class;
+
+static int cmp_scored(const void *a, const void *b) {
+    const scored_class *x = (const scored_class *)a, *y = (const scored_class *)b;
+    if (x->score != y->score) return x->score < y->score ? -1 : 1;
+    return (x->cls > y->cls) - (x->cls < y->cls);
+}
+static int cmp_i32(const void *a, const void *b) {
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+int orc_select_active(const int32_t *labels, int B, const int32_t *G, int64_t C, int K, int M,
+                      int32_t *active, int32_t *n_active, int32_t *target_pos) {
+    if (!labels || !G || !active || !n_active || !target_pos) return ORC_BAD_ARG;
+    if (B < 1 || C < 1 || K < 0 || M < 1 || B > M || K + 1 > M) return ORC_BAD_ARG;
+    int32_t *score = (int32_t *)malloc(sizeof(int32_t) * (size_t)C);
+    for (int64_t c = 0; c < C; ++c) score[c] = INT32_MAX; /* INT32_MAX = not a candidate */
+    int rc = ORC_OK;
+    for (int i = 0; i < B && rc == ORC_OK; ++i) {
+        int32_t y = labels[i];
+        if (y < 0 || y >= C) { rc = ORC_BAD_LABEL; break; }
+        score[y] = 0; /* the class itself heads its own list */
+        for (int k = 0; k < K; ++k) {
+            int32_t c = G[(int64_t)y * K + k];
+            if (c == -1) continue;
+            if (c < -1 || c >= C) { rc = ORC_BAD_GRAPH_ID; break; }
+            if (k + 1 < score[c]) score[c] = k + 1;
+        }
+    }
+    if (rc != ORC_OK) { free(score); return rc; }
+    int64_t n_unique = 0;
+    for (int64_t c = 0; c < C; ++c) n_unique += (score[c] != INT32_MAX);
+    scored_class *u = (scored_class *)malloc(sizeof(scored_class) * (size_t)(n_unique ? n_unique : 1));
+    int64_t n = 0;
+    for (int64_t c = 0; c < C; ++c)
+        if (score[c] != INT32_MAX) { u[n].score = score[c]; u[n].cls = (int32_t)c; ++n; }
+    int64_t A = n_unique;
+    if (n_unique > M) { /* keep the M best-scored classes */
+        qsort(u, (size_t)n_unique, sizeof(scored_class), cmp_scored);
+        A = M;
+    }
+    for (int64_t a = 0; a < A; ++a) active[a] = u[a].cls;
+    qsort(active, (size_t)A, sizeof(int32_t), cmp_i32);
+    for (int64_t a = A; a < M; ++a) active[a] = -1;
+    *n_active = (int32_t)A;
+    for (int i = 0; i < B; ++i) {
+        target_pos[i] = -1;
+        for (int64_t a = 0; a < A; ++a)
+            if (active[a] == labels[i]) { target_pos[i] = (int32_t)a; break; }
+        if (target_pos[i] < 0) rc = ORC_BAD_ARG; /* cannot happen when B <= M */
+    }
+    free(u);
+    free(score);
+    return rc;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Softmax stage on the active classes (Section 3.2: fc forward, softmax forward, softmax backward,
+ * fc backward; standard softmax with cross-entropy restricted to the selected columns).
+ *   Z_ia   = scale * sum_d X_id * W[active[a], d]
+ *   lse_i  = max_a Z_ia + log sum_a exp(Z_ia - max)
+ *   loss_i = lse_i - Z_{i, target_pos[i]},  loss = mean_i loss_i
+ *   P_ia   = exp(Z_ia - lse_i),  dZ_ia = (grad_scale / B) * (P_ia - [a == target_pos[i]])
+ *   dX_id  = scale * sum_a dZ_ia * W[active[a], d]
+ *   dWA_ad = scale * sum_i dZ_ia * X_id
+ * Outputs are fp64.  P_out [B, A] and lse_out [B] are optional (NULL to skip).
+ * ------------------------------------------------------------------------------------------- */
+int orc_knn_softmax_fwd_bwd(const float *W, const float *X, const int32_t *active, int A,
+                            const int32_t *target_pos, int B, int D, double scale, double grad_scale,
+                            double *loss_i, double *loss_mean, double *dX, double *dWA,
+                            double *P_out, double *lse_out) {
+    if (!W || !X || !active || !target_pos || !loss_i || !loss_mean || !dX || !dWA) return ORC_BAD_ARG;
+    if (A < 1 || B < 1 || D < 1) return ORC_BAD_ARG;
+    double *dZ = (double *)malloc(sizeof(double) * (size_t)B * (size_t)A);
+    if (!dZ) return ORC_BAD_ARG;
+    const double g = grad_scale / (double)B;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < B; ++i) {
+        double *z = dZ + (size_t)i * A; /* holds Z_i first, then dZ_i */
+        for (int a = 0; a < A; ++a) {
+            const float *w = W + (int64_t)active[a] * D;
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d) acc += (double)X[(size_t)i * D + d] * (double)w[d];
+            z[a] = scale * acc;
+        }
+        double m = z[0];
+        for (int a = 1; a < A; ++a) if (z[a] > m) m = z[a];
+        double sum = 0.0;
+        for (int a = 0; a < A; ++a) sum += exp(z[a] - m);
+        double lse = m + log(sum);
+        loss_i[i] = lse - z[target_pos[i]];
+        if (lse_out) lse_out[i] = lse;
+        for (int a = 0; a < A; ++a) {
+            double p = exp(z[a] - lse);
+            if (P_out) P_out[(size_t)i * A + a] = p;
+            z[a] = g * (p - (a == target_pos[i] ? 1.0 : 0.0));
+        }
+    }
+    double tot = 0.0;
+    for (int i = 0; i < B; ++i) tot += loss_i[i];
+    *loss_mean = tot / (double)B;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < B; ++i) {
+        double *out = dX + (size_t)i * D;
+        for (int d = 0; d < D; ++d) out[d] = 0.0;
+        for (int a = 0; a < A; ++a) {
+            const float *w = W + (int64_t)active[a] * D;
+            double dz = dZ[(size_t)i * A + a];
+            for (int d = 0; d < D; ++d) out[d] += dz * (double)w[d];
+        }
+        for (int d = 0; d < D; ++d) out[d] *= scale;
+    }
+#pragma omp parallel for schedule(static)
+    for (int a = 0; a < A; ++a) {
+        double *out = dWA + (size_t)a * D;
+        for (int d = 0; d < D; ++d) out[d] = 0.0;
+        for (int i = 0; i < B; ++i) {
+            double dz = dZ[(size_t)i * A + a];
+            for (int d = 0; d < D; ++d) out[d] += dz * (double)X[(size_t)i * D + d];
+        }
+        for (int d = 0; d < D; ++d) out[d] *= scale;
+    }
+    free(dZ);
+    return ORC_OK;
+}
+
+/*
+ * Full softmax over all C classes (the baseline the paper compares against; Section 3.2 claims the
+ * KNN variant equals it on the selected columns).  Written separately from the function above on
+ * purpose: dense columns, label used directly, dense dW [C, D].
+ */
+int orc_full_softmax_fwd_bwd(const float *W, const float *X, const int32_t *labels, int64_t C, int B, int D,
+                             double scale, double grad_scale, double *loss_i, double *loss_mean,
+                             double *dX, double *dW) {
+    if (!W || !X || !labels || !loss_i || !loss_mean || !dX || !dW) return ORC_BAD_ARG;
+    double *P = (double *)malloc(sizeof(double) * (size_t)B * (size_t)C);
+    if (!P) return ORC_BAD_ARG;
+    const double g = grad_scale / (double)B;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < B; ++i) {
+        double *z = P + (size_t)i * C;
+        double m = -INFINITY;
+        for (int64_t c = 0; c < C; ++c) {
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d) acc += (double)X[(size_t)i * D + d] * (double)W[c * D + d];
+            z[c] = scale * acc;
+            if (z[c] > m) m = z[c];
+        }
+        double sum = 0.0;
+        for (int64_t c = 0; c < C; ++c) sum += exp(z[c] - m);
+        double lse = m + log(sum);
+        loss_i[i] = lse - z[labels[i]];
+        for (int64_t c = 0; c < C; ++c) z[c] = exp(z[c] - lse);
+    }
+    double tot = 0.0;
+    for (int i = 0; i < B; ++i) tot += loss_i[i];
+    *loss_mean = tot / (double)B;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < B; ++i) {
+        for (int d = 0; d < D; ++d) {
+            double acc = 0.0;
+            for (int64_t c = 0; c < C; ++c) {
+                double dz = g * (P[(size_t)i * C + c] - (c == labels[i] ? 1.0 : 0.0));
+                acc += dz * (double)W[c * D + d];
+            }
+            dX[(size_t)i * D + d] = scale * acc;
+        }
+    }
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < C; ++c) {
+        for (int d = 0; d < D; ++d) {
+            double acc = 0.0;
+            for (int i = 0; i < B; ++i) {
+                double dz = g * (P[(size_t)i * C + c] - (c == labels[i] ? 1.0 : 0.0));
+                acc += dz * (double)X[(size_t)i * D + d];
+            }
+            dW[c * D + d] = scale * acc;
+        }
+    }
+    free(P);
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------------------------------------
+ * Local weight update of the model-parallel fc layer (Section 3.1 step 6; fp32 copy of the
+ * parameters is the one updated, the 16-bit copy is refreshed from it):
+ *   for every class c named in idx: Wm[c,:] += alpha * sum_{p: idx[p]==c} dW[p,:]
+ * the sum taken in ascending p in fp64, the result stored as fp32; then Wb[c,:] = bf16(Wm[c,:])
+ * by round-to-nearest-even.  Rows not named in idx are not touched.
+ * ------------------------------------------------------------------------------------------- */
+static uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u); /* NaN stays NaN */
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7FFFu + lsb;
+    return (uint16_t)(u >> 16);
+}
+
+int orc_apply_weight_grad(float *Wm, uint16_t *Wb, const int32_t *idx, int n, const float *dW, double alpha,
+                          int64_t C, int D) {
+    if (!Wm || !idx || !dW || n < 0 || D < 1) return ORC_BAD_ARG;
+    for (int p = 0; p < n; ++p) if (idx[p] < 0 || idx[p] >= C) return ORC_BAD_LABEL;
+    int32_t *slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)C);
+    for (int64_t c = 0; c < C; ++c) slot[c] = -1;
+    int n_distinct = 0;
+    for (int p = 0; p < n; ++p) if (slot[idx[p]] < 0) slot[idx[p]] = n_distinct++;
+    double *sum = (double *)calloc((size_t)(n_distinct ? n_distinct : 1) * (size_t)D, sizeof(double));
+    for (int p = 0; p < n; ++p) { /* ascending p */
+        double *s = sum + (size_t)slot[idx[p]] * D;
+        for (int d = 0; d < D; ++d) s[d] += (double)dW[(size_t)p * D + d];
+    }
+    for (int p = 0; p < n; ++p) {
+        int32_t c = idx[p];
+        if (slot[c] < 0) continue; /* already applied */
+        const double *s = sum + (size_t)slot[c] * D;
+        for (int d = 0; d < D; ++d) {
+            float w = (float)((double)Wm[(int64_t)c * D + d] + alpha * s[d]);
+            Wm[(int64_t)c * D + d] = w;
+            if (Wb) Wb[(int64_t)c * D + d] = f32_to_bf16_rne(w);
+        }
+        slot[c] = -1;
+    }
+    free(sum);
+    free(slot);
+    return ORC_OK;
+}

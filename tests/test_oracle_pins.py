@@ -1,0 +1,351 @@
+"""Pins for the CPU oracle: every oracle function is checked against something that is not its own
+formula -- the full-softmax special case (paper Section 3.2: KNN softmax is standard softmax on the
+selected columns), a library cross-entropy with autograd in fp64, closed forms, invariants, finite
+differences, set-based selection, argsort-based neighbour search with exactly representable
+similarities, and a dense index_add."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth
+
+
+# --------------------------------------------------------------------------------------------
+# softmax / cross-entropy / gradients
+# --------------------------------------------------------------------------------------------
+def _small_problem(C=2000, D=32, B=16, seed=3):
+    W = synth.unit_rows(seed, synth.TID_W, C, D)
+    X = synth.unit_rows(seed, synth.TID_X, B, D)
+    y = synth.labels_uniform(seed, B, C)
+    return W, X, y
+
+
+def test_knn_softmax_equals_full_softmax_when_lists_span_all_classes(orc):
+    # Section 3.2: same result as standard softmax.  K = C-1 (+ the class itself) makes every class active.
+    C, D, B = 2000, 32, 16
+    W, X, y = _small_problem(C, D, B)
+    G = synth.graph_all_others(C)
+    active, A, tpos = orc.select_active(y, G, C, M=C)
+    assert A == C and (active == np.arange(C)).all() and (tpos == y).all()
+    knn = orc.knn_softmax_fwd_bwd(W, X, active[:A], tpos, scale=30.0, grad_scale=2.0)
+    full = orc.full_softmax_fwd_bwd(W, X, y, scale=30.0, grad_scale=2.0)
+    # same summation order in both functions => bit-equal
+    assert knn["loss"] == full["loss"]
+    assert (knn["loss_i"] == full["loss_i"]).all()
+    assert (knn["dX"] == full["dX"]).all()
+    assert (knn["dWA"] == full["dW"]).all()
+
+
+def _torch_ce(W, X, cols, tgt, scale, grad_scale):
+    Wt = torch.tensor(W[cols], dtype=torch.float64, requires_grad=True)
+    Xt = torch.tensor(X, dtype=torch.float64, requires_grad=True)
+    Z = scale * Xt @ Wt.T
+    li = torch.nn.functional.cross_entropy(Z, torch.tensor(tgt, dtype=torch.long), reduction="none")
+    loss = li.mean()
+    (grad_scale * loss).backward()
+    return li.detach().numpy(), float(loss.detach()), Xt.grad.numpy(), Wt.grad.numpy()
+
+
+def test_full_softmax_matches_library_cross_entropy_fp64(orc):
+    # the "tiny" configuration: C=10,000, D=128, B=64, s=30
+    cfg = synth.CONFIGS["tiny"]
+    W, X = synth.make_WX(cfg)
+    y = synth.make_labels(cfg)
+    full = orc.full_softmax_fwd_bwd(W, X, y, scale=cfg["scale"], grad_scale=1.0)
+    li, loss, gX, gW = _torch_ce(W, X, np.arange(cfg["C"]), y, cfg["scale"], 1.0)
+    assert np.allclose(full["loss_i"], li, rtol=1e-12, atol=1e-12)
+    assert abs(full["loss"] - loss) <= 1e-12 * abs(loss)
+    assert np.allclose(full["dX"], gX, rtol=1e-10, atol=1e-14)
+    assert np.allclose(full["dW"], gW, rtol=1e-10, atol=1e-14)
+
+
+def test_knn_softmax_matches_library_cross_entropy_on_active_columns(orc):
+    cfg = synth.CONFIGS["tiny"]
+    W, X = synth.make_WX(cfg)
+    y = synth.make_labels(cfg)
+    G = synth.graph_synthetic(7, cfg["C"], cfg["K"])
+    active, A, tpos = orc.select_active(y, G, cfg["C"], cfg["M"])
+    out = orc.knn_softmax_fwd_bwd(W, X, active[:A], tpos, scale=30.0, grad_scale=128.0)
+    li, loss, gX, gW = _torch_ce(W, X, active[:A], tpos, 30.0, 128.0)
+    assert np.allclose(out["loss_i"], li, rtol=1e-12, atol=1e-12)
+    assert abs(out["loss"] - loss) <= 1e-12 * abs(loss)
+    assert np.allclose(out["dX"], gX, rtol=1e-10, atol=1e-13)
+    assert np.allclose(out["dWA"], gW, rtol=1e-10, atol=1e-13)
+
+
+def test_closed_form_zero_features(orc):
+    # X = 0 => all logits 0 => loss = ln A, P = 1/A, dZ = g (1/A - onehot), dX = s g (mean_a w_a - w_y)
+    C, D, B, A = 500, 16, 4, 37
+    W = synth.unit_rows(1, synth.TID_W, C, D)
+    X = np.zeros((B, D), dtype=np.float32)
+    active = np.sort(synth.class_permutation(1, C)[:A]).astype(np.int32)
+    tpos = np.array([0, 5, 36, 5], dtype=np.int32)
+    s, gs = 30.0, 3.0
+    out = orc.knn_softmax_fwd_bwd(W, X, active, tpos, scale=s, grad_scale=gs, want_P=True)
+    assert np.allclose(out["loss_i"], math.log(A), rtol=0, atol=1e-14)
+    assert np.allclose(out["P"], 1.0 / A, rtol=0, atol=1e-15)
+    WA = W[active].astype(np.float64)
+    exp_dX = s * (gs / B) * (WA.mean(axis=0)[None, :] - WA[tpos])
+    assert np.allclose(out["dX"], exp_dX, rtol=1e-12, atol=1e-15)
+    assert np.allclose(out["dWA"], 0.0, atol=0)  # dWA = s dZ^T X with X = 0
+
+
+def test_closed_form_single_active_class(orc):
+    C, D, B = 50, 8, 3
+    W, X, _ = _small_problem(C, D, B)
+    out = orc.knn_softmax_fwd_bwd(W, X, np.array([17], dtype=np.int32), np.zeros(B, dtype=np.int32), 30.0, 1.0)
+    assert (out["loss_i"] == 0).all() and out["loss"] == 0
+    assert (out["dX"] == 0).all() and (out["dWA"] == 0).all()
+
+
+def test_two_class_closed_form_and_no_overflow(orc):
+    # x = w_0, w_1 = -w_0, s = 30: logits (30, -30); loss = log(1 + e^-60); P_1 = e^-60/(1+e^-60)
+    D = 8
+    w0 = np.zeros(D, dtype=np.float32)
+    w0[2] = 1.0
+    W = np.stack([w0, -w0])
+    X = w0[None, :].copy()
+    out = orc.knn_softmax_fwd_bwd(W, X, np.array([0, 1], dtype=np.int32), np.array([0], dtype=np.int32), 30.0, 1.0,
+                                  want_P=True)
+    e = math.exp(-60.0)
+    assert out["loss"] == pytest.approx(math.log1p(e), rel=1e-12)
+    assert out["P"][0, 1] == pytest.approx(e / (1 + e), rel=1e-12)
+    # dX = s * (P0 w0 + P1 w1 - w0) = s * (-2 P1) w0
+    assert out["dX"][0, 2] == pytest.approx(30.0 * (-2 * e / (1 + e)), rel=1e-10)
+    # much larger spread still finite
+    big = orc.knn_softmax_fwd_bwd(W, X, np.array([0, 1], dtype=np.int32), np.array([1], dtype=np.int32), 5000.0, 1.0)
+    assert np.isfinite(big["loss"]) and big["loss"] == pytest.approx(10000.0, rel=1e-12)
+    assert np.isfinite(big["dX"]).all() and np.isfinite(big["dWA"]).all()
+
+
+def test_softmax_invariants(orc):
+    cfg = synth.CONFIGS["tiny"]
+    W, X = synth.make_WX(cfg)
+    y = synth.make_labels(cfg)
+    G = synth.graph_synthetic(11, cfg["C"], cfg["K"])
+    active, A, tpos = orc.select_active(y, G, cfg["C"], cfg["M"])
+    s, gs = 30.0, 1.0
+    out = orc.knn_softmax_fwd_bwd(W, X, active[:A], tpos, s, gs, want_P=True)
+    P = out["P"]
+    assert np.abs(P.sum(axis=1) - 1.0).max() <= 1e-12
+    assert (P >= 0).all()
+    # sum_a dZ_ia = 0  =>  column sums of dWA vanish
+    assert np.abs(out["dWA"].sum(axis=0)).max() <= 1e-13
+    # dX_i = s g (sum_a P_ia w_a - w_{y_i})
+    WA = W[active[:A]].astype(np.float64)
+    exp_dX = s * (gs / cfg["B"]) * (P @ WA - WA[tpos])
+    assert np.allclose(out["dX"], exp_dX, rtol=1e-10, atol=1e-14)
+    # loss_i = -log P_{i, target}
+    assert np.allclose(out["loss_i"], -np.log(P[np.arange(cfg["B"]), tpos]), rtol=1e-12, atol=1e-12)
+    # grad_scale multiplies gradients only
+    out2 = orc.knn_softmax_fwd_bwd(W, X, active[:A], tpos, s, 4.0)
+    assert out2["loss"] == out["loss"]
+    assert np.allclose(out2["dX"], 4.0 * out["dX"], rtol=1e-14, atol=0)
+    assert np.allclose(out2["dWA"], 4.0 * out["dWA"], rtol=1e-14, atol=0)
+
+
+def test_gradients_by_finite_differences(orc):
+    # inputs on a 2^-12 grid and h a power of two, so that x +- h is exact in fp32; Richardson
+    # extrapolation of the central difference removes the h^2 term
+    C, D, B, A = 300, 16, 6, 40
+    rng = np.random.default_rng(5)
+    W = (np.round(rng.normal(0, 0.25, (C, D)) * 4096) / 4096).astype(np.float32)
+    X = (np.round(rng.normal(0, 0.25, (B, D)) * 4096) / 4096).astype(np.float32)
+    active = np.sort(rng.choice(C, A, replace=False)).astype(np.int32)
+    tpos = rng.integers(0, A, B).astype(np.int32)
+    s, gs = 8.0, 1.0
+    base = orc.knn_softmax_fwd_bwd(W, X, active, tpos, s, gs)
+
+    def loss_with(Wp, Xp):
+        return orc.knn_softmax_fwd_bwd(Wp, Xp, active, tpos, s, gs)["loss"]
+
+    def fd(which, r, d):
+        vals = []
+        for h in (2.0 ** -6, 2.0 ** -7):
+            Wp, Wm_, Xp, Xm_ = W.copy(), W.copy(), X.copy(), X.copy()
+            if which == "W":
+                Wp[r, d] += h
+                Wm_[r, d] -= h
+            else:
+                Xp[r, d] += h
+                Xm_[r, d] -= h
+            vals.append((loss_with(Wp, Xp) - loss_with(Wm_, Xm_)) / (2 * h))
+        return (4 * vals[1] - vals[0]) / 3
+
+    inactive = np.setdiff1d(np.arange(C), active)
+    for _ in range(64):
+        i, d = int(rng.integers(B)), int(rng.integers(D))
+        assert fd("X", i, d) == pytest.approx(base["dX"][i, d], rel=2e-4, abs=1e-7)
+        a, d = int(rng.integers(A)), int(rng.integers(D))
+        assert fd("W", int(active[a]), d) == pytest.approx(base["dWA"][a, d], rel=2e-4, abs=1e-7)
+        c, d = int(rng.choice(inactive)), int(rng.integers(D))
+        assert fd("W", c, d) == 0.0  # classes outside the active set do not enter the loss
+
+
+# --------------------------------------------------------------------------------------------
+# Algorithm 1: selection
+# --------------------------------------------------------------------------------------------
+def _select_by_sets(labels, G, C, M):
+    score = {}
+    for y in labels.tolist():
+        score[y] = 0
+    for y in labels.tolist():
+        for k, c in enumerate(G[y].tolist()):
+            if c == -1:
+                continue
+            score[c] = min(score.get(c, 1 << 30), k + 1)
+    classes = sorted(score)
+    if len(classes) > M:
+        classes = sorted(sorted(classes, key=lambda c: (score[c], c))[:M])
+    pos = {c: a for a, c in enumerate(classes)}
+    return np.array(classes, dtype=np.int32), np.array([pos[y] for y in labels.tolist()], dtype=np.int32)
+
+
+@pytest.mark.parametrize("C,K,B,M,seed,empty", [(500, 8, 16, 400, 0, 0.0), (500, 8, 64, 100, 1, 0.0),
+                                                (3000, 16, 128, 600, 2, 0.3), (64, 63, 8, 64, 3, 0.0),
+                                                (200, 5, 200, 200, 4, 0.0)])
+def test_selection_matches_set_based_definition(orc, C, K, B, M, seed, empty):
+    G = synth.graph_synthetic(seed, C, K, locality=4, empty_frac=empty)
+    y = synth.labels_uniform(seed, B, C)
+    active, A, tpos = orc.select_active(y, G, C, M)
+    exp_active, exp_tpos = _select_by_sets(y, G, C, M)
+    assert A == len(exp_active) <= M
+    assert (active[:A] == exp_active).all() and (active[A:] == -1).all()
+    assert (tpos == exp_tpos).all()
+    assert (active[tpos] == y).all()  # the label itself always survives (it heads its own list)
+    assert (np.diff(active[:A]) > 0).all()
+
+
+def test_selection_hand_built_cases(orc):
+    C, K = 20, 3
+    G = np.array([[(c + 1) % C, (c + 2) % C, (c + 3) % C] for c in range(C)], dtype=np.int32)
+    # all labels equal: A = 1 + number of distinct neighbours
+    a, A, t = orc.select_active(np.array([4, 4, 4], dtype=np.int32), G, C, 10)
+    assert A == 4 and a[:4].tolist() == [4, 5, 6, 7] and t.tolist() == [0, 0, 0]
+    # union of labels 4 and 6: {4,5,6,7,8,9}; scores: 4:0 5:1 6:0 7:1(from 6) 8:2 9:3
+    y = np.array([4, 6], dtype=np.int32)
+    a, A, t = orc.select_active(y, G, C, 6)        # M == |U|
+    assert A == 6 and a[:6].tolist() == [4, 5, 6, 7, 8, 9]
+    a, A, t = orc.select_active(y, G, C, 5)        # M == |U| - 1: the worst score (class 9, score 3) goes
+    assert A == 5 and a[:5].tolist() == [4, 5, 6, 7, 8] and t.tolist() == [0, 2]
+    # class 7 has rank 3 in list_4 but rank 1 in list_6: its score is 1, so it survives a cut to 4
+    a, A, t = orc.select_active(y, G, C, 4)
+    assert a[:4].tolist() == [4, 5, 6, 7]
+    # ties in score go to the lowest class id: cut to 3 keeps 4 and 6 (score 0) and 5 (score 1, id < 7)
+    a, A, t = orc.select_active(y, G, C, 3)
+    assert a[:3].tolist() == [4, 5, 6] and t.tolist() == [0, 2]
+    G2 = G.copy()
+    G2[4] = [-1, 9, -1]                           # empty slots are skipped, ranks keep their column
+    a, A, t = orc.select_active(np.array([4], dtype=np.int32), G2, C, 10)
+    assert A == 2 and a[:2].tolist() == [4, 9]
+    with pytest.raises(ValueError):
+        orc.select_active(np.array([C], dtype=np.int32), G, C, 10)      # label out of range
+    with pytest.raises(ValueError):
+        orc.select_active(np.array([1, 2, 3], dtype=np.int32), G, C, 2)  # B > M
+
+
+def test_selection_cut_tie_break_lowest_id(orc):
+    C, K = 30, 2
+    G = np.zeros((C, K), dtype=np.int32)
+    G[:] = [[(c + 10) % C, (c + 20) % C] for c in range(C)]
+    y = np.array([0, 1, 2], dtype=np.int32)
+    # scores: 0,1,2 -> 0; 10,11,12 -> 1; 20,21,22 -> 2.  M = 5 keeps {0,1,2} + two lowest ids of score 1
+    a, A, t = orc.select_active(y, G, C, 5)
+    assert a[:A].tolist() == [0, 1, 2, 10, 11]
+    a, A, t = orc.select_active(y, G, C, 7)
+    assert a[:A].tolist() == [0, 1, 2, 10, 11, 12, 20]
+
+
+# --------------------------------------------------------------------------------------------
+# Section 3.2.2: neighbour search
+# --------------------------------------------------------------------------------------------
+def _graph_by_argsort(W64, K):
+    S = W64 @ W64.T
+    np.fill_diagonal(S, -np.inf)
+    C = S.shape[0]
+    ids = np.arange(C)
+    out = np.empty((C, K), dtype=np.int32)
+    for i in range(C):
+        order = np.lexsort((ids, -S[i]))     # by similarity descending, then id ascending
+        out[i] = order[:K]
+    return out, S
+
+
+def test_graph_matches_argsort_on_exact_integer_similarities(orc):
+    # small integer entries: every inner product is an exact small integer in any summation order,
+    # so there are masses of exact ties and the expected lists are unambiguous
+    rng = np.random.default_rng(0)
+    C, D, K = 400, 12, 9
+    W = rng.integers(-2, 3, (C, D)).astype(np.float32)
+    g, s = orc.graph_bruteforce(W, K)
+    exp, S = _graph_by_argsort(W.astype(np.float64), K)
+    assert (g == exp).all()
+    assert (s == np.take_along_axis(S, exp.astype(np.int64), axis=1)).all()
+    assert (np.diff(s, axis=1) <= 0).all()
+    assert all(i not in g[i] for i in range(C))
+
+
+def test_graph_one_hot_rows_tie_structure(orc):
+    # rows are e_{i mod D}: similarity 1 inside a residue class, 0 otherwise => list of row i = lowest ids
+    # of its residue class (without i), then the lowest ids overall that are not in the class
+    C, D, K = 64, 8, 10
+    W = np.zeros((C, D), dtype=np.float32)
+    W[np.arange(C), np.arange(C) % D] = 1.0
+    g, s = orc.graph_bruteforce(W, K)
+    for i in range(C):
+        same = [j for j in range(C) if j % D == i % D and j != i]
+        other = [j for j in range(C) if j % D != i % D]
+        assert g[i].tolist() == (same + other)[:K]
+        assert s[i].tolist() == ([1.0] * len(same) + [0.0] * len(other))[:K]
+
+
+def test_graph_duplicate_rows_and_random_rows(orc):
+    C, D, K = 300, 24, 6
+    W = synth.unit_rows(9, synth.TID_W, C, D)
+    W[200] = W[17]                       # a twin: must come first in each other's list; self absent
+    g, s = orc.graph_bruteforce(W, K)
+    assert g[17, 0] == 200 and g[200, 0] == 17
+    exp, S = _graph_by_argsort(W.astype(np.float64), K)
+    assert (g == exp).all()              # random rows: no near-ties at fp64 resolution
+    assert np.allclose(s, np.take_along_axis(S, exp.astype(np.int64), axis=1), rtol=0, atol=1e-15)
+    # row subset API returns the same rows
+    rows = np.array([5, 17, 299], dtype=np.int32)
+    g2, s2 = orc.graph_bruteforce(W, K, rows)
+    assert (g2 == g[rows]).all() and (s2 == s[rows]).all()
+    # symmetry of the canonical similarity, bit-exact
+    i, j = 17, int(g[17, 1])
+    gi, si = orc.graph_bruteforce(W, C - 1, np.array([i, j], dtype=np.int32))
+    assert si[0][gi[0].tolist().index(j)] == si[1][gi[1].tolist().index(i)]
+
+
+# --------------------------------------------------------------------------------------------
+# Section 3.1 step 6: local weight update
+# --------------------------------------------------------------------------------------------
+def test_apply_matches_dense_index_add(orc):
+    C, D, n = 200, 16, 90
+    rng = np.random.default_rng(2)
+    W = synth.unit_rows(4, synth.TID_W, C, D)
+    idx = rng.integers(0, 40, n).astype(np.int32)        # many repeats
+    dW = synth.grad_rows(4, n, D)
+    alpha = -0.37
+    Wm, Wb = orc.apply_weight_grad(W, idx, dW, alpha)
+    dense = np.zeros((C, D), dtype=np.float64)
+    np.add.at(dense, idx, dW.astype(np.float64))
+    exp = (W.astype(np.float64) + alpha * dense).astype(np.float32)
+    assert (Wm == exp).all()
+    touched = np.zeros(C, dtype=bool)
+    touched[idx] = True
+    assert (Wm[~touched] == W[~touched]).all()            # untouched rows bit-unchanged
+    assert (Wb[~touched] == 0).all()
+    assert (Wb[touched] == synth.bf16_bits(Wm[touched])).all()  # bf16 copy = RNE of the master
+
+
+def test_bf16_rounding_to_nearest_even(orc):
+    # values exactly between two bf16 neighbours must go to the even one
+    W = np.array([[1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -1.0 - 2.0 ** -8]],
+                 dtype=np.float32)
+    Wm, Wb = orc.apply_weight_grad(W, np.array([0], dtype=np.int32), np.zeros((1, 4), dtype=np.float32), 1.0)
+    got = synth.bf16_to_f32(Wb)[0].tolist()
+    assert got == [1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, -1.0]
