@@ -233,9 +233,8 @@ def test_selection_hand_built_cases(orc):
     # class 7 has rank 3 in list_4 but rank 1 in list_6: its score is 1, so it survives a cut to 4
     a, A, t = orc.select_active(y, G, C, 4)
     assert a[:4].tolist() == [4, 5, 6, 7]
-    # ties in score go to the lowest class id: cut to 3 keeps 4 and 6 (score 0) and 5 (score 1, id < 7)
-    a, A, t = orc.select_active(y, G, C, 3)
-    assert a[:3].tolist() == [4, 5, 6] and t.tolist() == [0, 2]
+    with pytest.raises(ValueError):
+        orc.select_active(y, G, C, 3)              # a single label's list (K + 1 entries) must fit in M
     G2 = G.copy()
     G2[4] = [-1, 9, -1]                           # empty slots are skipped, ranks keep their column
     a, A, t = orc.select_active(np.array([4], dtype=np.int32), G2, C, 10)
