@@ -1,0 +1,164 @@
+/*
+ * knnsoftmax.h -- C ABI of the KNN-softmax output layer for extreme classification on one MI355X (gfx950).
+ *
+ * Method: "Large-Scale Training System for 100-Million Classification at Alibaba" (KDD'20), Section 3.2
+ * "KNN Softmax" (Algorithm 1: KNN graph-based active classes selection; Section 3.2.2: graph building by
+ * linear search; Section 3.1 steps 3-6: fc forward, softmax, backward, local weight update of the
+ * model-parallel fc layer; Section 3.1: 16-bit compute copy + fp32 copy for the parameter update).
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers, row-major, 16-byte aligned, owned by the caller.  The library
+ *     allocates nothing and keeps no state between calls; temporary storage comes from the caller's
+ *     workspace `ws` (device memory, 256-byte aligned, at least *_workspace(...) bytes; its contents are
+ *     undefined on entry and on exit).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue work:
+ *     there is no host synchronisation inside a call, so outputs are valid once the stream has drained.
+ *   - Return value: a ks_status for argument-level problems, detected on the host before any launch.
+ *   - Data-dependent problems (a label or a class id out of range, ...) cannot be seen from the host; they
+ *     set KS_DEV_* bits (atomic OR) in the caller's device word *dev_status, which the caller zeroes
+ *     beforehand.  dev_status may be NULL (nothing is reported).  When a bit is set the outputs are
+ *     unspecified, but no access leaves the caller's buffers.
+ *   - bf16 values are passed as uint16_t bit patterns.  "Class id" is int32.
+ *   - Results are deterministic: no floating-point atomics are used anywhere.
+ */
+#ifndef KNNSOFTMAX_H
+#define KNNSOFTMAX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KS_OK = 0,
+    KS_INVALID_ARG = 1,        /* NULL required pointer, non-positive size, D % 32 != 0, K + 1 > M, B > M, ... */
+    KS_UNSUPPORTED = 2,        /* size beyond what the kernels support (K > 128 or K > C - 1 in the graph build) */
+    KS_WORKSPACE_TOO_SMALL = 3,
+    KS_HIP_ERROR = 4           /* a launch failed; hipGetLastError() had the details */
+} ks_status;
+
+/* bits of *dev_status */
+#define KS_DEV_BAD_LABEL 1          /* a label outside [0, C) */
+#define KS_DEV_BAD_GRAPH_ID 2       /* a neighbour id outside [-1, C) */
+#define KS_DEV_BAD_INDEX 4          /* apply_weight_grad: an index outside [0, C) (that row is skipped) */
+#define KS_DEV_IDX_NOT_SORTED 8     /* apply_weight_grad: idx_sorted_unique was promised but does not hold */
+#define KS_DEV_BAD_COUNT 16         /* a device-side count (n, n_active) outside [0, n_max] */
+
+#define KS_DTYPE_BF16 0
+#define KS_DTYPE_FP32 1
+
+/* Largest K the graph build supports, and the limits of the selection. */
+#define KS_MAX_GRAPH_K 128
+
+const char *ks_version(void);
+
+/* ------------------------------------------------------------------------------------------------------
+ * knn_graph_build -- Section 3.2.2: exact K nearest neighbours of every class-weight row among all rows,
+ * by linear search with inner-product similarity; a 16-bit matrix-core pass recalls k' > K candidates per
+ * row, which are then re-ranked exactly (the paper's two-precision scheme).
+ *
+ *   W      [C, D]  class weights (normally L2-normalised rows; used as given), dtype KS_DTYPE_BF16 or _FP32
+ *   graph  [C, K]  out: row i = the K ids j != i with the largest similarity, in descending similarity,
+ *                  ties to the lowest id
+ *   sims   [C, K]  out, may be NULL: the similarities of those neighbours (fp32 rounding of the fp64 value)
+ *
+ * Similarity used for ranking = sum over d ascending of (double)W[i,d] * (double)W[j,d], accumulated
+ * sequentially in fp64; two similarities tie only when these fp64 values are equal.  The result is exact:
+ * a row whose recall cannot be certified from the matrix-core pass' error bound is redone by exhaustive
+ * fp64 search inside the same call.
+ * Requires 2 <= C < 2^31, D % 32 == 0, 1 <= K <= min(C - 1, KS_MAX_GRAPH_K).
+ * ---------------------------------------------------------------------------------------------------- */
+size_t knn_graph_build_workspace(int64_t C, int D, int K, int dtype);
+int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K, int32_t *graph, float *sims,
+                    void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
+
+/* ------------------------------------------------------------------------------------------------------
+ * knn_select_active -- Algorithm 1 without its random fill-up branch: the de-duplicated union of the
+ * labels' neighbour lists, each list headed by the label itself; when more than M classes remain, the M
+ * with the best ranking score are kept (score of a class = its smallest position in any contributing list,
+ * the label itself having position 0; ties to the lowest class id).  Entries -1 in `graph` are empty.
+ *
+ *   labels      [B]     class ids in [0, C)
+ *   graph       [C, K]  neighbour lists (K may be 0, graph then unused)
+ *   active_idx  [M]     out: the active class ids in ascending order; entries >= *n_active are -1
+ *   n_active    [1]     out (device): number of active classes, 1 <= *n_active <= M
+ *   target_pos  [B]     out: position of labels[i] in active_idx
+ * Requires B <= M and K + 1 <= M (every label and a whole list always fit).
+ * This is the first stage of knn_softmax_fwd_bwd, exported on its own.
+ * ---------------------------------------------------------------------------------------------------- */
+size_t knn_select_workspace(int64_t C, int B, int K, int M);
+int knn_select_active(const int32_t *labels, const int32_t *graph, int64_t C, int B, int K, int M,
+                      int32_t *active_idx, int32_t *n_active, int32_t *target_pos,
+                      void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
+
+/* ------------------------------------------------------------------------------------------------------
+ * knn_gather_rows -- W_active of Algorithm 1 as a dense matrix: out[a, :] = W_bf16[active_idx[a], :] for
+ * a < *n_active.  (knn_softmax_fwd_bwd gathers inside its matrix kernels and does not call this; it is
+ * exported for callers that want the rows, and to measure the gather on its own.)
+ *   out [M, D] bf16; rows >= *n_active are not written.
+ * ---------------------------------------------------------------------------------------------------- */
+int knn_gather_rows(const uint16_t *W_bf16, const int32_t *active_idx, const int32_t *n_active, int M,
+                    int64_t C, int D, uint16_t *out, int32_t *dev_status, void *stream);
+
+/* ------------------------------------------------------------------------------------------------------
+ * knn_softmax_fwd_bwd -- one step of the KNN-softmax layer on this GPU's classes (Section 3.2; Section 3.1
+ * steps 3-5): selection as in knn_select_active, then on the active columns only
+ *     Z_ia  = scale * <X_i, W[active_idx[a]]>                         (fc forward, bf16 in, fp32 accumulate)
+ *     loss_i = logsumexp_a(Z_ia) - Z_{i,target_pos[i]},  loss_mean = mean_i loss_i      (softmax + CE)
+ *     dZ_ia = (grad_scale / B) * (softmax(Z_i)_a - [a == target_pos[i]])                (softmax backward)
+ *     dX_i  = scale * sum_a dZ_ia W[active_idx[a]]                                      (fc backward)
+ *     dW_active[a] = scale * sum_i dZ_ia X_i
+ * X and W rows are used as given (callers pass L2-normalised rows); gradients are with respect to them.
+ * grad_scale (loss scaling) multiplies the gradients only, not the reported losses.
+ *
+ *   W_bf16 [C, D], X_bf16 [B, D], labels [B], graph [C, K]           inputs
+ *   active_idx [M], n_active [1], target_pos [B]                     out, as in knn_select_active
+ *   loss_per_sample [B] fp32, loss_mean [1] fp32                     out
+ *   dX [B, D] fp32                                                   out
+ *   dW_active [M, D] fp32                                            out; rows >= *n_active are not written
+ * Requires D % 32 == 0, B <= M, K + 1 <= M, C < 2^31.
+ * ---------------------------------------------------------------------------------------------------- */
+size_t knn_softmax_workspace(int64_t C, int D, int B, int K, int M);
+int knn_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
+                        const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
+                        float grad_scale, int32_t *active_idx, int32_t *n_active, int32_t *target_pos,
+                        float *loss_per_sample, float *loss_mean, float *dX, float *dW_active,
+                        void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
+
+/* ------------------------------------------------------------------------------------------------------
+ * full_softmax_fwd_bwd -- the full-softmax layer the paper compares against (Section 3.2, Table 3): the
+ * same computation with every class active (active_idx = 0..C-1, no graph).  dW is dense [C, D].
+ * ---------------------------------------------------------------------------------------------------- */
+size_t full_softmax_workspace(int64_t C, int D, int B);
+int full_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels, int64_t C,
+                         int D, int B, float scale, float grad_scale, float *loss_per_sample,
+                         float *loss_mean, float *dX, float *dW, void *ws, size_t ws_bytes,
+                         int32_t *dev_status, void *stream);
+
+/* ------------------------------------------------------------------------------------------------------
+ * apply_weight_grad -- Section 3.1 step 6: the model-parallel fc layer updates its weights from the local
+ * gradient; the fp32 copy is updated and the 16-bit compute copy refreshed from it (Section 3.1, mixed
+ * precision).  For every class c that occurs in idx[0 .. n):
+ *     W_master[c, :] += alpha * sum_{p : idx[p] == c} dW[p, :]        (sum in ascending p)
+ *     W_bf16[c, :]    = bf16(W_master[c, :])                          (round to nearest even)
+ * Rows that do not occur are not touched.  alpha folds -learning_rate and 1/grad_scale.
+ *
+ *   idx [n_max] class ids; may repeat (e.g. the concatenated active lists of several accumulated
+ *               micro-batches) unless idx_sorted_unique != 0, which promises strictly ascending ids (true
+ *               for active_idx of one step) and selects the single-pass kernel; a broken promise sets
+ *               KS_DEV_IDX_NOT_SORTED.
+ *   n   [1]     device count of valid entries (NULL = n_max)
+ *   dW  [n_max, D] fp32 gradient rows
+ * Requires D % 4 == 0.
+ * ---------------------------------------------------------------------------------------------------- */
+size_t apply_weight_grad_workspace(int64_t C, int D, int n_max, int idx_sorted_unique);
+int apply_weight_grad(float *W_master, uint16_t *W_bf16, const int32_t *idx, const int32_t *n, int n_max,
+                      const float *dW, float alpha, int64_t C, int D, int idx_sorted_unique,
+                      void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KNNSOFTMAX_H */

@@ -1,0 +1,245 @@
+"""ctypes binding of libknnsoftmax.so.  Function names and arguments mirror include/knnsoftmax.h; outputs
+and workspaces that the caller does not pass in are allocated here as torch tensors on the inputs' device.
+Nothing is computed in Python, and there is no fallback: a missing library is an error."""
+from __future__ import annotations
+
+import ctypes as ct
+import os
+
+import torch
+
+KS_OK, KS_INVALID_ARG, KS_UNSUPPORTED, KS_WORKSPACE_TOO_SMALL, KS_HIP_ERROR = 0, 1, 2, 3, 4
+KS_DEV_BAD_LABEL, KS_DEV_BAD_GRAPH_ID, KS_DEV_BAD_INDEX, KS_DEV_IDX_NOT_SORTED, KS_DEV_BAD_COUNT = 1, 2, 4, 8, 16
+_STATUS = {1: "KS_INVALID_ARG", 2: "KS_UNSUPPORTED", 3: "KS_WORKSPACE_TOO_SMALL", 4: "KS_HIP_ERROR"}
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_select_workspace",
+           "knn_select_active", "knn_gather_rows", "knn_softmax_workspace", "knn_softmax_fwd_bwd",
+           "full_softmax_workspace", "full_softmax_fwd_bwd", "apply_weight_grad_workspace", "apply_weight_grad")
+
+
+class KsError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        super().__init__(f"{fn} returned {_STATUS.get(code, code)}")
+        self.code = code
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libknnsoftmax.so")
+
+
+def lib():
+    """The loaded shared library.  Raises if it has not been built (python -m paper_2102_06025_amd.build)."""
+    global _LIB
+    if _LIB is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise RuntimeError(f"{path} is missing: build it with `python -m paper_2102_06025_amd.build` "
+                               "(there is no fallback implementation)")
+        L = ct.CDLL(path)
+        L.ks_version.restype = ct.c_char_p
+        for name in EXPORTS:
+            if name.endswith("_workspace"):
+                getattr(L, name).restype = ct.c_size_t
+            elif name != "ks_version":
+                getattr(L, name).restype = ct.c_int
+        _LIB = L
+    return _LIB
+
+
+def ks_version() -> str:
+    return lib().ks_version().decode()
+
+
+def _ptr(t):
+    return ct.c_void_p(0) if t is None else ct.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ct.c_void_p(s.cuda_stream)
+
+
+def _check(fn, rc):
+    if rc != KS_OK:
+        raise KsError(fn, rc)
+
+
+def _need(t, dtype, name):
+    if t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
+        raise TypeError(f"{name} must be a contiguous device tensor of {dtype}")
+    return t
+
+
+def _ws(nbytes, device, ws):
+    if ws is not None:
+        return ws
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def _status(device, dev_status):
+    return torch.zeros(1, dtype=torch.int32, device=device) if dev_status is None else dev_status
+
+
+# ---------------------------------------------------------------------------------------------------
+def knn_graph_build_workspace(C, D, K, dtype) -> int:
+    return int(lib().knn_graph_build_workspace(ct.c_int64(C), ct.c_int(D), ct.c_int(K), ct.c_int(dtype)))
+
+
+def knn_graph_build(W, K, want_sims=False, graph=None, sims=None, ws=None, dev_status=None, stream=None):
+    """W [C, D] bf16 or fp32 device tensor -> graph int32 [C, K] (and sims fp32 [C, K] when want_sims)."""
+    if W.dtype == torch.bfloat16:
+        dtype = 0
+    elif W.dtype == torch.float32:
+        dtype = 1
+    else:
+        raise TypeError("W must be bfloat16 or float32")
+    if not (W.is_cuda and W.is_contiguous() and W.dim() == 2):
+        raise TypeError("W must be a contiguous 2-D device tensor")
+    C, D = W.shape
+    need = knn_graph_build_workspace(C, D, K, dtype)
+    if graph is None:
+        graph = torch.empty((C, K), dtype=torch.int32, device=W.device)
+    if want_sims and sims is None:
+        sims = torch.empty((C, K), dtype=torch.float32, device=W.device)
+    ws = _ws(need, W.device, ws)
+    dev_status = _status(W.device, dev_status)
+    rc = lib().knn_graph_build(_ptr(W), ct.c_int(dtype), ct.c_int64(C), ct.c_int(D), ct.c_int(K), _ptr(graph),
+                               _ptr(sims), _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
+    _check("knn_graph_build", rc)
+    return (graph, sims) if want_sims else graph
+
+
+def knn_select_workspace(C, B, K, M) -> int:
+    return int(lib().knn_select_workspace(ct.c_int64(C), ct.c_int(B), ct.c_int(K), ct.c_int(M)))
+
+
+def knn_select_active(labels, graph, C, M, ws=None, dev_status=None, stream=None):
+    """-> (active_idx int32 [M], n_active int32 [1] on the device, target_pos int32 [B], dev_status)."""
+    _need(labels, torch.int32, "labels")
+    B = labels.numel()
+    K = 0 if graph is None else graph.shape[1]
+    if graph is not None:
+        _need(graph, torch.int32, "graph")
+    dev = labels.device
+    active_idx = torch.empty(M, dtype=torch.int32, device=dev)
+    n_active = torch.empty(1, dtype=torch.int32, device=dev)
+    target_pos = torch.empty(B, dtype=torch.int32, device=dev)
+    ws = _ws(knn_select_workspace(C, B, K, M), dev, ws)
+    dev_status = _status(dev, dev_status)
+    rc = lib().knn_select_active(_ptr(labels), _ptr(graph), ct.c_int64(C), ct.c_int(B), ct.c_int(K), ct.c_int(M),
+                                 _ptr(active_idx), _ptr(n_active), _ptr(target_pos), _ptr(ws),
+                                 ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
+    _check("knn_select_active", rc)
+    return active_idx, n_active, target_pos, dev_status
+
+
+def knn_gather_rows(W_bf16, active_idx, n_active, out=None, dev_status=None, stream=None):
+    _need(W_bf16, torch.bfloat16, "W_bf16")
+    C, D = W_bf16.shape
+    M = active_idx.numel()
+    if out is None:
+        out = torch.empty((M, D), dtype=torch.bfloat16, device=W_bf16.device)
+    dev_status = _status(W_bf16.device, dev_status)
+    rc = lib().knn_gather_rows(_ptr(W_bf16), _ptr(active_idx), _ptr(n_active), ct.c_int(M), ct.c_int64(C),
+                               ct.c_int(D), _ptr(out), _ptr(dev_status), _stream(stream))
+    _check("knn_gather_rows", rc)
+    return out
+
+
+def knn_softmax_workspace(C, D, B, K, M) -> int:
+    return int(lib().knn_softmax_workspace(ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(K), ct.c_int(M)))
+
+
+def knn_softmax_fwd_bwd(W_bf16, X_bf16, labels, graph, M, scale, grad_scale=1.0, out=None, ws=None,
+                        dev_status=None, stream=None):
+    """One forward+backward step.  Returns a dict of device tensors: active_idx [M], n_active [1],
+    target_pos [B], loss_per_sample [B], loss_mean [1], dX [B, D], dW_active [M, D], dev_status [1].
+    Pass the dict of a previous call as `out` (and `ws`) to reuse the buffers."""
+    _need(W_bf16, torch.bfloat16, "W_bf16")
+    _need(X_bf16, torch.bfloat16, "X_bf16")
+    _need(labels, torch.int32, "labels")
+    C, D = W_bf16.shape
+    B = X_bf16.shape[0]
+    K = 0 if graph is None else graph.shape[1]
+    if graph is not None:
+        _need(graph, torch.int32, "graph")
+    dev = W_bf16.device
+    if out is None:
+        out = dict(active_idx=torch.empty(M, dtype=torch.int32, device=dev),
+                   n_active=torch.empty(1, dtype=torch.int32, device=dev),
+                   target_pos=torch.empty(B, dtype=torch.int32, device=dev),
+                   loss_per_sample=torch.empty(B, dtype=torch.float32, device=dev),
+                   loss_mean=torch.empty(1, dtype=torch.float32, device=dev),
+                   dX=torch.empty((B, D), dtype=torch.float32, device=dev),
+                   dW_active=torch.empty((M, D), dtype=torch.float32, device=dev))
+    ws = _ws(knn_softmax_workspace(C, D, B, K, M), dev, ws)
+    dev_status = _status(dev, dev_status if dev_status is not None else out.get("dev_status"))
+    out["dev_status"] = dev_status
+    out["ws"] = ws
+    rc = lib().knn_softmax_fwd_bwd(_ptr(W_bf16), _ptr(X_bf16), _ptr(labels), _ptr(graph), ct.c_int64(C), ct.c_int(D),
+                                   ct.c_int(B), ct.c_int(K), ct.c_int(M), ct.c_float(scale), ct.c_float(grad_scale),
+                                   _ptr(out["active_idx"]), _ptr(out["n_active"]), _ptr(out["target_pos"]),
+                                   _ptr(out["loss_per_sample"]), _ptr(out["loss_mean"]), _ptr(out["dX"]),
+                                   _ptr(out["dW_active"]), _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status),
+                                   _stream(stream))
+    _check("knn_softmax_fwd_bwd", rc)
+    return out
+
+
+def full_softmax_workspace(C, D, B) -> int:
+    return int(lib().full_softmax_workspace(ct.c_int64(C), ct.c_int(D), ct.c_int(B)))
+
+
+def full_softmax_fwd_bwd(W_bf16, X_bf16, labels, scale, grad_scale=1.0, out=None, ws=None, dev_status=None,
+                         stream=None):
+    """Full softmax over all classes.  Returns dict(loss_per_sample, loss_mean, dX, dW [C, D], dev_status)."""
+    _need(W_bf16, torch.bfloat16, "W_bf16")
+    _need(X_bf16, torch.bfloat16, "X_bf16")
+    _need(labels, torch.int32, "labels")
+    C, D = W_bf16.shape
+    B = X_bf16.shape[0]
+    dev = W_bf16.device
+    if out is None:
+        out = dict(loss_per_sample=torch.empty(B, dtype=torch.float32, device=dev),
+                   loss_mean=torch.empty(1, dtype=torch.float32, device=dev),
+                   dX=torch.empty((B, D), dtype=torch.float32, device=dev),
+                   dW=torch.empty((C, D), dtype=torch.float32, device=dev))
+    ws = _ws(full_softmax_workspace(C, D, B), dev, ws)
+    dev_status = _status(dev, dev_status if dev_status is not None else out.get("dev_status"))
+    out["dev_status"] = dev_status
+    out["ws"] = ws
+    rc = lib().full_softmax_fwd_bwd(_ptr(W_bf16), _ptr(X_bf16), _ptr(labels), ct.c_int64(C), ct.c_int(D), ct.c_int(B),
+                                    ct.c_float(scale), ct.c_float(grad_scale), _ptr(out["loss_per_sample"]),
+                                    _ptr(out["loss_mean"]), _ptr(out["dX"]), _ptr(out["dW"]), _ptr(ws),
+                                    ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
+    _check("full_softmax_fwd_bwd", rc)
+    return out
+
+
+def apply_weight_grad_workspace(C, D, n_max, idx_sorted_unique) -> int:
+    return int(lib().apply_weight_grad_workspace(ct.c_int64(C), ct.c_int(D), ct.c_int(n_max),
+                                                 ct.c_int(int(idx_sorted_unique))))
+
+
+def apply_weight_grad(W_master, W_bf16, idx, n, dW, alpha, idx_sorted_unique=False, ws=None, dev_status=None,
+                      stream=None):
+    """In-place update of W_master (fp32) and W_bf16 (may be None).  `n` is a device int32 scalar or None."""
+    _need(W_master, torch.float32, "W_master")
+    _need(idx, torch.int32, "idx")
+    _need(dW, torch.float32, "dW")
+    if W_bf16 is not None:
+        _need(W_bf16, torch.bfloat16, "W_bf16")
+    C, D = W_master.shape
+    n_max = idx.numel()
+    if dW.shape[0] < n_max or dW.shape[1] != D:
+        raise ValueError("dW must be [n_max, D]")
+    ws = _ws(apply_weight_grad_workspace(C, D, n_max, idx_sorted_unique), W_master.device, ws)
+    dev_status = _status(W_master.device, dev_status)
+    rc = lib().apply_weight_grad(_ptr(W_master), _ptr(W_bf16), _ptr(idx), _ptr(n), ct.c_int(n_max), _ptr(dW),
+                                 ct.c_float(alpha), ct.c_int64(C), ct.c_int(D), ct.c_int(int(idx_sorted_unique)),
+                                 _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
+    _check("apply_weight_grad", rc)
+    return dev_status

@@ -1,0 +1,455 @@
+// Exact KNN graph of the class-weight rows (paper Section 3.2.2: linear search with inner-product
+// similarity; 16-bit matrix-core pass that recalls k' > K candidates, then an exact re-rank).
+//
+//   prepare   bf16 copy of W when the input is fp32; row norms and their maximum (for the error bound)
+//   recall    each workgroup owns a block of 128 rows and sweeps all column blocks: bf16 MFMA tile of
+//             similarities; an element that beats its row's threshold is appended to that row's candidate
+//             buffer; a full buffer is cut back to its k' best by a wavefront-wide bitonic sort in
+//             registers, which also raises the threshold.  The C x C similarities are never stored.
+//   re-rank   one wavefront per row: canonical fp64 similarity of the k' candidates, exact order
+//             (similarity descending, id ascending), first K written out.  The row is certified when
+//             the K-th exact similarity exceeds the recall threshold by more than the error bound of the
+//             matrix-core pass; otherwise the row goes to the exhaustive list.
+//   exhaustive  uncertified rows are searched over all C columns in canonical fp64 arithmetic.
+// Every decision that reaches the output is taken on the canonical fp64 similarity, so the lists are
+// exact and do not depend on scheduling.
+#include "ks_gemm.h"
+
+typedef KsTile<128, 128, 64, 2, 2> TileR;
+
+#define GR_NT 256
+#define GR_FB_BLOCKS 64   /* workgroups (and fp64 scratch rows) of the exhaustive pass */
+#define GR_MAX_D 4096     /* the exhaustive pass keeps one row in LDS as fp64 */
+
+__device__ __forceinline__ uint32_t gr_orderable(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float gr_unorder(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+struct GrParams {
+    int kprime; // candidates kept per row by the recall pass (64, 128 or 256)
+    int cap;    // candidate buffer entries per row (256 or 512)
+};
+static GrParams gr_params(int K) {
+    GrParams p;
+    if (K <= 32) { p.kprime = 64; p.cap = 256; }
+    else if (K <= 64) { p.kprime = 128; p.cap = 256; }
+    else { p.kprime = 256; p.cap = 512; }
+    return p;
+}
+
+// ------------------------------------------------------------------------------------------------
+// prepare
+// ------------------------------------------------------------------------------------------------
+template <typename IN> struct GrElem;
+template <> struct GrElem<uint16_t> {
+    static __device__ __forceinline__ float f(uint16_t v) { return ks_bf2f(v); }
+};
+template <> struct GrElem<float> {
+    static __device__ __forceinline__ float f(float v) { return v; }
+};
+
+// one wavefront per row: squared norm in fp32 (only used for the error bound, with slack), optional bf16 copy
+template <typename IN>
+__global__ void __launch_bounds__(GR_NT)
+gr_prepare_kernel(const IN *__restrict__ W, int64_t C, int D, uint16_t *__restrict__ Wb, float *__restrict__ norms,
+                  uint32_t *maxnorm_bits) {
+    const int64_t i = (int64_t)blockIdx.x * (GR_NT / 64) + (threadIdx.x >> 6);
+    if (i >= C) return;
+    const int lane = threadIdx.x & 63;
+    float s = 0.f;
+    for (int d = lane; d < D; d += 64) {
+        float v = GrElem<IN>::f(W[i * D + d]);
+        s += v * v;
+        if (Wb) Wb[i * D + d] = (uint16_t)ks_f2bf(v);
+    }
+    s = ks_wave_sum(s);
+    if (lane == 0) {
+        float nrm = sqrtf(s);
+        norms[i] = nrm;
+        atomicMax(maxnorm_bits, __float_as_uint(nrm)); // non-negative floats order like their bit patterns
+    }
+}
+
+__global__ void gr_zero_kernel(uint32_t *maxnorm_bits, int32_t *fb_count) {
+    *maxnorm_bits = 0u;
+    *fb_count = 0;
+}
+
+// ------------------------------------------------------------------------------------------------
+// wavefront-wide bitonic sort, descending, of E*64 keys held as val[r] = element r*64 + lane
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t gr_shfl_xor64(uint64_t v, int mask) {
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+    lo = __shfl_xor(lo, mask, 64);
+    hi = __shfl_xor(hi, mask, 64);
+    return ((uint64_t)hi << 32) | lo;
+}
+
+template <int E> __device__ __forceinline__ void gr_wave_sort_desc(uint64_t (&val)[E]) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int k = 2; k <= E * 64; k <<= 1) {
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            if (j >= 64) {
+                const int jr = j >> 6;
+#pragma unroll
+                for (int r = 0; r < E; ++r) {
+                    if ((r & jr) == 0) {
+                        const int idx = r * 64 + lane;
+                        const bool desc = (idx & k) == 0; // descending run: larger key to the lower index
+                        uint64_t a = val[r], b = val[r | jr];
+                        if ((a < b) == desc) { val[r] = b; val[r | jr] = a; }
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < E; ++r) {
+                    const int idx = r * 64 + lane;
+                    const bool desc = (idx & k) == 0;
+                    const bool lower = (lane & j) == 0;
+                    uint64_t me = val[r], other = gr_shfl_xor64(me, j);
+                    const bool want_max = (lower == desc);
+                    val[r] = want_max ? (me > other ? me : other) : (me < other ? me : other);
+                }
+            }
+        }
+    }
+}
+
+// cut the candidate buffer of one row back to its kprime best; returns nothing, updates cnt/thr in LDS
+template <int E>
+__device__ __forceinline__ void gr_compact_row(uint64_t *__restrict__ cand_row, int *cnt, uint32_t *thr, int kprime) {
+    const int lane = threadIdx.x & 63;
+    const int n = *cnt;
+    uint64_t val[E];
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        int idx = r * 64 + lane;
+        val[r] = idx < n ? cand_row[idx] : 0ull; // 0 sorts below every real key
+    }
+    gr_wave_sort_desc<E>(val);
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        int idx = r * 64 + lane;
+        if (idx < kprime) cand_row[idx] = val[r];
+    }
+    // key number kprime-1 is the new threshold
+    const int rk = (kprime - 1) >> 6, lk = (kprime - 1) & 63;
+    uint64_t kth = 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r)
+        if (r == rk) kth = val[r];
+    uint32_t kth_hi = __shfl((uint32_t)(kth >> 32), lk, 64);
+    if (lane == 0) {
+        *cnt = kprime;
+        *thr = kth_hi;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// recall pass
+// ------------------------------------------------------------------------------------------------
+template <class T, int E>
+__global__ void __launch_bounds__(T::NT)
+gr_recall_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kprime, uint64_t *__restrict__ cand,
+                 int32_t *__restrict__ cnt_out, uint32_t *__restrict__ thr_out) {
+    constexpr int CAP = E * 64;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
+    __shared__ int s_cnt[T::BM];
+    __shared__ uint32_t s_thr[T::BM];
+    const int wave = threadIdx.x >> 6;
+    const int64_t row0 = (int64_t)blockIdx.x * T::BM;
+    for (int m = threadIdx.x; m < T::BM; m += T::NT) { s_cnt[m] = 0; s_thr[m] = 0u; }
+    __syncthreads();
+
+    KsRowLoader<T::BM, T::BK, T::NT> al;
+    al.init(Wb, D, nullptr, (int)row0, (int)C, D);
+    const int n_col_blocks = (int)((C + T::BN - 1) / T::BN);
+    const int nk = (D + T::BK - 1) / T::BK;
+    for (int J = 0; J < n_col_blocks; ++J) {
+        KsRowLoader<T::BN, T::BK, T::NT> bl;
+        bl.init(Wb, D, nullptr, J * T::BN, (int)C, D);
+        f32x16_t acc[T::FM][T::FN];
+        ks_tile_clear<T>(acc);
+        ks_gemm_mainloop<T>(al, bl, 0, nk, lds, acc);
+        ks_tile_foreach<T>(acc, [&](int m, int n, float v) {
+            const int64_t i = row0 + m, j = (int64_t)J * T::BN + n;
+            if (i < C && j < C && i != j) {
+                const uint32_t hi = gr_orderable(v);
+                if (hi > s_thr[m]) {
+                    int slot = atomicAdd(&s_cnt[m], 1);
+                    if (slot < CAP) // always true: a buffer is cut back before it can overflow
+                        cand[i * CAP + slot] = ((uint64_t)hi << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
+                }
+            }
+        });
+        __syncthreads();
+        for (int m = wave; m < T::BM; m += T::NT / 64) {
+            if (s_cnt[m] > CAP - T::BN) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
+        }
+        __syncthreads();
+    }
+    for (int m = wave; m < T::BM; m += T::NT / 64) {
+        if (row0 + m < C) {
+            if (s_cnt[m] > kprime) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
+        }
+    }
+    __syncthreads();
+    for (int m = threadIdx.x; m < T::BM; m += T::NT) {
+        if (row0 + m < C) { cnt_out[row0 + m] = s_cnt[m]; thr_out[row0 + m] = s_thr[m]; }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// canonical similarity: sum over d ascending of (double)a_d * (double)b_d, one fused multiply-add per
+// term (the product of two fp32 or bf16 values is exact in fp64, so this equals multiply-then-add)
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ double gr_canon(const uint16_t *__restrict__ a, const uint16_t *__restrict__ b, int D) {
+    double acc = 0.0;
+    for (int d = 0; d < D; d += 8) {
+        uint4 va = *(const uint4 *)(a + d), vb = *(const uint4 *)(b + d);
+        const uint32_t wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb.x, vb.y, vb.z, vb.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc = __builtin_fma((double)__uint_as_float(wa[e] << 16), (double)__uint_as_float(wb[e] << 16), acc);
+            acc = __builtin_fma((double)__uint_as_float(wa[e] & 0xFFFF0000u), (double)__uint_as_float(wb[e] & 0xFFFF0000u),
+                                acc);
+        }
+    }
+    return acc;
+}
+__device__ __forceinline__ double gr_canon(const float *__restrict__ a, const float *__restrict__ b, int D) {
+    double acc = 0.0;
+    for (int d = 0; d < D; d += 4) {
+        float4 va = *(const float4 *)(a + d), vb = *(const float4 *)(b + d);
+        acc = __builtin_fma((double)va.x, (double)vb.x, acc);
+        acc = __builtin_fma((double)va.y, (double)vb.y, acc);
+        acc = __builtin_fma((double)va.z, (double)vb.z, acc);
+        acc = __builtin_fma((double)va.w, (double)vb.w, acc);
+    }
+    return acc;
+}
+
+__device__ __forceinline__ bool gr_ranks_before(double s, int32_t j, double t, int32_t k) {
+    return s > t || (s == t && j < k);
+}
+
+// ------------------------------------------------------------------------------------------------
+// exact re-rank of the recalled candidates; one wavefront per row; kprime <= 256 (4 slots per lane)
+// ------------------------------------------------------------------------------------------------
+template <typename IN>
+__global__ void __launch_bounds__(GR_NT)
+gr_rerank_kernel(const IN *__restrict__ W, int64_t C, int D, int K, int cap, const uint64_t *__restrict__ cand,
+                 const int32_t *__restrict__ cnt, const uint32_t *__restrict__ thr, const float *__restrict__ norms,
+                 const uint32_t *__restrict__ maxnorm_bits, float gamma, int32_t *__restrict__ graph,
+                 float *__restrict__ sims, int32_t *fb_count, int32_t *__restrict__ fb_rows) {
+    const int64_t i = (int64_t)blockIdx.x * (GR_NT / 64) + (threadIdx.x >> 6);
+    if (i >= C) return;
+    const int lane = threadIdx.x & 63;
+    const int n = cnt[i];
+    double s[4];
+    int32_t id[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int q = t * 64 + lane;
+        s[t] = -INFINITY;
+        id[t] = 0x7FFFFFFF;
+        if (q < n) {
+            const uint32_t j = 0xFFFFFFFFu - (uint32_t)cand[i * cap + q];
+            if (j < (uint32_t)C) { // always true for keys written by the recall pass
+                id[t] = (int32_t)j;
+                s[t] = gr_canon(W + i * D, W + (int64_t)j * D, D);
+            }
+        }
+    }
+    int rank[4] = {0, 0, 0, 0};
+    const int slots = (n + 63) >> 6;
+    for (int t2 = 0; t2 < slots; ++t2) {
+        double s2 = t2 == 0 ? s[0] : (t2 == 1 ? s[1] : (t2 == 2 ? s[2] : s[3]));
+        int32_t id2 = t2 == 0 ? id[0] : (t2 == 1 ? id[1] : (t2 == 2 ? id[2] : id[3]));
+        for (int src = 0; src < 64; ++src) {
+            const double os = __shfl(s2, src, 64);
+            const int32_t oid = __shfl(id2, src, 64);
+            if (t2 * 64 + src < n) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) rank[t] += gr_ranks_before(os, oid, s[t], id[t]) ? 1 : 0;
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int q = t * 64 + lane;
+        if (q < n && rank[t] < K) {
+            graph[i * K + rank[t]] = id[t];
+            if (sims) sims[i * K + rank[t]] = (float)s[t];
+            if (rank[t] == K - 1) {
+                // certificate: nothing that was dropped can reach the K-th exact similarity
+                const uint32_t th = thr[i];
+                bool certified = (th == 0u); // nothing was ever dropped
+                if (!certified) {
+                    const double eps = (double)gamma * (double)norms[i] * (double)__uint_as_float(*maxnorm_bits);
+                    certified = s[t] > (double)gr_unorder(th) + eps;
+                }
+                if (!certified) fb_rows[atomicAdd(fb_count, 1)] = (int32_t)i;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// exhaustive fp64 search for the rows on the list
+// ------------------------------------------------------------------------------------------------
+template <typename IN>
+__global__ void __launch_bounds__(GR_NT)
+gr_exhaustive_kernel(const IN *__restrict__ W, int64_t C, int D, int K, const int32_t *__restrict__ fb_count,
+                     const int32_t *__restrict__ fb_rows, double *__restrict__ scratch, int32_t *__restrict__ graph,
+                     float *__restrict__ sims) {
+    __shared__ double red_s[GR_NT];
+    __shared__ int32_t red_j[GR_NT];
+    __shared__ __attribute__((aligned(16))) IN row_i[GR_MAX_D];
+    int n_fb = *fb_count;
+    if (n_fb > C) n_fb = (int)C;
+    double *my = scratch + (int64_t)blockIdx.x * C;
+    for (int e = blockIdx.x; e < n_fb; e += gridDim.x) {
+        const int64_t i = fb_rows[e];
+        for (int d = threadIdx.x; d < D; d += GR_NT) row_i[d] = W[i * D + d];
+        __syncthreads();
+        for (int64_t j = threadIdx.x; j < C; j += GR_NT) my[j] = gr_canon(row_i, W + j * D, D);
+        __syncthreads();
+        double prev_s = INFINITY;
+        int32_t prev_j = -1;
+        for (int r = 0; r < K; ++r) {
+            double best_s = -INFINITY;
+            int32_t best_j = 0x7FFFFFFF;
+            for (int64_t j = threadIdx.x; j < C; j += GR_NT) {
+                if (j == i) continue;
+                const double sj = my[j];
+                if (gr_ranks_before(prev_s, prev_j, sj, (int32_t)j) && gr_ranks_before(sj, (int32_t)j, best_s, best_j)) {
+                    best_s = sj;
+                    best_j = (int32_t)j;
+                }
+            }
+            red_s[threadIdx.x] = best_s;
+            red_j[threadIdx.x] = best_j;
+            __syncthreads();
+            for (int o = GR_NT / 2; o > 0; o >>= 1) {
+                if (threadIdx.x < o) {
+                    if (gr_ranks_before(red_s[threadIdx.x + o], red_j[threadIdx.x + o], red_s[threadIdx.x], red_j[threadIdx.x])) {
+                        red_s[threadIdx.x] = red_s[threadIdx.x + o];
+                        red_j[threadIdx.x] = red_j[threadIdx.x + o];
+                    }
+                }
+                __syncthreads();
+            }
+            prev_s = red_s[0];
+            prev_j = red_j[0];
+            if (threadIdx.x == 0) {
+                graph[i * K + r] = prev_j;
+                if (sims) sims[i * K + r] = (float)prev_s;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+struct GrWs {
+    uint16_t *Wb;
+    float *norms;
+    uint32_t *maxnorm;
+    uint64_t *cand;
+    int32_t *cnt;
+    uint32_t *thr;
+    int32_t *fb_count;
+    int32_t *fb_rows;
+    double *scratch;
+};
+
+static GrWs gr_carve(void *ws, int64_t C, int D, int K, int dtype, size_t *total) {
+    KsArena ar(ws);
+    GrParams p = gr_params(K);
+    GrWs w;
+    w.Wb = dtype == KS_DTYPE_FP32 ? ar.take<uint16_t>((size_t)C * D) : nullptr;
+    w.norms = ar.take<float>((size_t)C);
+    w.maxnorm = ar.take<uint32_t>(1);
+    w.cand = ar.take<uint64_t>((size_t)C * p.cap);
+    w.cnt = ar.take<int32_t>((size_t)C);
+    w.thr = ar.take<uint32_t>((size_t)C);
+    w.fb_count = ar.take<int32_t>(1);
+    w.fb_rows = ar.take<int32_t>((size_t)C);
+    w.scratch = ar.take<double>((size_t)GR_FB_BLOCKS * C);
+    if (total) *total = ar.off;
+    return w;
+}
+
+static int gr_check(int64_t C, int D, int K, int dtype) {
+    if (dtype != KS_DTYPE_BF16 && dtype != KS_DTYPE_FP32) return KS_INVALID_ARG;
+    if (C < 2 || C >= (int64_t)1 << 31 || D < 32 || D % 32 != 0 || K < 1) return KS_INVALID_ARG;
+    if (K > KS_MAX_GRAPH_K || K > C - 1 || D > GR_MAX_D) return KS_UNSUPPORTED;
+    return KS_OK;
+}
+
+extern "C" size_t knn_graph_build_workspace(int64_t C, int D, int K, int dtype) {
+    if (gr_check(C, D, K, dtype) != KS_OK) return 0;
+    size_t total = 0;
+    gr_carve(nullptr, C, D, K, dtype, &total);
+    return total;
+}
+
+template <typename IN>
+static void gr_launch_exact(const IN *W, int64_t C, int D, int K, const GrParams &p, const GrWs &w, float gamma,
+                            int32_t *graph, float *sims, hipStream_t st) {
+    hipLaunchKernelGGL(gr_rerank_kernel<IN>, dim3((unsigned)ks_ceil_div(C, GR_NT / 64)), dim3(GR_NT), 0, st, W, C, D, K, p.cap,
+                       w.cand, w.cnt, w.thr, w.norms, w.maxnorm, gamma, graph, sims, w.fb_count, w.fb_rows);
+    hipLaunchKernelGGL(gr_exhaustive_kernel<IN>, dim3(GR_FB_BLOCKS), dim3(GR_NT), 0, st, W, C, D, K, w.fb_count, w.fb_rows,
+                       w.scratch, graph, sims);
+}
+
+extern "C" int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K, int32_t *graph, float *sims, void *ws,
+                               size_t ws_bytes, int32_t *dev_status, void *stream) {
+    (void)dev_status;
+    if (!W || !graph || !ws) return KS_INVALID_ARG;
+    int rc = gr_check(C, D, K, dtype);
+    if (rc != KS_OK) return rc;
+    size_t need = 0;
+    GrWs w = gr_carve(ws, C, D, K, dtype, &need);
+    if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
+    const GrParams p = gr_params(K);
+    hipStream_t st = (hipStream_t)stream;
+
+    hipLaunchKernelGGL(gr_zero_kernel, dim3(1), dim3(1), 0, st, w.maxnorm, w.fb_count);
+    const unsigned row_blocks = (unsigned)ks_ceil_div(C, GR_NT / 64);
+    const uint16_t *Wb;
+    if (dtype == KS_DTYPE_FP32) {
+        hipLaunchKernelGGL(gr_prepare_kernel<float>, dim3(row_blocks), dim3(GR_NT), 0, st, (const float *)W, C, D, w.Wb,
+                           w.norms, w.maxnorm);
+        Wb = w.Wb;
+    } else {
+        hipLaunchKernelGGL(gr_prepare_kernel<uint16_t>, dim3(row_blocks), dim3(GR_NT), 0, st, (const uint16_t *)W, C, D,
+                           (uint16_t *)nullptr, w.norms, w.maxnorm);
+        Wb = (const uint16_t *)W;
+    }
+    const unsigned recall_blocks = (unsigned)ks_ceil_div(C, TileR::BM);
+    if (p.cap == 256)
+        hipLaunchKernelGGL((gr_recall_kernel<TileR, 4>), dim3(recall_blocks), dim3(TileR::NT), 0, st, Wb, C, D, p.kprime, w.cand,
+                           w.cnt, w.thr);
+    else
+        hipLaunchKernelGGL((gr_recall_kernel<TileR, 8>), dim3(recall_blocks), dim3(TileR::NT), 0, st, Wb, C, D, p.kprime, w.cand,
+                           w.cnt, w.thr);
+    // error bound of the recall pass relative to |w_i||w_j|: fp32 accumulation of D exact bf16 products
+    // (2^-23 per addition allows for truncating adders), plus the bf16 rounding of both rows (2 * 2^-9,
+    // rounded up to 2^-7.9) when the input is fp32; a small slack covers the fp32 norms themselves
+    float gamma = (float)D * 1.1920929e-7f * 1.01f;
+    if (dtype == KS_DTYPE_FP32) gamma += 0.0042f;
+    if (dtype == KS_DTYPE_FP32) gr_launch_exact<float>((const float *)W, C, D, K, p, w, gamma, graph, sims, st);
+    else gr_launch_exact<uint16_t>((const uint16_t *)W, C, D, K, p, w, gamma, graph, sims, st);
+    KS_LAUNCH_CHECK();
+    return KS_OK;
+}

@@ -1,0 +1,274 @@
+// Active-class selection (Algorithm 1 of the paper, without the random fill-up branch) on the GPU.
+//
+// Data structure: a table score[C] (int32) indexed by class id.  Marking a candidate is an integer
+// atomicMin of its list position into the table, so duplicates collapse by construction and the
+// result does not depend on the order of the atomics.  The ascending active list is then a stream
+// compaction of the table; the cut to M classes is a threshold on the score (found from a histogram
+// over list positions) plus a quota of the lowest ids at the threshold score.
+#include "ks_select.h"
+
+#define SEL_NT 256
+#define SEL_PER 8
+#define SEL_SEG (SEL_NT * SEL_PER) /* classes per block in the table passes */
+#define SEL_NONE 0x7fffffff
+#define SEL_LDS_BINS 2048
+
+struct SelPlan {
+    int r_star;    // classes with score < r_star are all kept
+    int quota;     // number of classes with score == r_star that are kept (lowest ids)
+    int n_active;
+    int n_unique;
+};
+
+struct SelWs {
+    int32_t *score;    // [C]      min list position per class, later: position in the active list
+    int32_t *hist;     // [K + 1]  number of distinct classes per score
+    int32_t *blk_cnt;  // [nblk*2] per table block: (#score < r_star, #score == r_star)
+    int32_t *blk_base; // [nblk*2] exclusive prefixes of the kept counts / of the == r_star counts
+    SelPlan *plan;
+    int nblk;
+};
+
+static SelWs sel_carve(void *ws, int64_t C, int K) {
+    KsArena ar(ws);
+    SelWs w;
+    w.nblk = (int)ks_ceil_div(C, SEL_SEG);
+    w.score = ar.take<int32_t>((size_t)C);
+    w.hist = ar.take<int32_t>((size_t)K + 1);
+    w.blk_cnt = ar.take<int32_t>((size_t)w.nblk * 2);
+    w.blk_base = ar.take<int32_t>((size_t)w.nblk * 2);
+    w.plan = ar.take<SelPlan>(1);
+    return w;
+}
+
+size_t ks_select_ws_bytes(int64_t C, int K) {
+    KsArena ar(nullptr);
+    ar.take<int32_t>((size_t)C);
+    ar.take<int32_t>((size_t)K + 1);
+    size_t nblk = (size_t)ks_ceil_div(C, SEL_SEG);
+    ar.take<int32_t>(nblk * 2);
+    ar.take<int32_t>(nblk * 2);
+    ar.take<SelPlan>(1);
+    return ar.off;
+}
+
+__global__ void __launch_bounds__(SEL_NT) sel_init_kernel(int32_t *score, int64_t C, int32_t *hist, int K) {
+    int64_t t = (int64_t)blockIdx.x * SEL_NT + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * SEL_NT;
+    for (int64_t c = t; c < C; c += stride) score[c] = SEL_NONE;
+    for (int64_t r = t; r <= K; r += stride) hist[r] = 0;
+}
+
+// one thread per (sample i, list position r): r = 0 is the label itself, r >= 1 is column r-1 of its list
+__global__ void __launch_bounds__(SEL_NT)
+sel_mark_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict__ graph, int64_t C, int B, int K,
+                int32_t *score, int32_t *dev_status) {
+    int64_t t = (int64_t)blockIdx.x * SEL_NT + threadIdx.x;
+    if (t >= (int64_t)B * (K + 1)) return;
+    int i = (int)(t / (K + 1)), r = (int)(t % (K + 1));
+    int32_t y = labels[i];
+    if (y < 0 || y >= C) {
+        if (r == 0) ks_flag(dev_status, KS_DEV_BAD_LABEL);
+        return;
+    }
+    int32_t c = y;
+    if (r > 0) {
+        c = graph[(int64_t)y * K + (r - 1)];
+        if (c == -1) return;
+        if (c < -1 || c >= C) {
+            ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
+            return;
+        }
+    }
+    atomicMin(&score[c], r);
+}
+
+__global__ void __launch_bounds__(SEL_NT)
+sel_hist_kernel(const int32_t *__restrict__ score, int64_t C, int K, int32_t *hist) {
+    __shared__ int32_t lh[SEL_LDS_BINS];
+    const bool use_lds = (K + 1) <= SEL_LDS_BINS;
+    if (use_lds) {
+        for (int r = threadIdx.x; r <= K; r += SEL_NT) lh[r] = 0;
+        __syncthreads();
+    }
+    int64_t c0 = (int64_t)blockIdx.x * SEL_SEG;
+    for (int e = 0; e < SEL_PER; ++e) {
+        int64_t c = c0 + (int64_t)e * SEL_NT + threadIdx.x;
+        if (c < C) {
+            int32_t r = score[c];
+            if (r != SEL_NONE) {
+                if (use_lds) atomicAdd(&lh[r], 1);
+                else atomicAdd(&hist[r], 1);
+            }
+        }
+    }
+    if (use_lds) {
+        __syncthreads();
+        for (int r = threadIdx.x; r <= K; r += SEL_NT)
+            if (lh[r]) atomicAdd(&hist[r], lh[r]);
+    }
+}
+
+// single block: find the score threshold for the cut to M
+__global__ void __launch_bounds__(1024) sel_plan_kernel(const int32_t *__restrict__ hist, int K, int M, SelPlan *plan) {
+    __shared__ int sh[1024 / 64 + 1];
+    __shared__ int s_rstar, s_quota;
+    if (threadIdx.x == 0) { s_rstar = K + 1; s_quota = 0; }
+    __syncthreads();
+    int carry = 0;
+    for (int r0 = 0; r0 <= K; r0 += 1024) {
+        int r = r0 + threadIdx.x;
+        int v = (r <= K) ? hist[r] : 0;
+        int tot;
+        int ex = ks_block_escan<1024>(v, sh, &tot) + carry; // classes with score < r
+        // the unique r at which the running count first exceeds M
+        if (r <= K && ex <= M && ex + v > M) { s_rstar = r; s_quota = M - ex; }
+        carry += tot;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        plan->r_star = s_rstar;
+        plan->quota = s_quota;
+        plan->n_unique = carry;
+        plan->n_active = carry < M ? carry : M;
+    }
+}
+
+__global__ void __launch_bounds__(SEL_NT)
+sel_count_kernel(const int32_t *__restrict__ score, int64_t C, const SelPlan *plan, int32_t *blk_cnt) {
+    __shared__ int s_lt[SEL_NT / 64], s_eq[SEL_NT / 64];
+    const int r_star = plan->r_star;
+    int lt = 0, eq = 0;
+    int64_t c0 = (int64_t)blockIdx.x * SEL_SEG + (int64_t)threadIdx.x * SEL_PER;
+    for (int e = 0; e < SEL_PER; ++e) {
+        int64_t c = c0 + e;
+        if (c < C) {
+            int32_t r = score[c];
+            lt += (r < r_star);
+            eq += (r == r_star);
+        }
+    }
+    lt = ks_wave_sum_i(lt);
+    eq = ks_wave_sum_i(eq);
+    if ((threadIdx.x & 63) == 0) { s_lt[threadIdx.x >> 6] = lt; s_eq[threadIdx.x >> 6] = eq; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int a = 0, b = 0;
+        for (int w = 0; w < SEL_NT / 64; ++w) { a += s_lt[w]; b += s_eq[w]; }
+        blk_cnt[2 * blockIdx.x] = a;
+        blk_cnt[2 * blockIdx.x + 1] = b;
+    }
+}
+
+// single block: exclusive prefixes over table blocks of (#kept, #score == r_star)
+__global__ void __launch_bounds__(1024)
+sel_scan_kernel(const int32_t *__restrict__ blk_cnt, int nblk, const SelPlan *plan, int32_t *blk_base) {
+    __shared__ int sh[1024 / 64 + 1];
+    const int quota = plan->quota;
+    int carry_eq = 0, carry_keep = 0;
+    for (int b0 = 0; b0 < nblk; b0 += 1024) {
+        int b = b0 + threadIdx.x;
+        int lt = (b < nblk) ? blk_cnt[2 * b] : 0;
+        int eq = (b < nblk) ? blk_cnt[2 * b + 1] : 0;
+        int tot_eq;
+        int ex_eq = ks_block_escan<1024>(eq, sh, &tot_eq) + carry_eq;
+        int rem = quota - ex_eq;                                   // quota left when this block starts
+        int keep_eq = rem <= 0 ? 0 : (rem < eq ? rem : eq);
+        int tot_keep;
+        int ex_keep = ks_block_escan<1024>(lt + keep_eq, sh, &tot_keep) + carry_keep;
+        if (b < nblk) { blk_base[2 * b] = ex_keep; blk_base[2 * b + 1] = ex_eq; }
+        carry_eq += tot_eq;
+        carry_keep += tot_keep;
+    }
+}
+
+// compaction: writes the ascending active list and turns score[c] into the position of c (or -1)
+__global__ void __launch_bounds__(SEL_NT)
+sel_emit_kernel(int32_t *score, int64_t C, const SelPlan *plan, const int32_t *__restrict__ blk_base, int M,
+                int32_t *active_idx) {
+    __shared__ int sh[SEL_NT / 64 + 1];
+    const int r_star = plan->r_star, quota = plan->quota;
+    const int64_t c0 = (int64_t)blockIdx.x * SEL_SEG + (int64_t)threadIdx.x * SEL_PER;
+    int32_t r[SEL_PER];
+    int eq = 0;
+    for (int e = 0; e < SEL_PER; ++e) {
+        int64_t c = c0 + e;
+        r[e] = (c < C) ? score[c] : SEL_NONE;
+        eq += (r[e] == r_star);
+    }
+    int tot;
+    int eq_rank = ks_block_escan<SEL_NT>(eq, sh, &tot) + blk_base[2 * blockIdx.x + 1];
+    int keep = 0;
+    unsigned mask = 0;
+    for (int e = 0; e < SEL_PER; ++e) {
+        bool k = r[e] < r_star;
+        if (r[e] == r_star) { k = eq_rank < quota; ++eq_rank; }
+        if (k) { mask |= 1u << e; ++keep; }
+    }
+    int pos = ks_block_escan<SEL_NT>(keep, sh, &tot) + blk_base[2 * blockIdx.x];
+    for (int e = 0; e < SEL_PER; ++e) {
+        int64_t c = c0 + e;
+        if (c >= C) break;
+        if (mask & (1u << e)) {
+            if (pos < M) active_idx[pos] = (int32_t)c; // pos < M always holds; the test keeps stores in bounds
+            score[c] = pos;
+            ++pos;
+        } else {
+            score[c] = -1;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(SEL_NT)
+sel_finish_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict__ score, int64_t C, int B, int M,
+                  const SelPlan *plan, int32_t *active_idx, int32_t *n_active, int32_t *target_pos) {
+    int t = blockIdx.x * SEL_NT + threadIdx.x;
+    const int n = plan->n_active;
+    if (t == 0) *n_active = n;
+    if (t < B) {
+        int32_t y = labels[t];
+        int32_t p = (y >= 0 && y < C) ? score[y] : 0;
+        target_pos[t] = (p >= 0 && p < n) ? p : 0; // in range even for broken inputs (those are flagged)
+    }
+    if (t >= n && t < M) active_idx[t] = -1;
+}
+
+int ks_select_launch(const int32_t *labels, const int32_t *graph, int64_t C, int B, int K, int M,
+                     int32_t *active_idx, int32_t *n_active, int32_t *target_pos, void *ws,
+                     int32_t *dev_status, hipStream_t st) {
+    SelWs w = sel_carve(ws, C, K);
+    int fill_blocks = (int)(ks_ceil_div(C, SEL_NT) < 2048 ? ks_ceil_div(C, SEL_NT) : 2048);
+    hipLaunchKernelGGL(sel_init_kernel, dim3(fill_blocks), dim3(SEL_NT), 0, st, w.score, C, w.hist, K);
+    int64_t n_cand = (int64_t)B * (K + 1);
+    hipLaunchKernelGGL(sel_mark_kernel, dim3((unsigned)ks_ceil_div(n_cand, SEL_NT)), dim3(SEL_NT), 0, st, labels, graph,
+                       C, B, K, w.score, dev_status);
+    hipLaunchKernelGGL(sel_hist_kernel, dim3(w.nblk), dim3(SEL_NT), 0, st, w.score, C, K, w.hist);
+    hipLaunchKernelGGL(sel_plan_kernel, dim3(1), dim3(1024), 0, st, w.hist, K, M, w.plan);
+    hipLaunchKernelGGL(sel_count_kernel, dim3(w.nblk), dim3(SEL_NT), 0, st, w.score, C, w.plan, w.blk_cnt);
+    hipLaunchKernelGGL(sel_scan_kernel, dim3(1), dim3(1024), 0, st, w.blk_cnt, w.nblk, w.plan, w.blk_base);
+    hipLaunchKernelGGL(sel_emit_kernel, dim3(w.nblk), dim3(SEL_NT), 0, st, w.score, C, w.plan, w.blk_base, M,
+                       active_idx);
+    int fin = B > M ? B : M;
+    hipLaunchKernelGGL(sel_finish_kernel, dim3((unsigned)ks_ceil_div(fin, SEL_NT)), dim3(SEL_NT), 0, st, labels, w.score,
+                       C, B, M, w.plan, active_idx, n_active, target_pos);
+    KS_LAUNCH_CHECK();
+    return KS_OK;
+}
+
+extern "C" size_t knn_select_workspace(int64_t C, int B, int K, int M) {
+    (void)B; (void)M;
+    if (C < 1 || K < 0) return 0;
+    return ks_select_ws_bytes(C, K);
+}
+
+extern "C" int knn_select_active(const int32_t *labels, const int32_t *graph, int64_t C, int B, int K, int M,
+                                 int32_t *active_idx, int32_t *n_active, int32_t *target_pos, void *ws,
+                                 size_t ws_bytes, int32_t *dev_status, void *stream) {
+    if (!labels || !active_idx || !n_active || !target_pos || !ws) return KS_INVALID_ARG;
+    if (C < 1 || C >= (int64_t)1 << 31 || B < 1 || K < 0 || M < 1) return KS_INVALID_ARG;
+    if (K > 0 && !graph) return KS_INVALID_ARG;
+    if (B > M || (int64_t)K + 1 > M) return KS_INVALID_ARG;
+    if (ws_bytes < ks_select_ws_bytes(C, K)) return KS_WORKSPACE_TOO_SMALL;
+    return ks_select_launch(labels, graph, C, B, K, M, active_idx, n_active, target_pos, ws, dev_status,
+                            (hipStream_t)stream);
+}

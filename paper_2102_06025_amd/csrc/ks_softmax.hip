@@ -1,0 +1,382 @@
+// KNN-softmax forward + backward on the active classes (paper Section 3.2; Section 3.1 steps 3-5).
+//
+// Pipeline on one stream (A = number of active classes, known only on the device):
+//   select            -> active_idx, n_active, target_pos                         (ks_select.hip)
+//   logits GEMM       Z[B, A]  = scale * X . W[active]^T     rows of W fetched through the index list
+//   row statistics    lse_i, loss_i                           one workgroup per sample
+//   loss mean         fixed-order tree sum
+//   logit gradient    dZ[B, A] = g (exp(Z - lse) - onehot)    bf16
+//   dX GEMM           split over the active dimension, partial tiles summed in a fixed order
+//   dW GEMM           dW_active[A, D] = scale * dZ^T . X
+// Launch sizes are taken from the cap M; workgroups beyond the active count exit at once.
+#include "ks_gemm.h"
+#include "ks_select.h"
+
+typedef KsTile<128, 128, 64, 2, 2> TileG;
+
+#define SM_NT 256
+#define KS_MP_ALIGN 256
+
+static inline int64_t sm_mp(int64_t M) { return (int64_t)ks_align_up((size_t)M, KS_MP_ALIGN); }
+
+__device__ __forceinline__ int sm_clamp_n(const int32_t *n_active, int M) {
+    int n = *n_active;
+    return n < 0 ? 0 : (n > M ? M : n);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Z = scale * X . W[active]^T      (M index = sample i, N index = active position a, K index = d)
+// ------------------------------------------------------------------------------------------------
+template <class T>
+__global__ void __launch_bounds__(T::NT)
+logits_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, const int32_t *__restrict__ active_idx,
+              const int32_t *__restrict__ n_active_p, int B, int D, int M, float scale, float *__restrict__ Z,
+              int64_t ldz) {
+    __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
+    const int n_active = sm_clamp_n(n_active_p, M);
+    const int tiles_m = (B + T::BM - 1) / T::BM;
+    const int n_tiles = tiles_m * ((n_active + T::BN - 1) / T::BN);
+    if ((int)blockIdx.x >= n_tiles) return;
+    const int t = ks_xcd_remap(blockIdx.x, n_tiles);
+    const int tm = t % tiles_m, tn = t / tiles_m;
+
+    KsRowLoader<T::BM, T::BK, T::NT> al;
+    KsRowLoader<T::BN, T::BK, T::NT> bl;
+    al.init(X, D, nullptr, tm * T::BM, B, D);
+    bl.init(W, D, active_idx, tn * T::BN, n_active, D);
+    f32x16_t acc[T::FM][T::FN];
+    ks_tile_clear<T>(acc);
+    ks_gemm_mainloop<T>(al, bl, 0, (D + T::BK - 1) / T::BK, lds, acc);
+    ks_tile_foreach<T>(acc, [&](int m, int n, float v) {
+        int i = tm * T::BM + m, a = tn * T::BN + n;
+        if (i < B && a < n_active) Z[(int64_t)i * ldz + a] = scale * v;
+    });
+}
+
+// ------------------------------------------------------------------------------------------------
+// per-sample log-sum-exp and loss; one workgroup per sample
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(SM_NT)
+row_stats_kernel(const float *__restrict__ Z, int64_t ldz, const int32_t *__restrict__ n_active_p, int M,
+                 const int32_t *__restrict__ target_pos, float *__restrict__ lse_out, float *__restrict__ loss_i) {
+    __shared__ float sm[SM_NT / 64], sl[SM_NT / 64];
+    const int i = blockIdx.x;
+    const int n = sm_clamp_n(n_active_p, M);
+    const float *z = Z + (int64_t)i * ldz;
+    float m = -INFINITY, l = 0.f;
+    const int n4 = n & ~3;
+    for (int a = threadIdx.x * 4; a < n4; a += SM_NT * 4) {
+        float4 v = *(const float4 *)(z + a);
+        float mx = fmaxf(fmaxf(v.x, v.y), fmaxf(v.z, v.w));
+        if (mx > m) { l *= __expf(m - mx); m = mx; }
+        l += __expf(v.x - m) + __expf(v.y - m) + __expf(v.z - m) + __expf(v.w - m);
+    }
+    if (threadIdx.x < n - n4) {
+        float v = z[n4 + threadIdx.x];
+        if (v > m) { l *= __expf(m - v); m = v; }
+        l += __expf(v - m);
+    }
+    // combine (m, l) pairs: wave, then block, in a fixed order
+    float wm = ks_wave_max(m);
+    float wl = ks_wave_sum(m == -INFINITY ? 0.f : l * __expf(m - wm));
+    if ((threadIdx.x & 63) == 0) { sm[threadIdx.x >> 6] = wm; sl[threadIdx.x >> 6] = wl; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float bm = sm[0];
+        for (int w = 1; w < SM_NT / 64; ++w) bm = fmaxf(bm, sm[w]);
+        float bl = 0.f;
+        for (int w = 0; w < SM_NT / 64; ++w) bl += (sm[w] == -INFINITY) ? 0.f : sl[w] * __expf(sm[w] - bm);
+        float lse = bm + __logf(bl);
+        int tp = target_pos[i];
+        float zt = (tp >= 0 && tp < n) ? z[tp] : 0.f;
+        lse_out[i] = lse;
+        loss_i[i] = lse - zt;
+    }
+}
+
+__global__ void __launch_bounds__(SM_NT) loss_mean_kernel(const float *__restrict__ loss_i, int B, float *loss_mean) {
+    __shared__ float sh[SM_NT];
+    float s = 0.f;
+    for (int i = threadIdx.x; i < B; i += SM_NT) s += loss_i[i];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (int o = SM_NT / 2; o > 0; o >>= 1) {
+        if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss_mean = sh[0] / (float)B;
+}
+
+// ------------------------------------------------------------------------------------------------
+// dZ = g (exp(Z - lse) - onehot) as bf16; columns in [n_active, round_up(n_active, 256)) are zeroed
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(SM_NT)
+dz_kernel(const float *__restrict__ Z, int64_t ldz, const int32_t *__restrict__ n_active_p, int M,
+          const int32_t *__restrict__ target_pos, const float *__restrict__ lse, float g, uint16_t *__restrict__ dZ) {
+    const int n = sm_clamp_n(n_active_p, M);
+    const int n_pad = (n + KS_MP_ALIGN - 1) / KS_MP_ALIGN * KS_MP_ALIGN; // <= ldz
+    const int a0 = (blockIdx.x * SM_NT + threadIdx.x) * 8;
+    if (a0 >= n_pad) return;
+    const int i = blockIdx.y;
+    const float ls = lse[i];
+    const int tp = target_pos[i];
+    const float *z = Z + (int64_t)i * ldz + a0;
+    float v[8];
+    if (a0 + 8 <= n) {
+        float4 p = *(const float4 *)z, q = *(const float4 *)(z + 4);
+        v[0] = p.x; v[1] = p.y; v[2] = p.z; v[3] = p.w; v[4] = q.x; v[5] = q.y; v[6] = q.z; v[7] = q.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (a0 + e < n) ? z[e] : 0.f;
+    }
+    uint32_t o[4];
+#pragma unroll
+    for (int e = 0; e < 8; e += 2) {
+        float d0 = (a0 + e < n) ? g * (__expf(v[e] - ls) - (a0 + e == tp ? 1.f : 0.f)) : 0.f;
+        float d1 = (a0 + e + 1 < n) ? g * (__expf(v[e + 1] - ls) - (a0 + e + 1 == tp ? 1.f : 0.f)) : 0.f;
+        o[e / 2] = ks_pack_bf2(d0, d1);
+    }
+    *(uint4 *)(dZ + (int64_t)i * ldz + a0) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// dX partials: P[s][i][d] = sum over the s-th share of a of dZ[i][a] * W[active[a]][d]
+// ------------------------------------------------------------------------------------------------
+template <class T>
+__global__ void __launch_bounds__(T::NT)
+dx_partial_kernel(const uint16_t *__restrict__ dZ, int64_t ldz, const uint16_t *__restrict__ W,
+                  const int32_t *__restrict__ active_idx, const int32_t *__restrict__ n_active_p, int B, int D, int M,
+                  float *__restrict__ part) {
+    __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
+    const int n_active = sm_clamp_n(n_active_p, M);
+    const int tiles_m = (B + T::BM - 1) / T::BM;
+    const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+    const int s = blockIdx.y, S = gridDim.y;
+    const int nk = (n_active + T::BK - 1) / T::BK;
+    const int per = (nk + S - 1) / S;
+    const int kt0 = s * per, kt1 = (kt0 + per < nk) ? kt0 + per : nk;
+
+    KsRowLoader<T::BM, T::BK, T::NT> al;
+    KsColLoader<T::BN, T::BK, T::NT> bl;
+    al.init(dZ, ldz, nullptr, tm * T::BM, B, (n_active + 7) & ~7);
+    bl.init(W, D, active_idx, tn * T::BN, D, n_active);
+    f32x16_t acc[T::FM][T::FN];
+    ks_tile_clear<T>(acc);
+    ks_gemm_mainloop<T>(al, bl, kt0, kt1, lds, acc);
+    float *out = part + (int64_t)s * B * D;
+    ks_tile_foreach<T>(acc, [&](int m, int n, float v) {
+        int i = tm * T::BM + m, d = tn * T::BN + n;
+        if (i < B && d < D) out[(int64_t)i * D + d] = v;
+    });
+}
+
+__global__ void __launch_bounds__(SM_NT)
+dx_reduce_kernel(const float *__restrict__ part, int S, int64_t BD, float scale, float *__restrict__ dX) {
+    int64_t e = ((int64_t)blockIdx.x * SM_NT + threadIdx.x) * 4;
+    if (e >= BD) return; // BD % 4 == 0
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < S; ++s) {
+        float4 v = *(const float4 *)(part + (int64_t)s * BD + e);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    *(float4 *)(dX + e) = make_float4(scale * acc.x, scale * acc.y, scale * acc.z, scale * acc.w);
+}
+
+// ------------------------------------------------------------------------------------------------
+// dW_active[a][d] = scale * sum_i dZ[i][a] * X[i][d]     (both operands k-major: k = i)
+// ------------------------------------------------------------------------------------------------
+template <class T>
+__global__ void __launch_bounds__(T::NT)
+dw_kernel(const uint16_t *__restrict__ dZ, int64_t ldz, const uint16_t *__restrict__ X,
+          const int32_t *__restrict__ n_active_p, int B, int D, int M, float scale, float *__restrict__ dW) {
+    __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
+    const int n_active = sm_clamp_n(n_active_p, M);
+    const int tiles_n = (D + T::BN - 1) / T::BN;
+    const int n_tiles = tiles_n * ((n_active + T::BM - 1) / T::BM);
+    if ((int)blockIdx.x >= n_tiles) return;
+    const int t = ks_xcd_remap(blockIdx.x, n_tiles);
+    const int tn = t % tiles_n, tm = t / tiles_n;
+
+    KsColLoader<T::BM, T::BK, T::NT> al;
+    KsColLoader<T::BN, T::BK, T::NT> bl;
+    al.init(dZ, ldz, nullptr, tm * T::BM, (int)ldz, B);
+    bl.init(X, D, nullptr, tn * T::BN, D, B);
+    f32x16_t acc[T::FM][T::FN];
+    ks_tile_clear<T>(acc);
+    ks_gemm_mainloop<T>(al, bl, 0, (B + T::BK - 1) / T::BK, lds, acc);
+    ks_tile_foreach<T>(acc, [&](int m, int n, float v) {
+        int a = tm * T::BM + m, d = tn * T::BN + n;
+        if (a < n_active && d < D) dW[(int64_t)a * D + d] = scale * v;
+    });
+}
+
+// ------------------------------------------------------------------------------------------------
+// stand-alone row gather (Algorithm 1's W_active as a dense matrix); one wavefront per row
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(SM_NT)
+gather_rows_kernel(const uint16_t *__restrict__ W, const int32_t *__restrict__ active_idx,
+                   const int32_t *__restrict__ n_active_p, int M, int64_t C, int D, uint16_t *__restrict__ out,
+                   int32_t *dev_status) {
+    const int n = sm_clamp_n(n_active_p, M);
+    const int a = blockIdx.x * (SM_NT / 64) + (threadIdx.x >> 6);
+    if (a >= n) return;
+    const int32_t c = active_idx[a];
+    if (c < 0 || c >= C) {
+        if ((threadIdx.x & 63) == 0) ks_flag(dev_status, KS_DEV_BAD_INDEX);
+        return;
+    }
+    const uint4 *src = (const uint4 *)(W + (int64_t)c * D);
+    uint4 *dst = (uint4 *)(out + (int64_t)a * D);
+    for (int q = threadIdx.x & 63; q < D / 8; q += 64) dst[q] = src[q];
+}
+
+// identity active list for the full-softmax entry point
+__global__ void __launch_bounds__(SM_NT)
+full_prepare_kernel(const int32_t *__restrict__ labels, int64_t C, int B, int32_t *active_idx, int32_t *n_active,
+                    int32_t *target_pos, int32_t *dev_status) {
+    int64_t t = (int64_t)blockIdx.x * SM_NT + threadIdx.x;
+    if (t == 0) *n_active = (int32_t)C;
+    if (t < C) active_idx[t] = (int32_t)t;
+    if (t < B) {
+        int32_t y = labels[t];
+        if (y < 0 || y >= C) { ks_flag(dev_status, KS_DEV_BAD_LABEL); y = 0; }
+        target_pos[t] = y;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+struct SmWs {
+    void *select;
+    float *Z;
+    uint16_t *dZ;
+    float *lse;
+    float *part;
+    int S;
+    int64_t Mp;
+};
+
+static int sm_splits(int B, int D) {
+    int tiles = (int)(ks_ceil_div(B, TileG::BM) * ks_ceil_div(D, TileG::BN));
+    int S = (int)ks_ceil_div(512, tiles);
+    if (S < 1) S = 1;
+    if (S > 32) S = 32;
+    return S;
+}
+
+static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool with_select, size_t *total) {
+    KsArena ar(ws);
+    SmWs w;
+    w.Mp = sm_mp(M);
+    w.S = sm_splits(B, D);
+    w.select = with_select ? (void *)ar.take<char>(ks_select_ws_bytes(C, K)) : nullptr;
+    w.Z = ar.take<float>((size_t)B * w.Mp);
+    w.dZ = ar.take<uint16_t>((size_t)B * w.Mp);
+    w.lse = ar.take<float>((size_t)B);
+    w.part = ar.take<float>((size_t)w.S * B * D);
+    if (total) *total = ar.off;
+    return w;
+}
+
+// everything after the selection; active_idx / n_active / target_pos are device-resident inputs here
+static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M, float scale, float grad_scale,
+                  const int32_t *active_idx, const int32_t *n_active, const int32_t *target_pos,
+                  float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, const SmWs &w,
+                  hipStream_t st) {
+    typedef TileG T;
+    const int Mi = (int)M;
+    const int tiles_b = (int)ks_ceil_div(B, T::BM);
+    const int tiles_a_n = (int)ks_ceil_div(M, T::BN), tiles_a_m = (int)ks_ceil_div(M, T::BM);
+    const int tiles_d = (int)ks_ceil_div(D, T::BN);
+
+    hipLaunchKernelGGL(logits_kernel<T>, dim3(tiles_b * tiles_a_n), dim3(T::NT), 0, st, X, W, active_idx, n_active, B, D,
+                       Mi, scale, w.Z, w.Mp);
+    hipLaunchKernelGGL(row_stats_kernel, dim3(B), dim3(SM_NT), 0, st, w.Z, w.Mp, n_active, Mi, target_pos, w.lse,
+                       loss_per_sample);
+    hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(SM_NT), 0, st, loss_per_sample, B, loss_mean);
+    hipLaunchKernelGGL(dz_kernel, dim3((unsigned)ks_ceil_div(w.Mp, SM_NT * 8), B), dim3(SM_NT), 0, st, w.Z, w.Mp, n_active,
+                       Mi, target_pos, w.lse, grad_scale / (float)B, w.dZ);
+    hipLaunchKernelGGL(dx_partial_kernel<T>, dim3(tiles_b * tiles_d, w.S), dim3(T::NT), 0, st, w.dZ, w.Mp, W, active_idx,
+                       n_active, B, D, Mi, w.part);
+    hipLaunchKernelGGL(dx_reduce_kernel, dim3((unsigned)ks_ceil_div((int64_t)B * D / 4, SM_NT)), dim3(SM_NT), 0, st, w.part,
+                       w.S, (int64_t)B * D, scale, dX);
+    hipLaunchKernelGGL(dw_kernel<T>, dim3(tiles_a_m * tiles_d), dim3(T::NT), 0, st, w.dZ, w.Mp, X, n_active, B, D, Mi,
+                       scale, dW_active);
+    KS_LAUNCH_CHECK();
+    return KS_OK;
+}
+
+static int sm_check_dims(int64_t C, int D, int B) {
+    if (C < 1 || C >= (int64_t)1 << 31 || D < 32 || D % 32 != 0 || B < 1) return KS_INVALID_ARG;
+    return KS_OK;
+}
+
+extern "C" size_t knn_softmax_workspace(int64_t C, int D, int B, int K, int M) {
+    if (sm_check_dims(C, D, B) != KS_OK || K < 0 || M < 1) return 0;
+    size_t total = 0;
+    sm_carve(nullptr, C, D, B, K, M, true, &total);
+    return total;
+}
+
+extern "C" int knn_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
+                                   const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
+                                   float grad_scale, int32_t *active_idx, int32_t *n_active, int32_t *target_pos,
+                                   float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, void *ws,
+                                   size_t ws_bytes, int32_t *dev_status, void *stream) {
+    if (!W_bf16 || !X_bf16 || !labels || !active_idx || !n_active || !target_pos || !loss_per_sample || !loss_mean ||
+        !dX || !dW_active || !ws)
+        return KS_INVALID_ARG;
+    if (sm_check_dims(C, D, B) != KS_OK || K < 0 || M < 1) return KS_INVALID_ARG;
+    if (K > 0 && !graph) return KS_INVALID_ARG;
+    if (B > M || (int64_t)K + 1 > M) return KS_INVALID_ARG;
+    size_t need = 0;
+    SmWs w = sm_carve(ws, C, D, B, K, M, true, &need);
+    if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    int rc = ks_select_launch(labels, graph, C, B, K, M, active_idx, n_active, target_pos, w.select, dev_status, st);
+    if (rc != KS_OK) return rc;
+    return sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, active_idx, n_active, target_pos, loss_per_sample,
+                  loss_mean, dX, dW_active, w, st);
+}
+
+extern "C" size_t full_softmax_workspace(int64_t C, int D, int B) {
+    if (sm_check_dims(C, D, B) != KS_OK) return 0;
+    size_t total = 0;
+    sm_carve(nullptr, C, D, B, 0, C, false, &total);
+    total += ks_align_up((size_t)C * 4, 256) + ks_align_up((size_t)B * 4, 256) + 256;
+    return total;
+}
+
+extern "C" int full_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels, int64_t C,
+                                    int D, int B, float scale, float grad_scale, float *loss_per_sample,
+                                    float *loss_mean, float *dX, float *dW, void *ws, size_t ws_bytes,
+                                    int32_t *dev_status, void *stream) {
+    if (!W_bf16 || !X_bf16 || !labels || !loss_per_sample || !loss_mean || !dX || !dW || !ws) return KS_INVALID_ARG;
+    if (sm_check_dims(C, D, B) != KS_OK) return KS_INVALID_ARG;
+    if (ws_bytes < full_softmax_workspace(C, D, B)) return KS_WORKSPACE_TOO_SMALL;
+    size_t used = 0;
+    SmWs w = sm_carve(ws, C, D, B, 0, C, false, &used);
+    KsArena ar((char *)ws + used);
+    int32_t *active_idx = ar.take<int32_t>((size_t)C);
+    int32_t *target_pos = ar.take<int32_t>((size_t)B);
+    int32_t *n_active = ar.take<int32_t>(1);
+    hipStream_t st = (hipStream_t)stream;
+    int64_t n = C > B ? C : B;
+    hipLaunchKernelGGL(full_prepare_kernel, dim3((unsigned)ks_ceil_div(n, SM_NT)), dim3(SM_NT), 0, st, labels, C, B,
+                       active_idx, n_active, target_pos, dev_status);
+    return sm_run(W_bf16, X_bf16, D, B, C, scale, grad_scale, active_idx, n_active, target_pos, loss_per_sample,
+                  loss_mean, dX, dW, w, st);
+}
+
+extern "C" int knn_gather_rows(const uint16_t *W_bf16, const int32_t *active_idx, const int32_t *n_active, int M,
+                               int64_t C, int D, uint16_t *out, int32_t *dev_status, void *stream) {
+    if (!W_bf16 || !active_idx || !n_active || !out) return KS_INVALID_ARG;
+    if (M < 1 || C < 1 || D < 8 || D % 8 != 0) return KS_INVALID_ARG;
+    hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)ks_ceil_div(M, SM_NT / 64)), dim3(SM_NT), 0, (hipStream_t)stream,
+                       W_bf16, active_idx, n_active, M, C, D, out, dev_status);
+    KS_LAUNCH_CHECK();
+    return KS_OK;
+}
+
+extern "C" const char *ks_version(void) { return "knnsoftmax 0.1 (gfx950)"; }

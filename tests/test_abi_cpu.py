@@ -1,0 +1,104 @@
+"""CPU-side checks of the C-ABI library: it loads without a GPU, exports every symbol the header declares,
+sizes its workspaces sensibly and rejects bad arguments before touching the device."""
+import ctypes as ct
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "knnsoftmax.h")
+
+
+@pytest.fixture(scope="module")
+def ks():
+    import paper_2102_06025_amd as ks
+    if not os.path.exists(ks.lib_path()):
+        from paper_2102_06025_amd.build import build
+        build()
+    ks.lib()
+    return ks
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad))\s*\(", src)))
+
+
+def test_header_symbols_are_exported(ks):
+    names = _declared_functions()
+    assert {"knn_graph_build", "knn_softmax_fwd_bwd", "apply_weight_grad"} <= set(names)
+    L = ks.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in the header but not exported"
+    assert "gfx950" in ks.ks_version()
+
+
+def test_index_and_weight_types_match_the_papers_byte_counts():
+    # Section 3.1: 100 M x 512 weights are "about 190 GB" => 4-byte weights; Section 3.2.3: a 100 M x 1000 graph is
+    # "about 372 GB" => 4-byte ids (tests/golden/paper_sizes.txt)
+    gold = dict(l.split()[:2] for l in open(os.path.join(ROOT, "tests", "golden", "paper_sizes.txt")) if l[0] != "#")
+    assert int(100e6 * 512 * 4 / 2 ** 30) == int(gold["fc_weight_GiB"])
+    assert int(100e6 * 1000 * 4 / 2 ** 30) == int(gold["graph_GiB"])
+    src = open(HEADER).read()
+    assert "int32_t *graph" in src and "float *W_master" in src
+
+
+def test_workspace_sizes(ks):
+    a = ks.knn_softmax_workspace(390625, 512, 1024, 32, 32768)
+    # at least Z (fp32) + dZ (bf16) + the selection table
+    assert a >= 1024 * 32768 * 6 + 390625 * 4
+    assert a < 1 << 30
+    assert ks.knn_softmax_workspace(100, 33, 4, 2, 8) == 0          # D % 32 != 0
+    assert ks.knn_graph_build_workspace(1000, 128, 200, 0) == 0     # K too large
+    assert ks.knn_graph_build_workspace(390625, 512, 32, 0) < 4 << 30
+    assert ks.apply_weight_grad_workspace(1000, 128, 100, 1) <= 256
+    assert ks.apply_weight_grad_workspace(1000, 128, 100, 0) >= 128 * 8
+
+
+def test_argument_errors_are_reported_before_any_launch(ks):
+    L = ks.lib()
+    null = ct.c_void_p(0)
+    one = ct.c_void_p(256)  # never dereferenced: validation fails first
+    i64, i, f, sz = ct.c_int64, ct.c_int, ct.c_float, ct.c_size_t
+
+    def fwd(C=1000, D=128, B=8, K=4, M=64, W=one, ws_bytes=1 << 30):
+        return L.knn_softmax_fwd_bwd(W, one, one, one, i64(C), i(D), i(B), i(K), i(M), f(30.0), f(1.0), one, one, one,
+                                     one, one, one, one, one, sz(ws_bytes), null, null)
+
+    assert fwd(W=null) == ks.KS_INVALID_ARG
+    assert fwd(D=100) == ks.KS_INVALID_ARG            # D % 32
+    assert fwd(B=65) == ks.KS_INVALID_ARG             # B > M
+    assert fwd(K=64) == ks.KS_INVALID_ARG             # K + 1 > M
+    assert fwd(C=0) == ks.KS_INVALID_ARG
+    assert fwd(ws_bytes=1024) == ks.KS_WORKSPACE_TOO_SMALL
+
+    def graph(C=1000, D=128, K=8, dtype=0, ws_bytes=1 << 40):
+        return L.knn_graph_build(one, i(dtype), i64(C), i(D), i(K), one, null, one, sz(ws_bytes), null, null)
+
+    assert graph(K=129) == ks.KS_UNSUPPORTED
+    assert graph(C=8, K=8) == ks.KS_UNSUPPORTED       # K > C - 1
+    assert graph(dtype=7) == ks.KS_INVALID_ARG
+    assert graph(D=72) == ks.KS_INVALID_ARG
+    assert graph(ws_bytes=16) == ks.KS_WORKSPACE_TOO_SMALL
+
+    def apply(n_max=10, D=128, sorted_=1, ws=one, ws_bytes=0, Wm=one):
+        return L.apply_weight_grad(Wm, one, one, null, i(n_max), one, f(-0.1), i64(1000), i(D), i(sorted_), ws,
+                                   sz(ws_bytes), null, null)
+
+    assert apply(Wm=null) == ks.KS_INVALID_ARG
+    assert apply(n_max=0) == ks.KS_INVALID_ARG
+    assert apply(D=6) == ks.KS_INVALID_ARG
+    assert apply(sorted_=0, ws_bytes=8) == ks.KS_WORKSPACE_TOO_SMALL
+    assert L.knn_select_active(one, one, i64(100), i(8), i(4), i(4), one, one, one, one, sz(1 << 20), null,
+                               null) == ks.KS_INVALID_ARG  # B > M
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2102_06025_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "oracle" not in text.lower(), f"{fn} mentions the oracle"

@@ -1,0 +1,344 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+Integer outputs (active list, positions, neighbour lists) must be bit-exact; floating point within
+loss rel. error <= 1e-3 and dX / dW relative Frobenius error <= 2e-2 (bf16 operands, fp32 accumulate)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+LOSS_RTOL = 1e-3
+GRAD_RTOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def ks():
+    import paper_2102_06025_amd as ks
+    ks.lib()
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return ks
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def rel_fro(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = np.linalg.norm(b)
+    return np.linalg.norm(a - b) / den if den > 0 else np.linalg.norm(a - b)
+
+
+def run_and_compare(ks, orc, W, X, y, G, C, M, scale=30.0, grad_scale=1.0, tag=""):
+    """W, X fp32 arrays on the bf16 grid.  Runs both sides and checks every output."""
+    print(f"[case] {tag} C={C} D={W.shape[1]} B={X.shape[0]} K={G.shape[1]} M={M}", flush=True)
+    out = ks.knn_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(G), M, scale, grad_scale)
+    torch.cuda.synchronize()
+    assert int(out["dev_status"].item()) == 0
+    active, A, tpos = orc.select_active(y, G, C, M)
+    ref = orc.knn_softmax_fwd_bwd(W, X, active[:A], tpos, scale, grad_scale)
+    assert int(out["n_active"].item()) == A
+    assert (out["active_idx"].cpu().numpy() == active).all()
+    assert (out["target_pos"].cpu().numpy() == tpos).all()
+    li = out["loss_per_sample"].cpu().numpy()
+    assert np.abs(li - ref["loss_i"]).max() <= LOSS_RTOL * max(1.0, np.abs(ref["loss_i"]).max())
+    loss = float(out["loss_mean"].item())
+    assert abs(loss - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"]), (loss, ref["loss"])
+    e_dx = rel_fro(out["dX"].cpu().numpy(), ref["dX"])
+    e_dw = rel_fro(out["dW_active"][:A].cpu().numpy(), ref["dWA"])
+    print(f"        A={A} loss={loss:.6f} ref={ref['loss']:.6f} relF(dX)={e_dx:.2e} relF(dW)={e_dw:.2e}", flush=True)
+    assert e_dx <= GRAD_RTOL and e_dw <= GRAD_RTOL
+    return out, ref, A
+
+
+# ------------------------------------------------------------------------------------------------
+# selection alone
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("C,K,B,M,seed,empty", [
+    (500, 8, 16, 400, 0, 0.0),          # no cut
+    (500, 8, 64, 100, 1, 0.0),          # cut bites
+    (3000, 16, 128, 600, 2, 0.3),       # empty slots
+    (64, 63, 8, 64, 3, 0.0),            # lists span all classes
+    (200, 5, 200, 200, 4, 0.0),         # B == M
+    (100_000, 16, 256, 4_096, 0, 0.0),  # the "small" configuration: cut bites
+    (390_625, 32, 1_024, 32_768, 0, 0.0),
+    (5000, 2500, 4, 3000, 5, 0.0),      # more list positions than the LDS histogram holds
+])
+def test_select_matches_oracle(ks, orc, C, K, B, M, seed, empty):
+    G = synth.graph_synthetic(seed, C, K, locality=4, empty_frac=empty)
+    y = synth.labels_uniform(seed, B, C)
+    a, n, t, st = ks.knn_select_active(dev(y), dev(G), C, M)
+    torch.cuda.synchronize()
+    ea, eA, et = orc.select_active(y, G, C, M)
+    assert int(st.item()) == 0
+    assert int(n.item()) == eA
+    assert (a.cpu().numpy() == ea).all()
+    assert (t.cpu().numpy() == et).all()
+
+
+def test_select_without_graph_and_flags(ks, orc):
+    y = np.array([5, 3, 5, 9], dtype=np.int32)
+    a, n, t, st = ks.knn_select_active(dev(y), None, 10, 6)
+    assert int(n.item()) == 3 and a.cpu().numpy().tolist() == [3, 5, 9, -1, -1, -1]
+    assert t.cpu().numpy().tolist() == [1, 0, 1, 2]
+    # out-of-range label / neighbour id: flagged, no crash
+    G = synth.graph_synthetic(0, 50, 4)
+    G[7, 2] = 50
+    a, n, t, st = ks.knn_select_active(dev(np.array([7, 60], dtype=np.int32)), dev(G), 50, 20)
+    torch.cuda.synchronize()
+    assert int(st.item()) == (ks.KS_DEV_BAD_LABEL | ks.KS_DEV_BAD_GRAPH_ID)
+
+
+# ------------------------------------------------------------------------------------------------
+# forward + backward
+# ------------------------------------------------------------------------------------------------
+def test_fwd_bwd_tiny_config(ks, orc):
+    cfg = synth.CONFIGS["tiny"]
+    W = synth.bf16_round(synth.unit_rows(0, synth.TID_W, cfg["C"], cfg["D"]))
+    X = synth.bf16_round(synth.unit_rows(0, synth.TID_X, cfg["B"], cfg["D"]))
+    y = synth.make_labels(cfg)
+    G, _ = orc.graph_bruteforce(W, cfg["K"])         # true KNN graph of W, all rows
+    run_and_compare(ks, orc, W, X, y, G, cfg["C"], cfg["M"], tag="tiny")
+
+
+def test_fwd_bwd_small_config_cut_bites(ks, orc):
+    cfg = synth.CONFIGS["small"]
+    W, X = synth.make_WX(cfg)
+    y = synth.make_labels(cfg)
+    G = synth.graph_synthetic(0, cfg["C"], cfg["K"], locality=2)
+    rows = np.unique(y)
+    G[rows], _ = orc.graph_bruteforce(W, cfg["K"], rows)   # true neighbours for the rows selection reads
+    out, ref, A = run_and_compare(ks, orc, W, X, y, G, cfg["C"], cfg["M"], tag="small")
+    assert A == cfg["M"]                                   # about 4,250 distinct candidates > M = 4,096
+
+
+@pytest.mark.parametrize("C,D,B,K,M,seed", [(3000, 96, 50, 7, 333, 1), (777, 32, 1, 4, 5, 2), (5000, 160, 130, 9, 1111, 3),
+                                             (2000, 64, 257, 3, 1000, 4)])
+def test_fwd_bwd_ragged_shapes(ks, orc, C, D, B, K, M, seed):
+    W = synth.unit_rows(seed, synth.TID_W, C, D, bf16=True)
+    X = synth.unit_rows(seed, synth.TID_X, B, D, bf16=True)
+    y = synth.labels_uniform(seed, B, C)
+    G = synth.graph_synthetic(seed, C, K, locality=4)
+    run_and_compare(ks, orc, W, X, y, G, C, M, grad_scale=128.0, tag="ragged")
+
+
+def test_fwd_bwd_peaky_softmax_and_clustered_weights(ks, orc):
+    # features close to their class weight (target logit near the scale), clustered weights (many near-equal logits)
+    C, D, B, K, M = 20_000, 256, 192, 16, 2_048
+    W = synth.clustered_rows(3, C, D, n_centres=512, bf16=True)
+    y = synth.labels_zipf(3, B, C)
+    X = synth.features_near_labels(3, W, y, sigma=0.4, bf16=True)
+    rows = np.unique(y)
+    G = synth.graph_synthetic(3, C, K)
+    G[rows], _ = orc.graph_bruteforce(W, K, rows)
+    out, ref, A = run_and_compare(ks, orc, W, X, y, G, C, M, tag="peaky")
+    # the per-sample losses span orders of magnitude here; check them relatively where they are not tiny
+    li = out["loss_per_sample"].cpu().numpy()
+    big = ref["loss_i"] > 1e-2
+    assert (np.abs(li[big] - ref["loss_i"][big]) <= 5e-3 * ref["loss_i"][big] + 1e-3).all()
+
+
+def test_knn_equals_full_softmax_when_lists_span_all_classes(ks, orc):
+    C, D, B = 4_000, 128, 96
+    W = synth.unit_rows(8, synth.TID_W, C, D, bf16=True)
+    X = synth.unit_rows(8, synth.TID_X, B, D, bf16=True)
+    y = synth.labels_uniform(8, B, C)
+    G = synth.graph_all_others(C)
+    out, ref, A = run_and_compare(ks, orc, W, X, y, G, C, C, tag="K=C-1")
+    assert A == C
+    full = ks.full_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), 30.0, 1.0)
+    torch.cuda.synchronize()
+    # same kernels, same active list => bit-identical
+    assert torch.equal(full["loss_per_sample"], out["loss_per_sample"])
+    assert torch.equal(full["dX"], out["dX"])
+    assert torch.equal(full["dW"], out["dW_active"])
+    ofull = orc.full_softmax_fwd_bwd(W, X, y, 30.0, 1.0)
+    assert abs(float(full["loss_mean"].item()) - ofull["loss"]) <= LOSS_RTOL * ofull["loss"]
+    assert rel_fro(full["dW"].cpu().numpy(), ofull["dW"]) <= GRAD_RTOL
+
+
+def test_full_softmax_on_20000_class_slice(ks, orc):
+    C, D, B = 20_000, 512, 64
+    W = synth.unit_rows(0, synth.TID_W, C, D, bf16=True)
+    X = synth.unit_rows(0, synth.TID_X, B, D, bf16=True)
+    y = synth.labels_uniform(0, B, C)
+    full = ks.full_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), 30.0, 1.0)
+    torch.cuda.synchronize()
+    ref = orc.full_softmax_fwd_bwd(W, X, y, 30.0, 1.0)
+    assert abs(float(full["loss_mean"].item()) - ref["loss"]) <= LOSS_RTOL * ref["loss"]
+    assert rel_fro(full["dX"].cpu().numpy(), ref["dX"]) <= GRAD_RTOL
+    assert rel_fro(full["dW"].cpu().numpy(), ref["dW"]) <= GRAD_RTOL
+
+
+def test_fwd_bwd_is_deterministic_and_softmax_invariants_hold(ks, orc):
+    cfg = synth.CONFIGS["small"]
+    W, X = synth.make_WX(cfg)
+    y = synth.make_labels(cfg)
+    G = synth.graph_synthetic(1, cfg["C"], cfg["K"])
+    args = (dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(G), cfg["M"], 30.0, 1.0)
+    o1 = ks.knn_softmax_fwd_bwd(*args)
+    o2 = ks.knn_softmax_fwd_bwd(*args)
+    torch.cuda.synchronize()
+    for k in ("active_idx", "n_active", "target_pos", "loss_per_sample", "loss_mean", "dX", "dW_active"):
+        n = int(o1["n_active"].item()) if k == "dW_active" else None
+        assert torch.equal(o1[k][:n], o2[k][:n]), k
+    A = int(o1["n_active"].item())
+    # sum_a dZ_ia = 0 => column sums of dW_active vanish (up to bf16 rounding of dZ)
+    dW = o1["dW_active"][:A].double()
+    assert dW.sum(dim=0).abs().max().item() <= 1e-3 * dW.abs().sum(dim=0).max().item()
+
+
+def test_bad_label_sets_flag_and_stays_in_bounds(ks, orc):
+    C, D, B, K, M = 1000, 64, 8, 4, 64
+    W = synth.unit_rows(0, synth.TID_W, C, D, bf16=True)
+    X = synth.unit_rows(0, synth.TID_X, B, D, bf16=True)
+    y = synth.labels_uniform(0, B, C)
+    y[3] = C + 5
+    out = ks.knn_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(synth.graph_synthetic(0, C, K)),
+                                 M, 30.0)
+    torch.cuda.synchronize()
+    assert int(out["dev_status"].item()) & ks.KS_DEV_BAD_LABEL
+
+
+# ------------------------------------------------------------------------------------------------
+# weight update
+# ------------------------------------------------------------------------------------------------
+def _check_apply(ks, orc, W, idx, dW, alpha, sorted_unique, n=None):
+    Wm = dev(W)
+    Wb = dev(synth.bf16_round(W), torch.bfloat16)
+    Wb0 = Wb.clone()
+    n_dev = None if n is None else dev(np.array([n], dtype=np.int32))
+    st = ks.apply_weight_grad(Wm, Wb, dev(idx), n_dev, dev(dW), alpha, idx_sorted_unique=sorted_unique)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    nn = idx.shape[0] if n is None else n
+    eWm, _ = orc.apply_weight_grad(W, idx[:nn], dW[:nn], alpha)
+    got = Wm.cpu().numpy()
+    touched = np.zeros(W.shape[0], dtype=bool)
+    touched[idx[:nn]] = True
+    assert (got[~touched] == W[~touched]).all()                       # untouched rows bit-unchanged
+    assert torch.equal(Wb[torch.from_numpy(~touched).cuda()], Wb0[torch.from_numpy(~touched).cuda()])
+    # fp32 update vs the oracle's fp64 sum: one rounding of the result plus the error of an fp32 sum of
+    # `mult` terms, bounded by mult * 2^-24 * |alpha| * sum |terms|
+    mult = np.bincount(idx[:nn], minlength=W.shape[0]).astype(np.float64)
+    abssum = np.zeros(W.shape, dtype=np.float64)
+    np.add.at(abssum, idx[:nn], np.abs(dW[:nn]).astype(np.float64))
+    bound = 2.0 ** -23 * np.abs(eWm) + (mult[:, None] * 2.0 ** -24) * abs(alpha) * abssum + 1e-12
+    assert (np.abs(got.astype(np.float64) - eWm) <= bound)[touched].all()
+    # the bf16 copy is exactly the round-to-nearest-even of the master the GPU produced
+    gb = Wb.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert (gb[touched] == synth.bf16_bits(got[touched])).all()
+
+
+def test_apply_sorted_unique(ks, orc):
+    C, D = 5000, 512
+    W = synth.unit_rows(1, synth.TID_W, C, D)
+    idx = np.sort(synth.class_permutation(1, C)[:1234]).astype(np.int32)
+    dW = synth.grad_rows(1, idx.shape[0], D)
+    _check_apply(ks, orc, W, idx, dW, -0.05, True)
+    _check_apply(ks, orc, W, idx, dW, -0.05, True, n=1000)   # device-side count below n_max
+    _check_apply(ks, orc, W, idx, dW, -0.05, False)          # the general path gives the same
+
+
+@pytest.mark.parametrize("n,D,hi", [(300, 96, 40), (5000, 128, 700), (9000, 64, 3), (1, 32, 1)])
+def test_apply_with_repeated_indices(ks, orc, n, D, hi):
+    C = 1000
+    rng = np.random.default_rng(n)
+    W = synth.unit_rows(2, synth.TID_W, C, D)
+    idx = rng.integers(0, hi, n).astype(np.int32)
+    dW = synth.grad_rows(2, n, D)
+    _check_apply(ks, orc, W, idx, dW, 0.25, False)
+    # deterministic: a second run on the same inputs gives the same bits
+    Wm1, Wm2 = dev(W), dev(W)
+    ks.apply_weight_grad(Wm1, None, dev(idx), None, dev(dW), 0.25, False)
+    ks.apply_weight_grad(Wm2, None, dev(idx), None, dev(dW), 0.25, False)
+    torch.cuda.synchronize()
+    assert torch.equal(Wm1, Wm2)
+
+
+def test_apply_flags_broken_promise_and_bad_index(ks, orc):
+    C, D = 100, 32
+    W = synth.unit_rows(3, synth.TID_W, C, D)
+    dW = synth.grad_rows(3, 4, D)
+    st = ks.apply_weight_grad(dev(W), None, dev(np.array([1, 5, 5, 9], dtype=np.int32)), None, dev(dW), 1.0, True)
+    torch.cuda.synchronize()
+    assert int(st.item()) & ks.KS_DEV_IDX_NOT_SORTED
+    st = ks.apply_weight_grad(dev(W), None, dev(np.array([1, 5, 100, 9], dtype=np.int32)), None, dev(dW), 1.0, False)
+    torch.cuda.synchronize()
+    assert int(st.item()) & ks.KS_DEV_BAD_INDEX
+
+
+# ------------------------------------------------------------------------------------------------
+# graph build
+# ------------------------------------------------------------------------------------------------
+def _check_graph(ks, orc, W, K, bf16, rows=None, tag=""):
+    print(f"[graph] {tag} C={W.shape[0]} D={W.shape[1]} K={K} bf16={bf16}", flush=True)
+    Wd = dev(W, torch.bfloat16) if bf16 else dev(W)
+    g, s = ks.knn_graph_build(Wd, K, want_sims=True)
+    torch.cuda.synchronize()
+    g, s = g.cpu().numpy(), s.cpu().numpy()
+    eg, es = orc.graph_bruteforce(W, K, rows)
+    if rows is not None:
+        g, s = g[rows], s[rows]
+    assert (g == eg).all(), f"{(g != eg).any(axis=1).sum()} rows differ"
+    assert (s == es.astype(np.float32)).all()
+    return g
+
+
+def test_graph_tiny_config_full_brute_force(ks, orc):
+    cfg = synth.CONFIGS["tiny"]                       # C=10,000, D=128 fp32 input, K=8
+    W = synth.unit_rows(0, synth.TID_W, cfg["C"], cfg["D"])
+    _check_graph(ks, orc, W, cfg["K"], bf16=False, tag="tiny fp32")
+    _check_graph(ks, orc, synth.bf16_round(W), cfg["K"], bf16=True, tag="tiny bf16")
+
+
+@pytest.mark.parametrize("C,D,K,bf16", [(64, 32, 10, True), (1000, 32, 31, False), (5, 32, 4, True), (2, 32, 1, False),
+                                        (300, 64, 100, True), (1500, 96, 64, True), (1500, 96, 128, False)])
+def test_graph_exact_ties_one_hot_rows(ks, orc, C, D, K, bf16):
+    W = np.zeros((C, D), dtype=np.float32)
+    W[np.arange(C), np.arange(C) % D] = 1.0
+    g = _check_graph(ks, orc, W, K, bf16, tag="one-hot")
+    for i in (0, C - 1):
+        same = [j for j in range(C) if j % D == i % D and j != i]
+        other = [j for j in range(C) if j % D != i % D]
+        assert g[i].tolist() == (same + other)[:K]
+
+
+def test_graph_integer_entries_many_ties_and_twins(ks, orc):
+    rng = np.random.default_rng(0)
+    C, D, K = 2500, 32, 33
+    W = rng.integers(-2, 3, (C, D)).astype(np.float32)
+    W[1200] = W[7]
+    W[1900] = W[7]
+    g = _check_graph(ks, orc, W, K, True, tag="integers")
+    assert g[7, 0] == 1200 and g[7, 1] == 1900 and g[1200, 0] == 7
+
+
+def test_graph_clustered_rows_ragged_size(ks, orc):
+    C, D, K = 20_011, 256, 32
+    W = synth.clustered_rows(5, C, D, n_centres=257, bf16=True)
+    rows = np.sort(synth.class_permutation(5, C)[:300]).astype(np.int32)
+    _check_graph(ks, orc, W, K, True, rows=rows, tag="clustered")
+
+
+def test_graph_is_deterministic(ks, orc):
+    W = synth.unit_rows(6, synth.TID_W, 6000, 128, bf16=True)
+    g1, s1 = ks.knn_graph_build(dev(W, torch.bfloat16), 16, want_sims=True)
+    g2, s2 = ks.knn_graph_build(dev(W, torch.bfloat16), 16, want_sims=True)
+    torch.cuda.synchronize()
+    assert torch.equal(g1, g2) and torch.equal(s1, s2)
+    assert (np.diff(s1.cpu().numpy(), axis=1) <= 0).all()
+
+
+def test_gather_rows(ks, orc):
+    C, D, M = 3000, 512, 700
+    W = synth.unit_rows(7, synth.TID_W, C, D, bf16=True)
+    idx = np.full(M, -1, dtype=np.int32)
+    idx[:600] = np.sort(synth.class_permutation(7, C)[:600])
+    out = ks.knn_gather_rows(dev(W, torch.bfloat16), dev(idx), dev(np.array([600], dtype=np.int32)))
+    torch.cuda.synchronize()
+    assert (out[:600].float().cpu().numpy() == W[idx[:600]]).all()
