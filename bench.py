@@ -1,0 +1,285 @@
+#!/usr/bin/env python3
+"""Benchmark of the KNN-softmax hot path on one MI355X.
+
+A "step" is one pass of the whole path over one synthetic batch: active-class selection, logits GEMM
+(with the row gather), softmax / cross-entropy / logit gradient, dX and dW GEMMs, and the weight update
+(knn_softmax_fwd_bwd + apply_weight_grad).  The KNN graph is rebuilt once before the loop
+(knn_graph_build, the once-per-epoch stage) and timed separately.
+
+Prints ONE JSON line on stdout: whole-job samples/s, the roofline figure of the dominant kernel (from
+HIP events recorded around every stage inside the timed region) and the CPU oracle timed on the host
+cores on the same inputs.  Everything else goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as ct
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+PHASES = ["select", "logits_gemm", "row_stats", "logit_grad", "dx_gemm", "dx_reduce", "dw_gemm", "apply"]
+
+# HBM bytes per launch from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), see profiles/; filled per workload
+MEASURED_TRAFFIC = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class HipEvents:
+    """hipEvent_t handles through the HIP runtime already loaded by torch."""
+
+    def __init__(self):
+        self.hip = ct.CDLL("libamdhip64.so")
+        self.hip.hipEventElapsedTime.argtypes = [ct.POINTER(ct.c_float), ct.c_void_p, ct.c_void_p]
+
+    def create(self, n):
+        evs = (ct.c_void_p * n)()
+        for k in range(n):
+            e = ct.c_void_p()
+            rc = self.hip.hipEventCreate(ct.byref(e))
+            assert rc == 0, f"hipEventCreate -> {rc}"
+            evs[k] = e
+        return evs
+
+    def record(self, ev, stream):
+        rc = self.hip.hipEventRecord(ct.c_void_p(ev), ct.c_void_p(stream))
+        assert rc == 0, f"hipEventRecord -> {rc}"
+
+    def elapsed_ms(self, a, b):
+        ms = ct.c_float()
+        rc = self.hip.hipEventElapsedTime(ct.byref(ms), ct.c_void_p(a), ct.c_void_p(b))
+        assert rc == 0, f"hipEventElapsedTime -> {rc}"
+        return float(ms.value)
+
+    def destroy(self, evs):
+        for e in evs:
+            self.hip.hipEventDestroy(ct.c_void_p(e))
+
+
+def make_inputs(cfg, log_fn=log):
+    import synth
+    t = time.time()
+    W, X = synth.make_WX(cfg)
+    y = synth.make_labels(cfg)
+    log_fn(f"[bench] inputs: C={cfg['C']} D={cfg['D']} B={cfg['B']} K={cfg['K']} M={cfg['M']} labels={cfg['labels']} "
+           f"({time.time() - t:.1f}s host generation)")
+    return W, X, y
+
+
+def oracle_graph_for_labels(orc, W, y, cfg):
+    """Neighbour lists for the oracle: exact brute force for the rows the selection reads (the labels), a
+    synthetic filler elsewhere (never read).  Returns (G, distinct rows, their lists, seconds)."""
+    import synth
+    rows = np.unique(y).astype(np.int32)
+    t = time.time()
+    lists, _ = orc.graph_bruteforce(W, cfg["K"], rows)
+    dt = time.time() - t
+    G = np.empty((cfg["C"], cfg["K"]), dtype=np.int32)
+    G[:] = (np.arange(cfg["C"], dtype=np.int64)[:, None] + 1 + np.arange(cfg["K"])[None, :]) % cfg["C"]
+    G[rows] = lists
+    return G, rows, lists, dt
+
+
+def phase_model(cfg, A):
+    """Algorithmic flops / bytes per launch of each stage at A active classes."""
+    B, D, K, C = cfg["B"], cfg["D"], cfg["K"], cfg["C"]
+    gemm = 2.0 * B * A * D
+    return {
+        "select": dict(bound="latency"),
+        "logits_gemm": dict(bound="mfma", flops=gemm),
+        "row_stats": dict(bound="hbm", bytes=4.0 * B * A),
+        "logit_grad": dict(bound="hbm", bytes=(4.0 + 2.0) * B * A),
+        "dx_gemm": dict(bound="mfma", flops=gemm),
+        "dx_reduce": dict(bound="latency"),
+        "dw_gemm": dict(bound="mfma", flops=gemm),
+        "apply": dict(bound="hbm", bytes=A * D * (4.0 + 4.0 + 4.0 + 2.0)),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="shard390k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-parity", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1")
+        sys.exit(2)
+
+    import torch
+    import synth
+    import paper_2102_06025_amd as ks
+
+    ks.lib()  # fails loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    cfg = dict(synth.CONFIGS[args.workload])
+    C, D, B, K, M, scale = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"], cfg["scale"]
+    grad_scale, lr = 128.0, 0.05
+    alpha = -lr / grad_scale
+
+    W, X, y = make_inputs(cfg)
+    W_bf = torch.from_numpy(W).cuda().to(torch.bfloat16)
+    W_master = torch.from_numpy(W).cuda()
+    X_bf = torch.from_numpy(X).cuda().to(torch.bfloat16)
+    labels = torch.from_numpy(y).cuda()
+    stream = torch.cuda.current_stream().cuda_stream
+    hev = HipEvents()
+
+    # ---- graph rebuild (once per epoch in the paper; timed on its own) -------------------------------
+    g_ws = torch.empty(ks.knn_graph_build_workspace(C, D, K, 0), dtype=torch.uint8, device="cuda")
+    graph = torch.empty((C, K), dtype=torch.int32, device="cuda")
+    gev = hev.create(2)
+    graph_ms = []
+    for _ in range(2):
+        hev.record(gev[0], stream)
+        ks.knn_graph_build(W_bf, K, graph=graph, ws=g_ws)
+        hev.record(gev[1], stream)
+        torch.cuda.synchronize()
+        graph_ms.append(hev.elapsed_ms(gev[0], gev[1]))
+    del g_ws
+    graph_best = min(graph_ms)
+    graph_tflops = 2.0 * C * C * D / (graph_best * 1e-3) / 1e12
+    log(f"[bench] knn_graph_build: {graph_best:.1f} ms  ({graph_tflops:.0f} TFLOP/s algorithmic, "
+        f"{graph_tflops / PEAK_BF16_TFLOPS:.1%} of bf16 peak)")
+
+    # ---- step buffers -----------------------------------------------------------------------------------
+    ws = torch.empty(ks.knn_softmax_workspace(C, D, B, K, M), dtype=torch.uint8, device="cuda")
+    out = ks.knn_softmax_fwd_bwd(W_bf, X_bf, labels, graph, M, scale, grad_scale, ws=ws)
+    torch.cuda.synchronize()
+    A = int(out["n_active"].item())
+    assert int(out["dev_status"].item()) == 0
+    log(f"[bench] active classes A={A} of M={M}")
+    first = {k: out[k].clone() for k in ("active_idx", "target_pos", "loss_per_sample", "loss_mean", "dX")}
+    first["dW_active"] = out["dW_active"][:A].clone()
+
+    L = ks.lib()
+    n_ev = 9
+    evs = [hev.create(n_ev) for _ in range(args.steps)]
+
+    def step(ev=None):
+        if ev is None:
+            ks.knn_softmax_fwd_bwd(W_bf, X_bf, labels, graph, M, scale, grad_scale, out=out, ws=ws)
+        else:
+            rc = L.knn_softmax_fwd_bwd_profiled(
+                ct.c_void_p(W_bf.data_ptr()), ct.c_void_p(X_bf.data_ptr()), ct.c_void_p(labels.data_ptr()),
+                ct.c_void_p(graph.data_ptr()), ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(K), ct.c_int(M),
+                ct.c_float(scale), ct.c_float(grad_scale), ct.c_void_p(out["active_idx"].data_ptr()),
+                ct.c_void_p(out["n_active"].data_ptr()), ct.c_void_p(out["target_pos"].data_ptr()),
+                ct.c_void_p(out["loss_per_sample"].data_ptr()), ct.c_void_p(out["loss_mean"].data_ptr()),
+                ct.c_void_p(out["dX"].data_ptr()), ct.c_void_p(out["dW_active"].data_ptr()),
+                ct.c_void_p(ws.data_ptr()), ct.c_size_t(ws.numel()), ct.c_void_p(out["dev_status"].data_ptr()),
+                ct.c_void_p(stream), ev, ct.c_int(8))
+            assert rc == 0, rc
+        ks.apply_weight_grad(W_master, W_bf, out["active_idx"], out["n_active"], out["dW_active"], alpha,
+                             idx_sorted_unique=True, ws=ws, dev_status=out["dev_status"])
+        if ev is not None:
+            hev.record(ev[8], stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = B / (ms_per_step * 1e-3)
+    assert int(out["dev_status"].item()) == 0
+
+    # per-stage durations from the events of the timed region
+    dur = {p: 0.0 for p in PHASES}
+    for ev in evs:
+        for k, p in enumerate(PHASES):
+            dur[p] += hev.elapsed_ms(ev[k], ev[k + 1])
+    for p in PHASES:
+        dur[p] = dur[p] / args.steps * 1e3  # microseconds
+    model = phase_model(cfg, A)
+    phases = {}
+    for p in PHASES:
+        m = model[p]
+        e = dict(us=round(dur[p], 2), bound=m["bound"])
+        if "flops" in m:
+            e["tflops"] = round(m["flops"] / (dur[p] * 1e-6) / 1e12, 1)
+            e["frac"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+        elif "bytes" in m:
+            e["gbs"] = round(m["bytes"] / (dur[p] * 1e-6) / 1e9, 1)
+            e["frac"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
+        phases[p] = e
+    log("[bench] stage times (us): " + ", ".join(f"{p}={phases[p]['us']}" for p in PHASES))
+    dom = max((p for p in PHASES if model[p]["bound"] in ("mfma", "hbm")), key=lambda p: dur[p])
+    if model[dom]["bound"] == "mfma":
+        roofline = dict(bound="mfma", achieved=phases[dom]["tflops"], peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                        frac=phases[dom]["frac"], traffic=MEASURED_TRAFFIC.get((args.workload, dom)), kernel=dom)
+    else:
+        roofline = dict(bound="hbm", achieved=phases[dom]["gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
+                        frac=phases[dom]["frac"], traffic=MEASURED_TRAFFIC.get((args.workload, dom)), kernel=dom)
+
+    # ---- CPU oracle on the same inputs: baseline + full-size parity of the first step -----------------------
+    cpu_baseline, parity = None, None
+    if not args.no_cpu_baseline:
+        import oracle as orc
+        threads = orc.num_threads()
+        G_orc, rows, lists, t_graph = oracle_graph_for_labels(orc, W, y, cfg)
+        t = time.perf_counter()
+        active, A_orc, tpos = orc.select_active(y, G_orc, C, M)
+        ref = orc.knn_softmax_fwd_bwd(W, X, active[:A_orc], tpos, scale, grad_scale)
+        ref_dW32 = ref["dWA"].astype(np.float32)
+        orc.apply_weight_grad(W, active[:A_orc], ref_dW32, alpha, want_bf16=False)
+        t_step = time.perf_counter() - t
+        cpu_baseline = dict(value=round(B / t_step, 2), unit="samples/s", cores=threads, kind="oracle",
+                            sample=f"one whole step (select + fwd/bwd + weight update) on the same batch, A={A_orc}; "
+                                   f"its graph rows by brute force on the {len(rows)} distinct labels",
+                            graph_rows_per_s=round(len(rows) / t_graph, 2),
+                            graph_build_s_scaled_to_C=round(t_graph / len(rows) * C, 1))
+        log(f"[bench] oracle: step {t_step:.2f}s on {threads} threads; graph rows {len(rows)} in {t_graph:.2f}s")
+        if not args.no_parity:
+            g_rows = graph[torch.from_numpy(rows.astype(np.int64)).cuda()].cpu().numpy()
+
+            def relf(a, b):
+                return float(np.linalg.norm(a.astype(np.float64) - b) / np.linalg.norm(b))
+
+            parity = dict(
+                graph_rows_checked=int(len(rows)), graph_rows_exact=bool((g_rows == lists).all()),
+                active_exact=bool(A == A_orc and (first["active_idx"].cpu().numpy() == active).all()
+                                  and (first["target_pos"].cpu().numpy() == tpos).all()),
+                loss_rel_err=abs(float(first["loss_mean"].item()) - ref["loss"]) / abs(ref["loss"]),
+                dX_rel_fro=relf(first["dX"].cpu().numpy(), ref["dX"]),
+                dW_rel_fro=relf(first["dW_active"].cpu().numpy(), ref["dWA"]))
+            log(f"[bench] parity of the first step vs the oracle: {parity}")
+
+    res = {
+        "metric": "KNN-softmax fwd+bwd samples/sec per GPU", "value": round(value, 1), "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: C={C} D={D} B={B} K={K} M={M} labels={cfg['labels']} s={scale}",
+                   "active_classes": A, "step": "select + knn_softmax_fwd_bwd + apply_weight_grad"},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "phases": phases,
+        "graph_build": {"ms": round(graph_best, 2), "tflops": round(graph_tflops, 1),
+                        "frac": round(graph_tflops / PEAK_BF16_TFLOPS, 4), "bound": "mfma"},
+        "parity": parity,
+    }
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

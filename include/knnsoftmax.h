@@ -127,6 +127,19 @@ int knn_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const in
                         float *loss_per_sample, float *loss_mean, float *dX, float *dW_active,
                         void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
+/* Measurement aid: knn_softmax_fwd_bwd with one hipEvent_t recorded on `stream` at each stage boundary, so that
+ * a caller can time the stages of a step without a profiler.  events[0..KS_N_PHASE_EVENTS) are created by the
+ * caller (hipEventCreate); event k is recorded: 0 at entry, 1 after the selection, 2 after the logits GEMM,
+ * 3 after the row statistics and the loss mean, 4 after the logit gradient, 5 after the dX partial GEMM,
+ * 6 after the dX reduction, 7 after the dW GEMM.  Same results as knn_softmax_fwd_bwd. */
+#define KS_N_PHASE_EVENTS 8
+int knn_softmax_fwd_bwd_profiled(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
+                                 const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
+                                 float grad_scale, int32_t *active_idx, int32_t *n_active, int32_t *target_pos,
+                                 float *loss_per_sample, float *loss_mean, float *dX, float *dW_active,
+                                 void *ws, size_t ws_bytes, int32_t *dev_status, void *stream,
+                                 void **events, int n_events);
+
 /* ------------------------------------------------------------------------------------------------------
  * full_softmax_fwd_bwd -- the full-softmax layer the paper compares against (Section 3.2, Table 3): the
  * same computation with every class active (active_idx = 0..C-1, no graph).  dW is dense [C, D].

@@ -283,8 +283,9 @@ static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool w
 static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M, float scale, float grad_scale,
                   const int32_t *active_idx, const int32_t *n_active, const int32_t *target_pos,
                   float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, const SmWs &w,
-                  hipStream_t st) {
+                  hipStream_t st, hipEvent_t *ev = nullptr) {
     typedef TileG T;
+    auto mark = [&](int k) { if (ev) (void)hipEventRecord(ev[k], st); };
     const int Mi = (int)M;
     const int tiles_b = (int)ks_ceil_div(B, T::BM);
     const int tiles_a_n = (int)ks_ceil_div(M, T::BN), tiles_a_m = (int)ks_ceil_div(M, T::BM);
@@ -292,17 +293,23 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
 
     hipLaunchKernelGGL(logits_kernel<T>, dim3(tiles_b * tiles_a_n), dim3(T::NT), 0, st, X, W, active_idx, n_active, B, D,
                        Mi, scale, w.Z, w.Mp);
+    mark(2);
     hipLaunchKernelGGL(row_stats_kernel, dim3(B), dim3(SM_NT), 0, st, w.Z, w.Mp, n_active, Mi, target_pos, w.lse,
                        loss_per_sample);
     hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(SM_NT), 0, st, loss_per_sample, B, loss_mean);
+    mark(3);
     hipLaunchKernelGGL(dz_kernel, dim3((unsigned)ks_ceil_div(w.Mp, SM_NT * 8), B), dim3(SM_NT), 0, st, w.Z, w.Mp, n_active,
                        Mi, target_pos, w.lse, grad_scale / (float)B, w.dZ);
+    mark(4);
     hipLaunchKernelGGL(dx_partial_kernel<T>, dim3(tiles_b * tiles_d, w.S), dim3(T::NT), 0, st, w.dZ, w.Mp, W, active_idx,
                        n_active, B, D, Mi, w.part);
+    mark(5);
     hipLaunchKernelGGL(dx_reduce_kernel, dim3((unsigned)ks_ceil_div((int64_t)B * D / 4, SM_NT)), dim3(SM_NT), 0, st, w.part,
                        w.S, (int64_t)B * D, scale, dX);
+    mark(6);
     hipLaunchKernelGGL(dw_kernel<T>, dim3(tiles_a_m * tiles_d), dim3(T::NT), 0, st, w.dZ, w.Mp, X, n_active, B, D, Mi,
                        scale, dW_active);
+    mark(7);
     KS_LAUNCH_CHECK();
     return KS_OK;
 }
@@ -319,11 +326,10 @@ extern "C" size_t knn_softmax_workspace(int64_t C, int D, int B, int K, int M) {
     return total;
 }
 
-extern "C" int knn_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
-                                   const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
-                                   float grad_scale, int32_t *active_idx, int32_t *n_active, int32_t *target_pos,
-                                   float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, void *ws,
-                                   size_t ws_bytes, int32_t *dev_status, void *stream) {
+static int sm_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels, const int32_t *graph,
+                      int64_t C, int D, int B, int K, int M, float scale, float grad_scale, int32_t *active_idx,
+                      int32_t *n_active, int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
+                      float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream, hipEvent_t *ev) {
     if (!W_bf16 || !X_bf16 || !labels || !active_idx || !n_active || !target_pos || !loss_per_sample || !loss_mean ||
         !dX || !dW_active || !ws)
         return KS_INVALID_ARG;
@@ -334,10 +340,34 @@ extern "C" int knn_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf1
     SmWs w = sm_carve(ws, C, D, B, K, M, true, &need);
     if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
+    if (ev) (void)hipEventRecord(ev[0], st);
     int rc = ks_select_launch(labels, graph, C, B, K, M, active_idx, n_active, target_pos, w.select, dev_status, st);
     if (rc != KS_OK) return rc;
+    if (ev) (void)hipEventRecord(ev[1], st);
     return sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, active_idx, n_active, target_pos, loss_per_sample,
-                  loss_mean, dX, dW_active, w, st);
+                  loss_mean, dX, dW_active, w, st, ev);
+}
+
+extern "C" int knn_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
+                                   const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
+                                   float grad_scale, int32_t *active_idx, int32_t *n_active, int32_t *target_pos,
+                                   float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, void *ws,
+                                   size_t ws_bytes, int32_t *dev_status, void *stream) {
+    return sm_fwd_bwd(W_bf16, X_bf16, labels, graph, C, D, B, K, M, scale, grad_scale, active_idx, n_active, target_pos,
+                      loss_per_sample, loss_mean, dX, dW_active, ws, ws_bytes, dev_status, stream, nullptr);
+}
+
+extern "C" int knn_softmax_fwd_bwd_profiled(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
+                                            const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
+                                            float grad_scale, int32_t *active_idx, int32_t *n_active,
+                                            int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
+                                            float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status,
+                                            void *stream, void **events, int n_events) {
+    if (!events || n_events < KS_N_PHASE_EVENTS) return KS_INVALID_ARG;
+    for (int k = 0; k < KS_N_PHASE_EVENTS; ++k)
+        if (!events[k]) return KS_INVALID_ARG;
+    return sm_fwd_bwd(W_bf16, X_bf16, labels, graph, C, D, B, K, M, scale, grad_scale, active_idx, n_active, target_pos,
+                      loss_per_sample, loss_mean, dX, dW_active, ws, ws_bytes, dev_status, stream, (hipEvent_t *)events);
 }
 
 extern "C" size_t full_softmax_workspace(int64_t C, int D, int B) {
