@@ -1,0 +1,182 @@
+// bf16 MFMA tile engine for gfx950, asynchronous version: operand tiles go from global memory straight
+// into LDS (global_load_lds_dwordx4, no staging registers), several k-tiles in flight.
+//
+// Both operands must be stored with k contiguous ("row = m or n, k fast"), 16-byte aligned rows, and the
+// k range handed to the main loop must be readable and finite for every row that is loaded (callers pad
+// k with zeros in memory); rows beyond the operand's row limit are redirected to the last valid row, so
+// the corresponding accumulator rows/columns hold finite garbage that the epilogue must not store.
+//
+// LDS layout of one operand tile: [ROWS][64] bf16, unpadded; the 16-byte chunk c of row r sits in slot
+// c ^ ((r >> 1) & 7) of that row.  One wave-wide load instruction fills 8 consecutive rows (lane l: row
+// l/8, slot l%8), so each lane fetches global chunk  slot ^ ((row >> 1) & 7)  of its row; the 16-byte
+// fragment reads of 16 consecutive rows at one k offset then hit 16 distinct bank groups.
+//
+// Pipeline: STAGES LDS buffers.  Iteration t: wait until this wave's loads of tile t have landed
+// (s_waitcnt vmcnt(N) with the number of younger loads), workgroup barrier (everyone's part of tile t
+// is in LDS and everyone is done reading tile t-1), issue the loads of tile t+STAGES-1 into the buffer
+// tile t-1 used, MFMAs of tile t with register double-buffered fragments.
+#pragma once
+#include "ks_common.h"
+
+#define KS_GPTR(p) ((const void __attribute__((address_space(1))) *)(p))
+#define KS_LPTR(p) ((void __attribute__((address_space(3))) *)(p))
+
+template <int BM_, int BN_, int WAVES_M_, int WAVES_N_, int STAGES_> struct KsATile {
+    static constexpr int BM = BM_, BN = BN_, BK = 64, WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, STAGES = STAGES_;
+    static constexpr int NW = WAVES_M * WAVES_N, NT = NW * 64;
+    static constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    static constexpr int FM = WM / 32, FN = WN / 32;
+    static constexpr int NI_A = BM / (8 * NW), NI_B = BN / (8 * NW); // load instructions per wave per tile
+    static constexpr int STAGE_ELEMS = (BM + BN) * 64;
+    static constexpr int LDS_ELEMS = STAGES * STAGE_ELEMS;
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0 && WM % 32 == 0 && WN % 32 == 0, "tile shape");
+    static_assert((STAGES - 2) * (NI_A + NI_B) <= 63, "vmcnt range");
+};
+
+// s_waitcnt vmcnt(n) only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14])
+template <int N> __device__ __forceinline__ void ks_wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0F70);
+}
+// workgroup barrier without the memory fence of __syncthreads() (which would drain the loads in flight);
+// the empty asm statements keep the compiler from moving LDS accesses across it
+__device__ __forceinline__ void ks_barrier_nofence() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// per-lane global pointers (k = 0) of the rows this lane loads, one per load instruction
+template <int ROWS, int NW> struct KsARows {
+    static constexpr int NI = ROWS / (8 * NW);
+    const uint16_t *ptr[NI];
+    __device__ __forceinline__ void init(const uint16_t *base, int64_t ld, const int32_t *gidx, int row0, int row_limit) {
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int row = (j * NW + wave) * 8 + (lane >> 3);
+            int gr = row0 + row;
+            if (gr >= row_limit) gr = row_limit - 1; // row_limit >= 1
+            const int64_t src = gidx ? (int64_t)gidx[gr] : (int64_t)gr;
+            const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+            ptr[j] = base + src * ld + chunk * 8;
+        }
+    }
+    // enqueue this wave's loads of the k-tile starting at element k0 into the tile at `lds`
+    __device__ __forceinline__ void issue(int k0, uint16_t *lds) const {
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+            __builtin_amdgcn_global_load_lds(KS_GPTR(ptr[j] + k0), KS_LPTR(lds + (j * NW + wave) * 8 * 64), 16, 0, 0);
+    }
+};
+
+template <class T> struct KsAFrags {
+    bf16x8_t a[T::FM], b[T::FN];
+};
+
+template <class T>
+__device__ __forceinline__ void ks_a_load_frags(KsAFrags<T> &f, const uint16_t *stA, const uint16_t *stB, int kk, int offA,
+                                                int offB, int swz, int khalf) {
+    const int co = ((kk * 2 + khalf) ^ swz) * 8;
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm) f.a[fm] = *(const bf16x8_t *)(stA + offA + fm * 32 * 64 + co);
+#pragma unroll
+    for (int fn = 0; fn < T::FN; ++fn) f.b[fn] = *(const bf16x8_t *)(stB + offB + fn * 32 * 64 + co);
+}
+
+template <class T>
+__device__ __forceinline__ void ks_a_mma(const KsAFrags<T> &f, f32x16_t (&acc)[T::FM][T::FN]) {
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+        for (int fn = 0; fn < T::FN; ++fn)
+            acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[fm], f.b[fn], acc[fm][fn], 0, 0, 0);
+}
+
+// MFMAs of one k-tile held in the stage at `st` (A tile first, then B tile)
+template <class T>
+__device__ __forceinline__ void ks_a_tile_mma(const uint16_t *st, f32x16_t (&acc)[T::FM][T::FN]) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 31, khalf = lane >> 5, swz = (lane >> 1) & 7;
+    const int offA = ((wave / T::WAVES_N) * T::WM + r) * 64;
+    const int offB = ((wave % T::WAVES_N) * T::WN + r) * 64;
+    const uint16_t *stA = st, *stB = st + T::BM * 64;
+    // register double buffering of the fragments; the scheduling barriers keep the compiler from
+    // collapsing it (reads of step kk+1 are in flight while the MFMAs of step kk issue)
+    KsAFrags<T> f0, f1;
+    ks_a_load_frags<T>(f0, stA, stB, 0, offA, offB, swz, khalf);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_load_frags<T>(f1, stA, stB, 1, offA, offB, swz, khalf);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_mma<T>(f0, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_load_frags<T>(f0, stA, stB, 2, offA, offB, swz, khalf);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_mma<T>(f1, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_load_frags<T>(f1, stA, stB, 3, offA, offB, swz, khalf);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_mma<T>(f0, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_mma<T>(f1, acc);
+}
+
+// Main loop over k-tiles [kt0, kt1) (k0 = kt * 64).  All threads of the workgroup must call it with the
+// same range.  On return every wave has passed a barrier after its last LDS read only if `final_barrier`.
+template <class T, class AR, class BR>
+__device__ __forceinline__ void ks_a_mainloop(const AR &ar, const BR &br, int kt0, int kt1, uint16_t *lds,
+                                              f32x16_t (&acc)[T::FM][T::FN]) {
+    constexpr int S = T::STAGES;
+    constexpr int PER_TILE = T::NI_A + T::NI_B;
+#pragma unroll
+    for (int s = 0; s < S - 1; ++s) {
+        if (kt0 + s < kt1) {
+            uint16_t *st = lds + s * T::STAGE_ELEMS;
+            ar.issue((kt0 + s) * 64, st);
+            br.issue((kt0 + s) * 64, st + T::BM * 64);
+        }
+    }
+    int stage = 0;
+    for (int kt = kt0; kt < kt1; ++kt) {
+        // loads younger than tile kt: tiles kt+1 .. kt+S-2 when they all exist
+        if (kt + S - 2 < kt1) ks_wait_vmcnt<(S - 2) * PER_TILE>();
+        else ks_wait_vmcnt<0>();
+        ks_barrier_nofence();
+        if (kt + S - 1 < kt1) {
+            int ns = stage + S - 1;
+            if (ns >= S) ns -= S;
+            uint16_t *st = lds + ns * T::STAGE_ELEMS;
+            ar.issue((kt + S - 1) * 64, st);
+            br.issue((kt + S - 1) * 64, st + T::BM * 64);
+        }
+        ks_a_tile_mma<T>(lds + stage * T::STAGE_ELEMS, acc);
+        if (++stage == S) stage = 0;
+    }
+    // make the LDS reusable by the caller (next tile or epilogue staging)
+    ks_barrier_nofence();
+}
+
+template <class T, class F>
+__device__ __forceinline__ void ks_a_foreach(const f32x16_t (&acc)[T::FM][T::FN], F f) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wm0 = (wave / T::WAVES_N) * T::WM, wn0 = (wave % T::WAVES_N) * T::WN;
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+        for (int fn = 0; fn < T::FN; ++fn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int m = wm0 + fm * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r & 3);
+                int n = wn0 + fn * 32 + (lane & 31);
+                f(m, n, acc[fm][fn][r]);
+            }
+}
+
+template <class T> __device__ __forceinline__ void ks_a_clear(f32x16_t (&acc)[T::FM][T::FN]) {
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+        for (int fn = 0; fn < T::FN; ++fn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[fm][fn][r] = 0.f;
+}

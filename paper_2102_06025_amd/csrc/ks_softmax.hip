@@ -10,9 +10,14 @@
 //   dW GEMM           dW_active[A, D] = scale * dZ^T . X
 // Launch sizes are taken from the cap M; workgroups beyond the active count exit at once.
 #include "ks_gemm.h"
+#include "ks_gemm_async.h"
 #include "ks_select.h"
 
-typedef KsTile<128, 128, 64, 2, 2> TileG;
+typedef KsTile<128, 128, 64, 2, 2> TileG;      // generic path (any D % 32 == 0)
+typedef KsATile<256, 256, 2, 4, 2> TileLogits; // fast path (D % 64 == 0): asynchronous engine
+typedef KsATile<128, 128, 2, 2, 2> TileDx;
+typedef KsATile<256, 256, 2, 4, 2> TileDw;
+#define KS_BP_ALIGN 128
 
 #define SM_NT 256
 #define KS_MP_ALIGN 256
@@ -210,6 +215,199 @@ dw_kernel(const uint16_t *__restrict__ dZ, int64_t ldz, const uint16_t *__restri
     });
 }
 
+// ================================================================================================
+// Fast path (D % 64 == 0).  All three contractions run on the asynchronous engine, which wants both
+// operands with k contiguous; the operands that are not (W_active for dX, dZ and X for dW) get
+// transposed copies from two bandwidth-bound kernels: the gather writes W_active^T, the logit-gradient
+// kernel writes dZ and dZ^T in one pass over Z.
+// ================================================================================================
+
+// 8x8 transpose of 16-bit elements held as 8 rows of uint4 (row k, elements n=0..7) -> out[n] = 8 k's
+__device__ __forceinline__ void sm_transpose8x8(const uint4 (&in)[8], uint4 (&out)[8]) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+        uint32_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint4 &ra = in[2 * j], &rb = in[2 * j + 1];
+            uint32_t a = (n >> 1) == 0 ? ra.x : ((n >> 1) == 1 ? ra.y : ((n >> 1) == 2 ? ra.z : ra.w));
+            uint32_t b = (n >> 1) == 0 ? rb.x : ((n >> 1) == 1 ? rb.y : ((n >> 1) == 2 ? rb.z : rb.w));
+            o[j] = (n & 1) ? ((a >> 16) | (b & 0xFFFF0000u)) : ((a & 0xFFFFu) | (b << 16));
+        }
+        out[n] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+#define TR_TILE 128
+#define TR_LD (TR_TILE + 8)
+// out[c][r] = in[src(r)][c] for r < n_rows (src through the optional index list), zero for
+// n_rows <= r < round_up(n_rows, 256); c < n_cols (n_cols % 8 == 0).  One 128 x 128 tile per workgroup.
+__global__ void __launch_bounds__(SM_NT)
+transpose_rows_kernel(const uint16_t *__restrict__ in, int64_t ld_in, const int32_t *__restrict__ gidx,
+                      const int32_t *__restrict__ n_rows_p, int rows_cap, int n_cols, uint16_t *__restrict__ out,
+                      int64_t ld_out) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[TR_TILE * TR_LD]; // [c][r]
+    int n_rows = n_rows_p ? *n_rows_p : rows_cap;
+    n_rows = n_rows < 0 ? 0 : (n_rows > rows_cap ? rows_cap : n_rows);
+    const int n_pad = (n_rows + KS_MP_ALIGN - 1) / KS_MP_ALIGN * KS_MP_ALIGN;
+    const int r0 = blockIdx.x * TR_TILE, c0 = blockIdx.y * TR_TILE;
+    if (r0 >= n_pad) return;
+    const int cb = threadIdx.x & 15, rb = threadIdx.x >> 4; // 16 column blocks x 16 row blocks of 8x8
+    uint4 v[8], t[8];
+    const int c = c0 + cb * 8;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int r = r0 + rb * 8 + k;
+        if (r < n_rows && c < n_cols) {
+            const int64_t src = gidx ? (int64_t)gidx[r] : (int64_t)r;
+            v[k] = *(const uint4 *)(in + src * ld_in + c);
+        } else {
+            v[k] = make_uint4(0, 0, 0, 0);
+        }
+    }
+    sm_transpose8x8(v, t);
+#pragma unroll
+    for (int n = 0; n < 8; ++n) *(uint4 *)(tile + (cb * 8 + n) * TR_LD + rb * 8) = t[n];
+    __syncthreads();
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+        const int cc = pass * 16 + (threadIdx.x >> 4), chunk = threadIdx.x & 15;
+        if (c0 + cc < n_cols && r0 + chunk * 8 < n_pad)
+            *(uint4 *)(out + (int64_t)(c0 + cc) * ld_out + r0 + chunk * 8) = *(const uint4 *)(tile + cc * TR_LD + chunk * 8);
+    }
+}
+
+// Z = scale * X . W[active]^T on the asynchronous engine
+template <class T>
+__global__ void __launch_bounds__(T::NT)
+logits_async_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W,
+                    const int32_t *__restrict__ active_idx, const int32_t *__restrict__ n_active_p, int B, int D, int M,
+                    float scale, float *__restrict__ Z, int64_t ldz) {
+    __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
+    const int n_active = sm_clamp_n(n_active_p, M);
+    const int tiles_m = (B + T::BM - 1) / T::BM;
+    const int n_tiles = tiles_m * ((n_active + T::BN - 1) / T::BN);
+    if ((int)blockIdx.x >= n_tiles) return;
+    const int t = ks_xcd_remap(blockIdx.x, n_tiles);
+    const int tm = t % tiles_m, tn = t / tiles_m;
+    KsARows<T::BM, T::NW> ar;
+    KsARows<T::BN, T::NW> br;
+    ar.init(X, D, nullptr, tm * T::BM, B);
+    br.init(W, D, active_idx, tn * T::BN, n_active);
+    f32x16_t acc[T::FM][T::FN];
+    ks_a_clear<T>(acc);
+    ks_a_mainloop<T>(ar, br, 0, D / 64, lds, acc);
+    ks_a_foreach<T>(acc, [&](int m, int n, float v) {
+        int i = tm * T::BM + m, a = tn * T::BN + n;
+        if (i < B && a < n_active) Z[(int64_t)i * ldz + a] = scale * v;
+    });
+}
+
+// dZ[i][a] and dZT[a][i] (bf16) from Z and the row log-sum-exps; 128 x 128 tile per workgroup, each
+// thread an 8 x 8 block.  Zero for a in [n_active, round_up(n_active, 256)) and for i in [B, Bp).
+__global__ void __launch_bounds__(SM_NT)
+dz_dual_kernel(const float *__restrict__ Z, int64_t ldz, const int32_t *__restrict__ n_active_p, int M, int B, int Bp,
+               const int32_t *__restrict__ target_pos, const float *__restrict__ lse, float g,
+               uint16_t *__restrict__ dZ, uint16_t *__restrict__ dZT) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[TR_TILE * TR_LD]; // [a][i]
+    const int n = sm_clamp_n(n_active_p, M);
+    const int n_pad = (n + KS_MP_ALIGN - 1) / KS_MP_ALIGN * KS_MP_ALIGN;
+    const int a0 = blockIdx.x * TR_TILE, i0 = blockIdx.y * TR_TILE;
+    if (a0 >= n_pad) return;
+    const int ab = threadIdx.x & 15, ib = threadIdx.x >> 4;
+    const int a = a0 + ab * 8;
+    uint4 v[8], t[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int i = i0 + ib * 8 + k;
+        float d[8];
+        if (i < B && a < n) {
+            const float *z = Z + (int64_t)i * ldz + a;
+            const float ls = lse[i];
+            const int tp = target_pos[i];
+            float zz[8];
+            if (a + 8 <= n) {
+                float4 p = *(const float4 *)z, q = *(const float4 *)(z + 4);
+                zz[0] = p.x; zz[1] = p.y; zz[2] = p.z; zz[3] = p.w; zz[4] = q.x; zz[5] = q.y; zz[6] = q.z; zz[7] = q.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) zz[e] = (a + e < n) ? z[e] : 0.f;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d[e] = (a + e < n) ? g * (__expf(zz[e] - ls) - (a + e == tp ? 1.f : 0.f)) : 0.f;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d[e] = 0.f;
+        }
+        v[k] = make_uint4(ks_pack_bf2(d[0], d[1]), ks_pack_bf2(d[2], d[3]), ks_pack_bf2(d[4], d[5]), ks_pack_bf2(d[6], d[7]));
+        if (i < B) *(uint4 *)(dZ + (int64_t)i * ldz + a) = v[k];
+    }
+    sm_transpose8x8(v, t);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) *(uint4 *)(tile + (ab * 8 + e) * TR_LD + ib * 8) = t[e];
+    __syncthreads();
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+        const int aa = pass * 16 + (threadIdx.x >> 4), chunk = threadIdx.x & 15;
+        if (i0 + chunk * 8 < Bp)
+            *(uint4 *)(dZT + (int64_t)(a0 + aa) * Bp + i0 + chunk * 8) = *(const uint4 *)(tile + aa * TR_LD + chunk * 8);
+    }
+}
+
+// dX partials on the asynchronous engine: P[s][i][d] = sum_{a in share s} dZ[i][a] * WAT[d][a]
+template <class T>
+__global__ void __launch_bounds__(T::NT)
+dx_partial_async_kernel(const uint16_t *__restrict__ dZ, int64_t ldz, const uint16_t *__restrict__ WAT,
+                        const int32_t *__restrict__ n_active_p, int B, int D, int M, int S, float *__restrict__ part) {
+    __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
+    const int n_active = sm_clamp_n(n_active_p, M);
+    const int tiles_m = (B + T::BM - 1) / T::BM, tiles_n = (D + T::BN - 1) / T::BN;
+    const int n_tiles = tiles_m * tiles_n;
+    const int L = ks_xcd_remap(blockIdx.x, n_tiles * S);
+    const int s = L / n_tiles, t = L % n_tiles;
+    const int tm = t % tiles_m, tn = t / tiles_m;
+    const int nk = (n_active + 63) / 64;
+    const int per = (nk + S - 1) / S;
+    const int kt0 = s * per, kt1 = (kt0 + per < nk) ? kt0 + per : nk;
+    KsARows<T::BM, T::NW> ar;
+    KsARows<T::BN, T::NW> br;
+    ar.init(dZ, ldz, nullptr, tm * T::BM, B);
+    br.init(WAT, ldz, nullptr, tn * T::BN, D);
+    f32x16_t acc[T::FM][T::FN];
+    ks_a_clear<T>(acc);
+    if (kt0 < kt1) ks_a_mainloop<T>(ar, br, kt0, kt1, lds, acc);
+    float *out = part + (int64_t)s * B * D;
+    ks_a_foreach<T>(acc, [&](int m, int n, float v) {
+        int i = tm * T::BM + m, d = tn * T::BN + n;
+        if (i < B && d < D) out[(int64_t)i * D + d] = v;
+    });
+}
+
+// dW_active[a][d] = scale * sum_i dZT[a][i] * XT[d][i] on the asynchronous engine
+template <class T>
+__global__ void __launch_bounds__(T::NT)
+dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ XT, int Bp,
+                const int32_t *__restrict__ n_active_p, int D, int M, int64_t Mp, float scale, float *__restrict__ dW) {
+    __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
+    const int n_active = sm_clamp_n(n_active_p, M);
+    const int tiles_n = (D + T::BN - 1) / T::BN;
+    const int n_tiles = tiles_n * ((n_active + T::BM - 1) / T::BM);
+    if ((int)blockIdx.x >= n_tiles) return;
+    const int t = ks_xcd_remap(blockIdx.x, n_tiles);
+    const int tn = t % tiles_n, tm = t / tiles_n;
+    KsARows<T::BM, T::NW> ar;
+    KsARows<T::BN, T::NW> br;
+    ar.init(dZT, Bp, nullptr, tm * T::BM, (int)Mp);
+    br.init(XT, Bp, nullptr, tn * T::BN, D);
+    f32x16_t acc[T::FM][T::FN];
+    ks_a_clear<T>(acc);
+    ks_a_mainloop<T>(ar, br, 0, Bp / 64, lds, acc);
+    ks_a_foreach<T>(acc, [&](int m, int n, float v) {
+        int a = tm * T::BM + m, d = tn * T::BN + n;
+        if (a < n_active && d < D) dW[(int64_t)a * D + d] = scale * v;
+    });
+}
+
 // ------------------------------------------------------------------------------------------------
 // stand-alone row gather (Algorithm 1's W_active as a dense matrix); one wavefront per row
 // ------------------------------------------------------------------------------------------------
@@ -253,12 +451,16 @@ struct SmWs {
     uint16_t *dZ;
     float *lse;
     float *part;
+    uint16_t *dZT, *WAT, *XT; // fast path only
     int S;
     int64_t Mp;
+    int Bp;
+    bool fast;
 };
 
-static int sm_splits(int B, int D) {
-    int tiles = (int)(ks_ceil_div(B, TileG::BM) * ks_ceil_div(D, TileG::BN));
+static int sm_splits(int B, int D, bool fast) {
+    int tiles = fast ? (int)(ks_ceil_div(B, TileDx::BM) * ks_ceil_div(D, TileDx::BN))
+                     : (int)(ks_ceil_div(B, TileG::BM) * ks_ceil_div(D, TileG::BN));
     int S = (int)ks_ceil_div(512, tiles);
     if (S < 1) S = 1;
     if (S > 32) S = 32;
@@ -268,13 +470,21 @@ static int sm_splits(int B, int D) {
 static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool with_select, size_t *total) {
     KsArena ar(ws);
     SmWs w;
+    w.fast = (D % 64 == 0);
     w.Mp = sm_mp(M);
-    w.S = sm_splits(B, D);
+    w.Bp = (int)ks_align_up((size_t)B, KS_BP_ALIGN);
+    w.S = sm_splits(B, D, w.fast);
     w.select = with_select ? (void *)ar.take<char>(ks_select_ws_bytes(C, K)) : nullptr;
     w.Z = ar.take<float>((size_t)B * w.Mp);
     w.dZ = ar.take<uint16_t>((size_t)B * w.Mp);
     w.lse = ar.take<float>((size_t)B);
     w.part = ar.take<float>((size_t)w.S * B * D);
+    w.dZT = w.WAT = w.XT = nullptr;
+    if (w.fast) {
+        w.dZT = ar.take<uint16_t>((size_t)w.Mp * w.Bp);
+        w.WAT = ar.take<uint16_t>((size_t)D * w.Mp);
+        w.XT = ar.take<uint16_t>((size_t)D * w.Bp);
+    }
     if (total) *total = ar.off;
     return w;
 }
@@ -284,9 +494,51 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
                   const int32_t *active_idx, const int32_t *n_active, const int32_t *target_pos,
                   float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, const SmWs &w,
                   hipStream_t st, hipEvent_t *ev = nullptr) {
-    typedef TileG T;
     auto mark = [&](int k) { if (ev) (void)hipEventRecord(ev[k], st); };
     const int Mi = (int)M;
+    const float g = grad_scale / (float)B;
+    if (w.fast) {
+        // transposed copies of the small operand X and of the active rows (both independent of Z)
+        hipLaunchKernelGGL(transpose_rows_kernel, dim3((unsigned)ks_ceil_div(w.Bp, TR_TILE), (unsigned)ks_ceil_div(D, TR_TILE)),
+                           dim3(SM_NT), 0, st, X, (int64_t)D, (const int32_t *)nullptr, (const int32_t *)nullptr, B, D, w.XT,
+                           (int64_t)w.Bp);
+        hipLaunchKernelGGL(transpose_rows_kernel, dim3((unsigned)ks_ceil_div(w.Mp, TR_TILE), (unsigned)ks_ceil_div(D, TR_TILE)),
+                           dim3(SM_NT), 0, st, W, (int64_t)D, active_idx, n_active, Mi, D, w.WAT, w.Mp);
+        {
+            typedef TileLogits T;
+            const int tiles = (int)(ks_ceil_div(B, T::BM) * ks_ceil_div(M, T::BN));
+            hipLaunchKernelGGL(logits_async_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, X, W, active_idx, n_active, B, D, Mi,
+                               scale, w.Z, w.Mp);
+        }
+        mark(2);
+        hipLaunchKernelGGL(row_stats_kernel, dim3(B), dim3(SM_NT), 0, st, w.Z, w.Mp, n_active, Mi, target_pos, w.lse,
+                           loss_per_sample);
+        hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(SM_NT), 0, st, loss_per_sample, B, loss_mean);
+        mark(3);
+        hipLaunchKernelGGL(dz_dual_kernel, dim3((unsigned)ks_ceil_div(w.Mp, TR_TILE), (unsigned)ks_ceil_div(w.Bp, TR_TILE)),
+                           dim3(SM_NT), 0, st, w.Z, w.Mp, n_active, Mi, B, w.Bp, target_pos, w.lse, g, w.dZ, w.dZT);
+        mark(4);
+        {
+            typedef TileDx T;
+            const int tiles = (int)(ks_ceil_div(B, T::BM) * ks_ceil_div(D, T::BN));
+            hipLaunchKernelGGL(dx_partial_async_kernel<T>, dim3(tiles * w.S), dim3(T::NT), 0, st, w.dZ, w.Mp, w.WAT, n_active,
+                               B, D, Mi, w.S, w.part);
+        }
+        mark(5);
+        hipLaunchKernelGGL(dx_reduce_kernel, dim3((unsigned)ks_ceil_div((int64_t)B * D / 4, SM_NT)), dim3(SM_NT), 0, st, w.part,
+                           w.S, (int64_t)B * D, scale, dX);
+        mark(6);
+        {
+            typedef TileDw T;
+            const int tiles = (int)(ks_ceil_div(M, T::BM) * ks_ceil_div(D, T::BN));
+            hipLaunchKernelGGL(dw_async_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, w.dZT, w.XT, w.Bp, n_active, D, Mi, w.Mp,
+                               scale, dW_active);
+        }
+        mark(7);
+        KS_LAUNCH_CHECK();
+        return KS_OK;
+    }
+    typedef TileG T;
     const int tiles_b = (int)ks_ceil_div(B, T::BM);
     const int tiles_a_n = (int)ks_ceil_div(M, T::BN), tiles_a_m = (int)ks_ceil_div(M, T::BM);
     const int tiles_d = (int)ks_ceil_div(D, T::BN);
@@ -299,7 +551,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
     hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(SM_NT), 0, st, loss_per_sample, B, loss_mean);
     mark(3);
     hipLaunchKernelGGL(dz_kernel, dim3((unsigned)ks_ceil_div(w.Mp, SM_NT * 8), B), dim3(SM_NT), 0, st, w.Z, w.Mp, n_active,
-                       Mi, target_pos, w.lse, grad_scale / (float)B, w.dZ);
+                       Mi, target_pos, w.lse, g, w.dZ);
     mark(4);
     hipLaunchKernelGGL(dx_partial_kernel<T>, dim3(tiles_b * tiles_d, w.S), dim3(T::NT), 0, st, w.dZ, w.Mp, W, active_idx,
                        n_active, B, D, Mi, w.part);
