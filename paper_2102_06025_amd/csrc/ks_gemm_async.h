@@ -70,18 +70,110 @@ template <int ROWS, int NW> struct KsARows {
     }
 };
 
+// ---------------------------------------------------------------------------------------------
+// Operand stored k-major: element (k, c) at base[src(k) * ld + c] (c = the operand's m or n index, fast in
+// memory).  The tile is kept in LDS as it is, [64 k-rows][W columns], and the MFMA fragments (8
+// consecutive k per lane) are produced by the transposing LDS read ds_read_b64_tr_b16: inside each group
+// of 16 lanes, lane 4r+q supplies the address of 4 consecutive columns of k-row r, and lane i receives
+// column i of those four k-rows.  16-byte chunk c of k-row k sits in slot c ^ ((k & 3) << 2), so that
+// the four k-rows touched by one read fall on different bank groups.
+// Rows k >= k_limit are redirected to row k_limit-1 (the other operand must be zero there); columns
+// beyond col_limit are redirected to the last 8 valid columns.  src(k) goes through an optional gather
+// list, read one k-tile ahead of its use.
+// ---------------------------------------------------------------------------------------------
+template <int W, int NW> struct KsAKmaj {
+    static constexpr int CPR = W / 8;            // 16-byte chunks per k-row
+    static constexpr int RPI = 64 / CPR;         // k-rows per wave-wide load instruction
+    static constexpr int NI = CPR / NW;          // load instructions per wave per tile
+    static_assert(CPR % NW == 0 && NI >= 1 && (W == 128 || W == 256), "k-major tile shape");
+    const uint16_t *base;
+    const int32_t *gidx;
+    int64_t ld;
+    int k_limit;
+    int col_off;          // element offset of this lane's chunk inside a source row
+    int kloc[NI];         // k-row (tile local) of this lane for each instruction
+    int32_t src_next[NI]; // gathered source rows of the next k-tile to be issued
+
+    __device__ __forceinline__ int src_row(int kg) const {
+        if (kg >= k_limit) kg = k_limit - 1;
+        return kg;
+    }
+    // k0_first: first k of the first tile that will be issued
+    __device__ __forceinline__ void init(const uint16_t *base_, int64_t ld_, const int32_t *gidx_, int col0, int col_limit,
+                                         int k_limit_, int k0_first) {
+        base = base_; ld = ld_; gidx = gidx_; k_limit = k_limit_;
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int j = 0; j < NI; ++j) kloc[j] = (j * NW + wave) * RPI + lane / CPR;
+        // the slot this lane fills is lane % CPR; it holds chunk slot ^ ((k & 3) << 2); k & 3 is the same for
+        // every instruction of this lane when RPI is a multiple of 4, otherwise it is folded in per instruction
+        int col = col0 + (lane % CPR) * 8;
+        col_off = col; // un-swizzled; the swizzle is applied per instruction in issue()
+        col_lim8 = col_limit - 8;
+        col_base = col0;
+        if (gidx) {
+#pragma unroll
+            for (int j = 0; j < NI; ++j) src_next[j] = gidx[src_row(k0_first + kloc[j])];
+        }
+    }
+    int col_lim8, col_base;
+    __device__ __forceinline__ void issue(int k0, uint16_t *lds) {
+        const int lane = threadIdx.x & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int k = kloc[j];
+            int col = col_base + (((lane % CPR) ^ ((k & 3) << 2)) * 8);
+            if (col > col_lim8) col = col_lim8;
+            int64_t src;
+            if (gidx) {
+                src = src_next[j];
+                src_next[j] = gidx[src_row(k0 + 64 + k)]; // for the next tile in the stream
+            } else {
+                src = src_row(k0 + k);
+            }
+            __builtin_amdgcn_global_load_lds(KS_GPTR(base + src * ld + col), KS_LPTR(lds + (j * NW + wave) * RPI * W), 16, 0, 0);
+        }
+    }
+};
+
+// fragment of a k-major tile: 8 consecutive k (k-step kk) of column block `cb` (32 columns)
+template <int W>
+__device__ __forceinline__ bf16x8_t ks_a_frag_kmaj(const uint16_t *tile, int cb32, int kk) {
+    typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 4, r = (lane >> 2) & 3, q = lane & 3;
+    const int kb = kk * 16 + (g >> 1) * 8 + r;
+    const int chunk = cb32 * 4 + (g & 1) * 2 + (q >> 1);
+    // k & 3 == r for both halves (kb + 4 has the same low bits)
+    const int off = ((chunk ^ (r << 2)) * 8) + (q & 1) * 4;
+    bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4_t __attribute__((address_space(3))) *)(tile + kb * W + off));
+    bf16x4_t hi =
+        __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4_t __attribute__((address_space(3))) *)(tile + (kb + 4) * W + off));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 template <class T> struct KsAFrags {
     bf16x8_t a[T::FM], b[T::FN];
 };
 
-template <class T>
-__device__ __forceinline__ void ks_a_load_frags(KsAFrags<T> &f, const uint16_t *stA, const uint16_t *stB, int kk, int offA,
-                                                int offB, int swz, int khalf) {
+// fragments of k-step kk; AK / BK say whether the operand tile is k-major
+template <class T, bool AK, bool BK>
+__device__ __forceinline__ void ks_a_load_frags(KsAFrags<T> &f, const uint16_t *stA, const uint16_t *stB, int kk) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
+    const int r = lane & 31, khalf = lane >> 5, swz = (lane >> 1) & 7;
     const int co = ((kk * 2 + khalf) ^ swz) * 8;
 #pragma unroll
-    for (int fm = 0; fm < T::FM; ++fm) f.a[fm] = *(const bf16x8_t *)(stA + offA + fm * 32 * 64 + co);
+    for (int fm = 0; fm < T::FM; ++fm) {
+        if (AK) f.a[fm] = ks_a_frag_kmaj<T::BM>(stA, wm * T::FM + fm, kk);
+        else f.a[fm] = *(const bf16x8_t *)(stA + (wm * T::WM + fm * 32 + r) * 64 + co);
+    }
 #pragma unroll
-    for (int fn = 0; fn < T::FN; ++fn) f.b[fn] = *(const bf16x8_t *)(stB + offB + fn * 32 * 64 + co);
+    for (int fn = 0; fn < T::FN; ++fn) {
+        if (BK) f.b[fn] = ks_a_frag_kmaj<T::BN>(stB, wn * T::FN + fn, kk);
+        else f.b[fn] = *(const bf16x8_t *)(stB + (wn * T::WN + fn * 32 + r) * 64 + co);
+    }
 }
 
 template <class T>
@@ -93,28 +185,24 @@ __device__ __forceinline__ void ks_a_mma(const KsAFrags<T> &f, f32x16_t (&acc)[T
             acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[fm], f.b[fn], acc[fm][fn], 0, 0, 0);
 }
 
-// MFMAs of one k-tile held in the stage at `st` (A tile first, then B tile)
-template <class T>
+// MFMAs of one k-tile held in the stage at `st` (A tile first, then B tile).  Register double buffering
+// of the fragments; the scheduling barriers keep the compiler from collapsing it (the reads of step
+// kk+1 are in flight while the MFMAs of step kk issue).
+template <class T, bool AK = false, bool BK = false>
 __device__ __forceinline__ void ks_a_tile_mma(const uint16_t *st, f32x16_t (&acc)[T::FM][T::FN]) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r = lane & 31, khalf = lane >> 5, swz = (lane >> 1) & 7;
-    const int offA = ((wave / T::WAVES_N) * T::WM + r) * 64;
-    const int offB = ((wave % T::WAVES_N) * T::WN + r) * 64;
     const uint16_t *stA = st, *stB = st + T::BM * 64;
-    // register double buffering of the fragments; the scheduling barriers keep the compiler from
-    // collapsing it (reads of step kk+1 are in flight while the MFMAs of step kk issue)
     KsAFrags<T> f0, f1;
-    ks_a_load_frags<T>(f0, stA, stB, 0, offA, offB, swz, khalf);
+    ks_a_load_frags<T, AK, BK>(f0, stA, stB, 0);
     __builtin_amdgcn_sched_barrier(0);
-    ks_a_load_frags<T>(f1, stA, stB, 1, offA, offB, swz, khalf);
+    ks_a_load_frags<T, AK, BK>(f1, stA, stB, 1);
     __builtin_amdgcn_sched_barrier(0);
     ks_a_mma<T>(f0, acc);
     __builtin_amdgcn_sched_barrier(0);
-    ks_a_load_frags<T>(f0, stA, stB, 2, offA, offB, swz, khalf);
+    ks_a_load_frags<T, AK, BK>(f0, stA, stB, 2);
     __builtin_amdgcn_sched_barrier(0);
     ks_a_mma<T>(f1, acc);
     __builtin_amdgcn_sched_barrier(0);
-    ks_a_load_frags<T>(f1, stA, stB, 3, offA, offB, swz, khalf);
+    ks_a_load_frags<T, AK, BK>(f1, stA, stB, 3);
     __builtin_amdgcn_sched_barrier(0);
     ks_a_mma<T>(f0, acc);
     __builtin_amdgcn_sched_barrier(0);
@@ -122,12 +210,14 @@ __device__ __forceinline__ void ks_a_tile_mma(const uint16_t *st, f32x16_t (&acc
 }
 
 // Main loop over k-tiles [kt0, kt1) (k0 = kt * 64).  All threads of the workgroup must call it with the
-// same range.  On return every wave has passed a barrier after its last LDS read only if `final_barrier`.
-template <class T, class AR, class BR>
-__device__ __forceinline__ void ks_a_mainloop(const AR &ar, const BR &br, int kt0, int kt1, uint16_t *lds,
+// same range.  Ends with a barrier, so the LDS can be reused at once.  AR / BR are KsARows (k contiguous)
+// or KsAKmaj (k-major) loaders; AK / BK tell the fragment reader which.
+template <class T, bool AK = false, bool BK = false, class AR, class BR>
+__device__ __forceinline__ void ks_a_mainloop(AR &ar, BR &br, int kt0, int kt1, uint16_t *lds,
                                               f32x16_t (&acc)[T::FM][T::FN]) {
     constexpr int S = T::STAGES;
     constexpr int PER_TILE = T::NI_A + T::NI_B;
+    static_assert(S == 2 || (!AK && !BK), "k-major loaders issue their gather-index loads in between: two stages only");
 #pragma unroll
     for (int s = 0; s < S - 1; ++s) {
         if (kt0 + s < kt1) {
@@ -139,7 +229,7 @@ __device__ __forceinline__ void ks_a_mainloop(const AR &ar, const BR &br, int kt
     int stage = 0;
     for (int kt = kt0; kt < kt1; ++kt) {
         // loads younger than tile kt: tiles kt+1 .. kt+S-2 when they all exist
-        if (kt + S - 2 < kt1) ks_wait_vmcnt<(S - 2) * PER_TILE>();
+        if (S > 2 && kt + S - 2 < kt1) ks_wait_vmcnt<(S - 2) * PER_TILE>();
         else ks_wait_vmcnt<0>();
         ks_barrier_nofence();
         if (kt + S - 1 < kt1) {
@@ -149,10 +239,9 @@ __device__ __forceinline__ void ks_a_mainloop(const AR &ar, const BR &br, int kt
             ar.issue((kt + S - 1) * 64, st);
             br.issue((kt + S - 1) * 64, st + T::BM * 64);
         }
-        ks_a_tile_mma<T>(lds + stage * T::STAGE_ELEMS, acc);
+        ks_a_tile_mma<T, AK, BK>(lds + stage * T::STAGE_ELEMS, acc);
         if (++stage == S) stage = 0;
     }
-    // make the LDS reusable by the caller (next tile or epilogue staging)
     ks_barrier_nofence();
 }
 

@@ -14,8 +14,10 @@
 // Every decision that reaches the output is taken on the canonical fp64 similarity, so the lists are
 // exact and do not depend on scheduling.
 #include "ks_gemm.h"
+#include "ks_gemm_async.h"
 
-typedef KsTile<128, 128, 64, 2, 2> TileR;
+typedef KsTile<128, 128, 64, 2, 2> TileR;       // generic recall tile (any D % 32 == 0)
+typedef KsATile<256, 256, 2, 4, 2> TileRA;      // asynchronous recall tile (D % 64 == 0)
 
 #define GR_NT 256
 #define GR_FB_BLOCKS 64   /* workgroups (and fp64 scratch rows) of the exhaustive pass */
@@ -33,11 +35,12 @@ struct GrParams {
     int kprime; // candidates kept per row by the recall pass (64, 128 or 256)
     int cap;    // candidate buffer entries per row (256 or 512)
 };
-static GrParams gr_params(int K) {
+static GrParams gr_params(int K, int D) {
     GrParams p;
     if (K <= 32) { p.kprime = 64; p.cap = 256; }
     else if (K <= 64) { p.kprime = 128; p.cap = 256; }
     else { p.kprime = 256; p.cap = 512; }
+    if (D % 64 == 0) p.cap = 512; // the asynchronous recall kernel appends up to 256 candidates per row and tile
     return p;
 }
 
@@ -195,6 +198,82 @@ gr_recall_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kprime, 
         __syncthreads();
     }
     for (int m = wave; m < T::BM; m += T::NT / 64) {
+        if (row0 + m < C) {
+            if (s_cnt[m] > kprime) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
+        }
+    }
+    __syncthreads();
+    for (int m = threadIdx.x; m < T::BM; m += T::NT) {
+        if (row0 + m < C) { cnt_out[row0 + m] = s_cnt[m]; thr_out[row0 + m] = s_thr[m]; }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// recall pass on the asynchronous engine (D % 64 == 0): 256 rows per workgroup, 256-column blocks.
+// The k-tiles of the whole sweep form one stream: the first k-tile of the next column block is already
+// on its way into LDS while the current block's similarities are filtered.
+// ------------------------------------------------------------------------------------------------
+template <class T, int E>
+__global__ void __launch_bounds__(T::NT)
+gr_recall_async_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kprime, uint64_t *__restrict__ cand,
+                       int32_t *__restrict__ cnt_out, uint32_t *__restrict__ thr_out) {
+    constexpr int CAP = E * 64;
+    static_assert(T::STAGES == 2 && CAP >= 256 + T::BN, "recall tile");
+    __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
+    __shared__ int s_cnt[T::BM];
+    __shared__ uint32_t s_thr[T::BM];
+    const int wave = threadIdx.x >> 6;
+    const int64_t row0 = (int64_t)blockIdx.x * T::BM;
+    for (int m = threadIdx.x; m < T::BM; m += T::NT) { s_cnt[m] = 0; s_thr[m] = 0u; }
+    __syncthreads();
+
+    KsARows<T::BM, T::NW> ar;
+    KsARows<T::BN, T::NW> br;
+    ar.init(Wb, D, nullptr, (int)row0, (int)C);
+    br.init(Wb, D, nullptr, 0, (int)C);
+    const int nJ = (int)((C + T::BN - 1) / T::BN), nk = D / 64;
+    // stream position of the next tile to load
+    int ld_J = 0, ld_kt = 0;
+    auto issue_next = [&](int stage) {
+        uint16_t *st = lds + stage * T::STAGE_ELEMS;
+        ar.issue(ld_kt * 64, st);
+        br.issue(ld_kt * 64, st + T::BM * 64);
+        if (++ld_kt == nk) {
+            ld_kt = 0;
+            ++ld_J;
+            if (ld_J < nJ) br.init(Wb, D, nullptr, ld_J * T::BN, (int)C);
+        }
+    };
+    issue_next(0);
+    int stage = 0;
+    for (int J = 0; J < nJ; ++J) {
+        f32x16_t acc[T::FM][T::FN];
+        ks_a_clear<T>(acc);
+        for (int kt = 0; kt < nk; ++kt) {
+            ks_wait_vmcnt<0>();
+            ks_barrier_nofence();
+            if (ld_J < nJ) issue_next(stage ^ 1);
+            ks_a_tile_mma<T>(lds + stage * T::STAGE_ELEMS, acc);
+            stage ^= 1;
+        }
+        ks_a_foreach<T>(acc, [&](int m, int n, float v) {
+            const int64_t i = row0 + m, j = (int64_t)J * T::BN + n;
+            if (i < C && j < C && i != j) {
+                const uint32_t hi = gr_orderable(v);
+                if (hi > s_thr[m]) {
+                    int slot = atomicAdd(&s_cnt[m], 1);
+                    if (slot < CAP) // always true: a buffer is cut back before it can overflow
+                        cand[i * CAP + slot] = ((uint64_t)hi << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
+                }
+            }
+        });
+        __syncthreads();
+        for (int m = wave; m < T::BM; m += T::NW) {
+            if (s_cnt[m] > CAP - T::BN) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
+        }
+        __syncthreads();
+    }
+    for (int m = wave; m < T::BM; m += T::NW) {
         if (row0 + m < C) {
             if (s_cnt[m] > kprime) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
         }
@@ -374,7 +453,7 @@ struct GrWs {
 
 static GrWs gr_carve(void *ws, int64_t C, int D, int K, int dtype, size_t *total) {
     KsArena ar(ws);
-    GrParams p = gr_params(K);
+    GrParams p = gr_params(K, D);
     GrWs w;
     w.Wb = dtype == KS_DTYPE_FP32 ? ar.take<uint16_t>((size_t)C * D) : nullptr;
     w.norms = ar.take<float>((size_t)C);
@@ -421,7 +500,7 @@ extern "C" int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K
     size_t need = 0;
     GrWs w = gr_carve(ws, C, D, K, dtype, &need);
     if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
-    const GrParams p = gr_params(K);
+    const GrParams p = gr_params(K, D);
     hipStream_t st = (hipStream_t)stream;
 
     hipLaunchKernelGGL(gr_zero_kernel, dim3(1), dim3(1), 0, st, w.maxnorm, w.fb_count);
@@ -436,13 +515,18 @@ extern "C" int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K
                            (uint16_t *)nullptr, w.norms, w.maxnorm);
         Wb = (const uint16_t *)W;
     }
-    const unsigned recall_blocks = (unsigned)ks_ceil_div(C, TileR::BM);
-    if (p.cap == 256)
-        hipLaunchKernelGGL((gr_recall_kernel<TileR, 4>), dim3(recall_blocks), dim3(TileR::NT), 0, st, Wb, C, D, p.kprime, w.cand,
-                           w.cnt, w.thr);
-    else
-        hipLaunchKernelGGL((gr_recall_kernel<TileR, 8>), dim3(recall_blocks), dim3(TileR::NT), 0, st, Wb, C, D, p.kprime, w.cand,
-                           w.cnt, w.thr);
+    if (D % 64 == 0) {
+        hipLaunchKernelGGL((gr_recall_async_kernel<TileRA, 8>), dim3((unsigned)ks_ceil_div(C, TileRA::BM)), dim3(TileRA::NT), 0,
+                           st, Wb, C, D, p.kprime, w.cand, w.cnt, w.thr);
+    } else {
+        const unsigned recall_blocks = (unsigned)ks_ceil_div(C, TileR::BM);
+        if (p.cap == 256)
+            hipLaunchKernelGGL((gr_recall_kernel<TileR, 4>), dim3(recall_blocks), dim3(TileR::NT), 0, st, Wb, C, D, p.kprime,
+                               w.cand, w.cnt, w.thr);
+        else
+            hipLaunchKernelGGL((gr_recall_kernel<TileR, 8>), dim3(recall_blocks), dim3(TileR::NT), 0, st, Wb, C, D, p.kprime,
+                               w.cand, w.cnt, w.thr);
+    }
     // error bound of the recall pass relative to |w_i||w_j|: fp32 accumulation of D exact bf16 products
     // (2^-23 per addition allows for truncating adders), plus the bf16 rounding of both rows (2 * 2^-9,
     // rounded up to 2^-7.9) when the input is fp32; a small slack covers the fp32 norms themselves

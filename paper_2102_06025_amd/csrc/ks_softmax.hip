@@ -216,10 +216,10 @@ dw_kernel(const uint16_t *__restrict__ dZ, int64_t ldz, const uint16_t *__restri
 }
 
 // ================================================================================================
-// Fast path (D % 64 == 0).  All three contractions run on the asynchronous engine, which wants both
-// operands with k contiguous; the operands that are not (W_active for dX, dZ and X for dW) get
-// transposed copies from two bandwidth-bound kernels: the gather writes W_active^T, the logit-gradient
-// kernel writes dZ and dZ^T in one pass over Z.
+// Fast path (D % 64 == 0).  All three contractions run on the asynchronous engine.  The logit gradient
+// is stored once, transposed (dZT[a][i]); it is the k-contiguous operand of the dW contraction and a
+// k-major operand of the dX contraction.  Weight rows (gathered through the index list) and X enter as
+// k-major operands where k is their row index, so no transposed copies of them are made.
 // ================================================================================================
 
 // 8x8 transpose of 16-bit elements held as 8 rows of uint4 (row k, elements n=0..7) -> out[n] = 8 k's
@@ -240,42 +240,6 @@ __device__ __forceinline__ void sm_transpose8x8(const uint4 (&in)[8], uint4 (&ou
 
 #define TR_TILE 128
 #define TR_LD (TR_TILE + 8)
-// out[c][r] = in[src(r)][c] for r < n_rows (src through the optional index list), zero for
-// n_rows <= r < round_up(n_rows, 256); c < n_cols (n_cols % 8 == 0).  One 128 x 128 tile per workgroup.
-__global__ void __launch_bounds__(SM_NT)
-transpose_rows_kernel(const uint16_t *__restrict__ in, int64_t ld_in, const int32_t *__restrict__ gidx,
-                      const int32_t *__restrict__ n_rows_p, int rows_cap, int n_cols, uint16_t *__restrict__ out,
-                      int64_t ld_out) {
-    __shared__ __attribute__((aligned(16))) uint16_t tile[TR_TILE * TR_LD]; // [c][r]
-    int n_rows = n_rows_p ? *n_rows_p : rows_cap;
-    n_rows = n_rows < 0 ? 0 : (n_rows > rows_cap ? rows_cap : n_rows);
-    const int n_pad = (n_rows + KS_MP_ALIGN - 1) / KS_MP_ALIGN * KS_MP_ALIGN;
-    const int r0 = blockIdx.x * TR_TILE, c0 = blockIdx.y * TR_TILE;
-    if (r0 >= n_pad) return;
-    const int cb = threadIdx.x & 15, rb = threadIdx.x >> 4; // 16 column blocks x 16 row blocks of 8x8
-    uint4 v[8], t[8];
-    const int c = c0 + cb * 8;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const int r = r0 + rb * 8 + k;
-        if (r < n_rows && c < n_cols) {
-            const int64_t src = gidx ? (int64_t)gidx[r] : (int64_t)r;
-            v[k] = *(const uint4 *)(in + src * ld_in + c);
-        } else {
-            v[k] = make_uint4(0, 0, 0, 0);
-        }
-    }
-    sm_transpose8x8(v, t);
-#pragma unroll
-    for (int n = 0; n < 8; ++n) *(uint4 *)(tile + (cb * 8 + n) * TR_LD + rb * 8) = t[n];
-    __syncthreads();
-#pragma unroll
-    for (int pass = 0; pass < 8; ++pass) {
-        const int cc = pass * 16 + (threadIdx.x >> 4), chunk = threadIdx.x & 15;
-        if (c0 + cc < n_cols && r0 + chunk * 8 < n_pad)
-            *(uint4 *)(out + (int64_t)(c0 + cc) * ld_out + r0 + chunk * 8) = *(const uint4 *)(tile + cc * TR_LD + chunk * 8);
-    }
-}
 
 // Z = scale * X . W[active]^T on the asynchronous engine
 template <class T>
@@ -303,12 +267,12 @@ logits_async_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
     });
 }
 
-// dZ[i][a] and dZT[a][i] (bf16) from Z and the row log-sum-exps; 128 x 128 tile per workgroup, each
-// thread an 8 x 8 block.  Zero for a in [n_active, round_up(n_active, 256)) and for i in [B, Bp).
+// dZT[a][i] = g (exp(Z[i][a] - lse_i) - [a == target_pos[i]]) as bf16, i.e. the logit gradient stored with
+// the sample index fast; 128 x 128 tile per workgroup, each thread an 8 x 8 block, transposed through
+// LDS.  Zero for a in [n_active, round_up(n_active, 256)) and for i in [B, Bp).
 __global__ void __launch_bounds__(SM_NT)
-dz_dual_kernel(const float *__restrict__ Z, int64_t ldz, const int32_t *__restrict__ n_active_p, int M, int B, int Bp,
-               const int32_t *__restrict__ target_pos, const float *__restrict__ lse, float g,
-               uint16_t *__restrict__ dZ, uint16_t *__restrict__ dZT) {
+dz_t_kernel(const float *__restrict__ Z, int64_t ldz, const int32_t *__restrict__ n_active_p, int M, int B, int Bp,
+            const int32_t *__restrict__ target_pos, const float *__restrict__ lse, float g, uint16_t *__restrict__ dZT) {
     __shared__ __attribute__((aligned(16))) uint16_t tile[TR_TILE * TR_LD]; // [a][i]
     const int n = sm_clamp_n(n_active_p, M);
     const int n_pad = (n + KS_MP_ALIGN - 1) / KS_MP_ALIGN * KS_MP_ALIGN;
@@ -340,7 +304,6 @@ dz_dual_kernel(const float *__restrict__ Z, int64_t ldz, const int32_t *__restri
             for (int e = 0; e < 8; ++e) d[e] = 0.f;
         }
         v[k] = make_uint4(ks_pack_bf2(d[0], d[1]), ks_pack_bf2(d[2], d[3]), ks_pack_bf2(d[4], d[5]), ks_pack_bf2(d[6], d[7]));
-        if (i < B) *(uint4 *)(dZ + (int64_t)i * ldz + a) = v[k];
     }
     sm_transpose8x8(v, t);
 #pragma unroll
@@ -354,11 +317,13 @@ dz_dual_kernel(const float *__restrict__ Z, int64_t ldz, const int32_t *__restri
     }
 }
 
-// dX partials on the asynchronous engine: P[s][i][d] = sum_{a in share s} dZ[i][a] * WAT[d][a]
+// dX partials on the asynchronous engine: P[s][i][d] = sum_{a in share s} dZT[a][i] * W[active[a]][d].
+// Both operands are k-major (k = a): dZT as stored, the weight rows fetched through the index list.
 template <class T>
 __global__ void __launch_bounds__(T::NT)
-dx_partial_async_kernel(const uint16_t *__restrict__ dZ, int64_t ldz, const uint16_t *__restrict__ WAT,
-                        const int32_t *__restrict__ n_active_p, int B, int D, int M, int S, float *__restrict__ part) {
+dx_partial_async_kernel(const uint16_t *__restrict__ dZT, int Bp, int64_t Mp, const uint16_t *__restrict__ W,
+                        const int32_t *__restrict__ active_idx, const int32_t *__restrict__ n_active_p, int B, int D, int M,
+                        int S, float *__restrict__ part) {
     __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
     const int n_active = sm_clamp_n(n_active_p, M);
     const int tiles_m = (B + T::BM - 1) / T::BM, tiles_n = (D + T::BN - 1) / T::BN;
@@ -369,13 +334,15 @@ dx_partial_async_kernel(const uint16_t *__restrict__ dZ, int64_t ldz, const uint
     const int nk = (n_active + 63) / 64;
     const int per = (nk + S - 1) / S;
     const int kt0 = s * per, kt1 = (kt0 + per < nk) ? kt0 + per : nk;
-    KsARows<T::BM, T::NW> ar;
-    KsARows<T::BN, T::NW> br;
-    ar.init(dZ, ldz, nullptr, tm * T::BM, B);
-    br.init(WAT, ldz, nullptr, tn * T::BN, D);
     f32x16_t acc[T::FM][T::FN];
     ks_a_clear<T>(acc);
-    if (kt0 < kt1) ks_a_mainloop<T>(ar, br, kt0, kt1, lds, acc);
+    if (kt0 < kt1) {
+        KsAKmaj<T::BM, T::NW> ar;
+        KsAKmaj<T::BN, T::NW> br;
+        ar.init(dZT, Bp, nullptr, tm * T::BM, Bp, (int)Mp, kt0 * 64);
+        br.init(W, D, active_idx, tn * T::BN, D, n_active, kt0 * 64);
+        ks_a_mainloop<T, true, true>(ar, br, kt0, kt1, lds, acc);
+    }
     float *out = part + (int64_t)s * B * D;
     ks_a_foreach<T>(acc, [&](int m, int n, float v) {
         int i = tm * T::BM + m, d = tn * T::BN + n;
@@ -383,10 +350,10 @@ dx_partial_async_kernel(const uint16_t *__restrict__ dZ, int64_t ldz, const uint
     });
 }
 
-// dW_active[a][d] = scale * sum_i dZT[a][i] * XT[d][i] on the asynchronous engine
+// dW_active[a][d] = scale * sum_i dZT[a][i] * X[i][d] on the asynchronous engine (X k-major, k = i)
 template <class T>
 __global__ void __launch_bounds__(T::NT)
-dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ XT, int Bp,
+dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X, int B, int Bp,
                 const int32_t *__restrict__ n_active_p, int D, int M, int64_t Mp, float scale, float *__restrict__ dW) {
     __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
     const int n_active = sm_clamp_n(n_active_p, M);
@@ -396,12 +363,12 @@ dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X
     const int t = ks_xcd_remap(blockIdx.x, n_tiles);
     const int tn = t % tiles_n, tm = t / tiles_n;
     KsARows<T::BM, T::NW> ar;
-    KsARows<T::BN, T::NW> br;
+    KsAKmaj<T::BN, T::NW> br;
     ar.init(dZT, Bp, nullptr, tm * T::BM, (int)Mp);
-    br.init(XT, Bp, nullptr, tn * T::BN, D);
+    br.init(X, D, nullptr, tn * T::BN, D, B, 0);
     f32x16_t acc[T::FM][T::FN];
     ks_a_clear<T>(acc);
-    ks_a_mainloop<T>(ar, br, 0, Bp / 64, lds, acc);
+    ks_a_mainloop<T, false, true>(ar, br, 0, Bp / 64, lds, acc);
     ks_a_foreach<T>(acc, [&](int m, int n, float v) {
         int a = tm * T::BM + m, d = tn * T::BN + n;
         if (a < n_active && d < D) dW[(int64_t)a * D + d] = scale * v;
@@ -451,7 +418,7 @@ struct SmWs {
     uint16_t *dZ;
     float *lse;
     float *part;
-    uint16_t *dZT, *WAT, *XT; // fast path only
+    uint16_t *dZT; // fast path: the logit gradient is kept transposed only
     int S;
     int64_t Mp;
     int Bp;
@@ -476,15 +443,11 @@ static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool w
     w.S = sm_splits(B, D, w.fast);
     w.select = with_select ? (void *)ar.take<char>(ks_select_ws_bytes(C, K)) : nullptr;
     w.Z = ar.take<float>((size_t)B * w.Mp);
-    w.dZ = ar.take<uint16_t>((size_t)B * w.Mp);
     w.lse = ar.take<float>((size_t)B);
     w.part = ar.take<float>((size_t)w.S * B * D);
-    w.dZT = w.WAT = w.XT = nullptr;
-    if (w.fast) {
-        w.dZT = ar.take<uint16_t>((size_t)w.Mp * w.Bp);
-        w.WAT = ar.take<uint16_t>((size_t)D * w.Mp);
-        w.XT = ar.take<uint16_t>((size_t)D * w.Bp);
-    }
+    w.dZ = w.dZT = nullptr;
+    if (w.fast) w.dZT = ar.take<uint16_t>((size_t)w.Mp * w.Bp);
+    else w.dZ = ar.take<uint16_t>((size_t)B * w.Mp);
     if (total) *total = ar.off;
     return w;
 }
@@ -498,12 +461,6 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
     const int Mi = (int)M;
     const float g = grad_scale / (float)B;
     if (w.fast) {
-        // transposed copies of the small operand X and of the active rows (both independent of Z)
-        hipLaunchKernelGGL(transpose_rows_kernel, dim3((unsigned)ks_ceil_div(w.Bp, TR_TILE), (unsigned)ks_ceil_div(D, TR_TILE)),
-                           dim3(SM_NT), 0, st, X, (int64_t)D, (const int32_t *)nullptr, (const int32_t *)nullptr, B, D, w.XT,
-                           (int64_t)w.Bp);
-        hipLaunchKernelGGL(transpose_rows_kernel, dim3((unsigned)ks_ceil_div(w.Mp, TR_TILE), (unsigned)ks_ceil_div(D, TR_TILE)),
-                           dim3(SM_NT), 0, st, W, (int64_t)D, active_idx, n_active, Mi, D, w.WAT, w.Mp);
         {
             typedef TileLogits T;
             const int tiles = (int)(ks_ceil_div(B, T::BM) * ks_ceil_div(M, T::BN));
@@ -515,14 +472,14 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
                            loss_per_sample);
         hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(SM_NT), 0, st, loss_per_sample, B, loss_mean);
         mark(3);
-        hipLaunchKernelGGL(dz_dual_kernel, dim3((unsigned)ks_ceil_div(w.Mp, TR_TILE), (unsigned)ks_ceil_div(w.Bp, TR_TILE)),
-                           dim3(SM_NT), 0, st, w.Z, w.Mp, n_active, Mi, B, w.Bp, target_pos, w.lse, g, w.dZ, w.dZT);
+        hipLaunchKernelGGL(dz_t_kernel, dim3((unsigned)ks_ceil_div(w.Mp, TR_TILE), (unsigned)ks_ceil_div(w.Bp, TR_TILE)),
+                           dim3(SM_NT), 0, st, w.Z, w.Mp, n_active, Mi, B, w.Bp, target_pos, w.lse, g, w.dZT);
         mark(4);
         {
             typedef TileDx T;
             const int tiles = (int)(ks_ceil_div(B, T::BM) * ks_ceil_div(D, T::BN));
-            hipLaunchKernelGGL(dx_partial_async_kernel<T>, dim3(tiles * w.S), dim3(T::NT), 0, st, w.dZ, w.Mp, w.WAT, n_active,
-                               B, D, Mi, w.S, w.part);
+            hipLaunchKernelGGL(dx_partial_async_kernel<T>, dim3(tiles * w.S), dim3(T::NT), 0, st, w.dZT, w.Bp, w.Mp, W,
+                               active_idx, n_active, B, D, Mi, w.S, w.part);
         }
         mark(5);
         hipLaunchKernelGGL(dx_reduce_kernel, dim3((unsigned)ks_ceil_div((int64_t)B * D / 4, SM_NT)), dim3(SM_NT), 0, st, w.part,
@@ -531,7 +488,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
         {
             typedef TileDw T;
             const int tiles = (int)(ks_ceil_div(M, T::BM) * ks_ceil_div(D, T::BN));
-            hipLaunchKernelGGL(dw_async_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, w.dZT, w.XT, w.Bp, n_active, D, Mi, w.Mp,
+            hipLaunchKernelGGL(dw_async_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, w.dZT, X, B, w.Bp, n_active, D, Mi, w.Mp,
                                scale, dW_active);
         }
         mark(7);
