@@ -12,6 +12,7 @@
 #define SEL_SEG (SEL_NT * SEL_PER) /* classes per block in the table passes */
 #define SEL_NONE 0x7fffffff
 #define SEL_LDS_BINS 2048
+#define SEL1_MAX_WORDS_HOST 12288 /* classes / 32 up to which the single-workgroup path is used */
 
 struct SelPlan {
     int r_star;    // classes with score < r_star are all kept
@@ -41,7 +42,8 @@ static SelWs sel_carve(void *ws, int64_t C, int K) {
     return w;
 }
 
-size_t ks_select_ws_bytes(int64_t C, int K) {
+size_t ks_select_ws_bytes(int64_t C, int B, int K) {
+    if (C <= (int64_t)SEL1_MAX_WORDS_HOST * 32) return ks_align_up((size_t)B * (K + 1) * sizeof(int32_t), 256);
     KsArena ar(nullptr);
     ar.take<int32_t>((size_t)C);
     ar.take<int32_t>((size_t)K + 1);
@@ -233,9 +235,174 @@ sel_finish_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict_
     if (t >= n && t < M) active_idx[t] = -1;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Whole selection in ONE workgroup when the class bitmap fits in LDS (C <= SEL1_MAX_WORDS * 32):
+// candidates are marked in an LDS bitmap (duplicates collapse in the atomic OR), the ascending list is the
+// bitmap read out in order, positions are prefix popcounts.  Only when more than M classes are marked
+// is the list-position order needed; then the bitmap is rebuilt position by position (r = 0, 1, ...)
+// until adding the classes first seen at position r would exceed M; of those, the lowest ids fill up.
+// ------------------------------------------------------------------------------------------------
+#define SEL1_NT 1024
+#define SEL1_MAX_WORDS SEL1_MAX_WORDS_HOST
+
+// Stage 1 (many workgroups, so that the scattered reads of the neighbour lists are spread over the chip):
+// validated candidates, list-position-major: cand[r * B + i] = class at position r of sample i's list
+// (r = 0: the label itself), or -1 for an empty or invalid entry.
+__global__ void __launch_bounds__(SEL_NT)
+sel_fetch_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict__ graph, int64_t C, int B, int K,
+                 int32_t *__restrict__ cand, int32_t *dev_status) {
+    const int64_t t = (int64_t)blockIdx.x * SEL_NT + threadIdx.x;
+    if (t >= (int64_t)B * (K + 1)) return;
+    const int i = (int)(t / (K + 1)), r = (int)(t % (K + 1));
+    const int32_t y = labels[i];
+    int32_t c = -1;
+    if (y < 0 || y >= C) {
+        if (r == 0) ks_flag(dev_status, KS_DEV_BAD_LABEL);
+    } else if (r == 0) {
+        c = y;
+    } else {
+        c = graph[(int64_t)y * K + (r - 1)];
+        if (c < -1 || c >= C) {
+            ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
+            c = -1;
+        }
+    }
+    cand[(int64_t)r * B + i] = c;
+}
+
+// exclusive prefix over the words of a bitmap: pre[w] = number of set bits in words < w; returns the total
+__device__ __forceinline__ int sel1_prefix(const uint32_t *bm, int nw, int *pre, int *sh) {
+    const int per = (nw + SEL1_NT - 1) / SEL1_NT;
+    const int w0 = threadIdx.x * per;
+    int local = 0;
+    for (int w = w0; w < w0 + per && w < nw; ++w) local += __popc(bm[w]);
+    int total;
+    int run = ks_block_escan<SEL1_NT>(local, sh, &total);
+    for (int w = w0; w < w0 + per && w < nw; ++w) {
+        pre[w] = run;
+        run += __popc(bm[w]);
+    }
+    __syncthreads();
+    return total;
+}
+
+__global__ void __launch_bounds__(SEL1_NT)
+sel_single_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict__ cand, int64_t C, int B, int K, int M,
+                  int32_t *__restrict__ active_idx, int32_t *__restrict__ n_active, int32_t *__restrict__ target_pos) {
+    __shared__ uint32_t bm[SEL1_MAX_WORDS];
+    __shared__ uint32_t eq[SEL1_MAX_WORDS];
+    __shared__ int pre[SEL1_MAX_WORDS];
+    __shared__ int sh[SEL1_NT / 64 + 1];
+    __shared__ int s_new;
+    const int nw = (int)((C + 31) >> 5);
+    const int tid = threadIdx.x;
+    for (int w = tid; w < nw; w += SEL1_NT) bm[w] = 0u;
+    __syncthreads();
+    // optimistic pass: every candidate, whatever its list position (eight loads in flight per thread)
+    const int64_t n_cand = (int64_t)B * (K + 1);
+    for (int64_t t0 = 0; t0 < n_cand; t0 += (int64_t)SEL1_NT * 8) {
+        int32_t c[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t t = t0 + (int64_t)e * SEL1_NT + tid;
+            c[e] = t < n_cand ? cand[t] : -1;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (c[e] >= 0) atomicOr(&bm[c[e] >> 5], 1u << (c[e] & 31));
+    }
+    __syncthreads();
+    int total = sel1_prefix(bm, nw, pre, sh);
+    if (total > M) {
+        // the cut bites: rebuild the bitmap in list-position order
+        for (int w = tid; w < nw; w += SEL1_NT) { bm[w] = 0u; eq[w] = 0u; }
+        __syncthreads();
+        int cum = 0, quota = 0;
+        for (int r = 0; r <= K; ++r) {
+            if (tid == 0) s_new = 0;
+            __syncthreads();
+            int local_new = 0;
+            for (int i = tid; i < B; i += SEL1_NT) {
+                const int c = cand[(int64_t)r * B + i];
+                if (c < 0) continue;
+                const uint32_t bit = 1u << (c & 31);
+                if (bm[c >> 5] & bit) continue; // already in with a better position
+                if (!(atomicOr(&eq[c >> 5], bit) & bit)) ++local_new;
+            }
+            local_new = ks_wave_sum_i(local_new);
+            if ((tid & 63) == 0 && local_new) atomicAdd(&s_new, local_new);
+            __syncthreads();
+            const int total_new = s_new;
+            if (cum + total_new > M) { // classes first seen at position r do not all fit: r is the cut score
+                quota = M - cum;
+                break;
+            }
+            for (int i = tid; i < B; i += SEL1_NT) { // commit position r
+                const int c = cand[(int64_t)r * B + i];
+                if (c < 0) continue;
+                const uint32_t bit = 1u << (c & 31);
+                if (eq[c >> 5] & bit) {
+                    atomicOr(&bm[c >> 5], bit);
+                    atomicAnd(&eq[c >> 5], ~bit);
+                }
+            }
+            cum += total_new;
+            __syncthreads();
+        }
+        // eq holds the classes whose best position is the cut score; the `quota` lowest ids of them are kept
+        sel1_prefix(eq, nw, pre, sh);
+        const int per = (nw + SEL1_NT - 1) / SEL1_NT;
+        for (int w = tid * per; w < tid * per + per && w < nw; ++w) {
+            uint32_t e = eq[w], keep = 0u;
+            int left = quota - pre[w];
+            while (left > 0 && e) {
+                keep |= e & (0u - e);
+                e &= e - 1;
+                --left;
+            }
+            bm[w] |= keep;
+        }
+        __syncthreads();
+        total = sel1_prefix(bm, nw, pre, sh);
+    }
+    // read the bitmap out in ascending order
+    {
+        const int per = (nw + SEL1_NT - 1) / SEL1_NT;
+        for (int w = tid * per; w < tid * per + per && w < nw; ++w) {
+            uint32_t e = bm[w];
+            int pos = pre[w];
+            while (e) {
+                const int b = __ffs(e) - 1;
+                if (pos < M) active_idx[pos] = w * 32 + b; // pos < M always holds; the test keeps the store in bounds
+                ++pos;
+                e &= e - 1;
+            }
+        }
+    }
+    const int n = total < M ? total : M;
+    for (int a = n + tid; a < M; a += SEL1_NT) active_idx[a] = -1;
+    for (int i = tid; i < B; i += SEL1_NT) {
+        const int32_t y = labels[i];
+        int p = 0;
+        if (y >= 0 && y < C) p = pre[y >> 5] + __popc(bm[y >> 5] & ((1u << (y & 31)) - 1u));
+        target_pos[i] = (p >= 0 && p < n) ? p : 0;
+    }
+    if (tid == 0) *n_active = n;
+}
+
 int ks_select_launch(const int32_t *labels, const int32_t *graph, int64_t C, int B, int K, int M,
                      int32_t *active_idx, int32_t *n_active, int32_t *target_pos, void *ws,
                      int32_t *dev_status, hipStream_t st) {
+    if (C <= (int64_t)SEL1_MAX_WORDS * 32) {
+        int32_t *cand = (int32_t *)ws;
+        const int64_t n_cand = (int64_t)B * (K + 1);
+        hipLaunchKernelGGL(sel_fetch_kernel, dim3((unsigned)ks_ceil_div(n_cand, SEL_NT)), dim3(SEL_NT), 0, st, labels, graph, C, B,
+                           K, cand, dev_status);
+        hipLaunchKernelGGL(sel_single_kernel, dim3(1), dim3(SEL1_NT), 0, st, labels, cand, C, B, K, M, active_idx, n_active,
+                           target_pos);
+        KS_LAUNCH_CHECK();
+        return KS_OK;
+    }
     SelWs w = sel_carve(ws, C, K);
     int fill_blocks = (int)(ks_ceil_div(C, SEL_NT) < 2048 ? ks_ceil_div(C, SEL_NT) : 2048);
     hipLaunchKernelGGL(sel_init_kernel, dim3(fill_blocks), dim3(SEL_NT), 0, st, w.score, C, w.hist, K);
@@ -256,9 +423,9 @@ int ks_select_launch(const int32_t *labels, const int32_t *graph, int64_t C, int
 }
 
 extern "C" size_t knn_select_workspace(int64_t C, int B, int K, int M) {
-    (void)B; (void)M;
+    (void)M;
     if (C < 1 || K < 0) return 0;
-    return ks_select_ws_bytes(C, K);
+    return ks_select_ws_bytes(C, B, K);
 }
 
 extern "C" int knn_select_active(const int32_t *labels, const int32_t *graph, int64_t C, int B, int K, int M,
@@ -268,7 +435,7 @@ extern "C" int knn_select_active(const int32_t *labels, const int32_t *graph, in
     if (C < 1 || C >= (int64_t)1 << 31 || B < 1 || K < 0 || M < 1) return KS_INVALID_ARG;
     if (K > 0 && !graph) return KS_INVALID_ARG;
     if (B > M || (int64_t)K + 1 > M) return KS_INVALID_ARG;
-    if (ws_bytes < ks_select_ws_bytes(C, K)) return KS_WORKSPACE_TOO_SMALL;
+    if (ws_bytes < ks_select_ws_bytes(C, B, K)) return KS_WORKSPACE_TOO_SMALL;
     return ks_select_launch(labels, graph, C, B, K, M, active_idx, n_active, target_pos, ws, dev_status,
                             (hipStream_t)stream);
 }

@@ -99,6 +99,9 @@ row_stats_kernel(const float *__restrict__ Z, int64_t ldz, const int32_t *__rest
     }
 }
 
+// mean of the per-sample losses: one workgroup, fixed summation order.  (Kept as its own tiny launch: folding
+// it into the kernel above needs a device-scope fence per workgroup, which costs far more on this chip,
+// whose eight L2 caches are only coherent through memory.)
 __global__ void __launch_bounds__(SM_NT) loss_mean_kernel(const float *__restrict__ loss_i, int B, float *loss_mean) {
     __shared__ float sh[SM_NT];
     float s = 0.f;
@@ -441,7 +444,7 @@ static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool w
     w.Mp = sm_mp(M);
     w.Bp = (int)ks_align_up((size_t)B, KS_BP_ALIGN);
     w.S = sm_splits(B, D, w.fast);
-    w.select = with_select ? (void *)ar.take<char>(ks_select_ws_bytes(C, K)) : nullptr;
+    w.select = with_select ? (void *)ar.take<char>(ks_select_ws_bytes(C, B, K)) : nullptr;
     w.Z = ar.take<float>((size_t)B * w.Mp);
     w.lse = ar.take<float>((size_t)B);
     w.part = ar.take<float>((size_t)w.S * B * D);

@@ -66,6 +66,9 @@ def run_and_compare(ks, orc, W, X, y, G, C, M, scale=30.0, grad_scale=1.0, tag="
     (200, 5, 200, 200, 4, 0.0),         # B == M
     (100_000, 16, 256, 4_096, 0, 0.0),  # the "small" configuration: cut bites
     (390_625, 32, 1_024, 32_768, 0, 0.0),
+    (390_625, 32, 1_024, 20_000, 1, 0.1),   # single-workgroup path, cut bites
+    (393_217, 16, 512, 4_000, 2, 0.0),      # just above the single-workgroup limit: table path, cut bites
+    (1_000_000, 64, 2_048, 131_072, 0, 0.0),
     (5000, 2500, 4, 3000, 5, 0.0),      # more list positions than the LDS histogram holds
 ])
 def test_select_matches_oracle(ks, orc, C, K, B, M, seed, empty):
