@@ -99,9 +99,9 @@ def phase_model(cfg, A):
     gemm = 2.0 * B * A * D
     return {
         "select": dict(bound="latency"),
-        "logits_gemm": dict(bound="mfma", flops=gemm),
-        "row_stats": dict(bound="hbm", bytes=4.0 * B * A),
-        "logit_grad": dict(bound="hbm", bytes=(4.0 + 2.0) * B * A),
+        "logits_gemm": dict(bound="mfma", flops=gemm),      # logits + per-tile softmax statistics, nothing stored
+        "row_stats": dict(bound="latency"),                  # merge of the per-tile statistics, loss mean
+        "logit_grad": dict(bound="mfma", flops=gemm),       # logits again -> logit gradient (stored transposed)
         "dx_gemm": dict(bound="mfma", flops=gemm),
         "dx_reduce": dict(bound="latency"),
         "dw_gemm": dict(bound="mfma", flops=gemm),

@@ -14,10 +14,10 @@
 #include "ks_select.h"
 
 typedef KsTile<128, 128, 64, 2, 2> TileG;      // generic path (any D % 32 == 0)
-typedef KsATile<256, 256, 2, 4, 2> TileLogits; // fast path (D % 64 == 0): asynchronous engine
+typedef KsATile<256, 256, 2, 4, 2> TileSm;     // fast path (D % 64 == 0): tile = 256 classes x 256 samples
 typedef KsATile<128, 128, 2, 2, 2> TileDx;
 typedef KsATile<256, 256, 2, 4, 2> TileDw;
-#define KS_BP_ALIGN 128
+#define KS_BP_ALIGN 256
 
 #define SM_NT 256
 #define KS_MP_ALIGN 256
@@ -219,9 +219,9 @@ dw_kernel(const uint16_t *__restrict__ dZ, int64_t ldz, const uint16_t *__restri
 }
 
 // ================================================================================================
-// Fast path (D % 64 == 0).  All three contractions run on the asynchronous engine.  The logit gradient
-// is stored once, transposed (dZT[a][i]); it is the k-contiguous operand of the dW contraction and a
-// k-major operand of the dX contraction.  Weight rows (gathered through the index list) and X enter as
+// Fast path (D % 64 == 0).  All contractions run on the asynchronous engine and the logits are recomputed
+// instead of stored (see below).  The logit gradient is stored once, transposed (dZT[a][i]); it is the
+// k-contiguous operand of the dW contraction and a k-major operand of the dX contraction.  Weight rows (gathered through the index list) and X enter as
 // k-major operands where k is their row index, so no transposed copies of them are made.
 // ================================================================================================
 
@@ -244,79 +244,179 @@ __device__ __forceinline__ void sm_transpose8x8(const uint4 (&in)[8], uint4 (&ou
 #define TR_TILE 128
 #define TR_LD (TR_TILE + 8)
 
-// Z = scale * X . W[active]^T on the asynchronous engine
+// The logits are never stored on the fast path.  Two passes over the same tile product
+//     Zt[a][i] = scale * <W[active[a]], X[i]>            (classes = MFMA rows, samples = MFMA columns)
+// First pass: per-sample running max / sum of exponentials of each class tile, and the target logit.
+// Second pass (after the per-sample log-sum-exp is known): the same product again, turned into the logit
+// gradient in registers and stored transposed, dZT[a][i].  In this orientation a lane owns one sample
+// column of the accumulator tile, so the per-sample reductions are lane-local.
+
+// accumulator element (fm, r) of a lane: class row inside the wave's part of the tile
+__device__ __forceinline__ int sm_tile_row(int fm, int r, int lane) { return fm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
 template <class T>
-__global__ void __launch_bounds__(T::NT)
-logits_async_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W,
-                    const int32_t *__restrict__ active_idx, const int32_t *__restrict__ n_active_p, int B, int D, int M,
-                    float scale, float *__restrict__ Z, int64_t ldz) {
-    __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
-    const int n_active = sm_clamp_n(n_active_p, M);
-    const int tiles_m = (B + T::BM - 1) / T::BM;
-    const int n_tiles = tiles_m * ((n_active + T::BN - 1) / T::BN);
-    if ((int)blockIdx.x >= n_tiles) return;
-    const int t = ks_xcd_remap(blockIdx.x, n_tiles);
-    const int tm = t % tiles_m, tn = t / tiles_m;
+__device__ __forceinline__ void sm_logits_tile(const uint16_t *X, const uint16_t *W, const int32_t *active_idx, int n_active,
+                                               int B, int D, int tc, int ts, uint16_t *lds, f32x16_t (&acc)[T::FM][T::FN]) {
     KsARows<T::BM, T::NW> ar;
     KsARows<T::BN, T::NW> br;
-    ar.init(X, D, nullptr, tm * T::BM, B);
-    br.init(W, D, active_idx, tn * T::BN, n_active);
-    f32x16_t acc[T::FM][T::FN];
+    ar.init(W, D, active_idx, tc * T::BM, n_active);
+    br.init(X, D, nullptr, ts * T::BN, B);
     ks_a_clear<T>(acc);
     ks_a_mainloop<T>(ar, br, 0, D / 64, lds, acc);
-    ks_a_foreach<T>(acc, [&](int m, int n, float v) {
-        int i = tm * T::BM + m, a = tn * T::BN + n;
-        if (i < B && a < n_active) Z[(int64_t)i * ldz + a] = scale * v;
-    });
 }
 
-// dZT[a][i] = g (exp(Z[i][a] - lse_i) - [a == target_pos[i]]) as bf16, i.e. the logit gradient stored with
-// the sample index fast; 128 x 128 tile per workgroup, each thread an 8 x 8 block, transposed through
-// LDS.  Zero for a in [n_active, round_up(n_active, 256)) and for i in [B, Bp).
-__global__ void __launch_bounds__(SM_NT)
-dz_t_kernel(const float *__restrict__ Z, int64_t ldz, const int32_t *__restrict__ n_active_p, int M, int B, int Bp,
-            const int32_t *__restrict__ target_pos, const float *__restrict__ lse, float g, uint16_t *__restrict__ dZT) {
-    __shared__ __attribute__((aligned(16))) uint16_t tile[TR_TILE * TR_LD]; // [a][i]
-    const int n = sm_clamp_n(n_active_p, M);
-    const int n_pad = (n + KS_MP_ALIGN - 1) / KS_MP_ALIGN * KS_MP_ALIGN;
-    const int a0 = blockIdx.x * TR_TILE, i0 = blockIdx.y * TR_TILE;
-    if (a0 >= n_pad) return;
-    const int ab = threadIdx.x & 15, ib = threadIdx.x >> 4;
-    const int a = a0 + ab * 8;
-    uint4 v[8], t[8];
+template <class T>
+__global__ void __launch_bounds__(T::NT)
+sm_stats_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, const int32_t *__restrict__ active_idx,
+                const int32_t *__restrict__ n_active_p, const int32_t *__restrict__ target_pos, int B, int Bp, int D, int M,
+                float scale, float *__restrict__ pm, float *__restrict__ pl, float *__restrict__ zt) {
+    __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
+    const int n_active = sm_clamp_n(n_active_p, M);
+    const int tiles_s = (B + T::BN - 1) / T::BN;
+    const int n_tiles = tiles_s * ((n_active + T::BM - 1) / T::BM);
+    if ((int)blockIdx.x >= n_tiles) return;
+    const int t = ks_xcd_remap(blockIdx.x, n_tiles);
+    const int ts = t % tiles_s, tc = t / tiles_s;
+    f32x16_t acc[T::FM][T::FN];
+    sm_logits_tile<T>(X, W, active_idx, n_active, B, D, tc, ts, lds, acc); // ends with a barrier: LDS is free
+
+    // per (wave row, sample) partial statistics go through LDS: [WAVES_M][BN] pairs
+    float *s_m = (float *)lds, *s_l = s_m + T::WAVES_M * T::BN;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
+    const int c0 = tc * T::BM + wm * T::WM;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const int i = i0 + ib * 8 + k;
-        float d[8];
-        if (i < B && a < n) {
-            const float *z = Z + (int64_t)i * ldz + a;
-            const float ls = lse[i];
-            const int tp = target_pos[i];
-            float zz[8];
-            if (a + 8 <= n) {
-                float4 p = *(const float4 *)z, q = *(const float4 *)(z + 4);
-                zz[0] = p.x; zz[1] = p.y; zz[2] = p.z; zz[3] = p.w; zz[4] = q.x; zz[5] = q.y; zz[6] = q.z; zz[7] = q.w;
-            } else {
+    for (int fn = 0; fn < T::FN; ++fn) {
+        const int col = wn * T::WN + fn * 32 + (lane & 31);
+        const int i = ts * T::BN + col;
+        const int tp = (i < B) ? target_pos[i] : -1;
+        float m = -INFINITY;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) zz[e] = (a + e < n) ? z[e] : 0.f;
+        for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int c = c0 + sm_tile_row(fm, r, lane);
+                const float z = scale * acc[fm][fn][r];
+                if (c < n_active) m = fmaxf(m, z);
+                if (c == tp) zt[i] = z;
             }
+        float l = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) d[e] = (a + e < n) ? g * (__expf(zz[e] - ls) - (a + e == tp ? 1.f : 0.f)) : 0.f;
-        } else {
+        for (int fm = 0; fm < T::FM; ++fm)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) d[e] = 0.f;
+            for (int r = 0; r < 16; ++r) {
+                const int c = c0 + sm_tile_row(fm, r, lane);
+                if (c < n_active) l += __expf(scale * acc[fm][fn][r] - m);
+            }
+        // the two half-waves hold disjoint class rows of the same 32 samples
+        const float mo = __shfl_xor(m, 32, 64), lo = __shfl_xor(l, 32, 64);
+        const float mm = fmaxf(m, mo);
+        const float ll = (m == -INFINITY ? 0.f : l * __expf(m - mm)) + (mo == -INFINITY ? 0.f : lo * __expf(mo - mm));
+        if (lane < 32) {
+            s_m[wm * T::BN + col] = mm;
+            s_l[wm * T::BN + col] = ll;
         }
-        v[k] = make_uint4(ks_pack_bf2(d[0], d[1]), ks_pack_bf2(d[2], d[3]), ks_pack_bf2(d[4], d[5]), ks_pack_bf2(d[6], d[7]));
     }
-    sm_transpose8x8(v, t);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) *(uint4 *)(tile + (ab * 8 + e) * TR_LD + ib * 8) = t[e];
     __syncthreads();
+    for (int col = threadIdx.x; col < T::BN; col += T::NT) {
+        const int i = ts * T::BN + col;
+        if (i >= B) continue;
+        float mm = s_m[col], ll = s_l[col];
 #pragma unroll
-    for (int pass = 0; pass < 8; ++pass) {
-        const int aa = pass * 16 + (threadIdx.x >> 4), chunk = threadIdx.x & 15;
-        if (i0 + chunk * 8 < Bp)
-            *(uint4 *)(dZT + (int64_t)(a0 + aa) * Bp + i0 + chunk * 8) = *(const uint4 *)(tile + aa * TR_LD + chunk * 8);
+        for (int w = 1; w < T::WAVES_M; ++w) { // fixed order
+            const float m2 = s_m[w * T::BN + col], l2 = s_l[w * T::BN + col];
+            const float mx = fmaxf(mm, m2);
+            ll = (mm == -INFINITY ? 0.f : ll * __expf(mm - mx)) + (m2 == -INFINITY ? 0.f : l2 * __expf(m2 - mx));
+            mm = mx;
+        }
+        pm[(int64_t)tc * Bp + i] = mm;
+        pl[(int64_t)tc * Bp + i] = ll;
+    }
+}
+
+// one wavefront per sample: merge the per-tile (max, sum) pairs in tile order -> lse_i, loss_i
+__global__ void __launch_bounds__(SM_NT)
+sm_combine_kernel(const float *__restrict__ pm, const float *__restrict__ pl, const float *__restrict__ zt,
+                  const int32_t *__restrict__ n_active_p, int M, int tile_rows, int B, int Bp, float *__restrict__ lse_out,
+                  float *__restrict__ loss_i) {
+    const int i = blockIdx.x * (SM_NT / 64) + (threadIdx.x >> 6);
+    if (i >= B) return;
+    const int lane = threadIdx.x & 63;
+    const int n = sm_clamp_n(n_active_p, M);
+    const int nt = (n + tile_rows - 1) / tile_rows;
+    float m = -INFINITY, l = 0.f;
+    for (int t = lane; t < nt; t += 64) {
+        const float tm = pm[(int64_t)t * Bp + i], tl = pl[(int64_t)t * Bp + i];
+        if (tm > m) { l *= __expf(m - tm); m = tm; }
+        if (tm != -INFINITY) l += tl * __expf(tm - m);
+    }
+    const float wm = ks_wave_max(m);
+    const float wl = ks_wave_sum(m == -INFINITY ? 0.f : l * __expf(m - wm));
+    if (lane == 0) {
+        const float lse = wm + __logf(wl);
+        lse_out[i] = lse;
+        loss_i[i] = lse - zt[i];
+    }
+}
+
+// second pass: logit gradient, stored transposed.  dZT[a][i] = g (exp(Zt[a][i] - lse_i) - [a == target_pos[i]]),
+// zero for a >= n_active (up to the end of the class tile) and for i >= B (up to Bp).
+template <class T>
+__global__ void __launch_bounds__(T::NT)
+sm_grad_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, const int32_t *__restrict__ active_idx,
+               const int32_t *__restrict__ n_active_p, const int32_t *__restrict__ target_pos, const float *__restrict__ lse,
+               int B, int Bp, int D, int M, float scale, float g, uint16_t *__restrict__ dZT) {
+    constexpr int STAGE_LD = T::BN + 8;
+    constexpr int STAGE_ELEMS = T::BM * STAGE_LD;
+    constexpr int LDS_N = STAGE_ELEMS > T::LDS_ELEMS ? STAGE_ELEMS : T::LDS_ELEMS;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[LDS_N];
+    const int n_active = sm_clamp_n(n_active_p, M);
+    const int tiles_s = (B + T::BN - 1) / T::BN;
+    const int n_tiles = tiles_s * ((n_active + T::BM - 1) / T::BM);
+    if ((int)blockIdx.x >= n_tiles) return;
+    const int t = ks_xcd_remap(blockIdx.x, n_tiles);
+    const int ts = t % tiles_s, tc = t / tiles_s;
+    f32x16_t acc[T::FM][T::FN];
+    sm_logits_tile<T>(X, W, active_idx, n_active, B, D, tc, ts, lds, acc); // ends with a barrier: LDS is free
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / T::WAVES_N, wn = wave % T::WAVES_N;
+    const int r0 = wm * T::WM;         // first class row of this wave inside the tile
+    const int c0 = tc * T::BM + r0;
+    const bool odd = lane & 1;
+#pragma unroll
+    for (int fn = 0; fn < T::FN; ++fn) {
+        const int col = wn * T::WN + fn * 32 + (lane & 31); // sample column inside the tile
+        const int i = ts * T::BN + col;
+        const bool i_ok = i < B;
+        const float ls = i_ok ? lse[i] : 0.f;
+        const int tp = i_ok ? target_pos[i] : -1;
+#pragma unroll
+        for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                float d[2];
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int c = c0 + sm_tile_row(fm, r + e, lane);
+                    d[e] = (i_ok && c < n_active) ? g * (__expf(scale * acc[fm][fn][r + e] - ls) - (c == tp ? 1.f : 0.f)) : 0.f;
+                }
+                // neighbouring lanes (samples 2j, 2j+1) trade so that each holds two adjacent samples of one class
+                // row: the even lane ends up with row r, the odd lane with row r+1
+                const float send = odd ? d[0] : d[1];
+                const float recv =
+                    __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0xB1, 0xF, 0xF, true));
+                const uint32_t packed = odd ? ks_pack_bf2(recv, d[1]) : ks_pack_bf2(d[0], recv);
+                const int row = r0 + sm_tile_row(fm, r + (odd ? 1 : 0), lane);
+                *(uint32_t *)(lds + row * STAGE_LD + (col & ~1)) = packed;
+            }
+    }
+    __syncthreads();
+    // coalesced store of the staged tile: 16 bytes per lane along the sample index
+    constexpr int CHUNKS = T::BM * (T::BN / 8);
+    for (int q = threadIdx.x; q < CHUNKS; q += T::NT) {
+        const int row = q / (T::BN / 8), ch = q % (T::BN / 8);
+        *(uint4 *)(dZT + (int64_t)(tc * T::BM + row) * Bp + ts * T::BN + ch * 8) = *(const uint4 *)(lds + row * STAGE_LD + ch * 8);
     }
 }
 
@@ -422,6 +522,7 @@ struct SmWs {
     float *lse;
     float *part;
     uint16_t *dZT; // fast path: the logit gradient is kept transposed only
+    float *pm, *pl, *zt; // fast path: per class-tile softmax statistics, target logits
     int S;
     int64_t Mp;
     int Bp;
@@ -445,12 +546,21 @@ static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool w
     w.Bp = (int)ks_align_up((size_t)B, KS_BP_ALIGN);
     w.S = sm_splits(B, D, w.fast);
     w.select = with_select ? (void *)ar.take<char>(ks_select_ws_bytes(C, B, K)) : nullptr;
-    w.Z = ar.take<float>((size_t)B * w.Mp);
     w.lse = ar.take<float>((size_t)B);
     w.part = ar.take<float>((size_t)w.S * B * D);
+    w.Z = nullptr;
     w.dZ = w.dZT = nullptr;
-    if (w.fast) w.dZT = ar.take<uint16_t>((size_t)w.Mp * w.Bp);
-    else w.dZ = ar.take<uint16_t>((size_t)B * w.Mp);
+    w.pm = w.pl = w.zt = nullptr;
+    if (w.fast) {
+        w.dZT = ar.take<uint16_t>((size_t)w.Mp * w.Bp);
+        const size_t nt = (size_t)(w.Mp / TileSm::BM);
+        w.pm = ar.take<float>(nt * w.Bp);
+        w.pl = ar.take<float>(nt * w.Bp);
+        w.zt = ar.take<float>((size_t)w.Bp);
+    } else {
+        w.Z = ar.take<float>((size_t)B * w.Mp);
+        w.dZ = ar.take<uint16_t>((size_t)B * w.Mp);
+    }
     if (total) *total = ar.off;
     return w;
 }
@@ -465,18 +575,18 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
     const float g = grad_scale / (float)B;
     if (w.fast) {
         {
-            typedef TileLogits T;
-            const int tiles = (int)(ks_ceil_div(B, T::BM) * ks_ceil_div(M, T::BN));
-            hipLaunchKernelGGL(logits_async_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, X, W, active_idx, n_active, B, D, Mi,
-                               scale, w.Z, w.Mp);
+            typedef TileSm T;
+            const int tiles = (int)(ks_ceil_div(B, T::BN) * ks_ceil_div(M, T::BM));
+            hipLaunchKernelGGL(sm_stats_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, X, W, active_idx, n_active, target_pos, B,
+                               w.Bp, D, Mi, scale, w.pm, w.pl, w.zt);
+            mark(2);
+            hipLaunchKernelGGL(sm_combine_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT / 64)), dim3(SM_NT), 0, st, w.pm, w.pl,
+                               w.zt, n_active, Mi, T::BM, B, w.Bp, w.lse, loss_per_sample);
+            hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(SM_NT), 0, st, loss_per_sample, B, loss_mean);
+            mark(3);
+            hipLaunchKernelGGL(sm_grad_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, X, W, active_idx, n_active, target_pos, w.lse,
+                               B, w.Bp, D, Mi, scale, g, w.dZT);
         }
-        mark(2);
-        hipLaunchKernelGGL(row_stats_kernel, dim3(B), dim3(SM_NT), 0, st, w.Z, w.Mp, n_active, Mi, target_pos, w.lse,
-                           loss_per_sample);
-        hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(SM_NT), 0, st, loss_per_sample, B, loss_mean);
-        mark(3);
-        hipLaunchKernelGGL(dz_t_kernel, dim3((unsigned)ks_ceil_div(w.Mp, TR_TILE), (unsigned)ks_ceil_div(w.Bp, TR_TILE)),
-                           dim3(SM_NT), 0, st, w.Z, w.Mp, n_active, Mi, B, w.Bp, target_pos, w.lse, g, w.dZT);
         mark(4);
         {
             typedef TileDx T;
