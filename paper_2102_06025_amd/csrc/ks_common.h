@@ -44,7 +44,14 @@ __device__ __forceinline__ uint32_t ks_f2bf(float f) {
     u += 0x7FFFu + ((u >> 16) & 1u);
     return u >> 16;
 }
-__device__ __forceinline__ uint32_t ks_pack_bf2(float lo, float hi) { return ks_f2bf(lo) | (ks_f2bf(hi) << 16); }
+// two fp32 -> packed bf16 pair (lo in bits 0-15), round to nearest even: one v_cvt_pk_bf16_f32 on gfx950
+__device__ __forceinline__ uint32_t ks_pack_bf2(float lo, float hi) {
+    typedef __bf16 ks_bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float ks_f32x2 __attribute__((ext_vector_type(2)));
+    ks_f32x2 v = {lo, hi};
+    ks_bf16x2 b = __builtin_convertvector(v, ks_bf16x2);
+    return *(uint32_t *)&b;
+}
 __device__ __forceinline__ float ks_bf2f(uint32_t b) { return __uint_as_float(b << 16); }
 
 __device__ __forceinline__ float ks_wave_max(float v) {

@@ -11,6 +11,7 @@
 // Launch sizes are taken from the cap M; workgroups beyond the active count exit at once.
 #include "ks_gemm.h"
 #include "ks_gemm_async.h"
+#include "ks_gemm_soe.h"
 #include "ks_select.h"
 
 typedef KsTile<128, 128, 64, 2, 2> TileG;      // generic path (any D % 32 == 0)
@@ -18,6 +19,7 @@ typedef KsATile<256, 256, 2, 4, 2> TileSm;     // fast path (D % 64 == 0): tile 
 typedef KsATile<128, 128, 2, 2, 2> TileDx;
 typedef KsATile<256, 256, 2, 4, 2> TileDw;
 #define KS_BP_ALIGN 256
+#define SM_SOE_GRID 256 /* workgroups of the stationary-operand softmax passes (one per compute unit) */
 
 #define SM_NT 256
 #define KS_MP_ALIGN 256
@@ -420,6 +422,232 @@ sm_grad_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, c
     }
 }
 
+// ================================================================================================
+// Stationary-operand versions of the two softmax passes (D = 128, 256 or 512): a workgroup keeps the MFMA
+// fragments of 256 samples in registers and streams its share ("slab") of the active classes past them.
+// The active classes are cut into G / tiles_s equal slabs (multiples of 32 rows), so the chip is loaded
+// evenly whatever the active count; per-sample softmax statistics are carried in registers along the slab.
+// ================================================================================================
+#define SOE_STAGES 4
+
+// rows per slab for n64 = round_up(n_active, 64) rows and `slabs` slabs
+__host__ __device__ __forceinline__ int sm_slab_rows(int n64, int slabs) {
+    int h = (n64 + slabs - 1) / slabs;
+    h = (h + 31) & ~31;
+    return h < 32 ? 32 : h;
+}
+
+template <int KT>
+__global__ void __launch_bounds__(256)
+sm_stats_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, const int32_t *__restrict__ active_idx,
+                    const int32_t *__restrict__ n_active_p, const int32_t *__restrict__ target_pos, int B, int Bp, int D, int M,
+                    int tiles_s, float scale, float *__restrict__ pm, float *__restrict__ pl, float *__restrict__ zt) {
+    typedef KsSoe<KT, 96, SOE_STAGES, 2> CFG;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
+    const int n = sm_clamp_n(n_active_p, M);
+    const int n64 = (n + 63) & ~63;
+    const int slabs = gridDim.x / tiles_s;
+    const int h = sm_slab_rows(n64, slabs);
+    const int id = ks_xcd_remap(blockIdx.x, gridDim.x);
+    const int ts = id % tiles_s, slab = id / tiles_s;
+    const int s0 = slab * h, s1 = (s0 + h < n64) ? s0 + h : n64;
+    if (slab >= slabs || s0 >= s1) return;
+    const int lane = threadIdx.x & 63;
+    const int lim = n < s1 ? n : s1; // rows of this slab that are real classes
+    int i[2], tp[2];
+    float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f};
+#pragma unroll
+    for (int fn = 0; fn < 2; ++fn) {
+        i[fn] = ts * CFG::RES + ks_soe_col(fn);
+        tp[fn] = (i[fn] < B) ? target_pos[i[fn]] : -1;
+    }
+    // scale > 0 (checked by the host): statistics are carried on the raw products, m = max of acc,
+    // l = sum exp(scale * (acc - m)) = sum exp2(fma(acc, k1, -k1 * m)); one fused multiply-add per element
+    const float k1 = scale * 1.4426950408889634f;
+    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM][2]) {
+        (void)rows_here;
+        // the target logit of a sample whose label sits in this chunk (rare: a scan over this lane's rows)
+#pragma unroll
+        for (int fn = 0; fn < 2; ++fn) {
+            if (tp[fn] >= c0 && tp[fn] < c0 + CFG::CH && tp[fn] < lim) {
+#pragma unroll
+                for (int fm = 0; fm < CFG::FM; ++fm)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (c0 + ks_soe_row(fm, r, lane) == tp[fn]) zt[i[fn]] = scale * acc[fm][fn][r];
+            }
+        }
+        if (c0 + CFG::CH <= lim) { // every row of the chunk is a real class: no masks
+#pragma unroll
+            for (int fn = 0; fn < 2; ++fn) {
+                float cmax = acc[0][fn][0];
+#pragma unroll
+                for (int fm = 0; fm < CFG::FM; ++fm)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) cmax = fmaxf(cmax, acc[fm][fn][r]);
+                const float mn = fmaxf(m[fn], cmax);
+                const float off = -k1 * mn;
+                float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f; // four chains: the exponentials do not wait on one sum
+#pragma unroll
+                for (int fm = 0; fm < CFG::FM; ++fm)
+#pragma unroll
+                    for (int r = 0; r < 16; r += 4) {
+                        s0 += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r], k1, off));
+                        s1 += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r + 1], k1, off));
+                        s2 += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r + 2], k1, off));
+                        s3 += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r + 3], k1, off));
+                    }
+                l[fn] = l[fn] * __builtin_amdgcn_exp2f(k1 * (m[fn] - mn)) + ((s0 + s1) + (s2 + s3)); // m = -inf, l = 0 at the start
+                m[fn] = mn;
+            }
+        } else {
+#pragma unroll
+            for (int fn = 0; fn < 2; ++fn) {
+                float cmax = -INFINITY;
+#pragma unroll
+                for (int fm = 0; fm < CFG::FM; ++fm)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (c0 + ks_soe_row(fm, r, lane) < lim) cmax = fmaxf(cmax, acc[fm][fn][r]);
+                if (cmax == -INFINITY) continue; // no real class among this lane's rows of the chunk
+                const float mn = fmaxf(m[fn], cmax);
+                const float off = -k1 * mn;
+                float sum = 0.f;
+#pragma unroll
+                for (int fm = 0; fm < CFG::FM; ++fm)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (c0 + ks_soe_row(fm, r, lane) < lim) sum += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r], k1, off));
+                l[fn] = l[fn] * __builtin_amdgcn_exp2f(k1 * (m[fn] - mn)) + sum;
+                m[fn] = mn;
+            }
+        }
+    };
+    ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi);
+#pragma unroll
+    for (int fn = 0; fn < 2; ++fn) {
+        // the two half-waves hold disjoint class rows of the same 32 samples
+        const float mz = scale * m[fn]; // back to logit units
+        const float mo = __shfl_xor(mz, 32, 64), lo = __shfl_xor(l[fn], 32, 64);
+        const float mm = fmaxf(mz, mo);
+        const float ll = (mz == -INFINITY ? 0.f : l[fn] * __expf(mz - mm)) + (mo == -INFINITY ? 0.f : lo * __expf(mo - mm));
+        if (lane < 32 && i[fn] < B) {
+            pm[(int64_t)slab * Bp + i[fn]] = mm;
+            pl[(int64_t)slab * Bp + i[fn]] = ll;
+        }
+    }
+}
+
+template <int KT>
+__global__ void __launch_bounds__(256)
+sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, const int32_t *__restrict__ active_idx,
+                   const int32_t *__restrict__ n_active_p, const int32_t *__restrict__ target_pos,
+                   const float *__restrict__ lse, int B, int Bp, int D, int M, int tiles_s, float scale, float g,
+                   uint16_t *__restrict__ dZT) {
+    typedef KsSoe<KT, 96, SOE_STAGES, 2> CFG;
+    constexpr int STAGE_LD = CFG::RES + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
+    __shared__ __attribute__((aligned(16))) uint16_t stage[CFG::CH * STAGE_LD];
+    const int n = sm_clamp_n(n_active_p, M);
+    const int n64 = (n + 63) & ~63;
+    const int slabs = gridDim.x / tiles_s;
+    const int h = sm_slab_rows(n64, slabs);
+    const int id = ks_xcd_remap(blockIdx.x, gridDim.x);
+    const int ts = id % tiles_s, slab = id / tiles_s;
+    const int s0 = slab * h, s1 = (s0 + h < n64) ? s0 + h : n64;
+    if (slab >= slabs || s0 >= s1) return;
+    const int lane = threadIdx.x & 63;
+    const bool odd = lane & 1;
+    int col[2], tp[2];
+    float ls[2];
+    bool ok[2];
+#pragma unroll
+    for (int fn = 0; fn < 2; ++fn) {
+        col[fn] = ks_soe_col(fn);
+        const int i = ts * CFG::RES + col[fn];
+        ok[fn] = i < B;
+        ls[fn] = ok[fn] ? lse[i] : 0.f;
+        tp[fn] = ok[fn] ? target_pos[i] : -1;
+    }
+    // scale > 0 and g > 0 (checked by the host): g * exp(scale * acc - lse) = exp2(fma(acc, k1, k2)) with
+    // k2 = log2(g) - lse * log2(e): one fused multiply-add and one exponential per element
+    const float k1 = scale * 1.4426950408889634f;
+    float k2[2];
+#pragma unroll
+    for (int fn = 0; fn < 2; ++fn) k2[fn] = __log2f(g) - ls[fn] * 1.4426950408889634f;
+    const bool samples_ok = (ts + 1) * CFG::RES <= B;
+    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM][2]) {
+        const bool plain = samples_ok && c0 + CFG::CH <= n; // no row or column of this chunk needs masking
+#pragma unroll
+        for (int fn = 0; fn < 2; ++fn) {
+            // does any sample of this wavefront have its label inside the chunk?  (about one chunk in three)
+            const bool mine = tp[fn] >= c0 && tp[fn] < c0 + CFG::CH;
+            const bool any_target = __builtin_amdgcn_ballot_w64(mine) != 0;
+#pragma unroll
+            for (int fm = 0; fm < CFG::FM; ++fm)
+#pragma unroll
+                for (int r = 0; r < 16; r += 2) {
+                    float d[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) d[e] = __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r + e], k1, k2[fn]));
+                    if (any_target) {
+#pragma unroll
+                        for (int e = 0; e < 2; ++e)
+                            if (c0 + ks_soe_row(fm, r + e, lane) == tp[fn]) d[e] -= g;
+                    }
+                    if (!plain) {
+#pragma unroll
+                        for (int e = 0; e < 2; ++e)
+                            if (!ok[fn] || c0 + ks_soe_row(fm, r + e, lane) >= n) d[e] = 0.f;
+                    }
+                    // neighbouring lanes (samples 2j, 2j+1) trade so that each holds two adjacent samples of one
+                    // class row: the even lane ends up with row r, the odd lane with row r+1
+                    const float send = odd ? d[0] : d[1];
+                    const float recv =
+                        __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0xB1, 0xF, 0xF, true));
+                    const uint32_t packed = odd ? ks_pack_bf2(recv, d[1]) : ks_pack_bf2(d[0], recv);
+                    const int row = ks_soe_row(fm, r + (odd ? 1 : 0), lane);
+                    *(uint32_t *)(stage + row * STAGE_LD + (col[fn] & ~1)) = packed;
+                }
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F); // LDS writes done (lgkmcnt 0); loads in flight are left alone
+        ks_barrier_nofence();
+        const int chunks = rows_here * (CFG::RES / 8);
+        for (int q = threadIdx.x; q < chunks; q += 256) {
+            const int row = q / (CFG::RES / 8), ch = q % (CFG::RES / 8);
+            *(uint4 *)(dZT + (int64_t)(c0 + row) * Bp + ts * CFG::RES + ch * 8) = *(const uint4 *)(stage + row * STAGE_LD + ch * 8);
+        }
+    };
+    ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi);
+}
+
+// one wavefront per sample: merge the per-slab (max, sum) pairs in slab order -> lse_i, loss_i
+__global__ void __launch_bounds__(SM_NT)
+sm_combine_soe_kernel(const float *__restrict__ pm, const float *__restrict__ pl, const float *__restrict__ zt,
+                      const int32_t *__restrict__ n_active_p, int M, int slabs, int B, int Bp, float *__restrict__ lse_out,
+                      float *__restrict__ loss_i) {
+    const int i = blockIdx.x * (SM_NT / 64) + (threadIdx.x >> 6);
+    if (i >= B) return;
+    const int lane = threadIdx.x & 63;
+    const int n = sm_clamp_n(n_active_p, M);
+    const int n64 = (n + 63) & ~63;
+    const int h = sm_slab_rows(n64, slabs);
+    const int nt = (n64 + h - 1) / h;
+    float m = -INFINITY, l = 0.f;
+    for (int t = lane; t < nt; t += 64) {
+        const float tm = pm[(int64_t)t * Bp + i], tl = pl[(int64_t)t * Bp + i];
+        if (tm > m) { l *= __expf(m - tm); m = tm; }
+        if (tm != -INFINITY) l += tl * __expf(tm - m);
+    }
+    const float wm = ks_wave_max(m);
+    const float wl = ks_wave_sum(m == -INFINITY ? 0.f : l * __expf(m - wm));
+    if (lane == 0) {
+        const float lse = wm + __logf(wl);
+        lse_out[i] = lse;
+        loss_i[i] = lse - zt[i];
+    }
+}
+
 // dX partials on the asynchronous engine: P[s][i][d] = sum_{a in share s} dZT[a][i] * W[active[a]][d].
 // Both operands are k-major (k = a): dZT as stored, the weight rows fetched through the index list.
 template <class T>
@@ -553,7 +781,8 @@ static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool w
     w.pm = w.pl = w.zt = nullptr;
     if (w.fast) {
         w.dZT = ar.take<uint16_t>((size_t)w.Mp * w.Bp);
-        const size_t nt = (size_t)(w.Mp / TileSm::BM);
+        size_t nt = (size_t)(w.Mp / TileSm::BM);
+        if (nt < (size_t)SM_SOE_GRID) nt = SM_SOE_GRID; // per-slab statistics of the stationary-operand kernels
         w.pm = ar.take<float>(nt * w.Bp);
         w.pl = ar.take<float>(nt * w.Bp);
         w.zt = ar.take<float>((size_t)w.Bp);
@@ -574,7 +803,26 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
     const int Mi = (int)M;
     const float g = grad_scale / (float)B;
     if (w.fast) {
-        {
+        const int tiles_s = (int)ks_ceil_div(B, 256);
+        if ((D == 128 || D == 256 || D == 512) && tiles_s <= SM_SOE_GRID && scale > 0.f && g > 0.f) {
+            const int grid = SM_SOE_GRID / tiles_s * tiles_s, slabs = grid / tiles_s;
+#define SM_SOE_LAUNCH(KT)                                                                                                 \
+    do {                                                                                                                  \
+        hipLaunchKernelGGL(sm_stats_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active, target_pos, \
+                           B, w.Bp, D, Mi, tiles_s, scale, w.pm, w.pl, w.zt);                                              \
+        mark(2);                                                                                                          \
+        hipLaunchKernelGGL(sm_combine_soe_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT / 64)), dim3(SM_NT), 0, st, w.pm,    \
+                           w.pl, w.zt, n_active, Mi, slabs, B, w.Bp, w.lse, loss_per_sample);                              \
+        hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(SM_NT), 0, st, loss_per_sample, B, loss_mean);                  \
+        mark(3);                                                                                                          \
+        hipLaunchKernelGGL(sm_grad_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active, target_pos,  \
+                           w.lse, B, w.Bp, D, Mi, tiles_s, scale, g, w.dZT);                                               \
+    } while (0)
+            if (D == 512) SM_SOE_LAUNCH(8);
+            else if (D == 256) SM_SOE_LAUNCH(4);
+            else SM_SOE_LAUNCH(2);
+#undef SM_SOE_LAUNCH
+        } else {
             typedef TileSm T;
             const int tiles = (int)(ks_ceil_div(B, T::BN) * ks_ceil_div(M, T::BM));
             hipLaunchKernelGGL(sm_stats_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, X, W, active_idx, n_active, target_pos, B,
