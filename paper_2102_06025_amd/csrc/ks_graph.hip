@@ -15,6 +15,7 @@
 // exact and do not depend on scheduling.
 #include "ks_gemm.h"
 #include "ks_gemm_async.h"
+#include "ks_gemm_soe.h"
 
 typedef KsTile<128, 128, 64, 2, 2> TileR;       // generic recall tile (any D % 32 == 0)
 typedef KsATile<256, 256, 2, 4, 2> TileRA;      // asynchronous recall tile (D % 64 == 0)
@@ -40,7 +41,8 @@ static GrParams gr_params(int K, int D) {
     if (K <= 32) { p.kprime = 64; p.cap = 256; }
     else if (K <= 64) { p.kprime = 128; p.cap = 256; }
     else { p.kprime = 256; p.cap = 512; }
-    if (D % 64 == 0) p.cap = 512; // the asynchronous recall kernel appends up to 256 candidates per row and tile
+    if (D % 64 == 0 && !(D == 128 || D == 256 || D == 512))
+        p.cap = 512; // the 256 x 256 asynchronous recall kernel appends up to 256 candidates per row and tile
     return p;
 }
 
@@ -285,6 +287,89 @@ gr_recall_async_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kp
 }
 
 // ------------------------------------------------------------------------------------------------
+// recall pass as a stationary-operand sweep (D = 128, 256 or 512): a workgroup keeps the MFMA fragments
+// of its 256 rows in registers and streams every row of W past them, 96 rows at a time.  A lane owns one
+// of the 256 rows in the accumulators, so the row's threshold is a register and most elements cost one
+// max operation; only 16-element blocks whose maximum beats the threshold are looked at one by one.
+// ------------------------------------------------------------------------------------------------
+template <int KT, int E>
+__global__ void __launch_bounds__(256)
+gr_recall_soe_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kprime, uint64_t *__restrict__ cand,
+                     int32_t *__restrict__ cnt_out, uint32_t *__restrict__ thr_out) {
+    typedef KsSoe<KT, 96, 6, 2> CFG;
+    constexpr int CAP = E * 64;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
+    __shared__ int s_cnt[CFG::RES];
+    __shared__ uint32_t s_thr[CFG::RES];
+    __shared__ int s_need;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t row0 = (int64_t)blockIdx.x * CFG::RES;
+    for (int m = threadIdx.x; m < CFG::RES; m += 256) { s_cnt[m] = 0; s_thr[m] = 0u; }
+    if (threadIdx.x == 0) s_need = 0;
+    __syncthreads();
+    int col[2], gi[2];
+#pragma unroll
+    for (int fn = 0; fn < 2; ++fn) {
+        col[fn] = ks_soe_col(fn);
+        gi[fn] = (int)row0 + col[fn]; // C < 2^31
+    }
+    const int Ci = (int)C;
+    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM][2]) {
+        // elements that need more than the threshold test: the tail of the last chunk, and the diagonal
+        const bool special = rows_here < CFG::CH || (c0 < (int)row0 + CFG::RES && c0 + CFG::CH > (int)row0);
+#pragma unroll
+        for (int fn = 0; fn < 2; ++fn) {
+            const uint32_t th = s_thr[col[fn]];
+            // 0 = nothing dropped yet: everything passes; rows beyond C never pass
+            const float thf = gi[fn] >= Ci ? INFINITY : (th == 0u ? -INFINITY : gr_unorder(th));
+#pragma unroll
+            for (int fm = 0; fm < CFG::FM; ++fm) {
+                float bm = acc[fm][fn][0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) bm = fmaxf(bm, acc[fm][fn][r]);
+                if (bm > thf) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float v = acc[fm][fn][r];
+                        if (v > thf) {
+                            const int lr = ks_soe_row(fm, r, lane);
+                            const int j = c0 + lr;
+                            if (special && (lr >= rows_here || j == gi[fn])) continue;
+                            const int slot = atomicAdd(&s_cnt[col[fn]], 1);
+                            if (slot < CAP) // always true: a buffer is cut back before it can overflow
+                                cand[(int64_t)gi[fn] * CAP + slot] =
+                                    ((uint64_t)gr_orderable(v) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
+                            if (slot + 1 > CAP - CFG::CH) s_need = 1;
+                        }
+                    }
+                }
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F); // LDS atomics done
+        ks_barrier_nofence();
+        if (s_need) { // some buffer could overflow in the next chunk: cut the full ones back
+            __syncthreads(); // the appended candidates are visible to the wavefront that sorts them
+            for (int m = wave; m < CFG::RES; m += 4) {
+                if (s_cnt[m] > CAP - CFG::CH) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) s_need = 0;
+        }
+    };
+    ks_soe_sweep<CFG>(Wb, D, (int)row0, (int)C, Wb, D, nullptr, 0, (int)C, (int)C, lds, epi);
+    __syncthreads();
+    for (int m = wave; m < CFG::RES; m += 4) {
+        if (row0 + m < C) {
+            if (s_cnt[m] > kprime) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
+        }
+    }
+    __syncthreads();
+    for (int m = threadIdx.x; m < CFG::RES; m += 256) {
+        if (row0 + m < C) { cnt_out[row0 + m] = s_cnt[m]; thr_out[row0 + m] = s_thr[m]; }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // canonical similarity: sum over d ascending of (double)a_d * (double)b_d, one fused multiply-add per
 // term (the product of two fp32 or bf16 values is exact in fp64, so this equals multiply-then-add)
 // ------------------------------------------------------------------------------------------------
@@ -515,7 +600,22 @@ extern "C" int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K
                            (uint16_t *)nullptr, w.norms, w.maxnorm);
         Wb = (const uint16_t *)W;
     }
-    if (D % 64 == 0) {
+    if (D == 128 || D == 256 || D == 512) {
+        const unsigned nb = (unsigned)ks_ceil_div(C, 256);
+#define GR_SOE_LAUNCH(KT)                                                                                                   \
+    do {                                                                                                                    \
+        if (p.cap == 256)                                                                                                   \
+            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 4>), dim3(nb), dim3(256), 0, st, Wb, C, D, p.kprime, w.cand, w.cnt, \
+                               w.thr);                                                                                      \
+        else                                                                                                                \
+            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 8>), dim3(nb), dim3(256), 0, st, Wb, C, D, p.kprime, w.cand, w.cnt, \
+                               w.thr);                                                                                      \
+    } while (0)
+        if (D == 512) GR_SOE_LAUNCH(8);
+        else if (D == 256) GR_SOE_LAUNCH(4);
+        else GR_SOE_LAUNCH(2);
+#undef GR_SOE_LAUNCH
+    } else if (D % 64 == 0) {
         hipLaunchKernelGGL((gr_recall_async_kernel<TileRA, 8>), dim3((unsigned)ks_ceil_div(C, TileRA::BM)), dim3(TileRA::NT), 0,
                            st, Wb, C, D, p.kprime, w.cand, w.cnt, w.thr);
     } else {
