@@ -30,8 +30,15 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 PHASES = ["select", "logits_gemm", "row_stats", "logit_grad", "dx_gemm", "dx_reduce", "dw_gemm", "apply"]
 
-# HBM bytes per launch from rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), see profiles/; filled per workload
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch of each stage's kernel from two rocprofv3 --pmc runs (FETCH_SIZE scaled by 2.0, WRITE_SIZE by
+# 1.0, the factors a copy of known size gives), copied from profiles/bench_shard390k_hbm_traffic.txt
+MEASURED_TRAFFIC = {
+    ("shard390k", "logits_gemm"): 27.26e6,
+    ("shard390k", "logit_grad"): 71.16e6,
+    ("shard390k", "dx_gemm"): 87.42e6,
+    ("shard390k", "dw_gemm"): 82.06e6,
+    ("shard390k", "apply"): 125.50e6,
+}
 
 
 def log(*a):
