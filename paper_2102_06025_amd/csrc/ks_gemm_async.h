@@ -79,7 +79,8 @@ template <int ROWS, int NW> struct KsARows {
 // the four k-rows touched by one read fall on different bank groups.
 // Rows k >= k_limit are redirected to row k_limit-1 (the other operand must be zero there); columns
 // beyond col_limit are redirected to the last 8 valid columns.  src(k) goes through an optional gather
-// list, read one k-tile ahead of its use.
+// list that the caller has staged in LDS for its k range (so that no global load sits between the
+// asynchronous tile loads and their counted waits).
 // ---------------------------------------------------------------------------------------------
 template <int W, int NW> struct KsAKmaj {
     static constexpr int CPR = W / 8;            // 16-byte chunks per k-row
@@ -87,51 +88,33 @@ template <int W, int NW> struct KsAKmaj {
     static constexpr int NI = CPR / NW;          // load instructions per wave per tile
     static_assert(CPR % NW == 0 && NI >= 1 && (W == 128 || W == 256), "k-major tile shape");
     const uint16_t *base;
-    const int32_t *gidx;
+    const int32_t *lidx;  // gather list of the caller's k range, staged in LDS (or nullptr: no gather)
     int64_t ld;
-    int k_limit;
-    int col_off;          // element offset of this lane's chunk inside a source row
+    int k_limit, k_first, col_base, col_lim8;
     int kloc[NI];         // k-row (tile local) of this lane for each instruction
-    int32_t src_next[NI]; // gathered source rows of the next k-tile to be issued
 
-    __device__ __forceinline__ int src_row(int kg) const {
-        if (kg >= k_limit) kg = k_limit - 1;
-        return kg;
-    }
-    // k0_first: first k of the first tile that will be issued
-    __device__ __forceinline__ void init(const uint16_t *base_, int64_t ld_, const int32_t *gidx_, int col0, int col_limit,
-                                         int k_limit_, int k0_first) {
-        base = base_; ld = ld_; gidx = gidx_; k_limit = k_limit_;
+    // lidx_[k - k_first_] = source row of k, for every k this loader will be asked for (k < k_limit_)
+    __device__ __forceinline__ void init(const uint16_t *base_, int64_t ld_, const int32_t *lidx_, int col0, int col_limit,
+                                         int k_limit_, int k_first_) {
+        base = base_; ld = ld_; lidx = lidx_; k_limit = k_limit_; k_first = k_first_;
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
         for (int j = 0; j < NI; ++j) kloc[j] = (j * NW + wave) * RPI + lane / CPR;
-        // the slot this lane fills is lane % CPR; it holds chunk slot ^ ((k & 3) << 2); k & 3 is the same for
-        // every instruction of this lane when RPI is a multiple of 4, otherwise it is folded in per instruction
-        int col = col0 + (lane % CPR) * 8;
-        col_off = col; // un-swizzled; the swizzle is applied per instruction in issue()
-        col_lim8 = col_limit - 8;
         col_base = col0;
-        if (gidx) {
-#pragma unroll
-            for (int j = 0; j < NI; ++j) src_next[j] = gidx[src_row(k0_first + kloc[j])];
-        }
+        col_lim8 = col_limit - 8;
     }
-    int col_lim8, col_base;
-    __device__ __forceinline__ void issue(int k0, uint16_t *lds) {
+    __device__ __forceinline__ void issue(int k0, uint16_t *lds) const {
         const int lane = threadIdx.x & 63;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int k = kloc[j];
+            // the slot this lane fills (lane % CPR) holds chunk slot ^ ((k & 3) << 2) of k-row k
             int col = col_base + (((lane % CPR) ^ ((k & 3) << 2)) * 8);
             if (col > col_lim8) col = col_lim8;
-            int64_t src;
-            if (gidx) {
-                src = src_next[j];
-                src_next[j] = gidx[src_row(k0 + 64 + k)]; // for the next tile in the stream
-            } else {
-                src = src_row(k0 + k);
-            }
+            int kg = k0 + k;
+            if (kg >= k_limit) kg = k_limit - 1;
+            const int64_t src = lidx ? (int64_t)lidx[kg - k_first] : (int64_t)kg;
             __builtin_amdgcn_global_load_lds(KS_GPTR(base + src * ld + col), KS_LPTR(lds + (j * NW + wave) * RPI * W), 16, 0, 0);
         }
     }

@@ -17,6 +17,7 @@
 typedef KsTile<128, 128, 64, 2, 2> TileG;      // generic path (any D % 32 == 0)
 typedef KsATile<256, 256, 2, 4, 2> TileSm;     // fast path (D % 64 == 0): tile = 256 classes x 256 samples
 typedef KsATile<128, 128, 2, 2, 2> TileDx;
+#define DX_IDX_CACHE 4096 /* gather indices of one workgroup's share of the active dimension, staged in LDS */
 typedef KsATile<256, 256, 2, 4, 2> TileDw;
 #define KS_BP_ALIGN 256
 #define SM_SOE_GRID 256 /* workgroups of the stationary-operand softmax passes (one per compute unit) */
@@ -656,6 +657,7 @@ dx_partial_async_kernel(const uint16_t *__restrict__ dZT, int Bp, int64_t Mp, co
                         const int32_t *__restrict__ active_idx, const int32_t *__restrict__ n_active_p, int B, int D, int M,
                         int S, float *__restrict__ part) {
     __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
+    __shared__ int32_t s_idx[DX_IDX_CACHE];
     const int n_active = sm_clamp_n(n_active_p, M);
     const int tiles_m = (B + T::BM - 1) / T::BM, tiles_n = (D + T::BN - 1) / T::BN;
     const int n_tiles = tiles_m * tiles_n;
@@ -668,10 +670,18 @@ dx_partial_async_kernel(const uint16_t *__restrict__ dZT, int Bp, int64_t Mp, co
     f32x16_t acc[T::FM][T::FN];
     ks_a_clear<T>(acc);
     if (kt0 < kt1) {
+        // gather list of this share, staged in LDS (the host sizes S so that a share fits), clamped at the end:
+        // rows at or beyond n_active meet zeros of dZT
+        for (int e = threadIdx.x; e < (kt1 - kt0) * 64 && e < DX_IDX_CACHE; e += T::NT) {
+            int k = kt0 * 64 + e;
+            if (k >= n_active) k = n_active - 1;
+            s_idx[e] = active_idx[k];
+        }
+        __syncthreads();
         KsAKmaj<T::BM, T::NW> ar;
         KsAKmaj<T::BN, T::NW> br;
         ar.init(dZT, Bp, nullptr, tm * T::BM, Bp, (int)Mp, kt0 * 64);
-        br.init(W, D, active_idx, tn * T::BN, D, n_active, kt0 * 64);
+        br.init(W, D, s_idx, tn * T::BN, D, kt1 * 64, kt0 * 64);
         ks_a_mainloop<T, true, true>(ar, br, kt0, kt1, lds, acc);
     }
     float *out = part + (int64_t)s * B * D;
@@ -757,12 +767,18 @@ struct SmWs {
     bool fast;
 };
 
-static int sm_splits(int B, int D, bool fast) {
+static int sm_splits(int B, int D, int64_t M, bool fast) {
     int tiles = fast ? (int)(ks_ceil_div(B, TileDx::BM) * ks_ceil_div(D, TileDx::BN))
                      : (int)(ks_ceil_div(B, TileG::BM) * ks_ceil_div(D, TileG::BN));
+    // two workgroups per compute unit
     int S = (int)ks_ceil_div(512, tiles);
     if (S < 1) S = 1;
     if (S > 32) S = 32;
+    if (fast) { // a share of the active dimension must fit the dX kernel's LDS index cache
+        const int64_t nk = ks_ceil_div(M, 64);
+        const int need = (int)ks_ceil_div(nk, DX_IDX_CACHE / 64);
+        if (S < need) S = need;
+    }
     return S;
 }
 
@@ -772,7 +788,7 @@ static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool w
     w.fast = (D % 64 == 0);
     w.Mp = sm_mp(M);
     w.Bp = (int)ks_align_up((size_t)B, KS_BP_ALIGN);
-    w.S = sm_splits(B, D, w.fast);
+    w.S = sm_splits(B, D, M, w.fast);
     w.select = with_select ? (void *)ar.take<char>(ks_select_ws_bytes(C, B, K)) : nullptr;
     w.lse = ar.take<float>((size_t)B);
     w.part = ar.take<float>((size_t)w.S * B * D);

@@ -1,0 +1,129 @@
+"""GPU parity at the full size of the headline workload (C=390,625, D=512, B=1,024, K=32, M=32,768; Zipf and
+uniform labels), in the launch configuration the benchmark times.  The oracle cannot brute-force the whole
+graph at this size, so the neighbour lists are checked on sampled rows (every distinct label of the batch
+plus random rows); selection, loss and gradients of one step are then compared in full, with the oracle
+working from its own brute-forced lists for the label rows.  The weight update is compared on every touched
+row, and sampled untouched rows must keep their bits."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+LOSS_RTOL = 1e-3
+GRAD_RTOL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def ks():
+    import paper_2102_06025_amd as ks
+    ks.lib()
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    return ks
+
+
+@pytest.fixture(scope="module")
+def shard(ks):
+    """Inputs of the headline shard and the GPU-built graph (shared by the cases below)."""
+    cfg = synth.CONFIGS["shard390k"]
+    print(f"[case] generating shard390k inputs C={cfg['C']} D={cfg['D']}", flush=True)
+    W, X = synth.make_WX(cfg)
+    W_bf = torch.from_numpy(W).cuda().to(torch.bfloat16)
+    print("[case] knn_graph_build on the full shard", flush=True)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    graph, sims = ks.knn_graph_build(W_bf, cfg["K"], want_sims=True, dev_status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    return dict(cfg=cfg, W=W, X=X, W_bf=W_bf, graph=graph, sims=sims)
+
+
+def rel_fro(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return np.linalg.norm(a - b) / np.linalg.norm(b)
+
+
+def test_graph_sampled_rows_exact(ks, orc, shard):
+    cfg, W = shard["cfg"], shard["W"]
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([rng.integers(0, cfg["C"], 192), [0, cfg["C"] - 1]])).astype(np.int32)
+    print(f"[case] graph rows by brute force: {len(rows)} sampled rows", flush=True)
+    lists, sims = orc.graph_bruteforce(W, cfg["K"], rows)
+    sel = torch.from_numpy(rows.astype(np.int64)).cuda()
+    g = shard["graph"][sel].cpu().numpy()
+    s = shard["sims"][sel].cpu().numpy()
+    assert (g == lists).all()
+    assert np.abs(s - sims).max() <= 1e-6
+    # properties that hold for every row: no self, ids in range, distinct, similarities non-increasing
+    G = shard["graph"]
+    ar = torch.arange(cfg["C"], device="cuda", dtype=torch.int32)[:, None]
+    assert bool(((G >= 0) & (G < cfg["C"]) & (G != ar)).all())
+    srt = torch.sort(G, dim=1).values
+    assert bool((srt[:, 1:] != srt[:, :-1]).all())
+    S = shard["sims"]
+    assert bool((S[:, 1:] <= S[:, :-1]).all())
+
+
+@pytest.mark.parametrize("name", ["shard390k", "shard390k_uniform"])
+def test_step_full_size(ks, orc, shard, name):
+    cfg = synth.CONFIGS[name]
+    C, D, B, K, M, scale = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"], cfg["scale"]
+    W, X, W_bf, graph = shard["W"], shard["X"], shard["W_bf"], shard["graph"]
+    y = synth.make_labels(cfg)
+    grad_scale, alpha = 128.0, -0.05 / 128.0
+    print(f"[case] {name}: fwd_bwd + apply at full size, B={B} M={M}", flush=True)
+    X_bf = torch.from_numpy(X).cuda().to(torch.bfloat16)
+    out = ks.knn_softmax_fwd_bwd(W_bf, X_bf, torch.from_numpy(y).cuda(), graph, M, scale, grad_scale)
+    torch.cuda.synchronize()
+    assert int(out["dev_status"].item()) == 0
+    A = int(out["n_active"].item())
+
+    # oracle: its own lists for the rows that selection reads
+    rows = np.unique(y).astype(np.int32)
+    print(f"        oracle: brute-force lists of the {len(rows)} distinct labels", flush=True)
+    lists, _ = orc.graph_bruteforce(W, K, rows)
+    g_rows = graph[torch.from_numpy(rows.astype(np.int64)).cuda()].cpu().numpy()
+    assert (g_rows == lists).all()
+    G = np.empty((C, K), dtype=np.int32)
+    G[:] = (np.arange(C, dtype=np.int64)[:, None] + 1 + np.arange(K)[None, :]) % C  # never read
+    G[rows] = lists
+    active, A_ref, tpos = orc.select_active(y, G, C, M)
+    assert A == A_ref
+    assert (out["active_idx"].cpu().numpy() == active).all()
+    assert (out["target_pos"].cpu().numpy() == tpos).all()
+    print(f"        oracle: fwd/bwd with A={A_ref}", flush=True)
+    ref = orc.knn_softmax_fwd_bwd(W, X, active[:A_ref], tpos, scale, grad_scale)
+    li = out["loss_per_sample"].cpu().numpy()
+    assert np.abs(li - ref["loss_i"]).max() <= LOSS_RTOL * max(1.0, np.abs(ref["loss_i"]).max())
+    loss = float(out["loss_mean"].item())
+    assert abs(loss - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+    e_dx = rel_fro(out["dX"].cpu().numpy(), ref["dX"])
+    e_dw = rel_fro(out["dW_active"][:A].cpu().numpy(), ref["dWA"])
+    print(f"        A={A} loss={loss:.6f} ref={ref['loss']:.6f} relF(dX)={e_dx:.2e} relF(dW)={e_dw:.2e}", flush=True)
+    assert e_dx <= GRAD_RTOL and e_dw <= GRAD_RTOL
+
+    # weight update with the GPU's own gradient rows (so that only the update arithmetic is compared)
+    W_master = torch.from_numpy(W).cuda()
+    W_copy = W_bf.clone()
+    st = ks.apply_weight_grad(W_master, W_copy, out["active_idx"], out["n_active"], out["dW_active"], alpha,
+                              idx_sorted_unique=True)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    dW32 = out["dW_active"][:A].cpu().numpy()
+    W_ref, W_ref_bf = orc.apply_weight_grad(W, active[:A], dW32, alpha, want_bf16=True)
+    idx = torch.from_numpy(active[:A].astype(np.int64)).cuda()
+    got = W_master[idx].cpu().numpy()
+    # one fp32 fused multiply-add per element against the oracle's fp64 sum rounded once: half an ulp each
+    assert np.abs(got - W_ref[active[:A]]).max() <= 2.0 ** -23 * np.abs(W_ref[active[:A]]).max()
+    got_bf = W_copy[idx].view(torch.int16).cpu().numpy().view(np.uint16)
+    # the bf16 copy is the rounding of the GPU's own fp32 master; it equals the oracle's wherever the two
+    # masters round the same way
+    assert (got_bf == synth.bf16_bits(got)).all()
+    assert np.mean(got_bf == W_ref_bf[active[:A]]) > 0.999
+    rng = np.random.default_rng(9)
+    untouched = np.setdiff1d(rng.integers(0, C, 4096), active[:A])
+    ui = torch.from_numpy(untouched.astype(np.int64)).cuda()
+    assert (W_master[ui].cpu().numpy() == W[untouched]).all()
+    assert bool((W_copy[ui] == W_bf[ui]).all())
