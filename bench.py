@@ -100,15 +100,18 @@ def oracle_graph_for_labels(orc, W, y, cfg):
     return G, rows, lists, dt
 
 
-def phase_model(cfg, A):
+def phase_model(cfg, A, unit_rows):
     """Algorithmic flops / bytes per launch of each stage at A active classes."""
     B, D, K, C = cfg["B"], cfg["D"], cfg["K"], cfg["C"]
     gemm = 2.0 * B * A * D
     return {
         "select": dict(bound="latency"),
-        "logits_gemm": dict(bound="mfma", flops=gemm),      # logits + per-tile softmax statistics, nothing stored
-        "row_stats": dict(bound="latency"),                  # merge of the per-tile statistics, loss mean
-        "logit_grad": dict(bound="mfma", flops=gemm),       # logits again -> logit gradient (stored transposed)
+        # unit rows: the only sweep (logits -> exponentials stored transposed + their sums); otherwise
+        # logits + per-slab softmax statistics, nothing stored
+        "logits_gemm": dict(bound="mfma", flops=gemm),
+        "row_stats": dict(bound="latency"),                  # merge of the per-slab sums, loss, loss mean
+        # logits again -> logit gradient (stored transposed); no such sweep with unit rows
+        "logit_grad": dict(bound="latency") if unit_rows else dict(bound="mfma", flops=gemm),
         "dx_gemm": dict(bound="mfma", flops=gemm),
         "dx_reduce": dict(bound="latency"),
         "dw_gemm": dict(bound="mfma", flops=gemm),
@@ -124,6 +127,8 @@ def main():
     ap.add_argument("--workload", default="shard390k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
+    ap.add_argument("--general-rows", action="store_true",
+                    help="do not tell the library that the rows are L2-normalised (two-sweep softmax)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1")
@@ -168,7 +173,9 @@ def main():
 
     # ---- step buffers -----------------------------------------------------------------------------------
     ws = torch.empty(ks.knn_softmax_workspace(C, D, B, K, M), dtype=torch.uint8, device="cuda")
-    out = ks.knn_softmax_fwd_bwd(W_bf, X_bf, labels, graph, M, scale, grad_scale, ws=ws)
+    # the synthetic rows are L2-normalised, as the paper's are: the library may rely on it
+    unit_rows = not args.general_rows
+    out = ks.knn_softmax_fwd_bwd(W_bf, X_bf, labels, graph, M, scale, grad_scale, ws=ws, unit_rows=unit_rows)
     torch.cuda.synchronize()
     A = int(out["n_active"].item())
     assert int(out["dev_status"].item()) == 0
@@ -182,12 +189,14 @@ def main():
 
     def step(ev=None):
         if ev is None:
-            ks.knn_softmax_fwd_bwd(W_bf, X_bf, labels, graph, M, scale, grad_scale, out=out, ws=ws)
+            ks.knn_softmax_fwd_bwd(W_bf, X_bf, labels, graph, M, scale, grad_scale, out=out, ws=ws,
+                                   unit_rows=unit_rows)
         else:
             rc = L.knn_softmax_fwd_bwd_profiled(
                 ct.c_void_p(W_bf.data_ptr()), ct.c_void_p(X_bf.data_ptr()), ct.c_void_p(labels.data_ptr()),
                 ct.c_void_p(graph.data_ptr()), ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(K), ct.c_int(M),
-                ct.c_float(scale), ct.c_float(grad_scale), ct.c_void_p(out["active_idx"].data_ptr()),
+                ct.c_float(scale), ct.c_float(grad_scale), ct.c_uint32(1 if unit_rows else 0),
+                ct.c_void_p(out["active_idx"].data_ptr()),
                 ct.c_void_p(out["n_active"].data_ptr()), ct.c_void_p(out["target_pos"].data_ptr()),
                 ct.c_void_p(out["loss_per_sample"].data_ptr()), ct.c_void_p(out["loss_mean"].data_ptr()),
                 ct.c_void_p(out["dX"].data_ptr()), ct.c_void_p(out["dW_active"].data_ptr()),
@@ -227,7 +236,7 @@ def main():
             dur[p] += hev.elapsed_ms(ev[k], ev[k + 1])
     for p in PHASES:
         dur[p] = dur[p] / args.steps * 1e3  # microseconds
-    model = phase_model(cfg, A)
+    model = phase_model(cfg, A, unit_rows)
     phases = {}
     for p in PHASES:
         m = model[p]
@@ -287,7 +296,8 @@ def main():
         "ms_per_step_with_stage_events": round(ms_per_step_instrumented, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: C={C} D={D} B={B} K={K} M={M} labels={cfg['labels']} s={scale}",
-                   "active_classes": A, "step": "select + knn_softmax_fwd_bwd + apply_weight_grad"},
+                   "active_classes": A, "step": "select + knn_softmax_fwd_bwd + apply_weight_grad",
+                   "unit_rows_flag": unit_rows},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "phases": phases,

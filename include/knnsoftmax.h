@@ -45,6 +45,10 @@ typedef enum {
 #define KS_DEV_BAD_INDEX 4          /* apply_weight_grad: an index outside [0, C) (that row is skipped) */
 #define KS_DEV_IDX_NOT_SORTED 8     /* apply_weight_grad: idx_sorted_unique was promised but does not hold */
 #define KS_DEV_BAD_COUNT 16         /* a device-side count (n, n_active) outside [0, n_max] */
+#define KS_DEV_RANGE 32             /* KS_FLAG_UNIT_ROWS was promised but a sample's exponentials overflowed or all vanished */
+
+/* bits of the `flags` argument of the softmax entry points */
+#define KS_FLAG_UNIT_ROWS 1u        /* every row of W_bf16 and X_bf16 has L2 norm <= 1 (up to rounding) */
 
 #define KS_DTYPE_BF16 0
 #define KS_DTYPE_FP32 1
@@ -113,6 +117,13 @@ int knn_gather_rows(const uint16_t *W_bf16, const int32_t *active_idx, const int
  * X and W rows are used as given (callers pass L2-normalised rows); gradients are with respect to them.
  * grad_scale (loss scaling) multiplies the gradients only, not the reported losses.
  *
+ * flags: 0, or KS_FLAG_UNIT_ROWS when the caller normalises the rows of W and X as the paper does (Section
+ * 3.2: the fc layer works on normalised weights and features).  All logits then lie in [-scale, scale], and
+ * for scale <= 40 the library evaluates the softmax against that fixed bound in a single sweep over the
+ * active rows instead of a statistics sweep followed by a gradient sweep.  The result is the same function
+ * of the inputs (the bound only shifts the exponent range), also when some norms exceed 1; should a
+ * sample's exponentials overflow or all underflow, KS_DEV_RANGE is raised and the outputs are unspecified.
+ *
  *   W_bf16 [C, D], X_bf16 [B, D], labels [B], graph [C, K]           inputs
  *   active_idx [M], n_active [1], target_pos [B]                     out, as in knn_select_active
  *   loss_per_sample [B] fp32, loss_mean [1] fp32                     out
@@ -123,21 +134,23 @@ int knn_gather_rows(const uint16_t *W_bf16, const int32_t *active_idx, const int
 size_t knn_softmax_workspace(int64_t C, int D, int B, int K, int M);
 int knn_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
                         const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
-                        float grad_scale, int32_t *active_idx, int32_t *n_active, int32_t *target_pos,
-                        float *loss_per_sample, float *loss_mean, float *dX, float *dW_active,
-                        void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
+                        float grad_scale, uint32_t flags, int32_t *active_idx, int32_t *n_active,
+                        int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
+                        float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
 /* Measurement aid: knn_softmax_fwd_bwd with one hipEvent_t recorded on `stream` at each stage boundary, so that
  * a caller can time the stages of a step without a profiler.  events[0..KS_N_PHASE_EVENTS) are created by the
- * caller (hipEventCreate); event k is recorded: 0 at entry, 1 after the selection, 2 after the logits GEMM,
- * 3 after the row statistics and the loss mean, 4 after the logit gradient, 5 after the dX partial GEMM,
- * 6 after the dX reduction, 7 after the dW GEMM.  Same results as knn_softmax_fwd_bwd. */
+ * caller (hipEventCreate); event k is recorded: 0 at entry, 1 after the selection, 2 after the first sweep
+ * over the active rows (softmax statistics; with KS_FLAG_UNIT_ROWS the only sweep, which also writes the
+ * exponentials), 3 after the per-sample combine and the loss mean, 4 after the second sweep (logit gradient;
+ * nothing with KS_FLAG_UNIT_ROWS), 5 after the dX partial GEMM, 6 after the dX reduction, 7 after the dW
+ * GEMM.  Same results as knn_softmax_fwd_bwd. */
 #define KS_N_PHASE_EVENTS 8
 int knn_softmax_fwd_bwd_profiled(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
                                  const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
-                                 float grad_scale, int32_t *active_idx, int32_t *n_active, int32_t *target_pos,
-                                 float *loss_per_sample, float *loss_mean, float *dX, float *dW_active,
-                                 void *ws, size_t ws_bytes, int32_t *dev_status, void *stream,
+                                 float grad_scale, uint32_t flags, int32_t *active_idx, int32_t *n_active,
+                                 int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
+                                 float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream,
                                  void **events, int n_events);
 
 /* ------------------------------------------------------------------------------------------------------
@@ -146,7 +159,7 @@ int knn_softmax_fwd_bwd_profiled(const uint16_t *W_bf16, const uint16_t *X_bf16,
  * ---------------------------------------------------------------------------------------------------- */
 size_t full_softmax_workspace(int64_t C, int D, int B);
 int full_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels, int64_t C,
-                         int D, int B, float scale, float grad_scale, float *loss_per_sample,
+                         int D, int B, float scale, float grad_scale, uint32_t flags, float *loss_per_sample,
                          float *loss_mean, float *dX, float *dW, void *ws, size_t ws_bytes,
                          int32_t *dev_status, void *stream);
 

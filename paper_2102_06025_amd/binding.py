@@ -10,6 +10,7 @@ import torch
 
 KS_OK, KS_INVALID_ARG, KS_UNSUPPORTED, KS_WORKSPACE_TOO_SMALL, KS_HIP_ERROR = 0, 1, 2, 3, 4
 KS_DEV_BAD_LABEL, KS_DEV_BAD_GRAPH_ID, KS_DEV_BAD_INDEX, KS_DEV_IDX_NOT_SORTED, KS_DEV_BAD_COUNT = 1, 2, 4, 8, 16
+KS_DEV_RANGE = 32
 _STATUS = {1: "KS_INVALID_ARG", 2: "KS_UNSUPPORTED", 3: "KS_WORKSPACE_TOO_SMALL", 4: "KS_HIP_ERROR"}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -153,11 +154,15 @@ def knn_softmax_workspace(C, D, B, K, M) -> int:
     return int(lib().knn_softmax_workspace(ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(K), ct.c_int(M)))
 
 
+FLAG_UNIT_ROWS = 1  # KS_FLAG_UNIT_ROWS
+
+
 def knn_softmax_fwd_bwd(W_bf16, X_bf16, labels, graph, M, scale, grad_scale=1.0, out=None, ws=None,
-                        dev_status=None, stream=None):
+                        dev_status=None, stream=None, unit_rows=False):
     """One forward+backward step.  Returns a dict of device tensors: active_idx [M], n_active [1],
     target_pos [B], loss_per_sample [B], loss_mean [1], dX [B, D], dW_active [M, D], dev_status [1].
-    Pass the dict of a previous call as `out` (and `ws`) to reuse the buffers."""
+    Pass the dict of a previous call as `out` (and `ws`) to reuse the buffers.  unit_rows=True passes
+    KS_FLAG_UNIT_ROWS (the rows of W_bf16 and X_bf16 are L2-normalised)."""
     _need(W_bf16, torch.bfloat16, "W_bf16")
     _need(X_bf16, torch.bfloat16, "X_bf16")
     _need(labels, torch.int32, "labels")
@@ -181,7 +186,7 @@ def knn_softmax_fwd_bwd(W_bf16, X_bf16, labels, graph, M, scale, grad_scale=1.0,
     out["ws"] = ws
     rc = lib().knn_softmax_fwd_bwd(_ptr(W_bf16), _ptr(X_bf16), _ptr(labels), _ptr(graph), ct.c_int64(C), ct.c_int(D),
                                    ct.c_int(B), ct.c_int(K), ct.c_int(M), ct.c_float(scale), ct.c_float(grad_scale),
-                                   _ptr(out["active_idx"]), _ptr(out["n_active"]), _ptr(out["target_pos"]),
+                                   ct.c_uint32(FLAG_UNIT_ROWS if unit_rows else 0), _ptr(out["active_idx"]), _ptr(out["n_active"]), _ptr(out["target_pos"]),
                                    _ptr(out["loss_per_sample"]), _ptr(out["loss_mean"]), _ptr(out["dX"]),
                                    _ptr(out["dW_active"]), _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status),
                                    _stream(stream))
@@ -194,7 +199,7 @@ def full_softmax_workspace(C, D, B) -> int:
 
 
 def full_softmax_fwd_bwd(W_bf16, X_bf16, labels, scale, grad_scale=1.0, out=None, ws=None, dev_status=None,
-                         stream=None):
+                         stream=None, unit_rows=False):
     """Full softmax over all classes.  Returns dict(loss_per_sample, loss_mean, dX, dW [C, D], dev_status)."""
     _need(W_bf16, torch.bfloat16, "W_bf16")
     _need(X_bf16, torch.bfloat16, "X_bf16")
@@ -212,7 +217,8 @@ def full_softmax_fwd_bwd(W_bf16, X_bf16, labels, scale, grad_scale=1.0, out=None
     out["dev_status"] = dev_status
     out["ws"] = ws
     rc = lib().full_softmax_fwd_bwd(_ptr(W_bf16), _ptr(X_bf16), _ptr(labels), ct.c_int64(C), ct.c_int(D), ct.c_int(B),
-                                    ct.c_float(scale), ct.c_float(grad_scale), _ptr(out["loss_per_sample"]),
+                                    ct.c_float(scale), ct.c_float(grad_scale), ct.c_uint32(FLAG_UNIT_ROWS if unit_rows else 0),
+                                    _ptr(out["loss_per_sample"]),
                                     _ptr(out["loss_mean"]), _ptr(out["dX"]), _ptr(out["dW"]), _ptr(ws),
                                     ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
     _check("full_softmax_fwd_bwd", rc)

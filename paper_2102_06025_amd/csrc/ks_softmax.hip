@@ -102,21 +102,9 @@ row_stats_kernel(const float *__restrict__ Z, int64_t ldz, const int32_t *__rest
     }
 }
 
-// mean of the per-sample losses: one workgroup, fixed summation order.  (Kept as its own tiny launch: folding
-// it into the kernel above needs a device-scope fence per workgroup, which costs far more on this chip,
-// whose eight L2 caches are only coherent through memory.)
-__global__ void __launch_bounds__(SM_NT) loss_mean_kernel(const float *__restrict__ loss_i, int B, float *loss_mean) {
-    __shared__ float sh[SM_NT];
-    float s = 0.f;
-    for (int i = threadIdx.x; i < B; i += SM_NT) s += loss_i[i];
-    sh[threadIdx.x] = s;
-    __syncthreads();
-    for (int o = SM_NT / 2; o > 0; o >>= 1) {
-        if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) *loss_mean = sh[0] / (float)B;
-}
+// (The mean of the per-sample losses is formed later in the stream, by one block of dx_reduce_kernel: folding
+// it into the kernel above would need a device-scope fence per workgroup, which costs far more on this chip,
+// whose eight L2 caches are only coherent through memory, and a launch of its own costs about 5 us.)
 
 // ------------------------------------------------------------------------------------------------
 // dZ = g (exp(Z - lse) - onehot) as bf16; columns in [n_active, round_up(n_active, 256)) are zeroed
@@ -182,14 +170,30 @@ dx_partial_kernel(const uint16_t *__restrict__ dZ, int64_t ldz, const uint16_t *
 }
 
 __global__ void __launch_bounds__(SM_NT)
-dx_reduce_kernel(const float *__restrict__ part, int S, int64_t BD, float scale, float *__restrict__ dX) {
+dx_reduce_kernel(const float *__restrict__ part, int S, int64_t BD, float scale, const float *__restrict__ row_factor,
+                 int D, float *__restrict__ dX, const float *__restrict__ loss_i, int B, float *loss_mean) {
+    // the last block also folds the per-sample losses (complete since an earlier launch) into the batch
+    // mean: thread t takes samples t, t + SM_NT, ..., then a tree -- a fixed order, and no launch of its own
+    if (loss_mean && blockIdx.x == gridDim.x - 1) {
+        __shared__ float sh[SM_NT];
+        float s = 0.f;
+        for (int i = threadIdx.x; i < B; i += SM_NT) s += loss_i[i];
+        sh[threadIdx.x] = s;
+        __syncthreads();
+        for (int o = SM_NT / 2; o > 0; o >>= 1) {
+            if (threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) *loss_mean = sh[0] / (float)B;
+    }
     int64_t e = ((int64_t)blockIdx.x * SM_NT + threadIdx.x) * 4;
-    if (e >= BD) return; // BD % 4 == 0
+    if (e >= BD) return; // BD % 4 == 0, D % 4 == 0
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int s = 0; s < S; ++s) {
         float4 v = *(const float4 *)(part + (int64_t)s * BD + e);
         acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
+    if (row_factor) scale *= row_factor[e / D]; // per-sample factor (the one-sweep softmax leaves 1 / sum there)
     *(float4 *)(dX + e) = make_float4(scale * acc.x, scale * acc.y, scale * acc.z, scale * acc.w);
 }
 
@@ -430,6 +434,7 @@ sm_grad_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, c
 // evenly whatever the active count; per-sample softmax statistics are carried in registers along the slab.
 // ================================================================================================
 #define SOE_STAGES 4
+#define KS_FUSED_MAX_SCALE 40.f // exp(-2 * scale) must stay a normal fp32 / bf16 number
 
 // rows per slab for n64 = round_up(n_active, 64) rows and `slabs` slabs
 __host__ __device__ __forceinline__ int sm_slab_rows(int n64, int slabs) {
@@ -622,6 +627,192 @@ sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
     ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi);
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// One-sweep variant for rows of norm <= 1 (the paper normalises W and X, section 3.2): every logit
+// lies in [-scale, scale], so the softmax can be evaluated against the fixed reference `scale` and no
+// statistics pass is needed.  The sweep writes E[a][i] = exp(z_ia - scale) (bf16, transposed, zero in the
+// padding) and per-slab sums of the stored (rounded) E; sm_combine_fused_kernel then forms sum_i = sum_a E_ia,
+// the loss, and turns column i into (P_ia - [a = target_i]) * sum_i by replacing the target entry.  The
+// factor g / sum_i that is still missing is applied where it is cheap: on the rows of dX after the
+// contraction over classes, and on the rows of X (X2 = X / sum_i, bf16) before the contraction over samples.
+// The reference only shifts the exponent range: results are the same function of the inputs as long as no
+// exponential overflows and not all of a sample's vanish, which the combine kernel checks.
+// ------------------------------------------------------------------------------------------------
+template <int KT>
+__global__ void __launch_bounds__(256)
+sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, const int32_t *__restrict__ active_idx,
+                    const int32_t *__restrict__ n_active_p, int B, int Bp, int D, int M, int tiles_s, float scale,
+                    float *__restrict__ pl, uint16_t *__restrict__ dZT) {
+    typedef KsSoe<KT, 96, SOE_STAGES, 2> CFG;
+    constexpr int STAGE_LD = CFG::RES + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
+    __shared__ __attribute__((aligned(16))) uint16_t stage[CFG::CH * STAGE_LD];
+    const int n = sm_clamp_n(n_active_p, M);
+    const int n64 = (n + 63) & ~63;
+    const int slabs = gridDim.x / tiles_s;
+    const int h = sm_slab_rows(n64, slabs);
+    const int id = ks_xcd_remap(blockIdx.x, gridDim.x);
+    const int ts = id % tiles_s, slab = id / tiles_s;
+    const int s0 = slab * h, s1 = (s0 + h < n64) ? s0 + h : n64;
+    if (slab >= slabs || s0 >= s1) return;
+    const int lane = threadIdx.x & 63;
+    const bool odd = lane & 1;
+    const int lim = n < s1 ? n : s1; // rows of this slab that are real classes
+    int col[2];
+    bool ok[2];
+    float l[2] = {0.f, 0.f};
+#pragma unroll
+    for (int fn = 0; fn < 2; ++fn) {
+        col[fn] = ks_soe_col(fn);
+        ok[fn] = ts * CFG::RES + col[fn] < B;
+    }
+    // exp(scale * acc - scale) = exp2(fma(acc, k1, -k1))
+    const float k1 = scale * 1.4426950408889634f;
+    const bool samples_ok = (ts + 1) * CFG::RES <= B;
+    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM][2]) {
+        const bool plain = samples_ok && c0 + CFG::CH <= lim; // no row or column of this chunk needs masking
+#pragma unroll
+        for (int fn = 0; fn < 2; ++fn) {
+#pragma unroll
+            for (int fm = 0; fm < CFG::FM; ++fm)
+#pragma unroll
+                for (int r = 0; r < 16; r += 2) {
+                    float d[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) d[e] = __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r + e], k1, -k1));
+                    if (!plain) {
+#pragma unroll
+                        for (int e = 0; e < 2; ++e)
+                            if (!ok[fn] || c0 + ks_soe_row(fm, r + e, lane) >= lim) d[e] = 0.f;
+                    }
+                    // neighbouring lanes (samples 2j, 2j+1) trade so that each holds two adjacent samples of one
+                    // class row: the even lane ends up with row r, the odd lane with row r+1
+                    const float send = odd ? d[0] : d[1];
+                    const float recv =
+                        __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0xB1, 0xF, 0xF, true));
+                    const uint32_t packed = odd ? ks_pack_bf2(recv, d[1]) : ks_pack_bf2(d[0], recv);
+                    const int row = ks_soe_row(fm, r + (odd ? 1 : 0), lane);
+                    *(uint32_t *)(stage + row * STAGE_LD + (col[fn] & ~1)) = packed;
+                }
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F); // LDS writes done (lgkmcnt 0); loads in flight are left alone
+        ks_barrier_nofence();
+        // sums over the class rows of the rounded values, as the two gradient contractions will read them:
+        // thread t takes the sample pair t % 128 and the rows of parity t / 128
+        {
+            const int pr = threadIdx.x & 127;
+            float lo = 0.f, hi = 0.f;
+            for (int r = threadIdx.x >> 7; r < rows_here; r += 2) {
+                const uint32_t v = *(const uint32_t *)(stage + r * STAGE_LD + 2 * pr);
+                lo += ks_bf2f(v & 0xFFFFu);
+                hi += ks_bf2f(v >> 16);
+            }
+            l[0] += lo;
+            l[1] += hi;
+        }
+        const int chunks = rows_here * (CFG::RES / 8);
+        for (int q = threadIdx.x; q < chunks; q += 256) {
+            const int row = q / (CFG::RES / 8), ch = q % (CFG::RES / 8);
+            *(uint4 *)(dZT + (int64_t)(c0 + row) * Bp + ts * CFG::RES + ch * 8) = *(const uint4 *)(stage + row * STAGE_LD + ch * 8);
+        }
+    };
+    ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi);
+    // the two row parities of a sample pair meet through LDS (the stream stages are free now)
+    float *red = (float *)lds;
+    if (threadIdx.x >= 128) {
+        red[2 * (threadIdx.x - 128)] = l[0];
+        red[2 * (threadIdx.x - 128) + 1] = l[1];
+    }
+    __syncthreads();
+    if (threadIdx.x < 128) {
+        const int i0 = ts * CFG::RES + 2 * threadIdx.x;
+        if (i0 < B) pl[(int64_t)slab * Bp + i0] = l[0] + red[2 * threadIdx.x];
+        if (i0 + 1 < B) pl[(int64_t)slab * Bp + i0 + 1] = l[1] + red[2 * threadIdx.x + 1];
+    }
+}
+
+// Combine step of the one-sweep variant.  A block owns 32 samples, eight threads per sample: sum of the slab
+// sums (every eighth slab each, then the eight partial sums in order); the target logit as an fp32 dot
+// product of the two bf16 rows (an eighth of the row each); with it the target's exponential E_t, which
+// replaces the stored rounded one in the sum, so that the stored column (with the target entry set to
+// E_t - sum = -(sum of the others)) sums to zero and P_t - 1 carries no cancellation; the loss; the
+// reciprocal sum for dX; the scaled row of X2.
+#define SM_CF_NT 256
+__global__ void __launch_bounds__(SM_CF_NT)
+sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict__ n_active_p,
+                        const int32_t *__restrict__ active_idx, const int32_t *__restrict__ target_pos,
+                        const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, int M, int slabs, int B, int Bp, int D,
+                        float scale, float *__restrict__ inv_sum, float *__restrict__ loss_i, uint16_t *__restrict__ dZT,
+                        uint16_t *__restrict__ X2, int32_t *dev_status) {
+    __shared__ float sh[SM_CF_NT], sh_dot[SM_CF_NT];
+    __shared__ float s_inv[32];
+    const int n = sm_clamp_n(n_active_p, M);
+    const int n64 = (n + 63) & ~63;
+    const int h = sm_slab_rows(n64, slabs);
+    const int nt = (n64 + h - 1) / h; // slabs that hold rows
+    const int j = threadIdx.x & 31, gq = threadIdx.x >> 5;
+    const int i = blockIdx.x * 32 + j;
+    int tp = 0;
+    {
+        float part = 0.f, dot = 0.f;
+        if (i < B) {
+            for (int t = gq; t < nt; t += 8) part += pl[(int64_t)t * Bp + i];
+            tp = target_pos[i];
+            tp = tp < 0 ? 0 : (tp >= n ? n - 1 : tp); // stays in bounds whatever the selection flagged
+            const uint16_t *xr = X + (int64_t)i * D + gq * (D / 8);
+            const uint16_t *wr = W + (int64_t)active_idx[tp] * D + gq * (D / 8);
+            for (int d = 0; d < D / 8; d += 8) { // D % 64 == 0 on this path
+                const uint4 xv = *(const uint4 *)(xr + d), wv = *(const uint4 *)(wr + d);
+                const uint32_t xa[4] = {xv.x, xv.y, xv.z, xv.w}, wa[4] = {wv.x, wv.y, wv.z, wv.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    dot = fmaf(ks_bf2f(xa[q] & 0xFFFFu), ks_bf2f(wa[q] & 0xFFFFu), dot);
+                    dot = fmaf(ks_bf2f(xa[q] >> 16), ks_bf2f(wa[q] >> 16), dot);
+                }
+            }
+        }
+        sh[threadIdx.x] = part;
+        sh_dot[threadIdx.x] = dot;
+    }
+    __syncthreads();
+    if (threadIdx.x < 32) {
+        float inv = 0.f;
+        if (i < B) {
+            float sum = 0.f, dot = 0.f;
+            for (int q = 0; q < 8; ++q) {
+                sum += sh[q * 32 + j];
+                dot += sh_dot[q * 32 + j];
+            }
+            const float z_t = scale * dot;
+            const float e_t = __expf(z_t - scale);
+            uint16_t *cell = dZT + (int64_t)tp * Bp + i;
+            const float others = sum - ks_bf2f(*cell); // sum of the exponentials of the other classes
+            sum = others + e_t;
+            if (!(sum > 0.f) || !(sum < INFINITY)) ks_flag(dev_status, KS_DEV_RANGE);
+            loss_i[i] = (scale + __logf(sum)) - z_t;
+            inv = 1.f / sum;
+            inv_sum[i] = inv;
+            *cell = (uint16_t)ks_f2bf(-others); // the column now holds (P - onehot) * sum
+        }
+        s_inv[j] = inv;
+    }
+    __syncthreads();
+    const int rows = (B - blockIdx.x * 32 < 32) ? B - blockIdx.x * 32 : 32;
+    const int per_row = D / 8; // 16-byte pieces per row
+    for (int q = threadIdx.x; q < rows * per_row; q += SM_CF_NT) {
+        const int r = q / per_row, c = q % per_row;
+        const float f = s_inv[r];
+        const uint4 v = *(const uint4 *)(X + ((int64_t)blockIdx.x * 32 + r) * D + c * 8);
+        uint4 o;
+        o.x = ks_pack_bf2(ks_bf2f(v.x & 0xFFFFu) * f, ks_bf2f(v.x >> 16) * f);
+        o.y = ks_pack_bf2(ks_bf2f(v.y & 0xFFFFu) * f, ks_bf2f(v.y >> 16) * f);
+        o.z = ks_pack_bf2(ks_bf2f(v.z & 0xFFFFu) * f, ks_bf2f(v.z >> 16) * f);
+        o.w = ks_pack_bf2(ks_bf2f(v.w & 0xFFFFu) * f, ks_bf2f(v.w >> 16) * f);
+        *(uint4 *)(X2 + ((int64_t)blockIdx.x * 32 + r) * D + c * 8) = o;
+    }
+}
+
 // one wavefront per sample: merge the per-slab (max, sum) pairs in slab order -> lse_i, loss_i
 __global__ void __launch_bounds__(SM_NT)
 sm_combine_soe_kernel(const float *__restrict__ pm, const float *__restrict__ pl, const float *__restrict__ zt,
@@ -761,6 +952,8 @@ struct SmWs {
     float *part;
     uint16_t *dZT; // fast path: the logit gradient is kept transposed only
     float *pm, *pl, *zt; // fast path: per class-tile softmax statistics, target logits
+    float *inv;          // one-sweep softmax: 1 / sum_a exp(z_ia - scale) per sample
+    uint16_t *X2;        // one-sweep softmax: rows of X scaled by that
     int S;
     int64_t Mp;
     int Bp;
@@ -794,7 +987,8 @@ static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool w
     w.part = ar.take<float>((size_t)w.S * B * D);
     w.Z = nullptr;
     w.dZ = w.dZT = nullptr;
-    w.pm = w.pl = w.zt = nullptr;
+    w.pm = w.pl = w.zt = w.inv = nullptr;
+    w.X2 = nullptr;
     if (w.fast) {
         w.dZT = ar.take<uint16_t>((size_t)w.Mp * w.Bp);
         size_t nt = (size_t)(w.Mp / TileSm::BM);
@@ -802,6 +996,8 @@ static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool w
         w.pm = ar.take<float>(nt * w.Bp);
         w.pl = ar.take<float>(nt * w.Bp);
         w.zt = ar.take<float>((size_t)w.Bp);
+        w.inv = ar.take<float>((size_t)w.Bp);
+        w.X2 = ar.take<uint16_t>((size_t)w.Bp * D);
     } else {
         w.Z = ar.take<float>((size_t)B * w.Mp);
         w.dZ = ar.take<uint16_t>((size_t)B * w.Mp);
@@ -814,13 +1010,31 @@ static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool w
 static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M, float scale, float grad_scale,
                   const int32_t *active_idx, const int32_t *n_active, const int32_t *target_pos,
                   float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, const SmWs &w,
-                  hipStream_t st, hipEvent_t *ev = nullptr) {
+                  uint32_t flags, int32_t *dev_status, hipStream_t st, hipEvent_t *ev = nullptr) {
     auto mark = [&](int k) { if (ev) (void)hipEventRecord(ev[k], st); };
     const int Mi = (int)M;
     const float g = grad_scale / (float)B;
+    bool fused = false;
     if (w.fast) {
         const int tiles_s = (int)ks_ceil_div(B, 256);
-        if ((D == 128 || D == 256 || D == 512) && tiles_s <= SM_SOE_GRID && scale > 0.f && g > 0.f) {
+        const bool soe = (D == 128 || D == 256 || D == 512) && tiles_s <= SM_SOE_GRID && scale > 0.f && g > 0.f;
+        // unit rows: |logit| <= scale, and exp(-2 scale) must stay a normal number
+        fused = soe && (flags & KS_FLAG_UNIT_ROWS) && scale <= KS_FUSED_MAX_SCALE;
+        if (fused) {
+            const int grid = SM_SOE_GRID / tiles_s * tiles_s, slabs = grid / tiles_s;
+#define SM_FUSED_LAUNCH(KT)                                                                                               \
+    hipLaunchKernelGGL(sm_fused_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active, B, w.Bp, D, Mi,  \
+                       tiles_s, scale, w.pl, w.dZT)
+            if (D == 512) SM_FUSED_LAUNCH(8);
+            else if (D == 256) SM_FUSED_LAUNCH(4);
+            else SM_FUSED_LAUNCH(2);
+#undef SM_FUSED_LAUNCH
+            mark(2);
+            hipLaunchKernelGGL(sm_combine_fused_kernel, dim3((unsigned)ks_ceil_div(B, 32)), dim3(SM_CF_NT), 0, st, w.pl,
+                               n_active, active_idx, target_pos, X, W, Mi, slabs, B, w.Bp, D, scale, w.inv, loss_per_sample,
+                               w.dZT, w.X2, dev_status);
+            mark(3);
+        } else if (soe) {
             const int grid = SM_SOE_GRID / tiles_s * tiles_s, slabs = grid / tiles_s;
 #define SM_SOE_LAUNCH(KT)                                                                                                 \
     do {                                                                                                                  \
@@ -829,7 +1043,6 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
         mark(2);                                                                                                          \
         hipLaunchKernelGGL(sm_combine_soe_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT / 64)), dim3(SM_NT), 0, st, w.pm,    \
                            w.pl, w.zt, n_active, Mi, slabs, B, w.Bp, w.lse, loss_per_sample);                              \
-        hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(SM_NT), 0, st, loss_per_sample, B, loss_mean);                  \
         mark(3);                                                                                                          \
         hipLaunchKernelGGL(sm_grad_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active, target_pos,  \
                            w.lse, B, w.Bp, D, Mi, tiles_s, scale, g, w.dZT);                                               \
@@ -846,7 +1059,6 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
             mark(2);
             hipLaunchKernelGGL(sm_combine_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT / 64)), dim3(SM_NT), 0, st, w.pm, w.pl,
                                w.zt, n_active, Mi, T::BM, B, w.Bp, w.lse, loss_per_sample);
-            hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(SM_NT), 0, st, loss_per_sample, B, loss_mean);
             mark(3);
             hipLaunchKernelGGL(sm_grad_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, X, W, active_idx, n_active, target_pos, w.lse,
                                B, w.Bp, D, Mi, scale, g, w.dZT);
@@ -860,13 +1072,14 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
         }
         mark(5);
         hipLaunchKernelGGL(dx_reduce_kernel, dim3((unsigned)ks_ceil_div((int64_t)B * D / 4, SM_NT)), dim3(SM_NT), 0, st, w.part,
-                           w.S, (int64_t)B * D, scale, dX);
+                           w.S, (int64_t)B * D, fused ? scale * g : scale, fused ? w.inv : (const float *)nullptr, D, dX,
+                           loss_per_sample, B, loss_mean);
         mark(6);
         {
             typedef TileDw T;
             const int tiles = (int)(ks_ceil_div(M, T::BM) * ks_ceil_div(D, T::BN));
-            hipLaunchKernelGGL(dw_async_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, w.dZT, X, B, w.Bp, n_active, D, Mi, w.Mp,
-                               scale, dW_active);
+            hipLaunchKernelGGL(dw_async_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, w.dZT, fused ? w.X2 : X, B, w.Bp, n_active,
+                               D, Mi, w.Mp, fused ? scale * g : scale, dW_active);
         }
         mark(7);
         KS_LAUNCH_CHECK();
@@ -882,7 +1095,6 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
     mark(2);
     hipLaunchKernelGGL(row_stats_kernel, dim3(B), dim3(SM_NT), 0, st, w.Z, w.Mp, n_active, Mi, target_pos, w.lse,
                        loss_per_sample);
-    hipLaunchKernelGGL(loss_mean_kernel, dim3(1), dim3(SM_NT), 0, st, loss_per_sample, B, loss_mean);
     mark(3);
     hipLaunchKernelGGL(dz_kernel, dim3((unsigned)ks_ceil_div(w.Mp, SM_NT * 8), B), dim3(SM_NT), 0, st, w.Z, w.Mp, n_active,
                        Mi, target_pos, w.lse, g, w.dZ);
@@ -891,7 +1103,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
                        n_active, B, D, Mi, w.part);
     mark(5);
     hipLaunchKernelGGL(dx_reduce_kernel, dim3((unsigned)ks_ceil_div((int64_t)B * D / 4, SM_NT)), dim3(SM_NT), 0, st, w.part,
-                       w.S, (int64_t)B * D, scale, dX);
+                       w.S, (int64_t)B * D, scale, (const float *)nullptr, D, dX, loss_per_sample, B, loss_mean);
     mark(6);
     hipLaunchKernelGGL(dw_kernel<T>, dim3(tiles_a_m * tiles_d), dim3(T::NT), 0, st, w.dZ, w.Mp, X, n_active, B, D, Mi,
                        scale, dW_active);
@@ -913,9 +1125,10 @@ extern "C" size_t knn_softmax_workspace(int64_t C, int D, int B, int K, int M) {
 }
 
 static int sm_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels, const int32_t *graph,
-                      int64_t C, int D, int B, int K, int M, float scale, float grad_scale, int32_t *active_idx,
-                      int32_t *n_active, int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
-                      float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream, hipEvent_t *ev) {
+                      int64_t C, int D, int B, int K, int M, float scale, float grad_scale, uint32_t flags,
+                      int32_t *active_idx, int32_t *n_active, int32_t *target_pos, float *loss_per_sample,
+                      float *loss_mean, float *dX, float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status,
+                      void *stream, hipEvent_t *ev) {
     if (!W_bf16 || !X_bf16 || !labels || !active_idx || !n_active || !target_pos || !loss_per_sample || !loss_mean ||
         !dX || !dW_active || !ws)
         return KS_INVALID_ARG;
@@ -931,29 +1144,30 @@ static int sm_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int3
     if (rc != KS_OK) return rc;
     if (ev) (void)hipEventRecord(ev[1], st);
     return sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, active_idx, n_active, target_pos, loss_per_sample,
-                  loss_mean, dX, dW_active, w, st, ev);
+                  loss_mean, dX, dW_active, w, flags, dev_status, st, ev);
 }
 
 extern "C" int knn_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
                                    const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
-                                   float grad_scale, int32_t *active_idx, int32_t *n_active, int32_t *target_pos,
-                                   float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, void *ws,
-                                   size_t ws_bytes, int32_t *dev_status, void *stream) {
-    return sm_fwd_bwd(W_bf16, X_bf16, labels, graph, C, D, B, K, M, scale, grad_scale, active_idx, n_active, target_pos,
-                      loss_per_sample, loss_mean, dX, dW_active, ws, ws_bytes, dev_status, stream, nullptr);
+                                   float grad_scale, uint32_t flags, int32_t *active_idx, int32_t *n_active,
+                                   int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
+                                   float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream) {
+    return sm_fwd_bwd(W_bf16, X_bf16, labels, graph, C, D, B, K, M, scale, grad_scale, flags, active_idx, n_active,
+                      target_pos, loss_per_sample, loss_mean, dX, dW_active, ws, ws_bytes, dev_status, stream, nullptr);
 }
 
 extern "C" int knn_softmax_fwd_bwd_profiled(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
                                             const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
-                                            float grad_scale, int32_t *active_idx, int32_t *n_active,
+                                            float grad_scale, uint32_t flags, int32_t *active_idx, int32_t *n_active,
                                             int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
                                             float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status,
                                             void *stream, void **events, int n_events) {
     if (!events || n_events < KS_N_PHASE_EVENTS) return KS_INVALID_ARG;
     for (int k = 0; k < KS_N_PHASE_EVENTS; ++k)
         if (!events[k]) return KS_INVALID_ARG;
-    return sm_fwd_bwd(W_bf16, X_bf16, labels, graph, C, D, B, K, M, scale, grad_scale, active_idx, n_active, target_pos,
-                      loss_per_sample, loss_mean, dX, dW_active, ws, ws_bytes, dev_status, stream, (hipEvent_t *)events);
+    return sm_fwd_bwd(W_bf16, X_bf16, labels, graph, C, D, B, K, M, scale, grad_scale, flags, active_idx, n_active,
+                      target_pos, loss_per_sample, loss_mean, dX, dW_active, ws, ws_bytes, dev_status, stream,
+                      (hipEvent_t *)events);
 }
 
 extern "C" size_t full_softmax_workspace(int64_t C, int D, int B) {
@@ -965,7 +1179,7 @@ extern "C" size_t full_softmax_workspace(int64_t C, int D, int B) {
 }
 
 extern "C" int full_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels, int64_t C,
-                                    int D, int B, float scale, float grad_scale, float *loss_per_sample,
+                                    int D, int B, float scale, float grad_scale, uint32_t flags, float *loss_per_sample,
                                     float *loss_mean, float *dX, float *dW, void *ws, size_t ws_bytes,
                                     int32_t *dev_status, void *stream) {
     if (!W_bf16 || !X_bf16 || !labels || !loss_per_sample || !loss_mean || !dX || !dW || !ws) return KS_INVALID_ARG;
@@ -982,7 +1196,7 @@ extern "C" int full_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf
     hipLaunchKernelGGL(full_prepare_kernel, dim3((unsigned)ks_ceil_div(n, SM_NT)), dim3(SM_NT), 0, st, labels, C, B,
                        active_idx, n_active, target_pos, dev_status);
     return sm_run(W_bf16, X_bf16, D, B, C, scale, grad_scale, active_idx, n_active, target_pos, loss_per_sample,
-                  loss_mean, dX, dW, w, st);
+                  loss_mean, dX, dW, w, flags, dev_status, st);
 }
 
 extern "C" int knn_gather_rows(const uint16_t *W_bf16, const int32_t *active_idx, const int32_t *n_active, int M,

@@ -66,16 +66,16 @@ def test_graph_sampled_rows_exact(ks, orc, shard):
     assert bool((S[:, 1:] <= S[:, :-1]).all())
 
 
-@pytest.mark.parametrize("name", ["shard390k", "shard390k_uniform"])
-def test_step_full_size(ks, orc, shard, name):
+@pytest.mark.parametrize("name,unit_rows", [("shard390k", True), ("shard390k", False), ("shard390k_uniform", True)])
+def test_step_full_size(ks, orc, shard, name, unit_rows):
     cfg = synth.CONFIGS[name]
     C, D, B, K, M, scale = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"], cfg["scale"]
     W, X, W_bf, graph = shard["W"], shard["X"], shard["W_bf"], shard["graph"]
     y = synth.make_labels(cfg)
     grad_scale, alpha = 128.0, -0.05 / 128.0
-    print(f"[case] {name}: fwd_bwd + apply at full size, B={B} M={M}", flush=True)
+    print(f"[case] {name}: fwd_bwd + apply at full size, B={B} M={M} unit_rows={unit_rows}", flush=True)
     X_bf = torch.from_numpy(X).cuda().to(torch.bfloat16)
-    out = ks.knn_softmax_fwd_bwd(W_bf, X_bf, torch.from_numpy(y).cuda(), graph, M, scale, grad_scale)
+    out = ks.knn_softmax_fwd_bwd(W_bf, X_bf, torch.from_numpy(y).cuda(), graph, M, scale, grad_scale, unit_rows=unit_rows)
     torch.cuda.synchronize()
     assert int(out["dev_status"].item()) == 0
     A = int(out["n_active"].item())

@@ -33,14 +33,22 @@ def rel_fro(a, b):
     return np.linalg.norm(a - b) / den if den > 0 else np.linalg.norm(a - b)
 
 
-def run_and_compare(ks, orc, W, X, y, G, C, M, scale=30.0, grad_scale=1.0, tag=""):
-    """W, X fp32 arrays on the bf16 grid.  Runs both sides and checks every output."""
-    print(f"[case] {tag} C={C} D={W.shape[1]} B={X.shape[0]} K={G.shape[1]} M={M}", flush=True)
-    out = ks.knn_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(G), M, scale, grad_scale)
-    torch.cuda.synchronize()
-    assert int(out["dev_status"].item()) == 0
+def run_and_compare(ks, orc, W, X, y, G, C, M, scale=30.0, grad_scale=1.0, tag="", modes=(False, True)):
+    """W, X fp32 arrays on the bf16 grid.  Runs both sides and checks every output, without and with the
+    unit-rows promise (the one-sweep softmax; the same results are required).  Returns the last mode's output."""
     active, A, tpos = orc.select_active(y, G, C, M)
     ref = orc.knn_softmax_fwd_bwd(W, X, active[:A], tpos, scale, grad_scale)
+    for unit_rows in modes:
+        out = _run_and_compare_one(ks, W, X, y, G, C, M, scale, grad_scale, tag, unit_rows, active, A, tpos, ref)
+    return out, ref, A
+
+
+def _run_and_compare_one(ks, W, X, y, G, C, M, scale, grad_scale, tag, unit_rows, active, A, tpos, ref):
+    print(f"[case] {tag} C={C} D={W.shape[1]} B={X.shape[0]} K={G.shape[1]} M={M} unit_rows={unit_rows}", flush=True)
+    out = ks.knn_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(G), M, scale, grad_scale,
+                                 unit_rows=unit_rows)
+    torch.cuda.synchronize()
+    assert int(out["dev_status"].item()) == 0
     assert int(out["n_active"].item()) == A
     assert (out["active_idx"].cpu().numpy() == active).all()
     assert (out["target_pos"].cpu().numpy() == tpos).all()
@@ -52,7 +60,7 @@ def run_and_compare(ks, orc, W, X, y, G, C, M, scale=30.0, grad_scale=1.0, tag="
     e_dw = rel_fro(out["dW_active"][:A].cpu().numpy(), ref["dWA"])
     print(f"        A={A} loss={loss:.6f} ref={ref['loss']:.6f} relF(dX)={e_dx:.2e} relF(dW)={e_dw:.2e}", flush=True)
     assert e_dx <= GRAD_RTOL and e_dw <= GRAD_RTOL
-    return out, ref, A
+    return out
 
 
 # ------------------------------------------------------------------------------------------------
@@ -153,9 +161,9 @@ def test_knn_equals_full_softmax_when_lists_span_all_classes(ks, orc):
     G = synth.graph_all_others(C)
     out, ref, A = run_and_compare(ks, orc, W, X, y, G, C, C, tag="K=C-1")
     assert A == C
-    full = ks.full_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), 30.0, 1.0)
+    full = ks.full_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), 30.0, 1.0, unit_rows=True)
     torch.cuda.synchronize()
-    # same kernels, same active list => bit-identical
+    # same kernels (the last mode run above is the unit-rows one), same active list => bit-identical
     assert torch.equal(full["loss_per_sample"], out["loss_per_sample"])
     assert torch.equal(full["dX"], out["dX"])
     assert torch.equal(full["dW"], out["dW_active"])
@@ -164,27 +172,30 @@ def test_knn_equals_full_softmax_when_lists_span_all_classes(ks, orc):
     assert rel_fro(full["dW"].cpu().numpy(), ofull["dW"]) <= GRAD_RTOL
 
 
-def test_full_softmax_on_20000_class_slice(ks, orc):
+@pytest.mark.parametrize("unit_rows", [False, True])
+def test_full_softmax_on_20000_class_slice(ks, orc, unit_rows):
     C, D, B = 20_000, 512, 64
     W = synth.unit_rows(0, synth.TID_W, C, D, bf16=True)
     X = synth.unit_rows(0, synth.TID_X, B, D, bf16=True)
     y = synth.labels_uniform(0, B, C)
-    full = ks.full_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), 30.0, 1.0)
+    full = ks.full_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), 30.0, 1.0, unit_rows=unit_rows)
     torch.cuda.synchronize()
+    assert int(full["dev_status"].item()) == 0
     ref = orc.full_softmax_fwd_bwd(W, X, y, 30.0, 1.0)
     assert abs(float(full["loss_mean"].item()) - ref["loss"]) <= LOSS_RTOL * ref["loss"]
     assert rel_fro(full["dX"].cpu().numpy(), ref["dX"]) <= GRAD_RTOL
     assert rel_fro(full["dW"].cpu().numpy(), ref["dW"]) <= GRAD_RTOL
 
 
-def test_fwd_bwd_is_deterministic_and_softmax_invariants_hold(ks, orc):
+@pytest.mark.parametrize("unit_rows", [False, True])
+def test_fwd_bwd_is_deterministic_and_softmax_invariants_hold(ks, orc, unit_rows):
     cfg = synth.CONFIGS["small"]
     W, X = synth.make_WX(cfg)
     y = synth.make_labels(cfg)
     G = synth.graph_synthetic(1, cfg["C"], cfg["K"])
     args = (dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(G), cfg["M"], 30.0, 1.0)
-    o1 = ks.knn_softmax_fwd_bwd(*args)
-    o2 = ks.knn_softmax_fwd_bwd(*args)
+    o1 = ks.knn_softmax_fwd_bwd(*args, unit_rows=unit_rows)
+    o2 = ks.knn_softmax_fwd_bwd(*args, unit_rows=unit_rows)
     torch.cuda.synchronize()
     for k in ("active_idx", "n_active", "target_pos", "loss_per_sample", "loss_mean", "dX", "dW_active"):
         n = int(o1["n_active"].item()) if k == "dW_active" else None
@@ -193,6 +204,38 @@ def test_fwd_bwd_is_deterministic_and_softmax_invariants_hold(ks, orc):
     # sum_a dZ_ia = 0 => column sums of dW_active vanish (up to bf16 rounding of dZ)
     dW = o1["dW_active"][:A].double()
     assert dW.sum(dim=0).abs().max().item() <= 1e-3 * dW.abs().sum(dim=0).max().item()
+
+
+def test_unit_rows_promise_with_longer_rows_still_gives_the_same_function(ks, orc):
+    # rows 15 % longer than promised: logits reach 1.32 * scale, the fixed reference only shifts the exponents
+    # (half of the samples sit near their class weight, so that some logits do exceed the scale)
+    C, D, B, K, M = 6_000, 256, 300, 8, 1_500
+    W = synth.bf16_round(1.15 * synth.unit_rows(11, synth.TID_W, C, D))
+    y = synth.labels_uniform(11, B, C)
+    X = synth.features_near_labels(11, W / 1.15, y, sigma=0.6)
+    X[1::2] = synth.unit_rows(11, synth.TID_X, B, D)[1::2]
+    X = synth.bf16_round(1.15 * X)
+    assert (30.0 * (X * W[y]).sum(axis=1)).max() > 31.0
+    G = synth.graph_synthetic(11, C, K, locality=3)
+    run_and_compare(ks, orc, W, X, y, G, C, M, tag="long rows", modes=(True,))
+
+
+def test_unit_rows_promise_broken_beyond_the_exponent_range_is_flagged(ks, orc):
+    # rows of norm 2 at scale 40: target logits near 160, exp(160 - 40) overflows
+    C, D, B, K, M = 2_000, 128, 64, 4, 512
+    W0 = synth.unit_rows(12, synth.TID_W, C, D)
+    y = synth.labels_uniform(12, B, C)
+    X = synth.bf16_round(2.0 * synth.features_near_labels(12, W0, y, sigma=0.05))
+    W = synth.bf16_round(2.0 * W0)
+    out = ks.knn_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(synth.graph_synthetic(12, C, K)),
+                                 M, 40.0, unit_rows=True)
+    torch.cuda.synchronize()
+    assert int(out["dev_status"].item()) & ks.KS_DEV_RANGE
+    # without the promise the same inputs are handled
+    out = ks.knn_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(synth.graph_synthetic(12, C, K)),
+                                 M, 40.0)
+    torch.cuda.synchronize()
+    assert int(out["dev_status"].item()) == 0 and bool(torch.isfinite(out["loss_mean"]).all())
 
 
 def test_bad_label_sets_flag_and_stays_in_bounds(ks, orc):
