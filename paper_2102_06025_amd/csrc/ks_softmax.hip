@@ -882,12 +882,53 @@ dx_partial_async_kernel(const uint16_t *__restrict__ dZT, int Bp, int64_t Mp, co
     });
 }
 
-// dW_active[a][d] = scale * sum_i dZT[a][i] * X[i][d] on the asynchronous engine (X k-major, k = i)
+// dW_active[a][d] = scale * sum_i dZT[a][i] * X[i][d] on the asynchronous engine (X k-major, k = i).
+// The grid is sized for M rows, so with fewer active rows part of the chip would idle; the last
+// DW_REDUCE_BLOCKS blocks of the grid therefore do a job that is due anyway and does not depend on this
+// kernel: the sum of the dX partial products of the kernel before (with the per-sample factor, if any) and
+// the batch mean of the losses.  They land on the compute units the tiles leave free.
+#define DW_REDUCE_BLOCKS 128
+struct DxReduceJob {
+    const float *part; // [S][B * D] partial sums
+    int S;
+    int64_t BD;
+    float scale;
+    const float *row_factor; // [B] or nullptr
+    float *dX;
+    const float *loss_i;
+    float *loss_mean;
+};
 template <class T>
 __global__ void __launch_bounds__(T::NT)
 dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X, int B, int Bp,
-                const int32_t *__restrict__ n_active_p, int D, int M, int64_t Mp, float scale, float *__restrict__ dW) {
+                const int32_t *__restrict__ n_active_p, int D, int M, int64_t Mp, float scale, float *__restrict__ dW,
+                int tiles_max, DxReduceJob job) {
     __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
+    if ((int)blockIdx.x >= tiles_max) { // reduction blocks
+        const int rb = blockIdx.x - tiles_max, nrb = gridDim.x - tiles_max;
+        for (int64_t e = ((int64_t)rb * T::NT + threadIdx.x) * 4; e < job.BD; e += (int64_t)nrb * T::NT * 4) {
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int sp = 0; sp < job.S; ++sp) {
+                const float4 v = *(const float4 *)(job.part + (int64_t)sp * job.BD + e);
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
+            const float f = job.row_factor ? job.scale * job.row_factor[e / D] : job.scale;
+            *(float4 *)(job.dX + e) = make_float4(f * acc.x, f * acc.y, f * acc.z, f * acc.w);
+        }
+        if (rb == nrb - 1) { // thread t takes samples t, t + NT, ..., then a tree: a fixed order
+            float *sh = (float *)lds;
+            float sum = 0.f;
+            for (int i = threadIdx.x; i < B; i += T::NT) sum += job.loss_i[i];
+            sh[threadIdx.x] = sum;
+            __syncthreads();
+            for (int o = T::NT / 2; o > 0; o >>= 1) {
+                if ((int)threadIdx.x < o) sh[threadIdx.x] += sh[threadIdx.x + o];
+                __syncthreads();
+            }
+            if (threadIdx.x == 0) *job.loss_mean = sh[0] / (float)B;
+        }
+        return;
+    }
     const int n_active = sm_clamp_n(n_active_p, M);
     const int tiles_n = (D + T::BN - 1) / T::BN;
     const int n_tiles = tiles_n * ((n_active + T::BM - 1) / T::BM);
@@ -1071,15 +1112,21 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
                                active_idx, n_active, B, D, Mi, w.S, w.part);
         }
         mark(5);
-        hipLaunchKernelGGL(dx_reduce_kernel, dim3((unsigned)ks_ceil_div((int64_t)B * D / 4, SM_NT)), dim3(SM_NT), 0, st, w.part,
-                           w.S, (int64_t)B * D, fused ? scale * g : scale, fused ? w.inv : (const float *)nullptr, D, dX,
-                           loss_per_sample, B, loss_mean);
-        mark(6);
+        mark(6); // the reduction of the partial products rides along with the next launch
         {
             typedef TileDw T;
             const int tiles = (int)(ks_ceil_div(M, T::BM) * ks_ceil_div(D, T::BN));
-            hipLaunchKernelGGL(dw_async_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, w.dZT, fused ? w.X2 : X, B, w.Bp, n_active,
-                               D, Mi, w.Mp, fused ? scale * g : scale, dW_active);
+            DxReduceJob job;
+            job.part = w.part;
+            job.S = w.S;
+            job.BD = (int64_t)B * D;
+            job.scale = fused ? scale * g : scale;
+            job.row_factor = fused ? w.inv : nullptr;
+            job.dX = dX;
+            job.loss_i = loss_per_sample;
+            job.loss_mean = loss_mean;
+            hipLaunchKernelGGL(dw_async_kernel<T>, dim3(tiles + DW_REDUCE_BLOCKS), dim3(T::NT), 0, st, w.dZT, fused ? w.X2 : X,
+                               B, w.Bp, n_active, D, Mi, w.Mp, fused ? scale * g : scale, dW_active, tiles, job);
         }
         mark(7);
         KS_LAUNCH_CHECK();
