@@ -236,13 +236,17 @@ sel_finish_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict_
 }
 
 // ------------------------------------------------------------------------------------------------
-// Whole selection in ONE workgroup when the class bitmap fits in LDS (C <= SEL1_MAX_WORDS * 32):
+// Whole selection inside a workgroup when the class bitmap fits in LDS (C <= SEL1_MAX_WORDS * 32):
 // candidates are marked in an LDS bitmap (duplicates collapse in the atomic OR), the ascending list is the
 // bitmap read out in order, positions are prefix popcounts.  Only when more than M classes are marked
 // is the list-position order needed; then the bitmap is rebuilt position by position (r = 0, 1, ...)
 // until adding the classes first seen at position r would exceed M; of those, the lowest ids fill up.
+// SEL1_GRID workgroups all do this same LDS work and differ only in which slice of the outputs they
+// write: the global stores and their latency are spread over several compute units with no
+// synchronisation between workgroups.
 // ------------------------------------------------------------------------------------------------
 #define SEL1_NT 1024
+#define SEL1_GRID 32
 #define SEL1_MAX_WORDS SEL1_MAX_WORDS_HOST
 
 // Stage 1 (many workgroups, so that the scattered reads of the neighbour lists are spread over the chip):
@@ -298,17 +302,18 @@ sel_single_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict_
     const int tid = threadIdx.x;
     for (int w = tid; w < nw; w += SEL1_NT) bm[w] = 0u;
     __syncthreads();
-    // optimistic pass: every candidate, whatever its list position (eight loads in flight per thread)
+    // optimistic pass: every candidate, whatever its list position (sixteen loads in flight per thread: the
+    // round trips to L2 are what this phase costs)
     const int64_t n_cand = (int64_t)B * (K + 1);
-    for (int64_t t0 = 0; t0 < n_cand; t0 += (int64_t)SEL1_NT * 8) {
-        int32_t c[8];
+    for (int64_t t0 = 0; t0 < n_cand; t0 += (int64_t)SEL1_NT * 16) {
+        int32_t c[16];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
+        for (int e = 0; e < 16; ++e) {
             const int64_t t = t0 + (int64_t)e * SEL1_NT + tid;
             c[e] = t < n_cand ? cand[t] : -1;
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
+        for (int e = 0; e < 16; ++e)
             if (c[e] >= 0) atomicOr(&bm[c[e] >> 5], 1u << (c[e] & 31));
     }
     __syncthreads();
@@ -365,10 +370,13 @@ sel_single_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict_
         __syncthreads();
         total = sel1_prefix(bm, nw, pre, sh);
     }
-    // read the bitmap out in ascending order
-    {
-        const int per = (nw + SEL1_NT - 1) / SEL1_NT;
-        for (int w = tid * per; w < tid * per + per && w < nw; ++w) {
+    // Every workgroup of the grid has built the same bitmap and prefix (redundantly: it is LDS work, and it
+    // spares a grid-wide synchronisation); each writes its share of the outputs.
+    const int G = gridDim.x, g = blockIdx.x;
+    { // read the bitmap out in ascending order: this workgroup's slice of the words, one word per thread
+        const int per_g = (nw + G - 1) / G;
+        const int w_end = (g + 1) * per_g < nw ? (g + 1) * per_g : nw;
+        for (int w = g * per_g + tid; w < w_end; w += SEL1_NT) {
             uint32_t e = bm[w];
             int pos = pre[w];
             while (e) {
@@ -380,14 +388,14 @@ sel_single_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict_
         }
     }
     const int n = total < M ? total : M;
-    for (int a = n + tid; a < M; a += SEL1_NT) active_idx[a] = -1;
-    for (int i = tid; i < B; i += SEL1_NT) {
+    for (int a = n + g * SEL1_NT + tid; a < M; a += G * SEL1_NT) active_idx[a] = -1;
+    for (int i = g * SEL1_NT + tid; i < B; i += G * SEL1_NT) {
         const int32_t y = labels[i];
         int p = 0;
         if (y >= 0 && y < C) p = pre[y >> 5] + __popc(bm[y >> 5] & ((1u << (y & 31)) - 1u));
         target_pos[i] = (p >= 0 && p < n) ? p : 0;
     }
-    if (tid == 0) *n_active = n;
+    if (g == 0 && tid == 0) *n_active = n;
 }
 
 int ks_select_launch(const int32_t *labels, const int32_t *graph, int64_t C, int B, int K, int M,
@@ -398,8 +406,8 @@ int ks_select_launch(const int32_t *labels, const int32_t *graph, int64_t C, int
         const int64_t n_cand = (int64_t)B * (K + 1);
         hipLaunchKernelGGL(sel_fetch_kernel, dim3((unsigned)ks_ceil_div(n_cand, SEL_NT)), dim3(SEL_NT), 0, st, labels, graph, C, B,
                            K, cand, dev_status);
-        hipLaunchKernelGGL(sel_single_kernel, dim3(1), dim3(SEL1_NT), 0, st, labels, cand, C, B, K, M, active_idx, n_active,
-                           target_pos);
+        hipLaunchKernelGGL(sel_single_kernel, dim3(SEL1_GRID), dim3(SEL1_NT), 0, st, labels, cand, C, B, K, M, active_idx,
+                           n_active, target_pos);
         KS_LAUNCH_CHECK();
         return KS_OK;
     }

@@ -757,18 +757,38 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
     {
         float part = 0.f, dot = 0.f;
         if (i < B) {
-            for (int t = gq; t < nt; t += 8) part += pl[(int64_t)t * Bp + i];
+            // all loads of a batch are issued before the first use: these are dependent only through the
+            // running sums, and one round trip to another L2 costs as much as everything else here
             tp = target_pos[i];
             tp = tp < 0 ? 0 : (tp >= n ? n - 1 : tp); // stays in bounds whatever the selection flagged
-            const uint16_t *xr = X + (int64_t)i * D + gq * (D / 8);
-            const uint16_t *wr = W + (int64_t)active_idx[tp] * D + gq * (D / 8);
-            for (int d = 0; d < D / 8; d += 8) { // D % 64 == 0 on this path
-                const uint4 xv = *(const uint4 *)(xr + d), wv = *(const uint4 *)(wr + d);
-                const uint32_t xa[4] = {xv.x, xv.y, xv.z, xv.w}, wa[4] = {wv.x, wv.y, wv.z, wv.w};
+            const int cls = active_idx[tp];
+            for (int t0 = gq; t0 < nt; t0 += 64) {
+                float v[8];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    dot = fmaf(ks_bf2f(xa[q] & 0xFFFFu), ks_bf2f(wa[q] & 0xFFFFu), dot);
-                    dot = fmaf(ks_bf2f(xa[q] >> 16), ks_bf2f(wa[q] >> 16), dot);
+                for (int q = 0; q < 8; ++q) v[q] = (t0 + 8 * q < nt) ? pl[(int64_t)(t0 + 8 * q) * Bp + i] : 0.f;
+#pragma unroll
+                for (int q = 0; q < 8; ++q) part += v[q];
+            }
+            const uint16_t *xr = X + (int64_t)i * D + gq * (D / 8);
+            const uint16_t *wr = W + (int64_t)cls * D + gq * (D / 8);
+            const int pieces = D / 64; // 16-byte pieces per thread; D is 128, 256 or 512 on this path
+            uint4 xv[8], wv[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (q < pieces) {
+                    xv[q] = *(const uint4 *)(xr + q * 8);
+                    wv[q] = *(const uint4 *)(wr + q * 8);
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                if (q < pieces) {
+                    const uint32_t xa[4] = {xv[q].x, xv[q].y, xv[q].z, xv[q].w}, wa[4] = {wv[q].x, wv[q].y, wv[q].z, wv[q].w};
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        dot = fmaf(ks_bf2f(xa[c] & 0xFFFFu), ks_bf2f(wa[c] & 0xFFFFu), dot);
+                        dot = fmaf(ks_bf2f(xa[c] >> 16), ks_bf2f(wa[c] >> 16), dot);
+                    }
                 }
             }
         }
@@ -800,16 +820,27 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
     __syncthreads();
     const int rows = (B - blockIdx.x * 32 < 32) ? B - blockIdx.x * 32 : 32;
     const int per_row = D / 8; // 16-byte pieces per row
-    for (int q = threadIdx.x; q < rows * per_row; q += SM_CF_NT) {
-        const int r = q / per_row, c = q % per_row;
-        const float f = s_inv[r];
-        const uint4 v = *(const uint4 *)(X + ((int64_t)blockIdx.x * 32 + r) * D + c * 8);
-        uint4 o;
-        o.x = ks_pack_bf2(ks_bf2f(v.x & 0xFFFFu) * f, ks_bf2f(v.x >> 16) * f);
-        o.y = ks_pack_bf2(ks_bf2f(v.y & 0xFFFFu) * f, ks_bf2f(v.y >> 16) * f);
-        o.z = ks_pack_bf2(ks_bf2f(v.z & 0xFFFFu) * f, ks_bf2f(v.z >> 16) * f);
-        o.w = ks_pack_bf2(ks_bf2f(v.w & 0xFFFFu) * f, ks_bf2f(v.w >> 16) * f);
-        *(uint4 *)(X2 + ((int64_t)blockIdx.x * 32 + r) * D + c * 8) = o;
+    const int total = rows * per_row;
+    const uint16_t *xb = X + (int64_t)blockIdx.x * 32 * D; // the block's rows are contiguous
+    uint16_t *ob = X2 + (int64_t)blockIdx.x * 32 * D;
+    for (int q0 = threadIdx.x; q0 < total; q0 += 4 * SM_CF_NT) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (q0 + u * SM_CF_NT < total) v[u] = *(const uint4 *)(xb + (int64_t)(q0 + u * SM_CF_NT) * 8);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = q0 + u * SM_CF_NT;
+            if (q < total) {
+                const float f = s_inv[q / per_row];
+                uint4 o;
+                o.x = ks_pack_bf2(ks_bf2f(v[u].x & 0xFFFFu) * f, ks_bf2f(v[u].x >> 16) * f);
+                o.y = ks_pack_bf2(ks_bf2f(v[u].y & 0xFFFFu) * f, ks_bf2f(v[u].y >> 16) * f);
+                o.z = ks_pack_bf2(ks_bf2f(v[u].z & 0xFFFFu) * f, ks_bf2f(v[u].z >> 16) * f);
+                o.w = ks_pack_bf2(ks_bf2f(v[u].w & 0xFFFFu) * f, ks_bf2f(v[u].w >> 16) * f);
+                *(uint4 *)(ob + (int64_t)q * 8) = o;
+            }
+        }
     }
 }
 
