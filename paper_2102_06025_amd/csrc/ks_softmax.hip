@@ -661,7 +661,7 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
     const int lim = n < s1 ? n : s1; // rows of this slab that are real classes
     int col[2];
     bool ok[2];
-    float l[2] = {0.f, 0.f};
+    float l[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int fn = 0; fn < 2; ++fn) {
         col[fn] = ks_soe_col(fn);
@@ -698,37 +698,46 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
         }
         __builtin_amdgcn_s_waitcnt(0xC07F); // LDS writes done (lgkmcnt 0); loads in flight are left alone
         ks_barrier_nofence();
-        // sums over the class rows of the rounded values, as the two gradient contractions will read them:
-        // thread t takes the sample pair t % 128 and the rows of parity t / 128
-        {
-            const int pr = threadIdx.x & 127;
-            float lo = 0.f, hi = 0.f;
-            for (int r = threadIdx.x >> 7; r < rows_here; r += 2) {
-                const uint32_t v = *(const uint32_t *)(stage + r * STAGE_LD + 2 * pr);
-                lo += ks_bf2f(v & 0xFFFFu);
-                hi += ks_bf2f(v >> 16);
+        // copy the chunk out in 16-byte pieces: thread t always takes the same eight samples (piece t % 32 of a
+        // row) of the rows t / 32, t / 32 + 8, ..., so it can also carry the sums over the class rows of those
+        // samples -- of the rounded values, as the two gradient contractions will read them
+        constexpr int PPR = CFG::RES / 8; // pieces per row
+        const int ch = threadIdx.x % PPR;
+        for (int r0 = threadIdx.x / PPR; r0 < rows_here; r0 += 4 * (256 / PPR)) {
+            uint4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int row = r0 + u * (256 / PPR);
+                v[u] = (row < rows_here) ? *(const uint4 *)(stage + row * STAGE_LD + ch * 8) : make_uint4(0u, 0u, 0u, 0u);
             }
-            l[0] += lo;
-            l[1] += hi;
-        }
-        const int chunks = rows_here * (CFG::RES / 8);
-        for (int q = threadIdx.x; q < chunks; q += 256) {
-            const int row = q / (CFG::RES / 8), ch = q % (CFG::RES / 8);
-            *(uint4 *)(dZT + (int64_t)(c0 + row) * Bp + ts * CFG::RES + ch * 8) = *(const uint4 *)(stage + row * STAGE_LD + ch * 8);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int row = r0 + u * (256 / PPR);
+                if (row < rows_here) *(uint4 *)(dZT + (int64_t)(c0 + row) * Bp + ts * CFG::RES + ch * 8) = v[u];
+                const uint32_t w4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    l[2 * c] += ks_bf2f(w4[c] & 0xFFFFu);
+                    l[2 * c + 1] += ks_bf2f(w4[c] >> 16);
+                }
+            }
         }
     };
     ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi);
-    // the two row parities of a sample pair meet through LDS (the stream stages are free now)
+    // the eight row groups of a sample meet through LDS (the stream stages are free now): red[group][sample]
     float *red = (float *)lds;
-    if (threadIdx.x >= 128) {
-        red[2 * (threadIdx.x - 128)] = l[0];
-        red[2 * (threadIdx.x - 128) + 1] = l[1];
+    {
+        const int grp = threadIdx.x / (CFG::RES / 8), ch = threadIdx.x % (CFG::RES / 8);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) red[grp * CFG::RES + ch * 8 + c] = l[c];
     }
     __syncthreads();
-    if (threadIdx.x < 128) {
-        const int i0 = ts * CFG::RES + 2 * threadIdx.x;
-        if (i0 < B) pl[(int64_t)slab * Bp + i0] = l[0] + red[2 * threadIdx.x];
-        if (i0 + 1 < B) pl[(int64_t)slab * Bp + i0 + 1] = l[1] + red[2 * threadIdx.x + 1];
+    {
+        const int i = ts * CFG::RES + threadIdx.x; // RES == blockDim.x: one sample per thread
+        float sum = 0.f;
+#pragma unroll
+        for (int grp = 0; grp < 8; ++grp) sum += red[grp * CFG::RES + threadIdx.x];
+        if (i < B) pl[(int64_t)slab * Bp + i] = sum;
     }
 }
 
