@@ -43,10 +43,15 @@ __device__ __forceinline__ int ks_soe_col(int fn) { return (threadIdx.x >> 6) * 
 // S: streamed operand; streamed row index g in [s_begin, s_end) maps to memory row gidx ? gidx[g'] : g'
 // with g' = min(g, s_clamp - 1).  epi(chunk_first_row, rows_in_chunk, acc) is called once per chunk by all
 // threads; it may use barriers (all threads call it) but must not touch the stream stages in `lds`.
+// lidx / lidx_cap: optional LDS array of the caller's in which the sweep keeps its part of the gather list
+// (used when the sweep's rows, rounded up to whole chunks, fit).  Without it the list is read from global
+// memory once per chunk, and waiting for that read means waiting for every stream load issued before it:
+// the wait counter of vector-memory instructions is shared.
 template <class CFG, class Epi>
 __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int64_t ldr, int r_row0, int r_limit,
                                              const uint16_t *__restrict__ S, int64_t lds_ld, const int32_t *__restrict__ gidx,
-                                             int s_begin, int s_end, int s_clamp, uint16_t *lds, Epi &epi) {
+                                             int s_begin, int s_end, int s_clamp, uint16_t *lds, Epi &epi,
+                                             int32_t *lidx = nullptr, int lidx_cap = 0) {
     constexpr int KT = CFG::KT, ST = CFG::STAGES, NI = CFG::NI, FM = CFG::FM;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -72,22 +77,35 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
                     bres[fn][kt * 4 + kk] =
                         *(const bf16x8_t *)(st + (wave * 64 + fn * 32 + r31) * 64 + (((kk * 2 + khalf) ^ swz) * 8));
         }
-        __builtin_amdgcn_s_waitcnt(0xC07F); // the fragment reads have returned before the stages are reused
-        ks_barrier_nofence();
     }
 
     // ---- stream state ---------------------------------------------------------------------------------------
     const int n_chunks = (s_end - s_begin + CFG::CH - 1) / CFG::CH;
     const int n_tiles = n_chunks * (KT / CFG::KSUB); // pipeline stages in the whole sweep
+    const bool use_lidx = gidx && lidx && n_chunks * CFG::CH <= lidx_cap;
+    if (use_lidx) {
+        for (int i = threadIdx.x; i < n_chunks * CFG::CH; i += CFG::NT) {
+            int g = s_begin + i;
+            if (g >= s_clamp) g = s_clamp - 1;
+            lidx[i] = gidx[g];
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0xC07F); // the fragment reads have returned before the stages are reused
+    __syncthreads();                    // (also publishes the gather list)
     const int chunk_slot = (lane & 7) ^ 0; // 16-byte slot of this lane inside a 128-byte LDS row
     const uint16_t *ptr[NI];               // row pointers (k = 0, swizzled chunk) of the chunk being issued
     auto chunk_ptrs = [&](int c) {
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int row = (j * CFG::NW + wave) * 8 + (lane >> 3);
-            int g = s_begin + c * CFG::CH + row;
-            if (g >= s_clamp) g = s_clamp - 1;
-            const int64_t src = gidx ? (int64_t)gidx[g] : (int64_t)g;
+            int64_t src;
+            if (use_lidx) {
+                src = lidx[c * CFG::CH + row];
+            } else {
+                int g = s_begin + c * CFG::CH + row;
+                if (g >= s_clamp) g = s_clamp - 1;
+                src = gidx ? (int64_t)gidx[g] : (int64_t)g;
+            }
             ptr[j] = S + src * lds_ld + ((chunk_slot ^ ((row >> 1) & 7)) * 8);
         }
     };

@@ -20,6 +20,7 @@ typedef KsATile<128, 128, 2, 2, 2> TileDx;
 #define DX_IDX_CACHE 4096 /* gather indices of one workgroup's share of the active dimension, staged in LDS */
 typedef KsATile<256, 256, 2, 4, 2> TileDw;
 #define KS_BP_ALIGN 256
+#define SM_LIDX_CAP 1536 // gather-list entries a sweep keeps in LDS (longer slabs read the list from memory)
 #define SM_SOE_GRID 256 /* workgroups of the stationary-operand softmax passes (one per compute unit) */
 
 #define SM_NT 256
@@ -450,6 +451,7 @@ sm_stats_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
                     int tiles_s, float scale, float *__restrict__ pm, float *__restrict__ pl, float *__restrict__ zt) {
     typedef KsSoe<KT, 96, SOE_STAGES, 2> CFG;
     __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
+    __shared__ int32_t s_lidx[SM_LIDX_CAP];
     const int n = sm_clamp_n(n_active_p, M);
     const int n64 = (n + 63) & ~63;
     const int slabs = gridDim.x / tiles_s;
@@ -529,7 +531,7 @@ sm_stats_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
             }
         }
     };
-    ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi);
+    ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi, s_lidx, SM_LIDX_CAP);
 #pragma unroll
     for (int fn = 0; fn < 2; ++fn) {
         // the two half-waves hold disjoint class rows of the same 32 samples
@@ -553,6 +555,7 @@ sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
     typedef KsSoe<KT, 96, SOE_STAGES, 2> CFG;
     constexpr int STAGE_LD = CFG::RES + 8;
     __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
+    __shared__ int32_t s_lidx[SM_LIDX_CAP];
     __shared__ __attribute__((aligned(16))) uint16_t stage[CFG::CH * STAGE_LD];
     const int n = sm_clamp_n(n_active_p, M);
     const int n64 = (n + 63) & ~63;
@@ -562,18 +565,13 @@ sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
     const int ts = id % tiles_s, slab = id / tiles_s;
     const int s0 = slab * h, s1 = (s0 + h < n64) ? s0 + h : n64;
     if (slab >= slabs || s0 >= s1) return;
-    const int lane = threadIdx.x & 63;
-    const bool odd = lane & 1;
-    int col[2], tp[2];
+    int tp[2];
     float ls[2];
-    bool ok[2];
 #pragma unroll
     for (int fn = 0; fn < 2; ++fn) {
-        col[fn] = ks_soe_col(fn);
-        const int i = ts * CFG::RES + col[fn];
-        ok[fn] = i < B;
-        ls[fn] = ok[fn] ? lse[i] : 0.f;
-        tp[fn] = ok[fn] ? target_pos[i] : -1;
+        const int i = ts * CFG::RES + ks_soe_col(fn);
+        ls[fn] = i < B ? lse[i] : 0.f;
+        tp[fn] = i < B ? target_pos[i] : -1;
     }
     // scale > 0 and g > 0 (checked by the host): g * exp(scale * acc - lse) = exp2(fma(acc, k1, k2)) with
     // k2 = log2(g) - lse * log2(e): one fused multiply-add and one exponential per element
@@ -584,6 +582,21 @@ sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
     const bool samples_ok = (ts + 1) * CFG::RES <= B;
     auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM][2]) {
         const bool plain = samples_ok && c0 + CFG::CH <= n; // no row or column of this chunk needs masking
+        // Everything derived from the thread index is derived afresh here, from a copy the compiler cannot see
+        // through: otherwise it hoists the dozens of LDS addresses below out of the sweep, runs out of
+        // registers and spills them -- and every reload of a spilled value is a vector-memory load whose wait
+        // also waits for the stream loads in flight.
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        const int lane = tid & 63;
+        const bool odd = lane & 1;
+        int col[2];
+        bool ok[2];
+#pragma unroll
+        for (int fn = 0; fn < 2; ++fn) {
+            col[fn] = (tid >> 6) * 64 + fn * 32 + (tid & 31);
+            ok[fn] = ts * CFG::RES + col[fn] < B;
+        }
 #pragma unroll
         for (int fn = 0; fn < 2; ++fn) {
             // does any sample of this wavefront have its label inside the chunk?  (about one chunk in three)
@@ -619,12 +632,12 @@ sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
         __builtin_amdgcn_s_waitcnt(0xC07F); // LDS writes done (lgkmcnt 0); loads in flight are left alone
         ks_barrier_nofence();
         const int chunks = rows_here * (CFG::RES / 8);
-        for (int q = threadIdx.x; q < chunks; q += 256) {
+        for (int q = tid; q < chunks; q += 256) {
             const int row = q / (CFG::RES / 8), ch = q % (CFG::RES / 8);
             *(uint4 *)(dZT + (int64_t)(c0 + row) * Bp + ts * CFG::RES + ch * 8) = *(const uint4 *)(stage + row * STAGE_LD + ch * 8);
         }
     };
-    ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi);
+    ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi, s_lidx, SM_LIDX_CAP);
 }
 
 
@@ -647,6 +660,7 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
     typedef KsSoe<KT, 96, SOE_STAGES, 2> CFG;
     constexpr int STAGE_LD = CFG::RES + 8;
     __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
+    __shared__ int32_t s_lidx[SM_LIDX_CAP];
     __shared__ __attribute__((aligned(16))) uint16_t stage[CFG::CH * STAGE_LD];
     const int n = sm_clamp_n(n_active_p, M);
     const int n64 = (n + 63) & ~63;
@@ -656,22 +670,30 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
     const int ts = id % tiles_s, slab = id / tiles_s;
     const int s0 = slab * h, s1 = (s0 + h < n64) ? s0 + h : n64;
     if (slab >= slabs || s0 >= s1) return;
-    const int lane = threadIdx.x & 63;
-    const bool odd = lane & 1;
     const int lim = n < s1 ? n : s1; // rows of this slab that are real classes
-    int col[2];
-    bool ok[2];
-    float l[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    __shared__ float s_sum[8 * 256]; // thread t: running sums of its eight samples over its rows, at [c * 256 + t]
 #pragma unroll
-    for (int fn = 0; fn < 2; ++fn) {
-        col[fn] = ks_soe_col(fn);
-        ok[fn] = ts * CFG::RES + col[fn] < B;
-    }
+    for (int c = 0; c < 8; ++c) s_sum[c * 256 + threadIdx.x] = 0.f;
     // exp(scale * acc - scale) = exp2(fma(acc, k1, -k1))
     const float k1 = scale * 1.4426950408889634f;
     const bool samples_ok = (ts + 1) * CFG::RES <= B;
     auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM][2]) {
         const bool plain = samples_ok && c0 + CFG::CH <= lim; // no row or column of this chunk needs masking
+        // Everything derived from the thread index is derived afresh here, from a copy the compiler cannot see
+        // through: otherwise it hoists the dozens of LDS addresses below out of the sweep, runs out of
+        // registers and spills them -- and every reload of a spilled value is a vector-memory load whose wait
+        // also waits for the stream loads in flight.
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        const int lane = tid & 63;
+        const bool odd = lane & 1;
+        int col[2];
+        bool ok[2];
+#pragma unroll
+        for (int fn = 0; fn < 2; ++fn) {
+            col[fn] = (tid >> 6) * 64 + fn * 32 + (tid & 31);
+            ok[fn] = ts * CFG::RES + col[fn] < B;
+        }
 #pragma unroll
         for (int fn = 0; fn < 2; ++fn) {
 #pragma unroll
@@ -702,8 +724,11 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
         // row) of the rows t / 32, t / 32 + 8, ..., so it can also carry the sums over the class rows of those
         // samples -- of the rounded values, as the two gradient contractions will read them
         constexpr int PPR = CFG::RES / 8; // pieces per row
-        const int ch = threadIdx.x % PPR;
-        for (int r0 = threadIdx.x / PPR; r0 < rows_here; r0 += 4 * (256 / PPR)) {
+        const int ch = tid % PPR;
+        float l[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) l[c] = s_sum[c * 256 + tid];
+        for (int r0 = tid / PPR; r0 < rows_here; r0 += 4 * (256 / PPR)) {
             uint4 v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -722,14 +747,16 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
                 }
             }
         }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) s_sum[c * 256 + tid] = l[c];
     };
-    ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi);
+    ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi, s_lidx, SM_LIDX_CAP);
     // the eight row groups of a sample meet through LDS (the stream stages are free now): red[group][sample]
     float *red = (float *)lds;
     {
         const int grp = threadIdx.x / (CFG::RES / 8), ch = threadIdx.x % (CFG::RES / 8);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) red[grp * CFG::RES + ch * 8 + c] = l[c];
+        for (int c = 0; c < 8; ++c) red[grp * CFG::RES + ch * 8 + c] = s_sum[c * 256 + threadIdx.x];
     }
     __syncthreads();
     {
