@@ -47,11 +47,22 @@ __device__ __forceinline__ int ks_soe_col(int fn) { return (threadIdx.x >> 6) * 
 // (used when the sweep's rows, rounded up to whole chunks, fit).  Without it the list is read from global
 // memory once per chunk, and waiting for that read means waiting for every stream load issued before it:
 // the wait counter of vector-memory instructions is shared.
-template <class CFG, class Epi>
+//
+// post(chunk_first_row, rows_in_chunk): optional second half of a chunk's epilogue, for global stores.  The
+// sweep tells that a stage has landed by counting outstanding vector-memory instructions, and stores count
+// too: stores issued at the end of a chunk make the very next wait sit out their round trip.  post() for
+// chunk c is therefore called inside chunk c+1, right after the loads of its first stage's successor have
+// been issued (the wait after that still lets exactly those loads and the stores be outstanding, and by
+// then a whole stage of MFMAs has passed), and after the sweep for the last chunk.  epi() leaves what
+// post() needs in LDS of the caller's.
+struct KsSoeNoPost {
+    __device__ __forceinline__ void operator()(int, int) const {}
+};
+template <class CFG, class Epi, class Post = KsSoeNoPost>
 __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int64_t ldr, int r_row0, int r_limit,
                                              const uint16_t *__restrict__ S, int64_t lds_ld, const int32_t *__restrict__ gidx,
                                              int s_begin, int s_end, int s_clamp, uint16_t *lds, Epi &epi,
-                                             int32_t *lidx = nullptr, int lidx_cap = 0) {
+                                             int32_t *lidx = nullptr, int lidx_cap = 0, Post post = Post()) {
     constexpr int KT = CFG::KT, ST = CFG::STAGES, NI = CFG::NI, FM = CFG::FM;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -152,6 +163,10 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
             else ks_wait_vmcnt<0>();
             ks_barrier_nofence();
             if (issued < n_tiles) issue_one();
+            if (kt0 == 0 && c > 0) {
+                const int pc0 = s_begin + (c - 1) * CFG::CH;
+                post(pc0, (s_end - pc0) < CFG::CH ? (s_end - pc0) : CFG::CH);
+            }
 #pragma unroll
             for (int u = 0; u < CFG::KSUB; ++u) {
                 const int kt = kt0 + u;
@@ -185,4 +200,8 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
         epi(s_begin + c * CFG::CH, rows_here, acc);
     }
     ks_barrier_nofence();
+    if (n_chunks > 0) {
+        const int pc0 = s_begin + (n_chunks - 1) * CFG::CH;
+        post(pc0, s_end - pc0);
+    }
 }

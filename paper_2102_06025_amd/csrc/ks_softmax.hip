@@ -719,10 +719,14 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
                 }
         }
         __builtin_amdgcn_s_waitcnt(0xC07F); // LDS writes done (lgkmcnt 0); loads in flight are left alone
-        ks_barrier_nofence();
-        // copy the chunk out in 16-byte pieces: thread t always takes the same eight samples (piece t % 32 of a
+    };
+    // second half of the epilogue, run one stage into the next chunk (a workgroup barrier has passed since
+    // the writes above): copy the chunk out in 16-byte pieces: thread t always takes the same eight samples (piece t % 32 of a
         // row) of the rows t / 32, t / 32 + 8, ..., so it can also carry the sums over the class rows of those
         // samples -- of the rounded values, as the two gradient contractions will read them
+    auto post = [&](int c0, int rows_here) {
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
         constexpr int PPR = CFG::RES / 8; // pieces per row
         const int ch = tid % PPR;
         float l[8];
@@ -750,7 +754,8 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
 #pragma unroll
         for (int c = 0; c < 8; ++c) s_sum[c * 256 + tid] = l[c];
     };
-    ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi, s_lidx, SM_LIDX_CAP);
+    ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi, s_lidx, SM_LIDX_CAP, post);
+    __syncthreads();
     // the eight row groups of a sample meet through LDS (the stream stages are free now): red[group][sample]
     float *red = (float *)lds;
     {
