@@ -32,11 +32,11 @@ PHASES = ["select", "logits_gemm", "row_stats", "logit_grad", "dx_gemm", "dx_red
 
 # HBM bytes per launch of each stage's kernel from two rocprofv3 --pmc runs (FETCH_SIZE scaled by 2.0, WRITE_SIZE by
 # 1.0, the factors a copy of known size gives), copied from profiles/bench_shard390k_hbm_traffic.txt
+# (unit-rows mode: one softmax sweep; the dW launch also carries the reduction of the dX partial sums)
 MEASURED_TRAFFIC = {
-    ("shard390k", "logits_gemm"): 27.26e6,
-    ("shard390k", "logit_grad"): 71.16e6,
-    ("shard390k", "dx_gemm"): 87.42e6,
-    ("shard390k", "dw_gemm"): 82.06e6,
+    ("shard390k", "logits_gemm"): 62.72e6,
+    ("shard390k", "dx_gemm"): 87.41e6,
+    ("shard390k", "dw_gemm"): 117.78e6,
     ("shard390k", "apply"): 125.50e6,
 }
 
@@ -113,7 +113,7 @@ def phase_model(cfg, A, unit_rows):
         # logits again -> logit gradient (stored transposed); no such sweep with unit rows
         "logit_grad": dict(bound="latency") if unit_rows else dict(bound="mfma", flops=gemm),
         "dx_gemm": dict(bound="mfma", flops=gemm),
-        "dx_reduce": dict(bound="latency"),
+        "dx_reduce": dict(bound="latency"),                  # nothing launched here: the reduction rides with dw_gemm
         "dw_gemm": dict(bound="mfma", flops=gemm),
         "apply": dict(bound="hbm", bytes=A * D * (4.0 + 4.0 + 4.0 + 2.0)),
     }
@@ -250,12 +250,13 @@ def main():
         phases[p] = e
     log("[bench] stage times (us): " + ", ".join(f"{p}={phases[p]['us']}" for p in PHASES))
     dom = max((p for p in PHASES if model[p]["bound"] in ("mfma", "hbm")), key=lambda p: dur[p])
+    traffic = MEASURED_TRAFFIC.get((args.workload, dom)) if unit_rows else None  # measured in unit-rows mode only
     if model[dom]["bound"] == "mfma":
         roofline = dict(bound="mfma", achieved=phases[dom]["tflops"], peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                        frac=phases[dom]["frac"], traffic=MEASURED_TRAFFIC.get((args.workload, dom)), kernel=dom)
+                        frac=phases[dom]["frac"], traffic=traffic, kernel=dom)
     else:
         roofline = dict(bound="hbm", achieved=phases[dom]["gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=phases[dom]["frac"], traffic=MEASURED_TRAFFIC.get((args.workload, dom)), kernel=dom)
+                        frac=phases[dom]["frac"], traffic=traffic, kernel=dom)
 
     # ---- CPU oracle on the same inputs: baseline + full-size parity of the first step -----------------------
     cpu_baseline, parity = None, None
