@@ -120,20 +120,33 @@ template <int W, int NW> struct KsAKmaj {
     }
 };
 
+// The transposing LDS read as inline assembly.  Through the compiler's builtin every such read is preceded by
+// s_waitcnt vmcnt(0): the compiler cannot tell it apart from the buffer the asynchronous loads in flight are
+// writing and waits for all of them, which serialises the loads of tile t+1 with the MFMAs of tile t.  As
+// assembly the read is invisible to that logic; the price is that its completion has to be waited for by hand
+// (ks_a_wait_frags) before the registers are used.
+typedef uint32_t ks_u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t ks_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ ks_u32x2 ks_ds_read_tr16_b64(const uint16_t *p) {
+    const uint32_t addr = (uint32_t)(uintptr_t)(const uint16_t __attribute__((address_space(3))) *)p;
+    ks_u32x2 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v) : "v"(addr));
+    return v;
+}
+
 // fragment of a k-major tile: 8 consecutive k (k-step kk) of column block `cb` (32 columns)
 template <int W>
 __device__ __forceinline__ bf16x8_t ks_a_frag_kmaj(const uint16_t *tile, int cb32, int kk) {
-    typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4, r = (lane >> 2) & 3, q = lane & 3;
     const int kb = kk * 16 + (g >> 1) * 8 + r;
     const int chunk = cb32 * 4 + (g & 1) * 2 + (q >> 1);
     // k & 3 == r for both halves (kb + 4 has the same low bits)
     const int off = ((chunk ^ (r << 2)) * 8) + (q & 1) * 4;
-    bf16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4_t __attribute__((address_space(3))) *)(tile + kb * W + off));
-    bf16x4_t hi =
-        __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4_t __attribute__((address_space(3))) *)(tile + (kb + 4) * W + off));
-    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    const ks_u32x2 lo = ks_ds_read_tr16_b64(tile + kb * W + off);
+    const ks_u32x2 hi = ks_ds_read_tr16_b64(tile + (kb + 4) * W + off);
+    const ks_u32x4 both = {lo.x, lo.y, hi.x, hi.y};
+    return __builtin_bit_cast(bf16x8_t, both);
 }
 
 template <class T> struct KsAFrags {
@@ -159,6 +172,24 @@ __device__ __forceinline__ void ks_a_load_frags(KsAFrags<T> &f, const uint16_t *
     }
 }
 
+// LDS instructions of one fragment set (a k-major fragment takes two reads)
+template <class T, bool AK, bool BK> struct KsAFragCount {
+    static constexpr int N = (AK ? 2 : 1) * T::FM + (BK ? 2 : 1) * T::FN;
+    static_assert(N <= 15, "lgkmcnt range");
+};
+// Wait until at most YOUNGER LDS instructions issued after this fragment set's reads are outstanding, and tie
+// the set's registers to the wait so that nothing using them is scheduled above it.  Only needed when some
+// read was issued from assembly (k-major operands); the compiler looks after the reads it knows.
+template <class T, bool AK, bool BK, int YOUNGER>
+__device__ __forceinline__ void ks_a_wait_frags(KsAFrags<T> &f) {
+    if (!AK && !BK) return;
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(YOUNGER));
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm) asm volatile("" : "+v"(f.a[fm]));
+#pragma unroll
+    for (int fn = 0; fn < T::FN; ++fn) asm volatile("" : "+v"(f.b[fn]));
+}
+
 template <class T>
 __device__ __forceinline__ void ks_a_mma(const KsAFrags<T> &f, f32x16_t (&acc)[T::FM][T::FN]) {
 #pragma unroll
@@ -174,21 +205,27 @@ __device__ __forceinline__ void ks_a_mma(const KsAFrags<T> &f, f32x16_t (&acc)[T
 template <class T, bool AK = false, bool BK = false>
 __device__ __forceinline__ void ks_a_tile_mma(const uint16_t *st, f32x16_t (&acc)[T::FM][T::FN]) {
     const uint16_t *stA = st, *stB = st + T::BM * 64;
+    constexpr int N = KsAFragCount<T, AK, BK>::N; // the reads of one set: what may stay outstanding behind the set in use
     KsAFrags<T> f0, f1;
+    __builtin_amdgcn_sched_barrier(0);
     ks_a_load_frags<T, AK, BK>(f0, stA, stB, 0);
     __builtin_amdgcn_sched_barrier(0);
     ks_a_load_frags<T, AK, BK>(f1, stA, stB, 1);
     __builtin_amdgcn_sched_barrier(0);
+    ks_a_wait_frags<T, AK, BK, N>(f0);
     ks_a_mma<T>(f0, acc);
     __builtin_amdgcn_sched_barrier(0);
     ks_a_load_frags<T, AK, BK>(f0, stA, stB, 2);
     __builtin_amdgcn_sched_barrier(0);
+    ks_a_wait_frags<T, AK, BK, N>(f1);
     ks_a_mma<T>(f1, acc);
     __builtin_amdgcn_sched_barrier(0);
     ks_a_load_frags<T, AK, BK>(f1, stA, stB, 3);
     __builtin_amdgcn_sched_barrier(0);
+    ks_a_wait_frags<T, AK, BK, N>(f0);
     ks_a_mma<T>(f0, acc);
     __builtin_amdgcn_sched_barrier(0);
+    ks_a_wait_frags<T, AK, BK, 0>(f1);
     ks_a_mma<T>(f1, acc);
 }
 
