@@ -127,3 +127,44 @@ def test_step_full_size(ks, orc, shard, name, unit_rows):
     ui = torch.from_numpy(untouched.astype(np.int64)).cuda()
     assert (W_master[ui].cpu().numpy() == W[untouched]).all()
     assert bool((W_copy[ui] == W_bf[ui]).all())
+
+
+def test_step_dense1m(ks, orc):
+    """The largest workload (C = 1,000,000, B = 2,048, K = 64, M = 131,072; about 124,500 active rows): eight
+    sample blocks per slab instead of four, and slabs too long for the sweeps' LDS copy of the gather list.
+    The neighbour lists are an arithmetic pattern here (what the selection and the softmax do with them does
+    not depend on their being true neighbours); both softmax modes against one oracle run."""
+    cfg = synth.CONFIGS["dense1m"]
+    C, D, B, K, M, scale = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"], cfg["scale"]
+    print(f"[case] dense1m: generating inputs C={C} D={D} B={B} K={K} M={M}", flush=True)
+    W, X = synth.make_WX(cfg)
+    y = synth.make_labels(cfg)
+    c = np.arange(C, dtype=np.int64)[:, None]
+    k = np.arange(K, dtype=np.int64)[None, :]
+    G = ((c + 1 + (c * 2654435761 + k * 40503) % (C - 1)) % C).astype(np.int32)  # K distinct ids, none equal to c
+    assert (G != c).all() and (np.sort(G[:1000], axis=1)[:, 1:] != np.sort(G[:1000], axis=1)[:, :-1]).all()
+    grad_scale = 128.0
+    active, A_ref, tpos = orc.select_active(y, G, C, M)
+    print(f"        oracle: fwd/bwd with A={A_ref}", flush=True)
+    ref = orc.knn_softmax_fwd_bwd(W, X, active[:A_ref], tpos, scale, grad_scale)
+    W_bf = torch.from_numpy(W).cuda().to(torch.bfloat16)
+    X_bf = torch.from_numpy(X).cuda().to(torch.bfloat16)
+    Gd = torch.from_numpy(G).cuda()
+    yd = torch.from_numpy(y).cuda()
+    for unit_rows in (True, False):
+        print(f"[case] dense1m: fwd_bwd unit_rows={unit_rows}", flush=True)
+        out = ks.knn_softmax_fwd_bwd(W_bf, X_bf, yd, Gd, M, scale, grad_scale, unit_rows=unit_rows)
+        torch.cuda.synchronize()
+        assert int(out["dev_status"].item()) == 0
+        assert int(out["n_active"].item()) == A_ref
+        assert (out["active_idx"].cpu().numpy() == active).all()
+        assert (out["target_pos"].cpu().numpy() == tpos).all()
+        li = out["loss_per_sample"].cpu().numpy()
+        assert np.abs(li - ref["loss_i"]).max() <= LOSS_RTOL * max(1.0, np.abs(ref["loss_i"]).max())
+        loss = float(out["loss_mean"].item())
+        assert abs(loss - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"])
+        e_dx = rel_fro(out["dX"].cpu().numpy(), ref["dX"])
+        e_dw = rel_fro(out["dW_active"][:A_ref].cpu().numpy(), ref["dWA"])
+        print(f"        A={A_ref} loss={loss:.6f} ref={ref['loss']:.6f} relF(dX)={e_dx:.2e} relF(dW)={e_dw:.2e}", flush=True)
+        assert e_dx <= GRAD_RTOL and e_dw <= GRAD_RTOL
+        del out
