@@ -66,16 +66,33 @@ gr_prepare_kernel(const IN *__restrict__ W, int64_t C, int D, uint16_t *__restri
     if (i >= C) return;
     const int lane = threadIdx.x & 63;
     float s = 0.f;
-    for (int d = lane; d < D; d += 64) {
-        float v = GrElem<IN>::f(W[i * D + d]);
-        s += v * v;
-        if (Wb) Wb[i * D + d] = (uint16_t)ks_f2bf(v);
+    if (sizeof(IN) == 2 && D % 8 == 0) { // 16-byte loads (the sum is only used for the error bound, with slack)
+        for (int d = lane * 8; d < D; d += 512) {
+            const uint4 v = *(const uint4 *)((const uint16_t *)W + i * D + d);
+            const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = __uint_as_float(w4[e] << 16), hi = __uint_as_float(w4[e] & 0xFFFF0000u);
+                s = fmaf(lo, lo, s);
+                s = fmaf(hi, hi, s);
+            }
+            if (Wb) *(uint4 *)(Wb + i * D + d) = v;
+        }
+    } else {
+        for (int d = lane; d < D; d += 64) {
+            float v = GrElem<IN>::f(W[i * D + d]);
+            s += v * v;
+            if (Wb) Wb[i * D + d] = (uint16_t)ks_f2bf(v);
+        }
     }
     s = ks_wave_sum(s);
     if (lane == 0) {
         float nrm = sqrtf(s);
         norms[i] = nrm;
-        atomicMax(maxnorm_bits, __float_as_uint(nrm)); // non-negative floats order like their bit patterns
+        // non-negative floats order like their bit patterns.  The running maximum is read first: one atomic
+        // per row on a single address would serialise the whole kernel in the L2
+        const uint32_t bits = __float_as_uint(nrm);
+        if (bits > __atomic_load_n(maxnorm_bits, __ATOMIC_RELAXED)) atomicMax(maxnorm_bits, bits);
     }
 }
 
@@ -375,7 +392,26 @@ gr_recall_soe_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kpri
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ double gr_canon(const uint16_t *__restrict__ a, const uint16_t *__restrict__ b, int D) {
     double acc = 0.0;
-    for (int d = 0; d < D; d += 8) {
+    int d = 0;
+    // whole 128-byte lines of b at a time: callers give every lane a row of its own, so a line that is only
+    // partly consumed is evicted before the lane comes back to it and is fetched again
+    for (; d + 64 <= D; d += 64) {
+        uint4 vb[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) vb[q] = *(const uint4 *)(b + d + q * 8);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint4 va = *(const uint4 *)(a + d + q * 8);
+            const uint32_t wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb[q].x, vb[q].y, vb[q].z, vb[q].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc = __builtin_fma((double)__uint_as_float(wa[e] << 16), (double)__uint_as_float(wb[e] << 16), acc);
+                acc = __builtin_fma((double)__uint_as_float(wa[e] & 0xFFFF0000u),
+                                    (double)__uint_as_float(wb[e] & 0xFFFF0000u), acc);
+            }
+        }
+    }
+    for (; d < D; d += 8) {
         uint4 va = *(const uint4 *)(a + d), vb = *(const uint4 *)(b + d);
         const uint32_t wa[4] = {va.x, va.y, va.z, va.w}, wb[4] = {vb.x, vb.y, vb.z, vb.w};
 #pragma unroll
