@@ -25,7 +25,8 @@ def lib():
         _lib = ct.CDLL(path)
         _lib.orc_num_threads.restype = ct.c_int
         for name in ("orc_graph_bruteforce", "orc_select_active", "orc_knn_softmax_fwd_bwd",
-                     "orc_full_softmax_fwd_bwd", "orc_apply_weight_grad"):
+                     "orc_full_softmax_fwd_bwd", "orc_apply_weight_grad", "orc_normalize_rows", "orc_norm_backward",
+                     "orc_apply_weight_grad_normalized"):
             getattr(_lib, name).restype = ct.c_int
     return _lib
 
@@ -135,3 +136,49 @@ def apply_weight_grad(W_master, idx, dW, alpha: float, want_bf16: bool = True):
     if rc != ORC_OK:
         raise ValueError(f"orc_apply_weight_grad failed with code {rc}")
     return Wm, Wb
+
+
+def normalize_rows(V, want_bf16: bool = True):
+    """Rows divided by their L2 norm (zero rows stay zero).  Returns (V_hat fp32, bf16 bit patterns of V_hat or
+    None, inv_norm fp32 [n])."""
+    V = _f32(V)
+    n, D = V.shape
+    Vh = np.empty((n, D), dtype=np.float32)
+    Vb = np.empty((n, D), dtype=np.uint16) if want_bf16 else None
+    inv = np.empty(n, dtype=np.float32)
+    rc = lib().orc_normalize_rows(_p(V, ct.c_float), ct.c_int64(n), ct.c_int(D), _p(Vh, ct.c_float),
+                                  _p(Vb, ct.c_uint16), _p(inv, ct.c_float))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_normalize_rows failed with code {rc}")
+    return Vh, Vb, inv
+
+
+def norm_backward(V, G):
+    """Gradient with respect to the rows V given the gradient G (fp64) with respect to V / |V|."""
+    V = _f32(V)
+    G = np.ascontiguousarray(G, dtype=np.float64)
+    n, D = V.shape
+    assert G.shape == (n, D)
+    out = np.empty((n, D), dtype=np.float64)
+    rc = lib().orc_norm_backward(_p(V, ct.c_float), _p(G, ct.c_double), ct.c_int64(n), ct.c_int(D), _p(out, ct.c_double))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_norm_backward failed with code {rc}")
+    return out
+
+
+def apply_weight_grad_normalized(W_master, idx, dW_hat, alpha: float):
+    """Update of the un-normalised master rows from gradients with respect to their normalised copies.
+    Returns (new fp32 master copy, bf16 bit patterns of the re-normalised touched rows in an array that is zero
+    elsewhere, inv_norm fp32 [C] that is zero for untouched rows).  The input array is not modified."""
+    Wm = _f32(W_master).copy()
+    idx, dW_hat = _i32(idx), _f32(dW_hat)
+    C, D = Wm.shape
+    n = idx.shape[0]
+    Wb = np.zeros((C, D), dtype=np.uint16)
+    inv = np.zeros(C, dtype=np.float32)
+    rc = lib().orc_apply_weight_grad_normalized(_p(Wm, ct.c_float), _p(Wb, ct.c_uint16), _p(inv, ct.c_float),
+                                                _p(idx, ct.c_int32), ct.c_int(n), _p(dW_hat, ct.c_float),
+                                                ct.c_double(alpha), ct.c_int64(C), ct.c_int(D))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_apply_weight_grad_normalized failed with code {rc}")
+    return Wm, Wb, inv

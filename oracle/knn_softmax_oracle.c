@@ -340,3 +340,97 @@ int orc_apply_weight_grad(float *Wm, uint16_t *Wb, const int32_t *idx, int n, co
     free(slot);
     return ORC_OK;
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * Normalisation of the rows of W and X inside the layer (Section 3.2.1: the GPU pipeline normalises
+ * W and X; Section 3.2: "normalization strategy").  With v_hat = v / |v| the layer works on the
+ * normalised rows; a gradient g with respect to v_hat becomes, with respect to v,
+ *     dv = (g - v_hat <v_hat, g>) / |v|                (the Jacobian of v -> v / |v| is symmetric).
+ * A zero row stays zero and receives a zero gradient.
+ * ------------------------------------------------------------------------------------------- */
+int orc_normalize_rows(const float *V, int64_t n, int D, float *V_hat, uint16_t *V_hat_bf16, float *inv_norm) {
+    if (!V || n < 0 || D < 1) return ORC_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const float *v = V + i * D;
+        double s = 0.0;
+        for (int d = 0; d < D; ++d) s += (double)v[d] * (double)v[d];
+        const double inv = s > 0.0 ? 1.0 / sqrt(s) : 0.0;
+        if (inv_norm) inv_norm[i] = (float)inv;
+        for (int d = 0; d < D; ++d) {
+            const float h = (float)((double)v[d] * inv);
+            if (V_hat) V_hat[i * D + d] = h;
+            if (V_hat_bf16) V_hat_bf16[i * D + d] = f32_to_bf16_rne(h);
+        }
+    }
+    return ORC_OK;
+}
+
+int orc_norm_backward(const float *V, const double *G, int64_t n, int D, double *dV) {
+    if (!V || !G || !dV || n < 0 || D < 1) return ORC_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        const float *v = V + i * D;
+        const double *g = G + i * D;
+        double s = 0.0;
+        for (int d = 0; d < D; ++d) s += (double)v[d] * (double)v[d];
+        if (!(s > 0.0)) {
+            for (int d = 0; d < D; ++d) dV[i * D + d] = 0.0;
+            continue;
+        }
+        const double inv = 1.0 / sqrt(s);
+        double dot = 0.0; /* <v_hat, g> */
+        for (int d = 0; d < D; ++d) dot += (double)v[d] * inv * g[d];
+        for (int d = 0; d < D; ++d) dV[i * D + d] = (g[d] - (double)v[d] * inv * dot) * inv;
+    }
+    return ORC_OK;
+}
+
+/* Weight update of the layer that keeps W un-normalised in fp32 and works on its normalised 16-bit copy
+ * (Section 3.1 step 6 with the normalisation of Section 3.2.1 folded in).  dW_hat[p,:] is the gradient
+ * with respect to the NORMALISED row of class idx[p].  For every class c that occurs in idx:
+ *     g = sum of its rows of dW_hat (ascending p, fp64);  dw = (g - w_hat <w_hat, g>) / |w|  with the
+ *     current master row;  W[c,:] += alpha * dw (stored fp32);  then, from the stored row,
+ *     inv_norm[c] = 1 / |W[c,:]|  and  W_hat_bf16[c,:] = bf16(fp32(W[c,:] * inv_norm)).
+ * Rows not named in idx are not touched. */
+int orc_apply_weight_grad_normalized(float *Wm, uint16_t *W_hat_bf16, float *inv_norm, const int32_t *idx, int n,
+                                     const float *dW_hat, double alpha, int64_t C, int D) {
+    if (!Wm || !idx || !dW_hat || n < 0 || D < 1) return ORC_BAD_ARG;
+    for (int p = 0; p < n; ++p) if (idx[p] < 0 || idx[p] >= C) return ORC_BAD_LABEL;
+    int32_t *slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)C);
+    for (int64_t c = 0; c < C; ++c) slot[c] = -1;
+    int n_distinct = 0;
+    for (int p = 0; p < n; ++p) if (slot[idx[p]] < 0) slot[idx[p]] = n_distinct++;
+    double *sum = (double *)calloc((size_t)(n_distinct ? n_distinct : 1) * (size_t)D, sizeof(double));
+    for (int p = 0; p < n; ++p) { /* ascending p */
+        double *s = sum + (size_t)slot[idx[p]] * D;
+        for (int d = 0; d < D; ++d) s[d] += (double)dW_hat[(size_t)p * D + d];
+    }
+    for (int p = 0; p < n; ++p) {
+        const int32_t c = idx[p];
+        if (slot[c] < 0) continue; /* already applied */
+        const double *g = sum + (size_t)slot[c] * D;
+        float *w = Wm + (int64_t)c * D;
+        double ss = 0.0;
+        for (int d = 0; d < D; ++d) ss += (double)w[d] * (double)w[d];
+        if (ss > 0.0) {
+            const double inv = 1.0 / sqrt(ss);
+            double dot = 0.0;
+            for (int d = 0; d < D; ++d) dot += (double)w[d] * inv * g[d];
+            for (int d = 0; d < D; ++d) {
+                const double dw = (g[d] - (double)w[d] * inv * dot) * inv;
+                w[d] = (float)((double)w[d] + alpha * dw);
+            }
+        }
+        double s2 = 0.0;
+        for (int d = 0; d < D; ++d) s2 += (double)w[d] * (double)w[d];
+        const double inv2 = s2 > 0.0 ? 1.0 / sqrt(s2) : 0.0;
+        if (inv_norm) inv_norm[c] = (float)inv2;
+        if (W_hat_bf16)
+            for (int d = 0; d < D; ++d) W_hat_bf16[(int64_t)c * D + d] = f32_to_bf16_rne((float)((double)w[d] * inv2));
+        slot[c] = -1;
+    }
+    free(sum);
+    free(slot);
+    return ORC_OK;
+}

@@ -348,3 +348,136 @@ def test_bf16_rounding_to_nearest_even(orc):
     Wm, Wb = orc.apply_weight_grad(W, np.array([0], dtype=np.int32), np.zeros((1, 4), dtype=np.float32), 1.0)
     got = synth.bf16_to_f32(Wb)[0].tolist()
     assert got == [1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, -1.0]
+
+
+# --------------------------------------------------------------------------------------------
+# normalisation inside the layer (Section 3.2.1) and the update of un-normalised weights through it
+# --------------------------------------------------------------------------------------------
+def _raw_rows(seed, tid, n, D):
+    """Rows of very different lengths (0.2 .. 5)."""
+    V = synth.unit_rows(seed, tid, n, D).astype(np.float64)
+    scale = 0.2 + 4.8 * ((np.arange(n) * 0.6180339887) % 1.0)
+    return (V * scale[:, None]).astype(np.float32)
+
+
+def test_normalize_rows_closed_forms(orc):
+    V = _raw_rows(1, synth.TID_W, 50, 24)
+    V[7] = 0.0
+    Vh, Vb, inv = orc.normalize_rows(V)
+    n = np.sqrt((V.astype(np.float64) ** 2).sum(axis=1))
+    ok = n > 0
+    assert np.allclose(inv[ok], 1.0 / n[ok], rtol=1e-6)
+    assert np.allclose((Vh[ok].astype(np.float64) ** 2).sum(axis=1), 1.0, atol=1e-6)
+    assert inv[7] == 0.0 and (Vh[7] == 0).all()
+    # direction kept, length dropped: scaling a row changes nothing
+    Vh2, _, _ = orc.normalize_rows(V * np.float32(4.0))    # power of two: the products are exact
+    assert np.array_equal(Vh2, Vh)
+    assert np.array_equal(Vb, synth.bf16_bits(Vh))
+    # a 3-4-5 row
+    Vh3, _, inv3 = orc.normalize_rows(np.array([[3.0, 4.0, 0.0]], dtype=np.float32))
+    assert np.allclose(Vh3, [[0.6, 0.8, 0.0]], atol=1e-7) and abs(inv3[0] - 0.2) < 1e-8
+
+
+def test_norm_backward_is_the_gradient_of_the_normalisation(orc):
+    n, D = 12, 10
+    V = _raw_rows(2, synth.TID_W, n, D)
+    Cc = synth.unit_rows(5, synth.TID_X, n, D).astype(np.float64) * 3.0   # f(V) = sum_i <c_i, v_i / |v_i|>
+    dV = orc.norm_backward(V, Cc)
+    V64 = V.astype(np.float64)
+    nrm = np.sqrt((V64 ** 2).sum(axis=1, keepdims=True))
+    # closed form of the Jacobian-vector product: (c - v_hat <v_hat, c>) / |v|
+    vh = V64 / nrm
+    assert np.allclose(dV, (Cc - vh * (vh * Cc).sum(axis=1, keepdims=True)) / nrm, rtol=1e-12, atol=1e-14)
+    # a gradient through a normalisation is orthogonal to the row, and scales inversely with its length
+    assert np.abs((dV * V64).sum(axis=1)).max() < 1e-12
+    dV2 = orc.norm_backward(V * np.float32(2.0), Cc)
+    assert np.allclose(dV2, dV / 2.0, rtol=1e-12)
+    # central differences in fp64 on f
+    def f(Vx):
+        return float((Cc * Vx / np.sqrt((Vx ** 2).sum(axis=1, keepdims=True))).sum())
+    rng = np.random.default_rng(0)
+    for _ in range(40):
+        i, d = int(rng.integers(n)), int(rng.integers(D))
+        h = 1e-6
+        Vp, Vm = V64.copy(), V64.copy()
+        Vp[i, d] += h
+        Vm[i, d] -= h
+        fd = (f(Vp) - f(Vm)) / (2 * h)
+        assert abs(fd - dV[i, d]) <= 1e-7 * max(1.0, abs(dV[i, d]))
+    # zero row: zero gradient
+    V0 = V.copy()
+    V0[3] = 0.0
+    assert (orc.norm_backward(V0, Cc)[3] == 0).all()
+
+
+def test_layer_with_normalisation_gradients_by_finite_differences(orc):
+    """loss(W_raw, X_raw) = KNN-softmax loss on the normalised rows; the analytic gradient is the softmax
+    oracle's gradient pushed through norm_backward."""
+    C, D, B, K, M = 300, 12, 6, 4, 40
+    Wr = _raw_rows(4, synth.TID_W, C, D)
+    Xr = _raw_rows(4, synth.TID_X, B, D)
+    y = synth.labels_uniform(4, B, C)
+    G = synth.graph_synthetic(4, C, K, locality=2)
+    active, A, tpos = orc.select_active(y, G, C, M)
+    active = active[:A]
+    s, gs = 8.0, 1.0
+
+    def loss_of(W64, X64):
+        Wh = W64 / np.sqrt((W64 ** 2).sum(axis=1, keepdims=True))
+        Xh = X64 / np.sqrt((X64 ** 2).sum(axis=1, keepdims=True))
+        Z = s * Xh @ Wh[active].T
+        lse = np.log(np.exp(Z - Z.max(axis=1, keepdims=True)).sum(axis=1)) + Z.max(axis=1)
+        return float((lse - Z[np.arange(B), tpos]).mean())
+
+    Wh, _, _ = orc.normalize_rows(Wr, want_bf16=False)
+    Xh, _, _ = orc.normalize_rows(Xr, want_bf16=False)
+    out = orc.knn_softmax_fwd_bwd(Wh, Xh, active, tpos, s, gs)
+    assert abs(out["loss"] - loss_of(Wr.astype(np.float64), Xr.astype(np.float64))) < 1e-6   # fp32 storage of the normalised rows
+    dWr = orc.norm_backward(Wr[active], out["dWA"])
+    dXr = orc.norm_backward(Xr, out["dX"])
+    rng = np.random.default_rng(1)
+    W64, X64 = Wr.astype(np.float64), Xr.astype(np.float64)
+    for _ in range(30):
+        a, d = int(rng.integers(A)), int(rng.integers(D))
+        h = 1e-5
+        Wp, Wm_ = W64.copy(), W64.copy()
+        Wp[active[a], d] += h
+        Wm_[active[a], d] -= h
+        fd = (loss_of(Wp, X64) - loss_of(Wm_, X64)) / (2 * h)
+        assert abs(fd - dWr[a, d]) <= 2e-5 * max(abs(dWr[a, d]), 1e-3), (fd, dWr[a, d])
+    for _ in range(30):
+        i, d = int(rng.integers(B)), int(rng.integers(D))
+        h = 1e-5
+        Xp, Xm = X64.copy(), X64.copy()
+        Xp[i, d] += h
+        Xm[i, d] -= h
+        fd = (loss_of(W64, Xp) - loss_of(W64, Xm)) / (2 * h)
+        assert abs(fd - dXr[i, d]) <= 2e-5 * max(abs(dXr[i, d]), 1e-3), (fd, dXr[i, d])
+
+
+def test_apply_weight_grad_normalized_against_numpy(orc):
+    C, D, n = 40, 16, 25
+    W = _raw_rows(6, synth.TID_W, C, D)
+    rng = np.random.default_rng(2)
+    idx = rng.integers(0, C // 2, n).astype(np.int32)          # repeats; the upper half stays untouched
+    dWh = synth.grad_rows(6, n, D).astype(np.float32)
+    alpha = -0.3
+    Wm, Wb, inv = orc.apply_weight_grad_normalized(W, idx, dWh, alpha)
+    W64 = W.astype(np.float64)
+    exp = W64.copy()
+    for c in np.unique(idx):
+        g = dWh[idx == c].astype(np.float64).sum(axis=0)
+        nrm = np.sqrt((W64[c] ** 2).sum())
+        wh = W64[c] / nrm
+        exp[c] = W64[c] + alpha * (g - wh * (wh @ g)) / nrm
+    assert np.allclose(Wm, exp, rtol=0, atol=2.0 ** -23 * np.abs(exp).max())
+    touched = np.unique(idx)
+    untouched = np.setdiff1d(np.arange(C), touched)
+    assert np.array_equal(Wm[untouched], W[untouched]) and (Wb[untouched] == 0).all() and (inv[untouched] == 0).all()
+    n2 = np.sqrt((Wm[touched].astype(np.float64) ** 2).sum(axis=1))
+    assert np.allclose(inv[touched], 1.0 / n2, rtol=1e-6)
+    assert np.array_equal(Wb[touched], synth.bf16_bits((Wm[touched].astype(np.float64) / n2[:, None]).astype(np.float32)))
+    # first-order property of a step through a normalisation: the length of a row changes only in second order
+    n1 = np.sqrt((W64[touched] ** 2).sum(axis=1))
+    step = np.sqrt(((Wm[touched] - W[touched]).astype(np.float64) ** 2).sum(axis=1))
+    assert np.all(np.abs(n2 - n1) <= step ** 2 / n1 + 1e-6)
