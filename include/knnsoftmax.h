@@ -184,6 +184,40 @@ int apply_weight_grad(float *W_master, uint16_t *W_bf16, const int32_t *idx, con
                       const float *dW, float alpha, int64_t C, int D, int idx_sorted_unique,
                       void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
+/* ------------------------------------------------------------------------------------------------------
+ * Normalisation inside the layer -- Section 3.2.1: the graph and the softmax work on normalised W and X,
+ * and the normalisation itself runs on the GPU.  The layer keeps W un-normalised in fp32 (W_master), its
+ * contractions read the normalised 16-bit copy W_hat = W / |W| (row-wise L2 norm; pass it wherever an entry
+ * point above takes W_bf16, with KS_FLAG_UNIT_ROWS), and a gradient g with respect to a normalised row is
+ * brought back to the row v itself through
+ *     dv = (g - v_hat <v_hat, g>) / |v|,       v_hat = v / |v|.
+ * Row reductions are taken in fp64.  A zero row has inv_norm 0, a zero normalised row and a zero gradient.
+ *
+ * knn_normalize_rows:  V [n, D] (dtype KS_DTYPE_*) ->  V_hat_bf16 [n, D] = bf16(fp32(V / |V|)) and
+ *     inv_norm [n] = 1 / |V| (either output may be NULL, not both).  Used for X every step and for W once,
+ *     when the layer is set up.
+ * knn_norm_backward_rows:  dV [n, D] fp32 from V [n, D] (dtype) and G [n, D] fp32 (the gradient with respect
+ *     to V / |V|, e.g. dX of knn_softmax_fwd_bwd); dV may alias G.
+ * apply_weight_grad_normalized -- Section 3.1 step 6 with the normalisation folded in.  dW_hat [n_max, D] is
+ *     the gradient with respect to the NORMALISED rows (dW_active of knn_softmax_fwd_bwd run on W_hat).  For
+ *     every class c that occurs in idx[0 .. n):  g = sum of its rows of dW_hat (ascending p);
+ *         W_master[c, :] += alpha * (g - w_hat <w_hat, g>) / |w|          (w = the row before the update)
+ *         inv_norm[c]     = 1 / |W_master[c, :]|                          (the row after the update)
+ *         W_hat_bf16[c,:] = bf16(fp32(W_master[c, :] * inv_norm[c]))
+ *     W_hat_bf16 and inv_norm may be NULL.  idx, n, idx_sorted_unique, dev_status as for apply_weight_grad;
+ *     the general path needs the workspace of apply_weight_grad_normalized_workspace (sort keys plus one
+ *     summed gradient row per position).
+ * All three require D % 4 == 0 and return KS_INVALID_ARG otherwise; all pointers are device pointers.
+ * ---------------------------------------------------------------------------------------------------- */
+int knn_normalize_rows(const void *V, int dtype, int64_t n, int D, uint16_t *V_hat_bf16, float *inv_norm,
+                       void *stream);
+int knn_norm_backward_rows(const void *V, int dtype, const float *G, int64_t n, int D, float *dV, void *stream);
+size_t apply_weight_grad_normalized_workspace(int64_t C, int D, int n_max, int idx_sorted_unique);
+int apply_weight_grad_normalized(float *W_master, uint16_t *W_hat_bf16, float *inv_norm, const int32_t *idx,
+                                 const int32_t *n, int n_max, const float *dW_hat, float alpha, int64_t C, int D,
+                                 int idx_sorted_unique, void *ws, size_t ws_bytes, int32_t *dev_status,
+                                 void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,9 @@ _LIB = None
 
 EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_select_workspace",
            "knn_select_active", "knn_gather_rows", "knn_softmax_workspace", "knn_softmax_fwd_bwd",
-           "full_softmax_workspace", "full_softmax_fwd_bwd", "apply_weight_grad_workspace", "apply_weight_grad")
+           "full_softmax_workspace", "full_softmax_fwd_bwd", "apply_weight_grad_workspace", "apply_weight_grad",
+           "knn_normalize_rows", "knn_norm_backward_rows", "apply_weight_grad_normalized_workspace",
+           "apply_weight_grad_normalized")
 
 
 class KsError(RuntimeError):
@@ -72,6 +74,10 @@ def _need(t, dtype, name):
     if t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
         raise TypeError(f"{name} must be a contiguous device tensor of {dtype}")
     return t
+
+
+def _dtype_code(t):
+    return 0 if t.dtype == torch.bfloat16 else 1  # KS_DTYPE_BF16 / KS_DTYPE_FP32
 
 
 def _ws(nbytes, device, ws):
@@ -248,4 +254,66 @@ def apply_weight_grad(W_master, W_bf16, idx, n, dW, alpha, idx_sorted_unique=Fal
                                  ct.c_float(alpha), ct.c_int64(C), ct.c_int(D), ct.c_int(int(idx_sorted_unique)),
                                  _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
     _check("apply_weight_grad", rc)
+    return dev_status
+
+
+def knn_normalize_rows(V, want_bf16=True, want_inv_norm=True, stream=None):
+    """Rows of V (bf16 or fp32) divided by their L2 norm.  Returns (V_hat bf16 or None, inv_norm fp32 or None)."""
+    if V.dtype not in (torch.bfloat16, torch.float32):
+        raise TypeError("V must be bfloat16 or float32")
+    _need(V, V.dtype, "V")
+    n, D = V.shape
+    Vh = torch.empty((n, D), dtype=torch.bfloat16, device=V.device) if want_bf16 else None
+    inv = torch.empty(n, dtype=torch.float32, device=V.device) if want_inv_norm else None
+    rc = lib().knn_normalize_rows(_ptr(V), ct.c_int(_dtype_code(V)), ct.c_int64(n), ct.c_int(D), _ptr(Vh), _ptr(inv),
+                                  _stream(stream))
+    _check("knn_normalize_rows", rc)
+    return Vh, inv
+
+
+def knn_norm_backward_rows(V, G, out=None, stream=None):
+    """Gradient with respect to the rows of V from the gradient G (fp32) with respect to V / |V|."""
+    if V.dtype not in (torch.bfloat16, torch.float32):
+        raise TypeError("V must be bfloat16 or float32")
+    _need(V, V.dtype, "V")
+    _need(G, torch.float32, "G")
+    n, D = V.shape
+    if tuple(G.shape) != (n, D):
+        raise ValueError("G must be [n, D]")
+    if out is None:
+        out = torch.empty_like(G)
+    _need(out, torch.float32, "out")
+    rc = lib().knn_norm_backward_rows(_ptr(V), ct.c_int(_dtype_code(V)), _ptr(G), ct.c_int64(n), ct.c_int(D), _ptr(out),
+                                      _stream(stream))
+    _check("knn_norm_backward_rows", rc)
+    return out
+
+
+def apply_weight_grad_normalized_workspace(C, D, n_max, idx_sorted_unique) -> int:
+    return int(lib().apply_weight_grad_normalized_workspace(ct.c_int64(C), ct.c_int(D), ct.c_int(n_max),
+                                                            ct.c_int(int(idx_sorted_unique))))
+
+
+def apply_weight_grad_normalized(W_master, W_hat_bf16, inv_norm, idx, n, dW_hat, alpha, idx_sorted_unique=False, ws=None,
+                                 dev_status=None, stream=None):
+    """In-place update of W_master (fp32), of the normalised copy W_hat_bf16 and of inv_norm (either may be None)
+    from gradients with respect to the normalised rows."""
+    _need(W_master, torch.float32, "W_master")
+    _need(idx, torch.int32, "idx")
+    _need(dW_hat, torch.float32, "dW_hat")
+    if W_hat_bf16 is not None:
+        _need(W_hat_bf16, torch.bfloat16, "W_hat_bf16")
+    if inv_norm is not None:
+        _need(inv_norm, torch.float32, "inv_norm")
+    C, D = W_master.shape
+    n_max = idx.numel()
+    if dW_hat.shape[0] < n_max or dW_hat.shape[1] != D:
+        raise ValueError("dW_hat must be [n_max, D]")
+    ws = _ws(apply_weight_grad_normalized_workspace(C, D, n_max, idx_sorted_unique), W_master.device, ws)
+    dev_status = _status(W_master.device, dev_status)
+    rc = lib().apply_weight_grad_normalized(_ptr(W_master), _ptr(W_hat_bf16), _ptr(inv_norm), _ptr(idx), _ptr(n),
+                                            ct.c_int(n_max), _ptr(dW_hat), ct.c_float(alpha), ct.c_int64(C), ct.c_int(D),
+                                            ct.c_int(int(idx_sorted_unique)), _ptr(ws), ct.c_size_t(ws.numel()),
+                                            _ptr(dev_status), _stream(stream))
+    _check("apply_weight_grad_normalized", rc)
     return dev_status

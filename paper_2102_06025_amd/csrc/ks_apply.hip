@@ -150,6 +150,189 @@ apply_segments_kernel(float *__restrict__ Wm, uint16_t *__restrict__ Wb, const u
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Normalisation inside the layer (paper Section 3.2.1: W and X are normalised on the GPU): the layer keeps
+// W un-normalised in fp32, its matrix kernels read the normalised 16-bit copy W_hat = W / |W| (row-wise), and
+// gradients with respect to normalised rows are brought back through
+//     dv = (g - v_hat <v_hat, g>) / |v|.
+// All of it is row-local HBM-bound work: one wavefront per row, the row's two or three reductions in fp64.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ double ap_wave_sum_d(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const int lo = __shfl_xor(__double2loint(v), o, 64), hi = __shfl_xor(__double2hiint(v), o, 64);
+        v += __hiloint2double(hi, lo);
+    }
+    return v;
+}
+template <typename IN> struct ApElem4;
+template <> struct ApElem4<float> {
+    static __device__ __forceinline__ float4 load(const float *p) { return *(const float4 *)p; }
+};
+template <> struct ApElem4<uint16_t> {
+    static __device__ __forceinline__ float4 load(const uint16_t *p) {
+        const uint2 v = *(const uint2 *)p;
+        return make_float4(ks_bf2f(v.x & 0xFFFFu), ks_bf2f(v.x >> 16), ks_bf2f(v.y & 0xFFFFu), ks_bf2f(v.y >> 16));
+    }
+};
+__device__ __forceinline__ double ap_dot4(float4 a, float4 b, double acc) {
+    acc = __builtin_fma((double)a.x, (double)b.x, acc);
+    acc = __builtin_fma((double)a.y, (double)b.y, acc);
+    acc = __builtin_fma((double)a.z, (double)b.z, acc);
+    return __builtin_fma((double)a.w, (double)b.w, acc);
+}
+
+// V_hat_bf16[i,:] = bf16(fp32(V[i,:] / |V[i,:]|)), inv_norm[i] = 1 / |V[i,:]| (0 for a zero row)
+template <typename IN>
+__global__ void __launch_bounds__(AP_NT)
+normalize_rows_kernel(const IN *__restrict__ V, int64_t n, int D, uint16_t *__restrict__ Vh, float *__restrict__ inv_norm) {
+    const int64_t i = (int64_t)blockIdx.x * (AP_NT / 64) + (threadIdx.x >> 6);
+    if (i >= n) return;
+    const int lane = threadIdx.x & 63;
+    const IN *v = V + i * D;
+    double ss = 0.0;
+    for (int d = lane * 4; d < D; d += 256) {
+        const float4 x = ApElem4<IN>::load(v + d);
+        ss = ap_dot4(x, x, ss);
+    }
+    ss = ap_wave_sum_d(ss);
+    const double inv = ss > 0.0 ? 1.0 / sqrt(ss) : 0.0;
+    if (lane == 0 && inv_norm) inv_norm[i] = (float)inv;
+    if (!Vh) return;
+    for (int d = lane * 4; d < D; d += 256) {
+        const float4 x = ApElem4<IN>::load(v + d);
+        const float h0 = (float)((double)x.x * inv), h1 = (float)((double)x.y * inv), h2 = (float)((double)x.z * inv),
+                    h3 = (float)((double)x.w * inv);
+        *(uint2 *)(Vh + i * D + d) = make_uint2(ks_pack_bf2(h0, h1), ks_pack_bf2(h2, h3));
+    }
+}
+
+// dV[i,:] = (G[i,:] - v_hat <v_hat, G[i,:]>) / |v|   (dV may be G)
+template <typename IN>
+__global__ void __launch_bounds__(AP_NT)
+norm_backward_rows_kernel(const IN *__restrict__ V, const float *__restrict__ G, int64_t n, int D, float *__restrict__ dV) {
+    const int64_t i = (int64_t)blockIdx.x * (AP_NT / 64) + (threadIdx.x >> 6);
+    if (i >= n) return;
+    const int lane = threadIdx.x & 63;
+    const IN *v = V + i * D;
+    const float *g = G + i * D;
+    double ss = 0.0, dot = 0.0;
+    for (int d = lane * 4; d < D; d += 256) {
+        const float4 x = ApElem4<IN>::load(v + d);
+        ss = ap_dot4(x, x, ss);
+        dot = ap_dot4(x, *(const float4 *)(g + d), dot);
+    }
+    ss = ap_wave_sum_d(ss);
+    dot = ap_wave_sum_d(dot);
+    const double inv = ss > 0.0 ? 1.0 / sqrt(ss) : 0.0;
+    const double c = dot * inv * inv; // <v_hat, g> / |v|
+    for (int d = lane * 4; d < D; d += 256) {
+        const float4 x = ApElem4<IN>::load(v + d);
+        const float4 gg = *(const float4 *)(g + d);
+        float4 o;
+        o.x = (float)(((double)gg.x - (double)x.x * c) * inv);
+        o.y = (float)(((double)gg.y - (double)x.y * c) * inv);
+        o.z = (float)(((double)gg.z - (double)x.z * c) * inv);
+        o.w = (float)(((double)gg.w - (double)x.w * c) * inv);
+        *(float4 *)(dV + i * D + d) = o;
+    }
+}
+
+// one wavefront: master row w of class c updated from the gradient g with respect to its normalised copy
+__device__ __forceinline__ void ap_update_row_normalized(float *__restrict__ w, uint16_t *__restrict__ wh,
+                                                         float *__restrict__ inv_out, const float *__restrict__ g,
+                                                         double alpha, int D) {
+    const int lane = threadIdx.x & 63;
+    double ss = 0.0, dot = 0.0;
+    for (int d = lane * 4; d < D; d += 256) {
+        const float4 x = *(const float4 *)(w + d);
+        ss = ap_dot4(x, x, ss);
+        dot = ap_dot4(x, *(const float4 *)(g + d), dot);
+    }
+    ss = ap_wave_sum_d(ss);
+    dot = ap_wave_sum_d(dot);
+    const double inv = ss > 0.0 ? 1.0 / sqrt(ss) : 0.0;
+    const double c = dot * inv * inv;
+    double s2 = 0.0;
+    for (int d = lane * 4; d < D; d += 256) { // second pass over the row (it is in cache)
+        float4 x = *(const float4 *)(w + d);
+        const float4 gg = *(const float4 *)(g + d);
+        if (ss > 0.0) {
+            x.x = (float)((double)x.x + alpha * (((double)gg.x - (double)x.x * c) * inv));
+            x.y = (float)((double)x.y + alpha * (((double)gg.y - (double)x.y * c) * inv));
+            x.z = (float)((double)x.z + alpha * (((double)gg.z - (double)x.z * c) * inv));
+            x.w = (float)((double)x.w + alpha * (((double)gg.w - (double)x.w * c) * inv));
+            *(float4 *)(w + d) = x;
+        }
+        s2 = ap_dot4(x, x, s2);
+    }
+    s2 = ap_wave_sum_d(s2);
+    const double inv2 = s2 > 0.0 ? 1.0 / sqrt(s2) : 0.0;
+    if (lane == 0 && inv_out) *inv_out = (float)inv2;
+    if (!wh) return;
+    __builtin_amdgcn_s_waitcnt(0x0070); // vmcnt(0): this wavefront's stores of the row are done before it is read back
+    for (int d = lane * 4; d < D; d += 256) {
+        const float4 x = *(const float4 *)(w + d);
+        const float h0 = (float)((double)x.x * inv2), h1 = (float)((double)x.y * inv2), h2 = (float)((double)x.z * inv2),
+                    h3 = (float)((double)x.w * inv2);
+        *(uint2 *)(wh + d) = make_uint2(ks_pack_bf2(h0, h1), ks_pack_bf2(h2, h3));
+    }
+}
+
+// strictly ascending idx: one wavefront per position
+__global__ void __launch_bounds__(AP_NT)
+apply_norm_sorted_kernel(float *__restrict__ Wm, uint16_t *__restrict__ Wh, float *__restrict__ inv_norm,
+                         const int32_t *__restrict__ idx, const int32_t *__restrict__ n_p, int n_max,
+                         const float *__restrict__ dW, float alpha, int64_t C, int D, int32_t *dev_status) {
+    const int n = ap_count(n_p, n_max, dev_status);
+    const int p = blockIdx.x * (AP_NT / 64) + (threadIdx.x >> 6);
+    if (p >= n) return;
+    const int32_t c = idx[p];
+    const bool lane0 = (threadIdx.x & 63) == 0;
+    if (c < 0 || c >= C) {
+        if (lane0) ks_flag(dev_status, KS_DEV_BAD_INDEX);
+        return;
+    }
+    if (p > 0 && idx[p - 1] >= c) {
+        if (lane0) ks_flag(dev_status, KS_DEV_IDX_NOT_SORTED);
+        return;
+    }
+    ap_update_row_normalized(Wm + (int64_t)c * D, Wh ? Wh + (int64_t)c * D : nullptr, inv_norm ? inv_norm + c : nullptr,
+                             dW + (int64_t)p * D, (double)alpha, D);
+}
+
+// repeated idx: the head of a segment of the sorted keys sums its rows (ascending position) into its row of
+// `gsum`, then updates the class from that sum
+__global__ void __launch_bounds__(AP_NT)
+apply_norm_segments_kernel(float *__restrict__ Wm, uint16_t *__restrict__ Wh, float *__restrict__ inv_norm,
+                           const uint64_t *__restrict__ keys, int n_pow2, const float *__restrict__ dW, float alpha, int D,
+                           float *__restrict__ gsum) {
+    const int q = blockIdx.x * (AP_NT / 64) + (threadIdx.x >> 6);
+    if (q >= n_pow2) return;
+    const uint64_t key = keys[q];
+    if (key == ~0ull) return;
+    const uint32_t c = (uint32_t)(key >> 32);
+    if (q > 0 && (uint32_t)(keys[q - 1] >> 32) == c) return; // not the head of its segment
+    const int lane = threadIdx.x & 63;
+    float *gs = gsum + (int64_t)q * D;
+    for (int d = lane * 4; d < D; d += 256) {
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0; // fp64 sum, rounded to fp32 once
+        for (int r = q; r < n_pow2; ++r) {
+            const uint64_t kr = keys[r];
+            if ((uint32_t)(kr >> 32) != c || kr == ~0ull) break;
+            const float4 v = *(const float4 *)(dW + (int64_t)(uint32_t)kr * D + d);
+            s0 += v.x; s1 += v.y; s2 += v.z; s3 += v.w;
+        }
+        *(float4 *)(gs + d) = make_float4((float)s0, (float)s1, (float)s2, (float)s3);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0070); // vmcnt(0): the sum is in memory before the wavefront reads it back
+    ap_update_row_normalized(Wm + (int64_t)c * D, Wh ? Wh + (int64_t)c * D : nullptr, inv_norm ? inv_norm + c : nullptr, gs,
+                             (double)alpha, D);
+}
+
+static void ap_sort_keys(const int32_t *idx, const int32_t *n, int n_max, int np2, int64_t C, uint64_t *keys,
+                         int32_t *dev_status, hipStream_t st);
 static int ap_pow2(int n) {
     int p = 1;
     while (p < n) p <<= 1;
@@ -179,9 +362,18 @@ extern "C" int apply_weight_grad(float *W_master, uint16_t *W_bf16, const int32_
     if (ws_bytes < apply_weight_grad_workspace(C, D, n_max, 0)) return KS_WORKSPACE_TOO_SMALL;
     const int np2 = ap_pow2(n_max);
     uint64_t *keys = (uint64_t *)ws;
+    ap_sort_keys(idx, n, n_max, np2, C, keys, dev_status, st); // steps with j < AP_CHUNK run in LDS, the others one launch each
+    hipLaunchKernelGGL(apply_segments_kernel, dim3((unsigned)ks_ceil_div(np2, AP_NT / 64)), dim3(AP_NT), 0, st, W_master,
+                       W_bf16, keys, np2, dW, alpha, D);
+    KS_LAUNCH_CHECK();
+    return KS_OK;
+}
+
+// sort of the (class, position) keys shared by the two update entry points
+static void ap_sort_keys(const int32_t *idx, const int32_t *n, int n_max, int np2, int64_t C, uint64_t *keys,
+                         int32_t *dev_status, hipStream_t st) {
     const unsigned gb = (unsigned)ks_ceil_div(np2, AP_NT);
     hipLaunchKernelGGL(apply_keys_kernel, dim3(gb), dim3(AP_NT), 0, st, idx, n, n_max, np2, C, keys, dev_status);
-    // steps with j < AP_CHUNK run in LDS, the others as one launch per step
     const unsigned cb = (unsigned)ks_ceil_div(np2, AP_CHUNK);
     hipLaunchKernelGGL(apply_bitonic_lds_kernel, dim3(cb), dim3(AP_NT), 0, st, keys, np2, 2, np2 < AP_CHUNK ? np2 : AP_CHUNK);
     for (int k = AP_CHUNK * 2; k <= np2; k <<= 1) {
@@ -189,8 +381,68 @@ extern "C" int apply_weight_grad(float *W_master, uint16_t *W_bf16, const int32_
             hipLaunchKernelGGL(apply_bitonic_kernel, dim3(gb), dim3(AP_NT), 0, st, keys, np2, k, j);
         hipLaunchKernelGGL(apply_bitonic_lds_kernel, dim3(cb), dim3(AP_NT), 0, st, keys, np2, k, k);
     }
-    hipLaunchKernelGGL(apply_segments_kernel, dim3((unsigned)ks_ceil_div(np2, AP_NT / 64)), dim3(AP_NT), 0, st, W_master,
-                       W_bf16, keys, np2, dW, alpha, D);
+}
+
+extern "C" int knn_normalize_rows(const void *V, int dtype, int64_t n, int D, uint16_t *V_hat_bf16, float *inv_norm,
+                                  void *stream) {
+    if (!V || (!V_hat_bf16 && !inv_norm)) return KS_INVALID_ARG;
+    if (n < 1 || D < 4 || D % 4 != 0) return KS_INVALID_ARG;
+    if (dtype != KS_DTYPE_BF16 && dtype != KS_DTYPE_FP32) return KS_INVALID_ARG;
+    const dim3 grid((unsigned)ks_ceil_div(n, AP_NT / 64));
+    if (dtype == KS_DTYPE_FP32)
+        hipLaunchKernelGGL(normalize_rows_kernel<float>, grid, dim3(AP_NT), 0, (hipStream_t)stream, (const float *)V, n, D,
+                           V_hat_bf16, inv_norm);
+    else
+        hipLaunchKernelGGL(normalize_rows_kernel<uint16_t>, grid, dim3(AP_NT), 0, (hipStream_t)stream, (const uint16_t *)V, n,
+                           D, V_hat_bf16, inv_norm);
+    KS_LAUNCH_CHECK();
+    return KS_OK;
+}
+
+extern "C" int knn_norm_backward_rows(const void *V, int dtype, const float *G, int64_t n, int D, float *dV, void *stream) {
+    if (!V || !G || !dV) return KS_INVALID_ARG;
+    if (n < 1 || D < 4 || D % 4 != 0) return KS_INVALID_ARG;
+    if (dtype != KS_DTYPE_BF16 && dtype != KS_DTYPE_FP32) return KS_INVALID_ARG;
+    const dim3 grid((unsigned)ks_ceil_div(n, AP_NT / 64));
+    if (dtype == KS_DTYPE_FP32)
+        hipLaunchKernelGGL(norm_backward_rows_kernel<float>, grid, dim3(AP_NT), 0, (hipStream_t)stream, (const float *)V, G, n,
+                           D, dV);
+    else
+        hipLaunchKernelGGL(norm_backward_rows_kernel<uint16_t>, grid, dim3(AP_NT), 0, (hipStream_t)stream,
+                           (const uint16_t *)V, G, n, D, dV);
+    KS_LAUNCH_CHECK();
+    return KS_OK;
+}
+
+extern "C" size_t apply_weight_grad_normalized_workspace(int64_t C, int D, int n_max, int idx_sorted_unique) {
+    (void)C;
+    if (n_max < 1 || D < 4) return 0;
+    if (idx_sorted_unique) return 256;
+    const size_t np2 = (size_t)ap_pow2(n_max);
+    return ks_align_up(np2 * sizeof(uint64_t), 256) + ks_align_up(np2 * (size_t)D * sizeof(float), 256);
+}
+
+extern "C" int apply_weight_grad_normalized(float *W_master, uint16_t *W_hat_bf16, float *inv_norm, const int32_t *idx,
+                                            const int32_t *n, int n_max, const float *dW_hat, float alpha, int64_t C, int D,
+                                            int idx_sorted_unique, void *ws, size_t ws_bytes, int32_t *dev_status,
+                                            void *stream) {
+    if (!W_master || !idx || !dW_hat) return KS_INVALID_ARG;
+    if (n_max < 1 || C < 1 || C >= (int64_t)1 << 31 || D < 4 || D % 4 != 0) return KS_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (idx_sorted_unique) {
+        hipLaunchKernelGGL(apply_norm_sorted_kernel, dim3((unsigned)ks_ceil_div(n_max, AP_NT / 64)), dim3(AP_NT), 0, st,
+                           W_master, W_hat_bf16, inv_norm, idx, n, n_max, dW_hat, alpha, C, D, dev_status);
+        KS_LAUNCH_CHECK();
+        return KS_OK;
+    }
+    if (!ws) return KS_INVALID_ARG;
+    if (ws_bytes < apply_weight_grad_normalized_workspace(C, D, n_max, 0)) return KS_WORKSPACE_TOO_SMALL;
+    const int np2 = ap_pow2(n_max);
+    uint64_t *keys = (uint64_t *)ws;
+    float *gsum = (float *)((char *)ws + ks_align_up((size_t)np2 * sizeof(uint64_t), 256));
+    ap_sort_keys(idx, n, n_max, np2, C, keys, dev_status, st);
+    hipLaunchKernelGGL(apply_norm_segments_kernel, dim3((unsigned)ks_ceil_div(np2, AP_NT / 64)), dim3(AP_NT), 0, st, W_master,
+                       W_hat_bf16, inv_norm, keys, np2, dW_hat, alpha, D, gsum);
     KS_LAUNCH_CHECK();
     return KS_OK;
 }

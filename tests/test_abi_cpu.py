@@ -23,12 +23,13 @@ def ks():
 def _declared_functions():
     src = open(HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad))\s*\(", src)))
+    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized))\s*\(", src)))
 
 
 def test_header_symbols_are_exported(ks):
     names = _declared_functions()
-    assert {"knn_graph_build", "knn_softmax_fwd_bwd", "apply_weight_grad"} <= set(names)
+    assert {"knn_graph_build", "knn_softmax_fwd_bwd", "apply_weight_grad", "apply_weight_grad_normalized",
+            "knn_normalize_rows", "knn_norm_backward_rows"} <= set(names)
     L = ks.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in the header but not exported"
@@ -92,6 +93,20 @@ def test_argument_errors_are_reported_before_any_launch(ks):
     assert apply(n_max=0) == ks.KS_INVALID_ARG
     assert apply(D=6) == ks.KS_INVALID_ARG
     assert apply(sorted_=0, ws_bytes=8) == ks.KS_WORKSPACE_TOO_SMALL
+
+    def apply_n(n_max=10, D=128, sorted_=1, ws=one, ws_bytes=0, Wm=one):
+        return L.apply_weight_grad_normalized(Wm, one, one, one, null, i(n_max), one, f(-0.1), i64(1000), i(D), i(sorted_),
+                                              ws, sz(ws_bytes), null, null)
+
+    assert apply_n(Wm=null) == ks.KS_INVALID_ARG
+    assert apply_n(D=6) == ks.KS_INVALID_ARG
+    assert apply_n(sorted_=0, ws=null) == ks.KS_INVALID_ARG
+    assert apply_n(sorted_=0, ws_bytes=8) == ks.KS_WORKSPACE_TOO_SMALL
+    assert ks.apply_weight_grad_normalized_workspace(1000, 128, 100, 0) >= 128 * 8 + 128 * 128 * 4
+    assert L.knn_normalize_rows(one, i(0), i64(4), i(128), null, null, null) == ks.KS_INVALID_ARG   # no output
+    assert L.knn_normalize_rows(one, i(3), i64(4), i(128), one, one, null) == ks.KS_INVALID_ARG     # dtype
+    assert L.knn_normalize_rows(one, i(0), i64(4), i(6), one, one, null) == ks.KS_INVALID_ARG       # D % 4
+    assert L.knn_norm_backward_rows(one, i(1), null, i64(4), i(128), one, null) == ks.KS_INVALID_ARG
     assert L.knn_select_active(one, one, i64(100), i(8), i(4), i(4), one, one, one, one, sz(1 << 20), null,
                                null) == ks.KS_INVALID_ARG  # B > M
 
