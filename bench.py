@@ -258,6 +258,46 @@ def main():
         roofline = dict(bound="hbm", achieved=phases[dom]["gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
                         frac=phases[dom]["frac"], traffic=traffic, kernel=dom)
 
+    # ---- the layer with un-normalised fp32 weights (normalisation inside the layer, Section 3.2.1): the same step
+    # with X normalised on the way in, dX projected on the way out and the weight update through the
+    # normalisation; timed after the headline region, reported beside it
+    inv_norm = torch.empty(C, dtype=torch.float32, device="cuda")
+    ks.knn_normalize_rows(W_master, out_bf16=W_bf, out_inv_norm=inv_norm)
+    X_raw = torch.from_numpy(X).cuda()
+    dX_raw = torch.empty_like(out["dX"])
+
+    def step_normalized():
+        ks.knn_normalize_rows(X_raw, want_inv_norm=False, out_bf16=X_bf)
+        ks.knn_softmax_fwd_bwd(W_bf, X_bf, labels, graph, M, scale, grad_scale, out=out, ws=ws, unit_rows=True)
+        ks.knn_norm_backward_rows(X_raw, out["dX"], out=dX_raw)
+        ks.apply_weight_grad_normalized(W_master, W_bf, inv_norm, out["active_idx"], out["n_active"], out["dW_active"],
+                                        alpha, idx_sorted_unique=True, ws=ws, dev_status=out["dev_status"])
+
+    for _ in range(args.warmup):
+        step_normalized()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step_normalized()
+    torch.cuda.synchronize()
+    ms_norm_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    nev = hev.create(2)
+    hev.record(nev[0], stream)
+    for s in range(args.steps):
+        ks.apply_weight_grad_normalized(W_master, W_bf, inv_norm, out["active_idx"], out["n_active"], out["dW_active"],
+                                        alpha, idx_sorted_unique=True, ws=ws, dev_status=out["dev_status"])
+    hev.record(nev[1], stream)
+    torch.cuda.synchronize()
+    us_apply_n = hev.elapsed_ms(nev[0], nev[1]) * 1e3 / args.steps
+    assert int(out["dev_status"].item()) == 0
+    bytes_apply_n = A * (D * (4.0 + 4.0 + 4.0 + 2.0) + 4.0)
+    normalized_layer = dict(ms_per_step=round(ms_norm_step, 4), samples_per_s=round(B / (ms_norm_step * 1e-3), 1),
+                            step="normalize X + select + knn_softmax_fwd_bwd + project dX + apply_weight_grad_normalized",
+                            apply_normalized=dict(us=round(us_apply_n, 2), bound="hbm",
+                                                  gbs=round(bytes_apply_n / (us_apply_n * 1e-6) / 1e9, 1),
+                                                  frac=round(bytes_apply_n / (us_apply_n * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)))
+    log(f"[bench] layer with normalisation inside: {ms_norm_step:.4f} ms/step, apply_normalized {us_apply_n:.1f} us")
+
     # ---- CPU oracle on the same inputs: baseline + full-size parity of the first step -----------------------
     cpu_baseline, parity = None, None
     if not args.no_cpu_baseline:
@@ -304,6 +344,7 @@ def main():
         "phases": phases,
         "graph_build": {"ms": round(graph_best, 2), "tflops": round(graph_tflops, 1),
                         "frac": round(graph_tflops / PEAK_BF16_TFLOPS, 4), "bound": "mfma"},
+        "normalized_layer": normalized_layer,
         "parity": parity,
     }
     print(json.dumps(res), flush=True)

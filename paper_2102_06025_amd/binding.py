@@ -257,14 +257,21 @@ def apply_weight_grad(W_master, W_bf16, idx, n, dW, alpha, idx_sorted_unique=Fal
     return dev_status
 
 
-def knn_normalize_rows(V, want_bf16=True, want_inv_norm=True, stream=None):
-    """Rows of V (bf16 or fp32) divided by their L2 norm.  Returns (V_hat bf16 or None, inv_norm fp32 or None)."""
+def knn_normalize_rows(V, want_bf16=True, want_inv_norm=True, out_bf16=None, out_inv_norm=None, stream=None):
+    """Rows of V (bf16 or fp32) divided by their L2 norm.  Returns (V_hat bf16 or None, inv_norm fp32 or None);
+    `out_bf16` / `out_inv_norm` are used as the outputs when given."""
     if V.dtype not in (torch.bfloat16, torch.float32):
         raise TypeError("V must be bfloat16 or float32")
     _need(V, V.dtype, "V")
     n, D = V.shape
-    Vh = torch.empty((n, D), dtype=torch.bfloat16, device=V.device) if want_bf16 else None
-    inv = torch.empty(n, dtype=torch.float32, device=V.device) if want_inv_norm else None
+    Vh = out_bf16 if out_bf16 is not None else (
+        torch.empty((n, D), dtype=torch.bfloat16, device=V.device) if want_bf16 else None)
+    inv = out_inv_norm if out_inv_norm is not None else (
+        torch.empty(n, dtype=torch.float32, device=V.device) if want_inv_norm else None)
+    if Vh is not None and (_need(Vh, torch.bfloat16, "out_bf16").numel() != n * D):
+        raise ValueError("out_bf16 must be [n, D]")
+    if inv is not None and (_need(inv, torch.float32, "out_inv_norm").numel() != n):
+        raise ValueError("out_inv_norm must be [n]")
     rc = lib().knn_normalize_rows(_ptr(V), ct.c_int(_dtype_code(V)), ct.c_int64(n), ct.c_int(D), _ptr(Vh), _ptr(inv),
                                   _stream(stream))
     _check("knn_normalize_rows", rc)
