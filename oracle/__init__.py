@@ -26,7 +26,8 @@ def lib():
         _lib.orc_num_threads.restype = ct.c_int
         for name in ("orc_graph_bruteforce", "orc_select_active", "orc_knn_softmax_fwd_bwd",
                      "orc_full_softmax_fwd_bwd", "orc_apply_weight_grad", "orc_normalize_rows", "orc_norm_backward",
-                     "orc_apply_weight_grad_normalized"):
+                     "orc_apply_weight_grad_normalized", "orc_graph_compress", "orc_pad_draws",
+                     "orc_select_active_csr"):
             getattr(_lib, name).restype = ct.c_int
     return _lib
 
@@ -182,3 +183,51 @@ def apply_weight_grad_normalized(W_master, idx, dW_hat, alpha: float):
     if rc != ORC_OK:
         raise ValueError(f"orc_apply_weight_grad_normalized failed with code {rc}")
     return Wm, Wb, inv
+
+
+def graph_compress(G, c0: int, C_loc: int):
+    """Compressed graph of the node that owns classes [c0, c0 + C_loc): (counts int32 [Cg], offsets int64 [Cg + 1],
+    flat int32 [offsets[-1]] of local ids)."""
+    G = _i32(G)
+    Cg, K = G.shape
+    counts = np.empty(Cg, dtype=np.int32)
+    offsets = np.empty(Cg + 1, dtype=np.int64)
+    args = (_p(G, ct.c_int32), ct.c_int64(Cg), ct.c_int(K), ct.c_int64(c0), ct.c_int64(C_loc), _p(counts, ct.c_int32),
+            _p(offsets, ct.c_int64))
+    rc = lib().orc_graph_compress(*args, None)
+    if rc != ORC_OK:
+        raise ValueError(f"orc_graph_compress failed with code {rc}")
+    flat = np.empty(max(int(offsets[-1]), 1), dtype=np.int32)
+    rc = lib().orc_graph_compress(*args, _p(flat, ct.c_int32))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_graph_compress failed with code {rc}")
+    return counts, offsets, flat[:int(offsets[-1])]
+
+
+def pad_draws(C_loc: int, seed: int, n: int):
+    """The first n draws of the fill-up order for a node with C_loc classes (values in [0, 2^b))."""
+    out = np.empty(n, dtype=np.uint32)
+    rc = lib().orc_pad_draws(ct.c_int64(C_loc), ct.c_uint64(seed), ct.c_int64(n), _p(out, ct.c_uint32))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_pad_draws failed with code {rc}")
+    return out
+
+
+def select_active_csr(labels, counts, offsets, flat, c0: int, C_loc: int, M: int, pad: bool = False, seed: int = 0):
+    """Algorithm 1 on one node's compressed graph.  Returns (active int32 [M] of local ids padded with -1, n_active,
+    n_found, target_pos int32 [B] with -1 for labels the node does not own)."""
+    labels, counts, flat = _i32(labels), _i32(counts), _i32(flat)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    B, Cg = labels.shape[0], counts.shape[0]
+    if flat.shape[0] == 0:
+        flat = np.zeros(1, dtype=np.int32)
+    active = np.empty(M, dtype=np.int32)
+    n_active, n_found = ct.c_int32(0), ct.c_int32(0)
+    target_pos = np.empty(B, dtype=np.int32)
+    rc = lib().orc_select_active_csr(_p(labels, ct.c_int32), ct.c_int(B), _p(counts, ct.c_int32), _p(offsets, ct.c_int64),
+                                     _p(flat, ct.c_int32), ct.c_int64(Cg), ct.c_int64(c0), ct.c_int64(C_loc), ct.c_int(M),
+                                     ct.c_int(int(pad)), ct.c_uint64(seed), _p(active, ct.c_int32), ct.byref(n_active),
+                                     ct.byref(n_found), _p(target_pos, ct.c_int32))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_select_active_csr failed with code {rc}")
+    return active, int(n_active.value), int(n_found.value), target_pos

@@ -170,6 +170,132 @@ int orc_select_active(const int32_t *labels, int B, const int32_t *G, int64_t C,
 }
 
 /* ---------------------------------------------------------------------------------------------
+ * Compressed graph of one node (Section 3.2.3): the node that owns the classes [c0, c0 + C_loc) keeps, for every
+ * class g of the whole problem, only those neighbours of g that it owns, in the order of g's list, as ids local to
+ * the node; the lists, now of different lengths, are laid end to end (flat) with counts[g] entries starting at
+ * offsets[g] (offsets = running sum of the counts, offsets[Cg] = total).  Entries -1 of the dense graph are empty
+ * slots.  flat may be NULL (counts and offsets only).
+ * ------------------------------------------------------------------------------------------- */
+int orc_graph_compress(const int32_t *G, int64_t Cg, int K, int64_t c0, int64_t C_loc, int32_t *counts,
+                       int64_t *offsets, int32_t *flat) {
+    if (!G || !counts || !offsets || Cg < 1 || K < 0 || c0 < 0 || C_loc < 1 || c0 + C_loc > Cg) return ORC_BAD_ARG;
+    int64_t run = 0;
+    for (int64_t g = 0; g < Cg; ++g) {
+        offsets[g] = run;
+        int32_t n = 0;
+        for (int k = 0; k < K; ++k) {
+            const int32_t c = G[g * K + k];
+            if (c == -1) continue;
+            if (c < -1 || c >= Cg) return ORC_BAD_GRAPH_ID;
+            if (c >= c0 && c < c0 + C_loc) {
+                if (flat) flat[run + n] = (int32_t)(c - c0);
+                ++n;
+            }
+        }
+        counts[g] = n;
+        run += n;
+    }
+    offsets[Cg] = run;
+    return ORC_OK;
+}
+
+/* The order in which classes are drawn for the random fill-up of Algorithm 1: the k-th draw, k = 0, 1, ..., is
+ * class pad_draw(k) where pad_draw is a keyed one-to-one map of [0, 2^b) onto itself, 2^b the smallest power of
+ * two >= C_loc (every step below is one-to-one on b-bit numbers: adding a constant, multiplying by an odd
+ * constant, xor with a right shift of itself).  Draws >= C_loc or already in the set are passed over, so the
+ * fill-up is a sample without replacement of the classes not chosen.  The paper only says "random sample"; the
+ * map is this build's choice, implemented on both sides from this description. */
+static int pad_bits(int64_t C_loc) {
+    int b = 1;
+    while (((int64_t)1 << b) < C_loc) ++b;
+    return b;
+}
+static uint32_t pad_draw(uint32_t k, int b, uint64_t seed) {
+    const uint32_t mask = b >= 32 ? 0xFFFFFFFFu : (((uint32_t)1 << b) - 1u);
+    const int s1 = (b + 1) / 2, s2 = b / 3 > 0 ? b / 3 : 1;
+    uint32_t x = (k + (uint32_t)seed) & mask;
+    x = (x * 0x9E3779B1u) & mask;
+    x ^= x >> s1;
+    x = (x * 0x85EBCA6Bu) & mask;
+    x ^= x >> s2;
+    x = (x * 0xC2B2AE35u) & mask;
+    x ^= x >> s1;
+    x = (x + (uint32_t)(seed >> 32)) & mask;
+    return x;
+}
+int orc_pad_draws(int64_t C_loc, uint64_t seed, int64_t n, uint32_t *out) { /* the first n draws, for tests */
+    if (C_loc < 1 || C_loc > ((int64_t)1 << 31) || !out) return ORC_BAD_ARG;
+    const int b = pad_bits(C_loc);
+    for (int64_t k = 0; k < n; ++k) out[k] = pad_draw((uint32_t)k, b, seed);
+    return ORC_OK;
+}
+
+/* Algorithm 1 on a node of the sharded layer: labels are ids of the whole problem, the neighbour lists come from
+ * the node's compressed graph, the result holds ids local to the node.
+ *   - sample i contributes its own class at list position 0 if the node owns it, and entry j of the compressed
+ *     list of its class at position j + 1; a class's score is its smallest position; duplicates are removed;
+ *   - more than M classes found: the M best scores are kept, ties to the lowest local id;
+ *   - fewer than M found and pad != 0: filled up to min(M, C_loc) by the draws of pad_draw (see above);
+ *   - active: ascending local ids, -1 beyond n_active; n_found = classes found before the fill-up (capped at M);
+ *   - target_pos[i] = position of sample i's class in the active list, -1 if another node owns the class. */
+int orc_select_active_csr(const int32_t *labels, int B, const int32_t *counts, const int64_t *offsets,
+                          const int32_t *flat, int64_t Cg, int64_t c0, int64_t C_loc, int M, int pad, uint64_t seed,
+                          int32_t *active, int32_t *n_active, int32_t *n_found, int32_t *target_pos) {
+    if (!labels || !counts || !offsets || !active || !n_active || !target_pos) return ORC_BAD_ARG;
+    if (B < 1 || Cg < 1 || c0 < 0 || C_loc < 1 || c0 + C_loc > Cg || M < 1 || B > M) return ORC_BAD_ARG;
+    int32_t *score = (int32_t *)malloc(sizeof(int32_t) * (size_t)C_loc);
+    for (int64_t c = 0; c < C_loc; ++c) score[c] = INT32_MAX;
+    for (int i = 0; i < B; ++i) {
+        const int32_t y = labels[i];
+        if (y < 0 || y >= Cg) { free(score); return ORC_BAD_LABEL; }
+        if (y >= c0 && y < c0 + C_loc) score[y - c0] = 0;
+        if (counts[y] < 0 || counts[y] + 1 > M) { free(score); return ORC_BAD_ARG; }
+        for (int32_t j = 0; j < counts[y]; ++j) {
+            const int32_t c = flat[offsets[y] + j];
+            if (c == -1) continue;
+            if (c < -1 || c >= C_loc) { free(score); return ORC_BAD_GRAPH_ID; }
+            if (j + 1 < score[c]) score[c] = j + 1;
+        }
+    }
+    int64_t n_unique = 0;
+    for (int64_t c = 0; c < C_loc; ++c) n_unique += (score[c] != INT32_MAX);
+    scored_class *u = (scored_class *)malloc(sizeof(scored_class) * (size_t)(n_unique ? n_unique : 1));
+    int64_t n = 0;
+    for (int64_t c = 0; c < C_loc; ++c)
+        if (score[c] != INT32_MAX) { u[n].score = score[c]; u[n].cls = (int32_t)c; ++n; }
+    int64_t A = n_unique;
+    if (n_unique > M) {
+        qsort(u, (size_t)n_unique, sizeof(scored_class), cmp_scored);
+        A = M;
+    }
+    for (int64_t a = 0; a < A; ++a) active[a] = u[a].cls;
+    if (n_found) *n_found = (int32_t)A;
+    if (pad && A < M) {
+        const int64_t want = M < C_loc ? M : C_loc;
+        const int b = pad_bits(C_loc);
+        for (uint64_t k = 0; A < want && k < ((uint64_t)1 << b); ++k) {
+            const uint32_t c = pad_draw((uint32_t)k, b, seed);
+            if ((int64_t)c >= C_loc || score[c] != INT32_MAX) continue;
+            score[c] = INT32_MAX - 1; /* drawn */
+            active[A++] = (int32_t)c;
+        }
+    }
+    qsort(active, (size_t)A, sizeof(int32_t), cmp_i32);
+    for (int64_t a = A; a < M; ++a) active[a] = -1;
+    *n_active = (int32_t)A;
+    for (int i = 0; i < B; ++i) {
+        target_pos[i] = -1;
+        const int64_t y = (int64_t)labels[i] - c0;
+        if (y < 0 || y >= C_loc) continue;
+        for (int64_t a = 0; a < A; ++a)
+            if (active[a] == y) { target_pos[i] = (int32_t)a; break; }
+    }
+    free(u);
+    free(score);
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------------------------------------
  * Softmax stage on the active classes (Section 3.2: fc forward, softmax forward, softmax backward,
  * fc backward; standard softmax with cross-entropy restricted to the selected columns).
  *   Z_ia   = scale * sum_d X_id * W[active[a], d]

@@ -481,3 +481,123 @@ def test_apply_weight_grad_normalized_against_numpy(orc):
     n1 = np.sqrt((W64[touched] ** 2).sum(axis=1))
     step = np.sqrt(((Wm[touched] - W[touched]).astype(np.float64) ** 2).sum(axis=1))
     assert np.all(np.abs(n2 - n1) <= step ** 2 / n1 + 1e-6)
+
+
+# ------------------------------------------------------------------------------------------------
+# compressed graph of one node, selection on it, random fill-up (Section 3.2.3, Algorithm 1)
+# ------------------------------------------------------------------------------------------------
+def test_graph_compress_by_brute_force_and_partition(orc):
+    Cg, K = 37, 5
+    G = synth.graph_synthetic(3, Cg, K, locality=8, empty_frac=0.2)
+    bounds = [0, 10, 11, 30, 37]                                  # four nodes of unequal size (one owns one class)
+    seen = [[] for _ in range(Cg)]
+    for c0, c1 in zip(bounds[:-1], bounds[1:]):
+        counts, offsets, flat = orc.graph_compress(G, c0, c1 - c0)
+        assert offsets[0] == 0 and np.array_equal(offsets[1:], np.cumsum(counts)) and len(flat) == offsets[-1]
+        for g in range(Cg):
+            want = [int(c) - c0 for c in G[g] if c0 <= c < c1]   # the node's part of the list, order kept
+            assert flat[offsets[g]:offsets[g + 1]].tolist() == want
+            seen[g] += [c + c0 for c in want]
+    for g in range(Cg):                                           # the nodes' parts partition every list
+        assert sorted(seen[g]) == sorted(int(c) for c in G[g] if c >= 0)
+
+
+def test_selection_on_compressed_graph_hand_worked_case(orc):
+    # eight classes, the node owns 4..7; K = 3
+    G = np.array([[5, 1, 6], [4, 7, 2], [6, 5, 4], [0, 1, 2], [0, 1, 2], [0, 1, 2], [7, 0, 5], [0, 1, 2]], dtype=np.int32)
+    counts, offsets, flat = orc.graph_compress(G, 4, 4)
+    assert counts.tolist() == [2, 2, 3, 0, 0, 0, 2, 0]
+    assert flat.tolist() == [1, 2, 0, 3, 2, 1, 0, 3, 1]
+    labels = np.array([0, 1, 6], dtype=np.int32)
+    # sample 0 (class 0, another node's): local 1 at position 1, local 2 at 2; sample 1 (class 1): local 0 at 1,
+    # local 3 at 2; sample 2 (class 6 = local 2, owned): itself at 0, local 3 at 1, local 1 at 2
+    # => scores: local 0: 1, local 1: 1, local 2: 0, local 3: 1
+    a, n, nf, t = orc.select_active_csr(labels, counts, offsets, flat, 4, 4, 4)
+    assert (a.tolist(), n, nf, t.tolist()) == ([0, 1, 2, 3], 4, 4, [-1, -1, 2])
+    a, n, nf, t = orc.select_active_csr(labels, counts, offsets, flat, 4, 4, 3)
+    assert (a.tolist(), n, nf, t.tolist()) == ([0, 1, 2], 3, 3, [-1, -1, 2])    # score 0 first, then the lowest ids at score 1
+    # a node that owns none of the labels and nothing in their lists finds nothing
+    c2, o2, f2 = orc.graph_compress(G, 3, 1)
+    a, n, nf, t = orc.select_active_csr(labels, c2, o2, f2, 3, 1, 4)
+    assert (a.tolist(), n, nf, t.tolist()) == ([-1, -1, -1, -1], 0, 0, [-1, -1, -1])
+
+
+@pytest.mark.parametrize("Cg,K,B,M,seed", [(500, 6, 40, 400, 0), (500, 6, 40, 60, 1), (2000, 12, 100, 300, 2)])
+def test_selection_on_one_node_owning_everything_equals_the_dense_selection(orc, Cg, K, B, M, seed):
+    G = synth.graph_synthetic(seed, Cg, K, locality=16)          # no empty slots: positions survive the compression
+    labels = synth.labels_uniform(seed, B, Cg)
+    counts, offsets, flat = orc.graph_compress(G, 0, Cg)
+    assert (counts == K).all() and np.array_equal(flat.reshape(Cg, K), G)
+    a0, n0, t0 = orc.select_active(labels, G, Cg, M)
+    a1, n1, nf, t1 = orc.select_active_csr(labels, counts, offsets, flat, 0, Cg, M)
+    assert n0 == n1 == nf and np.array_equal(a0, a1) and np.array_equal(t0, t1)
+
+
+def test_selection_over_all_nodes_reassembles_the_dense_selection(orc):
+    Cg, K, B, P = 3000, 10, 64, 4
+    G = synth.graph_synthetic(5, Cg, K, locality=32, empty_frac=0.1)
+    labels = synth.labels_uniform(5, B, Cg)
+    M = 2000                                                      # no cut anywhere
+    a0, n0, t0 = orc.select_active(labels, G, Cg, M)
+    union, owners = [], np.zeros(B, dtype=int)
+    for p in range(P):
+        c0, C_loc = p * Cg // P, (p + 1) * Cg // P - p * Cg // P
+        counts, offsets, flat = orc.graph_compress(G, c0, C_loc)
+        a, n, nf, t = orc.select_active_csr(labels, counts, offsets, flat, c0, C_loc, M)
+        assert n == nf and (a[n:] == -1).all() and (np.diff(a[:n]) > 0).all()
+        union += (a[:n] + c0).tolist()
+        own = (labels >= c0) & (labels < c0 + C_loc)
+        assert (t[~own] == -1).all() and np.array_equal(a[t[own]] + c0, labels[own])
+        owners += own
+    assert (owners == 1).all() and union == a0[:n0].tolist()      # ascending node by node = ascending overall
+
+
+def test_fill_up_order_is_one_to_one(orc):
+    for C_loc, seed in [(1, 0), (2, 1), (3, 2), (64, 3), (65, 4), (1000, 5), (390625, 6), (390625, 7 << 40)]:
+        b = max(1, int(np.ceil(np.log2(C_loc))))
+        d = orc.pad_draws(C_loc, seed, 1 << b)
+        assert d.max() == (1 << b) - 1 and len(np.unique(d)) == 1 << b
+    a, b_ = orc.pad_draws(390625, 6, 4096), orc.pad_draws(390625, 7 << 40, 4096)
+    assert len(np.intersect1d(a, b_)) < 200                       # another seed, another order
+
+
+def test_fill_up_takes_the_first_draws_not_yet_chosen(orc):
+    Cg, K, B, c0, C_loc = 4000, 8, 50, 1000, 1500
+    G = synth.graph_synthetic(8, Cg, K, locality=16)
+    labels = synth.labels_uniform(8, B, Cg)
+    counts, offsets, flat = orc.graph_compress(G, c0, C_loc)
+    for M, seed in [(256, 11), (1500, 12), (3000, 13)]:
+        a0, n0, nf0, t0 = orc.select_active_csr(labels, counts, offsets, flat, c0, C_loc, M)
+        a1, n1, nf1, t1 = orc.select_active_csr(labels, counts, offsets, flat, c0, C_loc, M, pad=True, seed=seed)
+        assert nf1 == nf0 == n0 and n1 == min(M, C_loc) and (np.diff(a1[:n1]) > 0).all()
+        found, final = set(a0[:n0].tolist()), set(a1[:n1].tolist())
+        assert found <= final
+        draws = [int(c) for c in orc.pad_draws(C_loc, seed, 4096) if c < C_loc and int(c) not in found]
+        assert final - found == set(draws[:n1 - n0])
+        own = (labels >= c0) & (labels < c0 + C_loc)
+        assert (t1[~own] == -1).all() and np.array_equal(a1[t1[own]] + c0, labels[own])
+    # nothing to fill when the cut bites
+    a2, n2, nf2, _ = orc.select_active_csr(labels, counts, offsets, flat, c0, C_loc, 60, pad=True, seed=1)
+    a3, n3, _, _ = orc.select_active_csr(labels, counts, offsets, flat, c0, C_loc, 60)
+    assert n2 == nf2 == 60 and np.array_equal(a2, a3)
+
+
+def test_fill_up_is_uniform_over_the_classes_not_chosen(orc):
+    # 40 classes, 8 found by the lists; 8 more drawn from the other 32 under 4,000 seeds: each with probability 1/4
+    Cg = C_loc = 40
+    G = ((np.arange(Cg)[:, None] + 1 + np.arange(3)[None, :]) % Cg).astype(np.int32)
+    labels = np.array([0, 20], dtype=np.int32)                    # finds 0..3 and 20..23
+    counts, offsets, flat = orc.graph_compress(G, 0, C_loc)
+    hits = np.zeros(C_loc)
+    n_seeds = 4000
+    for seed in range(n_seeds):
+        a, n, nf, _ = orc.select_active_csr(labels, counts, offsets, flat, 0, C_loc, 16, pad=True, seed=seed * 2654435761 + 17)
+        assert n == 16 and nf == 8
+        hits[a[:n]] += 1
+    found = [0, 1, 2, 3, 20, 21, 22, 23]
+    assert (hits[found] == n_seeds).all()
+    rest = np.delete(hits, found)
+    sigma = np.sqrt(n_seeds * 0.25 * 0.75)
+    assert np.abs(rest - n_seeds * 0.25).max() < 5 * sigma
+    chi2 = ((rest - n_seeds * 0.25) ** 2 / (n_seeds * 0.25 * 0.75)).sum()
+    assert chi2 < 32 + 6 * np.sqrt(2 * 32)
