@@ -44,11 +44,13 @@ typedef enum {
 #define KS_DEV_BAD_GRAPH_ID 2       /* a neighbour id outside [-1, C) */
 #define KS_DEV_BAD_INDEX 4          /* apply_weight_grad: an index outside [0, C) (that row is skipped) */
 #define KS_DEV_IDX_NOT_SORTED 8     /* apply_weight_grad: idx_sorted_unique was promised but does not hold */
-#define KS_DEV_BAD_COUNT 16         /* a device-side count (n, n_active) outside [0, n_max] */
+#define KS_DEV_BAD_COUNT 16         /* a device-side count (n, n_active) outside [0, n_max]; a compressed-graph list
+                                       longer than promised or outside its array; a flat array too short */
 #define KS_DEV_RANGE 32             /* KS_FLAG_UNIT_ROWS was promised but a sample's exponentials overflowed or all vanished */
 
 /* bits of the `flags` argument of the softmax entry points */
 #define KS_FLAG_UNIT_ROWS 1u        /* every row of W_bf16 and X_bf16 has L2 norm <= 1 (up to rounding) */
+#define KS_FLAG_PAD_RANDOM 2u       /* knn_select_active_csr: fill the active list up to M with randomly drawn classes */
 
 #define KS_DTYPE_BF16 0
 #define KS_DTYPE_FP32 1
@@ -183,6 +185,50 @@ size_t apply_weight_grad_workspace(int64_t C, int D, int n_max, int idx_sorted_u
 int apply_weight_grad(float *W_master, uint16_t *W_bf16, const int32_t *idx, const int32_t *n, int n_max,
                       const float *dW, float alpha, int64_t C, int D, int idx_sorted_unique,
                       void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
+
+/* ------------------------------------------------------------------------------------------------------
+ * One node of the sharded layer -- Section 3.2.3 (graph compression, quick access) and the fill-up branch of
+ * Algorithm 1.  The node owns the classes [c0, c0 + C_loc) of a problem with Cg classes; labels and the dense
+ * graph carry ids of the whole problem, everything the node produces carries local ids (global id - c0).
+ *
+ * knn_graph_compress -- (i) of Section 3.2.3: for every class g of the whole problem keep only the neighbours the
+ *   node owns, in the order of g's list, as local ids; the lists are laid end to end:
+ *     graph  [Cg, K]   dense graph, global ids, -1 = empty slot
+ *     counts [Cg]      out: length of g's compressed list
+ *     offsets[Cg + 1]  out: running sum of the counts (offsets[Cg] = total length)
+ *     flat   [flat_capacity] out: the lists; NULL = counts and offsets only (read offsets[Cg], allocate, call
+ *                      again).  A capacity below the total sets KS_DEV_BAD_COUNT; lists that do not fit are not
+ *                      written.
+ * knn_select_active_csr -- Algorithm 1 on the compressed graph ((ii) of Section 3.2.3: a sample finds its list at
+ *   offsets[label]):
+ *     labels [B]       global ids.  A sample whose class the node owns contributes that class at list position 0;
+ *                      entry j of its class's compressed list counts as position j + 1 (ranking for the cut to M
+ *                      as in knn_select_active: smallest position first, ties to the lowest local id)
+ *     K_max            upper bound of the list lengths (K of the dense graph); a longer list, or one that does
+ *                      not lie inside flat[0 .. flat_len), sets KS_DEV_BAD_COUNT and is not read
+ *     flags            KS_FLAG_PAD_RANDOM: when fewer than M classes are found the list is filled up to
+ *                      min(M, C_loc) with classes drawn without replacement from those not chosen.  The k-th
+ *                      draw (k = 0, 1, ...) is x_7 of: b = number of bits of the smallest power of two >= C_loc
+ *                      (at least 1), all arithmetic modulo 2^b, s1 = (b+1)/2, s2 = max(1, b/3),
+ *                        x_0 = k + lo32(pad_seed), x_1 = x_0 * 0x9E3779B1, x_2 = x_1 ^ (x_1 >> s1),
+ *                        x_3 = x_2 * 0x85EBCA6B,   x_4 = x_3 ^ (x_3 >> s2), x_5 = x_4 * 0xC2B2AE35,
+ *                        x_6 = x_5 ^ (x_5 >> s1),  x_7 = x_6 + hi32(pad_seed);
+ *                      draws >= C_loc or already in the list are passed over.  (The paper says only "random
+ *                      sample"; a caller changes pad_seed from step to step.)
+ *     active_idx [M]   out: ascending local ids, -1 beyond n_active;  n_found [1] (may be NULL): classes found by
+ *                      the lists, before the fill-up
+ *     target_pos [B]   out: position of the sample's class in active_idx, -1 if another node owns the class
+ *   Requires B <= M and K_max + 1 <= M.  Workspace: knn_select_active_csr_workspace.
+ * ---------------------------------------------------------------------------------------------------- */
+size_t knn_graph_compress_workspace(int64_t Cg, int K);
+int knn_graph_compress(const int32_t *graph, int64_t Cg, int K, int64_t c0, int64_t C_loc, int32_t *counts,
+                       int64_t *offsets, int32_t *flat, int64_t flat_capacity, void *ws, size_t ws_bytes,
+                       int32_t *dev_status, void *stream);
+size_t knn_select_active_csr_workspace(int64_t C_loc, int B, int K_max, int M);
+int knn_select_active_csr(const int32_t *labels, const int32_t *counts, const int64_t *offsets, const int32_t *flat,
+                          int64_t flat_len, int64_t Cg, int64_t c0, int64_t C_loc, int B, int K_max, int M,
+                          uint32_t flags, uint64_t pad_seed, int32_t *active_idx, int32_t *n_active, int32_t *n_found,
+                          int32_t *target_pos, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
 /* ------------------------------------------------------------------------------------------------------
  * Normalisation inside the layer -- Section 3.2.1: the graph and the softmax work on normalised W and X,

@@ -11,6 +11,7 @@ import torch
 KS_OK, KS_INVALID_ARG, KS_UNSUPPORTED, KS_WORKSPACE_TOO_SMALL, KS_HIP_ERROR = 0, 1, 2, 3, 4
 KS_DEV_BAD_LABEL, KS_DEV_BAD_GRAPH_ID, KS_DEV_BAD_INDEX, KS_DEV_IDX_NOT_SORTED, KS_DEV_BAD_COUNT = 1, 2, 4, 8, 16
 KS_DEV_RANGE = 32
+FLAG_PAD_RANDOM = 2
 _STATUS = {1: "KS_INVALID_ARG", 2: "KS_UNSUPPORTED", 3: "KS_WORKSPACE_TOO_SMALL", 4: "KS_HIP_ERROR"}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -20,7 +21,8 @@ EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_se
            "knn_select_active", "knn_gather_rows", "knn_softmax_workspace", "knn_softmax_fwd_bwd",
            "full_softmax_workspace", "full_softmax_fwd_bwd", "apply_weight_grad_workspace", "apply_weight_grad",
            "knn_normalize_rows", "knn_norm_backward_rows", "apply_weight_grad_normalized_workspace",
-           "apply_weight_grad_normalized")
+           "apply_weight_grad_normalized", "knn_graph_compress_workspace", "knn_graph_compress",
+           "knn_select_active_csr_workspace", "knn_select_active_csr")
 
 
 class KsError(RuntimeError):
@@ -324,3 +326,63 @@ def apply_weight_grad_normalized(W_master, W_hat_bf16, inv_norm, idx, n, dW_hat,
                                             _ptr(dev_status), _stream(stream))
     _check("apply_weight_grad_normalized", rc)
     return dev_status
+
+
+def knn_graph_compress(graph, c0, C_loc, dev_status=None, stream=None):
+    """Compressed graph of the node that owns classes [c0, c0 + C_loc) of the dense graph [Cg, K] (global ids).
+    Returns (counts int32 [Cg], offsets int64 [Cg + 1], flat int32 [total] of local ids, dev_status).  Two calls of
+    the library (lengths first, then the lists) with one read-back of the total in between."""
+    _need(graph, torch.int32, "graph")
+    Cg, K = graph.shape
+    dev = graph.device
+    counts = torch.empty(Cg, dtype=torch.int32, device=dev)
+    offsets = torch.empty(Cg + 1, dtype=torch.int64, device=dev)
+    ws = _ws(int(lib().knn_graph_compress_workspace(ct.c_int64(Cg), ct.c_int(K))), dev, None)
+    dev_status = _status(dev, dev_status)
+
+    def call(flat, cap):
+        rc = lib().knn_graph_compress(_ptr(graph), ct.c_int64(Cg), ct.c_int(K), ct.c_int64(c0), ct.c_int64(C_loc),
+                                      _ptr(counts), _ptr(offsets), _ptr(flat), ct.c_int64(cap), _ptr(ws),
+                                      ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
+        _check("knn_graph_compress", rc)
+
+    call(None, 0)
+    total = int(offsets[Cg].item())
+    flat = torch.empty(max(total, 1), dtype=torch.int32, device=dev)
+    call(flat, total)
+    return counts, offsets, flat[:total], dev_status
+
+
+def knn_select_active_csr_workspace(C_loc, B, K_max, M) -> int:
+    return int(lib().knn_select_active_csr_workspace(ct.c_int64(C_loc), ct.c_int(B), ct.c_int(K_max), ct.c_int(M)))
+
+
+def knn_select_active_csr(labels, counts, offsets, flat, c0, C_loc, K_max, M, pad_random=False, pad_seed=0, ws=None,
+                          dev_status=None, stream=None):
+    """Algorithm 1 on one node's compressed graph.  Returns dict(active_idx [M] local ids, n_active [1], n_found [1],
+    target_pos [B] with -1 for labels of other nodes' classes, dev_status)."""
+    _need(labels, torch.int32, "labels")
+    _need(counts, torch.int32, "counts")
+    _need(offsets, torch.int64, "offsets")
+    if flat.numel():
+        _need(flat, torch.int32, "flat")
+    dev = labels.device
+    B, Cg = labels.numel(), counts.numel()
+    if offsets.numel() != Cg + 1:
+        raise ValueError("offsets must be [Cg + 1]")
+    out = dict(active_idx=torch.empty(M, dtype=torch.int32, device=dev),
+               n_active=torch.empty(1, dtype=torch.int32, device=dev),
+               n_found=torch.empty(1, dtype=torch.int32, device=dev),
+               target_pos=torch.empty(B, dtype=torch.int32, device=dev))
+    ws = _ws(knn_select_active_csr_workspace(C_loc, B, K_max, M), dev, ws)
+    dev_status = _status(dev, dev_status)
+    out["dev_status"] = dev_status
+    rc = lib().knn_select_active_csr(_ptr(labels), _ptr(counts), _ptr(offsets), _ptr(flat if flat.numel() else None),
+                                     ct.c_int64(flat.numel()), ct.c_int64(Cg), ct.c_int64(c0), ct.c_int64(C_loc),
+                                     ct.c_int(B), ct.c_int(K_max), ct.c_int(M),
+                                     ct.c_uint32(FLAG_PAD_RANDOM if pad_random else 0), ct.c_uint64(pad_seed),
+                                     _ptr(out["active_idx"]), _ptr(out["n_active"]), _ptr(out["n_found"]),
+                                     _ptr(out["target_pos"]), _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status),
+                                     _stream(stream))
+    _check("knn_select_active_csr", rc)
+    return out

@@ -5,6 +5,11 @@
 // result does not depend on the order of the atomics.  The ascending active list is then a stream
 // compaction of the table; the cut to M classes is a threshold on the score (found from a histogram
 // over list positions) plus a quota of the lowest ids at the threshold score.
+//
+// Where the candidates come from is a template parameter: the dense [C, K] graph of a GPU that owns all classes, or
+// the compressed graph of one node of the sharded layer (Section 3.2.3: per class of the whole problem only the
+// neighbours this node owns, as local ids, lists of different lengths laid end to end and found through a
+// running sum of their lengths).  The random fill-up of Algorithm 1 is an optional last stage of both.
 #include "ks_select.h"
 
 #define SEL_NT 256
@@ -14,11 +19,96 @@
 #define SEL_LDS_BINS 2048
 #define SEL1_MAX_WORDS_HOST 12288 /* classes / 32 up to which the single-workgroup path is used */
 
+// candidate at list position r of sample i (r = 0: the sample's own class), as an id in [0, C), or -1
+struct SelDense {
+    const int32_t *labels, *graph;
+    int64_t C;
+    int K;
+    static constexpr bool kForeignLabels = false; // a label this GPU does not own is an error
+    __device__ __forceinline__ int32_t cand(int i, int r, int32_t *dev_status) const {
+        const int32_t y = labels[i];
+        if (y < 0 || y >= C) {
+            if (r == 0) ks_flag(dev_status, KS_DEV_BAD_LABEL);
+            return -1;
+        }
+        if (r == 0) return y;
+        int32_t c = graph[(int64_t)y * K + (r - 1)];
+        if (c < -1 || c >= C) {
+            ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
+            c = -1;
+        }
+        return c;
+    }
+};
+struct SelCsr {
+    const int32_t *labels, *counts;
+    const int64_t *offsets;
+    const int32_t *flat;
+    int64_t Cg, c0, C, flat_len; // classes of the whole problem; first class and number of classes of this node
+    int K;                       // upper bound of the list lengths
+    static constexpr bool kForeignLabels = true; // labels of other nodes' classes have no target here
+    __device__ __forceinline__ int32_t cand(int i, int r, int32_t *dev_status) const {
+        const int32_t y = labels[i];
+        if (y < 0 || y >= Cg) {
+            if (r == 0) ks_flag(dev_status, KS_DEV_BAD_LABEL);
+            return -1;
+        }
+        if (r == 0) {
+            const int64_t l = (int64_t)y - c0;
+            return (l >= 0 && l < C) ? (int32_t)l : -1;
+        }
+        const int32_t n = counts[y];
+        if (r - 1 >= n) return -1;
+        const int64_t off = offsets[y];
+        if (n > K || off < 0 || off + n > flat_len) { // a list longer than promised or outside the array: not read
+            if (r == 1) ks_flag(dev_status, KS_DEV_BAD_COUNT);
+            return -1;
+        }
+        int32_t c = flat[off + (r - 1)];
+        if (c < -1 || c >= C) {
+            ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
+            c = -1;
+        }
+        return c;
+    }
+};
+
+// k-th draw of the random fill-up: a keyed one-to-one map of [0, 2^b) onto itself (adding a constant, multiplying
+// by an odd constant and xor with a right shift of itself are each one-to-one on b-bit numbers), 2^b the smallest
+// power of two >= C.  Draws >= C or already in the set are passed over: a sample without replacement of the
+// classes not chosen (Algorithm 1 only says "random sample").
+struct SelPad {
+    int on, b;
+    uint32_t mask, s_lo, s_hi;
+};
+static SelPad sel_pad_make(int on, int64_t C, uint64_t seed) {
+    SelPad p;
+    p.on = on;
+    p.b = 1;
+    while (((int64_t)1 << p.b) < C) ++p.b;
+    p.mask = p.b >= 32 ? 0xFFFFFFFFu : ((1u << p.b) - 1u);
+    p.s_lo = (uint32_t)seed;
+    p.s_hi = (uint32_t)(seed >> 32);
+    return p;
+}
+__device__ __forceinline__ uint32_t sel_pad_draw(uint32_t k, const SelPad &p) {
+    const int s1 = (p.b + 1) >> 1, s2 = p.b / 3 > 0 ? p.b / 3 : 1;
+    uint32_t x = (k + p.s_lo) & p.mask;
+    x = (x * 0x9E3779B1u) & p.mask;
+    x ^= x >> s1;
+    x = (x * 0x85EBCA6Bu) & p.mask;
+    x ^= x >> s2;
+    x = (x * 0xC2B2AE35u) & p.mask;
+    x ^= x >> s1;
+    return (x + p.s_hi) & p.mask;
+}
+
 struct SelPlan {
     int r_star;    // classes with score < r_star are all kept
     int quota;     // number of classes with score == r_star that are kept (lowest ids)
     int n_active;
     int n_unique;
+    int n_found;   // classes found by the lists (capped at M), before the fill-up
 };
 
 struct SelWs {
@@ -62,27 +152,13 @@ __global__ void __launch_bounds__(SEL_NT) sel_init_kernel(int32_t *score, int64_
 }
 
 // one thread per (sample i, list position r): r = 0 is the label itself, r >= 1 is column r-1 of its list
-__global__ void __launch_bounds__(SEL_NT)
-sel_mark_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict__ graph, int64_t C, int B, int K,
-                int32_t *score, int32_t *dev_status) {
+template <class Src>
+__global__ void __launch_bounds__(SEL_NT) sel_mark_kernel(Src src, int B, int K, int32_t *score, int32_t *dev_status) {
     int64_t t = (int64_t)blockIdx.x * SEL_NT + threadIdx.x;
     if (t >= (int64_t)B * (K + 1)) return;
     int i = (int)(t / (K + 1)), r = (int)(t % (K + 1));
-    int32_t y = labels[i];
-    if (y < 0 || y >= C) {
-        if (r == 0) ks_flag(dev_status, KS_DEV_BAD_LABEL);
-        return;
-    }
-    int32_t c = y;
-    if (r > 0) {
-        c = graph[(int64_t)y * K + (r - 1)];
-        if (c == -1) return;
-        if (c < -1 || c >= C) {
-            ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
-            return;
-        }
-    }
-    atomicMin(&score[c], r);
+    const int32_t c = src.cand(i, r, dev_status);
+    if (c >= 0) atomicMin(&score[c], r);
 }
 
 __global__ void __launch_bounds__(SEL_NT)
@@ -133,7 +209,43 @@ __global__ void __launch_bounds__(1024) sel_plan_kernel(const int32_t *__restric
         plan->quota = s_quota;
         plan->n_unique = carry;
         plan->n_active = carry < M ? carry : M;
+        plan->n_found = plan->n_active;
     }
+}
+
+// single block, after the plan: random fill-up when fewer than M classes were found.  Drawn classes get the score
+// K (any score below the cut), so the compaction that follows emits them with the rest.
+__global__ void __launch_bounds__(1024) sel_pad_kernel(int32_t *score, int64_t C, int K, int M, SelPad pad, SelPlan *plan) {
+    __shared__ int sh[1024 / 64 + 1];
+    const int found = plan->n_unique;
+    const int64_t want = M < C ? M : C;
+    if (found >= want) return;
+    const int need = (int)(want - found);
+    const uint64_t n_draws = (uint64_t)1 << pad.b;
+    int got = 0;
+    for (uint64_t k0 = 0; got < need && k0 < n_draws; k0 += 1024 * 8) {
+        uint32_t cs[8];
+        int valid = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint64_t k = k0 + (uint64_t)threadIdx.x * 8 + e;
+            const uint32_t c = k < n_draws ? sel_pad_draw((uint32_t)k, pad) : 0xFFFFFFFFu;
+            cs[e] = (c < (uint64_t)C && score[c] == SEL_NONE) ? c : 0xFFFFFFFFu;
+            valid += cs[e] != 0xFFFFFFFFu;
+        }
+        int tot;
+        int ex = ks_block_escan<1024>(valid, sh, &tot);
+        const int room = need - got;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (cs[e] != 0xFFFFFFFFu) {
+                if (ex < room) score[cs[e]] = K;
+                ++ex;
+            }
+        got += tot < room ? tot : room;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) plan->n_active = found + got;
 }
 
 __global__ void __launch_bounds__(SEL_NT)
@@ -221,16 +333,21 @@ sel_emit_kernel(int32_t *score, int64_t C, const SelPlan *plan, const int32_t *_
     }
 }
 
+template <class Src>
 __global__ void __launch_bounds__(SEL_NT)
-sel_finish_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict__ score, int64_t C, int B, int M,
-                  const SelPlan *plan, int32_t *active_idx, int32_t *n_active, int32_t *target_pos) {
+sel_finish_kernel(Src src, const int32_t *__restrict__ score, int B, int M, const SelPlan *plan, int32_t *active_idx,
+                  int32_t *n_active, int32_t *n_found, int32_t *target_pos) {
     int t = blockIdx.x * SEL_NT + threadIdx.x;
     const int n = plan->n_active;
-    if (t == 0) *n_active = n;
+    if (t == 0) {
+        *n_active = n;
+        if (n_found) *n_found = plan->n_found;
+    }
     if (t < B) {
-        int32_t y = labels[t];
-        int32_t p = (y >= 0 && y < C) ? score[y] : 0;
-        target_pos[t] = (p >= 0 && p < n) ? p : 0; // in range even for broken inputs (those are flagged)
+        const int32_t y = src.cand(t, 0, nullptr);
+        const int32_t none = Src::kForeignLabels ? -1 : 0; // in range even for broken inputs (those are flagged)
+        int32_t p = y >= 0 ? score[y] : none;
+        target_pos[t] = (p >= 0 && p < n) ? p : none;
     }
     if (t >= n && t < M) active_idx[t] = -1;
 }
@@ -252,26 +369,13 @@ sel_finish_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict_
 // Stage 1 (many workgroups, so that the scattered reads of the neighbour lists are spread over the chip):
 // validated candidates, list-position-major: cand[r * B + i] = class at position r of sample i's list
 // (r = 0: the label itself), or -1 for an empty or invalid entry.
+template <class Src>
 __global__ void __launch_bounds__(SEL_NT)
-sel_fetch_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict__ graph, int64_t C, int B, int K,
-                 int32_t *__restrict__ cand, int32_t *dev_status) {
+sel_fetch_kernel(Src src, int B, int K, int32_t *__restrict__ cand, int32_t *dev_status) {
     const int64_t t = (int64_t)blockIdx.x * SEL_NT + threadIdx.x;
     if (t >= (int64_t)B * (K + 1)) return;
     const int i = (int)(t / (K + 1)), r = (int)(t % (K + 1));
-    const int32_t y = labels[i];
-    int32_t c = -1;
-    if (y < 0 || y >= C) {
-        if (r == 0) ks_flag(dev_status, KS_DEV_BAD_LABEL);
-    } else if (r == 0) {
-        c = y;
-    } else {
-        c = graph[(int64_t)y * K + (r - 1)];
-        if (c < -1 || c >= C) {
-            ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
-            c = -1;
-        }
-    }
-    cand[(int64_t)r * B + i] = c;
+    cand[(int64_t)r * B + i] = src.cand(i, r, dev_status);
 }
 
 // exclusive prefix over the words of a bitmap: pre[w] = number of set bits in words < w; returns the total
@@ -291,8 +395,9 @@ __device__ __forceinline__ int sel1_prefix(const uint32_t *bm, int nw, int *pre,
 }
 
 __global__ void __launch_bounds__(SEL1_NT)
-sel_single_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict__ cand, int64_t C, int B, int K, int M,
-                  int32_t *__restrict__ active_idx, int32_t *__restrict__ n_active, int32_t *__restrict__ target_pos) {
+sel_single_kernel(const int32_t *__restrict__ cand, int64_t C, int B, int K, int M, int foreign_labels, SelPad pad,
+                  int32_t *__restrict__ active_idx, int32_t *__restrict__ n_active, int32_t *__restrict__ n_found,
+                  int32_t *__restrict__ target_pos) {
     __shared__ uint32_t bm[SEL1_MAX_WORDS];
     __shared__ uint32_t eq[SEL1_MAX_WORDS];
     __shared__ int pre[SEL1_MAX_WORDS];
@@ -370,6 +475,38 @@ sel_single_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict_
         __syncthreads();
         total = sel1_prefix(bm, nw, pre, sh);
     }
+    const int found = total < M ? total : M;
+    const int64_t want = M < C ? M : C;
+    if (pad.on && total < want) {
+        // random fill-up: the first draws that are classes of this GPU and not in the bitmap yet (the draws are
+        // distinct, so marking one cannot change the test of another)
+        const int need = (int)(want - total);
+        const uint32_t n_draws = 1u << pad.b; // b <= 19 here
+        int got = 0;
+        for (uint32_t k0 = 0; got < need && k0 < n_draws; k0 += SEL1_NT * 8) {
+            uint32_t cs[8];
+            int valid = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t k = k0 + (uint32_t)tid * 8 + e;
+                const uint32_t c = k < n_draws ? sel_pad_draw(k, pad) : 0xFFFFFFFFu;
+                cs[e] = (c < (uint64_t)C && !(bm[c >> 5] & (1u << (c & 31)))) ? c : 0xFFFFFFFFu;
+                valid += cs[e] != 0xFFFFFFFFu;
+            }
+            int tot;
+            int ex = ks_block_escan<SEL1_NT>(valid, sh, &tot);
+            const int room = need - got;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (cs[e] != 0xFFFFFFFFu) {
+                    if (ex < room) atomicOr(&bm[cs[e] >> 5], 1u << (cs[e] & 31));
+                    ++ex;
+                }
+            got += tot < room ? tot : room;
+            __syncthreads();
+        }
+        total = sel1_prefix(bm, nw, pre, sh);
+    }
     // Every workgroup of the grid has built the same bitmap and prefix (redundantly: it is LDS work, and it
     // spares a grid-wide synchronisation); each writes its share of the outputs.
     const int G = gridDim.x, g = blockIdx.x;
@@ -389,45 +526,56 @@ sel_single_kernel(const int32_t *__restrict__ labels, const int32_t *__restrict_
     }
     const int n = total < M ? total : M;
     for (int a = n + g * SEL1_NT + tid; a < M; a += G * SEL1_NT) active_idx[a] = -1;
+    const int none = foreign_labels ? -1 : 0; // in range even for broken inputs (those are flagged)
     for (int i = g * SEL1_NT + tid; i < B; i += G * SEL1_NT) {
-        const int32_t y = labels[i];
-        int p = 0;
+        const int32_t y = cand[i]; // list position 0: the sample's own class, -1 if it is not one of this GPU's
+        int p = none;
         if (y >= 0 && y < C) p = pre[y >> 5] + __popc(bm[y >> 5] & ((1u << (y & 31)) - 1u));
-        target_pos[i] = (p >= 0 && p < n) ? p : 0;
+        target_pos[i] = (p >= 0 && p < n) ? p : none;
     }
-    if (g == 0 && tid == 0) *n_active = n;
+    if (g == 0 && tid == 0) {
+        *n_active = n;
+        if (n_found) *n_found = found;
+    }
 }
 
-int ks_select_launch(const int32_t *labels, const int32_t *graph, int64_t C, int B, int K, int M,
-                     int32_t *active_idx, int32_t *n_active, int32_t *target_pos, void *ws,
-                     int32_t *dev_status, hipStream_t st) {
+template <class Src>
+static int sel_launch(const Src &src, int64_t C, int B, int K, int M, SelPad pad, int32_t *active_idx, int32_t *n_active,
+                      int32_t *n_found, int32_t *target_pos, void *ws, int32_t *dev_status, hipStream_t st) {
+    const int64_t n_cand = (int64_t)B * (K + 1);
     if (C <= (int64_t)SEL1_MAX_WORDS * 32) {
         int32_t *cand = (int32_t *)ws;
-        const int64_t n_cand = (int64_t)B * (K + 1);
-        hipLaunchKernelGGL(sel_fetch_kernel, dim3((unsigned)ks_ceil_div(n_cand, SEL_NT)), dim3(SEL_NT), 0, st, labels, graph, C, B,
-                           K, cand, dev_status);
-        hipLaunchKernelGGL(sel_single_kernel, dim3(SEL1_GRID), dim3(SEL1_NT), 0, st, labels, cand, C, B, K, M, active_idx,
-                           n_active, target_pos);
+        hipLaunchKernelGGL(sel_fetch_kernel<Src>, dim3((unsigned)ks_ceil_div(n_cand, SEL_NT)), dim3(SEL_NT), 0, st, src, B, K,
+                           cand, dev_status);
+        hipLaunchKernelGGL(sel_single_kernel, dim3(SEL1_GRID), dim3(SEL1_NT), 0, st, cand, C, B, K, M,
+                           (int)Src::kForeignLabels, pad, active_idx, n_active, n_found, target_pos);
         KS_LAUNCH_CHECK();
         return KS_OK;
     }
     SelWs w = sel_carve(ws, C, K);
     int fill_blocks = (int)(ks_ceil_div(C, SEL_NT) < 2048 ? ks_ceil_div(C, SEL_NT) : 2048);
     hipLaunchKernelGGL(sel_init_kernel, dim3(fill_blocks), dim3(SEL_NT), 0, st, w.score, C, w.hist, K);
-    int64_t n_cand = (int64_t)B * (K + 1);
-    hipLaunchKernelGGL(sel_mark_kernel, dim3((unsigned)ks_ceil_div(n_cand, SEL_NT)), dim3(SEL_NT), 0, st, labels, graph,
-                       C, B, K, w.score, dev_status);
+    hipLaunchKernelGGL(sel_mark_kernel<Src>, dim3((unsigned)ks_ceil_div(n_cand, SEL_NT)), dim3(SEL_NT), 0, st, src, B, K,
+                       w.score, dev_status);
     hipLaunchKernelGGL(sel_hist_kernel, dim3(w.nblk), dim3(SEL_NT), 0, st, w.score, C, K, w.hist);
     hipLaunchKernelGGL(sel_plan_kernel, dim3(1), dim3(1024), 0, st, w.hist, K, M, w.plan);
+    if (pad.on) hipLaunchKernelGGL(sel_pad_kernel, dim3(1), dim3(1024), 0, st, w.score, C, K, M, pad, w.plan);
     hipLaunchKernelGGL(sel_count_kernel, dim3(w.nblk), dim3(SEL_NT), 0, st, w.score, C, w.plan, w.blk_cnt);
     hipLaunchKernelGGL(sel_scan_kernel, dim3(1), dim3(1024), 0, st, w.blk_cnt, w.nblk, w.plan, w.blk_base);
     hipLaunchKernelGGL(sel_emit_kernel, dim3(w.nblk), dim3(SEL_NT), 0, st, w.score, C, w.plan, w.blk_base, M,
                        active_idx);
     int fin = B > M ? B : M;
-    hipLaunchKernelGGL(sel_finish_kernel, dim3((unsigned)ks_ceil_div(fin, SEL_NT)), dim3(SEL_NT), 0, st, labels, w.score,
-                       C, B, M, w.plan, active_idx, n_active, target_pos);
+    hipLaunchKernelGGL(sel_finish_kernel<Src>, dim3((unsigned)ks_ceil_div(fin, SEL_NT)), dim3(SEL_NT), 0, st, src, w.score,
+                       B, M, w.plan, active_idx, n_active, n_found, target_pos);
     KS_LAUNCH_CHECK();
     return KS_OK;
+}
+
+int ks_select_launch(const int32_t *labels, const int32_t *graph, int64_t C, int B, int K, int M,
+                     int32_t *active_idx, int32_t *n_active, int32_t *target_pos, void *ws,
+                     int32_t *dev_status, hipStream_t st) {
+    SelDense src{labels, graph, C, K};
+    return sel_launch(src, C, B, K, M, sel_pad_make(0, C, 0), active_idx, n_active, nullptr, target_pos, ws, dev_status, st);
 }
 
 extern "C" size_t knn_select_workspace(int64_t C, int B, int K, int M) {
@@ -446,4 +594,147 @@ extern "C" int knn_select_active(const int32_t *labels, const int32_t *graph, in
     if (ws_bytes < ks_select_ws_bytes(C, B, K)) return KS_WORKSPACE_TOO_SMALL;
     return ks_select_launch(labels, graph, C, B, K, M, active_idx, n_active, target_pos, ws, dev_status,
                             (hipStream_t)stream);
+}
+
+extern "C" size_t knn_select_active_csr_workspace(int64_t C_loc, int B, int K_max, int M) {
+    (void)M;
+    if (C_loc < 1 || K_max < 0 || B < 1) return 0;
+    return ks_select_ws_bytes(C_loc, B, K_max);
+}
+
+extern "C" int knn_select_active_csr(const int32_t *labels, const int32_t *counts, const int64_t *offsets,
+                                     const int32_t *flat, int64_t flat_len, int64_t Cg, int64_t c0, int64_t C_loc, int B,
+                                     int K_max, int M, uint32_t flags, uint64_t pad_seed, int32_t *active_idx,
+                                     int32_t *n_active, int32_t *n_found, int32_t *target_pos, void *ws, size_t ws_bytes,
+                                     int32_t *dev_status, void *stream) {
+    if (!labels || !counts || !offsets || !active_idx || !n_active || !target_pos || !ws) return KS_INVALID_ARG;
+    if (Cg < 1 || Cg >= (int64_t)1 << 31 || c0 < 0 || C_loc < 1 || c0 + C_loc > Cg) return KS_INVALID_ARG;
+    if (B < 1 || K_max < 0 || M < 1 || flat_len < 0) return KS_INVALID_ARG;
+    if (flat_len > 0 && !flat) return KS_INVALID_ARG;
+    if (B > M || (int64_t)K_max + 1 > M) return KS_INVALID_ARG;
+    if (flags & ~(uint32_t)KS_FLAG_PAD_RANDOM) return KS_INVALID_ARG;
+    if (ws_bytes < ks_select_ws_bytes(C_loc, B, K_max)) return KS_WORKSPACE_TOO_SMALL;
+    SelCsr src{labels, counts, offsets, flat, Cg, c0, C_loc, flat_len, K_max};
+    return sel_launch(src, C_loc, B, K_max, M, sel_pad_make((flags & KS_FLAG_PAD_RANDOM) != 0, C_loc, pad_seed), active_idx,
+                      n_active, n_found, target_pos, ws, dev_status, (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Graph compression (Section 3.2.3 (i)): per class of the whole problem the neighbours this node owns.
+// Three launches: list lengths and their sums per block of classes; running sum over the blocks; offsets and the
+// lists themselves.
+// ------------------------------------------------------------------------------------------------
+#define GC_NT 256
+#define GC_SEG (GC_NT * 4) /* classes per block */
+
+__device__ __forceinline__ int gc_row_count(const int32_t *__restrict__ row, int K, int64_t Cg, int64_t c0, int64_t c1,
+                                            int32_t *dev_status) {
+    int n = 0;
+    for (int k = 0; k < K; ++k) {
+        const int32_t c = row[k];
+        if (c < -1 || c >= Cg) ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
+        n += (c >= c0 && c < c1);
+    }
+    return n;
+}
+
+__global__ void __launch_bounds__(GC_NT)
+gc_count_kernel(const int32_t *__restrict__ graph, int64_t Cg, int K, int64_t c0, int64_t C_loc, int32_t *__restrict__ counts,
+                int64_t *__restrict__ blk_sum, int32_t *dev_status) {
+    __shared__ int s_w[GC_NT / 64];
+    int local = 0;
+    for (int e = 0; e < 4; ++e) {
+        const int64_t g = (int64_t)blockIdx.x * GC_SEG + (int64_t)e * GC_NT + threadIdx.x;
+        if (g < Cg) {
+            const int n = gc_row_count(graph + g * K, K, Cg, c0, c0 + C_loc, dev_status);
+            counts[g] = n;
+            local += n;
+        }
+    }
+    local = ks_wave_sum_i(local);
+    if ((threadIdx.x & 63) == 0) s_w[threadIdx.x >> 6] = local;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t t = 0;
+        for (int w = 0; w < GC_NT / 64; ++w) t += s_w[w];
+        blk_sum[blockIdx.x] = t;
+    }
+}
+
+// single block: blk_sum -> exclusive running sum in place; the total goes to offsets[Cg]
+__global__ void __launch_bounds__(1024) gc_scan_kernel(int64_t *blk_sum, int nblk, int64_t *offsets, int64_t Cg,
+                                                       int64_t flat_capacity, int check_capacity, int32_t *dev_status) {
+    __shared__ int64_t s_w[1024 / 64];
+    __shared__ int64_t s_carry;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (int b0 = 0; b0 < nblk; b0 += 1024) {
+        const int b = b0 + threadIdx.x;
+        const int64_t v = b < nblk ? blk_sum[b] : 0;
+        int64_t inc = v; // inclusive scan inside the wavefront
+        for (int o = 1; o < 64; o <<= 1) {
+            const int lo = __shfl_up((int)(uint32_t)inc, o, 64), hi = __shfl_up((int)(inc >> 32), o, 64);
+            if ((threadIdx.x & 63) >= o) inc += ((int64_t)hi << 32) | (uint32_t)lo;
+        }
+        if ((threadIdx.x & 63) == 63) s_w[threadIdx.x >> 6] = inc;
+        __syncthreads();
+        int64_t base = s_carry;
+        for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) base += s_w[w];
+        if (b < nblk) blk_sum[b] = base + inc - v;
+        __syncthreads();
+        if (threadIdx.x == 1023) s_carry = base + inc;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        offsets[Cg] = s_carry;
+        if (check_capacity && s_carry > flat_capacity) ks_flag(dev_status, KS_DEV_BAD_COUNT);
+    }
+}
+
+__global__ void __launch_bounds__(GC_NT)
+gc_fill_kernel(const int32_t *__restrict__ graph, int64_t Cg, int K, int64_t c0, int64_t C_loc,
+               const int32_t *__restrict__ counts, const int64_t *__restrict__ blk_base, int64_t *__restrict__ offsets,
+               int32_t *__restrict__ flat, int64_t flat_capacity) {
+    __shared__ int sh[GC_NT / 64 + 1];
+    int64_t base = blk_base[blockIdx.x];
+    for (int e = 0; e < 4; ++e) {
+        const int64_t g = (int64_t)blockIdx.x * GC_SEG + (int64_t)e * GC_NT + threadIdx.x;
+        const int n = g < Cg ? counts[g] : 0;
+        int tot;
+        const int64_t off = base + ks_block_escan<GC_NT>(n, sh, &tot);
+        base += tot;
+        if (g >= Cg) continue;
+        offsets[g] = off;
+        if (!flat || off + n > flat_capacity) continue; // the array is too short: flagged by the scan, nothing written
+        const int32_t *row = graph + g * K;
+        int64_t o = off;
+        for (int k = 0; k < K; ++k) {
+            const int32_t c = row[k];
+            if (c >= c0 && c < c0 + C_loc && o < off + n) flat[o++] = (int32_t)(c - c0);
+        }
+    }
+}
+
+extern "C" size_t knn_graph_compress_workspace(int64_t Cg, int K) {
+    if (Cg < 1 || K < 0) return 0;
+    return ks_align_up((size_t)ks_ceil_div(Cg, GC_SEG) * sizeof(int64_t), 256);
+}
+
+extern "C" int knn_graph_compress(const int32_t *graph, int64_t Cg, int K, int64_t c0, int64_t C_loc, int32_t *counts,
+                                  int64_t *offsets, int32_t *flat, int64_t flat_capacity, void *ws, size_t ws_bytes,
+                                  int32_t *dev_status, void *stream) {
+    if (!graph || !counts || !offsets || !ws) return KS_INVALID_ARG;
+    if (Cg < 1 || Cg >= (int64_t)1 << 31 || K < 1 || c0 < 0 || C_loc < 1 || c0 + C_loc > Cg) return KS_INVALID_ARG;
+    if (flat && flat_capacity < 0) return KS_INVALID_ARG;
+    if (ws_bytes < knn_graph_compress_workspace(Cg, K)) return KS_WORKSPACE_TOO_SMALL;
+    const int nblk = (int)ks_ceil_div(Cg, GC_SEG);
+    int64_t *blk = (int64_t *)ws;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(gc_count_kernel, dim3(nblk), dim3(GC_NT), 0, st, graph, Cg, K, c0, C_loc, counts, blk, dev_status);
+    hipLaunchKernelGGL(gc_scan_kernel, dim3(1), dim3(1024), 0, st, blk, nblk, offsets, Cg, flat_capacity, flat != nullptr,
+                       dev_status);
+    hipLaunchKernelGGL(gc_fill_kernel, dim3(nblk), dim3(GC_NT), 0, st, graph, Cg, K, c0, C_loc, counts, blk, offsets, flat,
+                       flat_capacity);
+    KS_LAUNCH_CHECK();
+    return KS_OK;
 }

@@ -23,7 +23,7 @@ def ks():
 def _declared_functions():
     src = open(HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized))\s*\(", src)))
+    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress))\s*\(", src)))
 
 
 def test_header_symbols_are_exported(ks):
@@ -103,6 +103,20 @@ def test_argument_errors_are_reported_before_any_launch(ks):
     assert apply_n(sorted_=0, ws=null) == ks.KS_INVALID_ARG
     assert apply_n(sorted_=0, ws_bytes=8) == ks.KS_WORKSPACE_TOO_SMALL
     assert ks.apply_weight_grad_normalized_workspace(1000, 128, 100, 0) >= 128 * 8 + 128 * 128 * 4
+
+    def csr(Cg=1000, c0=100, C_loc=200, B=8, K=4, M=64, flags=0, ws_bytes=1 << 30, flat=one, flat_len=10):
+        return L.knn_select_active_csr(one, one, one, flat, i64(flat_len), i64(Cg), i64(c0), i64(C_loc), i(B), i(K), i(M),
+                                       ct.c_uint32(flags), ct.c_uint64(1), one, one, null, one, one, sz(ws_bytes), null, null)
+
+    assert csr(c0=900) == ks.KS_INVALID_ARG           # the node's range sticks out of the problem
+    assert csr(B=65) == ks.KS_INVALID_ARG
+    assert csr(flags=8) == ks.KS_INVALID_ARG
+    assert csr(flat=null) == ks.KS_INVALID_ARG
+    assert csr(ws_bytes=16) == ks.KS_WORKSPACE_TOO_SMALL
+    assert L.knn_graph_compress(one, i64(1000), i(8), i64(990), i64(20), one, one, null, i64(0), one, sz(1 << 20), null,
+                                null) == ks.KS_INVALID_ARG
+    assert L.knn_graph_compress(one, i64(1000), i(8), i64(0), i64(20), one, one, null, i64(0), one, sz(0), null,
+                                null) == ks.KS_WORKSPACE_TOO_SMALL
     assert L.knn_normalize_rows(one, i(0), i64(4), i(128), null, null, null) == ks.KS_INVALID_ARG   # no output
     assert L.knn_normalize_rows(one, i(3), i64(4), i(128), one, one, null) == ks.KS_INVALID_ARG     # dtype
     assert L.knn_normalize_rows(one, i(0), i64(4), i(6), one, one, null) == ks.KS_INVALID_ARG       # D % 4
