@@ -298,6 +298,52 @@ def main():
                                                   frac=round(bytes_apply_n / (us_apply_n * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)))
     log(f"[bench] layer with normalisation inside: {ms_norm_step:.4f} ms/step, apply_normalized {us_apply_n:.1f} us")
 
+    # ---- this GPU as one node of four (Section 3.2.3): graph compression and selection on the compressed graph,
+    # with and without the random fill-up to M (Algorithm 1); integer work, bit-exact against the oracle in the tests
+    sharded_node = None
+    if args.workload == "shard390k":
+        Cg4, c0 = 4 * C, C
+        cc = np.arange(Cg4, dtype=np.int64)[:, None]
+        kk = np.arange(K, dtype=np.int64)[None, :]
+        G4 = torch.from_numpy(((cc + 1 + (cc * 2654435761 + kk * 40503) % (Cg4 - 1)) % Cg4).astype(np.int32)).cuda()
+        y4 = torch.from_numpy(synth.labels_zipf(cfg["seed"], B, Cg4, 1.1)).cuda()
+        counts, offsets, flat, st4 = ks.knn_graph_compress(G4, c0, C)
+        c_ws = torch.empty(int(L.knn_graph_compress_workspace(ct.c_int64(Cg4), ct.c_int(K))), dtype=torch.uint8, device="cuda")
+        s_ws = torch.empty(ks.knn_select_active_csr_workspace(C, B, K, M), dtype=torch.uint8, device="cuda")
+
+        def timed(fn, reps):
+            fn()
+            hev.record(nev[0], stream)
+            for _ in range(reps):
+                fn()
+            hev.record(nev[1], stream)
+            torch.cuda.synchronize()
+            return hev.elapsed_ms(nev[0], nev[1]) * 1e3 / reps
+
+        def compress():
+            rc = L.knn_graph_compress(ct.c_void_p(G4.data_ptr()), ct.c_int64(Cg4), ct.c_int(K), ct.c_int64(c0), ct.c_int64(C),
+                                      ct.c_void_p(counts.data_ptr()), ct.c_void_p(offsets.data_ptr()),
+                                      ct.c_void_p(flat.data_ptr()), ct.c_int64(flat.numel()), ct.c_void_p(c_ws.data_ptr()),
+                                      ct.c_size_t(c_ws.numel()), ct.c_void_p(st4.data_ptr()), ct.c_void_p(stream))
+            assert rc == 0, rc
+
+        us_compress = timed(compress, 10)
+        us_sel = timed(lambda: ks.knn_select_active_csr(y4, counts, offsets, flat, c0, C, K, M, ws=s_ws, dev_status=st4), 20)
+        us_sel_pad = timed(lambda: ks.knn_select_active_csr(y4, counts, offsets, flat, c0, C, K, M, pad_random=True, pad_seed=1,
+                                                            ws=s_ws, dev_status=st4), 20)
+        o4 = ks.knn_select_active_csr(y4, counts, offsets, flat, c0, C, K, M, ws=s_ws, dev_status=st4)
+        torch.cuda.synchronize()
+        assert int(st4.item()) == 0
+        bytes_c = Cg4 * K * 4.0 * 2 + flat.numel() * 4.0 + Cg4 * (4.0 * 2 + 8.0)
+        sharded_node = dict(problem=f"Cg={Cg4} classes on 4 nodes, this node owns [{c0}, {c0 + C}); K={K}, global batch {B}",
+                            compressed_entries=int(flat.numel()), classes_found=int(o4["n_found"].item()),
+                            graph_compress=dict(us=round(us_compress, 1), bound="hbm",
+                                                gbs=round(bytes_c / (us_compress * 1e-6) / 1e9, 1),
+                                                frac=round(bytes_c / (us_compress * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)),
+                            select_csr_us=round(us_sel, 2), select_csr_with_fill_up_us=round(us_sel_pad, 2))
+        log(f"[bench] one node of four: compress {us_compress:.0f} us, select {us_sel:.1f} us, with fill-up {us_sel_pad:.1f} us")
+        del G4
+
     # ---- CPU oracle on the same inputs: baseline + full-size parity of the first step -----------------------
     cpu_baseline, parity = None, None
     if not args.no_cpu_baseline:
@@ -345,6 +391,7 @@ def main():
         "graph_build": {"ms": round(graph_best, 2), "tflops": round(graph_tflops, 1),
                         "frac": round(graph_tflops / PEAK_BF16_TFLOPS, 4), "bound": "mfma"},
         "normalized_layer": normalized_layer,
+        "sharded_node": sharded_node,
         "parity": parity,
     }
     print(json.dumps(res), flush=True)

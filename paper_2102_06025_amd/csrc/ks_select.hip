@@ -627,26 +627,49 @@ extern "C" int knn_select_active_csr(const int32_t *labels, const int32_t *count
 #define GC_NT 256
 #define GC_SEG (GC_NT * 4) /* classes per block */
 
-__device__ __forceinline__ int gc_row_count(const int32_t *__restrict__ row, int K, int64_t Cg, int64_t c0, int64_t c1,
-                                            int32_t *dev_status) {
-    int n = 0;
-    for (int k = 0; k < K; ++k) {
-        const int32_t c = row[k];
-        if (c < -1 || c >= Cg) ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
-        n += (c >= c0 && c < c1);
+#define GC_COLS 32               /* list entries staged per pass */
+#define GC_LD (GC_COLS + 1)      /* LDS row stride (odd: lanes reading their own rows hit different banks) */
+
+// Calls f(c) on lane l for every entry c of row g0 + l, in list order (rows past Cg and columns past K read as -1).
+// The 64 rows of a wavefront are contiguous in memory: they are loaded 128 bytes per row at a time, coalesced,
+// staged in the wavefront's part of LDS and read back row-wise.  Uniform trip counts: every thread of the block
+// must call it.
+template <class F>
+__device__ __forceinline__ void gc_for_rows(const int32_t *__restrict__ graph, int64_t Cg, int K, int64_t g0, int32_t *lds,
+                                            F f) {
+    const int lane = threadIdx.x & 63;
+    int32_t *mine = lds + (threadIdx.x >> 6) * 64 * GC_LD;
+    for (int kc = 0; kc < K; kc += GC_COLS) {
+        const int kn = K - kc < GC_COLS ? K - kc : GC_COLS;
+        for (int t = lane; t < 64 * GC_COLS; t += 64) {
+            const int r = t / GC_COLS, j = t % GC_COLS;
+            int32_t v = -1;
+            if (j < kn && g0 + r < Cg) v = graph[(g0 + r) * K + kc + j];
+            mine[r * GC_LD + j] = v;
+        }
+        __syncthreads();
+        for (int j = 0; j < kn; ++j) f(mine[lane * GC_LD + j]);
+        __syncthreads();
     }
-    return n;
 }
 
 __global__ void __launch_bounds__(GC_NT)
 gc_count_kernel(const int32_t *__restrict__ graph, int64_t Cg, int K, int64_t c0, int64_t C_loc, int32_t *__restrict__ counts,
                 int64_t *__restrict__ blk_sum, int32_t *dev_status) {
     __shared__ int s_w[GC_NT / 64];
+    __shared__ int32_t s_rows[(GC_NT / 64) * 64 * GC_LD];
     int local = 0;
+    const int64_t c1 = c0 + C_loc;
     for (int e = 0; e < 4; ++e) {
         const int64_t g = (int64_t)blockIdx.x * GC_SEG + (int64_t)e * GC_NT + threadIdx.x;
+        int n = 0;
+        bool bad = false;
+        gc_for_rows(graph, Cg, K, g - (threadIdx.x & 63), s_rows, [&](int32_t c) {
+            bad |= (c < -1 || c >= Cg);
+            n += (c >= c0 && c < c1);
+        });
+        if (bad) ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
         if (g < Cg) {
-            const int n = gc_row_count(graph + g * K, K, Cg, c0, c0 + C_loc, dev_status);
             counts[g] = n;
             local += n;
         }
@@ -696,22 +719,23 @@ gc_fill_kernel(const int32_t *__restrict__ graph, int64_t Cg, int K, int64_t c0,
                const int32_t *__restrict__ counts, const int64_t *__restrict__ blk_base, int64_t *__restrict__ offsets,
                int32_t *__restrict__ flat, int64_t flat_capacity) {
     __shared__ int sh[GC_NT / 64 + 1];
+    __shared__ int32_t s_rows[(GC_NT / 64) * 64 * GC_LD];
     int64_t base = blk_base[blockIdx.x];
+    const int64_t c1 = c0 + C_loc;
     for (int e = 0; e < 4; ++e) {
         const int64_t g = (int64_t)blockIdx.x * GC_SEG + (int64_t)e * GC_NT + threadIdx.x;
         const int n = g < Cg ? counts[g] : 0;
         int tot;
         const int64_t off = base + ks_block_escan<GC_NT>(n, sh, &tot);
         base += tot;
-        if (g >= Cg) continue;
-        offsets[g] = off;
-        if (!flat || off + n > flat_capacity) continue; // the array is too short: flagged by the scan, nothing written
-        const int32_t *row = graph + g * K;
+        if (g < Cg) offsets[g] = off;
+        if (!flat) continue; // uniform over the block
+        // a list that does not fit the array is not written (the scan has flagged the short array)
+        const int64_t end = (g < Cg && off + n <= flat_capacity) ? off + n : off;
         int64_t o = off;
-        for (int k = 0; k < K; ++k) {
-            const int32_t c = row[k];
-            if (c >= c0 && c < c0 + C_loc && o < off + n) flat[o++] = (int32_t)(c - c0);
-        }
+        gc_for_rows(graph, Cg, K, g - (threadIdx.x & 63), s_rows, [&](int32_t c) {
+            if (c >= c0 && c < c1 && o < end) flat[o++] = (int32_t)(c - c0);
+        });
     }
 }
 
