@@ -27,7 +27,7 @@ def lib():
         for name in ("orc_graph_bruteforce", "orc_select_active", "orc_knn_softmax_fwd_bwd",
                      "orc_full_softmax_fwd_bwd", "orc_apply_weight_grad", "orc_normalize_rows", "orc_norm_backward",
                      "orc_apply_weight_grad_normalized", "orc_graph_compress", "orc_pad_draws",
-                     "orc_select_active_csr"):
+                     "orc_select_active_csr", "orc_graph_update"):
             getattr(_lib, name).restype = ct.c_int
     return _lib
 
@@ -231,3 +231,19 @@ def select_active_csr(labels, counts, offsets, flat, c0: int, C_loc: int, M: int
     if rc != ORC_OK:
         raise ValueError(f"orc_select_active_csr failed with code {rc}")
     return active, int(n_active.value), int(n_found.value), target_pos
+
+
+def graph_update(W_local, W_visit, local_offset: int, visit_offset: int, graph, sims):
+    """One hop of the distributed graph build: merges the visiting rows into the lists (graph int32 [C_loc, K] of
+    ids of the whole problem, -1 = empty; sims fp64 [C_loc, K]).  Returns new arrays; the inputs are not modified."""
+    W_local, W_visit = _f32(W_local), _f32(W_visit)
+    graph = _i32(graph).copy()
+    sims = np.ascontiguousarray(sims, dtype=np.float64).copy()
+    (C_loc, D), C_vis, K = W_local.shape, W_visit.shape[0], graph.shape[1]
+    assert graph.shape == (C_loc, K) and sims.shape == (C_loc, K) and W_visit.shape[1] == D
+    rc = lib().orc_graph_update(_p(W_local, ct.c_float), ct.c_int64(C_loc), _p(W_visit, ct.c_float), ct.c_int64(C_vis),
+                                ct.c_int(D), ct.c_int(K), ct.c_int64(local_offset), ct.c_int64(visit_offset),
+                                _p(graph, ct.c_int32), _p(sims, ct.c_double))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_graph_update failed with code {rc}")
+    return graph, sims

@@ -104,6 +104,53 @@ int orc_graph_bruteforce(const float *W, int64_t C, int D, int K, const int32_t 
     return bad ? ORC_BAD_ARG : ORC_OK;
 }
 
+/*
+ * One hop of the distributed graph build (Section 3.2.2: the weight shards travel from node to node, every
+ * node searches each visiting shard and keeps its rows' best K so far).  The node owns C_loc rows W_local whose
+ * ids in the whole problem start at local_offset; W_visit holds C_vis rows with ids from visit_offset.
+ * graph [C_loc, K] / sims [C_loc, K] are the lists so far (ids of the whole problem in rank order, -1 = empty
+ * slot, sims = canonical fp64 similarities) and are updated in place to the best K of (list so far) U (visiting
+ * rows), the row itself excluded, a visiting row already in the list ignored.  Empty slots get -1 / -infinity.
+ */
+typedef struct { double s; int32_t id; } sim_id;
+static int cmp_sim_id(const void *a, const void *b) {
+    const sim_id *x = (const sim_id *)a, *y = (const sim_id *)b;
+    if (ranks_before(x->s, x->id, y->s, y->id)) return -1;
+    if (ranks_before(y->s, y->id, x->s, x->id)) return 1;
+    return 0;
+}
+int orc_graph_update(const float *W_local, int64_t C_loc, const float *W_visit, int64_t C_vis, int D, int K,
+                     int64_t local_offset, int64_t visit_offset, int32_t *graph, double *sims) {
+    if (!W_local || !W_visit || !graph || !sims || C_loc < 1 || C_vis < 1 || D < 1 || K < 1) return ORC_BAD_ARG;
+    if (local_offset < 0 || visit_offset < 0 || local_offset + C_loc > INT32_MAX || visit_offset + C_vis > INT32_MAX)
+        return ORC_BAD_ARG;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t i = 0; i < C_loc; ++i) {
+        sim_id *u = (sim_id *)malloc(sizeof(sim_id) * (size_t)(C_vis + K));
+        int64_t n = 0;
+        for (int k = 0; k < K; ++k)
+            if (graph[i * K + k] >= 0) { u[n].s = sims[i * K + k]; u[n].id = graph[i * K + k]; ++n; }
+        const int64_t n_old = n;
+        for (int64_t j = 0; j < C_vis; ++j) {
+            const int64_t id = visit_offset + j;
+            if (id == local_offset + i) continue;
+            int known = 0;
+            for (int64_t e = 0; e < n_old; ++e) known |= (u[e].id == id);
+            if (known) continue;
+            u[n].s = row_similarity(W_local + i * D, W_visit + j * D, D);
+            u[n].id = (int32_t)id;
+            ++n;
+        }
+        qsort(u, (size_t)n, sizeof(sim_id), cmp_sim_id);
+        for (int k = 0; k < K; ++k) {
+            graph[i * K + k] = k < n ? u[k].id : -1;
+            sims[i * K + k] = k < n ? u[k].s : -INFINITY;
+        }
+        free(u);
+    }
+    return ORC_OK;
+}
+
 /* ---------------------------------------------------------------------------------------------
  * Algorithm 1 (KNN graph-based active classes selection), without the random fill-up branch:
  * the union of the labels' neighbour lists (each list headed by the label itself), duplicates

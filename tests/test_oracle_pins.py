@@ -601,3 +601,48 @@ def test_fill_up_is_uniform_over_the_classes_not_chosen(orc):
     assert np.abs(rest - n_seeds * 0.25).max() < 5 * sigma
     chi2 = ((rest - n_seeds * 0.25) ** 2 / (n_seeds * 0.25 * 0.75)).sum()
     assert chi2 < 32 + 6 * np.sqrt(2 * 32)
+
+
+# ------------------------------------------------------------------------------------------------
+# one hop of the distributed graph build (Section 3.2.2): merging a visiting shard into the lists
+# ------------------------------------------------------------------------------------------------
+def _empty_lists(n, K):
+    return np.full((n, K), -1, dtype=np.int32), np.full((n, K), -np.inf)
+
+
+@pytest.mark.parametrize("bounds,order", [([0, 150, 300], [0, 1]), ([0, 150, 300], [1, 0]), ([0, 40, 41, 170, 300], [2, 0, 3, 1]),
+                                          ([0, 300], [0])])
+def test_graph_hops_over_all_shards_give_the_brute_force_graph(orc, bounds, order):
+    C, D, K = 300, 32, 7
+    W = synth.clustered_rows(4, C, D, n_centres=20, noise=0.4)
+    W[17] = W[3]                                                  # duplicate rows: ties decided by the id
+    W[250] = W[3]
+    G, S = orc.graph_bruteforce(W, K)
+    shards = list(zip(bounds[:-1], bounds[1:]))
+    for a, b in shards:                                           # every node in turn
+        g, s = _empty_lists(b - a, K)
+        for v in order:
+            va, vb = shards[v]
+            g, s = orc.graph_update(W[a:b], W[va:vb], a, va, g, s)
+        assert np.array_equal(g, G[a:b]) and np.array_equal(s, S[a:b])
+        g2, s2 = orc.graph_update(W[a:b], W[shards[0][0]:shards[0][1]], a, shards[0][0], g, s)   # a shard seen twice
+        assert np.array_equal(g2, g) and np.array_equal(s2, s)
+
+
+def test_graph_hop_hand_worked_case(orc):
+    # node owns ids 10, 11 (rows e0, e1); the visiting shard holds ids 4..6: e0, e1, (e0 + e1)
+    e = np.eye(4, dtype=np.float32)
+    W_local = np.stack([e[0], e[1]])
+    W_visit = np.stack([e[0], e[1], e[0] + e[1]])
+    g, s = _empty_lists(2, 2)
+    g, s = orc.graph_update(W_local, W_visit, 10, 4, g, s)
+    assert g.tolist() == [[4, 6], [5, 6]] and s.tolist() == [[1.0, 1.0], [1.0, 1.0]]         # ties: lower id first
+    # a second shard with ids 0..1: 2*e0 and e1 -- beats everything for row 10, ties for row 11
+    g, s = orc.graph_update(W_local, np.stack([2 * e[0], e[1]]), 10, 0, g, s)
+    assert g.tolist() == [[0, 4], [1, 5]] and s.tolist() == [[2.0, 1.0], [1.0, 1.0]]
+    # the node's own shard: the row itself is skipped, the other row has similarity 0 and does not make the list
+    g, s = orc.graph_update(W_local, W_local, 10, 10, g, s)
+    assert g.tolist() == [[0, 4], [1, 5]]
+    # fewer candidates than K: empty slots stay -1 / -inf
+    g, s = orc.graph_update(W_local, W_local[:1], 10, 10, *_empty_lists(2, 2))
+    assert g.tolist() == [[-1, -1], [10, -1]] and s[0].tolist() == [-np.inf, -np.inf] and s[1].tolist() == [0.0, -np.inf]
