@@ -187,6 +187,27 @@ int apply_weight_grad(float *W_master, uint16_t *W_bf16, const int32_t *idx, con
                       void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
 /* ------------------------------------------------------------------------------------------------------
+ * knn_graph_update -- one hop of the distributed graph build of Section 3.2.2 (the shards of W travel from
+ * node to node; every node searches each visiting shard and keeps the best K so far for its own rows).
+ *   W_local [C_loc, D]  the node's rows (dtype as knn_graph_build); their ids in the whole problem are
+ *                       local_offset + row
+ *   W_visit [C_vis, D]  the visiting shard, ids visit_offset + row (the node's own shard visits too, once)
+ *   graph   [C_loc, K]  in/out: the lists so far, ids of the whole problem in rank order, -1 = empty slot
+ *                       (a build starts from all -1)
+ *   sims    [C_loc, K]  in/out, fp64: canonical similarities of the entries (exact; fp32 would lose the order
+ *                       of near-ties between hops); -infinity in empty slots on output
+ * After the call each row's list holds the best K of (list so far) U (visiting rows) by (canonical similarity
+ * descending, id ascending) -- the same order and arithmetic as knn_graph_build -- the row itself excluded; a
+ * visiting row that is in the list already is ignored, so a shard that visits twice changes nothing.  After
+ * every shard has visited, the lists equal the graph knn_graph_build computes on the whole W.
+ * Requires D % 32 == 0, K <= KS_MAX_GRAPH_K, all ids < 2^31.  Workspace: knn_graph_update_workspace.
+ * ---------------------------------------------------------------------------------------------------- */
+size_t knn_graph_update_workspace(int64_t C_loc, int64_t C_vis, int D, int K, int dtype);
+int knn_graph_update(const void *W_local, const void *W_visit, int dtype, int64_t C_loc, int64_t C_vis, int D, int K,
+                     int64_t local_offset, int64_t visit_offset, int32_t *graph, double *sims, void *ws,
+                     size_t ws_bytes, int32_t *dev_status, void *stream);
+
+/* ------------------------------------------------------------------------------------------------------
  * One node of the sharded layer -- Section 3.2.3 (graph compression, quick access) and the fill-up branch of
  * Algorithm 1.  The node owns the classes [c0, c0 + C_loc) of a problem with Cg classes; labels and the dense
  * graph carry ids of the whole problem, everything the node produces carries local ids (global id - c0).

@@ -22,7 +22,7 @@ EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_se
            "full_softmax_workspace", "full_softmax_fwd_bwd", "apply_weight_grad_workspace", "apply_weight_grad",
            "knn_normalize_rows", "knn_norm_backward_rows", "apply_weight_grad_normalized_workspace",
            "apply_weight_grad_normalized", "knn_graph_compress_workspace", "knn_graph_compress",
-           "knn_select_active_csr_workspace", "knn_select_active_csr")
+           "knn_select_active_csr_workspace", "knn_select_active_csr", "knn_graph_update_workspace", "knn_graph_update")
 
 
 class KsError(RuntimeError):
@@ -386,3 +386,30 @@ def knn_select_active_csr(labels, counts, offsets, flat, c0, C_loc, K_max, M, pa
                                      _stream(stream))
     _check("knn_select_active_csr", rc)
     return out
+
+
+def knn_graph_update_workspace(C_loc, C_vis, D, K, dtype) -> int:
+    return int(lib().knn_graph_update_workspace(ct.c_int64(C_loc), ct.c_int64(C_vis), ct.c_int(D), ct.c_int(K),
+                                                ct.c_int(dtype)))
+
+
+def knn_graph_update(W_local, W_visit, local_offset, visit_offset, graph, sims, ws=None, dev_status=None, stream=None):
+    """One hop of the distributed graph build: merges the visiting shard into graph (int32 [C_loc, K], -1 = empty) and
+    sims (float64 [C_loc, K]) in place."""
+    if W_local.dtype not in (torch.bfloat16, torch.float32) or W_visit.dtype != W_local.dtype:
+        raise TypeError("W_local and W_visit must both be bfloat16 or both float32")
+    _need(W_local, W_local.dtype, "W_local")
+    _need(W_visit, W_visit.dtype, "W_visit")
+    _need(graph, torch.int32, "graph")
+    _need(sims, torch.float64, "sims")
+    (C_loc, D), C_vis, K = W_local.shape, W_visit.shape[0], graph.shape[1]
+    if W_visit.shape[1] != D or tuple(graph.shape) != (C_loc, K) or tuple(sims.shape) != (C_loc, K):
+        raise ValueError("shapes: W_visit [C_vis, D], graph and sims [C_loc, K]")
+    dtype = _dtype_code(W_local)
+    ws = _ws(knn_graph_update_workspace(C_loc, C_vis, D, K, dtype), W_local.device, ws)
+    dev_status = _status(W_local.device, dev_status)
+    rc = lib().knn_graph_update(_ptr(W_local), _ptr(W_visit), ct.c_int(dtype), ct.c_int64(C_loc), ct.c_int64(C_vis),
+                                ct.c_int(D), ct.c_int(K), ct.c_int64(local_offset), ct.c_int64(visit_offset), _ptr(graph),
+                                _ptr(sims), _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
+    _check("knn_graph_update", rc)
+    return dev_status

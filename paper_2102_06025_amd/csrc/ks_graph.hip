@@ -32,6 +32,17 @@ __device__ __forceinline__ float gr_unorder(uint32_t k) {
     return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
 }
 
+// The two sides of a recall pass: the rows whose neighbours are searched (resident in the workgroups) and the rows
+// that are searched (streamed past them).  The graph build searches W in W; one hop of the distributed build
+// searches the node's rows in a visiting shard.
+struct GrPair {
+    const uint16_t *R; // [Cr, D]
+    int64_t Cr;
+    const uint16_t *S; // [Cs, D]
+    int64_t Cs;
+    int64_t self;      // streamed row i + self is resident row i itself and is skipped
+};
+
 struct GrParams {
     int kprime; // candidates kept per row by the recall pass (64, 128 or 256)
     int cap;    // candidate buffer entries per row (256 or 512)
@@ -178,8 +189,9 @@ __device__ __forceinline__ void gr_compact_row(uint64_t *__restrict__ cand_row, 
 // ------------------------------------------------------------------------------------------------
 template <class T, int E>
 __global__ void __launch_bounds__(T::NT)
-gr_recall_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kprime, uint64_t *__restrict__ cand,
-                 int32_t *__restrict__ cnt_out, uint32_t *__restrict__ thr_out) {
+gr_recall_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, int32_t *__restrict__ cnt_out,
+                 uint32_t *__restrict__ thr_out) {
+    const int64_t C = pr.Cr;
     constexpr int CAP = E * 64;
     __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
     __shared__ int s_cnt[T::BM];
@@ -190,18 +202,18 @@ gr_recall_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kprime, 
     __syncthreads();
 
     KsRowLoader<T::BM, T::BK, T::NT> al;
-    al.init(Wb, D, nullptr, (int)row0, (int)C, D);
-    const int n_col_blocks = (int)((C + T::BN - 1) / T::BN);
+    al.init(pr.R, D, nullptr, (int)row0, (int)C, D);
+    const int n_col_blocks = (int)((pr.Cs + T::BN - 1) / T::BN);
     const int nk = (D + T::BK - 1) / T::BK;
     for (int J = 0; J < n_col_blocks; ++J) {
         KsRowLoader<T::BN, T::BK, T::NT> bl;
-        bl.init(Wb, D, nullptr, J * T::BN, (int)C, D);
+        bl.init(pr.S, D, nullptr, J * T::BN, (int)pr.Cs, D);
         f32x16_t acc[T::FM][T::FN];
         ks_tile_clear<T>(acc);
         ks_gemm_mainloop<T>(al, bl, 0, nk, lds, acc);
         ks_tile_foreach<T>(acc, [&](int m, int n, float v) {
             const int64_t i = row0 + m, j = (int64_t)J * T::BN + n;
-            if (i < C && j < C && i != j) {
+            if (i < C && j < pr.Cs && j != i + pr.self) {
                 const uint32_t hi = gr_orderable(v);
                 if (hi > s_thr[m]) {
                     int slot = atomicAdd(&s_cnt[m], 1);
@@ -234,8 +246,9 @@ gr_recall_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kprime, 
 // ------------------------------------------------------------------------------------------------
 template <class T, int E>
 __global__ void __launch_bounds__(T::NT)
-gr_recall_async_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kprime, uint64_t *__restrict__ cand,
-                       int32_t *__restrict__ cnt_out, uint32_t *__restrict__ thr_out) {
+gr_recall_async_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, int32_t *__restrict__ cnt_out,
+                       uint32_t *__restrict__ thr_out) {
+    const int64_t C = pr.Cr;
     constexpr int CAP = E * 64;
     static_assert(T::STAGES == 2 && CAP >= 256 + T::BN, "recall tile");
     __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
@@ -248,9 +261,9 @@ gr_recall_async_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kp
 
     KsARows<T::BM, T::NW> ar;
     KsARows<T::BN, T::NW> br;
-    ar.init(Wb, D, nullptr, (int)row0, (int)C);
-    br.init(Wb, D, nullptr, 0, (int)C);
-    const int nJ = (int)((C + T::BN - 1) / T::BN), nk = D / 64;
+    ar.init(pr.R, D, nullptr, (int)row0, (int)C);
+    br.init(pr.S, D, nullptr, 0, (int)pr.Cs);
+    const int nJ = (int)((pr.Cs + T::BN - 1) / T::BN), nk = D / 64;
     // stream position of the next tile to load
     int ld_J = 0, ld_kt = 0;
     auto issue_next = [&](int stage) {
@@ -260,7 +273,7 @@ gr_recall_async_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kp
         if (++ld_kt == nk) {
             ld_kt = 0;
             ++ld_J;
-            if (ld_J < nJ) br.init(Wb, D, nullptr, ld_J * T::BN, (int)C);
+            if (ld_J < nJ) br.init(pr.S, D, nullptr, ld_J * T::BN, (int)pr.Cs);
         }
     };
     issue_next(0);
@@ -277,7 +290,7 @@ gr_recall_async_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kp
         }
         ks_a_foreach<T>(acc, [&](int m, int n, float v) {
             const int64_t i = row0 + m, j = (int64_t)J * T::BN + n;
-            if (i < C && j < C && i != j) {
+            if (i < C && j < pr.Cs && j != i + pr.self) {
                 const uint32_t hi = gr_orderable(v);
                 if (hi > s_thr[m]) {
                     int slot = atomicAdd(&s_cnt[m], 1);
@@ -311,8 +324,9 @@ gr_recall_async_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kp
 // ------------------------------------------------------------------------------------------------
 template <int KT, int E>
 __global__ void __launch_bounds__(256)
-gr_recall_soe_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kprime, uint64_t *__restrict__ cand,
-                     int32_t *__restrict__ cnt_out, uint32_t *__restrict__ thr_out) {
+gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, int32_t *__restrict__ cnt_out,
+                     uint32_t *__restrict__ thr_out) {
+    const int64_t C = pr.Cr;
     typedef KsSoe<KT, 96, 6, 2> CFG;
     constexpr int CAP = E * 64;
     __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
@@ -331,9 +345,10 @@ gr_recall_soe_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kpri
         gi[fn] = (int)row0 + col[fn]; // C < 2^31
     }
     const int Ci = (int)C;
+    const int64_t self0 = row0 + pr.self; // streamed rows [self0, self0 + RES) are this workgroup's own rows
     auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM][2]) {
         // elements that need more than the threshold test: the tail of the last chunk, and the diagonal
-        const bool special = rows_here < CFG::CH || (c0 < (int)row0 + CFG::RES && c0 + CFG::CH > (int)row0);
+        const bool special = rows_here < CFG::CH || ((int64_t)c0 < self0 + CFG::RES && (int64_t)c0 + CFG::CH > self0);
 #pragma unroll
         for (int fn = 0; fn < 2; ++fn) {
             const uint32_t th = s_thr[col[fn]];
@@ -351,7 +366,7 @@ gr_recall_soe_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kpri
                         if (v > thf) {
                             const int lr = ks_soe_row(fm, r, lane);
                             const int j = c0 + lr;
-                            if (special && (lr >= rows_here || j == gi[fn])) continue;
+                            if (special && (lr >= rows_here || (int64_t)j == (int64_t)gi[fn] + pr.self)) continue;
                             const int slot = atomicAdd(&s_cnt[col[fn]], 1);
                             if (slot < CAP) // always true: a buffer is cut back before it can overflow
                                 cand[(int64_t)gi[fn] * CAP + slot] =
@@ -373,7 +388,7 @@ gr_recall_soe_kernel(const uint16_t *__restrict__ Wb, int64_t C, int D, int kpri
             if (threadIdx.x == 0) s_need = 0;
         }
     };
-    ks_soe_sweep<CFG>(Wb, D, (int)row0, (int)C, Wb, D, nullptr, 0, (int)C, (int)C, lds, epi);
+    ks_soe_sweep<CFG>(pr.R, D, (int)row0, (int)C, pr.S, D, nullptr, 0, (int)pr.Cs, (int)pr.Cs, lds, epi);
     __syncthreads();
     for (int m = wave; m < CFG::RES; m += 4) {
         if (row0 + m < C) {
@@ -612,6 +627,45 @@ static void gr_launch_exact(const IN *W, int64_t C, int D, int K, const GrParams
                        w.scratch, graph, sims);
 }
 
+static void gr_launch_recall(const GrPair &pr, int D, const GrParams &p, uint64_t *cand, int32_t *cnt, uint32_t *thr,
+                             hipStream_t st) {
+    const int64_t C = pr.Cr;
+    if (D == 128 || D == 256 || D == 512) {
+        const unsigned nb = (unsigned)ks_ceil_div(C, 256);
+#define GR_SOE_LAUNCH(KT)                                                                                                   \
+    do {                                                                                                                    \
+        if (p.cap == 256)                                                                                                   \
+            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 4>), dim3(nb), dim3(256), 0, st, pr, D, p.kprime, cand, cnt, thr);  \
+        else                                                                                                                \
+            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 8>), dim3(nb), dim3(256), 0, st, pr, D, p.kprime, cand, cnt, thr);  \
+    } while (0)
+        if (D == 512) GR_SOE_LAUNCH(8);
+        else if (D == 256) GR_SOE_LAUNCH(4);
+        else GR_SOE_LAUNCH(2);
+#undef GR_SOE_LAUNCH
+    } else if (D % 64 == 0) {
+        hipLaunchKernelGGL((gr_recall_async_kernel<TileRA, 8>), dim3((unsigned)ks_ceil_div(C, TileRA::BM)), dim3(TileRA::NT), 0,
+                           st, pr, D, p.kprime, cand, cnt, thr);
+    } else {
+        const unsigned recall_blocks = (unsigned)ks_ceil_div(C, TileR::BM);
+        if (p.cap == 256)
+            hipLaunchKernelGGL((gr_recall_kernel<TileR, 4>), dim3(recall_blocks), dim3(TileR::NT), 0, st, pr, D, p.kprime, cand,
+                               cnt, thr);
+        else
+            hipLaunchKernelGGL((gr_recall_kernel<TileR, 8>), dim3(recall_blocks), dim3(TileR::NT), 0, st, pr, D, p.kprime, cand,
+                               cnt, thr);
+    }
+}
+
+// error bound of the recall pass relative to |w_i||w_j|: fp32 accumulation of D exact bf16 products
+// (2^-23 per addition allows for truncating adders), plus the bf16 rounding of both rows (2 * 2^-9,
+// rounded up to 2^-7.9) when the input is fp32; a small slack covers the fp32 norms themselves
+static float gr_gamma(int D, int dtype) {
+    float gamma = (float)D * 1.1920929e-7f * 1.01f;
+    if (dtype == KS_DTYPE_FP32) gamma += 0.0042f;
+    return gamma;
+}
+
 extern "C" int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K, int32_t *graph, float *sims, void *ws,
                                size_t ws_bytes, int32_t *dev_status, void *stream) {
     (void)dev_status;
@@ -636,40 +690,303 @@ extern "C" int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K
                            (uint16_t *)nullptr, w.norms, w.maxnorm);
         Wb = (const uint16_t *)W;
     }
-    if (D == 128 || D == 256 || D == 512) {
-        const unsigned nb = (unsigned)ks_ceil_div(C, 256);
-#define GR_SOE_LAUNCH(KT)                                                                                                   \
-    do {                                                                                                                    \
-        if (p.cap == 256)                                                                                                   \
-            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 4>), dim3(nb), dim3(256), 0, st, Wb, C, D, p.kprime, w.cand, w.cnt, \
-                               w.thr);                                                                                      \
-        else                                                                                                                \
-            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 8>), dim3(nb), dim3(256), 0, st, Wb, C, D, p.kprime, w.cand, w.cnt, \
-                               w.thr);                                                                                      \
-    } while (0)
-        if (D == 512) GR_SOE_LAUNCH(8);
-        else if (D == 256) GR_SOE_LAUNCH(4);
-        else GR_SOE_LAUNCH(2);
-#undef GR_SOE_LAUNCH
-    } else if (D % 64 == 0) {
-        hipLaunchKernelGGL((gr_recall_async_kernel<TileRA, 8>), dim3((unsigned)ks_ceil_div(C, TileRA::BM)), dim3(TileRA::NT), 0,
-                           st, Wb, C, D, p.kprime, w.cand, w.cnt, w.thr);
-    } else {
-        const unsigned recall_blocks = (unsigned)ks_ceil_div(C, TileR::BM);
-        if (p.cap == 256)
-            hipLaunchKernelGGL((gr_recall_kernel<TileR, 4>), dim3(recall_blocks), dim3(TileR::NT), 0, st, Wb, C, D, p.kprime,
-                               w.cand, w.cnt, w.thr);
-        else
-            hipLaunchKernelGGL((gr_recall_kernel<TileR, 8>), dim3(recall_blocks), dim3(TileR::NT), 0, st, Wb, C, D, p.kprime,
-                               w.cand, w.cnt, w.thr);
-    }
-    // error bound of the recall pass relative to |w_i||w_j|: fp32 accumulation of D exact bf16 products
-    // (2^-23 per addition allows for truncating adders), plus the bf16 rounding of both rows (2 * 2^-9,
-    // rounded up to 2^-7.9) when the input is fp32; a small slack covers the fp32 norms themselves
-    float gamma = (float)D * 1.1920929e-7f * 1.01f;
-    if (dtype == KS_DTYPE_FP32) gamma += 0.0042f;
+    const GrPair pr{Wb, C, Wb, C, 0};
+    gr_launch_recall(pr, D, p, w.cand, w.cnt, w.thr, st);
+    const float gamma = gr_gamma(D, dtype);
     if (dtype == KS_DTYPE_FP32) gr_launch_exact<float>((const float *)W, C, D, K, p, w, gamma, graph, sims, st);
     else gr_launch_exact<uint16_t>((const uint16_t *)W, C, D, K, p, w, gamma, graph, sims, st);
+    KS_LAUNCH_CHECK();
+    return KS_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// One hop of the distributed graph build (Section 3.2.2: the shards of W travel from node to node, each node
+// searches every visiting shard and keeps its rows' best K so far).  Recall pass of the node's rows against the
+// visiting rows as above; then per row an exact merge of the recalled candidates with the list so far, on
+// (canonical fp64 similarity descending, id of the whole problem ascending), with the same certificate; rows
+// that fail it are merged against every visiting row.
+// ------------------------------------------------------------------------------------------------
+#define GR_NO_ID 0x7FFFFFFF
+
+// one wavefront per row; k' <= 256 candidates (slots 0..3) + K <= 128 list entries (slots 4, 5) per lane
+template <typename IN>
+__global__ void __launch_bounds__(GR_NT)
+gr_merge_kernel(const IN *__restrict__ Wl, int64_t C_loc, const IN *__restrict__ Wv, int64_t C_vis, int D, int K, int cap,
+                const uint64_t *__restrict__ cand, const int32_t *__restrict__ cnt, const uint32_t *__restrict__ thr,
+                const float *__restrict__ norms, const uint32_t *__restrict__ maxnorm_bits, float gamma, int64_t local_offset,
+                int64_t visit_offset, int32_t *__restrict__ graph, double *__restrict__ sims, int32_t *fb_count,
+                int32_t *__restrict__ fb_rows) {
+    const int64_t i = (int64_t)blockIdx.x * (GR_NT / 64) + (threadIdx.x >> 6);
+    if (i >= C_loc) return;
+    const int lane = threadIdx.x & 63;
+    const int n = cnt[i];
+    double s[6];
+    int32_t id[6];
+#pragma unroll
+    for (int t = 4; t < 6; ++t) { // the list so far
+        const int e = (t - 4) * 64 + lane;
+        s[t] = -INFINITY;
+        id[t] = GR_NO_ID;
+        if (e < K) {
+            const int32_t g = graph[i * K + e];
+            if (g >= 0) {
+                id[t] = g;
+                s[t] = sims[i * K + e];
+            }
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) { // the recalled candidates
+        const int q = t * 64 + lane;
+        s[t] = -INFINITY;
+        id[t] = GR_NO_ID;
+        if (q < n) {
+            const uint32_t j = 0xFFFFFFFFu - (uint32_t)cand[i * cap + q];
+            if (j < (uint64_t)C_vis) { // always true for keys written by the recall pass
+                id[t] = (int32_t)(visit_offset + j);
+                s[t] = gr_canon(Wl + i * D, Wv + (int64_t)j * D, D);
+            }
+        }
+    }
+    // a visiting row that is in the list already (a shard seen twice) is not a new candidate
+    const int list_slots = (K + 63) >> 6;
+    for (int t2 = 0; t2 < list_slots; ++t2) {
+        const int32_t mine = t2 == 0 ? id[4] : id[5];
+        for (int src = 0; src < 64; ++src) {
+            const int32_t oid = __shfl(mine, src, 64);
+            if (oid == GR_NO_ID) continue;
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (id[t] == oid) {
+                    id[t] = GR_NO_ID;
+                    s[t] = -INFINITY;
+                }
+        }
+    }
+    int rank[6] = {0, 0, 0, 0, 0, 0};
+    int n_valid = 0;
+    const int cand_slots = (n + 63) >> 6;
+#pragma unroll
+    for (int t2 = 0; t2 < 6; ++t2) {
+        if (t2 < 4 ? t2 >= cand_slots : t2 - 4 >= list_slots) continue; // uniform over the wavefront
+        n_valid += __popcll(__ballot(id[t2] != GR_NO_ID));
+        for (int src = 0; src < 64; ++src) {
+            const double os = __shfl(s[t2], src, 64);
+            const int32_t oid = __shfl(id[t2], src, 64);
+            if (oid == GR_NO_ID) continue;
+#pragma unroll
+            for (int t = 0; t < 6; ++t) rank[t] += gr_ranks_before(os, oid, s[t], id[t]) ? 1 : 0;
+        }
+    }
+    bool certified = true;
+#pragma unroll
+    for (int t = 0; t < 6; ++t) {
+        if (id[t] != GR_NO_ID && rank[t] < K) {
+            graph[i * K + rank[t]] = id[t];
+            sims[i * K + rank[t]] = s[t];
+            if (rank[t] == K - 1) {
+                // certificate: no visiting row that the recall pass dropped can reach the K-th exact similarity
+                const uint32_t th = thr[i];
+                if (th != 0u) {
+                    const double eps = (double)gamma * (double)norms[i] * (double)__uint_as_float(*maxnorm_bits);
+                    certified = s[t] > (double)gr_unorder(th) + eps;
+                }
+            }
+        }
+    }
+    for (int e = n_valid + lane; e < K; e += 64) { // fewer than K known so far: empty slots
+        graph[i * K + e] = -1;
+        sims[i * K + e] = -INFINITY;
+    }
+    if (n_valid < K && thr[i] != 0u) certified = false; // cannot happen (something was dropped, so k' >= K were kept)
+    if (__ballot(!certified) != 0ull && lane == 0) fb_rows[atomicAdd(fb_count, 1)] = (int32_t)i;
+}
+
+// rows on the list: every visiting row in canonical fp64 arithmetic, merged with the row's list
+template <typename IN>
+__global__ void __launch_bounds__(GR_NT)
+gr_exhaustive_merge_kernel(const IN *__restrict__ Wl, int64_t C_loc, const IN *__restrict__ Wv, int64_t C_vis, int D, int K,
+                           int64_t local_offset, int64_t visit_offset, const int32_t *__restrict__ fb_count,
+                           const int32_t *__restrict__ fb_rows, double *__restrict__ scratch, int32_t *__restrict__ graph,
+                           double *__restrict__ sims) {
+    __shared__ double red_s[GR_NT];
+    __shared__ int32_t red_j[GR_NT];
+    __shared__ __attribute__((aligned(16))) IN row_i[GR_MAX_D];
+    __shared__ double l_s[KS_MAX_GRAPH_K], o_s[KS_MAX_GRAPH_K];
+    __shared__ int32_t l_id[KS_MAX_GRAPH_K], o_id[KS_MAX_GRAPH_K];
+    int n_fb = *fb_count;
+    if (n_fb > C_loc) n_fb = (int)C_loc;
+    double *my = scratch + (int64_t)blockIdx.x * C_vis;
+    for (int e = blockIdx.x; e < n_fb; e += gridDim.x) {
+        const int64_t i = fb_rows[e];
+        for (int d = threadIdx.x; d < D; d += GR_NT) row_i[d] = Wl[i * D + d];
+        for (int k = threadIdx.x; k < K; k += GR_NT) {
+            l_id[k] = graph[i * K + k];
+            l_s[k] = sims[i * K + k];
+        }
+        __syncthreads();
+        for (int64_t j = threadIdx.x; j < C_vis; j += GR_NT) my[j] = gr_canon(row_i, Wv + j * D, D);
+        __syncthreads();
+        // the row itself and visiting rows that are in the list already are no candidates (-inf marks them: the
+        // similarity of real rows is finite)
+        if (threadIdx.x == 0) {
+            const int64_t js = local_offset + i - visit_offset;
+            if (js >= 0 && js < C_vis) my[js] = -INFINITY;
+        }
+        for (int k = threadIdx.x; k < K; k += GR_NT) {
+            const int64_t jl = (int64_t)l_id[k] - visit_offset;
+            if (l_id[k] >= 0 && jl >= 0 && jl < C_vis) my[jl] = -INFINITY;
+        }
+        __syncthreads();
+        double prev_s = INFINITY;
+        int32_t prev_j = -1;
+        for (int r = 0; r < K; ++r) {
+            double best_s = -INFINITY;
+            int32_t best_j = GR_NO_ID;
+            for (int64_t j = threadIdx.x; j < C_vis; j += GR_NT) {
+                const double sj = my[j];
+                if (sj == -INFINITY) continue;
+                const int32_t gj = (int32_t)(visit_offset + j);
+                if (gr_ranks_before(prev_s, prev_j, sj, gj) && gr_ranks_before(sj, gj, best_s, best_j)) {
+                    best_s = sj;
+                    best_j = gj;
+                }
+            }
+            for (int k = threadIdx.x; k < K; k += GR_NT) {
+                if (l_id[k] < 0) continue;
+                if (gr_ranks_before(prev_s, prev_j, l_s[k], l_id[k]) && gr_ranks_before(l_s[k], l_id[k], best_s, best_j)) {
+                    best_s = l_s[k];
+                    best_j = l_id[k];
+                }
+            }
+            red_s[threadIdx.x] = best_s;
+            red_j[threadIdx.x] = best_j;
+            __syncthreads();
+            for (int o = GR_NT / 2; o > 0; o >>= 1) {
+                if (threadIdx.x < o) {
+                    if (gr_ranks_before(red_s[threadIdx.x + o], red_j[threadIdx.x + o], red_s[threadIdx.x], red_j[threadIdx.x])) {
+                        red_s[threadIdx.x] = red_s[threadIdx.x + o];
+                        red_j[threadIdx.x] = red_j[threadIdx.x + o];
+                    }
+                }
+                __syncthreads();
+            }
+            prev_s = red_s[0];
+            prev_j = red_j[0];
+            if (threadIdx.x == 0) {
+                o_id[r] = prev_j == GR_NO_ID ? -1 : prev_j;
+                o_s[r] = prev_j == GR_NO_ID ? -INFINITY : prev_s;
+            }
+            __syncthreads();
+            if (prev_j == GR_NO_ID) { // nothing left: the remaining slots are empty
+                for (int k = r + 1 + threadIdx.x; k < K; k += GR_NT) { o_id[k] = -1; o_s[k] = -INFINITY; }
+                break;
+            }
+        }
+        __syncthreads();
+        for (int k = threadIdx.x; k < K; k += GR_NT) {
+            graph[i * K + k] = o_id[k];
+            sims[i * K + k] = o_s[k];
+        }
+        __syncthreads();
+    }
+}
+
+struct GrUpWs {
+    uint16_t *Wlb, *Wvb;
+    float *norms_l, *norms_v;
+    uint32_t *maxnorm_l, *maxnorm_v;
+    uint64_t *cand;
+    int32_t *cnt;
+    uint32_t *thr;
+    int32_t *fb_count;
+    int32_t *fb_rows;
+    double *scratch;
+};
+static GrUpWs gr_up_carve(void *ws, int64_t C_loc, int64_t C_vis, int D, int K, int dtype, size_t *total) {
+    KsArena ar(ws);
+    GrParams p = gr_params(K, D);
+    GrUpWs w;
+    w.Wlb = dtype == KS_DTYPE_FP32 ? ar.take<uint16_t>((size_t)C_loc * D) : nullptr;
+    w.Wvb = dtype == KS_DTYPE_FP32 ? ar.take<uint16_t>((size_t)C_vis * D) : nullptr;
+    w.norms_l = ar.take<float>((size_t)C_loc);
+    w.norms_v = ar.take<float>((size_t)C_vis);
+    w.maxnorm_l = ar.take<uint32_t>(1);
+    w.maxnorm_v = ar.take<uint32_t>(1);
+    w.cand = ar.take<uint64_t>((size_t)C_loc * p.cap);
+    w.cnt = ar.take<int32_t>((size_t)C_loc);
+    w.thr = ar.take<uint32_t>((size_t)C_loc);
+    w.fb_count = ar.take<int32_t>(1);
+    w.fb_rows = ar.take<int32_t>((size_t)C_loc);
+    w.scratch = ar.take<double>((size_t)GR_FB_BLOCKS * C_vis);
+    if (total) *total = ar.off;
+    return w;
+}
+static int gr_up_check(int64_t C_loc, int64_t C_vis, int D, int K, int dtype, int64_t lo, int64_t vo) {
+    if (dtype != KS_DTYPE_BF16 && dtype != KS_DTYPE_FP32) return KS_INVALID_ARG;
+    if (C_loc < 1 || C_vis < 1 || D < 32 || D % 32 != 0 || K < 1 || lo < 0 || vo < 0) return KS_INVALID_ARG;
+    if (lo + C_loc >= (int64_t)1 << 31 || vo + C_vis >= (int64_t)1 << 31) return KS_INVALID_ARG;
+    if (K > KS_MAX_GRAPH_K || D > GR_MAX_D) return KS_UNSUPPORTED;
+    return KS_OK;
+}
+
+extern "C" size_t knn_graph_update_workspace(int64_t C_loc, int64_t C_vis, int D, int K, int dtype) {
+    if (gr_up_check(C_loc, C_vis, D, K, dtype, 0, 0) != KS_OK) return 0;
+    size_t total = 0;
+    gr_up_carve(nullptr, C_loc, C_vis, D, K, dtype, &total);
+    return total;
+}
+
+template <typename IN>
+static void gr_up_prepare(const IN *W, int64_t C, int D, uint16_t *Wb, float *norms, uint32_t *maxnorm, hipStream_t st) {
+    hipLaunchKernelGGL(gr_prepare_kernel<IN>, dim3((unsigned)ks_ceil_div(C, GR_NT / 64)), dim3(GR_NT), 0, st, W, C, D, Wb, norms,
+                       maxnorm);
+}
+template <typename IN>
+static void gr_up_exact(const IN *Wl, int64_t C_loc, const IN *Wv, int64_t C_vis, int D, int K, const GrParams &p,
+                        const GrUpWs &w, float gamma, int64_t lo, int64_t vo, int32_t *graph, double *sims, hipStream_t st) {
+    hipLaunchKernelGGL(gr_merge_kernel<IN>, dim3((unsigned)ks_ceil_div(C_loc, GR_NT / 64)), dim3(GR_NT), 0, st, Wl, C_loc, Wv,
+                       C_vis, D, K, p.cap, w.cand, w.cnt, w.thr, w.norms_l, w.maxnorm_v, gamma, lo, vo, graph, sims, w.fb_count,
+                       w.fb_rows);
+    hipLaunchKernelGGL(gr_exhaustive_merge_kernel<IN>, dim3(GR_FB_BLOCKS), dim3(GR_NT), 0, st, Wl, C_loc, Wv, C_vis, D, K, lo, vo,
+                       w.fb_count, w.fb_rows, w.scratch, graph, sims);
+}
+
+extern "C" int knn_graph_update(const void *W_local, const void *W_visit, int dtype, int64_t C_loc, int64_t C_vis, int D, int K,
+                                int64_t local_offset, int64_t visit_offset, int32_t *graph, double *sims, void *ws,
+                                size_t ws_bytes, int32_t *dev_status, void *stream) {
+    (void)dev_status;
+    if (!W_local || !W_visit || !graph || !sims || !ws) return KS_INVALID_ARG;
+    int rc = gr_up_check(C_loc, C_vis, D, K, dtype, local_offset, visit_offset);
+    if (rc != KS_OK) return rc;
+    size_t need = 0;
+    GrUpWs w = gr_up_carve(ws, C_loc, C_vis, D, K, dtype, &need);
+    if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
+    const GrParams p = gr_params(K, D);
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(gr_zero_kernel, dim3(1), dim3(1), 0, st, w.maxnorm_l, w.fb_count);
+    hipLaunchKernelGGL(gr_zero_kernel, dim3(1), dim3(1), 0, st, w.maxnorm_v, w.fb_count);
+    const uint16_t *Rl, *Sv;
+    if (dtype == KS_DTYPE_FP32) {
+        gr_up_prepare<float>((const float *)W_local, C_loc, D, w.Wlb, w.norms_l, w.maxnorm_l, st);
+        gr_up_prepare<float>((const float *)W_visit, C_vis, D, w.Wvb, w.norms_v, w.maxnorm_v, st);
+        Rl = w.Wlb;
+        Sv = w.Wvb;
+    } else {
+        gr_up_prepare<uint16_t>((const uint16_t *)W_local, C_loc, D, nullptr, w.norms_l, w.maxnorm_l, st);
+        gr_up_prepare<uint16_t>((const uint16_t *)W_visit, C_vis, D, nullptr, w.norms_v, w.maxnorm_v, st);
+        Rl = (const uint16_t *)W_local;
+        Sv = (const uint16_t *)W_visit;
+    }
+    const GrPair pr{Rl, C_loc, Sv, C_vis, local_offset - visit_offset};
+    gr_launch_recall(pr, D, p, w.cand, w.cnt, w.thr, st);
+    const float gamma = gr_gamma(D, dtype);
+    if (dtype == KS_DTYPE_FP32)
+        gr_up_exact<float>((const float *)W_local, C_loc, (const float *)W_visit, C_vis, D, K, p, w, gamma, local_offset,
+                           visit_offset, graph, sims, st);
+    else
+        gr_up_exact<uint16_t>((const uint16_t *)W_local, C_loc, (const uint16_t *)W_visit, C_vis, D, K, p, w, gamma,
+                              local_offset, visit_offset, graph, sims, st);
     KS_LAUNCH_CHECK();
     return KS_OK;
 }

@@ -23,7 +23,7 @@ def ks():
 def _declared_functions():
     src = open(HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress))\s*\(", src)))
+    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update))\s*\(", src)))
 
 
 def test_header_symbols_are_exported(ks):
@@ -117,6 +117,16 @@ def test_argument_errors_are_reported_before_any_launch(ks):
                                 null) == ks.KS_INVALID_ARG
     assert L.knn_graph_compress(one, i64(1000), i(8), i64(0), i64(20), one, one, null, i64(0), one, sz(0), null,
                                 null) == ks.KS_WORKSPACE_TOO_SMALL
+
+    def upd(C_loc=100, C_vis=50, D=128, K=8, lo=0, vo=100, ws_bytes=1 << 40, dtype=0):
+        return L.knn_graph_update(one, one, i(dtype), i64(C_loc), i64(C_vis), i(D), i(K), i64(lo), i64(vo), one, one, one,
+                                  sz(ws_bytes), null, null)
+
+    assert upd(D=72) == ks.KS_INVALID_ARG
+    assert upd(K=129) == ks.KS_UNSUPPORTED
+    assert upd(vo=(1 << 31) - 10) == ks.KS_INVALID_ARG    # ids must stay below 2^31
+    assert upd(dtype=5) == ks.KS_INVALID_ARG
+    assert upd(ws_bytes=64) == ks.KS_WORKSPACE_TOO_SMALL
     assert L.knn_normalize_rows(one, i(0), i64(4), i(128), null, null, null) == ks.KS_INVALID_ARG   # no output
     assert L.knn_normalize_rows(one, i(3), i64(4), i(128), one, one, null) == ks.KS_INVALID_ARG     # dtype
     assert L.knn_normalize_rows(one, i(0), i64(4), i(6), one, one, null) == ks.KS_INVALID_ARG       # D % 4
