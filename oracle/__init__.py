@@ -27,7 +27,8 @@ def lib():
         for name in ("orc_graph_bruteforce", "orc_select_active", "orc_knn_softmax_fwd_bwd",
                      "orc_full_softmax_fwd_bwd", "orc_apply_weight_grad", "orc_normalize_rows", "orc_norm_backward",
                      "orc_apply_weight_grad_normalized", "orc_graph_compress", "orc_pad_draws",
-                     "orc_select_active_csr", "orc_graph_update"):
+                     "orc_select_active_csr", "orc_graph_update", "orc_softmax_node_stats",
+                     "orc_softmax_node_bwd"):
             getattr(_lib, name).restype = ct.c_int
     return _lib
 
@@ -247,3 +248,46 @@ def graph_update(W_local, W_visit, local_offset: int, visit_offset: int, graph, 
     if rc != ORC_OK:
         raise ValueError(f"orc_graph_update failed with code {rc}")
     return graph, sims
+
+
+def softmax_node_stats(W, X, active, target_pos, scale: float):
+    """One node's part of the distributed softmax: per sample (max, sum of exponentials relative to it, target logit
+    or 0 when target_pos < 0) over the node's active columns.  fp64 arrays [B]."""
+    W, X = _f32(W), _f32(X)
+    active, target_pos = _i32(active), _i32(target_pos)
+    A, (B, D) = active.shape[0], X.shape
+    m, l, t = (np.empty(B, dtype=np.float64) for _ in range(3))
+    rc = lib().orc_softmax_node_stats(_p(W, ct.c_float), _p(X, ct.c_float), _p(active, ct.c_int32), ct.c_int(A),
+                                      _p(target_pos, ct.c_int32), ct.c_int(B), ct.c_int(D), ct.c_double(scale),
+                                      _p(m, ct.c_double), _p(l, ct.c_double), _p(t, ct.c_double))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_softmax_node_stats failed with code {rc}")
+    return m, l, t
+
+
+def softmax_node_bwd(W, X, active, target_pos, scale: float, grad_scale: float, Mg, Sg, Tg):
+    """One node's backward pass given the statistics combined over all nodes.  Returns dict(loss_i, loss, dX (this
+    node's contribution), dWA), fp64."""
+    W, X = _f32(W), _f32(X)
+    active, target_pos = _i32(active), _i32(target_pos)
+    Mg, Sg, Tg = (np.ascontiguousarray(v, dtype=np.float64) for v in (Mg, Sg, Tg))
+    A, (B, D) = active.shape[0], X.shape
+    loss_i = np.empty(B, dtype=np.float64)
+    loss = ct.c_double(0.0)
+    dX = np.empty((B, D), dtype=np.float64)
+    dWA = np.empty((A, D), dtype=np.float64)
+    rc = lib().orc_softmax_node_bwd(_p(W, ct.c_float), _p(X, ct.c_float), _p(active, ct.c_int32), ct.c_int(A),
+                                    _p(target_pos, ct.c_int32), ct.c_int(B), ct.c_int(D), ct.c_double(scale),
+                                    ct.c_double(grad_scale), _p(Mg, ct.c_double), _p(Sg, ct.c_double), _p(Tg, ct.c_double),
+                                    _p(loss_i, ct.c_double), ct.byref(loss), _p(dX, ct.c_double), _p(dWA, ct.c_double))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_softmax_node_bwd failed with code {rc}")
+    return dict(loss_i=loss_i, loss=float(loss.value), dX=dX, dWA=dWA)
+
+
+def combine_node_stats(stats):
+    """(M, S, T) over nodes from a list of (m, l, t): M = max m, S = sum l exp(m - M), T = sum t."""
+    M = np.max([m for m, _, _ in stats], axis=0)
+    S = np.sum([l * np.exp(m - M) for m, l, _ in stats], axis=0)
+    T = np.sum([t for _, _, t in stats], axis=0)
+    return M, S, T

@@ -412,6 +412,91 @@ int orc_knn_softmax_fwd_bwd(const float *W, const float *X, const int32_t *activ
     return ORC_OK;
 }
 
+/* ---------------------------------------------------------------------------------------------
+ * The softmax of the model-parallel layer, one node's part (Section 3.1, steps 3-5: every node holds the logits
+ * of its own classes; the softmax needs each sample's maximum and sum of exponentials over ALL nodes, which the
+ * nodes exchange; then every node forms the gradient of its own logits).
+ *
+ * orc_softmax_node_stats: for the node's active columns, per sample
+ *     m_i = max_a Z_ia,   l_i = sum_a exp(Z_ia - m_i),   t_i = Z_{i, target_pos[i]}  (0 if target_pos[i] < 0:
+ *     another node owns the sample's class).
+ * Combining nodes p:  M_i = max_p m_i^p,  S_i = sum_p l_i^p exp(m_i^p - M_i),  T_i = sum_p t_i^p.
+ * orc_softmax_node_bwd: with the combined (M, S, T):
+ *     loss_i = M_i + log S_i - T_i,   dZ_ia = (grad_scale / B) (exp(Z_ia - M_i) / S_i - [a == target_pos[i]]),
+ *     dX (this node's contribution, to be summed over the nodes) and dWA as in orc_knn_softmax_fwd_bwd.
+ * ------------------------------------------------------------------------------------------- */
+int orc_softmax_node_stats(const float *W, const float *X, const int32_t *active, int A, const int32_t *target_pos, int B,
+                           int D, double scale, double *m_out, double *l_out, double *t_out) {
+    if (!W || !X || !active || !target_pos || !m_out || !l_out || !t_out || A < 1 || B < 1 || D < 1) return ORC_BAD_ARG;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < B; ++i) {
+        double *z = (double *)malloc(sizeof(double) * (size_t)A);
+        for (int a = 0; a < A; ++a) {
+            const float *w = W + (int64_t)active[a] * D;
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d) acc += (double)X[(size_t)i * D + d] * (double)w[d];
+            z[a] = scale * acc;
+        }
+        double m = z[0];
+        for (int a = 1; a < A; ++a) if (z[a] > m) m = z[a];
+        double l = 0.0;
+        for (int a = 0; a < A; ++a) l += exp(z[a] - m);
+        m_out[i] = m;
+        l_out[i] = l;
+        t_out[i] = (target_pos[i] >= 0 && target_pos[i] < A) ? z[target_pos[i]] : 0.0;
+        free(z);
+    }
+    return ORC_OK;
+}
+
+int orc_softmax_node_bwd(const float *W, const float *X, const int32_t *active, int A, const int32_t *target_pos, int B,
+                         int D, double scale, double grad_scale, const double *Mg, const double *Sg, const double *Tg,
+                         double *loss_i, double *loss_mean, double *dX, double *dWA) {
+    if (!W || !X || !active || !target_pos || !Mg || !Sg || !Tg || !loss_i || !loss_mean || !dX || !dWA) return ORC_BAD_ARG;
+    if (A < 1 || B < 1 || D < 1) return ORC_BAD_ARG;
+    double *dZ = (double *)malloc(sizeof(double) * (size_t)B * (size_t)A);
+    if (!dZ) return ORC_BAD_ARG;
+    const double g = grad_scale / (double)B;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < B; ++i) {
+        double *z = dZ + (size_t)i * A;
+        for (int a = 0; a < A; ++a) {
+            const float *w = W + (int64_t)active[a] * D;
+            double acc = 0.0;
+            for (int d = 0; d < D; ++d) acc += (double)X[(size_t)i * D + d] * (double)w[d];
+            z[a] = scale * acc;
+        }
+        loss_i[i] = Mg[i] + log(Sg[i]) - Tg[i];
+        for (int a = 0; a < A; ++a) z[a] = g * (exp(z[a] - Mg[i]) / Sg[i] - (a == target_pos[i] ? 1.0 : 0.0));
+    }
+    double tot = 0.0;
+    for (int i = 0; i < B; ++i) tot += loss_i[i];
+    *loss_mean = tot / (double)B;
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < B; ++i) {
+        double *out = dX + (size_t)i * D;
+        for (int d = 0; d < D; ++d) out[d] = 0.0;
+        for (int a = 0; a < A; ++a) {
+            const float *w = W + (int64_t)active[a] * D;
+            const double dz = dZ[(size_t)i * A + a];
+            for (int d = 0; d < D; ++d) out[d] += dz * (double)w[d];
+        }
+        for (int d = 0; d < D; ++d) out[d] *= scale;
+    }
+#pragma omp parallel for schedule(static)
+    for (int a = 0; a < A; ++a) {
+        double *out = dWA + (size_t)a * D;
+        for (int d = 0; d < D; ++d) out[d] = 0.0;
+        for (int i = 0; i < B; ++i) {
+            const double dz = dZ[(size_t)i * A + a];
+            for (int d = 0; d < D; ++d) out[d] += dz * (double)X[(size_t)i * D + d];
+        }
+        for (int d = 0; d < D; ++d) out[d] *= scale;
+    }
+    free(dZ);
+    return ORC_OK;
+}
+
 /*
  * Full softmax over all C classes (the baseline the paper compares against; Section 3.2 claims the
  * KNN variant equals it on the selected columns).  Written separately from the function above on

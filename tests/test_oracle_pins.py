@@ -646,3 +646,59 @@ def test_graph_hop_hand_worked_case(orc):
     # fewer candidates than K: empty slots stay -1 / -inf
     g, s = orc.graph_update(W_local, W_local[:1], 10, 10, *_empty_lists(2, 2))
     assert g.tolist() == [[-1, -1], [10, -1]] and s[0].tolist() == [-np.inf, -np.inf] and s[1].tolist() == [0.0, -np.inf]
+
+
+# ------------------------------------------------------------------------------------------------
+# the softmax split over nodes (Section 3.1 steps 3-5)
+# ------------------------------------------------------------------------------------------------
+def test_softmax_split_over_nodes_equals_the_softmax_on_one_gpu(orc):
+    C, D, B, K, s, gs, P = 600, 24, 20, 6, 12.0, 64.0, 3
+    W = synth.unit_rows(31, synth.TID_W, C, D)
+    y = synth.labels_uniform(31, B, C)
+    X = synth.features_near_labels(31, W, y, sigma=1.0)
+    G = synth.graph_synthetic(31, C, K, locality=16)
+    active, A, tpos = orc.select_active(y, G, C, 512)
+    ref = orc.knn_softmax_fwd_bwd(W, X, active[:A], tpos, s, gs)
+    bounds = [0, 150, 420, 600]
+    nodes = []
+    for c0, c1 in zip(bounds[:-1], bounds[1:]):
+        counts, offsets, flat = orc.graph_compress(G, c0, c1 - c0)
+        a, n, _, t = orc.select_active_csr(y, counts, offsets, flat, c0, c1 - c0, 512)
+        nodes.append((c0, c1, a[:n], t))
+    stats = [orc.softmax_node_stats(W[c0:c1], X, a, t, s) for c0, c1, a, t in nodes]
+    Mg, Sg, Tg = orc.combine_node_stats(stats)
+    assert np.allclose(Mg + np.log(Sg), ref["lse"], rtol=0, atol=1e-12)
+    dX = np.zeros((B, D))
+    dW_rows = {}
+    for (c0, c1, a, t), (m, l, tz) in zip(nodes, stats):
+        out = orc.softmax_node_bwd(W[c0:c1], X, a, t, s, gs, Mg, Sg, Tg)
+        assert np.allclose(out["loss_i"], ref["loss_i"], rtol=0, atol=1e-11) and abs(out["loss"] - ref["loss"]) < 1e-12
+        dX += out["dX"]
+        for r, c in enumerate(a):
+            dW_rows[int(c) + c0] = out["dWA"][r]
+        # another pair (m, l) for the same sums gives the same statistics after combining
+        shifted = [(mm - 3.0, ll * np.exp(3.0), tt) if k == 0 else (mm, ll, tt) for k, (mm, ll, tt) in enumerate(stats)]
+        M2, S2, _ = orc.combine_node_stats(shifted)
+        assert np.allclose(M2 + np.log(S2), Mg + np.log(Sg), rtol=0, atol=1e-12)
+    assert np.allclose(dX, ref["dX"], rtol=0, atol=1e-13 * gs)
+    assert sorted(dW_rows) == active[:A].tolist()
+    assert np.allclose(np.stack([dW_rows[int(c)] for c in active[:A]]), ref["dWA"], rtol=0, atol=1e-13 * gs)
+    # every sample has its target on exactly one node, and that node reports the target's logit
+    owners = np.sum([(t >= 0).astype(int) for _, _, _, t in nodes], axis=0)
+    assert (owners == 1).all()
+    Z = s * X.astype(np.float64) @ W.astype(np.float64).T
+    assert np.allclose(Tg, Z[np.arange(B), y], rtol=0, atol=1e-12)
+
+
+def test_softmax_node_with_a_single_column_closed_form(orc):
+    # one node holding one class, one sample whose class lives elsewhere: m = z, l = 1, t = 0; with the other node's
+    # statistics (M, S, T) the gradient of the only logit is g * exp(z - M) / S
+    W = np.array([[0.6, 0.8]], dtype=np.float32)
+    X = np.array([[1.0, 0.0]], dtype=np.float32)
+    m, l, t = orc.softmax_node_stats(W, X, np.array([0], dtype=np.int32), np.array([-1], dtype=np.int32), 10.0)
+    assert abs(m[0] - 6.0) < 1e-6 and l[0] == 1.0 and t[0] == 0.0
+    out = orc.softmax_node_bwd(W, X, np.array([0], dtype=np.int32), np.array([-1], dtype=np.int32), 10.0, 2.0,
+                               np.array([8.0]), np.array([1.5]), np.array([7.0]))
+    dz = 2.0 * np.exp(m[0] - 8.0) / 1.5
+    assert abs(out["loss"] - (8.0 + np.log(1.5) - 7.0)) < 1e-12
+    assert np.allclose(out["dX"][0], 10.0 * dz * W[0].astype(np.float64)) and np.allclose(out["dWA"][0], 10.0 * dz * X[0])
