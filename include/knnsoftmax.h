@@ -187,6 +187,47 @@ int apply_weight_grad(float *W_master, uint16_t *W_bf16, const int32_t *idx, con
                       void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
 /* ------------------------------------------------------------------------------------------------------
+ * The softmax split over the nodes of the model-parallel layer -- Section 3.1, steps 3 to 5: every node
+ * computes the logits of its own classes for the whole (gathered) batch; the softmax needs each sample's maximum
+ * and sum of exponentials over all nodes, which the nodes exchange (a tiny message, Section 3.4); then every node
+ * forms the gradient of its own logits, its weight gradient and its contribution to the feature gradient.
+ * This is one node's half of it, in two calls around the exchange:
+ *
+ * knn_softmax_fwd_stats: logits of the active classes (active_idx, n_active, target_pos as written by
+ *   knn_select_active or knn_select_active_csr: local ids, target_pos = -1 for a sample whose class another node
+ *   owns) and per sample
+ *     row_max [B], row_sumexp [B]:  a pair with  sum_a exp(z_ia - row_max_i) = row_sumexp_i, not necessarily
+ *                  the maximum itself: where the one-sweep softmax runs (KS_FLAG_UNIT_ROWS, D = 128, 256 or 512,
+ *                  scale <= 40) row_max = scale for every sample on every node, so that combining the nodes
+ *                  comes down to ADDING their sums; otherwise the pair is normalised to row_sumexp = 1.  A node
+ *                  without active classes gives (-infinity, 0)
+ *     target_logit [B]:  z of the sample's own class, 0 where target_pos < 0
+ *   The caller combines the nodes p:  M_i = max_p row_max,  S_i = sum_p row_sumexp * exp(row_max - M_i),
+ *   T_i = sum_p target_logit.
+ * knn_softmax_bwd_from_stats: with global_max = M, global_sumexp = S, global_target_logit = T:
+ *     loss_per_sample_i = M_i + log S_i - T_i (the same on every node), loss_mean;
+ *     dZ_ia = (grad_scale / B) * (exp(z_ia - M_i) / S_i - [a == target_pos[i]]);
+ *     dX [B, D] = scale * dZ * W_active  -- THIS NODE'S CONTRIBUTION, to be summed over the nodes;
+ *     dW_active [M, D] = scale * dZ^T * X  (rows >= n_active not written), for apply_weight_grad.
+ * Same arguments (W, X, selection, scale, flags, B, M) in both calls, and the SAME workspace, untouched in between:
+ * with KS_FLAG_UNIT_ROWS the first call leaves the exponentials there and the second call makes no second sweep.
+ * B is the gathered batch (the mean and grad_scale / B refer to it).  An active_idx entry outside [0, C) sets
+ * KS_DEV_BAD_INDEX (and is replaced by row 0), a target_pos >= n_active sets KS_DEV_BAD_LABEL (treated as -1).
+ * Requires D % 64 == 0 (KS_UNSUPPORTED otherwise), B <= M not required.  Tolerances as knn_softmax_fwd_bwd.
+ * ---------------------------------------------------------------------------------------------------- */
+size_t knn_softmax_split_workspace(int64_t C, int D, int B, int M);
+int knn_softmax_fwd_stats(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *active_idx,
+                          const int32_t *n_active, const int32_t *target_pos, int64_t C, int D, int B, int M,
+                          float scale, uint32_t flags, float *row_max, float *row_sumexp, float *target_logit,
+                          void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
+int knn_softmax_bwd_from_stats(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *active_idx,
+                               const int32_t *n_active, const int32_t *target_pos, const float *global_max,
+                               const float *global_sumexp, const float *global_target_logit, int64_t C, int D, int B,
+                               int M, float scale, float grad_scale, uint32_t flags, float *loss_per_sample,
+                               float *loss_mean, float *dX, float *dW_active, void *ws, size_t ws_bytes,
+                               int32_t *dev_status, void *stream);
+
+/* ------------------------------------------------------------------------------------------------------
  * knn_graph_update -- one hop of the distributed graph build of Section 3.2.2 (the shards of W travel from
  * node to node; every node searches each visiting shard and keeps the best K so far for its own rows).
  *   W_local [C_loc, D]  the node's rows (dtype as knn_graph_build); their ids in the whole problem are

@@ -22,7 +22,8 @@ EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_se
            "full_softmax_workspace", "full_softmax_fwd_bwd", "apply_weight_grad_workspace", "apply_weight_grad",
            "knn_normalize_rows", "knn_norm_backward_rows", "apply_weight_grad_normalized_workspace",
            "apply_weight_grad_normalized", "knn_graph_compress_workspace", "knn_graph_compress",
-           "knn_select_active_csr_workspace", "knn_select_active_csr", "knn_graph_update_workspace", "knn_graph_update")
+           "knn_select_active_csr_workspace", "knn_select_active_csr", "knn_graph_update_workspace", "knn_graph_update",
+           "knn_softmax_split_workspace", "knn_softmax_fwd_stats", "knn_softmax_bwd_from_stats")
 
 
 class KsError(RuntimeError):
@@ -413,3 +414,56 @@ def knn_graph_update(W_local, W_visit, local_offset, visit_offset, graph, sims, 
                                 _ptr(sims), _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
     _check("knn_graph_update", rc)
     return dev_status
+
+
+def knn_softmax_split_workspace(C, D, B, M) -> int:
+    return int(lib().knn_softmax_split_workspace(ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(M)))
+
+
+def knn_softmax_fwd_stats(W_bf16, X_bf16, active_idx, n_active, target_pos, scale, unit_rows=False, ws=None,
+                          dev_status=None, stream=None):
+    """First call of the softmax split over nodes.  Returns dict(row_max, row_sumexp, target_logit [B] fp32, ws,
+    dev_status); pass the same `ws` to knn_softmax_bwd_from_stats."""
+    _need(W_bf16, torch.bfloat16, "W_bf16")
+    _need(X_bf16, torch.bfloat16, "X_bf16")
+    _need(active_idx, torch.int32, "active_idx")
+    _need(target_pos, torch.int32, "target_pos")
+    (C, D), B, M = W_bf16.shape, X_bf16.shape[0], active_idx.numel()
+    dev = W_bf16.device
+    out = dict(row_max=torch.empty(B, dtype=torch.float32, device=dev),
+               row_sumexp=torch.empty(B, dtype=torch.float32, device=dev),
+               target_logit=torch.empty(B, dtype=torch.float32, device=dev))
+    ws = _ws(knn_softmax_split_workspace(C, D, B, M), dev, ws)
+    dev_status = _status(dev, dev_status)
+    out["ws"], out["dev_status"] = ws, dev_status
+    rc = lib().knn_softmax_fwd_stats(_ptr(W_bf16), _ptr(X_bf16), _ptr(active_idx), _ptr(n_active), _ptr(target_pos),
+                                     ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(M), ct.c_float(scale),
+                                     ct.c_uint32(FLAG_UNIT_ROWS if unit_rows else 0), _ptr(out["row_max"]),
+                                     _ptr(out["row_sumexp"]), _ptr(out["target_logit"]), _ptr(ws), ct.c_size_t(ws.numel()),
+                                     _ptr(dev_status), _stream(stream))
+    _check("knn_softmax_fwd_stats", rc)
+    return out
+
+
+def knn_softmax_bwd_from_stats(W_bf16, X_bf16, active_idx, n_active, target_pos, global_max, global_sumexp,
+                               global_target_logit, scale, grad_scale, ws, unit_rows=False, dev_status=None, stream=None):
+    """Second call of the softmax split over nodes (`ws` is the first call's).  Returns dict(loss_per_sample,
+    loss_mean, dX (this node's contribution), dW_active, dev_status)."""
+    for t, name in ((global_max, "global_max"), (global_sumexp, "global_sumexp"), (global_target_logit, "global_target_logit")):
+        _need(t, torch.float32, name)
+    (C, D), B, M = W_bf16.shape, X_bf16.shape[0], active_idx.numel()
+    dev = W_bf16.device
+    out = dict(loss_per_sample=torch.empty(B, dtype=torch.float32, device=dev),
+               loss_mean=torch.empty(1, dtype=torch.float32, device=dev),
+               dX=torch.empty((B, D), dtype=torch.float32, device=dev),
+               dW_active=torch.empty((M, D), dtype=torch.float32, device=dev))
+    dev_status = _status(dev, dev_status)
+    out["dev_status"] = dev_status
+    rc = lib().knn_softmax_bwd_from_stats(_ptr(W_bf16), _ptr(X_bf16), _ptr(active_idx), _ptr(n_active), _ptr(target_pos),
+                                          _ptr(global_max), _ptr(global_sumexp), _ptr(global_target_logit), ct.c_int64(C),
+                                          ct.c_int(D), ct.c_int(B), ct.c_int(M), ct.c_float(scale), ct.c_float(grad_scale),
+                                          ct.c_uint32(FLAG_UNIT_ROWS if unit_rows else 0), _ptr(out["loss_per_sample"]),
+                                          _ptr(out["loss_mean"]), _ptr(out["dX"]), _ptr(out["dW_active"]), _ptr(ws),
+                                          ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
+    _check("knn_softmax_bwd_from_stats", rc)
+    return out

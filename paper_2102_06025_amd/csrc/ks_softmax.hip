@@ -780,12 +780,21 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
 // E_t - sum = -(sum of the others)) sums to zero and P_t - 1 carries no cancellation; the loss; the
 // reciprocal sum for dX; the scaled row of X2.
 #define SM_CF_NT 256
+// The softmax split over the nodes of the model-parallel layer (Section 3.1 steps 3-5) runs the same kernels in two
+// calls with an exchange of the per-sample statistics in between:
+#define SM_WHOLE 0  /* one GPU owns all classes: statistics and gradient in one go */
+#define SM_EXPORT 1 /* first call: this node's statistics go out, nothing is normalised yet */
+#define SM_IMPORT 2 /* second call: the statistics combined over all nodes come in */
+struct SmSplitIO {
+    float *row_max, *row_sum, *tz_out;    // SM_EXPORT
+    const float *gmax, *gsum, *gtz;       // SM_IMPORT
+};
 __global__ void __launch_bounds__(SM_CF_NT)
 sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict__ n_active_p,
                         const int32_t *__restrict__ active_idx, const int32_t *__restrict__ target_pos,
                         const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, int M, int slabs, int B, int Bp, int D,
                         float scale, float *__restrict__ inv_sum, float *__restrict__ loss_i, uint16_t *__restrict__ dZT,
-                        uint16_t *__restrict__ X2, int32_t *dev_status) {
+                        uint16_t *__restrict__ X2, int32_t *dev_status, int mode, SmSplitIO io) {
     __shared__ float sh[SM_CF_NT], sh_dot[SM_CF_NT];
     __shared__ float s_inv[32];
     const int n = sm_clamp_n(n_active_p, M);
@@ -795,15 +804,17 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
     const int j = threadIdx.x & 31, gq = threadIdx.x >> 5;
     const int i = blockIdx.x * 32 + j;
     int tp = 0;
+    bool owned = n > 0; // split over nodes: does this node hold the sample's class?  (one GPU: always)
     {
         float part = 0.f, dot = 0.f;
-        if (i < B) {
+        if (i < B && n > 0) {
             // all loads of a batch are issued before the first use: these are dependent only through the
             // running sums, and one round trip to another L2 costs as much as everything else here
             tp = target_pos[i];
+            if (mode != SM_WHOLE) owned = tp >= 0 && tp < n;
             tp = tp < 0 ? 0 : (tp >= n ? n - 1 : tp); // stays in bounds whatever the selection flagged
             const int cls = active_idx[tp];
-            for (int t0 = gq; t0 < nt; t0 += 64) {
+            for (int t0 = gq; mode != SM_IMPORT && t0 < nt; t0 += 64) {
                 float v[8];
 #pragma unroll
                 for (int q = 0; q < 8; ++q) v[q] = (t0 + 8 * q < nt) ? pl[(int64_t)(t0 + 8 * q) * Bp + i] : 0.f;
@@ -848,17 +859,37 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
             const float z_t = scale * dot;
             const float e_t = __expf(z_t - scale);
             uint16_t *cell = dZT + (int64_t)tp * Bp + i;
-            const float others = sum - ks_bf2f(*cell); // sum of the exponentials of the other classes
-            sum = others + e_t;
-            if (!(sum > 0.f) || !(sum < INFINITY)) ks_flag(dev_status, KS_DEV_RANGE);
-            loss_i[i] = (scale + __logf(sum)) - z_t;
-            inv = 1.f / sum;
-            inv_sum[i] = inv;
-            *cell = (uint16_t)ks_f2bf(-others); // the column now holds (P - onehot) * sum
+            if (mode == SM_IMPORT) {
+                // the sum over the classes of all nodes, brought to this kernel's reference `scale`
+                const float S = io.gsum[i] * __expf(io.gmax[i] - scale);
+                if (!(S > 0.f) || !(S < INFINITY)) ks_flag(dev_status, KS_DEV_RANGE);
+                loss_i[i] = (io.gmax[i] + __logf(io.gsum[i])) - io.gtz[i];
+                inv = 1.f / S;
+                inv_sum[i] = inv;
+                if (owned) *cell = (uint16_t)ks_f2bf(e_t - S); // (P_t - 1) * S
+            } else {
+                float others = sum;
+                if (owned) {
+                    others = sum - ks_bf2f(*cell); // sum of the exponentials of the other classes
+                    sum = others + e_t;
+                }
+                if (mode == SM_EXPORT) {
+                    io.row_max[i] = scale;
+                    io.row_sum[i] = sum;
+                    io.tz_out[i] = owned ? z_t : 0.f;
+                } else {
+                    if (!(sum > 0.f) || !(sum < INFINITY)) ks_flag(dev_status, KS_DEV_RANGE);
+                    loss_i[i] = (scale + __logf(sum)) - z_t;
+                    inv = 1.f / sum;
+                    inv_sum[i] = inv;
+                    *cell = (uint16_t)ks_f2bf(-others); // the column now holds (P - onehot) * sum
+                }
+            }
         }
         s_inv[j] = inv;
     }
     __syncthreads();
+    if (mode == SM_EXPORT) return; // nothing is normalised before the nodes have exchanged their sums
     const int rows = (B - blockIdx.x * 32 < 32) ? B - blockIdx.x * 32 : 32;
     const int per_row = D / 8; // 16-byte pieces per row
     const int total = rows * per_row;
@@ -1057,6 +1088,60 @@ full_prepare_kernel(const int32_t *__restrict__ labels, int64_t C, int B, int32_
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
+// two-sweep softmax, split over nodes: what goes out after the statistics sweep, what comes in before the
+// gradient sweep.  (lse_i, 1) is a valid (max, sum) pair: sum_a exp(z_ia - lse_i) = 1.
+__global__ void __launch_bounds__(SM_NT)
+sm_export_kernel(const float *__restrict__ lse, const float *__restrict__ zt, const int32_t *__restrict__ target_pos,
+                 const int32_t *__restrict__ n_active_p, int M, int B, SmSplitIO io) {
+    const int i = blockIdx.x * SM_NT + threadIdx.x;
+    if (i >= B) return;
+    const int n = sm_clamp_n(n_active_p, M);
+    const int tp = target_pos[i];
+    io.row_max[i] = n > 0 ? lse[i] : -INFINITY;
+    io.row_sum[i] = n > 0 ? 1.f : 0.f;
+    io.tz_out[i] = (tp >= 0 && tp < n) ? zt[i] : 0.f;
+}
+__global__ void __launch_bounds__(SM_NT)
+sm_import_kernel(SmSplitIO io, int B, float *__restrict__ lse, float *__restrict__ loss_i) {
+    const int i = blockIdx.x * SM_NT + threadIdx.x;
+    if (i >= B) return;
+    const float l = io.gmax[i] + __logf(io.gsum[i]);
+    lse[i] = l;
+    loss_i[i] = l - io.gtz[i];
+}
+// caller-supplied selection: ids outside [0, C) and positions outside the list are flagged and made harmless
+__global__ void __launch_bounds__(SM_NT)
+sm_sanitize_kernel(const int32_t *__restrict__ active_idx, const int32_t *__restrict__ n_active_p,
+                   const int32_t *__restrict__ target_pos, int64_t C, int M, int B, int32_t *__restrict__ act_safe,
+                   int32_t *__restrict__ n_safe, int32_t *__restrict__ tp_safe, int32_t *dev_status) {
+    const int t = blockIdx.x * SM_NT + threadIdx.x;
+    int n = *n_active_p;
+    if (n < 0 || n > M) {
+        if (t == 0) ks_flag(dev_status, KS_DEV_BAD_COUNT);
+        n = n < 0 ? 0 : M;
+    }
+    if (t == 0) *n_safe = n;
+    if (t < M) {
+        int32_t a = -1;
+        if (t < n) {
+            a = active_idx[t];
+            if (a < 0 || a >= C) {
+                ks_flag(dev_status, KS_DEV_BAD_INDEX);
+                a = 0;
+            }
+        }
+        act_safe[t] = a;
+    }
+    if (t < B) {
+        int32_t tp = target_pos[t];
+        if (tp >= n) {
+            ks_flag(dev_status, KS_DEV_BAD_LABEL);
+            tp = -1;
+        }
+        tp_safe[t] = tp < 0 ? -1 : tp;
+    }
+}
+
 struct SmWs {
     void *select;
     float *Z;
@@ -1123,8 +1208,11 @@ static SmWs sm_carve(void *ws, int64_t C, int D, int B, int K, int64_t M, bool w
 static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M, float scale, float grad_scale,
                   const int32_t *active_idx, const int32_t *n_active, const int32_t *target_pos,
                   float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, const SmWs &w,
-                  uint32_t flags, int32_t *dev_status, hipStream_t st, hipEvent_t *ev = nullptr) {
+                  uint32_t flags, int32_t *dev_status, hipStream_t st, hipEvent_t *ev = nullptr, int mode = SM_WHOLE,
+                  SmSplitIO io = SmSplitIO()) {
     auto mark = [&](int k) { if (ev) (void)hipEventRecord(ev[k], st); };
+    if (mode != SM_WHOLE && !w.fast) return KS_UNSUPPORTED;
+    if (mode == SM_EXPORT) loss_per_sample = w.inv; // not known before the exchange: the kernels' loss output is scratch
     const int Mi = (int)M;
     const float g = grad_scale / (float)B;
     bool fused = false;
@@ -1138,28 +1226,40 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
 #define SM_FUSED_LAUNCH(KT)                                                                                               \
     hipLaunchKernelGGL(sm_fused_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active, B, w.Bp, D, Mi,  \
                        tiles_s, scale, w.pl, w.dZT)
-            if (D == 512) SM_FUSED_LAUNCH(8);
-            else if (D == 256) SM_FUSED_LAUNCH(4);
-            else SM_FUSED_LAUNCH(2);
+            if (mode != SM_IMPORT) { // the first call of a split has left the exponentials in the workspace
+                if (D == 512) SM_FUSED_LAUNCH(8);
+                else if (D == 256) SM_FUSED_LAUNCH(4);
+                else SM_FUSED_LAUNCH(2);
+            }
 #undef SM_FUSED_LAUNCH
             mark(2);
             hipLaunchKernelGGL(sm_combine_fused_kernel, dim3((unsigned)ks_ceil_div(B, 32)), dim3(SM_CF_NT), 0, st, w.pl,
                                n_active, active_idx, target_pos, X, W, Mi, slabs, B, w.Bp, D, scale, w.inv, loss_per_sample,
-                               w.dZT, w.X2, dev_status);
+                               w.dZT, w.X2, dev_status, mode, io);
             mark(3);
+            if (mode == SM_EXPORT) {
+                KS_LAUNCH_CHECK();
+                return KS_OK;
+            }
         } else if (soe) {
             const int grid = SM_SOE_GRID / tiles_s * tiles_s, slabs = grid / tiles_s;
 #define SM_SOE_LAUNCH(KT)                                                                                                 \
     do {                                                                                                                  \
-        hipLaunchKernelGGL(sm_stats_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active, target_pos, \
-                           B, w.Bp, D, Mi, tiles_s, scale, w.pm, w.pl, w.zt);                                              \
-        mark(2);                                                                                                          \
-        hipLaunchKernelGGL(sm_combine_soe_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT / 64)), dim3(SM_NT), 0, st, w.pm,    \
-                           w.pl, w.zt, n_active, Mi, slabs, B, w.Bp, w.lse, loss_per_sample);                              \
-        mark(3);                                                                                                          \
-        hipLaunchKernelGGL(sm_grad_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active, target_pos,  \
-                           w.lse, B, w.Bp, D, Mi, tiles_s, scale, g, w.dZT);                                               \
+        if (mode != SM_IMPORT) {                                                                                          \
+            hipLaunchKernelGGL(sm_stats_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active,         \
+                               target_pos, B, w.Bp, D, Mi, tiles_s, scale, w.pm, w.pl, w.zt);                              \
+            mark(2);                                                                                                      \
+            hipLaunchKernelGGL(sm_combine_soe_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT / 64)), dim3(SM_NT), 0, st,     \
+                               w.pm, w.pl, w.zt, n_active, Mi, slabs, B, w.Bp, w.lse, loss_per_sample);                    \
+            mark(3);                                                                                                      \
+        }                                                                                                                 \
+        if (mode != SM_EXPORT)                                                                                            \
+            hipLaunchKernelGGL(sm_grad_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active,          \
+                               target_pos, w.lse, B, w.Bp, D, Mi, tiles_s, scale, g, w.dZT);                               \
     } while (0)
+            if (mode == SM_IMPORT)
+                hipLaunchKernelGGL(sm_import_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT)), dim3(SM_NT), 0, st, io, B, w.lse,
+                                   loss_per_sample);
             if (D == 512) SM_SOE_LAUNCH(8);
             else if (D == 256) SM_SOE_LAUNCH(4);
             else SM_SOE_LAUNCH(2);
@@ -1167,14 +1267,26 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
         } else {
             typedef TileSm T;
             const int tiles = (int)(ks_ceil_div(B, T::BN) * ks_ceil_div(M, T::BM));
-            hipLaunchKernelGGL(sm_stats_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, X, W, active_idx, n_active, target_pos, B,
-                               w.Bp, D, Mi, scale, w.pm, w.pl, w.zt);
-            mark(2);
-            hipLaunchKernelGGL(sm_combine_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT / 64)), dim3(SM_NT), 0, st, w.pm, w.pl,
-                               w.zt, n_active, Mi, T::BM, B, w.Bp, w.lse, loss_per_sample);
-            mark(3);
-            hipLaunchKernelGGL(sm_grad_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, X, W, active_idx, n_active, target_pos, w.lse,
-                               B, w.Bp, D, Mi, scale, g, w.dZT);
+            if (mode != SM_IMPORT) {
+                hipLaunchKernelGGL(sm_stats_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, X, W, active_idx, n_active, target_pos,
+                                   B, w.Bp, D, Mi, scale, w.pm, w.pl, w.zt);
+                mark(2);
+                hipLaunchKernelGGL(sm_combine_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT / 64)), dim3(SM_NT), 0, st, w.pm,
+                                   w.pl, w.zt, n_active, Mi, T::BM, B, w.Bp, w.lse, loss_per_sample);
+                mark(3);
+            } else {
+                hipLaunchKernelGGL(sm_import_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT)), dim3(SM_NT), 0, st, io, B, w.lse,
+                                   loss_per_sample);
+            }
+            if (mode != SM_EXPORT)
+                hipLaunchKernelGGL(sm_grad_kernel<T>, dim3(tiles), dim3(T::NT), 0, st, X, W, active_idx, n_active, target_pos,
+                                   w.lse, B, w.Bp, D, Mi, scale, g, w.dZT);
+        }
+        if (mode == SM_EXPORT) { // two-sweep paths: the statistics sweep is done, (lse, 1) and the target logit go out
+            hipLaunchKernelGGL(sm_export_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT)), dim3(SM_NT), 0, st, w.lse, w.zt,
+                               target_pos, n_active, Mi, B, io);
+            KS_LAUNCH_CHECK();
+            return KS_OK;
         }
         mark(4);
         {
@@ -1287,6 +1399,87 @@ extern "C" int knn_softmax_fwd_bwd_profiled(const uint16_t *W_bf16, const uint16
     return sm_fwd_bwd(W_bf16, X_bf16, labels, graph, C, D, B, K, M, scale, grad_scale, flags, active_idx, n_active,
                       target_pos, loss_per_sample, loss_mean, dX, dW_active, ws, ws_bytes, dev_status, stream,
                       (hipEvent_t *)events);
+}
+
+// The two calls of the softmax split over nodes.  Workspace: the softmax buffers (which carry the first call's
+// exponentials, or nothing on the two-sweep paths, to the second call), then the sanitised copy of the selection.
+struct SmSplitWs {
+    SmWs w;
+    int32_t *act, *n, *tp;
+};
+static SmSplitWs sm_split_carve(void *ws, int64_t C, int D, int B, int64_t M, size_t *total) {
+    size_t used = 0;
+    SmSplitWs s;
+    s.w = sm_carve(ws, C, D, B, 0, M, false, &used);
+    KsArena ar(ws ? (void *)((char *)ws + used) : nullptr);
+    s.act = ar.take<int32_t>((size_t)M);
+    s.tp = ar.take<int32_t>((size_t)B);
+    s.n = ar.take<int32_t>(1);
+    if (total) *total = used + ar.off;
+    return s;
+}
+static int sm_split_check(int64_t C, int D, int B, int M, float scale, uint32_t flags) {
+    if (sm_check_dims(C, D, B) != KS_OK || M < 1 || !(scale > 0.f)) return KS_INVALID_ARG;
+    if (flags & ~(uint32_t)KS_FLAG_UNIT_ROWS) return KS_INVALID_ARG;
+    if (D % 64 != 0) return KS_UNSUPPORTED;
+    return KS_OK;
+}
+
+extern "C" size_t knn_softmax_split_workspace(int64_t C, int D, int B, int M) {
+    if (sm_split_check(C, D, B, M, 1.f, 0) != KS_OK) return 0;
+    size_t total = 0;
+    sm_split_carve(nullptr, C, D, B, M, &total);
+    return total;
+}
+
+extern "C" int knn_softmax_fwd_stats(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *active_idx,
+                                     const int32_t *n_active, const int32_t *target_pos, int64_t C, int D, int B, int M,
+                                     float scale, uint32_t flags, float *row_max, float *row_sumexp, float *target_logit,
+                                     void *ws, size_t ws_bytes, int32_t *dev_status, void *stream) {
+    if (!W_bf16 || !X_bf16 || !active_idx || !n_active || !target_pos || !row_max || !row_sumexp || !target_logit || !ws)
+        return KS_INVALID_ARG;
+    int rc = sm_split_check(C, D, B, M, scale, flags);
+    if (rc != KS_OK) return rc;
+    size_t need = 0;
+    SmSplitWs s = sm_split_carve(ws, C, D, B, M, &need);
+    if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    const int nmax = M > B ? M : B;
+    hipLaunchKernelGGL(sm_sanitize_kernel, dim3((unsigned)ks_ceil_div(nmax, SM_NT)), dim3(SM_NT), 0, st, active_idx, n_active,
+                       target_pos, C, M, B, s.act, s.n, s.tp, dev_status);
+    SmSplitIO io = SmSplitIO();
+    io.row_max = row_max;
+    io.row_sum = row_sumexp;
+    io.tz_out = target_logit;
+    return sm_run(W_bf16, X_bf16, D, B, M, scale, 1.f, s.act, s.n, s.tp, nullptr, nullptr, nullptr, nullptr, s.w, flags,
+                  dev_status, st, nullptr, SM_EXPORT, io);
+}
+
+extern "C" int knn_softmax_bwd_from_stats(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *active_idx,
+                                          const int32_t *n_active, const int32_t *target_pos, const float *global_max,
+                                          const float *global_sumexp, const float *global_target_logit, int64_t C, int D,
+                                          int B, int M, float scale, float grad_scale, uint32_t flags,
+                                          float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, void *ws,
+                                          size_t ws_bytes, int32_t *dev_status, void *stream) {
+    if (!W_bf16 || !X_bf16 || !active_idx || !n_active || !target_pos || !global_max || !global_sumexp ||
+        !global_target_logit || !loss_per_sample || !loss_mean || !dX || !dW_active || !ws)
+        return KS_INVALID_ARG;
+    int rc = sm_split_check(C, D, B, M, scale, flags);
+    if (rc != KS_OK) return rc;
+    if (!(grad_scale > 0.f)) return KS_INVALID_ARG;
+    size_t need = 0;
+    SmSplitWs s = sm_split_carve(ws, C, D, B, M, &need);
+    if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    const int nmax = M > B ? M : B;
+    hipLaunchKernelGGL(sm_sanitize_kernel, dim3((unsigned)ks_ceil_div(nmax, SM_NT)), dim3(SM_NT), 0, st, active_idx, n_active,
+                       target_pos, C, M, B, s.act, s.n, s.tp, dev_status);
+    SmSplitIO io = SmSplitIO();
+    io.gmax = global_max;
+    io.gsum = global_sumexp;
+    io.gtz = global_target_logit;
+    return sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, s.act, s.n, s.tp, loss_per_sample, loss_mean, dX, dW_active,
+                  s.w, flags, dev_status, st, nullptr, SM_IMPORT, io);
 }
 
 extern "C" size_t full_softmax_workspace(int64_t C, int D, int B) {

@@ -23,7 +23,7 @@ def ks():
 def _declared_functions():
     src = open(HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update))\s*\(", src)))
+    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update|_stats))\s*\(", src)))
 
 
 def test_header_symbols_are_exported(ks):
@@ -127,6 +127,20 @@ def test_argument_errors_are_reported_before_any_launch(ks):
     assert upd(vo=(1 << 31) - 10) == ks.KS_INVALID_ARG    # ids must stay below 2^31
     assert upd(dtype=5) == ks.KS_INVALID_ARG
     assert upd(ws_bytes=64) == ks.KS_WORKSPACE_TOO_SMALL
+
+    def stats(D=128, B=8, M=64, scale=30.0, flags=0, ws_bytes=1 << 30, W=one):
+        return L.knn_softmax_fwd_stats(W, one, one, one, one, i64(1000), i(D), i(B), i(M), f(scale), ct.c_uint32(flags), one,
+                                       one, one, one, sz(ws_bytes), null, null)
+
+    assert stats(W=null) == ks.KS_INVALID_ARG
+    assert stats(D=96) == ks.KS_UNSUPPORTED            # the split runs on the D % 64 == 0 paths
+    assert stats(scale=0.0) == ks.KS_INVALID_ARG
+    assert stats(flags=2) == ks.KS_INVALID_ARG
+    assert stats(ws_bytes=64) == ks.KS_WORKSPACE_TOO_SMALL
+    assert L.knn_softmax_bwd_from_stats(one, one, one, one, one, one, one, null, i64(1000), i(128), i(8), i(64), f(30.0),
+                                        f(1.0), ct.c_uint32(0), one, one, one, one, one, sz(1 << 30), null,
+                                        null) == ks.KS_INVALID_ARG
+    assert ks.knn_softmax_split_workspace(1000, 128, 8, 64) > ks.knn_softmax_split_workspace(1000, 96, 8, 64) == 0
     assert L.knn_normalize_rows(one, i(0), i64(4), i(128), null, null, null) == ks.KS_INVALID_ARG   # no output
     assert L.knn_normalize_rows(one, i(3), i64(4), i(128), one, one, null) == ks.KS_INVALID_ARG     # dtype
     assert L.knn_normalize_rows(one, i(0), i64(4), i(6), one, one, null) == ks.KS_INVALID_ARG       # D % 4
