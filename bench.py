@@ -334,14 +334,53 @@ def main():
         o4 = ks.knn_select_active_csr(y4, counts, offsets, flat, c0, C, K, M, ws=s_ws, dev_status=st4)
         torch.cuda.synchronize()
         assert int(st4.item()) == 0
+        # the node's whole step with the softmax split over the nodes (Section 3.1 steps 3-5): selection with fill-up,
+        # statistics out, [exchange: here the node's own statistics times a constant stand in for the other nodes'],
+        # gradients from the combined statistics, weight update
+        sp_ws = torch.empty(ks.knn_softmax_split_workspace(C, D, B, M), dtype=torch.uint8, device="cuda")
+        ks.knn_normalize_rows(W_master, out_bf16=W_bf, out_inv_norm=inv_norm)
+
+        def node_step(pad):
+            sel = ks.knn_select_active_csr(y4, counts, offsets, flat, c0, C, K, M, pad_random=pad, pad_seed=7, ws=s_ws,
+                                           dev_status=st4)
+            s1 = ks.knn_softmax_fwd_stats(W_bf, X_bf, sel["active_idx"], sel["n_active"], sel["target_pos"], scale,
+                                          unit_rows=True, ws=sp_ws, dev_status=st4)
+            s1["row_sumexp"].mul_(4.0)      # "all-reduce": four nodes with equal sums (the reference is the same on all)
+            s2 = ks.knn_softmax_bwd_from_stats(W_bf, X_bf, sel["active_idx"], sel["n_active"], sel["target_pos"], s1["row_max"],
+                                               s1["row_sumexp"], s1["target_logit"], scale, grad_scale, sp_ws,
+                                               unit_rows=True, dev_status=st4)
+            ks.apply_weight_grad_normalized(W_master, W_bf, inv_norm, sel["active_idx"], sel["n_active"], s2["dW_active"],
+                                            alpha, idx_sorted_unique=True, ws=ws, dev_status=st4)
+            return sel
+
+        def wall(fn, reps):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / reps
+
+        ms_node = wall(lambda: node_step(False), args.steps)
+        ms_node_pad = wall(lambda: node_step(True), args.steps)
+        n_act4 = int(node_step(False)["n_active"].item())
+        torch.cuda.synchronize()
+        assert int(st4.item()) == 0
         bytes_c = Cg4 * K * 4.0 * 2 + flat.numel() * 4.0 + Cg4 * (4.0 * 2 + 8.0)
         sharded_node = dict(problem=f"Cg={Cg4} classes on 4 nodes, this node owns [{c0}, {c0 + C}); K={K}, global batch {B}",
                             compressed_entries=int(flat.numel()), classes_found=int(o4["n_found"].item()),
                             graph_compress=dict(us=round(us_compress, 1), bound="hbm",
                                                 gbs=round(bytes_c / (us_compress * 1e-6) / 1e9, 1),
                                                 frac=round(bytes_c / (us_compress * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)),
-                            select_csr_us=round(us_sel, 2), select_csr_with_fill_up_us=round(us_sel_pad, 2))
-        log(f"[bench] one node of four: compress {us_compress:.0f} us, select {us_sel:.1f} us, with fill-up {us_sel_pad:.1f} us")
+                            select_csr_us=round(us_sel, 2), select_csr_with_fill_up_us=round(us_sel_pad, 2),
+                            node_step=dict(what="select_csr + fwd_stats + exchange stand-in + bwd_from_stats + "
+                                                "apply_weight_grad_normalized, one-sweep softmax",
+                                           ms_per_step=round(ms_node, 4), active_classes=n_act4,
+                                           ms_per_step_filled_to_M=round(ms_node_pad, 4)))
+        log(f"[bench] one node of four: compress {us_compress:.0f} us, select {us_sel:.1f} us, with fill-up {us_sel_pad:.1f} us; "
+            f"node step {ms_node:.4f} ms (A={n_act4}), filled to M {ms_node_pad:.4f} ms")
         del G4
 
     # ---- CPU oracle on the same inputs: baseline + full-size parity of the first step -----------------------
