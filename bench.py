@@ -100,7 +100,7 @@ def oracle_graph_for_labels(orc, W, y, cfg):
     return G, rows, lists, dt
 
 
-def phase_model(cfg, A, unit_rows):
+def phase_model(cfg, A, unit_rows, fused_update=False):
     """Algorithmic flops / bytes per launch of each stage at A active classes."""
     B, D, K, C = cfg["B"], cfg["D"], cfg["K"], cfg["C"]
     gemm = 2.0 * B * A * D
@@ -115,7 +115,8 @@ def phase_model(cfg, A, unit_rows):
         "dx_gemm": dict(bound="mfma", flops=gemm),
         "dx_reduce": dict(bound="latency"),                  # nothing launched here: the reduction rides with dw_gemm
         "dw_gemm": dict(bound="mfma", flops=gemm),
-        "apply": dict(bound="hbm", bytes=A * D * (4.0 + 4.0 + 4.0 + 2.0)),
+        # the stand-alone update; nothing is launched here when the update runs inside the dW kernel
+        "apply": dict(bound="latency") if fused_update else dict(bound="hbm", bytes=A * D * (4.0 + 4.0 + 4.0 + 2.0)),
     }
 
 
@@ -127,6 +128,8 @@ def main():
     ap.add_argument("--workload", default="shard390k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
+    ap.add_argument("--separate-update", action="store_true",
+                    help="run the weight update as a call of its own (apply_weight_grad) instead of knn_softmax_fwd_bwd_update")
     ap.add_argument("--general-rows", action="store_true",
                     help="do not tell the library that the rows are L2-normalised (two-sweep softmax)")
     args = ap.parse_args()
@@ -175,6 +178,7 @@ def main():
     ws = torch.empty(ks.knn_softmax_workspace(C, D, B, K, M), dtype=torch.uint8, device="cuda")
     # the synthetic rows are L2-normalised, as the paper's are: the library may rely on it
     unit_rows = not args.general_rows
+    fused_update = not args.separate_update
     out = ks.knn_softmax_fwd_bwd(W_bf, X_bf, labels, graph, M, scale, grad_scale, ws=ws, unit_rows=unit_rows)
     torch.cuda.synchronize()
     A = int(out["n_active"].item())
@@ -183,28 +187,36 @@ def main():
     first = {k: out[k].clone() for k in ("active_idx", "target_pos", "loss_per_sample", "loss_mean", "dX")}
     first["dW_active"] = out["dW_active"][:A].clone()
 
+    out_fused = dict(out)
+    out_fused["dW_active"] = None      # the fused step does not store the gradient rows
     L = ks.lib()
     n_ev = 9
     evs = [hev.create(n_ev) for _ in range(args.steps)]
 
     def step(ev=None):
+        if ev is None and fused_update:
+            ks.knn_softmax_fwd_bwd_update(W_master, W_bf, X_bf, labels, graph, M, scale, grad_scale, alpha, out=out_fused,
+                                          ws=ws, unit_rows=unit_rows)
+            return
         if ev is None:
             ks.knn_softmax_fwd_bwd(W_bf, X_bf, labels, graph, M, scale, grad_scale, out=out, ws=ws,
                                    unit_rows=unit_rows)
         else:
             rc = L.knn_softmax_fwd_bwd_profiled(
-                ct.c_void_p(W_bf.data_ptr()), ct.c_void_p(X_bf.data_ptr()), ct.c_void_p(labels.data_ptr()),
+                ct.c_void_p(W_master.data_ptr() if fused_update else 0), ct.c_void_p(W_bf.data_ptr()),
+                ct.c_void_p(X_bf.data_ptr()), ct.c_void_p(labels.data_ptr()),
                 ct.c_void_p(graph.data_ptr()), ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(K), ct.c_int(M),
-                ct.c_float(scale), ct.c_float(grad_scale), ct.c_uint32(1 if unit_rows else 0),
+                ct.c_float(scale), ct.c_float(grad_scale), ct.c_float(alpha), ct.c_uint32(1 if unit_rows else 0),
                 ct.c_void_p(out["active_idx"].data_ptr()),
                 ct.c_void_p(out["n_active"].data_ptr()), ct.c_void_p(out["target_pos"].data_ptr()),
                 ct.c_void_p(out["loss_per_sample"].data_ptr()), ct.c_void_p(out["loss_mean"].data_ptr()),
-                ct.c_void_p(out["dX"].data_ptr()), ct.c_void_p(out["dW_active"].data_ptr()),
+                ct.c_void_p(out["dX"].data_ptr()), ct.c_void_p(0 if fused_update else out["dW_active"].data_ptr()),
                 ct.c_void_p(ws.data_ptr()), ct.c_size_t(ws.numel()), ct.c_void_p(out["dev_status"].data_ptr()),
                 ct.c_void_p(stream), ev, ct.c_int(8))
             assert rc == 0, rc
-        ks.apply_weight_grad(W_master, W_bf, out["active_idx"], out["n_active"], out["dW_active"], alpha,
-                             idx_sorted_unique=True, ws=ws, dev_status=out["dev_status"])
+        if not fused_update:
+            ks.apply_weight_grad(W_master, W_bf, out["active_idx"], out["n_active"], out["dW_active"], alpha,
+                                 idx_sorted_unique=True, ws=ws, dev_status=out["dev_status"])
         if ev is not None:
             hev.record(ev[8], stream)
 
@@ -236,7 +248,7 @@ def main():
             dur[p] += hev.elapsed_ms(ev[k], ev[k + 1])
     for p in PHASES:
         dur[p] = dur[p] / args.steps * 1e3  # microseconds
-    model = phase_model(cfg, A, unit_rows)
+    model = phase_model(cfg, A, unit_rows, fused_update)
     phases = {}
     for p in PHASES:
         m = model[p]
@@ -422,7 +434,8 @@ def main():
         "ms_per_step_with_stage_events": round(ms_per_step_instrumented, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: C={C} D={D} B={B} K={K} M={M} labels={cfg['labels']} s={scale}",
-                   "active_classes": A, "step": "select + knn_softmax_fwd_bwd + apply_weight_grad",
+                   "active_classes": A, "step": "knn_softmax_fwd_bwd_update (select + fwd/bwd + weight update in one call)" if fused_update
+                   else "select + knn_softmax_fwd_bwd + apply_weight_grad",
                    "unit_rows_flag": unit_rows},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

@@ -140,20 +140,33 @@ int knn_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const in
                         int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
                         float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
-/* Measurement aid: knn_softmax_fwd_bwd with one hipEvent_t recorded on `stream` at each stage boundary, so that
- * a caller can time the stages of a step without a profiler.  events[0..KS_N_PHASE_EVENTS) are created by the
- * caller (hipEventCreate); event k is recorded: 0 at entry, 1 after the selection, 2 after the first sweep
- * over the active rows (softmax statistics; with KS_FLAG_UNIT_ROWS the only sweep, which also writes the
- * exponentials), 3 after the per-sample combine and the loss mean, 4 after the second sweep (logit gradient;
- * nothing with KS_FLAG_UNIT_ROWS), 5 after the dX partial GEMM, 6 after the dX reduction, 7 after the dW
- * GEMM.  Same results as knn_softmax_fwd_bwd. */
+/* knn_softmax_fwd_bwd_update -- the whole step of the layer in one call: knn_softmax_fwd_bwd followed by the
+ * weight update of Section 3.1 step 6 (apply_weight_grad with idx = active_idx, idx_sorted_unique), with the
+ * same results bit for bit:
+ *     W_master[active_idx[a], :] += alpha * dW_active[a, :],   W_bf16[same rows] = bf16 of the new values.
+ * For D % 64 == 0 the update runs inside the kernel that produces dW_active, so the gradient does not travel
+ * through memory; dW_active may then be NULL (not stored).  Otherwise dW_active is required and the two steps
+ * run one after the other.  W_bf16 is read by the forward pass and updated at the end of the call. */
+int knn_softmax_fwd_bwd_update(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
+                               const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
+                               float grad_scale, float alpha, uint32_t flags, int32_t *active_idx, int32_t *n_active,
+                               int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
+                               float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
+
+/* Measurement aid: knn_softmax_fwd_bwd (W_master == NULL) or knn_softmax_fwd_bwd_update with one hipEvent_t
+ * recorded on `stream` at each stage boundary, so that a caller can time the stages of a step without a profiler.
+ * events[0..KS_N_PHASE_EVENTS) are created by the caller (hipEventCreate); event k is recorded: 0 at entry, 1
+ * after the selection, 2 after the first sweep over the active rows (softmax statistics; with KS_FLAG_UNIT_ROWS
+ * the only sweep, which also writes the exponentials), 3 after the per-sample combine and the loss mean, 4 after
+ * the second sweep (logit gradient; nothing with KS_FLAG_UNIT_ROWS), 5 after the dX partial GEMM, 6 after the dX
+ * reduction, 7 after the dW GEMM (and the update, if any).  Same results as the entry points it stands for. */
 #define KS_N_PHASE_EVENTS 8
-int knn_softmax_fwd_bwd_profiled(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
+int knn_softmax_fwd_bwd_profiled(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
                                  const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
-                                 float grad_scale, uint32_t flags, int32_t *active_idx, int32_t *n_active,
-                                 int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
-                                 float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream,
-                                 void **events, int n_events);
+                                 float grad_scale, float alpha, uint32_t flags, int32_t *active_idx,
+                                 int32_t *n_active, int32_t *target_pos, float *loss_per_sample, float *loss_mean,
+                                 float *dX, float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status,
+                                 void *stream, void **events, int n_events);
 
 /* ------------------------------------------------------------------------------------------------------
  * full_softmax_fwd_bwd -- the full-softmax layer the paper compares against (Section 3.2, Table 3): the

@@ -23,7 +23,8 @@ EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_se
            "knn_normalize_rows", "knn_norm_backward_rows", "apply_weight_grad_normalized_workspace",
            "apply_weight_grad_normalized", "knn_graph_compress_workspace", "knn_graph_compress",
            "knn_select_active_csr_workspace", "knn_select_active_csr", "knn_graph_update_workspace", "knn_graph_update",
-           "knn_softmax_split_workspace", "knn_softmax_fwd_stats", "knn_softmax_bwd_from_stats")
+           "knn_softmax_split_workspace", "knn_softmax_fwd_stats", "knn_softmax_bwd_from_stats",
+           "knn_softmax_fwd_bwd_update")
 
 
 class KsError(RuntimeError):
@@ -200,6 +201,45 @@ def knn_softmax_fwd_bwd(W_bf16, X_bf16, labels, graph, M, scale, grad_scale=1.0,
                                    _ptr(out["dW_active"]), _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status),
                                    _stream(stream))
     _check("knn_softmax_fwd_bwd", rc)
+    return out
+
+
+def knn_softmax_fwd_bwd_update(W_master, W_bf16, X_bf16, labels, graph, M, scale, grad_scale, alpha, out=None, ws=None,
+                               dev_status=None, stream=None, unit_rows=False, want_dW=False):
+    """The whole step in one call: forward+backward and the in-place update of W_master (fp32) and W_bf16.
+    Returns the dict of knn_softmax_fwd_bwd; dW_active is None unless want_dW (or D % 64 != 0, where it is needed)."""
+    _need(W_master, torch.float32, "W_master")
+    _need(W_bf16, torch.bfloat16, "W_bf16")
+    _need(X_bf16, torch.bfloat16, "X_bf16")
+    _need(labels, torch.int32, "labels")
+    C, D = W_bf16.shape
+    if tuple(W_master.shape) != (C, D):
+        raise ValueError("W_master and W_bf16 must have the same shape")
+    B = X_bf16.shape[0]
+    K = 0 if graph is None else graph.shape[1]
+    if graph is not None:
+        _need(graph, torch.int32, "graph")
+    dev = W_bf16.device
+    if out is None:
+        out = dict(active_idx=torch.empty(M, dtype=torch.int32, device=dev),
+                   n_active=torch.empty(1, dtype=torch.int32, device=dev),
+                   target_pos=torch.empty(B, dtype=torch.int32, device=dev),
+                   loss_per_sample=torch.empty(B, dtype=torch.float32, device=dev),
+                   loss_mean=torch.empty(1, dtype=torch.float32, device=dev),
+                   dX=torch.empty((B, D), dtype=torch.float32, device=dev),
+                   dW_active=torch.empty((M, D), dtype=torch.float32, device=dev) if (want_dW or D % 64) else None)
+    ws = _ws(knn_softmax_workspace(C, D, B, K, M), dev, ws)
+    dev_status = _status(dev, dev_status if dev_status is not None else out.get("dev_status"))
+    out["dev_status"] = dev_status
+    out["ws"] = ws
+    rc = lib().knn_softmax_fwd_bwd_update(_ptr(W_master), _ptr(W_bf16), _ptr(X_bf16), _ptr(labels), _ptr(graph),
+                                          ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(K), ct.c_int(M), ct.c_float(scale),
+                                          ct.c_float(grad_scale), ct.c_float(alpha),
+                                          ct.c_uint32(FLAG_UNIT_ROWS if unit_rows else 0), _ptr(out["active_idx"]),
+                                          _ptr(out["n_active"]), _ptr(out["target_pos"]), _ptr(out["loss_per_sample"]),
+                                          _ptr(out["loss_mean"]), _ptr(out["dX"]), _ptr(out.get("dW_active")), _ptr(ws),
+                                          ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
+    _check("knn_softmax_fwd_bwd_update", rc)
     return out
 
 

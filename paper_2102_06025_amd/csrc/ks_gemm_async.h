@@ -281,6 +281,38 @@ __device__ __forceinline__ void ks_a_foreach(const f32x16_t (&acc)[T::FM][T::FN]
             }
 }
 
+// Row-wise hand-out of the accumulator tile.  A lane of the MFMA result holds single elements of many rows, and a
+// vector-memory instruction that moves 4 bytes per lane keeps the address unit busy as long as one that moves 16:
+// element-wise stores run at a quarter of the rate of row-wise ones.  So the tile goes through LDS (free once the
+// main loop is done) in WAVES_M slabs of BM / WAVES_M rows: ks_a_stage_slab writes slab p (the wavefronts that own
+// it), and after a barrier every thread reads 16-byte pieces of whole rows with ks_a_slab_quad.  Columns are
+// XOR-swizzled by 32 on every other group of four rows (the two half-wavefronts of a store hit different banks).
+template <class T> struct KsASlab {
+    static constexpr int ROWS = T::WM, QUADS = T::BN / 4; // rows per slab, 16-byte pieces per row
+    static_assert(ROWS * T::BN * 4 <= T::LDS_ELEMS * 2, "a slab must fit into the stream stages");
+    static_assert(T::BN % 64 == 0, "swizzle");
+};
+template <class T>
+__device__ __forceinline__ void ks_a_stage_slab(const f32x16_t (&acc)[T::FM][T::FN], float *st, int p) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (wave / T::WAVES_N != p) return;
+    const int wn0 = (wave % T::WAVES_N) * T::WN;
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+        for (int fn = 0; fn < T::FN; ++fn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = fm * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r & 3);
+                const int col = (wn0 + fn * 32 + (lane & 31)) ^ (((row >> 2) & 1) << 5);
+                st[row * T::BN + col] = acc[fm][fn][r];
+            }
+}
+// elements (row, 4 * quad .. 4 * quad + 3) of the staged slab
+template <class T> __device__ __forceinline__ float4 ks_a_slab_quad(const float *st, int row, int quad) {
+    return *(const float4 *)(st + row * T::BN + ((quad * 4) ^ (((row >> 2) & 1) << 5)));
+}
+
 template <class T> __device__ __forceinline__ void ks_a_clear(f32x16_t (&acc)[T::FM][T::FN]) {
 #pragma unroll
     for (int fm = 0; fm < T::FM; ++fm)

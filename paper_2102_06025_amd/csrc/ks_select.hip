@@ -410,16 +410,25 @@ sel_single_kernel(const int32_t *__restrict__ cand, int64_t C, int B, int K, int
     // optimistic pass: every candidate, whatever its list position (sixteen loads in flight per thread: the
     // round trips to L2 are what this phase costs)
     const int64_t n_cand = (int64_t)B * (K + 1);
-    for (int64_t t0 = 0; t0 < n_cand; t0 += (int64_t)SEL1_NT * 16) {
-        int32_t c[16];
+    const int64_t n_vec = n_cand >> 2; // the staging array is 256-byte aligned: whole 16-byte pieces, then a tail
+    for (int64_t t0 = 0; t0 < n_vec; t0 += (int64_t)SEL1_NT * 8) {
+        int4 c[8];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
+        for (int e = 0; e < 8; ++e) {
             const int64_t t = t0 + (int64_t)e * SEL1_NT + tid;
-            c[e] = t < n_cand ? cand[t] : -1;
+            c[e] = t < n_vec ? ((const int4 *)cand)[t] : make_int4(-1, -1, -1, -1);
         }
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-            if (c[e] >= 0) atomicOr(&bm[c[e] >> 5], 1u << (c[e] & 31));
+        for (int e = 0; e < 8; ++e) {
+            if (c[e].x >= 0) atomicOr(&bm[c[e].x >> 5], 1u << (c[e].x & 31));
+            if (c[e].y >= 0) atomicOr(&bm[c[e].y >> 5], 1u << (c[e].y & 31));
+            if (c[e].z >= 0) atomicOr(&bm[c[e].z >> 5], 1u << (c[e].z & 31));
+            if (c[e].w >= 0) atomicOr(&bm[c[e].w >> 5], 1u << (c[e].w & 31));
+        }
+    }
+    for (int64_t t = n_vec * 4 + tid; t < n_cand; t += SEL1_NT) {
+        const int32_t c = cand[t];
+        if (c >= 0) atomicOr(&bm[c >> 5], 1u << (c & 31));
     }
     __syncthreads();
     int total = sel1_prefix(bm, nw, pre, sh);
@@ -543,6 +552,7 @@ template <class Src>
 static int sel_launch(const Src &src, int64_t C, int B, int K, int M, SelPad pad, int32_t *active_idx, int32_t *n_active,
                       int32_t *n_found, int32_t *target_pos, void *ws, int32_t *dev_status, hipStream_t st) {
     const int64_t n_cand = (int64_t)B * (K + 1);
+    if ((uintptr_t)ws & 15) return KS_INVALID_ARG; // the staging array is read in 16-byte pieces
     if (C <= (int64_t)SEL1_MAX_WORDS * 32) {
         int32_t *cand = (int32_t *)ws;
         hipLaunchKernelGGL(sel_fetch_kernel<Src>, dim3((unsigned)ks_ceil_div(n_cand, SEL_NT)), dim3(SEL_NT), 0, st, src, B, K,

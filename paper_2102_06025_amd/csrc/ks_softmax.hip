@@ -1001,11 +1001,21 @@ struct DxReduceJob {
     const float *loss_i;
     float *loss_mean;
 };
+// The weight update of Section 3.1 step 6 done where the gradient is produced: the tile that has just computed a
+// block of dW_active adds alpha times it to the fp32 rows of the active classes and refreshes their 16-bit copy,
+// so the gradient never travels to memory and back (same arithmetic as the stand-alone update: one fused
+// multiply-add per element on the stored fp32 value of the gradient).  Wm == nullptr: no update.
+struct DwUpdate {
+    float *Wm;
+    uint16_t *Wb;
+    const int32_t *idx;
+    float alpha;
+};
 template <class T>
 __global__ void __launch_bounds__(T::NT)
 dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X, int B, int Bp,
                 const int32_t *__restrict__ n_active_p, int D, int M, int64_t Mp, float scale, float *__restrict__ dW,
-                int tiles_max, DxReduceJob job) {
+                int tiles_max, DxReduceJob job, DwUpdate up) {
     __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
     if ((int)blockIdx.x >= tiles_max) { // reduction blocks
         const int rb = blockIdx.x - tiles_max, nrb = gridDim.x - tiles_max;
@@ -1045,10 +1055,52 @@ dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X
     f32x16_t acc[T::FM][T::FN];
     ks_a_clear<T>(acc);
     ks_a_mainloop<T, false, true>(ar, br, 0, Bp / 64, lds, acc);
-    ks_a_foreach<T>(acc, [&](int m, int n, float v) {
-        int a = tm * T::BM + m, d = tn * T::BN + n;
-        if (a < n_active && d < D) dW[(int64_t)a * D + d] = scale * v;
-    });
+    // epilogue, row-wise through LDS: gradient rows out (if wanted) and, if asked for, the update of the master
+    // rows and of their 16-bit copy.  Four rows per thread are in flight at a time.
+    typedef KsASlab<T> SL;
+    float *st = (float *)lds;
+    const int d_base = tn * T::BN;
+    for (int p = 0; p < T::WAVES_M; ++p) {
+        ks_a_stage_slab<T>(acc, st, p);
+        __syncthreads();
+        constexpr int PER = SL::ROWS * SL::QUADS / T::NT; // pieces per thread
+        static_assert(SL::ROWS * SL::QUADS % T::NT == 0 && PER % 4 == 0, "slab shape");
+        for (int q0 = 0; q0 < PER; q0 += 4) {
+            float4 g[4], w[4];
+            int64_t at[4];
+            int a_[4], d_[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = (q0 + u) * T::NT + threadIdx.x;
+                const int row = q / SL::QUADS, quad = q % SL::QUADS;
+                a_[u] = tm * T::BM + p * SL::ROWS + row;
+                d_[u] = d_base + quad * 4;
+                const float4 v = ks_a_slab_quad<T>(st, row, quad);
+                g[u] = make_float4(scale * v.x, scale * v.y, scale * v.z, scale * v.w);
+                at[u] = -1;
+                if (a_[u] < n_active && d_[u] < D) at[u] = up.Wm ? (int64_t)up.idx[a_[u]] * D + d_[u] : 0; // D % 4 == 0
+            }
+            if (up.Wm) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    w[u] = at[u] >= 0 ? *(const float4 *)(up.Wm + at[u]) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (at[u] < 0) continue;
+                if (dW) *(float4 *)(dW + (int64_t)a_[u] * D + d_[u]) = g[u];
+                if (up.Wm) {
+                    w[u].x = fmaf(up.alpha, g[u].x, w[u].x);
+                    w[u].y = fmaf(up.alpha, g[u].y, w[u].y);
+                    w[u].z = fmaf(up.alpha, g[u].z, w[u].z);
+                    w[u].w = fmaf(up.alpha, g[u].w, w[u].w);
+                    *(float4 *)(up.Wm + at[u]) = w[u];
+                    if (up.Wb) *(uint2 *)(up.Wb + at[u]) = make_uint2(ks_pack_bf2(w[u].x, w[u].y), ks_pack_bf2(w[u].z, w[u].w));
+                }
+            }
+        }
+        __syncthreads();
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1209,7 +1261,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
                   const int32_t *active_idx, const int32_t *n_active, const int32_t *target_pos,
                   float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, const SmWs &w,
                   uint32_t flags, int32_t *dev_status, hipStream_t st, hipEvent_t *ev = nullptr, int mode = SM_WHOLE,
-                  SmSplitIO io = SmSplitIO()) {
+                  SmSplitIO io = SmSplitIO(), DwUpdate up = DwUpdate()) {
     auto mark = [&](int k) { if (ev) (void)hipEventRecord(ev[k], st); };
     if (mode != SM_WHOLE && !w.fast) return KS_UNSUPPORTED;
     if (mode == SM_EXPORT) loss_per_sample = w.inv; // not known before the exchange: the kernels' loss output is scratch
@@ -1310,7 +1362,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
             job.loss_i = loss_per_sample;
             job.loss_mean = loss_mean;
             hipLaunchKernelGGL(dw_async_kernel<T>, dim3(tiles + DW_REDUCE_BLOCKS), dim3(T::NT), 0, st, w.dZT, fused ? w.X2 : X,
-                               B, w.Bp, n_active, D, Mi, w.Mp, fused ? scale * g : scale, dW_active, tiles, job);
+                               B, w.Bp, n_active, D, Mi, w.Mp, fused ? scale * g : scale, dW_active, tiles, job, up);
         }
         mark(7);
         KS_LAUNCH_CHECK();
@@ -1359,10 +1411,13 @@ static int sm_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int3
                       int64_t C, int D, int B, int K, int M, float scale, float grad_scale, uint32_t flags,
                       int32_t *active_idx, int32_t *n_active, int32_t *target_pos, float *loss_per_sample,
                       float *loss_mean, float *dX, float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status,
-                      void *stream, hipEvent_t *ev) {
+                      void *stream, hipEvent_t *ev, float *W_master = nullptr, uint16_t *W_bf16_out = nullptr,
+                      float alpha = 0.f) {
     if (!W_bf16 || !X_bf16 || !labels || !active_idx || !n_active || !target_pos || !loss_per_sample || !loss_mean ||
-        !dX || !dW_active || !ws)
+        !dX || !ws)
         return KS_INVALID_ARG;
+    const bool fast = D % 64 == 0; // the update runs inside the dW kernel of these paths; the others keep dW_active
+    if (!dW_active && !(W_master && fast)) return KS_INVALID_ARG;
     if (sm_check_dims(C, D, B) != KS_OK || K < 0 || M < 1) return KS_INVALID_ARG;
     if (K > 0 && !graph) return KS_INVALID_ARG;
     if (B > M || (int64_t)K + 1 > M) return KS_INVALID_ARG;
@@ -1374,8 +1429,19 @@ static int sm_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int3
     int rc = ks_select_launch(labels, graph, C, B, K, M, active_idx, n_active, target_pos, w.select, dev_status, st);
     if (rc != KS_OK) return rc;
     if (ev) (void)hipEventRecord(ev[1], st);
-    return sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, active_idx, n_active, target_pos, loss_per_sample,
-                  loss_mean, dX, dW_active, w, flags, dev_status, st, ev);
+    DwUpdate up = DwUpdate();
+    if (W_master && fast) {
+        up.Wm = W_master;
+        up.Wb = W_bf16_out;
+        up.idx = active_idx;
+        up.alpha = alpha;
+    }
+    rc = sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, active_idx, n_active, target_pos, loss_per_sample, loss_mean,
+                dX, dW_active, w, flags, dev_status, st, ev, SM_WHOLE, SmSplitIO(), up);
+    if (rc != KS_OK || !W_master || fast) return rc;
+    // other shapes: the stand-alone update on the stored gradient (active_idx is strictly ascending)
+    return apply_weight_grad(W_master, W_bf16_out, active_idx, n_active, M, dW_active, alpha, C, D, 1, ws, ws_bytes,
+                             dev_status, stream);
 }
 
 extern "C" int knn_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
@@ -1387,18 +1453,31 @@ extern "C" int knn_softmax_fwd_bwd(const uint16_t *W_bf16, const uint16_t *X_bf1
                       target_pos, loss_per_sample, loss_mean, dX, dW_active, ws, ws_bytes, dev_status, stream, nullptr);
 }
 
-extern "C" int knn_softmax_fwd_bwd_profiled(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
-                                            const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
-                                            float grad_scale, uint32_t flags, int32_t *active_idx, int32_t *n_active,
-                                            int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
-                                            float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status,
-                                            void *stream, void **events, int n_events) {
+extern "C" int knn_softmax_fwd_bwd_update(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *labels,
+                                          const int32_t *graph, int64_t C, int D, int B, int K, int M, float scale,
+                                          float grad_scale, float alpha, uint32_t flags, int32_t *active_idx,
+                                          int32_t *n_active, int32_t *target_pos, float *loss_per_sample, float *loss_mean,
+                                          float *dX, float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status,
+                                          void *stream) {
+    if (!W_master) return KS_INVALID_ARG;
+    return sm_fwd_bwd(W_bf16, X_bf16, labels, graph, C, D, B, K, M, scale, grad_scale, flags, active_idx, n_active,
+                      target_pos, loss_per_sample, loss_mean, dX, dW_active, ws, ws_bytes, dev_status, stream, nullptr,
+                      W_master, W_bf16, alpha);
+}
+
+extern "C" int knn_softmax_fwd_bwd_profiled(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16,
+                                            const int32_t *labels, const int32_t *graph, int64_t C, int D, int B, int K,
+                                            int M, float scale, float grad_scale, float alpha, uint32_t flags,
+                                            int32_t *active_idx, int32_t *n_active, int32_t *target_pos,
+                                            float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, void *ws,
+                                            size_t ws_bytes, int32_t *dev_status, void *stream, void **events,
+                                            int n_events) {
     if (!events || n_events < KS_N_PHASE_EVENTS) return KS_INVALID_ARG;
     for (int k = 0; k < KS_N_PHASE_EVENTS; ++k)
         if (!events[k]) return KS_INVALID_ARG;
     return sm_fwd_bwd(W_bf16, X_bf16, labels, graph, C, D, B, K, M, scale, grad_scale, flags, active_idx, n_active,
                       target_pos, loss_per_sample, loss_mean, dX, dW_active, ws, ws_bytes, dev_status, stream,
-                      (hipEvent_t *)events);
+                      (hipEvent_t *)events, W_master, W_bf16, alpha);
 }
 
 // The two calls of the softmax split over nodes.  Workspace: the softmax buffers (which carry the first call's

@@ -23,7 +23,7 @@ def ks():
 def _declared_functions():
     src = open(HEADER).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update|_stats))\s*\(", src)))
+    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update|_stats|_profiled))\s*\(", src)))
 
 
 def test_header_symbols_are_exported(ks):
@@ -75,6 +75,14 @@ def test_argument_errors_are_reported_before_any_launch(ks):
     assert fwd(K=64) == ks.KS_INVALID_ARG             # K + 1 > M
     assert fwd(C=0) == ks.KS_INVALID_ARG
     assert fwd(ws_bytes=1024) == ks.KS_WORKSPACE_TOO_SMALL
+
+    def upd_step(Wm=one, dW=null, D=128):
+        return L.knn_softmax_fwd_bwd_update(Wm, one, one, one, one, i64(1000), i(D), i(8), i(4), i(64), f(30.0), f(1.0),
+                                            f(-0.01), ct.c_uint32(0), one, one, one, one, one, one, dW, one, sz(1 << 30),
+                                            null, null)
+
+    assert upd_step(Wm=null) == ks.KS_INVALID_ARG
+    assert upd_step(D=96) == ks.KS_INVALID_ARG        # the gradient has to be stored on the paths without the fused update
 
     def graph(C=1000, D=128, K=8, dtype=0, ws_bytes=1 << 40):
         return L.knn_graph_build(one, i(dtype), i64(C), i(D), i(K), one, null, one, sz(ws_bytes), null, null)

@@ -122,6 +122,16 @@ def test_step_full_size(ks, orc, shard, name, unit_rows):
     # masters round the same way
     assert (got_bf == synth.bf16_bits(got)).all()
     assert np.mean(got_bf == W_ref_bf[active[:A]]) > 0.999
+    # the whole step in one call (update inside the dW kernel) gives the same bits
+    W_master2 = torch.from_numpy(W).cuda()
+    W_copy2 = W_bf.clone()
+    out2 = ks.knn_softmax_fwd_bwd_update(W_master2, W_copy2, X_bf, torch.from_numpy(y).cuda(), graph, M, scale, grad_scale,
+                                         alpha, unit_rows=unit_rows)
+    torch.cuda.synchronize()
+    assert int(out2["dev_status"].item()) == 0 and out2["dW_active"] is None
+    assert torch.equal(out2["dX"], out["dX"]) and torch.equal(out2["loss_mean"], out["loss_mean"])
+    assert torch.equal(W_master2, W_master) and torch.equal(W_copy2, W_copy)
+    del W_master2, W_copy2, out2
     rng = np.random.default_rng(9)
     untouched = np.setdiff1d(rng.integers(0, C, 4096), active[:A])
     ui = torch.from_numpy(untouched.astype(np.int64)).cuda()

@@ -388,3 +388,64 @@ def test_gather_rows(ks, orc):
     out = ks.knn_gather_rows(dev(W, torch.bfloat16), dev(idx), dev(np.array([600], dtype=np.int32)))
     torch.cuda.synchronize()
     assert (out[:600].float().cpu().numpy() == W[idx[:600]]).all()
+
+
+# ------------------------------------------------------------------------------------------------
+# the whole step in one call (update inside the dW kernel)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,unit_rows,want_dW", [("small", True, False), ("small", False, True), ("tiny", False, False)])
+def test_one_call_step_equals_forward_backward_then_update(ks, orc, name, unit_rows, want_dW):
+    """Bit for bit: master weights, 16-bit copy, dX, loss -- the fused update does the same fused multiply-add on the
+    same fp32 gradient value.  `tiny` has D = 128 in fp32 inputs rounded to bf16 (stationary-operand path too)."""
+    cfg = synth.CONFIGS[name]
+    C, D, B, K, M, scale = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"], cfg["scale"]
+    W, X = synth.make_WX(cfg)
+    W = synth.bf16_round(W)
+    y = synth.make_labels(cfg)
+    G = synth.graph_synthetic(cfg["seed"], C, K)
+    gs, alpha = 128.0, -0.05 / 128.0
+    Wb, Xb, yd, Gd = dev(W, torch.bfloat16), dev(synth.bf16_round(X), torch.bfloat16), dev(y), dev(G)
+    # two calls
+    Wm1, Wb1 = dev(W), Wb.clone()
+    a = ks.knn_softmax_fwd_bwd(Wb1, Xb, yd, Gd, M, scale, gs, unit_rows=unit_rows)
+    ks.apply_weight_grad(Wm1, Wb1, a["active_idx"], a["n_active"], a["dW_active"], alpha, idx_sorted_unique=True)
+    # one call
+    Wm2, Wb2 = dev(W), Wb.clone()
+    b = ks.knn_softmax_fwd_bwd_update(Wm2, Wb2, Xb, yd, Gd, M, scale, gs, alpha, unit_rows=unit_rows, want_dW=want_dW)
+    torch.cuda.synchronize()
+    assert int(a["dev_status"].item()) == 0 and int(b["dev_status"].item()) == 0
+    assert torch.equal(a["active_idx"], b["active_idx"]) and torch.equal(a["target_pos"], b["target_pos"])
+    assert torch.equal(a["loss_per_sample"], b["loss_per_sample"]) and torch.equal(a["dX"], b["dX"])
+    assert torch.equal(Wm1, Wm2) and torch.equal(Wb1, Wb2)
+    A = int(a["n_active"].item())
+    assert not torch.equal(Wm2, dev(W))                           # something was updated
+    if want_dW:
+        assert torch.equal(a["dW_active"][:A], b["dW_active"][:A])
+    else:
+        assert b["dW_active"] is None
+    # and against the oracle: the change of the touched rows
+    active = a["active_idx"][:A].cpu().numpy()
+    tpos = a["target_pos"].cpu().numpy()
+    ref = orc.knn_softmax_fwd_bwd(W, synth.bf16_round(X), active, tpos, scale, gs)
+    eW, _ = orc.apply_weight_grad(W, active, ref["dWA"].astype(np.float32), alpha, want_bf16=False)
+    got = Wm2[torch.from_numpy(active.astype(np.int64)).cuda()].cpu().numpy().astype(np.float64)
+    assert rel_fro(got - W[active], eW[active].astype(np.float64) - W[active]) <= GRAD_RTOL
+    rest = np.setdiff1d(np.arange(C), active)
+    assert (Wm2.cpu().numpy()[rest] == W[rest]).all()
+
+
+def test_one_call_step_on_a_shape_without_the_fused_update(ks, orc):
+    """D = 96: the gradient is stored and the stand-alone update runs inside the same call."""
+    C, D, B, K, M, scale = 3000, 96, 64, 8, 512, 20.0
+    W = synth.unit_rows(6, synth.TID_W, C, D, bf16=True)
+    X = synth.unit_rows(6, synth.TID_X, B, D, bf16=True)
+    y = synth.labels_uniform(6, B, C)
+    G = synth.graph_synthetic(6, C, K)
+    Wb, Xb, yd, Gd = dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(G)
+    Wm1, Wb1 = dev(W), Wb.clone()
+    a = ks.knn_softmax_fwd_bwd(Wb1, Xb, yd, Gd, M, scale, 1.0)
+    ks.apply_weight_grad(Wm1, Wb1, a["active_idx"], a["n_active"], a["dW_active"], -0.1, idx_sorted_unique=True)
+    Wm2, Wb2 = dev(W), Wb.clone()
+    b = ks.knn_softmax_fwd_bwd_update(Wm2, Wb2, Xb, yd, Gd, M, scale, 1.0, -0.1)
+    torch.cuda.synchronize()
+    assert b["dW_active"] is not None and torch.equal(Wm1, Wm2) and torch.equal(Wb1, Wb2) and torch.equal(a["dX"], b["dX"])
