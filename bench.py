@@ -34,9 +34,10 @@ PHASES = ["select", "logits_gemm", "row_stats", "logit_grad", "dx_gemm", "dx_red
 # 1.0, the factors a copy of known size gives), copied from profiles/bench_shard390k_hbm_traffic.txt
 # (unit-rows mode: one softmax sweep; the dW launch also carries the reduction of the dX partial sums)
 MEASURED_TRAFFIC = {
-    ("shard390k", "logits_gemm"): 62.72e6,
-    ("shard390k", "dx_gemm"): 87.41e6,
-    ("shard390k", "dw_gemm"): 117.78e6,
+    ("shard390k", "logits_gemm"): 62.74e6,
+    ("shard390k", "dx_gemm"): 87.42e6,
+    ("shard390k", "dw_gemm"): 171.45e6,          # with the weight update inside the kernel (the default step)
+    ("shard390k", "dw_gemm_separate"): 117.78e6,  # --separate-update
     ("shard390k", "apply"): 125.50e6,
 }
 
@@ -128,6 +129,8 @@ def main():
     ap.add_argument("--workload", default="shard390k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="only the headline step (no normalised-layer and sharded-node measurements): used for the profiles")
     ap.add_argument("--separate-update", action="store_true",
                     help="run the weight update as a call of its own (apply_weight_grad) instead of knn_softmax_fwd_bwd_update")
     ap.add_argument("--general-rows", action="store_true",
@@ -262,58 +265,71 @@ def main():
         phases[p] = e
     log("[bench] stage times (us): " + ", ".join(f"{p}={phases[p]['us']}" for p in PHASES))
     dom = max((p for p in PHASES if model[p]["bound"] in ("mfma", "hbm")), key=lambda p: dur[p])
-    traffic = MEASURED_TRAFFIC.get((args.workload, dom)) if unit_rows else None  # measured in unit-rows mode only
+    key = "dw_gemm_separate" if (dom == "dw_gemm" and not fused_update) else dom
+    traffic = MEASURED_TRAFFIC.get((args.workload, key)) if unit_rows else None  # measured in unit-rows mode only
     if model[dom]["bound"] == "mfma":
         roofline = dict(bound="mfma", achieved=phases[dom]["tflops"], peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                         frac=phases[dom]["frac"], traffic=traffic, kernel=dom)
+        if dom == "dw_gemm" and fused_update:
+            # this launch is two things: the dW contraction (the flops counted above) and the weight update of the
+            # active rows in its epilogue, which is HBM work; both against their own peaks, one after the other
+            upd_bytes = A * D * (4.0 + 4.0 + 2.0)
+            t_roof = model[dom]["flops"] / (PEAK_BF16_TFLOPS * 1e12) + upd_bytes / (PEAK_HBM_GBS * 1e9)
+            roofline.update(kernel="dw_gemm + weight update (one launch)", update_bytes=upd_bytes,
+                            frac_of_two_phase_roofline=round(t_roof / (dur[dom] * 1e-6), 4),
+                            runner_up=dict(kernel="logits_gemm", bound="mfma", achieved=phases["logits_gemm"]["tflops"],
+                                           frac=phases["logits_gemm"]["frac"], us=phases["logits_gemm"]["us"],
+                                           traffic=MEASURED_TRAFFIC.get((args.workload, "logits_gemm")) if unit_rows else None))
     else:
         roofline = dict(bound="hbm", achieved=phases[dom]["gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
                         frac=phases[dom]["frac"], traffic=traffic, kernel=dom)
 
-    # ---- the layer with un-normalised fp32 weights (normalisation inside the layer, Section 3.2.1): the same step
-    # with X normalised on the way in, dX projected on the way out and the weight update through the
-    # normalisation; timed after the headline region, reported beside it
-    inv_norm = torch.empty(C, dtype=torch.float32, device="cuda")
-    ks.knn_normalize_rows(W_master, out_bf16=W_bf, out_inv_norm=inv_norm)
-    X_raw = torch.from_numpy(X).cuda()
-    dX_raw = torch.empty_like(out["dX"])
-
-    def step_normalized():
-        ks.knn_normalize_rows(X_raw, want_inv_norm=False, out_bf16=X_bf)
-        ks.knn_softmax_fwd_bwd(W_bf, X_bf, labels, graph, M, scale, grad_scale, out=out, ws=ws, unit_rows=True)
-        ks.knn_norm_backward_rows(X_raw, out["dX"], out=dX_raw)
-        ks.apply_weight_grad_normalized(W_master, W_bf, inv_norm, out["active_idx"], out["n_active"], out["dW_active"],
-                                        alpha, idx_sorted_unique=True, ws=ws, dev_status=out["dev_status"])
-
-    for _ in range(args.warmup):
-        step_normalized()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        step_normalized()
-    torch.cuda.synchronize()
-    ms_norm_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    normalized_layer = None
     nev = hev.create(2)
-    hev.record(nev[0], stream)
-    for s in range(args.steps):
-        ks.apply_weight_grad_normalized(W_master, W_bf, inv_norm, out["active_idx"], out["n_active"], out["dW_active"],
-                                        alpha, idx_sorted_unique=True, ws=ws, dev_status=out["dev_status"])
-    hev.record(nev[1], stream)
-    torch.cuda.synchronize()
-    us_apply_n = hev.elapsed_ms(nev[0], nev[1]) * 1e3 / args.steps
-    assert int(out["dev_status"].item()) == 0
-    bytes_apply_n = A * (D * (4.0 + 4.0 + 4.0 + 2.0) + 4.0)
-    normalized_layer = dict(ms_per_step=round(ms_norm_step, 4), samples_per_s=round(B / (ms_norm_step * 1e-3), 1),
-                            step="normalize X + select + knn_softmax_fwd_bwd + project dX + apply_weight_grad_normalized",
-                            apply_normalized=dict(us=round(us_apply_n, 2), bound="hbm",
-                                                  gbs=round(bytes_apply_n / (us_apply_n * 1e-6) / 1e9, 1),
-                                                  frac=round(bytes_apply_n / (us_apply_n * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)))
-    log(f"[bench] layer with normalisation inside: {ms_norm_step:.4f} ms/step, apply_normalized {us_apply_n:.1f} us")
+    if not args.headline_only:
+        # ---- the layer with un-normalised fp32 weights (normalisation inside the layer, Section 3.2.1): the same step
+        # with X normalised on the way in, dX projected on the way out and the weight update through the
+        # normalisation; timed after the headline region, reported beside it
+        inv_norm = torch.empty(C, dtype=torch.float32, device="cuda")
+        ks.knn_normalize_rows(W_master, out_bf16=W_bf, out_inv_norm=inv_norm)
+        X_raw = torch.from_numpy(X).cuda()
+        dX_raw = torch.empty_like(out["dX"])
+
+        def step_normalized():
+            ks.knn_normalize_rows(X_raw, want_inv_norm=False, out_bf16=X_bf)
+            ks.knn_softmax_fwd_bwd(W_bf, X_bf, labels, graph, M, scale, grad_scale, out=out, ws=ws, unit_rows=True)
+            ks.knn_norm_backward_rows(X_raw, out["dX"], out=dX_raw)
+            ks.apply_weight_grad_normalized(W_master, W_bf, inv_norm, out["active_idx"], out["n_active"], out["dW_active"],
+                                            alpha, idx_sorted_unique=True, ws=ws, dev_status=out["dev_status"])
+
+        for _ in range(args.warmup):
+            step_normalized()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            step_normalized()
+        torch.cuda.synchronize()
+        ms_norm_step = (time.perf_counter() - t0) * 1e3 / args.steps
+        hev.record(nev[0], stream)
+        for s in range(args.steps):
+            ks.apply_weight_grad_normalized(W_master, W_bf, inv_norm, out["active_idx"], out["n_active"], out["dW_active"],
+                                            alpha, idx_sorted_unique=True, ws=ws, dev_status=out["dev_status"])
+        hev.record(nev[1], stream)
+        torch.cuda.synchronize()
+        us_apply_n = hev.elapsed_ms(nev[0], nev[1]) * 1e3 / args.steps
+        assert int(out["dev_status"].item()) == 0
+        bytes_apply_n = A * (D * (4.0 + 4.0 + 4.0 + 2.0) + 4.0)
+        normalized_layer = dict(ms_per_step=round(ms_norm_step, 4), samples_per_s=round(B / (ms_norm_step * 1e-3), 1),
+                                step="normalize X + select + knn_softmax_fwd_bwd + project dX + apply_weight_grad_normalized",
+                                apply_normalized=dict(us=round(us_apply_n, 2), bound="hbm",
+                                                      gbs=round(bytes_apply_n / (us_apply_n * 1e-6) / 1e9, 1),
+                                                      frac=round(bytes_apply_n / (us_apply_n * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)))
+        log(f"[bench] layer with normalisation inside: {ms_norm_step:.4f} ms/step, apply_normalized {us_apply_n:.1f} us")
 
     # ---- this GPU as one node of four (Section 3.2.3): graph compression and selection on the compressed graph,
     # with and without the random fill-up to M (Algorithm 1); integer work, bit-exact against the oracle in the tests
     sharded_node = None
-    if args.workload == "shard390k":
+    if args.workload == "shard390k" and not args.headline_only:
         Cg4, c0 = 4 * C, C
         cc = np.arange(Cg4, dtype=np.int64)[:, None]
         kk = np.arange(K, dtype=np.int64)[None, :]
