@@ -780,6 +780,9 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
 // E_t - sum = -(sum of the others)) sums to zero and P_t - 1 carries no cancellation; the loss; the
 // reciprocal sum for dX; the scaled row of X2.
 #define SM_CF_NT 256
+#ifndef SM_CF_SPB
+#define SM_CF_SPB 8 /* samples per workgroup of the combine kernel */
+#endif
 // The softmax split over the nodes of the model-parallel layer (Section 3.1 steps 3-5) runs the same kernels in two
 // calls with an exchange of the per-sample statistics in between:
 #define SM_WHOLE 0  /* one GPU owns all classes: statistics and gradient in one go */
@@ -795,14 +798,17 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
                         const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, int M, int slabs, int B, int Bp, int D,
                         float scale, float *__restrict__ inv_sum, float *__restrict__ loss_i, uint16_t *__restrict__ dZT,
                         uint16_t *__restrict__ X2, int32_t *dev_status, int mode, SmSplitIO io) {
+    // SM_CF_SPB samples per workgroup, SM_CF_PARTS threads per sample (each takes a share of the slab sums and of
+    // the dot product): the kernel is a chain of dependent round trips, so it is spread over many compute units
+    constexpr int SPB = SM_CF_SPB, PARTS = SM_CF_NT / SPB;
     __shared__ float sh[SM_CF_NT], sh_dot[SM_CF_NT];
-    __shared__ float s_inv[32];
+    __shared__ float s_inv[SPB];
     const int n = sm_clamp_n(n_active_p, M);
     const int n64 = (n + 63) & ~63;
     const int h = sm_slab_rows(n64, slabs);
     const int nt = (n64 + h - 1) / h; // slabs that hold rows
-    const int j = threadIdx.x & 31, gq = threadIdx.x >> 5;
-    const int i = blockIdx.x * 32 + j;
+    const int j = threadIdx.x % SPB, gq = threadIdx.x / SPB;
+    const int i = blockIdx.x * SPB + j;
     int tp = 0;
     bool owned = n > 0; // split over nodes: does this node hold the sample's class?  (one GPU: always)
     {
@@ -814,33 +820,33 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
             if (mode != SM_WHOLE) owned = tp >= 0 && tp < n;
             tp = tp < 0 ? 0 : (tp >= n ? n - 1 : tp); // stays in bounds whatever the selection flagged
             const int cls = active_idx[tp];
-            for (int t0 = gq; mode != SM_IMPORT && t0 < nt; t0 += 64) {
-                float v[8];
+            for (int t0 = gq; mode != SM_IMPORT && t0 < nt; t0 += 4 * PARTS) {
+                float v[4];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) v[q] = (t0 + 8 * q < nt) ? pl[(int64_t)(t0 + 8 * q) * Bp + i] : 0.f;
+                for (int q = 0; q < 4; ++q) v[q] = (t0 + PARTS * q < nt) ? pl[(int64_t)(t0 + PARTS * q) * Bp + i] : 0.f;
 #pragma unroll
-                for (int q = 0; q < 8; ++q) part += v[q];
+                for (int q = 0; q < 4; ++q) part += v[q];
             }
-            const uint16_t *xr = X + (int64_t)i * D + gq * (D / 8);
-            const uint16_t *wr = W + (int64_t)cls * D + gq * (D / 8);
-            const int pieces = D / 64; // 16-byte pieces per thread; D is 128, 256 or 512 on this path
-            uint4 xv[8], wv[8];
+            // this thread's share of the dot product: D / PARTS elements, in 8-byte pieces (D is 128, 256 or 512)
+            const int per = D / PARTS;
+            const uint16_t *xr = X + (int64_t)i * D + gq * per;
+            const uint16_t *wr = W + (int64_t)cls * D + gq * per;
+            constexpr int MAXP = 512 / PARTS / 4;
+            uint2 xv[MAXP], wv[MAXP];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                if (q < pieces) {
-                    xv[q] = *(const uint4 *)(xr + q * 8);
-                    wv[q] = *(const uint4 *)(wr + q * 8);
+            for (int q = 0; q < MAXP; ++q) {
+                if (q * 4 < per) {
+                    xv[q] = *(const uint2 *)(xr + q * 4);
+                    wv[q] = *(const uint2 *)(wr + q * 4);
                 }
             }
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                if (q < pieces) {
-                    const uint32_t xa[4] = {xv[q].x, xv[q].y, xv[q].z, xv[q].w}, wa[4] = {wv[q].x, wv[q].y, wv[q].z, wv[q].w};
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        dot = fmaf(ks_bf2f(xa[c] & 0xFFFFu), ks_bf2f(wa[c] & 0xFFFFu), dot);
-                        dot = fmaf(ks_bf2f(xa[c] >> 16), ks_bf2f(wa[c] >> 16), dot);
-                    }
+            for (int q = 0; q < MAXP; ++q) {
+                if (q * 4 < per) {
+                    dot = fmaf(ks_bf2f(xv[q].x & 0xFFFFu), ks_bf2f(wv[q].x & 0xFFFFu), dot);
+                    dot = fmaf(ks_bf2f(xv[q].x >> 16), ks_bf2f(wv[q].x >> 16), dot);
+                    dot = fmaf(ks_bf2f(xv[q].y & 0xFFFFu), ks_bf2f(wv[q].y & 0xFFFFu), dot);
+                    dot = fmaf(ks_bf2f(xv[q].y >> 16), ks_bf2f(wv[q].y >> 16), dot);
                 }
             }
         }
@@ -848,13 +854,13 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
         sh_dot[threadIdx.x] = dot;
     }
     __syncthreads();
-    if (threadIdx.x < 32) {
+    if (threadIdx.x < SPB) {
         float inv = 0.f;
         if (i < B) {
             float sum = 0.f, dot = 0.f;
-            for (int q = 0; q < 8; ++q) {
-                sum += sh[q * 32 + j];
-                dot += sh_dot[q * 32 + j];
+            for (int q = 0; q < PARTS; ++q) { // a fixed order
+                sum += sh[q * SPB + j];
+                dot += sh_dot[q * SPB + j];
             }
             const float z_t = scale * dot;
             const float e_t = __expf(z_t - scale);
@@ -890,11 +896,11 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
     }
     __syncthreads();
     if (mode == SM_EXPORT) return; // nothing is normalised before the nodes have exchanged their sums
-    const int rows = (B - blockIdx.x * 32 < 32) ? B - blockIdx.x * 32 : 32;
+    const int rows = (B - blockIdx.x * SPB < SPB) ? B - blockIdx.x * SPB : SPB;
     const int per_row = D / 8; // 16-byte pieces per row
     const int total = rows * per_row;
-    const uint16_t *xb = X + (int64_t)blockIdx.x * 32 * D; // the block's rows are contiguous
-    uint16_t *ob = X2 + (int64_t)blockIdx.x * 32 * D;
+    const uint16_t *xb = X + (int64_t)blockIdx.x * SPB * D; // the block's rows are contiguous
+    uint16_t *ob = X2 + (int64_t)blockIdx.x * SPB * D;
     for (int q0 = threadIdx.x; q0 < total; q0 += 4 * SM_CF_NT) {
         uint4 v[4];
 #pragma unroll
@@ -1285,7 +1291,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
             }
 #undef SM_FUSED_LAUNCH
             mark(2);
-            hipLaunchKernelGGL(sm_combine_fused_kernel, dim3((unsigned)ks_ceil_div(B, 32)), dim3(SM_CF_NT), 0, st, w.pl,
+            hipLaunchKernelGGL(sm_combine_fused_kernel, dim3((unsigned)ks_ceil_div(B, SM_CF_SPB)), dim3(SM_CF_NT), 0, st, w.pl,
                                n_active, active_idx, target_pos, X, W, Mi, slabs, B, w.Bp, D, scale, w.inv, loss_per_sample,
                                w.dZT, w.X2, dev_status, mode, io);
             mark(3);
