@@ -434,6 +434,27 @@ def test_one_call_step_equals_forward_backward_then_update(ks, orc, name, unit_r
     assert (Wm2.cpu().numpy()[rest] == W[rest]).all()
 
 
+@pytest.mark.parametrize("C,D,B,K,M", [(3000, 64, 70, 8, 300), (5000, 192, 200, 12, 1000), (2000, 320, 33, 4, 130)])
+def test_one_call_step_ragged_shapes(ks, orc, C, D, B, K, M):
+    """D below and between the tile widths, B and the active count not multiples of anything: the update inside the
+    dW kernel against forward/backward followed by the stand-alone update, bit for bit."""
+    W = synth.unit_rows(7, synth.TID_W, C, D, bf16=True)
+    X = synth.unit_rows(7, synth.TID_X, B, D, bf16=True)
+    y = synth.labels_uniform(7, B, C)
+    G = synth.graph_synthetic(7, C, K)
+    Wb, Xb, yd, Gd = dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(G)
+    for unit_rows in (False, True):
+        Wm1, Wb1 = dev(W), Wb.clone()
+        a = ks.knn_softmax_fwd_bwd(Wb1, Xb, yd, Gd, M, 25.0, 4.0, unit_rows=unit_rows)
+        ks.apply_weight_grad(Wm1, Wb1, a["active_idx"], a["n_active"], a["dW_active"], -0.02, idx_sorted_unique=True)
+        Wm2, Wb2 = dev(W), Wb.clone()
+        b = ks.knn_softmax_fwd_bwd_update(Wm2, Wb2, Xb, yd, Gd, M, 25.0, 4.0, -0.02, unit_rows=unit_rows)
+        torch.cuda.synchronize()
+        assert int(a["dev_status"].item()) == 0 and int(b["dev_status"].item()) == 0
+        assert torch.equal(Wm1, Wm2) and torch.equal(Wb1, Wb2) and torch.equal(a["dX"], b["dX"])
+        assert torch.equal(a["loss_mean"], b["loss_mean"]) and not torch.equal(Wm2, dev(W))
+
+
 def test_one_call_step_on_a_shape_without_the_fused_update(ks, orc):
     """D = 96: the gradient is stored and the stand-alone update runs inside the same call."""
     C, D, B, K, M, scale = 3000, 96, 64, 8, 512, 20.0
