@@ -18,7 +18,11 @@ typedef KsTile<128, 128, 64, 2, 2> TileG;      // generic path (any D % 32 == 0)
 typedef KsATile<256, 256, 2, 4, 2> TileSm;     // fast path (D % 64 == 0): tile = 256 classes x 256 samples
 typedef KsATile<128, 128, 2, 2, 2> TileDx;
 #define DX_IDX_CACHE 4096 /* gather indices of one workgroup's share of the active dimension, staged in LDS */
+// dW tiles: 256 columns of D, and 256, 192 or 128 active rows -- chosen inside the kernel from the number of active
+// rows, which only the device knows (see dw_tile_rows)
 typedef KsATile<256, 256, 2, 4, 2> TileDw;
+typedef KsATile<192, 256, 2, 4, 2> TileDw192;
+typedef KsATile<128, 256, 2, 4, 2> TileDw128;
 #define KS_BP_ALIGN 256
 #define SM_LIDX_CAP 1536 // gather-list entries a sweep keeps in LDS (longer slabs read the list from memory)
 #define SM_SOE_GRID 256 /* workgroups of the stationary-operand softmax passes (one per compute unit) */
@@ -1017,11 +1021,34 @@ struct DwUpdate {
     const int32_t *idx;
     float alpha;
 };
+// Height of the dW tiles for n_active rows on a chip of n_cu compute units (one tile per compute unit at a time).
+// With few active rows 256-row tiles leave compute units idle (17,425 rows x 512 columns are 138 tiles); lower tiles
+// cost more per flop (the X panel is loaded per tile whatever its height) but fill the chip: estimated time =
+// rounds x relative cost per tile (measured: 1, 0.81, 0.57), the smallest wins, ties to the taller tile.
+__device__ __forceinline__ int dw_tile_rows(int n_active, int tiles_n, int n_cu) {
+    const int heights[3] = {256, 192, 128}, cost[3] = {100, 81, 57};
+    int best = 256, best_t = 0x7fffffff;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+        const int tiles = tiles_n * ((n_active + heights[k] - 1) / heights[k]);
+        const int t = ((tiles + n_cu - 1) / n_cu) * cost[k];
+        if (t < best_t) { best_t = t; best = heights[k]; }
+    }
+    return best;
+}
+
 template <class T>
-__global__ void __launch_bounds__(T::NT)
+__device__ __forceinline__ void dw_tile(uint16_t *lds, const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X, int B,
+                                        int Bp, int n_active, int D, int64_t Mp, float scale, float *__restrict__ dW,
+                                        const DwUpdate &up);
+
+__global__ void __launch_bounds__(TileDw::NT)
 dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X, int B, int Bp,
                 const int32_t *__restrict__ n_active_p, int D, int M, int64_t Mp, float scale, float *__restrict__ dW,
-                int tiles_max, DxReduceJob job, DwUpdate up) {
+                int tiles_max, int n_cu, DxReduceJob job, DwUpdate up) {
+    typedef TileDw T;
+    static_assert(TileDw192::NT == T::NT && TileDw128::NT == T::NT && TileDw192::LDS_ELEMS <= T::LDS_ELEMS &&
+                      TileDw128::LDS_ELEMS <= T::LDS_ELEMS, "one launch shape for all tile heights");
     __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
     if ((int)blockIdx.x >= tiles_max) { // reduction blocks
         const int rb = blockIdx.x - tiles_max, nrb = gridDim.x - tiles_max;
@@ -1049,6 +1076,16 @@ dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X
         return;
     }
     const int n_active = sm_clamp_n(n_active_p, M);
+    const int rows = dw_tile_rows(n_active, (D + T::BN - 1) / T::BN, n_cu);
+    if (rows == 256) dw_tile<TileDw>(lds, dZT, X, B, Bp, n_active, D, Mp, scale, dW, up);
+    else if (rows == 192) dw_tile<TileDw192>(lds, dZT, X, B, Bp, n_active, D, Mp, scale, dW, up);
+    else dw_tile<TileDw128>(lds, dZT, X, B, Bp, n_active, D, Mp, scale, dW, up);
+}
+
+template <class T>
+__device__ __forceinline__ void dw_tile(uint16_t *lds, const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X, int B,
+                                        int Bp, int n_active, int D, int64_t Mp, float scale, float *__restrict__ dW,
+                                        const DwUpdate &up) {
     const int tiles_n = (D + T::BN - 1) / T::BN;
     const int n_tiles = tiles_n * ((n_active + T::BM - 1) / T::BM);
     if ((int)blockIdx.x >= n_tiles) return;
@@ -1198,6 +1235,19 @@ sm_sanitize_kernel(const int32_t *__restrict__ active_idx, const int32_t *__rest
         }
         tp_safe[t] = tp < 0 ? -1 : tp;
     }
+}
+
+// compute units of the current device (asked once)
+static int ks_n_cu() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
 }
 
 struct SmWs {
@@ -1357,7 +1407,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
         mark(6); // the reduction of the partial products rides along with the next launch
         {
             typedef TileDw T;
-            const int tiles = (int)(ks_ceil_div(M, T::BM) * ks_ceil_div(D, T::BN));
+            const int tiles = (int)(ks_ceil_div(M, TileDw128::BM) * ks_ceil_div(D, T::BN)); // the most any tile height needs
             DxReduceJob job;
             job.part = w.part;
             job.S = w.S;
@@ -1367,8 +1417,8 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
             job.dX = dX;
             job.loss_i = loss_per_sample;
             job.loss_mean = loss_mean;
-            hipLaunchKernelGGL(dw_async_kernel<T>, dim3(tiles + DW_REDUCE_BLOCKS), dim3(T::NT), 0, st, w.dZT, fused ? w.X2 : X,
-                               B, w.Bp, n_active, D, Mi, w.Mp, fused ? scale * g : scale, dW_active, tiles, job, up);
+            hipLaunchKernelGGL(dw_async_kernel, dim3(tiles + DW_REDUCE_BLOCKS), dim3(T::NT), 0, st, w.dZT, fused ? w.X2 : X, B,
+                               w.Bp, n_active, D, Mi, w.Mp, fused ? scale * g : scale, dW_active, tiles, ks_n_cu(), job, up);
         }
         mark(7);
         KS_LAUNCH_CHECK();
