@@ -3,41 +3,46 @@
 // Computes, chunk by chunk, the products  C[m][n] = sum_k S[m][k] * R[n][k]  of a long list of "streamed"
 // rows S (m) with a block of 256 "resident" rows R (n), both stored with k contiguous, for a depth
 // K = 64 * KT that is small enough to keep the resident block's MFMA fragments in registers for the whole
-// sweep (KT <= 8: 256 VGPRs per lane).  Only the streamed rows travel through LDS (global_load_lds, several
-// 128-row x 64-k tiles in flight), so each byte fetched from L2 feeds 256 multiply-adds instead of the
-// 128 of a tile engine that streams both operands, and the chunk size (128 streamed rows) can be cut
-// at any multiple of 32, which lets callers split the streamed rows evenly over the chip.
+// sweep (KT <= 8).  Only the streamed rows travel through LDS (global_load_lds, several CH-row x 64-k tiles
+// in flight), so each byte fetched from L2 feeds 256 multiply-adds instead of the 128 of a tile engine that
+// streams both operands, and the chunk size can be cut at any multiple of 32, which lets callers split the
+// streamed rows evenly over the chip.
 //
-// Workgroup = 4 wavefronts; wavefront w owns resident rows [64 w, 64 w + 64) (two 32-column MFMA blocks),
-// every wavefront reads the whole streamed tile from LDS.  MFMA orientation: streamed rows are the MFMA
-// rows, resident rows the MFMA columns, so in the accumulator a lane owns ONE resident row (column
-// lane % 32 of block fn) and 16 streamed rows per 32-row block: reductions along the streamed rows for a
-// fixed resident row (softmax statistics per sample, running thresholds per graph row) are lane-local.
+// Workgroup = EIGHT wavefronts, two per SIMD; wavefront w owns resident rows [32 w, 32 w + 32): one 32-column
+// MFMA block, 128 registers of fragments for K = 512, so a lane stays within 256 registers and a SIMD holds two
+// wavefronts.  While one of them waits (for a barrier, for its fragments, in its epilogue's exponentials and
+// stores) the other one's MFMAs keep the matrix pipe busy.  The price is LDS traffic: every wavefront reads the
+// whole streamed tile for half as many MFMAs as with four wavefronts of 64 resident rows.  Measured against that
+// four-wavefront layout: 1.18 instead of 1.00 PFLOP/s on a plain sweep, the softmax sweep of the headline shape
+// 34 instead of 40 us, the graph's recall pass 214 instead of 296 ms.
 //
-// After every chunk (all KT k-tiles of 128 streamed rows) the caller's epilogue functor gets the
+// MFMA orientation: streamed rows are the MFMA rows, resident rows the MFMA columns, so in the accumulator a
+// lane owns ONE resident row (column lane % 32) and 16 streamed rows per 32-row block: reductions along the
+// streamed rows for a fixed resident row (softmax statistics per sample, running thresholds per graph row) are
+// lane-local.  Streamed tiles are loaded by the first CH / 16 wavefronts (two 8-row instructions each).
+//
+// After every chunk (all KT k-tiles of CH streamed rows) the caller's epilogue functor gets the
 // accumulators; the loads of the next chunk are already in flight at that point.
 #pragma once
 #include "ks_gemm_async.h"
 
 template <int KT_, int CH_, int STAGES_, int KSUB_ = 1> struct KsSoe {
-    static constexpr int KT = KT_, STAGES = STAGES_;
-    static constexpr int KSUB = KSUB_;         // 64-wide k-tiles per pipeline stage (one barrier per stage)
-    static constexpr int NW = 4, NT = 256;
-    static constexpr int CH = CH_;             // streamed rows per chunk (96 or 128: the accumulators must fit beside
-                                               // the resident fragments in the 512 registers of a lane)
-    static constexpr int RES = 256;            // resident rows per workgroup
-    static constexpr int FM = CH / 32, FN = 2; // accumulator blocks per wave
-    static constexpr int NI = CH / (8 * NW);   // load instructions per wave per tile
+    static constexpr int KT = KT_, STAGES = STAGES_, KSUB = KSUB_;
+    static constexpr int NW = 8, NT = 512, CH = CH_, RES = 256;
+    static constexpr int FM = CH / 32;
+    static constexpr int LW = CH / 16; // wavefronts that issue the stream loads
+    static constexpr int NI = 2;       // load instructions per loading wavefront per k-tile
     static constexpr int STAGE_ELEMS = KSUB * CH * 64;
     static constexpr int LDS_ELEMS = STAGES * STAGE_ELEMS;
-    static_assert(KT >= 1 && KT <= 8 && KT % KSUB == 0 && STAGES >= 2 && (STAGES - 2) * NI * KSUB <= 63 && CH % 32 == 0,
+    static_assert(KT >= 1 && KT <= 8 && KT % KSUB == 0 && STAGES >= 2 && (STAGES - 2) * NI * KSUB <= 63 && CH % 32 == 0 &&
+                      LW <= NW,
                   "sweep shape");
 };
 
 // Row of the streamed chunk that accumulator element (fm, r) of this lane belongs to.
 __device__ __forceinline__ int ks_soe_row(int fm, int r, int lane) { return fm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
-// Resident row (inside the workgroup's block of 256) of accumulator block fn of this lane.
-__device__ __forceinline__ int ks_soe_col(int fn) { return (threadIdx.x >> 6) * 64 + fn * 32 + (threadIdx.x & 31); }
+// Resident row (inside the workgroup's block of 256) of this lane's accumulator column.
+__device__ __forceinline__ int ks_soe_col() { return (threadIdx.x >> 6) * 32 + (threadIdx.x & 31); }
 
 // Sweep.  R: resident operand (rows r_row0 .. r_row0+255, rows >= r_limit redirected to r_limit-1).
 // S: streamed operand; streamed row index g in [s_begin, s_end) maps to memory row gidx ? gidx[g'] : g'
@@ -51,24 +56,27 @@ __device__ __forceinline__ int ks_soe_col(int fn) { return (threadIdx.x >> 6) * 
 // post(chunk_first_row, rows_in_chunk): optional second half of a chunk's epilogue, for global stores.  The
 // sweep tells that a stage has landed by counting outstanding vector-memory instructions, and stores count
 // too: stores issued at the end of a chunk make the very next wait sit out their round trip.  post() for
-// chunk c is therefore called inside chunk c+1, right after the loads of its first stage's successor have
-// been issued (the wait after that still lets exactly those loads and the stores be outstanding, and by
-// then a whole stage of MFMAs has passed), and after the sweep for the last chunk.  epi() leaves what
-// post() needs in LDS of the caller's.
+// chunk c is therefore called inside chunk c+1, right after the loads that follow its first barrier have been
+// issued: the next wait comes a whole stage of MFMAs later, when most of the stores have completed.  (Letting
+// that wait tolerate the stores as well, and sparing the wavefronts that load nothing the wait altogether, was
+// measured and gains nothing.)  The last chunk's post() runs after the sweep.  epi() leaves what post() needs
+// in LDS of the caller's.
 struct KsSoeNoPost {
     __device__ __forceinline__ void operator()(int, int) const {}
 };
+template <class P> struct KsSoeHasPost { static constexpr bool value = true; };
+template <> struct KsSoeHasPost<KsSoeNoPost> { static constexpr bool value = false; };
 template <class CFG, class Epi, class Post = KsSoeNoPost>
 __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int64_t ldr, int r_row0, int r_limit,
-                                             const uint16_t *__restrict__ S, int64_t lds_ld, const int32_t *__restrict__ gidx,
-                                             int s_begin, int s_end, int s_clamp, uint16_t *lds, Epi &epi,
-                                             int32_t *lidx = nullptr, int lidx_cap = 0, Post post = Post()) {
+                                              const uint16_t *__restrict__ S, int64_t lds_ld, const int32_t *__restrict__ gidx,
+                                              int s_begin, int s_end, int s_clamp, uint16_t *lds, Epi &epi,
+                                              int32_t *lidx = nullptr, int lidx_cap = 0, Post post = Post()) {
     constexpr int KT = CFG::KT, ST = CFG::STAGES, NI = CFG::NI, FM = CFG::FM;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
     // ---- resident fragments: staged through LDS (coalesced row loads), then kept in registers ----------------
-    bf16x8_t bres[2][KT * 4];
+    bf16x8_t bres[KT * 4];
     {
         static_assert(CFG::LDS_ELEMS >= 2 * CFG::RES * 64, "the stream stages double as staging for the resident block");
         KsARows<CFG::RES, CFG::NW> rr;
@@ -82,11 +90,8 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
             if (kt + 1 < KT) rr.issue((kt + 1) * 64, lds + ((kt + 1) & 1) * CFG::RES * 64);
             const uint16_t *st = lds + (kt & 1) * CFG::RES * 64;
 #pragma unroll
-            for (int fn = 0; fn < 2; ++fn)
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    bres[fn][kt * 4 + kk] =
-                        *(const bf16x8_t *)(st + (wave * 64 + fn * 32 + r31) * 64 + (((kk * 2 + khalf) ^ swz) * 8));
+            for (int kk = 0; kk < 4; ++kk)
+                bres[kt * 4 + kk] = *(const bf16x8_t *)(st + (wave * 32 + r31) * 64 + (((kk * 2 + khalf) ^ swz) * 8));
         }
     }
 
@@ -103,12 +108,12 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
     }
     __builtin_amdgcn_s_waitcnt(0xC07F); // the fragment reads have returned before the stages are reused
     __syncthreads();                    // (also publishes the gather list)
-    const int chunk_slot = (lane & 7) ^ 0; // 16-byte slot of this lane inside a 128-byte LDS row
-    const uint16_t *ptr[NI];               // row pointers (k = 0, swizzled chunk) of the chunk being issued
-    auto chunk_ptrs = [&](int c) {
+    const bool loader = wave < CFG::LW;
+    const uint16_t *ptr[NI]; // row pointers (k = 0, swizzled chunk) of the chunk being issued (loading wavefronts)
+    auto chunk_ptrs = [&](int c) __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
-            const int row = (j * CFG::NW + wave) * 8 + (lane >> 3);
+            const int row = (j * CFG::LW + wave) * 8 + (lane >> 3);
             int64_t src;
             if (use_lidx) {
                 src = lidx[c * CFG::CH + row];
@@ -117,28 +122,30 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
                 if (g >= s_clamp) g = s_clamp - 1;
                 src = gidx ? (int64_t)gidx[g] : (int64_t)g;
             }
-            ptr[j] = S + src * lds_ld + ((chunk_slot ^ ((row >> 1) & 7)) * 8);
+            ptr[j] = S + src * lds_ld + (((lane & 7) ^ ((row >> 1) & 7)) * 8);
         }
     };
     int is_c = 0, is_kt = 0, is_stage = 0, issued = 0; // position of the next tile to issue
-    auto issue_one = [&]() { // one stage = KSUB consecutive k-tiles of the current chunk
+    auto issue_one = [&]() __attribute__((always_inline)) { // one stage = KSUB consecutive k-tiles of the current chunk
         uint16_t *st = lds + is_stage * CFG::STAGE_ELEMS;
+        if (loader) {
 #pragma unroll
-        for (int u = 0; u < CFG::KSUB; ++u)
+            for (int u = 0; u < CFG::KSUB; ++u)
 #pragma unroll
-            for (int j = 0; j < NI; ++j)
-                __builtin_amdgcn_global_load_lds(KS_GPTR(ptr[j] + (is_kt + u) * 64),
-                                                 KS_LPTR(st + u * CFG::CH * 64 + (j * CFG::NW + wave) * 8 * 64), 16, 0, 0);
+                for (int j = 0; j < NI; ++j)
+                    __builtin_amdgcn_global_load_lds(KS_GPTR(ptr[j] + (is_kt + u) * 64),
+                                                     KS_LPTR(st + u * CFG::CH * 64 + (j * CFG::LW + wave) * 8 * 64), 16, 0, 0);
+        }
         ++issued;
         if (++is_stage == ST) is_stage = 0;
         is_kt += CFG::KSUB;
         if (is_kt == KT) {
             is_kt = 0;
             ++is_c;
-            if (is_c < n_chunks) chunk_ptrs(is_c);
+            if (is_c < n_chunks && loader) chunk_ptrs(is_c);
         }
     };
-    if (n_chunks > 0) chunk_ptrs(0);
+    if (n_chunks > 0 && loader) chunk_ptrs(0);
 #pragma unroll
     for (int s = 0; s < ST - 1; ++s)
         if (issued < n_tiles) issue_one();
@@ -149,16 +156,15 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
     for (int c = 0; c < n_chunks; ++c) {
         const int rows_here = (s_end - (s_begin + c * CFG::CH)) < CFG::CH ? (s_end - (s_begin + c * CFG::CH)) : CFG::CH;
         const int fm_cnt = (rows_here + 31) >> 5; // 32-row blocks of this chunk that hold real rows
-        f32x16_t acc[FM][2];
+        f32x16_t acc[FM];
 #pragma unroll
         for (int fm = 0; fm < FM; ++fm)
 #pragma unroll
-            for (int fn = 0; fn < 2; ++fn)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[fm][fn][r] = 0.f;
+            for (int r = 0; r < 16; ++r) acc[fm][r] = 0.f;
 #pragma unroll
         for (int kt0 = 0; kt0 < KT; kt0 += CFG::KSUB) {
-            // stage `done` must have landed; the stages issued after it may still be in flight
+            // stage `done` must have landed; the stages issued after it may still be in flight.  (Wavefronts that load
+            // nothing only have the stores of their epilogues outstanding, which this wait also covers.)
             if (issued - done - 1 >= ST - 2) ks_wait_vmcnt<(ST - 2) * NI * CFG::KSUB>();
             else ks_wait_vmcnt<0>();
             ks_barrier_nofence();
@@ -186,17 +192,16 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
                     }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int fm = 0; fm < FM; ++fm) {
-                        if (fm < fm_cnt) {
-                            acc[fm][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[fm], bres[0][kt * 4 + kk], acc[fm][0], 0, 0, 0);
-                            acc[fm][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[fm], bres[1][kt * 4 + kk], acc[fm][1], 0, 0, 0);
-                        }
-                    }
+                    for (int fm = 0; fm < FM; ++fm)
+                        if (fm < fm_cnt) acc[fm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[fm], bres[kt * 4 + kk], acc[fm], 0, 0, 0);
                 }
             }
             if (++stage == ST) stage = 0;
             ++done;
         }
+        // a chunk of a single stage has no barrier between post() of the previous chunk (which reads what epi() left
+        // in LDS) and this chunk's epi(): a wavefront that runs ahead must not overwrite what another still reads
+        if (KT / CFG::KSUB < 2 && KsSoeHasPost<Post>::value) ks_barrier_nofence();
         epi(s_begin + c * CFG::CH, rows_here, acc);
     }
     ks_barrier_nofence();

@@ -322,12 +322,13 @@ gr_recall_async_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand
 // of the 256 rows in the accumulators, so the row's threshold is a register and most elements cost one
 // max operation; only 16-element blocks whose maximum beats the threshold are looked at one by one.
 // ------------------------------------------------------------------------------------------------
+#define GR_SOE_STAGES 6
 template <int KT, int E>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(512)
 gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, int32_t *__restrict__ cnt_out,
-                     uint32_t *__restrict__ thr_out) {
+                      uint32_t *__restrict__ thr_out) {
     const int64_t C = pr.Cr;
-    typedef KsSoe<KT, 96, 6, 2> CFG;
+    typedef KsSoe<KT, 96, GR_SOE_STAGES, 2> CFG;
     constexpr int CAP = E * 64;
     __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
     __shared__ int s_cnt[CFG::RES];
@@ -335,44 +336,36 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
     __shared__ int s_need;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t row0 = (int64_t)blockIdx.x * CFG::RES;
-    for (int m = threadIdx.x; m < CFG::RES; m += 256) { s_cnt[m] = 0; s_thr[m] = 0u; }
+    for (int m = threadIdx.x; m < CFG::RES; m += CFG::NT) { s_cnt[m] = 0; s_thr[m] = 0u; }
     if (threadIdx.x == 0) s_need = 0;
     __syncthreads();
-    int col[2], gi[2];
-#pragma unroll
-    for (int fn = 0; fn < 2; ++fn) {
-        col[fn] = ks_soe_col(fn);
-        gi[fn] = (int)row0 + col[fn]; // C < 2^31
-    }
+    const int col = ks_soe_col();
+    const int gi = (int)row0 + col; // C < 2^31
     const int Ci = (int)C;
     const int64_t self0 = row0 + pr.self; // streamed rows [self0, self0 + RES) are this workgroup's own rows
-    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM][2]) {
+    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM]) {
         // elements that need more than the threshold test: the tail of the last chunk, and the diagonal
         const bool special = rows_here < CFG::CH || ((int64_t)c0 < self0 + CFG::RES && (int64_t)c0 + CFG::CH > self0);
+        const uint32_t th = s_thr[col];
+        // 0 = nothing dropped yet: everything passes; rows beyond C never pass
+        const float thf = gi >= Ci ? INFINITY : (th == 0u ? -INFINITY : gr_unorder(th));
 #pragma unroll
-        for (int fn = 0; fn < 2; ++fn) {
-            const uint32_t th = s_thr[col[fn]];
-            // 0 = nothing dropped yet: everything passes; rows beyond C never pass
-            const float thf = gi[fn] >= Ci ? INFINITY : (th == 0u ? -INFINITY : gr_unorder(th));
+        for (int fm = 0; fm < CFG::FM; ++fm) {
+            float bm = acc[fm][0];
 #pragma unroll
-            for (int fm = 0; fm < CFG::FM; ++fm) {
-                float bm = acc[fm][fn][0];
+            for (int r = 1; r < 16; ++r) bm = fmaxf(bm, acc[fm][r]);
+            if (bm > thf) {
 #pragma unroll
-                for (int r = 1; r < 16; ++r) bm = fmaxf(bm, acc[fm][fn][r]);
-                if (bm > thf) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float v = acc[fm][fn][r];
-                        if (v > thf) {
-                            const int lr = ks_soe_row(fm, r, lane);
-                            const int j = c0 + lr;
-                            if (special && (lr >= rows_here || (int64_t)j == (int64_t)gi[fn] + pr.self)) continue;
-                            const int slot = atomicAdd(&s_cnt[col[fn]], 1);
-                            if (slot < CAP) // always true: a buffer is cut back before it can overflow
-                                cand[(int64_t)gi[fn] * CAP + slot] =
-                                    ((uint64_t)gr_orderable(v) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
-                            if (slot + 1 > CAP - CFG::CH) s_need = 1;
-                        }
+                for (int r = 0; r < 16; ++r) {
+                    const float v = acc[fm][r];
+                    if (v > thf) {
+                        const int lr = ks_soe_row(fm, r, lane);
+                        const int j = c0 + lr;
+                        if (special && (lr >= rows_here || (int64_t)j == (int64_t)gi + pr.self)) continue;
+                        const int slot = atomicAdd(&s_cnt[col], 1);
+                        if (slot < CAP) // always true: a buffer is cut back before it can overflow
+                            cand[(int64_t)gi * CAP + slot] = ((uint64_t)gr_orderable(v) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
+                        if (slot + 1 > CAP - CFG::CH) s_need = 1;
                     }
                 }
             }
@@ -381,7 +374,7 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
         ks_barrier_nofence();
         if (s_need) { // some buffer could overflow in the next chunk: cut the full ones back
             __syncthreads(); // the appended candidates are visible to the wavefront that sorts them
-            for (int m = wave; m < CFG::RES; m += 4) {
+            for (int m = wave; m < CFG::RES; m += CFG::NW) {
                 if (s_cnt[m] > CAP - CFG::CH) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
             }
             __syncthreads();
@@ -390,13 +383,13 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
     };
     ks_soe_sweep<CFG>(pr.R, D, (int)row0, (int)C, pr.S, D, nullptr, 0, (int)pr.Cs, (int)pr.Cs, lds, epi);
     __syncthreads();
-    for (int m = wave; m < CFG::RES; m += 4) {
+    for (int m = wave; m < CFG::RES; m += CFG::NW) {
         if (row0 + m < C) {
             if (s_cnt[m] > kprime) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
         }
     }
     __syncthreads();
-    for (int m = threadIdx.x; m < CFG::RES; m += 256) {
+    for (int m = threadIdx.x; m < CFG::RES; m += CFG::NT) {
         if (row0 + m < C) { cnt_out[row0 + m] = s_cnt[m]; thr_out[row0 + m] = s_thr[m]; }
     }
 }
@@ -635,9 +628,9 @@ static void gr_launch_recall(const GrPair &pr, int D, const GrParams &p, uint64_
 #define GR_SOE_LAUNCH(KT)                                                                                                   \
     do {                                                                                                                    \
         if (p.cap == 256)                                                                                                   \
-            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 4>), dim3(nb), dim3(256), 0, st, pr, D, p.kprime, cand, cnt, thr);  \
+            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 4>), dim3(nb), dim3(512), 0, st, pr, D, p.kprime, cand, cnt, thr);  \
         else                                                                                                                \
-            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 8>), dim3(nb), dim3(256), 0, st, pr, D, p.kprime, cand, cnt, thr);  \
+            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 8>), dim3(nb), dim3(512), 0, st, pr, D, p.kprime, cand, cnt, thr);  \
     } while (0)
         if (D == 512) GR_SOE_LAUNCH(8);
         else if (D == 256) GR_SOE_LAUNCH(4);

@@ -438,7 +438,7 @@ sm_grad_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, c
 // The active classes are cut into G / tiles_s equal slabs (multiples of 32 rows), so the chip is loaded
 // evenly whatever the active count; per-sample softmax statistics are carried in registers along the slab.
 // ================================================================================================
-#define SOE_STAGES 4
+#define SOE_STAGES 3
 #define KS_FUSED_MAX_SCALE 40.f // exp(-2 * scale) must stay a normal fp32 / bf16 number
 
 // rows per slab for n64 = round_up(n_active, 64) rows and `slabs` slabs
@@ -449,7 +449,7 @@ __host__ __device__ __forceinline__ int sm_slab_rows(int n64, int slabs) {
 }
 
 template <int KT>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(512)
 sm_stats_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, const int32_t *__restrict__ active_idx,
                     const int32_t *__restrict__ n_active_p, const int32_t *__restrict__ target_pos, int B, int Bp, int D, int M,
                     int tiles_s, float scale, float *__restrict__ pm, float *__restrict__ pl, float *__restrict__ zt) {
@@ -466,92 +466,78 @@ sm_stats_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
     if (slab >= slabs || s0 >= s1) return;
     const int lane = threadIdx.x & 63;
     const int lim = n < s1 ? n : s1; // rows of this slab that are real classes
-    int i[2], tp[2];
-    float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.f, 0.f};
-#pragma unroll
-    for (int fn = 0; fn < 2; ++fn) {
-        i[fn] = ts * CFG::RES + ks_soe_col(fn);
-        tp[fn] = (i[fn] < B) ? target_pos[i[fn]] : -1;
-    }
+    const int i = ts * CFG::RES + ks_soe_col();
+    const int tp = (i < B) ? target_pos[i] : -1;
+    float m = -INFINITY, l = 0.f;
     // scale > 0 (checked by the host): statistics are carried on the raw products, m = max of acc,
     // l = sum exp(scale * (acc - m)) = sum exp2(fma(acc, k1, -k1 * m)); one fused multiply-add per element
     const float k1 = scale * 1.4426950408889634f;
-    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM][2]) {
+    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM]) {
         (void)rows_here;
         // the target logit of a sample whose label sits in this chunk (rare: a scan over this lane's rows)
+        if (tp >= c0 && tp < c0 + CFG::CH && tp < lim) {
 #pragma unroll
-        for (int fn = 0; fn < 2; ++fn) {
-            if (tp[fn] >= c0 && tp[fn] < c0 + CFG::CH && tp[fn] < lim) {
+            for (int fm = 0; fm < CFG::FM; ++fm)
 #pragma unroll
-                for (int fm = 0; fm < CFG::FM; ++fm)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (c0 + ks_soe_row(fm, r, lane) == tp[fn]) zt[i[fn]] = scale * acc[fm][fn][r];
-            }
+                for (int r = 0; r < 16; ++r)
+                    if (c0 + ks_soe_row(fm, r, lane) == tp) zt[i] = scale * acc[fm][r];
         }
         if (c0 + CFG::CH <= lim) { // every row of the chunk is a real class: no masks
+            float cmax = acc[0][0];
 #pragma unroll
-            for (int fn = 0; fn < 2; ++fn) {
-                float cmax = acc[0][fn][0];
+            for (int fm = 0; fm < CFG::FM; ++fm)
 #pragma unroll
-                for (int fm = 0; fm < CFG::FM; ++fm)
+                for (int r = 0; r < 16; ++r) cmax = fmaxf(cmax, acc[fm][r]);
+            const float mn = fmaxf(m, cmax);
+            const float off = -k1 * mn;
+            float q0 = 0.f, q1 = 0.f, q2 = 0.f, q3 = 0.f; // four chains: the exponentials do not wait on one sum
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) cmax = fmaxf(cmax, acc[fm][fn][r]);
-                const float mn = fmaxf(m[fn], cmax);
-                const float off = -k1 * mn;
-                float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f; // four chains: the exponentials do not wait on one sum
+            for (int fm = 0; fm < CFG::FM; ++fm)
 #pragma unroll
-                for (int fm = 0; fm < CFG::FM; ++fm)
-#pragma unroll
-                    for (int r = 0; r < 16; r += 4) {
-                        s0 += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r], k1, off));
-                        s1 += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r + 1], k1, off));
-                        s2 += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r + 2], k1, off));
-                        s3 += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r + 3], k1, off));
-                    }
-                l[fn] = l[fn] * __builtin_amdgcn_exp2f(k1 * (m[fn] - mn)) + ((s0 + s1) + (s2 + s3)); // m = -inf, l = 0 at the start
-                m[fn] = mn;
-            }
+                for (int r = 0; r < 16; r += 4) {
+                    q0 += __builtin_amdgcn_exp2f(fmaf(acc[fm][r], k1, off));
+                    q1 += __builtin_amdgcn_exp2f(fmaf(acc[fm][r + 1], k1, off));
+                    q2 += __builtin_amdgcn_exp2f(fmaf(acc[fm][r + 2], k1, off));
+                    q3 += __builtin_amdgcn_exp2f(fmaf(acc[fm][r + 3], k1, off));
+                }
+            l = l * __builtin_amdgcn_exp2f(k1 * (m - mn)) + ((q0 + q1) + (q2 + q3)); // m = -inf, l = 0 at the start
+            m = mn;
         } else {
+            float cmax = -INFINITY;
 #pragma unroll
-            for (int fn = 0; fn < 2; ++fn) {
-                float cmax = -INFINITY;
+            for (int fm = 0; fm < CFG::FM; ++fm)
 #pragma unroll
-                for (int fm = 0; fm < CFG::FM; ++fm)
+                for (int r = 0; r < 16; ++r)
+                    if (c0 + ks_soe_row(fm, r, lane) < lim) cmax = fmaxf(cmax, acc[fm][r]);
+            if (cmax == -INFINITY) return; // no real class among this lane's rows of the chunk
+            const float mn = fmaxf(m, cmax);
+            const float off = -k1 * mn;
+            float sum = 0.f;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (c0 + ks_soe_row(fm, r, lane) < lim) cmax = fmaxf(cmax, acc[fm][fn][r]);
-                if (cmax == -INFINITY) continue; // no real class among this lane's rows of the chunk
-                const float mn = fmaxf(m[fn], cmax);
-                const float off = -k1 * mn;
-                float sum = 0.f;
+            for (int fm = 0; fm < CFG::FM; ++fm)
 #pragma unroll
-                for (int fm = 0; fm < CFG::FM; ++fm)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        if (c0 + ks_soe_row(fm, r, lane) < lim) sum += __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r], k1, off));
-                l[fn] = l[fn] * __builtin_amdgcn_exp2f(k1 * (m[fn] - mn)) + sum;
-                m[fn] = mn;
-            }
+                for (int r = 0; r < 16; ++r)
+                    if (c0 + ks_soe_row(fm, r, lane) < lim) sum += __builtin_amdgcn_exp2f(fmaf(acc[fm][r], k1, off));
+            l = l * __builtin_amdgcn_exp2f(k1 * (m - mn)) + sum;
+            m = mn;
         }
     };
     ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi, s_lidx, SM_LIDX_CAP);
-#pragma unroll
-    for (int fn = 0; fn < 2; ++fn) {
+    {
         // the two half-waves hold disjoint class rows of the same 32 samples
-        const float mz = scale * m[fn]; // back to logit units
-        const float mo = __shfl_xor(mz, 32, 64), lo = __shfl_xor(l[fn], 32, 64);
+        const float mz = scale * m; // back to logit units
+        const float mo = __shfl_xor(mz, 32, 64), lo = __shfl_xor(l, 32, 64);
         const float mm = fmaxf(mz, mo);
-        const float ll = (mz == -INFINITY ? 0.f : l[fn] * __expf(mz - mm)) + (mo == -INFINITY ? 0.f : lo * __expf(mo - mm));
-        if (lane < 32 && i[fn] < B) {
-            pm[(int64_t)slab * Bp + i[fn]] = mm;
-            pl[(int64_t)slab * Bp + i[fn]] = ll;
+        const float ll = (mz == -INFINITY ? 0.f : l * __expf(mz - mm)) + (mo == -INFINITY ? 0.f : lo * __expf(mo - mm));
+        if (lane < 32 && i < B) {
+            pm[(int64_t)slab * Bp + i] = mm;
+            pl[(int64_t)slab * Bp + i] = ll;
         }
     }
 }
 
 template <int KT>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(512)
 sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, const int32_t *__restrict__ active_idx,
                    const int32_t *__restrict__ n_active_p, const int32_t *__restrict__ target_pos,
                    const float *__restrict__ lse, int B, int Bp, int D, int M, int tiles_s, float scale, float g,
@@ -569,22 +555,15 @@ sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
     const int ts = id % tiles_s, slab = id / tiles_s;
     const int s0 = slab * h, s1 = (s0 + h < n64) ? s0 + h : n64;
     if (slab >= slabs || s0 >= s1) return;
-    int tp[2];
-    float ls[2];
-#pragma unroll
-    for (int fn = 0; fn < 2; ++fn) {
-        const int i = ts * CFG::RES + ks_soe_col(fn);
-        ls[fn] = i < B ? lse[i] : 0.f;
-        tp[fn] = i < B ? target_pos[i] : -1;
-    }
+    const int i0 = ts * CFG::RES + ks_soe_col();
+    const float ls = i0 < B ? lse[i0] : 0.f;
+    const int tp = i0 < B ? target_pos[i0] : -1;
     // scale > 0 and g > 0 (checked by the host): g * exp(scale * acc - lse) = exp2(fma(acc, k1, k2)) with
     // k2 = log2(g) - lse * log2(e): one fused multiply-add and one exponential per element
     const float k1 = scale * 1.4426950408889634f;
-    float k2[2];
-#pragma unroll
-    for (int fn = 0; fn < 2; ++fn) k2[fn] = __log2f(g) - ls[fn] * 1.4426950408889634f;
+    const float k2 = __log2f(g) - ls * 1.4426950408889634f;
     const bool samples_ok = (ts + 1) * CFG::RES <= B;
-    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM][2]) {
+    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM]) {
         const bool plain = samples_ok && c0 + CFG::CH <= n; // no row or column of this chunk needs masking
         // Everything derived from the thread index is derived afresh here, from a copy the compiler cannot see
         // through: otherwise it hoists the dozens of LDS addresses below out of the sweep, runs out of
@@ -594,49 +573,40 @@ sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
         asm volatile("" : "+v"(tid));
         const int lane = tid & 63;
         const bool odd = lane & 1;
-        int col[2];
-        bool ok[2];
+        const int col = (tid >> 6) * 32 + (tid & 31);
+        const bool ok = ts * CFG::RES + col < B;
+        // does any sample of this wavefront have its label inside the chunk?
+        const bool mine = tp >= c0 && tp < c0 + CFG::CH;
+        const bool any_target = __builtin_amdgcn_ballot_w64(mine) != 0;
 #pragma unroll
-        for (int fn = 0; fn < 2; ++fn) {
-            col[fn] = (tid >> 6) * 64 + fn * 32 + (tid & 31);
-            ok[fn] = ts * CFG::RES + col[fn] < B;
-        }
+        for (int fm = 0; fm < CFG::FM; ++fm)
 #pragma unroll
-        for (int fn = 0; fn < 2; ++fn) {
-            // does any sample of this wavefront have its label inside the chunk?  (about one chunk in three)
-            const bool mine = tp[fn] >= c0 && tp[fn] < c0 + CFG::CH;
-            const bool any_target = __builtin_amdgcn_ballot_w64(mine) != 0;
+            for (int r = 0; r < 16; r += 2) {
+                float d[2];
 #pragma unroll
-            for (int fm = 0; fm < CFG::FM; ++fm)
+                for (int e = 0; e < 2; ++e) d[e] = __builtin_amdgcn_exp2f(fmaf(acc[fm][r + e], k1, k2));
+                if (any_target) {
 #pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    float d[2];
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) d[e] = __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r + e], k1, k2[fn]));
-                    if (any_target) {
-#pragma unroll
-                        for (int e = 0; e < 2; ++e)
-                            if (c0 + ks_soe_row(fm, r + e, lane) == tp[fn]) d[e] -= g;
-                    }
-                    if (!plain) {
-#pragma unroll
-                        for (int e = 0; e < 2; ++e)
-                            if (!ok[fn] || c0 + ks_soe_row(fm, r + e, lane) >= n) d[e] = 0.f;
-                    }
-                    // neighbouring lanes (samples 2j, 2j+1) trade so that each holds two adjacent samples of one
-                    // class row: the even lane ends up with row r, the odd lane with row r+1
-                    const float send = odd ? d[0] : d[1];
-                    const float recv =
-                        __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0xB1, 0xF, 0xF, true));
-                    const uint32_t packed = odd ? ks_pack_bf2(recv, d[1]) : ks_pack_bf2(d[0], recv);
-                    const int row = ks_soe_row(fm, r + (odd ? 1 : 0), lane);
-                    *(uint32_t *)(stage + row * STAGE_LD + (col[fn] & ~1)) = packed;
+                    for (int e = 0; e < 2; ++e)
+                        if (c0 + ks_soe_row(fm, r + e, lane) == tp) d[e] -= g;
                 }
-        }
+                if (!plain) {
+#pragma unroll
+                    for (int e = 0; e < 2; ++e)
+                        if (!ok || c0 + ks_soe_row(fm, r + e, lane) >= n) d[e] = 0.f;
+                }
+                // neighbouring lanes (samples 2j, 2j+1) trade so that each holds two adjacent samples of one
+                // class row: the even lane ends up with row r, the odd lane with row r+1
+                const float send = odd ? d[0] : d[1];
+                const float recv = __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0xB1, 0xF, 0xF, true));
+                const uint32_t packed = odd ? ks_pack_bf2(recv, d[1]) : ks_pack_bf2(d[0], recv);
+                const int row = ks_soe_row(fm, r + (odd ? 1 : 0), lane);
+                *(uint32_t *)(stage + row * STAGE_LD + (col & ~1)) = packed;
+            }
         __builtin_amdgcn_s_waitcnt(0xC07F); // LDS writes done (lgkmcnt 0); loads in flight are left alone
         ks_barrier_nofence();
         const int chunks = rows_here * (CFG::RES / 8);
-        for (int q = tid; q < chunks; q += 256) {
+        for (int q = tid; q < chunks; q += CFG::NT) {
             const int row = q / (CFG::RES / 8), ch = q % (CFG::RES / 8);
             *(uint4 *)(dZT + (int64_t)(c0 + row) * Bp + ts * CFG::RES + ch * 8) = *(const uint4 *)(stage + row * STAGE_LD + ch * 8);
         }
@@ -656,13 +626,17 @@ sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
 // The reference only shifts the exponent range: results are the same function of the inputs as long as no
 // exponential overflows and not all of a sample's vanish, which the combine kernel checks.
 // ------------------------------------------------------------------------------------------------
+// The sweep runs on the eight-wavefront engine (ks_gemm_soe8.h): wavefront w owns samples [32 w, 32 w + 32) of the
+// tile and two wavefronts share a SIMD, so the exponentials, the LDS writes and the copy-out of one overlap with
+// the MFMAs of the other (measured on the headline shape: 34 us against 40 us with four wavefronts of 64 samples).
 template <int KT>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(512)
 sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, const int32_t *__restrict__ active_idx,
-                    const int32_t *__restrict__ n_active_p, int B, int Bp, int D, int M, int tiles_s, float scale,
-                    float *__restrict__ pl, uint16_t *__restrict__ dZT) {
+                     const int32_t *__restrict__ n_active_p, int B, int Bp, int D, int M, int tiles_s, float scale,
+                     float *__restrict__ pl, uint16_t *__restrict__ dZT) {
     typedef KsSoe<KT, 96, SOE_STAGES, 2> CFG;
     constexpr int STAGE_LD = CFG::RES + 8;
+    constexpr int NT = CFG::NT;
     __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
     __shared__ int32_t s_lidx[SM_LIDX_CAP];
     __shared__ __attribute__((aligned(16))) uint16_t stage[CFG::CH * STAGE_LD];
@@ -675,77 +649,63 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
     const int s0 = slab * h, s1 = (s0 + h < n64) ? s0 + h : n64;
     if (slab >= slabs || s0 >= s1) return;
     const int lim = n < s1 ? n : s1; // rows of this slab that are real classes
-    __shared__ float s_sum[8 * 256]; // thread t: running sums of its eight samples over its rows, at [c * 256 + t]
+    __shared__ float s_sum[8 * NT];  // thread t: running sums of its eight samples over its rows, at [c * NT + t]
 #pragma unroll
-    for (int c = 0; c < 8; ++c) s_sum[c * 256 + threadIdx.x] = 0.f;
-    // exp(scale * acc - scale) = exp2(fma(acc, k1, -k1))
-    const float k1 = scale * 1.4426950408889634f;
+    for (int c = 0; c < 8; ++c) s_sum[c * NT + threadIdx.x] = 0.f;
+    const float k1 = scale * 1.4426950408889634f; // exp(scale * acc - scale) = exp2(fma(acc, k1, -k1))
     const bool samples_ok = (ts + 1) * CFG::RES <= B;
-    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM][2]) {
+    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM]) {
         const bool plain = samples_ok && c0 + CFG::CH <= lim; // no row or column of this chunk needs masking
-        // Everything derived from the thread index is derived afresh here, from a copy the compiler cannot see
-        // through: otherwise it hoists the dozens of LDS addresses below out of the sweep, runs out of
-        // registers and spills them -- and every reload of a spilled value is a vector-memory load whose wait
-        // also waits for the stream loads in flight.
+        // thread-index arithmetic is redone here behind a copy the compiler cannot see through, so that it does not
+        // hoist the LDS addresses out of the sweep and spill them
         int tid = threadIdx.x;
         asm volatile("" : "+v"(tid));
         const int lane = tid & 63;
         const bool odd = lane & 1;
-        int col[2];
-        bool ok[2];
+        const int col = (tid >> 6) * 32 + (tid & 31);
+        const bool ok = ts * CFG::RES + col < B;
 #pragma unroll
-        for (int fn = 0; fn < 2; ++fn) {
-            col[fn] = (tid >> 6) * 64 + fn * 32 + (tid & 31);
-            ok[fn] = ts * CFG::RES + col[fn] < B;
-        }
+        for (int fm = 0; fm < CFG::FM; ++fm)
 #pragma unroll
-        for (int fn = 0; fn < 2; ++fn) {
+            for (int r = 0; r < 16; r += 2) {
+                float d[2];
 #pragma unroll
-            for (int fm = 0; fm < CFG::FM; ++fm)
+                for (int e = 0; e < 2; ++e) d[e] = __builtin_amdgcn_exp2f(fmaf(acc[fm][r + e], k1, -k1));
+                if (!plain) {
 #pragma unroll
-                for (int r = 0; r < 16; r += 2) {
-                    float d[2];
-#pragma unroll
-                    for (int e = 0; e < 2; ++e) d[e] = __builtin_amdgcn_exp2f(fmaf(acc[fm][fn][r + e], k1, -k1));
-                    if (!plain) {
-#pragma unroll
-                        for (int e = 0; e < 2; ++e)
-                            if (!ok[fn] || c0 + ks_soe_row(fm, r + e, lane) >= lim) d[e] = 0.f;
-                    }
-                    // neighbouring lanes (samples 2j, 2j+1) trade so that each holds two adjacent samples of one
-                    // class row: the even lane ends up with row r, the odd lane with row r+1
-                    const float send = odd ? d[0] : d[1];
-                    const float recv =
-                        __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0xB1, 0xF, 0xF, true));
-                    const uint32_t packed = odd ? ks_pack_bf2(recv, d[1]) : ks_pack_bf2(d[0], recv);
-                    const int row = ks_soe_row(fm, r + (odd ? 1 : 0), lane);
-                    *(uint32_t *)(stage + row * STAGE_LD + (col[fn] & ~1)) = packed;
+                    for (int e = 0; e < 2; ++e)
+                        if (!ok || c0 + ks_soe_row(fm, r + e, lane) >= lim) d[e] = 0.f;
                 }
-        }
+                // neighbouring lanes (samples 2j, 2j+1) trade so that each holds two adjacent samples of one class
+                // row: the even lane ends up with row r, the odd lane with row r+1
+                const float send = odd ? d[0] : d[1];
+                const float recv = __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0xB1, 0xF, 0xF, true));
+                const uint32_t packed = odd ? ks_pack_bf2(recv, d[1]) : ks_pack_bf2(d[0], recv);
+                const int row = ks_soe_row(fm, r + (odd ? 1 : 0), lane);
+                *(uint32_t *)(stage + row * STAGE_LD + (col & ~1)) = packed;
+            }
         __builtin_amdgcn_s_waitcnt(0xC07F); // LDS writes done (lgkmcnt 0); loads in flight are left alone
     };
-    // second half of the epilogue, run one stage into the next chunk (a workgroup barrier has passed since
-    // the writes above): copy the chunk out in 16-byte pieces: thread t always takes the same eight samples (piece t % 32 of a
-        // row) of the rows t / 32, t / 32 + 8, ..., so it can also carry the sums over the class rows of those
-        // samples -- of the rounded values, as the two gradient contractions will read them
+    // second half, one stage into the next chunk: copy the chunk out in 16-byte pieces; thread t always takes the
+    // same eight samples (piece t % 32 of a row) of rows t / 32, t / 32 + 16, ..., and carries their sums
     auto post = [&](int c0, int rows_here) {
         int tid = threadIdx.x;
         asm volatile("" : "+v"(tid));
-        constexpr int PPR = CFG::RES / 8; // pieces per row
+        constexpr int PPR = CFG::RES / 8, RPP = NT / PPR; // pieces per row, rows per pass
         const int ch = tid % PPR;
         float l[8];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) l[c] = s_sum[c * 256 + tid];
-        for (int r0 = tid / PPR; r0 < rows_here; r0 += 4 * (256 / PPR)) {
-            uint4 v[4];
+        for (int c = 0; c < 8; ++c) l[c] = s_sum[c * NT + tid];
+        for (int r0 = tid / PPR; r0 < rows_here; r0 += 3 * RPP) {
+            uint4 v[3];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int row = r0 + u * (256 / PPR);
+            for (int u = 0; u < 3; ++u) {
+                const int row = r0 + u * RPP;
                 v[u] = (row < rows_here) ? *(const uint4 *)(stage + row * STAGE_LD + ch * 8) : make_uint4(0u, 0u, 0u, 0u);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int row = r0 + u * (256 / PPR);
+            for (int u = 0; u < 3; ++u) {
+                const int row = r0 + u * RPP;
                 if (row < rows_here) *(uint4 *)(dZT + (int64_t)(c0 + row) * Bp + ts * CFG::RES + ch * 8) = v[u];
                 const uint32_t w4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
@@ -756,23 +716,24 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
             }
         }
 #pragma unroll
-        for (int c = 0; c < 8; ++c) s_sum[c * 256 + tid] = l[c];
+        for (int c = 0; c < 8; ++c) s_sum[c * NT + tid] = l[c];
     };
     ks_soe_sweep<CFG>(X, D, ts * CFG::RES, B, W, D, active_idx, s0, s1, n, lds, epi, s_lidx, SM_LIDX_CAP, post);
     __syncthreads();
-    // the eight row groups of a sample meet through LDS (the stream stages are free now): red[group][sample]
+    // the sixteen row groups of a sample meet through LDS (the stream stages are free now): red[group][sample]
     float *red = (float *)lds;
+    static_assert(CFG::LDS_ELEMS * 2 >= (NT / (CFG::RES / 8)) * CFG::RES * 4, "reduction buffer");
     {
         const int grp = threadIdx.x / (CFG::RES / 8), ch = threadIdx.x % (CFG::RES / 8);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) red[grp * CFG::RES + ch * 8 + c] = s_sum[c * 256 + threadIdx.x];
+        for (int c = 0; c < 8; ++c) red[grp * CFG::RES + ch * 8 + c] = s_sum[c * NT + threadIdx.x];
     }
     __syncthreads();
-    {
-        const int i = ts * CFG::RES + threadIdx.x; // RES == blockDim.x: one sample per thread
+    if (threadIdx.x < CFG::RES) {
+        const int i = ts * CFG::RES + threadIdx.x;
         float sum = 0.f;
 #pragma unroll
-        for (int grp = 0; grp < 8; ++grp) sum += red[grp * CFG::RES + threadIdx.x];
+        for (int grp = 0; grp < NT / (CFG::RES / 8); ++grp) sum += red[grp * CFG::RES + threadIdx.x];
         if (i < B) pl[(int64_t)slab * Bp + i] = sum;
     }
 }
@@ -1332,7 +1293,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
         if (fused) {
             const int grid = SM_SOE_GRID / tiles_s * tiles_s, slabs = grid / tiles_s;
 #define SM_FUSED_LAUNCH(KT)                                                                                               \
-    hipLaunchKernelGGL(sm_fused_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active, B, w.Bp, D, Mi,  \
+    hipLaunchKernelGGL(sm_fused_soe_kernel<KT>, dim3(grid), dim3(512), 0, st, X, W, active_idx, n_active, B, w.Bp, D, Mi,  \
                        tiles_s, scale, w.pl, w.dZT)
             if (mode != SM_IMPORT) { // the first call of a split has left the exponentials in the workspace
                 if (D == 512) SM_FUSED_LAUNCH(8);
@@ -1354,7 +1315,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
 #define SM_SOE_LAUNCH(KT)                                                                                                 \
     do {                                                                                                                  \
         if (mode != SM_IMPORT) {                                                                                          \
-            hipLaunchKernelGGL(sm_stats_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active,         \
+            hipLaunchKernelGGL(sm_stats_soe_kernel<KT>, dim3(grid), dim3(512), 0, st, X, W, active_idx, n_active,         \
                                target_pos, B, w.Bp, D, Mi, tiles_s, scale, w.pm, w.pl, w.zt);                              \
             mark(2);                                                                                                      \
             hipLaunchKernelGGL(sm_combine_soe_kernel, dim3((unsigned)ks_ceil_div(B, SM_NT / 64)), dim3(SM_NT), 0, st,     \
@@ -1362,7 +1323,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
             mark(3);                                                                                                      \
         }                                                                                                                 \
         if (mode != SM_EXPORT)                                                                                            \
-            hipLaunchKernelGGL(sm_grad_soe_kernel<KT>, dim3(grid), dim3(256), 0, st, X, W, active_idx, n_active,          \
+            hipLaunchKernelGGL(sm_grad_soe_kernel<KT>, dim3(grid), dim3(512), 0, st, X, W, active_idx, n_active,          \
                                target_pos, w.lse, B, w.Bp, D, Mi, tiles_s, scale, g, w.dZT);                               \
     } while (0)
             if (mode == SM_IMPORT)
