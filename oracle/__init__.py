@@ -1,4 +1,4 @@
-"""ctypes front-end of the CPU oracle (oracle/knn_softmax_oracle.c).
+"""ctypes front-end of the CPU oracle (oracle/knn_softmax_oracle.c, oracle/topk_oracle.c).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the benchmark's CPU-baseline
 leg.  The product package never imports this module, and this module never imports the product.
@@ -28,7 +28,7 @@ def lib():
                      "orc_full_softmax_fwd_bwd", "orc_apply_weight_grad", "orc_normalize_rows", "orc_norm_backward",
                      "orc_apply_weight_grad_normalized", "orc_graph_compress", "orc_pad_draws",
                      "orc_select_active_csr", "orc_graph_update", "orc_softmax_node_stats",
-                     "orc_softmax_node_bwd"):
+                     "orc_softmax_node_bwd", "orc_topk_abs", "orc_topk_dc", "orc_topk_group"):
             getattr(_lib, name).restype = ct.c_int
     return _lib
 
@@ -291,3 +291,45 @@ def combine_node_stats(stats):
     S = np.sum([l * np.exp(m - M) for m, l, _ in stats], axis=0)
     T = np.sum([t for _, _, t in stats], axis=0)
     return M, S, T
+
+
+def topk_abs(g, k: int):
+    """The k elements of largest magnitude of a tensor (Section 3.3.2), by definition: descending magnitude, equal
+    magnitudes in ascending index.  Returns (idx int32 [k], val fp32 [k])."""
+    g = _f32(g).ravel()
+    idx = np.empty(k, dtype=np.int32)
+    val = np.empty(k, dtype=np.float32)
+    rc = lib().orc_topk_abs(_p(g, ct.c_float), ct.c_int64(g.size), ct.c_int(k), _p(idx, ct.c_int32), _p(val, ct.c_float))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_topk_abs: {rc}")
+    return idx, val
+
+
+def topk_dc(g, k: int, M: int):
+    """The same selection by the paper's two steps: top-k of each of M chunks, then top-k of the survivors."""
+    g = _f32(g).ravel()
+    idx = np.empty(k, dtype=np.int32)
+    val = np.empty(k, dtype=np.float32)
+    rc = lib().orc_topk_dc(_p(g, ct.c_float), ct.c_int64(g.size), ct.c_int(k), ct.c_int(M), _p(idx, ct.c_int32),
+                           _p(val, ct.c_float))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_topk_dc: {rc}")
+    return idx, val
+
+
+def topk_group(g, offsets, k, M=None):
+    """Layer-wise selection over tensors stored back to back; M=None: by definition, else chunks per tensor.
+    Returns (idx int32 [sum k], val fp32 [sum k]); tensor t's part starts at sum(k[:t])."""
+    g = _f32(g).ravel()
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    k = _i32(k)
+    T = k.size
+    Ma = None if M is None else _i32(M)
+    total = int(k.sum())
+    idx = np.empty(total, dtype=np.int32)
+    val = np.empty(total, dtype=np.float32)
+    rc = lib().orc_topk_group(_p(g, ct.c_float), _p(offsets, ct.c_int64), _p(k, ct.c_int32), _p(Ma, ct.c_int32), ct.c_int(T),
+                              _p(idx, ct.c_int32), _p(val, ct.c_float))
+    if rc != ORC_OK:
+        raise ValueError(f"orc_topk_group: {rc}")
+    return idx, val

@@ -7,14 +7,15 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "knn_softmax_oracle.c")
+SRCS = [SRC, os.path.join(HERE, "topk_oracle.c")]
 LIB = os.path.join(HERE, "liboracle.so")
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(os.path.getmtime(p) for p in SRCS):
         return LIB
     cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
-           "-ffp-contract=off", "-o", LIB, SRC, "-lm"]
+           "-ffp-contract=off", "-o", LIB] + SRCS + ["-lm"]
     subprocess.check_call(cmd)
     return LIB
 

@@ -291,3 +291,55 @@ def make_WX(cfg: dict, seed: int | None = None):
     W = unit_rows(seed, TID_W, cfg["C"], cfg["D"], bf16=cfg["bf16"])
     X = unit_rows(seed, TID_X, cfg["B"], cfg["D"], bf16=cfg["bf16"])
     return W, X
+
+
+# ---------------------------------------------------------------------------------------------
+# inputs of the layer-wise top-k sparsification (Section 3.3): a set of gradient tensors with the
+# sizes of a ResNet-50's parameters (the feature-extraction net of the paper's experiments)
+# ---------------------------------------------------------------------------------------------
+TID_GRAD_SET = 20
+
+
+def resnet50_tensor_sizes(num_classes: int = 1000) -> list[int]:
+    """Element counts of the parameter tensors of a ResNet-50 (convolutions, batch-norm scale and shift,
+    classifier), in network order: 161 tensors, 25,557,032 elements for 1,000 classes."""
+    sizes = [64 * 3 * 7 * 7, 64, 64]
+    inplanes = 64
+    for planes, blocks in ((64, 3), (128, 4), (256, 6), (512, 3)):
+        for b in range(blocks):
+            sizes += [planes * inplanes, planes, planes]          # 1x1 reduce + bn
+            sizes += [planes * planes * 9, planes, planes]         # 3x3 + bn
+            sizes += [4 * planes * planes, 4 * planes, 4 * planes]  # 1x1 expand + bn
+            if b == 0:
+                sizes += [4 * planes * inplanes, 4 * planes, 4 * planes]  # projection shortcut + bn
+            inplanes = 4 * planes
+    sizes += [num_classes * 2048, num_classes]
+    return sizes
+
+
+def grad_tensor_set(seed: int, sizes, zero_every: int = 5) -> tuple[np.ndarray, np.ndarray]:
+    """(flat fp32 array holding the tensors back to back, int64 offsets [T + 1]).  Tensor t is N(0, s_t^2) with
+    s_t = 1e-3 * 2^(t mod 7 - 3); every `zero_every`-th tensor has its second eighth set to exactly zero and
+    its third eighth rounded to multiples of s_t / 4 (dead units and repeated values: ties)."""
+    offs = np.zeros(len(sizes) + 1, dtype=np.int64)
+    offs[1:] = np.cumsum(np.asarray(sizes, dtype=np.int64))
+    total = int(offs[-1])
+    g = np.empty(total, dtype=np.float32)
+    step = 1 << 22
+    for s0 in range(0, total, step):
+        s1 = min(total, s0 + step)
+        g[s0:s1] = normal(seed, TID_GRAD_SET, s0, s1 - s0).astype(np.float32)
+    for t, n in enumerate(sizes):
+        a, sc = int(offs[t]), np.float32(1e-3 * 2.0 ** (t % 7 - 3))
+        g[a:a + n] *= sc
+        if zero_every and t % zero_every == 0 and n >= 8:
+            e = n // 8
+            g[a + e:a + 2 * e] = 0.0
+            q = sc / np.float32(4)
+            g[a + 2 * e:a + 3 * e] = np.round(g[a + 2 * e:a + 3 * e] / q) * q
+    return g, offs
+
+
+def topk_counts(sizes, density: float = 1e-3) -> np.ndarray:
+    """k per tensor at the given density (99.9 % sparsity by default), at least 1."""
+    return np.maximum(1, np.floor(np.asarray(sizes, dtype=np.float64) * density)).astype(np.int32)
