@@ -1,0 +1,68 @@
+/*
+ * grad_topk.h -- C ABI of the layer-wise top-k selection for gradient sparsification on one MI355X (gfx950).
+ *
+ * Method: "Large-Scale Training System for 100-Million Classification at Alibaba" (KDD'20), Section 3.3.2
+ * "Efficient layer-wise top-k sparsification" and its figure on divide-and-conquer top-k selection: the top-k
+ * of a large gradient tensor is found exactly in two steps -- the tensor is cut into M chunks whose top-k are
+ * taken side by side, then the top-k of the M*k survivors -- and tensors are grouped so that one launch serves
+ * many layers.  Part of the same shared library as knnsoftmax.h; the conventions stated there hold here too
+ * (device pointers unless marked HOST, caller-owned memory, nothing allocated, calls only enqueue work on
+ * `stream`, ks_status return values).
+ *
+ * Definition of the result (what the paper leaves open is fixed as follows).  Of tensor t, the k[t] elements
+ * of largest magnitude |g|, magnitudes compared as the 31-bit patterns of |g| (the numeric order for finite
+ * values and infinities; NaN patterns rank above infinity; +0 and -0 are equal); among equal magnitudes the
+ * lowest index wins.  They are emitted in descending magnitude, equal magnitudes in ascending index, so the
+ * output is unique and independent of M.
+ */
+#ifndef GRAD_TOPK_H
+#define GRAD_TOPK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KS_TOPK_MAX_K 4096 /* largest k per tensor */
+
+/* ------------------------------------------------------------------------------------------------------
+ * grad_topk_plan -- host-side planning for a group of T tensors stored back to back (Section 3.3.2: "grouping
+ * tensors"): picks the number of chunks M[t] of every tensor and lays out the survivors' buffer.  No device
+ * work.  The plan depends only on the sizes, so it is made once per model.
+ *
+ *   offsets  HOST [T + 1]  tensor t is g[offsets[t] .. offsets[t+1]) of the flat gradient array; ascending,
+ *                          every tensor has 1 <= n[t] < 2^31 elements
+ *   k        HOST [T]      elements to select from tensor t, 1 <= k[t] <= min(n[t], KS_TOPK_MAX_K)
+ *   chunks   0: M[t] = round(sqrt(n[t] / k[t])) (both steps then select from about sqrt(n k) elements), limited so
+ *            that a chunk has at least 8,192 elements and M[t] <= 256;  > 0: M[t] = min(chunks, n[t]) for every
+ *            tensor (for tests and sweeps); chunks are consecutive ranges of ceil(n / M) elements
+ *   plan     HOST [plan_capacity] out, may be NULL: the plan, a flat int64 array that the caller also copies to
+ *            device memory as it is
+ * Returns the number of int64 words of the plan (written only if plan != NULL and plan_capacity suffices), or
+ * the negative of a ks_status for bad arguments.
+ * ---------------------------------------------------------------------------------------------------- */
+int64_t grad_topk_plan(const int64_t *offsets, const int32_t *k, int T, int chunks, int64_t *plan, int64_t plan_capacity);
+
+/* Bytes of device workspace grad_topk_select needs for this plan (HOST pointer); 0 for a plan it does not accept. */
+size_t grad_topk_workspace(const int64_t *plan_host);
+
+/* ------------------------------------------------------------------------------------------------------
+ * grad_topk_select -- Section 3.3.2: the selection itself, two launches for the whole group (step 1: one
+ * workgroup per chunk of every tensor; step 2: one workgroup per tensor).
+ *
+ *   g          [offsets[T]]  the gradient tensors, fp32, back to back as planned (4-byte aligned is enough)
+ *   plan_dev   the plan in device memory;  plan_host  HOST: the same words (launch geometry is read from it)
+ *   out_idx    [sum k]  out: indices within the tensor; tensor t's part starts at sum(k[0..t))
+ *   out_val    [sum k]  out: the signed values g[idx]
+ * Returns KS_INVALID_ARG for NULL pointers or a plan that was not produced by grad_topk_plan,
+ * KS_WORKSPACE_TOO_SMALL, KS_HIP_ERROR.
+ * ---------------------------------------------------------------------------------------------------- */
+int grad_topk_select(const float *g, const int64_t *plan_dev, const int64_t *plan_host, int32_t *out_idx, float *out_val,
+                     void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -24,7 +24,7 @@ EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_se
            "apply_weight_grad_normalized", "knn_graph_compress_workspace", "knn_graph_compress",
            "knn_select_active_csr_workspace", "knn_select_active_csr", "knn_graph_update_workspace", "knn_graph_update",
            "knn_softmax_split_workspace", "knn_softmax_fwd_stats", "knn_softmax_bwd_from_stats",
-           "knn_softmax_fwd_bwd_update")
+           "knn_softmax_fwd_bwd_update", "grad_topk_plan", "grad_topk_workspace", "grad_topk_select")
 
 
 class KsError(RuntimeError):
@@ -50,6 +50,8 @@ def lib():
         for name in EXPORTS:
             if name.endswith("_workspace"):
                 getattr(L, name).restype = ct.c_size_t
+            elif name == "grad_topk_plan":
+                L.grad_topk_plan.restype = ct.c_int64
             elif name != "ks_version":
                 getattr(L, name).restype = ct.c_int
         _LIB = L
@@ -507,3 +509,58 @@ def knn_softmax_bwd_from_stats(W_bf16, X_bf16, active_idx, n_active, target_pos,
                                           ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
     _check("knn_softmax_bwd_from_stats", rc)
     return out
+
+
+# ---------------------------------------------------------------------------------------------------
+# layer-wise top-k selection for gradient sparsification (include/grad_topk.h)
+# ---------------------------------------------------------------------------------------------------
+class GradTopkPlan:
+    """Plan of grad_topk_select for a group of tensors: the host words and their copy in device memory."""
+
+    def __init__(self, host, device):
+        self.host = host        # numpy int64, the words written by grad_topk_plan
+        self.dev = torch.from_numpy(host).to(device)
+        self.T = int(host[1])
+        self.n_chunk_workgroups = int(host[2])
+        self.n_out = int(host[4])
+        self.ws_bytes = int(lib().grad_topk_workspace(host.ctypes.data_as(ct.c_void_p)))
+
+    def chunks(self):
+        """M of every tensor."""
+        return [int(self.host[8 + 8 * t + 3]) for t in range(self.T)]
+
+
+def grad_topk_plan(offsets, k, chunks=0, device="cuda") -> GradTopkPlan:
+    import numpy as np
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    k = np.ascontiguousarray(k, dtype=np.int32)
+    T = int(k.size)
+    if offsets.size != T + 1:
+        raise ValueError("offsets must have one more entry than k")
+    args = (offsets.ctypes.data_as(ct.c_void_p), k.ctypes.data_as(ct.c_void_p), ct.c_int(T), ct.c_int(chunks))
+    words = int(lib().grad_topk_plan(*args, ct.c_void_p(0), ct.c_int64(0)))
+    if words < 0:
+        raise KsError("grad_topk_plan", -words)
+    host = np.zeros(words, dtype=np.int64)
+    got = int(lib().grad_topk_plan(*args, host.ctypes.data_as(ct.c_void_p), ct.c_int64(words)))
+    if got != words:
+        raise KsError("grad_topk_plan", -got if got < 0 else KS_INVALID_ARG)
+    return GradTopkPlan(host, device)
+
+
+def grad_topk_select(g, plan: GradTopkPlan, out_idx=None, out_val=None, ws=None, stream=None):
+    """Top-k by magnitude of every tensor of the group (two launches).  Returns (idx int32 [sum k], val fp32 [sum k])."""
+    _need(g, torch.float32, "g")
+    if out_idx is None:
+        out_idx = torch.empty(plan.n_out, dtype=torch.int32, device=g.device)
+    if out_val is None:
+        out_val = torch.empty(plan.n_out, dtype=torch.float32, device=g.device)
+    _need(out_idx, torch.int32, "out_idx")
+    _need(out_val, torch.float32, "out_val")
+    if g.numel() < int(plan.host[5]) or out_idx.numel() < plan.n_out or out_val.numel() < plan.n_out:
+        raise ValueError("g, out_idx or out_val is smaller than the plan requires")
+    ws = _ws(plan.ws_bytes, g.device, ws)
+    _check("grad_topk_select", lib().grad_topk_select(_ptr(g), _ptr(plan.dev), plan.host.ctypes.data_as(ct.c_void_p),
+                                                      _ptr(out_idx), _ptr(out_val), _ptr(ws), ct.c_size_t(ws.numel()),
+                                                      _stream(stream)))
+    return out_idx, out_val

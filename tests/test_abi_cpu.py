@@ -21,15 +21,16 @@ def ks():
 
 
 def _declared_functions():
-    src = open(HEADER).read()
+    src = open(HEADER).read() + open(os.path.join(ROOT, "include", "grad_topk.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update|_stats|_profiled))\s*\(", src)))
+    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update|_stats|_profiled|_plan|_select))\s*\(", src)))
 
 
 def test_header_symbols_are_exported(ks):
     names = _declared_functions()
     assert {"knn_graph_build", "knn_softmax_fwd_bwd", "apply_weight_grad", "apply_weight_grad_normalized",
-            "knn_normalize_rows", "knn_norm_backward_rows"} <= set(names)
+            "knn_normalize_rows", "knn_norm_backward_rows", "grad_topk_plan", "grad_topk_workspace",
+            "grad_topk_select"} <= set(names)
     L = ks.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in the header but not exported"
@@ -164,3 +165,69 @@ def test_product_never_imports_the_oracle():
             if fn.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "oracle" not in text.lower(), f"{fn} mentions the oracle"
+
+
+# ------------------------------------------------------------------------------------------------
+# planning of the layer-wise top-k selection (host logic of include/grad_topk.h)
+# ------------------------------------------------------------------------------------------------
+def _plan(ks, sizes, k, chunks=0):
+    import numpy as np
+    offs = np.zeros(len(sizes) + 1, dtype=np.int64)
+    offs[1:] = np.cumsum(sizes)
+    k = np.asarray(k, dtype=np.int32)
+    L = ks.lib()
+    args = (offs.ctypes.data_as(ct.c_void_p), k.ctypes.data_as(ct.c_void_p), ct.c_int(len(sizes)), ct.c_int(chunks))
+    words = L.grad_topk_plan(*args, ct.c_void_p(0), ct.c_int64(0))
+    if words < 0:
+        return words, None
+    plan = np.zeros(words, dtype=np.int64)
+    assert L.grad_topk_plan(*args, plan.ctypes.data_as(ct.c_void_p), ct.c_int64(words)) == words
+    return words, plan
+
+
+def test_topk_plan_layout(ks):
+    import synth
+    sizes = synth.resnet50_tensor_sizes()
+    k = synth.topk_counts(sizes)
+    words, plan = _plan(ks, sizes, k)
+    T = len(sizes)
+    assert plan[1] == T and plan[4] == k.sum() and plan[5] == sum(sizes)
+    rec = plan[8:8 + 8 * T].reshape(T, 8)
+    begin, n, kk, M, chunk, cand_off, out_off, kc = rec.T
+    assert (n == sizes).all() and (kk == k).all() and (begin == [0] + list(__import__("numpy").cumsum(sizes)[:-1])).all()
+    assert ((M - 1) * chunk < n).all() and (M * chunk >= n).all()          # M chunks, none empty
+    assert (M[n < 16384] == 1).all() and M.max() <= 256 and (chunk[M > 1] >= 8192).all()
+    big = n == 512 * 512 * 9                                              # n / k = 1000: about 32 chunks
+    assert ((M[big] >= 30) & (M[big] <= 33)).all()
+    assert (kc == __import__("numpy").minimum(kk, chunk)).all()
+    assert (out_off == [0] + list(__import__("numpy").cumsum(k)[:-1])).all()
+    assert (cand_off[1:] == __import__("numpy").cumsum(M * kc)[:-1]).all() and plan[3] == (M * kc).sum()
+    # the table of step-1 workgroups lists every (tensor, chunk) once, in order
+    W1 = int(plan[2])
+    assert W1 == M.sum() and words == 8 + 8 * T + W1
+    table = plan[8 + 8 * T:]
+    want = [(t << 32) | j for t in range(T) for j in range(int(M[t]))]
+    assert table.tolist() == want
+    assert ks.lib().grad_topk_workspace(plan.ctypes.data_as(ct.c_void_p)) >= int(plan[3]) * 8
+    # forced chunk counts
+    _, p2 = _plan(ks, [100, 10_000], [5, 10], chunks=7)
+    assert p2[8 + 3] == 7 and p2[8 + 4] == 15 and p2[16 + 3] == 7 and p2[16 + 4] == 1429
+    _, p3 = _plan(ks, [5], [5], chunks=64)
+    assert p3[8 + 3] == 5 and p3[8 + 4] == 1 and p3[8 + 7] == 1
+
+
+def test_topk_argument_errors(ks):
+    assert _plan(ks, [10], [0])[0] == -ks.KS_INVALID_ARG          # k < 1
+    assert _plan(ks, [10], [11])[0] == -ks.KS_INVALID_ARG         # k > n
+    assert _plan(ks, [10, 0], [1, 1])[0] == -ks.KS_INVALID_ARG    # an empty tensor
+    assert _plan(ks, [100_000], [5000])[0] == -ks.KS_UNSUPPORTED  # k beyond the limit
+    L = ks.lib()
+    import numpy as np
+    junk = np.zeros(64, dtype=np.int64)
+    assert L.grad_topk_workspace(junk.ctypes.data_as(ct.c_void_p)) == 0
+    one = ct.c_void_p(256)
+    assert L.grad_topk_select(one, one, junk.ctypes.data_as(ct.c_void_p), one, one, one, ct.c_size_t(1 << 20), None) == ks.KS_INVALID_ARG
+    _, plan = _plan(ks, [100_000], [100])
+    ph = plan.ctypes.data_as(ct.c_void_p)
+    assert L.grad_topk_select(None, one, ph, one, one, one, ct.c_size_t(1 << 20), None) == ks.KS_INVALID_ARG
+    assert L.grad_topk_select(one, one, ph, one, one, one, ct.c_size_t(8), None) == ks.KS_WORKSPACE_TOO_SMALL

@@ -9,13 +9,6 @@ import pytest
 import synth
 
 
-@pytest.fixture(scope="module")
-def orc():
-    import oracle
-    oracle.lib()
-    return oracle
-
-
 def _argsort_topk(g, k):
     # library routine: a stable sort of -|g| keeps equal magnitudes in ascending index
     order = np.argsort(-np.abs(g.astype(np.float64)), kind="stable")[:k]
