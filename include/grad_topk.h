@@ -29,19 +29,24 @@ extern "C" {
 
 /* ------------------------------------------------------------------------------------------------------
  * grad_topk_plan -- host-side planning for a group of T tensors stored back to back (Section 3.3.2: "grouping
- * tensors"): picks the number of chunks M[t] of every tensor and lays out the survivors' buffer.  No device
- * work.  The plan depends only on the sizes, so it is made once per model.
+ * tensors"): cuts every tensor into chunks and lays out the selection steps and the survivors' buffer.  No
+ * device work.  The plan depends only on the sizes, so it is made once per model.
  *
  *   offsets  HOST [T + 1]  tensor t is g[offsets[t] .. offsets[t+1]) of the flat gradient array; ascending,
  *                          every tensor has 1 <= n[t] < 2^31 elements
  *   k        HOST [T]      elements to select from tensor t, 1 <= k[t] <= min(n[t], KS_TOPK_MAX_K)
- *   chunks   0: M[t] = round(sqrt(n[t] / k[t])) (both steps then select from about sqrt(n k) elements), limited so
- *            that a chunk has at least 8,192 elements and M[t] <= 256;  > 0: M[t] = min(chunks, n[t]) for every
+ *   chunks   0: tensor t is cut into M[t] = ceil(n[t] / 32,768) chunks;  > 0: M[t] = min(chunks, n[t]) for every
  *            tensor (for tests and sweeps); chunks are consecutive ranges of ceil(n / M) elements
  *   plan     HOST [plan_capacity] out, may be NULL: the plan, a flat int64 array that the caller also copies to
  *            device memory as it is
+ * The paper's method has two steps (top-k of every chunk, then top-k of the M*k survivors).  Here one workgroup
+ * performs one selection, and no selection gets more than 32,768 items: where M * k exceeds that, the survivors
+ * are first reduced in groups of floor(32,768 / k) chunks, and so on -- a tree of exact selections with the
+ * paper's two steps as its smallest case, one launch per level for the whole group of tensors.
  * Returns the number of int64 words of the plan (written only if plan != NULL and plan_capacity suffices), or
- * the negative of a ks_status for bad arguments.
+ * the negative of a ks_status for bad arguments.  Plan words a caller may read: [1] = T, [2] = selections
+ * (workgroups) in all, [3] = survivors' buffer in 8-byte words, [4] = sum of k, [5] = elements in all,
+ * [6] = levels (launches per call); per tensor t at [32 + 4 t]: n, k, chunks, levels.
  * ---------------------------------------------------------------------------------------------------- */
 int64_t grad_topk_plan(const int64_t *offsets, const int32_t *k, int T, int chunks, int64_t *plan, int64_t plan_capacity);
 
@@ -49,8 +54,9 @@ int64_t grad_topk_plan(const int64_t *offsets, const int32_t *k, int T, int chun
 size_t grad_topk_workspace(const int64_t *plan_host);
 
 /* ------------------------------------------------------------------------------------------------------
- * grad_topk_select -- Section 3.3.2: the selection itself, two launches for the whole group (step 1: one
- * workgroup per chunk of every tensor; step 2: one workgroup per tensor).
+ * grad_topk_select -- Section 3.3.2: the selection itself, one launch per level of the plan for the whole group
+ * (first level: one workgroup per chunk of every tensor; last level of a tensor: one workgroup that writes its
+ * output).
  *
  *   g          [offsets[T]]  the gradient tensors, fp32, back to back as planned (4-byte aligned is enough)
  *   plan_dev   the plan in device memory;  plan_host  HOST: the same words (launch geometry is read from it)

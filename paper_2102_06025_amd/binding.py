@@ -521,13 +521,18 @@ class GradTopkPlan:
         self.host = host        # numpy int64, the words written by grad_topk_plan
         self.dev = torch.from_numpy(host).to(device)
         self.T = int(host[1])
-        self.n_chunk_workgroups = int(host[2])
+        self.n_workgroups = int(host[2])   # selection steps over all levels
         self.n_out = int(host[4])
+        self.n_levels = int(host[6])       # launches per call
         self.ws_bytes = int(lib().grad_topk_workspace(host.ctypes.data_as(ct.c_void_p)))
 
     def chunks(self):
-        """M of every tensor."""
-        return [int(self.host[8 + 8 * t + 3]) for t in range(self.T)]
+        """Chunks of every tensor (the paper's M)."""
+        return [int(self.host[32 + 4 * t + 2]) for t in range(self.T)]
+
+    def steps(self):
+        """Selection steps every tensor goes through (2 = the paper's chunks + final selection)."""
+        return [int(self.host[32 + 4 * t + 3]) for t in range(self.T)]
 
 
 def grad_topk_plan(offsets, k, chunks=0, device="cuda") -> GradTopkPlan:

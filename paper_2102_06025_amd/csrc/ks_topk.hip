@@ -1,58 +1,177 @@
 // Layer-wise top-k selection for gradient sparsification (Section 3.3.2: divide-and-conquer top-k selection,
 // tensors grouped into one launch).
 //
-// Both steps of the method are the same workgroup-level routine, tk_select: the exact top-k of a list of items
-// that sits in global memory (step 1: a chunk of a gradient tensor; step 2: the survivors of all chunks of a
-// tensor).  An item is the 64-bit word  (bits of |g|) << 32 | (0xFFFFFFFF - index) : larger word = larger
-// magnitude, equal magnitudes ordered by ascending index, all words distinct, so "top-k" is unique.
+// Every step of the method is the same workgroup-level routine, tk_select: the exact top-k of a list of items that
+// sits in global memory (first step: a chunk of a gradient tensor; later steps: the survivors of several chunks).
+// An item is the 64-bit word  (bits of |g|) << 32 | (0xFFFFFFFF - index) : larger word = larger magnitude, equal
+// magnitudes ordered by ascending index, all words distinct, so "top-k" is unique and no step depends on the
+// order in which it finds its input.
 //
-// tk_select (512 threads):
-//   1. histogram of the top 11 bits of the magnitude (sign dropped: exponent and three mantissa bits) in LDS;
-//      a descending scan finds the bin b in which the k-th largest item falls;
-//   2. if the items above b plus the items in b fit the LDS sort array (8,192 words), they are all collected and
-//      sorted there (bitonic, descending): the first k words are the answer, already in output order.  For
-//      gradient-like data this is the path taken: the list is read twice (it sits in L2 after the first pass);
-//   3. otherwise the bin is refined by two more histogram passes over the next 11 and the last 9 bits, restricted
-//      to the items that share the prefix found so far, until the candidates fit -- or until the k-th magnitude
-//      itself is known exactly and still has too many equals (constant or mostly-zero tensors): then the items
-//      above it are collected, and of the equal ones the first in list order, which is ascending index order in
-//      both steps (the survivors of a chunk are stored sorted, chunks in order).
+// tk_select (1,024 threads) is a radix selection on the item word, most significant digits first:
+//   1. histogram of the current digit in LDS over the items that share the prefix found so far (first level:
+//      all items, on the 14 bits of exponent and leading mantissa, in the 64 KB of the still unused sort array;
+//      later levels 11 bits); a descending scan finds the bin in which the k-th largest item falls;
+//   2. as soon as the items above that bin and the items in it fit the LDS array (8,192 words) they are collected
+//      in one more pass over the list -- for gradient-like data after the first level, so the list is read twice;
+//   3. the selection goes on inside the boundary bin, now in LDS, down to the item that closes the top-k;
+//   4. a step that is not the last one of its tensor hands its survivors on unsorted; the last step orders its k
+//      survivors (buckets by an 11-bit digit, then ranks inside the buckets), which are the output.
+// Tensors with long runs of one magnitude (constant, mostly zero) are caught where they would hurt: wavefronts
+// merge their histogram adds when all lanes hit one bin, and a chunk whose k-th magnitude is shared by more items
+// than LDS holds takes the first of them in index order instead of resolving 32 index bits level by level.
+// The passes wait on memory (a workgroup has its list to itself) and on instruction issue, not on bandwidth:
+// 16-byte loads, the next batch requested before the current one is worked on, 32-bit arithmetic per item, and
+// a plan that cuts tensors so that no step has more than 32,768 items: a tensor of more than about 260,000
+// elements at k = 4,096 goes through more than the paper's two steps (a tree of selections instead of chunks +
+// one final selection), still without any approximation.
 // Everything is integer work: the result is bit-exact and deterministic.
+#include <vector>
 #include "ks_common.h"
 #include "../../include/grad_topk.h"
 
-#define TK_NT 512
+#define TK_NT 1024 /* one workgroup per compute unit: its passes wait on memory, and more threads have more loads in flight */
 #define TK_BINS 2048
 #define TK_CAP 8192
-#define TK_MIN_CHUNK 8192
-#define TK_MAX_AUTO_CHUNKS 256
+#define TK_LEAF 32768      /* largest chunk of a tensor */
+#define TK_NODE_CAP 32768  /* largest input of a later step */
+#define TK_MAX_LEVELS 12
 #define TK_MAGIC 0x6B706F74646172ll /* "gradtopk" cut to seven bytes */
-#define TK_HEADER 8
-#define TK_RECORD 8
+#define TK_HEADER (8 + 2 * TK_MAX_LEVELS)
+#define TK_TENSOR 4        /* words per tensor record: n, k, chunks, steps */
+#define TK_NODE 8          /* words per step ("node") record */
 
-// plan record of a tensor (int64 words)
-enum { TK_R_BEGIN = 0, TK_R_N, TK_R_K, TK_R_M, TK_R_CHUNK, TK_R_CAND_OFF, TK_R_OUT_OFF, TK_R_KC };
+// node record (int64 words)
+enum { TK_N_SRC = 0, TK_N_ITEMS, TK_N_K, TK_N_OUT, TK_N_FLAGS, TK_N_FIRST, TK_N_GBEGIN, TK_N_GN };
+#define TK_F_LEAF 1  /* reads gradients (src = element offset in g); otherwise items (src = offset in the workspace) */
+#define TK_F_FINAL 2 /* writes the tensor's output (out = offset in out_idx / out_val); otherwise items (workspace) */
 
 struct TkShared {
     uint64_t sort[TK_CAP];
     uint32_t hist[TK_BINS];
     uint32_t wave_sum[TK_NT / 64];
-    uint32_t b_star, above, count;
+    uint32_t b_star, above, count, count_tie, kmin, kmax;
+    uint16_t cnt16[TK_BINS];
 };
 
 // step 1 reads a chunk of a gradient tensor; index of item i within the tensor = first + i
 struct TkSrcGrad {
+    static constexpr int VEC = 4; // items per 16-byte load
+    static constexpr bool ORDERED = true; // the list is in ascending index order: of equal magnitudes the first ones win
     const float *g;
     uint32_t first;
     __device__ __forceinline__ uint32_t key(int i) const { return __float_as_uint(g[i]) & 0x7FFFFFFFu; }
-    __device__ __forceinline__ uint64_t item(int i) const { return ((uint64_t)key(i) << 32) | (0xFFFFFFFFu - (first + (uint32_t)i)); }
+    __device__ __forceinline__ uint32_t aux(int i) const { return 0xFFFFFFFFu - (first + (uint32_t)i); }
+    __device__ __forceinline__ uint64_t item(int i) const { return ((uint64_t)key(i) << 32) | aux(i); }
+    __device__ __forceinline__ int head() const { return (int)(((16u - ((uint32_t)(uintptr_t)g & 15u)) & 15u) >> 2); }
+    __device__ __forceinline__ uint4 loadv(int i) const { return *(const uint4 *)(g + i); }
+    // item e of the vector that starts at item i (e is a constant after unrolling)
+    __device__ __forceinline__ uint32_t key_of(const uint4 &v, int e) const {
+        return (e == 0 ? v.x : (e == 1 ? v.y : (e == 2 ? v.z : v.w))) & 0x7FFFFFFFu;
+    }
+    __device__ __forceinline__ uint32_t aux_of(const uint4 &, int i, int e) const { return aux(i + e); }
+    __device__ __forceinline__ void unpack(const uint4 &v, int i, uint32_t (&k)[VEC], uint32_t (&a)[VEC]) const {
+        k[0] = v.x & 0x7FFFFFFFu, k[1] = v.y & 0x7FFFFFFFu, k[2] = v.z & 0x7FFFFFFFu, k[3] = v.w & 0x7FFFFFFFu;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) a[e] = aux(i + e);
+    }
 };
 // step 2 reads the survivors
 struct TkSrcItems {
+    static constexpr int VEC = 2;
+    static constexpr bool ORDERED = false;
     const uint64_t *c;
     __device__ __forceinline__ uint32_t key(int i) const { return ((const uint32_t *)c)[2 * (int64_t)i + 1]; }
+    __device__ __forceinline__ uint32_t aux(int i) const { return ((const uint32_t *)c)[2 * (int64_t)i]; }
     __device__ __forceinline__ uint64_t item(int i) const { return c[i]; }
+    __device__ __forceinline__ int head() const { return ((uint32_t)(uintptr_t)c & 15u) ? 1 : 0; }
+    __device__ __forceinline__ uint4 loadv(int i) const { return *(const uint4 *)(c + i); }
+    __device__ __forceinline__ uint32_t key_of(const uint4 &v, int e) const { return e == 0 ? v.y : v.w; }
+    __device__ __forceinline__ uint32_t aux_of(const uint4 &v, int, int e) const { return e == 0 ? v.x : v.z; }
+    __device__ __forceinline__ void unpack(const uint4 &v, int, uint32_t (&k)[VEC], uint32_t (&a)[VEC]) const {
+        a[0] = v.x, k[0] = v.y, a[1] = v.z, k[1] = v.w;
+    }
 };
+
+// The list a workgroup selects from: n items behind a source, read in 16-byte vectors (plus up to three items
+// before the first and after the last whole vector).  Every pass of the selection streams the list from memory
+// (from L2 after the first).  A workgroup has its list to itself, so the passes are bound by memory latency: U
+// loads per thread are in flight, and the next batch is requested before the current one is worked on.
+template <class Src> struct TkList {
+    static constexpr int V = Src::VEC;
+    static constexpr bool ORDERED = Src::ORDERED;
+    Src src;
+    int n, head, nq, tail0;
+
+    __device__ __forceinline__ void init(const Src &s, int n_) {
+        src = s;
+        n = n_;
+        head = src.head(); // items before the first 16-byte boundary
+        if (head > n) head = n;
+        nq = (n - head) / V;
+        tail0 = head + nq * V;
+    }
+    template <int U> __device__ __forceinline__ void load(uint4 (&v)[U], int qb) const {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int q = qb + u * TK_NT + (int)threadIdx.x;
+            v[u] = q < nq ? src.loadv(head + q * V) : make_uint4(0u, 0u, 0u, 0u);
+        }
+    }
+    // f(v, qb): v[u] is vector qb + u * TK_NT + threadIdx.x of the list (zero beyond nq), U vectors at a time
+    template <int U, class F> __device__ __forceinline__ void batches(F f) const {
+        uint4 cur[U], nxt[U];
+        load<U>(cur, 0);
+        for (int qb = 0; qb < nq; qb += U * TK_NT) {
+            const bool more = qb + U * TK_NT < nq;
+            if (more) load<U>(nxt, qb + U * TK_NT);
+            f(cur, qb);
+            if (more) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) cur[u] = nxt[u];
+            }
+        }
+    }
+    // the up to 2 V - 2 items outside the whole vectors: thread t gets one of them (valid) or none
+    __device__ __forceinline__ bool edge_item(uint32_t *key, uint32_t *aux) const {
+        const int tid = threadIdx.x;
+        const int i = tid < head ? tid : tail0 + (tid - head);
+        const bool valid = i < n;
+        *key = valid ? src.key(i) : 0u;
+        *aux = valid ? src.aux(i) : 0u;
+        return valid;
+    }
+    // One pass: f(key, aux, valid) for every item (key = magnitude bits, aux = low word of the item), called by all
+    // threads together, so f may use wavefront-wide operations; lanes without an item call it with valid = false.
+    template <class F> __device__ __forceinline__ void scan(F f) const {
+        uint32_t ekey, eaux;
+        const bool evalid = edge_item(&ekey, &eaux); // requested first, used last
+        batches<4>([&](const uint4 (&v)[4], int qb) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = qb + u * TK_NT + (int)threadIdx.x;
+                uint32_t key[V], aux[V];
+                src.unpack(v[u], head + q * V, key, aux);
+#pragma unroll
+                for (int e = 0; e < V; ++e) f(key[e], aux[e], q < nq);
+            }
+        });
+        f(ekey, eaux, evalid);
+    }
+};
+
+// histogram update for the lanes in play; when all of them hit the same bin (lists of equal values: a constant or
+// mostly-zero tensor), one lane adds for all instead of 64 atomics serialising on one address
+__device__ __forceinline__ void tk_hist_add(bool in_play, uint32_t bin, uint32_t *hist) {
+    const uint64_t act = __builtin_amdgcn_ballot_w64(in_play);
+    if (act == 0ull) return;
+    const int first = __builtin_ctzll(act);
+    const uint32_t b0 = (uint32_t)__shfl((int)bin, first, 64);
+    if (__builtin_amdgcn_ballot_w64(in_play && bin == b0) == act) {
+        if ((int)(threadIdx.x & 63) == first) atomicAdd(&hist[b0], (uint32_t)__builtin_popcountll(act));
+    } else if (in_play) {
+        atomicAdd(&hist[bin], 1u);
+    }
+}
 
 // exclusive prefix sum of v over the workgroup in thread order (all threads call)
 __device__ __forceinline__ uint32_t tk_block_exclusive_scan(uint32_t v, TkShared &sh, uint32_t *total) {
@@ -77,28 +196,29 @@ __device__ __forceinline__ uint32_t tk_block_exclusive_scan(uint32_t v, TkShared
     return base + inc - v;
 }
 
-// append `item` to sh.sort for the lanes with sel set: one LDS atomic per wavefront, not per item
-__device__ __forceinline__ void tk_append(bool sel, uint64_t item, TkShared &sh) {
+// append `item` to an LDS array for the lanes with sel set (slot = base[dir * position], position from *counter):
+// one LDS atomic per wavefront, not per item
+__device__ __forceinline__ void tk_append(bool sel, uint64_t item, uint64_t *base_ptr, uint32_t *counter, int dir) {
     const uint64_t m = __builtin_amdgcn_ballot_w64(sel);
     if (m == 0ull) return;
     const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
     uint32_t base = 0u;
-    if (sel && rank == 0u) base = atomicAdd(&sh.count, (uint32_t)__builtin_popcountll(m));
+    if (sel && rank == 0u) base = atomicAdd(counter, (uint32_t)__builtin_popcountll(m));
     base = (uint32_t)__shfl((int)base, __builtin_ctzll(m), 64);
-    if (sel && base + rank < TK_CAP) sh.sort[base + rank] = item; // always inside: the caller has counted
+    if (sel && base + rank < TK_CAP) base_ptr[dir * (int)(base + rank)] = item; // always inside: the caller has counted
 }
 
-// bitonic sort of sh.sort[0 .. S) in descending order, S a power of two >= 2
-__device__ __forceinline__ void tk_sort_desc(TkShared &sh, int S) {
+// bitonic sort of a[0 .. S) in descending order, S a power of two >= 2
+__device__ __forceinline__ void tk_sort_desc(uint64_t *a, int S) {
     for (int size = 2; size <= S; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
             for (int p = threadIdx.x; p < (S >> 1); p += TK_NT) {
                 const int i = 2 * p - (p & (stride - 1)), j = i + stride;
-                const uint64_t a = sh.sort[i], b = sh.sort[j];
+                const uint64_t x = a[i], y = a[j];
                 const bool desc = (i & size) == 0;
-                if ((a < b) == desc) {
-                    sh.sort[i] = b;
-                    sh.sort[j] = a;
+                if ((x < y) == desc) {
+                    a[i] = y;
+                    a[j] = x;
                 }
             }
             __syncthreads();
@@ -106,220 +226,536 @@ __device__ __forceinline__ void tk_sort_desc(TkShared &sh, int S) {
     }
 }
 
-// Exact top-k of src's items 0 .. n-1.  On return sh.sort[0 .. min(n, k)) holds them in descending order.
-template <class Src> __device__ void tk_select(const Src &src, int n, int k, TkShared &sh, bool presorted) {
+__device__ __forceinline__ int tk_pow2_ceil(int v) {
+    int S = 2;
+    while (S < v) S <<= 1;
+    return S;
+}
+
+// The bin of hist[0 .. nb) (an LDS array) in which the need-th largest counted item falls, bins taken in descending order:
+// returns it, the number of items in higher bins (*above) and in the bin itself (*in_bin).  All threads call.
+__device__ __forceinline__ uint32_t tk_find_bin(const uint32_t *hist, int nb, uint32_t need, TkShared &sh, uint32_t *above, uint32_t *in_bin) {
     const int tid = threadIdx.x;
-    int count;
-    if (n <= k) { // everything survives
-        for (int i = tid; i < n; i += TK_NT) sh.sort[i] = src.item(i);
-        count = n;
-        if (presorted) {
-            __syncthreads();
-            return;
-        }
-    } else {
-        // items in play: (key >> hi) == prefix.  `need` of them are still to be taken, `taken` lie above them.
-        uint32_t prefix = 0, need = (uint32_t)k, taken = 0, P = 0, in_bin = 0;
-        int hi = 31, lo = 31;
-        bool fits = false;
-        for (int lev = 0; lev < 3 && !fits; ++lev) {
-            lo = lev == 0 ? 20 : (lev == 1 ? 9 : 0);
-            const int nb = 1 << (hi - lo);
-            for (int b = tid; b < nb; b += TK_NT) sh.hist[b] = 0u;
-            if (tid == 0) sh.b_star = sh.above = 0u; // (always overwritten below: at least `need` items are in play)
-            __syncthreads();
-            for (int i0 = 0; i0 < n; i0 += 4 * TK_NT) {
-                uint32_t key[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int i = i0 + u * TK_NT + tid;
-                    key[u] = i < n ? src.key(i) : 0xFFFFFFFFu; // bit 31 set: never in play
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if ((key[u] >> hi) == prefix) atomicAdd(&sh.hist[(key[u] >> lo) & (uint32_t)(nb - 1)], 1u);
+    const int per = nb / TK_NT > 0 ? nb / TK_NT : 1; // thread t owns bins nb-1 - t*per ... downwards (per = 2^j)
+    const int top = nb - 1 - tid * per;
+    uint32_t own = 0;
+    if (tid * per < nb) // (summed in rotated order: with 32 bins per thread a straight walk would put all lanes on one bank)
+        for (int q = 0; q < per; ++q) own += hist[top - ((q + tid) & (per - 1))];
+    if (tid == 0) sh.b_star = sh.above = 0u; // (always overwritten below: at least `need` items were counted)
+    uint32_t run = tk_block_exclusive_scan(own, sh, nullptr);
+    if (tid * per < nb && run < need && need <= run + own) { // exactly one thread: the bin is among its own
+        for (int q = 0; q < per; ++q) {
+            const uint32_t h = hist[top - q];
+            if (need <= run + h) {
+                sh.b_star = (uint32_t)(top - q);
+                sh.above = run;
+                break;
             }
-            __syncthreads();
-            // thread t owns bins nb-1 - t*per ... downwards: scan in descending bin order
-            const int per = nb / TK_NT > 0 ? nb / TK_NT : 1;
-            uint32_t own = 0;
-            if (tid * per < nb)
-                for (int q = 0; q < per; ++q) own += sh.hist[nb - 1 - (tid * per + q)];
-            uint32_t run = tk_block_exclusive_scan(own, sh, nullptr);
-            if (tid * per < nb) {
-                for (int q = 0; q < per; ++q) {
-                    const int b = nb - 1 - (tid * per + q);
-                    const uint32_t h = sh.hist[b];
-                    if (run < need && need <= run + h) { // exactly one bin
-                        sh.b_star = (uint32_t)b;
-                        sh.above = run;
+            run += h;
+        }
+    }
+    __syncthreads();
+    const uint32_t b_star = sh.b_star;
+    *above = sh.above;
+    *in_bin = hist[b_star];
+    __syncthreads();
+    return b_star;
+}
+
+// digit positions of the radix selection on the 64-bit item: level l covers bits [tk_lo(l), tk_lo(l - 1))
+// (the first level has 14 bits: its histogram has the 64 KB of the sort array, which is still free, to itself, and
+// 16,384 bins keep the LDS atomics of gradient-like data apart -- with 2,048 bins they serialise on a few dozen bins)
+__device__ __forceinline__ int tk_lo(int lev) { return lev == 0 ? 49 : (lev == 1 ? 38 : (lev == 2 ? 32 : (lev == 3 ? 21 : (lev == 4 ? 10 : 0)))); }
+#define TK_BINS0 (2 * TK_CAP) /* bins of the first level: the sort array as 32-bit counters */
+
+// Collect pass: items with (item >> lo) > P go to sh.sort from the front (counter sh.count), items with
+// (item >> lo) == P from the back (counter sh.count_tie).  A thread counts its items of a batch first, the
+// wavefront's counts are summed by shuffles, and one LDS atomic per wavefront and batch reserves the slots.
+template <class List> __device__ __forceinline__ void tk_collect(const List &list, int lo, uint64_t P, TkShared &sh) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    constexpr int V = List::V, U = 4; // U * V <= 32 flag bits (eight vectors at a time cost more registers than a lane has)
+    uint32_t ekey, eaux;
+    const bool evalid = list.edge_item(&ekey, &eaux); // requested first, used last
+    // The comparison is made on the magnitude alone when the digit boundary lies in it (lo >= 32, the usual case):
+    // 32-bit operations, a few instructions per item -- these passes are bound by instruction issue, not by memory.
+    const bool narrow = lo >= 32;
+    const uint32_t P32 = (uint32_t)P;
+    const int sh32 = narrow ? lo - 32 : 0;
+    list.template batches<U>([&](const uint4 (&v)[U], int qb) {
+        uint32_t fa = 0u, ft = 0u; // this thread's items above the bin / in the bin
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int q = qb + u * TK_NT + tid;
+            if (q < list.nq) {
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    const uint32_t key = list.src.key_of(v[u], e);
+                    bool above, equal;
+                    if (narrow) {
+                        const uint32_t d = key >> sh32;
+                        above = d > P32;
+                        equal = d == P32;
+                    } else {
+                        const uint64_t d = (((uint64_t)key << 32) | list.src.aux_of(v[u], list.head + q * V, e)) >> lo;
+                        above = d > P;
+                        equal = d == P;
                     }
-                    run += h;
+                    fa |= (above ? 1u : 0u) << (u * V + e);
+                    ft |= (equal ? 1u : 0u) << (u * V + e);
                 }
             }
-            __syncthreads();
-            const uint32_t b_star = sh.b_star, above = sh.above;
-            in_bin = sh.hist[b_star];
-            P = (prefix << (hi - lo)) | b_star;
-            taken += above;
-            need -= above;
-            fits = taken + in_bin <= TK_CAP;
-            prefix = P;
-            hi = lo;
-            __syncthreads();
         }
+        const uint32_t mine = (uint32_t)__builtin_popcount(fa) | ((uint32_t)__builtin_popcount(ft) << 16);
+        uint32_t inc = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t up = __shfl_up(inc, o, 64);
+            if (lane >= o) inc += up;
+        }
+        const uint32_t tot = (uint32_t)__shfl((int)inc, 63, 64);
+        if (tot == 0u) return; // nothing of this batch is kept by this wavefront
+        uint32_t base_a = 0u, base_t = 0u;
+        if (lane == 63) {
+            if (tot & 0xFFFFu) base_a = atomicAdd(&sh.count, tot & 0xFFFFu);
+            if (tot >> 16) base_t = atomicAdd(&sh.count_tie, tot >> 16);
+        }
+        uint32_t pa = (uint32_t)__shfl((int)base_a, 63, 64) + ((inc - mine) & 0xFFFFu);
+        uint32_t pt = (uint32_t)__shfl((int)base_t, 63, 64) + ((inc - mine) >> 16);
+        const uint32_t any = fa | ft;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (((any >> (u * V)) & ((1u << V) - 1u)) == 0u) continue; // most vectors hold nothing to keep
+            const int q = qb + u * TK_NT + tid;
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const int j = u * V + e;
+                if ((any >> j) & 1u) {
+                    const uint64_t item = ((uint64_t)list.src.key_of(v[u], e) << 32) | list.src.aux_of(v[u], list.head + q * V, e);
+                    if ((fa >> j) & 1u) {
+                        if (pa < TK_CAP) sh.sort[pa] = item; // always inside: the caller has counted
+                        ++pa;
+                    } else {
+                        if (pt < TK_CAP) sh.sort[TK_CAP - 1 - pt] = item;
+                        ++pt;
+                    }
+                }
+            }
+        }
+    });
+    {
+        const uint64_t item = ((uint64_t)ekey << 32) | eaux;
+        tk_append(evalid && (item >> lo) > P, item, sh.sort, &sh.count, 1);
+        tk_append(evalid && (item >> lo) == P, item, sh.sort + TK_CAP - 1, &sh.count_tie, -1);
+    }
+}
+
+// sh.sort[0 .. k) in any order -> descending order.  Items are spread over up to 2,048 buckets by the 11 bits below
+// the highest bit in which the largest and the smallest differ (histogram, descending prefix, scatter into the
+// upper half of the array), then every item counts the larger items of its bucket: its rank.  Buckets are small
+// for anything but pathological inputs (which take the bitonic sort instead).  k <= TK_CAP / 2.
+__device__ void tk_order(int k, TkShared &sh) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint64_t *grouped = sh.sort + TK_CAP / 2;
+    // largest and smallest item
+    uint64_t mx = 0ull, mn = ~0ull;
+    for (int i = tid; i < k; i += TK_NT) {
+        const uint64_t x = sh.sort[i];
+        mx = x > mx ? x : mx;
+        mn = x < mn ? x : mn;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint64_t a = __shfl_xor((unsigned long long)mx, o, 64), b = __shfl_xor((unsigned long long)mn, o, 64);
+        mx = a > mx ? a : mx;
+        mn = b < mn ? b : mn;
+    }
+    if (lane == 0) {
+        grouped[2 * wave] = mx;
+        grouped[2 * wave + 1] = mn;
+    }
+    __syncthreads();
+    for (int w = 0; w < TK_NT / 64; ++w) {
+        const uint64_t a = grouped[2 * w], b = grouped[2 * w + 1];
+        mx = a > mx ? a : mx;
+        mn = b < mn ? b : mn;
+    }
+    __syncthreads();
+    const uint64_t diff = mx ^ mn;
+    const int h = diff ? 63 - __builtin_clzll(diff) : 0;
+    const int shift = h > 10 ? h - 10 : 0; // digit = 11 bits ending at the highest differing bit
+    for (int b = tid; b < TK_BINS; b += TK_NT) sh.hist[b] = 0u;
+    __syncthreads();
+    for (int i = tid; i < k; i += TK_NT) atomicAdd(&sh.hist[(uint32_t)(sh.sort[i] >> shift) & (TK_BINS - 1)], 1u);
+    __syncthreads();
+    // descending exclusive prefix: bucket b starts at the number of items in higher buckets; keep the counts
+    constexpr int per = TK_BINS / TK_NT;
+    uint32_t cnt[per], own = 0, big = 0;
+#pragma unroll
+    for (int q = 0; q < per; ++q) {
+        cnt[q] = sh.hist[TK_BINS - 1 - (tid * per + q)];
+        own += cnt[q];
+        big = cnt[q] > big ? cnt[q] : big;
+    }
+    uint32_t run = tk_block_exclusive_scan(own, sh, nullptr);
+#pragma unroll
+    for (int q = 0; q < per; ++q) {
+        const int b = TK_BINS - 1 - (tid * per + q);
+        sh.hist[b] = run;               // start of the bucket; the scatter below advances it to the bucket's end
+        sh.cnt16[b] = (uint16_t)cnt[q];
+        run += cnt[q];
+    }
+    const bool pathological = __syncthreads_or(big > 1024u);
+    if (pathological) {
+        const int S = tk_pow2_ceil(k);
+        for (int i = k + tid; i < S; i += TK_NT) sh.sort[i] = 0ull;
+        __syncthreads();
+        tk_sort_desc(sh.sort, S);
+        return;
+    }
+    for (int i = tid; i < k; i += TK_NT) {
+        const uint64_t x = sh.sort[i];
+        grouped[atomicAdd(&sh.hist[(uint32_t)(x >> shift) & (TK_BINS - 1)], 1u)] = x;
+    }
+    __syncthreads();
+    for (int i = tid; i < k; i += TK_NT) {
+        const uint64_t x = grouped[i];
+        const uint32_t b = (uint32_t)(x >> shift) & (TK_BINS - 1);
+        const int end = (int)sh.hist[b], begin = end - (int)sh.cnt16[b];
+        int rank = 0;
+        for (int j = begin; j < end; ++j) rank += grouped[j] > x ? 1 : 0;
+        sh.sort[begin + rank] = x;
+    }
+    __syncthreads();
+}
+
+// Exact top-k of src's items 0 .. n-1.  On return sh.sort[0 .. min(n, k)) holds them; in descending order if
+// `sorted` is asked for, otherwise in no particular order.
+template <class List> __device__ __forceinline__ void tk_select(const List &list, int k, TkShared &sh, bool sorted) {
+    const int tid = threadIdx.x;
+    const int n = list.n;
+    if (n <= k) { // everything survives
+        for (int i = tid; i < n; i += TK_NT) sh.sort[i] = list.src.item(i);
+        __syncthreads();
+        if (sorted) tk_order(n, sh);
+        return;
+    }
+    // Items in play: (item >> hi) == prefix.  `need` of them are still to be taken, `taken` items lie above them.
+    uint64_t prefix = 0, P = 0;
+    uint32_t need = (uint32_t)k, taken = 0, in_bin = 0, above = 0;
+    int hi = 63, lo = 63, lev = 0;
+    bool ordered = false, settled = false;
+    for (;; ++lev) { // passes over the list in memory, until the boundary bin fits the LDS array beside the items above it
+        lo = tk_lo(lev);
+        const int nb = 1 << (hi - lo);
+        uint32_t *hist = lev == 0 ? (uint32_t *)sh.sort : sh.hist;
+        for (int b = tid; b < nb; b += TK_NT) hist[b] = 0u;
+        __syncthreads();
+        const uint32_t bin_mask = (uint32_t)(nb - 1);
+        if (lev == 0) { // all items are in play, the digit lies in the magnitude
+            // Stretches of one value -- a constant or mostly-zero tensor -- would send all 64 atomics of an instruction to
+            // one address; they show in the first vector of a batch, and then the wavefront merges its adds.
+            // (If all of the list turns out to be one value, the magnitude is settled after this pass.)
+            uint32_t ekey, eaux;
+            const bool evalid = list.edge_item(&ekey, &eaux);
+            uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+            bool mixed = false;
+            if (tid == 0) {
+                sh.kmin = 0xFFFFFFFFu;
+                sh.kmax = 0u;
+            }
+            list.template batches<4>([&](const uint4 (&v)[4], int qb) {
+                const uint32_t b0 = list.src.key_of(v[0], 0) >> 17, b1 = list.src.key_of(v[0], List::V - 1) >> 17;
+                const uint32_t w0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)b0);
+                const bool one_value = __builtin_amdgcn_ballot_w64(b0 == w0 && b1 == w0) == __builtin_amdgcn_ballot_w64(true);
+                if (one_value) {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+#pragma unroll
+                        for (int e = 0; e < List::V; ++e) {
+                            const bool valid = qb + u * TK_NT + tid < list.nq;
+                            const uint32_t key = list.src.key_of(v[u], e);
+                            tk_hist_add(valid, key >> 17, hist);
+                            kmin = valid && key < kmin ? key : kmin;
+                            kmax = valid && key > kmax ? key : kmax;
+                        }
+                } else {
+                    mixed = true;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        if (qb + u * TK_NT + tid < list.nq) {
+#pragma unroll
+                            for (int e = 0; e < List::V; ++e) atomicAdd(&hist[list.src.key_of(v[u], e) >> 17], 1u);
+                        }
+                    }
+                }
+            });
+            if (evalid) {
+                atomicAdd(&hist[ekey >> 17], 1u);
+                kmin = ekey < kmin ? ekey : kmin;
+                kmax = ekey > kmax ? ekey : kmax;
+            }
+            const bool uniform = __syncthreads_and(!mixed) != 0; // (also orders the initialisation of sh.kmin / sh.kmax)
+            if (List::ORDERED && uniform) {
+                if (kmin <= kmax) {
+                    atomicMin(&sh.kmin, kmin);
+                    atomicMax(&sh.kmax, kmax);
+                }
+            }
+            settled = List::ORDERED && uniform;
+        } else {
+            list.scan([&](uint32_t key, uint32_t aux, bool valid) {
+                const uint64_t item = ((uint64_t)key << 32) | aux;
+                tk_hist_add(valid && (item >> hi) == prefix, (uint32_t)(item >> lo) & bin_mask, hist);
+            });
+        }
+        __syncthreads();
+        const uint32_t b_star = tk_find_bin(hist, nb, need, sh, &above, &in_bin);
+        P = (prefix << (hi - lo)) | b_star;
+        taken += above;
+        need -= above;
+        prefix = P;
+        hi = lo;
+        if (taken + in_bin <= TK_CAP || lo == 0) break; // (at lo == 0 the bin holds one item: items are distinct)
+        if (lev == 0 && settled && sh.kmin == sh.kmax) { // one magnitude throughout: nothing lies above it
+            P = sh.kmin;
+            lo = hi = 32;
+            ordered = true;
+            break;
+        }
+        if (List::ORDERED && lo == 32) { // the magnitude is settled and more items share it than LDS holds
+            ordered = true;
+            break;
+        }
+    }
+    if (ordered) {
+        // Chunks of constant or mostly-zero tensors: the items above the magnitude T, then the first `need` items
+        // equal to T in list order (= ascending index) -- one pass each instead of three more levels.
+        const uint32_t T = (uint32_t)P;
         if (tid == 0) sh.count = 0u;
         __syncthreads();
-        if (fits) { // everything at or above the boundary bin: (key >> lo) >= P
-            for (int i0 = 0; i0 < n; i0 += 4 * TK_NT) {
-                uint32_t key[4];
+        list.scan([&](uint32_t key, uint32_t aux, bool valid) {
+            tk_append(valid && key > T, ((uint64_t)key << 32) | aux, sh.sort, &sh.count, 1);
+        });
+        uint32_t done = 0; // equal items seen so far (the same in every thread)
+        auto place = [&](uint32_t flags, int i0) { // this thread's items i0 + e with bit e of flags set equal T
+            uint32_t tot;
+            uint32_t rank = done + tk_block_exclusive_scan((uint32_t)__builtin_popcount(flags), sh, &tot);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int i = i0 + u * TK_NT + tid;
-                    key[u] = i < n ? src.key(i) : 0u;
+            for (int e = 0; e < List::V; ++e) {
+                if ((flags >> e) & 1u) {
+                    if (rank < need) sh.sort[taken + rank] = list.src.item(i0 + e);
+                    ++rank;
                 }
+            }
+            done += tot;
+        };
+        place(tid < list.head && list.src.key(tid) == T ? 1u : 0u, tid);
+        for (int qb = 0; qb < list.nq && done < need; qb += TK_NT) {
+            const int q = qb + tid;
+            uint32_t flags = 0u;
+            if (q < list.nq) {
+                const uint4 v = list.src.loadv(list.head + q * List::V);
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int i = i0 + u * TK_NT + tid;
-                    const bool sel = i < n && (key[u] >> lo) >= P;
-                    tk_append(sel, sel ? src.item(i) : 0ull, sh);
-                }
+                for (int e = 0; e < List::V; ++e) flags |= (list.src.key_of(v, e) == T ? 1u : 0u) << e;
             }
-            count = (int)(taken + in_bin);
-        } else {
-            // lo == 0: P is the k-th magnitude itself and more items equal it than the sort array holds.
-            // Larger ones first (any order), then the first `need` equal ones in list order.
-            for (int i0 = 0; i0 < n; i0 += TK_NT) {
-                const int i = i0 + tid;
-                const bool sel = i < n && src.key(i) > P;
-                tk_append(sel, sel ? src.item(i) : 0ull, sh);
-            }
-            uint32_t done = 0; // equal items placed so far (uniform over the workgroup)
-            for (int i0 = 0; i0 < n && done < need; i0 += TK_NT) {
-                const int i = i0 + tid;
-                const bool eq = i < n && src.key(i) == P;
-                uint32_t tot;
-                const uint32_t rank = done + tk_block_exclusive_scan(eq ? 1u : 0u, sh, &tot);
-                if (eq && rank < need) sh.sort[taken + rank] = src.item(i);
-                done += tot;
-            }
-            count = k;
+            place(flags, list.head + q * List::V);
         }
+        if (done < need) place(list.tail0 + tid < n && list.src.key(list.tail0 + tid) == T ? 1u : 0u, list.tail0 + tid);
+        __syncthreads(); // sh.sort[0 .. k) is the top-k
+        if (sorted) tk_order(k, sh);
+        return;
+    }
+    if (tid == 0) sh.count = sh.count_tie = 0u;
+    __syncthreads();
+    tk_collect(list, lo, P, sh);
+    __syncthreads();
+    // The boundary bin now lies in sh.sort[TK_CAP - in_bin, TK_CAP); `need` of its items belong to the top-k.  The
+    // selection goes on there, level by level, until the bin in play is needed whole; its members are then
+    // recognised by (item >> lo) >= P.
+    uint64_t *tie = sh.sort + TK_CAP - in_bin;
+    const int n_tie = (int)in_bin;
+    while (need < in_bin) {
+        ++lev;
+        lo = tk_lo(lev);
+        const int nb = 1 << (hi - lo);
+        for (int b = tid; b < nb; b += TK_NT) sh.hist[b] = 0u;
+        __syncthreads();
+        const uint32_t bin_mask = (uint32_t)(nb - 1);
+        for (int i0 = 0; i0 < n_tie; i0 += TK_NT) {
+            const int i = i0 + tid;
+            const uint64_t item = i < n_tie ? tie[i] : 0ull;
+            tk_hist_add(i < n_tie && (item >> hi) == prefix, (uint32_t)(item >> lo) & bin_mask, sh.hist);
+        }
+        __syncthreads();
+        const uint32_t b_star = tk_find_bin(sh.hist, nb, need, sh, &above, &in_bin);
+        P = (prefix << (hi - lo)) | b_star;
+        need -= above; // the items above the new bin are taken: they satisfy (item >> lo) > P
+        prefix = P;
+        hi = lo;
+        // at lo == 0 the bin holds a single item, so need == in_bin == 1 and the loop ends
+    }
+    // move the chosen members of the boundary bin up behind the items above it (they cannot overlap what is still to
+    // be read: a member at tie[i] lands at an index <= TK_CAP - n_tie + i only if ... so it goes through registers)
+    uint64_t mv[TK_CAP / TK_NT];
+#pragma unroll
+    for (int q = 0; q < TK_CAP / TK_NT; ++q) {
+        const int i = q * TK_NT + tid;
+        mv[q] = i < n_tie ? tie[i] : 0ull;
     }
     __syncthreads();
-    int S = 2;
-    while (S < count) S <<= 1;
-    for (int i = count + tid; i < S; i += TK_NT) sh.sort[i] = 0ull; // below every item
-    __syncthreads();
-    tk_sort_desc(sh, S);
+#pragma unroll
+    for (int q = 0; q < TK_CAP / TK_NT; ++q) {
+        const int i = q * TK_NT + tid;
+        tk_append(i < n_tie && (mv[q] >> lo) >= P, mv[q], sh.sort, &sh.count, 1);
+    }
+    __syncthreads(); // sh.sort[0 .. k) is the top-k
+    if (sorted) tk_order(k, sh);
 }
 
-// step 1: one workgroup per chunk
+// one step of the tree: one workgroup per node of the level
 __global__ void __launch_bounds__(TK_NT)
-tk_chunk_kernel(const float *__restrict__ g, const int64_t *__restrict__ plan, uint64_t *__restrict__ cand) {
+tk_node_kernel(const float *__restrict__ g, const int64_t *__restrict__ plan, uint64_t *__restrict__ cand,
+               int32_t *__restrict__ out_idx, float *__restrict__ out_val, int first_node) {
     __shared__ TkShared sh;
     const int T = (int)plan[1];
-    const int64_t w = plan[TK_HEADER + (int64_t)T * TK_RECORD + blockIdx.x];
-    const int t = (int)(w >> 32), j = (int)(w & 0xFFFFFFFFll);
-    const int64_t *rec = plan + TK_HEADER + (int64_t)t * TK_RECORD;
-    const int64_t n = rec[TK_R_N], chunk = rec[TK_R_CHUNK];
-    const int k = (int)rec[TK_R_K], kc = (int)rec[TK_R_KC];
-    const int64_t a = (int64_t)j * chunk;
-    const int len = (int)((a + chunk < n ? a + chunk : n) - a);
-    TkSrcGrad src;
-    src.g = g + rec[TK_R_BEGIN] + a;
-    src.first = (uint32_t)a;
-    tk_select(src, len, k, sh, false);
-    const int keep = len < k ? len : k;
-    uint64_t *out = cand + rec[TK_R_CAND_OFF] + (int64_t)j * kc;
-    for (int r = threadIdx.x; r < keep; r += TK_NT) out[r] = sh.sort[r];
-}
-
-// step 2: one workgroup per tensor
-__global__ void __launch_bounds__(TK_NT)
-tk_final_kernel(const float *__restrict__ g, const int64_t *__restrict__ plan, const uint64_t *__restrict__ cand,
-                int32_t *__restrict__ out_idx, float *__restrict__ out_val) {
-    __shared__ TkShared sh;
-    const int t = blockIdx.x;
-    const int64_t *rec = plan + TK_HEADER + (int64_t)t * TK_RECORD;
-    const int64_t n = rec[TK_R_N], chunk = rec[TK_R_CHUNK], M = rec[TK_R_M];
-    const int k = (int)rec[TK_R_K], kc = (int)rec[TK_R_KC];
-    const int64_t last_len = n - (M - 1) * chunk;
-    const int n_cand = (int)((M - 1) * kc + (last_len < k ? last_len : k));
-    TkSrcItems src;
-    src.c = cand + rec[TK_R_CAND_OFF];
-    tk_select(src, n_cand, k, sh, M == 1); // a single chunk's survivors are the answer, already in order
-    const float *gt = g + rec[TK_R_BEGIN];
-    const int64_t o = rec[TK_R_OUT_OFF];
-    for (int r = threadIdx.x; r < k; r += TK_NT) {
-        const uint32_t idx = 0xFFFFFFFFu - (uint32_t)sh.sort[r];
-        out_idx[o + r] = (int32_t)idx;
-        out_val[o + r] = gt[idx];
+    const int64_t *rec = plan + TK_HEADER + (int64_t)T * TK_TENSOR + (int64_t)(first_node + blockIdx.x) * TK_NODE;
+    const int n = (int)rec[TK_N_ITEMS], k = (int)rec[TK_N_K];
+    const int flags = (int)rec[TK_N_FLAGS];
+    const bool final_step = flags & TK_F_FINAL;
+    if (flags & TK_F_LEAF) {
+        TkSrcGrad src;
+        src.g = g + rec[TK_N_SRC];
+        src.first = (uint32_t)rec[TK_N_FIRST];
+        TkList<TkSrcGrad> list;
+        list.init(src, n);
+        tk_select(list, k, sh, final_step);
+    } else {
+        TkSrcItems src;
+        src.c = cand + rec[TK_N_SRC];
+        TkList<TkSrcItems> list;
+        list.init(src, n);
+        tk_select(list, k, sh, final_step);
+    }
+    const int keep = n < k ? n : k; // (a final step has n >= k)
+    const int64_t o = rec[TK_N_OUT];
+    if (final_step) {
+        const float *gt = g + rec[TK_N_GBEGIN];
+        const uint32_t gn = (uint32_t)rec[TK_N_GN];
+        for (int r = threadIdx.x; r < keep; r += TK_NT) {
+            const uint32_t idx = 0xFFFFFFFFu - (uint32_t)sh.sort[r];
+            out_idx[o + r] = (int32_t)idx;
+            out_val[o + r] = idx < gn ? gt[idx] : 0.f; // (always inside: items carry indices of this tensor)
+        }
+    } else {
+        for (int r = threadIdx.x; r < keep; r += TK_NT) cand[o + r] = sh.sort[r];
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
+struct TkNode {
+    int64_t src, items, k, out, flags, first, gbegin, gn;
+    int level;
+};
+
 extern "C" int64_t grad_topk_plan(const int64_t *offsets, const int32_t *k, int T, int chunks, int64_t *plan,
                                   int64_t plan_capacity) {
     if (!offsets || !k || T < 1 || chunks < 0) return -(int64_t)KS_INVALID_ARG;
-    int64_t W1 = 0;
-    for (int pass = 0; pass < 2; ++pass) {
-        int64_t cand = 0, out = 0, w = 0;
-        for (int t = 0; t < T; ++t) {
-            const int64_t n = offsets[t + 1] - offsets[t];
-            if (n < 1 || n >= ((int64_t)1 << 31) || k[t] < 1 || k[t] > n) return -(int64_t)KS_INVALID_ARG;
-            if (k[t] > KS_TOPK_MAX_K) return -(int64_t)KS_UNSUPPORTED;
-            int64_t M;
-            if (chunks > 0) {
-                M = chunks < n ? chunks : n;
-            } else {
-                M = 1;
-                while (M < TK_MAX_AUTO_CHUNKS && (M + 1) * (M + 1) * (int64_t)k[t] <= n) ++M;                   // floor(sqrt(n / k))
-                if ((2 * M + 1) * (2 * M + 1) * (int64_t)k[t] <= 4 * n) ++M;            // to nearest
-                if (M > n / TK_MIN_CHUNK) M = n / TK_MIN_CHUNK;
-                if (M > TK_MAX_AUTO_CHUNKS) M = TK_MAX_AUTO_CHUNKS;
-                if (M < 1) M = 1;
-            }
-            const int64_t chunk = (n + M - 1) / M;
-            M = (n + chunk - 1) / chunk; // no empty chunks
-            const int64_t kc = k[t] < chunk ? k[t] : chunk;
-            if (pass == 1) {
-                int64_t *rec = plan + TK_HEADER + (int64_t)t * TK_RECORD;
-                rec[TK_R_BEGIN] = offsets[t];
-                rec[TK_R_N] = n;
-                rec[TK_R_K] = k[t];
-                rec[TK_R_M] = M;
-                rec[TK_R_CHUNK] = chunk;
-                rec[TK_R_CAND_OFF] = cand;
-                rec[TK_R_OUT_OFF] = out;
-                rec[TK_R_KC] = kc;
-                for (int64_t j = 0; j < M; ++j) plan[TK_HEADER + (int64_t)T * TK_RECORD + w + j] = ((int64_t)t << 32) | j;
-            }
-            cand += M * kc;
-            out += k[t];
-            w += M;
+    std::vector<TkNode> nodes;
+    std::vector<int64_t> tensors;
+    int64_t cand = 0, out = 0;
+    int n_levels = 0;
+    for (int t = 0; t < T; ++t) {
+        const int64_t n = offsets[t + 1] - offsets[t];
+        if (n < 1 || n >= ((int64_t)1 << 31) || k[t] < 1 || k[t] > n) return -(int64_t)KS_INVALID_ARG;
+        if (k[t] > KS_TOPK_MAX_K) return -(int64_t)KS_UNSUPPORTED;
+        int64_t M = chunks > 0 ? (chunks < n ? (int64_t)chunks : n) : (n + TK_LEAF - 1) / TK_LEAF;
+        const int64_t chunk = (n + M - 1) / M;
+        M = (n + chunk - 1) / chunk; // no empty chunks
+        // the lists of the current level: (offset, items) of each; level 0 = the chunks of the tensor
+        std::vector<TkNode> cur;
+        for (int64_t j = 0; j < M; ++j) {
+            TkNode nd = {offsets[t] + j * chunk, (j + 1) * chunk < n ? chunk : n - j * chunk, k[t], 0, TK_F_LEAF, j * chunk, offsets[t], n, 0};
+            cur.push_back(nd);
         }
-        if (w >= ((int64_t)1 << 31)) return -(int64_t)KS_UNSUPPORTED;
-        if (pass == 0) {
-            W1 = w;
-            const int64_t words = TK_HEADER + (int64_t)T * TK_RECORD + W1;
-            if (!plan || plan_capacity < words) return words;
-        } else {
-            plan[0] = TK_MAGIC;
-            plan[1] = T;
-            plan[2] = W1;
-            plan[3] = cand;
-            plan[4] = out;
-            plan[5] = offsets[T] - offsets[0];
-            plan[6] = plan[7] = 0;
+        int level = 0;
+        for (;;) {
+            if (cur.size() == 1) { // the last step of the tensor
+                cur[0].flags |= TK_F_FINAL;
+                cur[0].out = out;
+                nodes.push_back(cur[0]);
+                break;
+            }
+            // the nodes of this level hand their survivors on, back to back in the workspace
+            int64_t total = 0;
+            for (auto &nd : cur) {
+                nd.out = cand + total;
+                total += nd.items < nd.k ? nd.items : nd.k;
+                nodes.push_back(nd);
+            }
+            // next level: as few steps as the input limit allows (at least two lists each)
+            int64_t G = TK_NODE_CAP / k[t];
+            if (G < 2) G = 2;
+            if (total <= TK_NODE_CAP) G = (int64_t)cur.size();
+            std::vector<TkNode> next;
+            for (size_t a = 0; a < cur.size(); a += (size_t)G) {
+                const size_t b = a + (size_t)G < cur.size() ? a + (size_t)G : cur.size();
+                int64_t items = 0;
+                for (size_t c = a; c < b; ++c) items += cur[c].items < cur[c].k ? cur[c].items : cur[c].k;
+                TkNode nd = {cur[a].out, items, k[t], 0, 0, 0, offsets[t], n, level + 1};
+                next.push_back(nd);
+            }
+            cand += total;
+            cur.swap(next);
+            ++level;
+            if (level >= TK_MAX_LEVELS) return -(int64_t)KS_UNSUPPORTED;
         }
+        if (level + 1 > n_levels) n_levels = level + 1;
+        tensors.push_back(n);
+        tensors.push_back(k[t]);
+        tensors.push_back(M);
+        tensors.push_back(level + 1);
+        out += k[t];
     }
-    return TK_HEADER + (int64_t)T * TK_RECORD + W1;
+    const int64_t n_nodes = (int64_t)nodes.size();
+    if (n_nodes >= ((int64_t)1 << 31)) return -(int64_t)KS_UNSUPPORTED;
+    const int64_t words = TK_HEADER + (int64_t)T * TK_TENSOR + n_nodes * TK_NODE;
+    if (!plan || plan_capacity < words) return words;
+    for (int64_t i = 0; i < TK_HEADER; ++i) plan[i] = 0;
+    plan[0] = TK_MAGIC;
+    plan[1] = T;
+    plan[2] = n_nodes;
+    plan[3] = cand > 0 ? cand : 1;
+    plan[4] = out;
+    plan[5] = offsets[T] - offsets[0];
+    plan[6] = n_levels;
+    for (size_t i = 0; i < tensors.size(); ++i) plan[TK_HEADER + (int64_t)i] = tensors[i];
+    int64_t *nrec = plan + TK_HEADER + (int64_t)T * TK_TENSOR;
+    int64_t w = 0;
+    for (int lev = 0; lev < n_levels; ++lev) { // nodes level by level, tensors in order inside a level
+        plan[8 + 2 * lev] = w;
+        for (const TkNode &nd : nodes) {
+            if (nd.level != lev) continue;
+            int64_t *r = nrec + w * TK_NODE;
+            r[TK_N_SRC] = nd.src;
+            r[TK_N_ITEMS] = nd.items;
+            r[TK_N_K] = nd.k;
+            r[TK_N_OUT] = nd.out;
+            r[TK_N_FLAGS] = nd.flags;
+            r[TK_N_FIRST] = nd.first;
+            r[TK_N_GBEGIN] = nd.gbegin;
+            r[TK_N_GN] = nd.gn;
+            ++w;
+        }
+        plan[9 + 2 * lev] = w - plan[8 + 2 * lev];
+    }
+    return words;
 }
 
-static bool tk_plan_ok(const int64_t *p) { return p && p[0] == TK_MAGIC && p[1] >= 1 && p[2] >= p[1] && p[3] >= 1 && p[4] >= 1; }
+static bool tk_plan_ok(const int64_t *p) {
+    return p && p[0] == TK_MAGIC && p[1] >= 1 && p[2] >= p[1] && p[3] >= 1 && p[4] >= 1 && p[6] >= 1 && p[6] <= TK_MAX_LEVELS;
+}
 
 extern "C" size_t grad_topk_workspace(const int64_t *plan_host) {
     if (!tk_plan_ok(plan_host)) return 0;
@@ -332,8 +768,12 @@ extern "C" int grad_topk_select(const float *g, const int64_t *plan_dev, const i
     if (ws_bytes < grad_topk_workspace(plan_host)) return KS_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
     uint64_t *cand = (uint64_t *)ws;
-    hipLaunchKernelGGL(tk_chunk_kernel, dim3((unsigned)plan_host[2]), dim3(TK_NT), 0, st, g, plan_dev, cand);
-    hipLaunchKernelGGL(tk_final_kernel, dim3((unsigned)plan_host[1]), dim3(TK_NT), 0, st, g, plan_dev, cand, out_idx, out_val);
+    for (int lev = 0; lev < (int)plan_host[6]; ++lev) {
+        const int64_t first = plan_host[8 + 2 * lev], count = plan_host[9 + 2 * lev];
+        if (count < 1) continue;
+        hipLaunchKernelGGL(tk_node_kernel, dim3((unsigned)count), dim3(TK_NT), 0, st, g, plan_dev, cand, out_idx, out_val,
+                           (int)first);
+    }
     KS_LAUNCH_CHECK();
     return KS_OK;
 }

@@ -186,34 +186,46 @@ def _plan(ks, sizes, k, chunks=0):
 
 
 def test_topk_plan_layout(ks):
+    import numpy as np
     import synth
     sizes = synth.resnet50_tensor_sizes()
     k = synth.topk_counts(sizes)
     words, plan = _plan(ks, sizes, k)
     T = len(sizes)
     assert plan[1] == T and plan[4] == k.sum() and plan[5] == sum(sizes)
-    rec = plan[8:8 + 8 * T].reshape(T, 8)
-    begin, n, kk, M, chunk, cand_off, out_off, kc = rec.T
-    assert (n == sizes).all() and (kk == k).all() and (begin == [0] + list(__import__("numpy").cumsum(sizes)[:-1])).all()
-    assert ((M - 1) * chunk < n).all() and (M * chunk >= n).all()          # M chunks, none empty
-    assert (M[n < 16384] == 1).all() and M.max() <= 256 and (chunk[M > 1] >= 8192).all()
-    big = n == 512 * 512 * 9                                              # n / k = 1000: about 32 chunks
-    assert ((M[big] >= 30) & (M[big] <= 33)).all()
-    assert (kc == __import__("numpy").minimum(kk, chunk)).all()
-    assert (out_off == [0] + list(__import__("numpy").cumsum(k)[:-1])).all()
-    assert (cand_off[1:] == __import__("numpy").cumsum(M * kc)[:-1]).all() and plan[3] == (M * kc).sum()
-    # the table of step-1 workgroups lists every (tensor, chunk) once, in order
-    W1 = int(plan[2])
-    assert W1 == M.sum() and words == 8 + 8 * T + W1
-    table = plan[8 + 8 * T:]
-    want = [(t << 32) | j for t in range(T) for j in range(int(M[t]))]
-    assert table.tolist() == want
+    n, kk, M, levels = plan[32:32 + 4 * T].reshape(T, 4).T
+    assert (n == sizes).all() and (kk == k).all() and (M == -(-n // 32768)).all()
+    assert (levels[M == 1] == 1).all() and (levels[M > 1] >= 2).all() and plan[6] == levels.max()
+    big = n == 512 * 512 * 9   # 72 chunks x 2,359 survivors = 169,848 items: reduced in groups of 13 chunks first
+    assert (M[big] == 72).all() and (levels[big] == 3).all()
+    n_nodes = int(plan[2])
+    assert words == 32 + 4 * T + 8 * n_nodes
+    nodes = plan[32 + 4 * T:].reshape(n_nodes, 8)
+    src, items, nk, out, flags, first, gbegin = nodes.T[:7]
+    # levels are stored one after the other and cover all nodes
+    firsts, counts = plan[8:8 + 2 * int(plan[6]):2], plan[9:9 + 2 * int(plan[6]):2]
+    assert firsts[0] == 0 and (firsts[1:] == np.cumsum(counts)[:-1]).all() and counts.sum() == n_nodes
+    leaf, final = (flags & 1) == 1, (flags & 2) == 2
+    assert leaf[:counts[0]].all() and not leaf[counts[0]:].any() and final.sum() == T and leaf.sum() == M.sum()
+    assert (items <= 32768).all() and (items[final] >= nk[final]).all()
+    # the leaves tile the gradient array; the final nodes tile the output
+    order = np.argsort(src[leaf], kind="stable")
+    assert (src[leaf][order][1:] == (src[leaf] + items[leaf])[order][:-1]).all() and items[leaf].sum() == sum(sizes)
+    assert sorted(out[final].tolist()) == [0] + np.cumsum(k)[:-1].tolist()
+    # survivors of the other nodes lie back to back in the workspace, and every inner node reads whole lists
+    keep = np.minimum(items, nk)
+    o = np.argsort(out[~final], kind="stable")
+    assert (out[~final][o][1:] == (out[~final] + keep[~final])[o][:-1]).all() and plan[3] == keep[~final].sum()
+    starts = set(out[~final].tolist())
+    assert all(int(s) in starts for s in src[~leaf]) and items[~leaf].sum() == keep[~final].sum()
     assert ks.lib().grad_topk_workspace(plan.ctypes.data_as(ct.c_void_p)) >= int(plan[3]) * 8
     # forced chunk counts
     _, p2 = _plan(ks, [100, 10_000], [5, 10], chunks=7)
-    assert p2[8 + 3] == 7 and p2[8 + 4] == 15 and p2[16 + 3] == 7 and p2[16 + 4] == 1429
+    assert p2[32 + 2] == 7 and p2[32 + 4 + 2] == 7 and p2[6] == 2
+    nodes2 = p2[32 + 8:].reshape(-1, 8)
+    assert nodes2[:7, 1].tolist() == [15] * 6 + [10] and nodes2[7:14, 1].tolist() == [1429] * 6 + [1426]
     _, p3 = _plan(ks, [5], [5], chunks=64)
-    assert p3[8 + 3] == 5 and p3[8 + 4] == 1 and p3[8 + 7] == 1
+    assert p3[32 + 2] == 5 and p3[2] == 6 and p3[6] == 2
 
 
 def test_topk_argument_errors(ks):
