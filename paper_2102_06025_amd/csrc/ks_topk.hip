@@ -659,9 +659,19 @@ struct TkNode {
     int level;
 };
 
+static int64_t tk_plan_build(const int64_t *offsets, const int32_t *k, int T, int chunks, int64_t *plan, int64_t plan_capacity);
+
 extern "C" int64_t grad_topk_plan(const int64_t *offsets, const int32_t *k, int T, int chunks, int64_t *plan,
                                   int64_t plan_capacity) {
     if (!offsets || !k || T < 1 || chunks < 0) return -(int64_t)KS_INVALID_ARG;
+    try {
+        return tk_plan_build(offsets, k, T, chunks, plan, plan_capacity);
+    } catch (...) { // out of host memory while laying out the plan: nothing may escape through the C ABI
+        return -(int64_t)KS_UNSUPPORTED;
+    }
+}
+
+static int64_t tk_plan_build(const int64_t *offsets, const int32_t *k, int T, int chunks, int64_t *plan, int64_t plan_capacity) {
     std::vector<TkNode> nodes;
     std::vector<int64_t> tensors;
     int64_t cand = 0, out = 0;
