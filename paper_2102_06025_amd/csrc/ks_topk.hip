@@ -594,8 +594,8 @@ template <class List> __device__ __forceinline__ void tk_select(const List &list
         hi = lo;
         // at lo == 0 the bin holds a single item, so need == in_bin == 1 and the loop ends
     }
-    // move the chosen members of the boundary bin up behind the items above it (they cannot overlap what is still to
-    // be read: a member at tie[i] lands at an index <= TK_CAP - n_tie + i only if ... so it goes through registers)
+    // move the chosen members of the boundary bin up behind the items above it; the target range may reach into the
+    // bin's own place at the end of the array, so the bin is read into registers first
     uint64_t mv[TK_CAP / TK_NT];
 #pragma unroll
     for (int q = 0; q < TK_CAP / TK_NT; ++q) {
