@@ -15,7 +15,7 @@
 //      in one more pass over the list -- for gradient-like data after the first level, so the list is read twice;
 //   3. the selection goes on inside the boundary bin, now in LDS, down to the item that closes the top-k;
 //   4. a step that is not the last one of its tensor hands its survivors on unsorted; the last step orders its k
-//      survivors (buckets by an 11-bit digit, then ranks inside the buckets), which are the output.
+//      survivors (2,048 buckets over their range, then ranks inside the buckets), which are the output.
 // Tensors with long runs of one magnitude (constant, mostly zero) are caught where they would hurt: wavefronts
 // merge their histogram adds when all lanes hit one bin, and a chunk whose k-th magnitude is shared by more items
 // than LDS holds takes the first of them in index order instead of resolving 32 index bits level by level.
@@ -349,9 +349,9 @@ template <class List> __device__ __forceinline__ void tk_collect(const List &lis
     }
 }
 
-// sh.sort[0 .. k) in any order -> descending order.  Items are spread over up to 2,048 buckets by the 11 bits below
-// the highest bit in which the largest and the smallest differ (histogram, descending prefix, scatter into the
-// upper half of the array), then every item counts the larger items of its bucket: its rank.  Buckets are small
+// sh.sort[0 .. k) in any order -> descending order.  Items are spread over up to 2,048 buckets by their distance from
+// the smallest one (histogram, descending prefix, scatter into the upper half of the array), then every item
+// counts the larger items of its bucket: its rank.  Buckets are small
 // for anything but pathological inputs (which take the bitonic sort instead).  k <= TK_CAP / 2.
 __device__ void tk_order(int k, TkShared &sh) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -380,12 +380,14 @@ __device__ void tk_order(int k, TkShared &sh) {
         mn = b < mn ? b : mn;
     }
     __syncthreads();
-    const uint64_t diff = mx ^ mn;
-    const int h = diff ? 63 - __builtin_clzll(diff) : 0;
-    const int shift = h > 10 ? h - 10 : 0; // digit = 11 bits ending at the highest differing bit
+    // bucket = distance from the smallest item, scaled so that the largest item lands in the last bucket (bits of the
+    // items themselves would not do: neighbours on either side of a power of two differ in every bit)
+    const uint64_t range = mx - mn;
+    const int bits = range ? 64 - __builtin_clzll(range) : 0;
+    const int shift = bits > 11 ? bits - 11 : 0;
     for (int b = tid; b < TK_BINS; b += TK_NT) sh.hist[b] = 0u;
     __syncthreads();
-    for (int i = tid; i < k; i += TK_NT) atomicAdd(&sh.hist[(uint32_t)(sh.sort[i] >> shift) & (TK_BINS - 1)], 1u);
+    for (int i = tid; i < k; i += TK_NT) atomicAdd(&sh.hist[(uint32_t)((sh.sort[i] - mn) >> shift)], 1u);
     __syncthreads();
     // descending exclusive prefix: bucket b starts at the number of items in higher buckets; keep the counts
     constexpr int per = TK_BINS / TK_NT;
@@ -414,12 +416,12 @@ __device__ void tk_order(int k, TkShared &sh) {
     }
     for (int i = tid; i < k; i += TK_NT) {
         const uint64_t x = sh.sort[i];
-        grouped[atomicAdd(&sh.hist[(uint32_t)(x >> shift) & (TK_BINS - 1)], 1u)] = x;
+        grouped[atomicAdd(&sh.hist[(uint32_t)((x - mn) >> shift)], 1u)] = x;
     }
     __syncthreads();
     for (int i = tid; i < k; i += TK_NT) {
         const uint64_t x = grouped[i];
-        const uint32_t b = (uint32_t)(x >> shift) & (TK_BINS - 1);
+        const uint32_t b = (uint32_t)((x - mn) >> shift);
         const int end = (int)sh.hist[b], begin = end - (int)sh.cnt16[b];
         int rank = 0;
         for (int j = begin; j < end; ++j) rank += grouped[j] > x ? 1 : 0;
