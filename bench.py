@@ -284,6 +284,26 @@ def main():
         roofline = dict(bound="hbm", achieved=phases[dom]["gbs"], peak=PEAK_HBM_GBS, unit="GB/s",
                         frac=phases[dom]["frac"], traffic=traffic, kernel=dom)
 
+    # ---- the row gather as a kernel of its own (in the step it is fused into the loaders of the contractions):
+    # A rows of D bf16 values read and written once
+    gather = None
+    if not args.headline_only:
+        gev = hev.create(2)
+        g_out = torch.empty((M, D), dtype=torch.bfloat16, device="cuda")
+        g_st = torch.zeros(1, dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            ks.knn_gather_rows(W_bf, out["active_idx"], out["n_active"], out=g_out, dev_status=g_st)
+        hev.record(gev[0], stream)
+        for _ in range(20):
+            ks.knn_gather_rows(W_bf, out["active_idx"], out["n_active"], out=g_out, dev_status=g_st)
+        hev.record(gev[1], stream)
+        torch.cuda.synchronize()
+        us_g = hev.elapsed_ms(gev[0], gev[1]) * 1e3 / 20
+        bytes_g = A * D * 2.0 * 2
+        gather = dict(us=round(us_g, 2), bound="hbm", gbs=round(bytes_g / (us_g * 1e-6) / 1e9, 1),
+                      frac=round(bytes_g / (us_g * 1e-6) / 1e9 / PEAK_HBM_GBS, 4))
+        log(f"[bench] stand-alone gather of the {A} active rows: {gather}")
+
     normalized_layer = None
     nev = hev.create(2)
     if not args.headline_only:
@@ -503,6 +523,7 @@ def main():
         "phases": phases,
         "graph_build": {"ms": round(graph_best, 2), "tflops": round(graph_tflops, 1),
                         "frac": round(graph_tflops / PEAK_BF16_TFLOPS, 4), "bound": "mfma"},
+        "gather_rows": gather,
         "normalized_layer": normalized_layer,
         "sharded_node": sharded_node,
         "grad_topk": grad_topk,
