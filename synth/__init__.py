@@ -273,6 +273,10 @@ CONFIGS = {
     "shard390k": dict(C=390_625, D=512, B=1_024, K=32, M=32_768, bf16=True, labels="zipf", scale=30.0, seed=0),
     "shard390k_uniform": dict(C=390_625, D=512, B=1_024, K=32, M=32_768, bf16=True, labels="uniform",
                               scale=30.0, seed=0),
+    # the headline shape with clustered class weights (centre[c mod 4096] + 0.3 noise): neighbour lists overlap
+    # heavily, as those of trained weights of similar products do
+    "shard390k_clustered": dict(C=390_625, D=512, B=1_024, K=32, M=32_768, bf16=True, labels="zipf", scale=30.0,
+                                seed=0, weights="clustered"),
     "dense1m": dict(C=1_000_000, D=512, B=2_048, K=64, M=131_072, bf16=True, labels="uniform", scale=30.0,
                     seed=0),
 }
@@ -288,7 +292,10 @@ def make_labels(cfg: dict, seed: int | None = None) -> np.ndarray:
 def make_WX(cfg: dict, seed: int | None = None):
     """(W [C,D] fp32, X [B,D] fp32), on the bf16 grid when cfg['bf16']."""
     seed = cfg["seed"] if seed is None else seed
-    W = unit_rows(seed, TID_W, cfg["C"], cfg["D"], bf16=cfg["bf16"])
+    if cfg.get("weights") == "clustered":
+        W = clustered_rows(seed, cfg["C"], cfg["D"], bf16=cfg["bf16"])
+    else:
+        W = unit_rows(seed, TID_W, cfg["C"], cfg["D"], bf16=cfg["bf16"])
     X = unit_rows(seed, TID_X, cfg["B"], cfg["D"], bf16=cfg["bf16"])
     return W, X
 
