@@ -243,3 +243,11 @@ def test_topk_argument_errors(ks):
     ph = plan.ctypes.data_as(ct.c_void_p)
     assert L.grad_topk_select(None, one, ph, one, one, one, ct.c_size_t(1 << 20), None) == ks.KS_INVALID_ARG
     assert L.grad_topk_select(one, one, ph, one, one, one, ct.c_size_t(8), None) == ks.KS_WORKSPACE_TOO_SMALL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the benchmark measures one GPU's share; asking for more ends with a message and a non-zero status, before any GPU work
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
