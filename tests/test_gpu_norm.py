@@ -8,6 +8,7 @@ import pytest
 import torch
 
 import synth
+from gradcheck import check_step_grads
 
 pytestmark = pytest.mark.gpu
 
@@ -223,6 +224,16 @@ def _layer_step(ks, orc, W, X, y, G, M, scale, grad_scale, lr):
     ref = orc.knn_softmax_fwd_bwd(W_hat, X_hat, active[:A], tpos, scale, grad_scale)
     loss = float(out["loss_mean"].item())
     assert abs(loss - ref["loss"]) <= 1e-3 * abs(ref["loss"])
+    # the gradients with respect to the normalised rows, row by row, against the oracle working from the 16-bit
+    # normalised rows the contractions read (the oracle's own rounding of its own normalised rows)
+    _, Wb_o, _ = orc.normalize_rows(W[active[:A]])
+    _, Xb_o, _ = orc.normalize_rows(X)
+    W16 = np.zeros((C, D), dtype=np.float32)
+    W16[active[:A]] = synth.bf16_to_f32(Wb_o)
+    X16 = synth.bf16_to_f32(Xb_o)
+    ref16 = orc.knn_softmax_fwd_bwd(W16, X16, active[:A], tpos, scale, grad_scale)
+    check_step_grads(out["dX"].cpu().numpy(), out["dW_active"][:A].cpu().numpy(), ref16, W16[active[:A]], X16, tpos, scale,
+                     grad_scale, tag="normalised layer")
     dX_ref = orc.norm_backward(X, ref["dX"])
     eW, _, einv = orc.apply_weight_grad_normalized(W, active[:A], ref["dWA"].astype(np.float32), alpha)
     e_dx = rel_fro(dX.cpu().numpy(), dX_ref)

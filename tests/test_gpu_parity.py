@@ -6,11 +6,12 @@ import pytest
 import torch
 
 import synth
+from gradcheck import GRAD_RTOL, check_rows, check_step_grads, grad_floors
 
 pytestmark = pytest.mark.gpu
 
 LOSS_RTOL = 1e-3
-GRAD_RTOL = 2e-2
+SENTINEL = -12345.0
 
 
 @pytest.fixture(scope="module")
@@ -45,8 +46,17 @@ def run_and_compare(ks, orc, W, X, y, G, C, M, scale=30.0, grad_scale=1.0, tag="
 
 def _run_and_compare_one(ks, W, X, y, G, C, M, scale, grad_scale, tag, unit_rows, active, A, tpos, ref):
     print(f"[case] {tag} C={C} D={W.shape[1]} B={X.shape[0]} K={G.shape[1]} M={M} unit_rows={unit_rows}", flush=True)
+    B, D = X.shape
+    # the gradient buffers start from a sentinel: every row that must be written is, and no row beyond is
+    bufs = dict(active_idx=torch.empty(M, dtype=torch.int32, device="cuda"),
+                n_active=torch.empty(1, dtype=torch.int32, device="cuda"),
+                target_pos=torch.empty(B, dtype=torch.int32, device="cuda"),
+                loss_per_sample=torch.empty(B, dtype=torch.float32, device="cuda"),
+                loss_mean=torch.empty(1, dtype=torch.float32, device="cuda"),
+                dX=torch.full((B, D), SENTINEL, dtype=torch.float32, device="cuda"),
+                dW_active=torch.full((M, D), SENTINEL, dtype=torch.float32, device="cuda"))
     out = ks.knn_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(G), M, scale, grad_scale,
-                                 unit_rows=unit_rows)
+                                 out=bufs, unit_rows=unit_rows)
     torch.cuda.synchronize()
     assert int(out["dev_status"].item()) == 0
     assert int(out["n_active"].item()) == A
@@ -56,10 +66,11 @@ def _run_and_compare_one(ks, W, X, y, G, C, M, scale, grad_scale, tag, unit_rows
     assert np.abs(li - ref["loss_i"]).max() <= LOSS_RTOL * max(1.0, np.abs(ref["loss_i"]).max())
     loss = float(out["loss_mean"].item())
     assert abs(loss - ref["loss"]) <= LOSS_RTOL * abs(ref["loss"]), (loss, ref["loss"])
-    e_dx = rel_fro(out["dX"].cpu().numpy(), ref["dX"])
-    e_dw = rel_fro(out["dW_active"][:A].cpu().numpy(), ref["dWA"])
-    print(f"        A={A} loss={loss:.6f} ref={ref['loss']:.6f} relF(dX)={e_dx:.2e} relF(dW)={e_dw:.2e}", flush=True)
-    assert e_dx <= GRAD_RTOL and e_dw <= GRAD_RTOL
+    print(f"        A={A} loss={loss:.6f} ref={ref['loss']:.6f}", flush=True)
+    # every sample's row of dX and every active class's row of dW_A against the oracle's
+    check_step_grads(out["dX"].cpu().numpy(), out["dW_active"][:A].cpu().numpy(), ref, W[active[:A]], X, tpos, scale,
+                     grad_scale, tag=tag)
+    assert bool((out["dW_active"][A:] == SENTINEL).all()), "rows beyond n_active were written"
     return out
 
 
@@ -169,7 +180,15 @@ def test_knn_equals_full_softmax_when_lists_span_all_classes(ks, orc):
     assert torch.equal(full["dW"], out["dW_active"])
     ofull = orc.full_softmax_fwd_bwd(W, X, y, 30.0, 1.0)
     assert abs(float(full["loss_mean"].item()) - ofull["loss"]) <= LOSS_RTOL * ofull["loss"]
-    assert rel_fro(full["dW"].cpu().numpy(), ofull["dW"]) <= GRAD_RTOL
+    _check_full(full, ofull, W, X, y, 30.0, 1.0, "full K=C-1")
+
+
+def _check_full(full, ref, W, X, y, scale, grad_scale, tag):
+    """Full softmax: every row of dX and of the dense dW [C, D] against the oracle's full-softmax function."""
+    lse = ref["loss_i"] + scale * (X.astype(np.float64) * W[y].astype(np.float64)).sum(axis=1)   # loss_i = lse - z_target
+    f_dx, f_dw = grad_floors(W, X, np.asarray(y), lse, scale, grad_scale / X.shape[0])
+    check_rows(full["dX"].cpu().numpy(), ref["dX"], f_dx, f"{tag} dX")
+    check_rows(full["dW"].cpu().numpy(), ref["dW"], f_dw, f"{tag} dW")
 
 
 @pytest.mark.parametrize("unit_rows", [False, True])
@@ -183,8 +202,7 @@ def test_full_softmax_on_20000_class_slice(ks, orc, unit_rows):
     assert int(full["dev_status"].item()) == 0
     ref = orc.full_softmax_fwd_bwd(W, X, y, 30.0, 1.0)
     assert abs(float(full["loss_mean"].item()) - ref["loss"]) <= LOSS_RTOL * ref["loss"]
-    assert rel_fro(full["dX"].cpu().numpy(), ref["dX"]) <= GRAD_RTOL
-    assert rel_fro(full["dW"].cpu().numpy(), ref["dW"]) <= GRAD_RTOL
+    _check_full(full, ref, W, X, y, 30.0, 1.0, f"full 20k unit_rows={unit_rows}")
 
 
 @pytest.mark.parametrize("unit_rows", [False, True])
@@ -424,12 +442,19 @@ def test_one_call_step_equals_forward_backward_then_update(ks, orc, name, unit_r
     else:
         assert b["dW_active"] is None
     # and against the oracle: the change of the touched rows
-    active = a["active_idx"][:A].cpu().numpy()
-    tpos = a["target_pos"].cpu().numpy()
+    active, A_ref, tpos = orc.select_active(y, G, C, M)
+    active = active[:A_ref]
+    assert A == A_ref and (a["active_idx"][:A].cpu().numpy() == active).all()
+    assert (a["target_pos"].cpu().numpy() == tpos).all()
     ref = orc.knn_softmax_fwd_bwd(W, synth.bf16_round(X), active, tpos, scale, gs)
     eW, _ = orc.apply_weight_grad(W, active, ref["dWA"].astype(np.float32), alpha, want_bf16=False)
     got = Wm2[torch.from_numpy(active.astype(np.int64)).cuda()].cpu().numpy().astype(np.float64)
     assert rel_fro(got - W[active], eW[active].astype(np.float64) - W[active]) <= GRAD_RTOL
+    # row by row: the change of every touched row is alpha times the oracle's gradient row, up to the rounding of the
+    # stored logit gradient and one fp32 rounding of the updated row
+    _, f_dw = grad_floors(W[active], synth.bf16_round(X), tpos, ref["lse"], scale, gs / B)
+    f_dw = f_dw + 2.0 ** -24 * np.linalg.norm(W[active].astype(np.float64), axis=1) / abs(alpha)
+    check_rows((got - W[active]) / alpha, ref["dWA"], f_dw, f"{name} weight change / alpha")
     rest = np.setdiff1d(np.arange(C), active)
     assert (Wm2.cpu().numpy()[rest] == W[rest]).all()
 
