@@ -21,7 +21,8 @@ ORC_OK, ORC_BAD_ARG, ORC_BAD_LABEL, ORC_BAD_GRAPH_ID = 0, 1, 2, 3
 def lib():
     global _lib
     if _lib is None:
-        path = _build(force=False) if not os.path.exists(LIB) else LIB
+        # ORACLE_LIB_PATH: another build of the same sources (the sanitizer build of the oracle's own test)
+        path = os.environ.get("ORACLE_LIB_PATH") or (_build(force=False) if not os.path.exists(LIB) else LIB)
         _lib = ct.CDLL(path)
         _lib.orc_num_threads.restype = ct.c_int
         for name in ("orc_graph_bruteforce", "orc_select_active", "orc_knn_softmax_fwd_bwd",

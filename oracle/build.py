@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(HERE, "knn_softmax_oracle.c")
 SRCS = [SRC, os.path.join(HERE, "topk_oracle.c")]
 LIB = os.path.join(HERE, "liboracle.so")
+LIB_SANITIZED = os.path.join(HERE, "liboracle_sanitized.so")
 
 
 def build(force: bool = True) -> str:
@@ -18,6 +19,21 @@ def build(force: bool = True) -> str:
            "-ffp-contract=off", "-o", LIB] + SRCS + ["-lm"]
     subprocess.check_call(cmd)
     return LIB
+
+
+def build_sanitized() -> str:
+    """The same sources under AddressSanitizer and UndefinedBehaviorSanitizer (-O1, host code only), for the test that
+    runs a small case of every exported function through it.  A process that loads it must have the sanitizer
+    runtime loaded first (LD_PRELOAD of `gcc -print-file-name=libasan.so`)."""
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra", "-ffp-contract=off",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+           "-o", LIB_SANITIZED] + SRCS + ["-lm"]
+    subprocess.check_call(cmd)
+    return LIB_SANITIZED
+
+
+def sanitizer_runtime() -> str:
+    return subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
 
 
 if __name__ == "__main__":

@@ -483,6 +483,65 @@ def test_apply_weight_grad_normalized_against_numpy(orc):
     assert np.all(np.abs(n2 - n1) <= step ** 2 / n1 + 1e-6)
 
 
+def test_apply_weight_grad_normalized_is_a_gradient_step_of_a_loss_of_the_normalised_rows(orc):
+    """Independent of the projection formula: take any scalar loss L(W) = f(W_hat) of the normalised rows, hand the
+    update the gradient of f with respect to W_hat, and the change of W must be alpha times the gradient of L with
+    respect to W itself -- which central differences of L (normalisation written out in numpy, fp64) give without
+    any formula for the Jacobian.  f is a cubic, so that its gradient depends on the point."""
+    C, D = 12, 10
+    W = _raw_rows(8, synth.TID_W, C, D)
+    W64 = W.astype(np.float64)
+    Q = synth.normal(8, synth.TID_MISC, 0, C * D).reshape(C, D)
+    R = synth.normal(9, synth.TID_MISC, 0, C * D).reshape(C, D)
+
+    def hat(V):
+        return V / np.sqrt((V * V).sum(axis=1, keepdims=True))
+
+    def loss(V):                                   # f(V_hat) = sum Q * V_hat + sum R * V_hat^3
+        H = hat(V)
+        return float((Q * H).sum() + (R * H ** 3).sum())
+
+    H0 = hat(W64)
+    grad_f = (Q + 3.0 * R * H0 ** 2).astype(np.float32)      # df/dW_hat at the starting point (what the layer passes on)
+    idx = np.array([1, 4, 7, 9, 11], dtype=np.int32)
+    alpha = -0.125
+    Wm, _, _ = orc.apply_weight_grad_normalized(W, idx, grad_f[idx], alpha)
+    h = 1e-6
+    for c in idx:
+        fd = np.empty(D)
+        for d in range(D):
+            Vp, Vn = W64.copy(), W64.copy()
+            Vp[c, d] += h
+            Vn[c, d] -= h
+            fd[d] = (loss(Vp) - loss(Vn)) / (2 * h)
+        step = Wm[c].astype(np.float64) - W64[c]
+        assert np.abs(step - alpha * fd).max() <= 1e-6 * np.abs(alpha * fd).max() + 2.0 ** -23 * np.abs(W64[c]).max()
+    rest = np.setdiff1d(np.arange(C), idx)
+    assert np.array_equal(Wm[rest], W[rest])
+
+
+def test_apply_weight_grad_normalized_equals_the_two_pinned_steps_composed(orc):
+    """Projection through the normalisation (orc_norm_backward, pinned by finite differences) followed by the plain
+    update (orc_apply_weight_grad, pinned against numpy's add.at): the same master rows up to the fp32 rounding of the
+    projected gradient that the composed version hands over; repeated indices included (the projection is linear)."""
+    C, D, n = 60, 24, 40
+    W = _raw_rows(10, synth.TID_W, C, D)
+    rng = np.random.default_rng(4)
+    idx = rng.integers(0, C // 2, n).astype(np.int32)
+    dWh = synth.grad_rows(10, n, D).astype(np.float32)
+    alpha = 0.2
+    Wm, Wb, inv = orc.apply_weight_grad_normalized(W, idx, dWh, alpha)
+    dW = orc.norm_backward(W[idx], dWh.astype(np.float64))                 # row p: projected with the row of class idx[p]
+    Wc, _ = orc.apply_weight_grad(W, idx, dW.astype(np.float32), alpha, want_bf16=False)
+    mult = np.bincount(idx, minlength=C).max()
+    tol = 2.0 ** -23 * np.abs(Wc).max() + mult * 2.0 ** -24 * abs(alpha) * np.abs(dW).max()
+    assert np.abs(Wm.astype(np.float64) - Wc).max() <= tol
+    # the refreshed copies describe the stored rows (normalize_rows has its own closed-form pins)
+    touched = np.unique(idx)
+    _, eb, einv = orc.normalize_rows(Wm[touched])
+    assert np.array_equal(Wb[touched], eb) and np.array_equal(inv[touched], einv)
+
+
 # ------------------------------------------------------------------------------------------------
 # compressed graph of one node, selection on it, random fill-up (Section 3.2.3, Algorithm 1)
 # ------------------------------------------------------------------------------------------------
