@@ -12,18 +12,21 @@ cause in that row:
   * row a of dW_A = s * sum_i dZ[i, a] * X[i, :]  =>  || error || <= EPS * s * sigma_max(X) * || dZ[:, a] ||_2;
   * row i of dX   = s * sum_a dZ[i, a] * W_A[a, :] =>  || error || <= EPS * s * sigma_max(W_A) * || dZ[i, :] ||_2,
 
-sigma_max being the largest singular value.  One more term covers the softmax itself being evaluated in fp32: a
-probability next to 1 is only known to 2^-24, so the target entry g * (P_t - 1) of a confident sample carries an
-ABSOLUTE error of up to EPS32 * g with EPS32 = 2^-23 (any fp32 softmax has it; for such a sample the whole row of dX
-is of that size).  It adds  EPS32 * s * g * || w_target ||  to the floor of the sample's row of dX and
-EPS32 * s * g * sum over the samples of class a of || x_i ||  to the floor of row a of dW_A.  The fp32
-accumulation of the contractions is left to rtol.  The floors are bounds on a tolerance, not expected values: they
-are evaluated here in numpy (fp64) from the inputs and the oracle's log-sum-exp.  A zeroed, permuted or stale row
+sigma_max being the largest singular value.  One more term covers the logits being fp32 sums: the matrix cores add
+the D products of a logit into an fp32 accumulator in D/16 steps of 16 products, each step rounding once at the size
+of the partial sum (at most |x||w|), and the log-sum-exp and the exponent's argument are rounded as well, so a logit
+is known to  dz = s * (D/16 + 4) * 2^-24 * |x| * |w|.  That moves a probability by the RELATIVE amount dz, far
+below the bf16 term, except where it matters absolutely: the target entry g * (P_t - 1) of a confident sample
+(P_t next to 1) moves by up to g * dz, and for such a sample the whole row of dX is of that size.  It adds
+s * g * dz_i * |w_target|  to the floor of the sample's row of dX and  s * g * sum over the samples i of class a of
+dz_i * |x_i|  to the floor of row a of dW_A.  The rest of the fp32 accumulation of the contractions is left to
+rtol.  The floors are bounds on a tolerance, not expected values: they are evaluated here in numpy (fp64) from the
+inputs and the oracle's log-sum-exp.  A zeroed, permuted or stale row
 misses its reference by about its whole length and fails."""
 import numpy as np
 
 EPS_BF16_TWICE = 2.0 ** -8
-EPS32 = 2.0 ** -23
+EPS32 = 2.0 ** -24
 GRAD_RTOL = 2e-2
 
 
@@ -53,12 +56,14 @@ def grad_floors(W_A, X, tpos, lse, scale, g, chunk=8192):
         col[a0:a1] = np.sqrt((dZ * dZ).sum(axis=0))
     floor_dX = EPS_BF16_TWICE * scale * sigma_max(W_A) * np.sqrt(row_sq)
     floor_dW = EPS_BF16_TWICE * scale * sigma_max(X) * col
-    # fp32 resolution of the target probability
+    # fp32 evaluation of the target logit
     tpos = np.asarray(tpos)
     own = np.nonzero((tpos >= 0) & (tpos < A))[0]
-    x_len = np.linalg.norm(X, axis=1)
-    floor_dX[own] += EPS32 * scale * g * np.linalg.norm(W_A[tpos[own]], axis=1)
-    np.add.at(floor_dW, tpos[own], EPS32 * scale * g * x_len[own])
+    x_len = np.linalg.norm(X, axis=1)[own]
+    w_len = np.linalg.norm(W_A[tpos[own]], axis=1)
+    dz = scale * (X.shape[1] / 16.0 + 4.0) * EPS32 * x_len * w_len
+    floor_dX[own] += scale * g * dz * w_len
+    np.add.at(floor_dW, tpos[own], scale * g * dz * x_len)
     return floor_dX, floor_dW
 
 
