@@ -100,6 +100,24 @@ int knn_select_active(const int32_t *labels, const int32_t *graph, int64_t C, in
                       void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
 /* ------------------------------------------------------------------------------------------------------
+ * knn_select_active_static -- knn_select_active for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments (without ws / ws_bytes), same kernels, same results bit for bit; the scratch memory the kernels need
+ * (the staging array of the candidates, or the score table of the large-C path) is a device array of
+ * KS_SELECT_STATIC_BYTES that is part of the library's code object: every GPU the library runs on holds its own
+ * copy from the first call on that GPU until the process ends.  The call allocates nothing and frees nothing.
+ *
+ * Limit: knn_select_workspace(C, B, K, M) <= KS_SELECT_STATIC_BYTES, else KS_UNSUPPORTED (nothing is launched).
+ * All calls on one GPU share the one array: calls that overlap in time on the same GPU (different streams or
+ * threads) race with each other; calls on one stream are ordered and safe.  Nothing in the array has to
+ * survive between calls and nothing has to be zero on entry (the kernels write every word before reading it).
+ * ---------------------------------------------------------------------------------------------------- */
+#define KS_SELECT_STATIC_BYTES (2u << 20)
+int knn_select_active_static(const int32_t *labels, const int32_t *graph, int64_t C, int B, int K, int M,
+                             int32_t *active_idx, int32_t *n_active, int32_t *target_pos,
+                             int32_t *dev_status, void *stream);
+
+/* ------------------------------------------------------------------------------------------------------
  * knn_gather_rows -- W_active of Algorithm 1 as a dense matrix: out[a, :] = W_bf16[active_idx[a], :] for
  * a < *n_active.  (knn_softmax_fwd_bwd gathers inside its matrix kernels and does not call this; it is
  * exported for callers that want the rows, and to measure the gather on its own.)

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_select_workspace",
-           "knn_select_active", "knn_gather_rows", "knn_softmax_workspace", "knn_softmax_fwd_bwd",
+           "knn_select_active", "knn_select_active_static", "knn_gather_rows", "knn_softmax_workspace", "knn_softmax_fwd_bwd",
            "full_softmax_workspace", "full_softmax_fwd_bwd", "apply_weight_grad_workspace", "apply_weight_grad",
            "knn_normalize_rows", "knn_norm_backward_rows", "apply_weight_grad_normalized_workspace",
            "apply_weight_grad_normalized", "knn_graph_compress_workspace", "knn_graph_compress",
@@ -146,6 +146,33 @@ def knn_select_active(labels, graph, C, M, ws=None, dev_status=None, stream=None
                                  _ptr(active_idx), _ptr(n_active), _ptr(target_pos), _ptr(ws),
                                  ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
     _check("knn_select_active", rc)
+    return active_idx, n_active, target_pos, dev_status
+
+
+KS_SELECT_STATIC_BYTES = 2 << 20
+
+
+def knn_select_active_static(labels, graph, C, M, out=None, dev_status=None, stream=None):
+    """knn_select_active without a workspace: the library's own static device array serves as scratch (sizes up to
+    knn_select_workspace(...) <= KS_SELECT_STATIC_BYTES).  `out` = (active_idx [M], n_active [1], target_pos [B])
+    are used as the outputs when given, so that the call allocates nothing at all."""
+    _need(labels, torch.int32, "labels")
+    B = labels.numel()
+    K = 0 if graph is None else graph.shape[1]
+    if graph is not None:
+        _need(graph, torch.int32, "graph")
+    dev = labels.device
+    if out is None:
+        out = (torch.empty(M, dtype=torch.int32, device=dev), torch.empty(1, dtype=torch.int32, device=dev),
+               torch.empty(B, dtype=torch.int32, device=dev))
+    active_idx, n_active, target_pos = out
+    if active_idx.numel() < M or target_pos.numel() < B:
+        raise ValueError("out = (active_idx [M], n_active [1], target_pos [B])")
+    dev_status = _status(dev, dev_status)
+    rc = lib().knn_select_active_static(_ptr(labels), _ptr(graph), ct.c_int64(C), ct.c_int(B), ct.c_int(K), ct.c_int(M),
+                                        _ptr(active_idx), _ptr(n_active), _ptr(target_pos), _ptr(dev_status),
+                                        _stream(stream))
+    _check("knn_select_active_static", rc)
     return active_idx, n_active, target_pos, dev_status
 
 

@@ -11,6 +11,7 @@
 // neighbours this node owns, as local ids, lists of different lengths laid end to end and found through a
 // running sum of their lengths).  The random fill-up of Algorithm 1 is an optional last stage of both.
 #include "ks_select.h"
+#include <mutex>
 
 #define SEL_NT 256
 #define SEL_PER 8
@@ -603,6 +604,44 @@ extern "C" int knn_select_active(const int32_t *labels, const int32_t *graph, in
     if (B > M || (int64_t)K + 1 > M) return KS_INVALID_ARG;
     if (ws_bytes < ks_select_ws_bytes(C, B, K)) return KS_WORKSPACE_TOO_SMALL;
     return ks_select_launch(labels, graph, C, B, K, M, active_idx, n_active, target_pos, ws, dev_status,
+                            (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The selection for callers that cannot allocate: its scratch memory is this file-scope device array.  In host
+// code the array's name is only a handle of the symbol; the address of each GPU's copy is asked for once per
+// device (hipGetSymbolAddress, with that device current) and kept.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[KS_SELECT_STATIC_BYTES];
+#define KS_MAX_DEVICES 64
+static void *g_scratch_ptr[KS_MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+static int sel_scratch_for_current_device(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= KS_MAX_DEVICES) return KS_HIP_ERROR;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KS_HIP_ERROR;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return KS_OK;
+}
+
+extern "C" int knn_select_active_static(const int32_t *labels, const int32_t *graph, int64_t C, int B, int K, int M,
+                                        int32_t *active_idx, int32_t *n_active, int32_t *target_pos, int32_t *dev_status,
+                                        void *stream) {
+    if (!labels || !active_idx || !n_active || !target_pos) return KS_INVALID_ARG;
+    if (C < 1 || C >= (int64_t)1 << 31 || B < 1 || K < 0 || M < 1) return KS_INVALID_ARG;
+    if (K > 0 && !graph) return KS_INVALID_ARG;
+    if (B > M || (int64_t)K + 1 > M) return KS_INVALID_ARG;
+    if (ks_select_ws_bytes(C, B, K) > (size_t)KS_SELECT_STATIC_BYTES) return KS_UNSUPPORTED;
+    void *ptr = nullptr;
+    const int rc = sel_scratch_for_current_device(&ptr);
+    if (rc != KS_OK) return rc;
+    return ks_select_launch(labels, graph, C, B, K, M, active_idx, n_active, target_pos, ptr, dev_status,
                             (hipStream_t)stream);
 }
 

@@ -23,14 +23,14 @@ def ks():
 def _declared_functions():
     src = open(HEADER).read() + open(os.path.join(ROOT, "include", "grad_topk.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update|_stats|_profiled|_plan|_select))\s*\(", src)))
+    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update|_stats|_profiled|_plan|_select|_static))\s*\(", src)))
 
 
 def test_header_symbols_are_exported(ks):
     names = _declared_functions()
     assert {"knn_graph_build", "knn_softmax_fwd_bwd", "apply_weight_grad", "apply_weight_grad_normalized",
             "knn_normalize_rows", "knn_norm_backward_rows", "grad_topk_plan", "grad_topk_workspace",
-            "grad_topk_select"} <= set(names)
+            "grad_topk_select", "knn_select_active_static"} <= set(names)
     L = ks.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in the header but not exported"
@@ -251,3 +251,24 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
+
+
+def test_static_selection_rejects_sizes_beyond_its_scratch_array_before_any_launch(ks):
+    """knn_select_active_static: sizes whose scratch need exceeds KS_SELECT_STATIC_BYTES are KS_UNSUPPORTED, bad
+    arguments KS_INVALID_ARG; neither touches the device (no GPU here)."""
+    L = ks.lib()
+    null, one = ct.c_void_p(0), ct.c_void_p(256)
+    i64, i = ct.c_int64, ct.c_int
+
+    def sel(C=390_625, B=1024, K=32, M=32_768, labels=one):
+        return L.knn_select_active_static(labels, one, i64(C), i(B), i(K), i(M), one, one, one, null, null)
+
+    src = open(HEADER).read()
+    limit = int(re.search(r"#define KS_SELECT_STATIC_BYTES \((\d+)u << (\d+)\)", src).group(1)) << 20
+    assert limit == ks.binding.KS_SELECT_STATIC_BYTES
+    assert ks.knn_select_workspace(390_625, 1024, 32, 32_768) <= limit       # the headline shape fits
+    assert ks.knn_select_workspace(1_000_000, 2048, 64, 131_072) > limit
+    assert sel(C=1_000_000, B=2048, K=64, M=131_072) == ks.KS_UNSUPPORTED
+    assert sel(B=20_000, K=32) == ks.KS_UNSUPPORTED                          # staging array of 20,000 x 33 candidates
+    assert sel(labels=null) == ks.KS_INVALID_ARG
+    assert sel(B=40_000) == ks.KS_INVALID_ARG                                # B > M
