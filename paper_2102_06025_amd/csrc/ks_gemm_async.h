@@ -68,6 +68,11 @@ template <int ROWS, int NW> struct KsARows {
         for (int j = 0; j < NI; ++j)
             __builtin_amdgcn_global_load_lds(KS_GPTR(ptr[j] + k0), KS_LPTR(lds + (j * NW + wave) * 8 * 64), 16, 0, 0);
     }
+    // the j-th of them alone (j is a compile-time constant after unrolling)
+    __device__ __forceinline__ void issue_one(int j, int k0, uint16_t *lds) const {
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        __builtin_amdgcn_global_load_lds(KS_GPTR(ptr[j] + k0), KS_LPTR(lds + (j * NW + wave) * 8 * 64), 16, 0, 0);
+    }
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -117,6 +122,17 @@ template <int W, int NW> struct KsAKmaj {
             const int64_t src = lidx ? (int64_t)lidx[kg - k_first] : (int64_t)kg;
             __builtin_amdgcn_global_load_lds(KS_GPTR(base + src * ld + col), KS_LPTR(lds + (j * NW + wave) * RPI * W), 16, 0, 0);
         }
+    }
+    __device__ __forceinline__ void issue_one(int j, int k0, uint16_t *lds) const {
+        const int lane = threadIdx.x & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int k = kloc[j];
+        int col = col_base + (((lane % CPR) ^ ((k & 3) << 2)) * 8);
+        if (col > col_lim8) col = col_lim8;
+        int kg = k0 + k;
+        if (kg >= k_limit) kg = k_limit - 1;
+        const int64_t src = lidx ? (int64_t)lidx[kg - k_first] : (int64_t)kg;
+        __builtin_amdgcn_global_load_lds(KS_GPTR(base + src * ld + col), KS_LPTR(lds + (j * NW + wave) * RPI * W), 16, 0, 0);
     }
 };
 
@@ -261,6 +277,88 @@ __device__ __forceinline__ void ks_a_mainloop(AR &ar, BR &br, int kt0, int kt1, 
         }
         ks_a_tile_mma<T, AK, BK>(lds + stage * T::STAGE_ELEMS, acc);
         if (++stage == S) stage = 0;
+    }
+    ks_barrier_nofence();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Main loop with the loads of the next k-tile INTERLEAVED with the MFMAs of the current one.  A wavefront that
+// requests a direct-to-LDS load stalls until the vector-memory pipeline of the compute unit accepts it, and that
+// pipeline takes a 1 KB request about every 32 clocks: the 64 requests of a 256 x 256 x 64 k-tile keep it busy for
+// as long as the k-tile's MFMAs keep the matrix pipes busy.  Requested in one burst after the barrier (ks_a_mainloop)
+// all eight wavefronts sit in that queue first and compute afterwards: the two times add up.  Here each wavefront
+// requests one load every few MFMAs, over the first SPREAD of the k-tile's four k-steps (the rest of the k-tile is
+// left for the last loads to land): while one wavefront of a SIMD waits to get a request accepted, the other one's
+// MFMAs run.  Two stages only: the loads of tile t + 1 go out during tile t.
+// ---------------------------------------------------------------------------------------------
+template <class T, int KK, int SLOTS, class Issue>
+__device__ __forceinline__ void ks_a_mma_il(const KsAFrags<T> &f, f32x16_t (&acc)[T::FM][T::FN], bool do_load, Issue &issue) {
+    constexpr int NL = T::NI_A + T::NI_B, PER = T::FM * T::FN;
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+        for (int fn = 0; fn < T::FN; ++fn) {
+            constexpr int dummy = 0;
+            (void)dummy;
+            const int idx = KK * PER + fm * T::FN + fn; // constant after unrolling
+#pragma unroll
+            for (int q = 0; q < NL; ++q)
+                if (q * SLOTS / NL == idx) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (do_load) issue(q);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            acc[fm][fn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[fm], f.b[fn], acc[fm][fn], 0, 0, 0);
+        }
+}
+
+template <class T, bool AK, bool BK, int SPREAD, class Issue>
+__device__ __forceinline__ void ks_a_tile_mma_il(const uint16_t *st, f32x16_t (&acc)[T::FM][T::FN], bool do_load, Issue &issue) {
+    const uint16_t *stA = st, *stB = st + T::BM * 64;
+    constexpr int N = KsAFragCount<T, AK, BK>::N;
+    constexpr int SLOTS = SPREAD * T::FM * T::FN;
+    KsAFrags<T> f0, f1;
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_load_frags<T, AK, BK>(f0, stA, stB, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_load_frags<T, AK, BK>(f1, stA, stB, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_wait_frags<T, AK, BK, N>(f0);
+    ks_a_mma_il<T, 0, SLOTS>(f0, acc, do_load, issue);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_load_frags<T, AK, BK>(f0, stA, stB, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_wait_frags<T, AK, BK, N>(f1);
+    ks_a_mma_il<T, 1, SLOTS>(f1, acc, do_load, issue);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_load_frags<T, AK, BK>(f1, stA, stB, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_wait_frags<T, AK, BK, N>(f0);
+    ks_a_mma_il<T, 2, SLOTS>(f0, acc, do_load, issue);
+    __builtin_amdgcn_sched_barrier(0);
+    ks_a_wait_frags<T, AK, BK, 0>(f1);
+    ks_a_mma_il<T, 3, SLOTS>(f1, acc, do_load, issue);
+}
+
+template <class T, bool AK = false, bool BK = false, int SPREAD = 3, class AR, class BR>
+__device__ __forceinline__ void ks_a_mainloop_il(AR &ar, BR &br, int kt0, int kt1, uint16_t *lds,
+                                                 f32x16_t (&acc)[T::FM][T::FN]) {
+    static_assert(T::STAGES == 2 && SPREAD >= 1 && SPREAD <= 4, "two stages");
+    if (kt0 >= kt1) return;
+    ar.issue(kt0 * 64, lds);
+    br.issue(kt0 * 64, lds + T::BM * 64);
+    int stage = 0;
+    for (int kt = kt0; kt < kt1; ++kt) {
+        ks_wait_vmcnt<0>();
+        ks_barrier_nofence();
+        uint16_t *nst = lds + (stage ^ 1) * T::STAGE_ELEMS;
+        const int k0n = (kt + 1) * 64;
+        auto issue = [&](int q) __attribute__((always_inline)) {
+            if (q < T::NI_A) ar.issue_one(q, k0n, nst);
+            else br.issue_one(q - T::NI_A, k0n, nst + T::BM * 64);
+        };
+        ks_a_tile_mma_il<T, AK, BK, SPREAD>(lds + stage * T::STAGE_ELEMS, acc, kt + 1 < kt1, issue);
+        stage ^= 1;
     }
     ks_barrier_nofence();
 }

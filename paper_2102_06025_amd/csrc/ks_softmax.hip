@@ -14,6 +14,15 @@
 #include "ks_gemm_soe.h"
 #include "ks_select.h"
 
+#ifndef KS_DX_IL
+#define KS_DX_IL 0
+#endif
+#ifndef KS_DW_IL
+#define KS_DW_IL 1
+#endif
+#ifndef KS_IL_SPREAD
+#define KS_IL_SPREAD 2
+#endif
 typedef KsTile<128, 128, 64, 2, 2> TileG;      // generic path (any D % 32 == 0)
 typedef KsATile<256, 256, 2, 4, 2> TileSm;     // fast path (D % 64 == 0): tile = 256 classes x 256 samples
 typedef KsATile<128, 128, 2, 2, 2> TileDx;
@@ -947,7 +956,11 @@ dx_partial_async_kernel(const uint16_t *__restrict__ dZT, int Bp, int64_t Mp, co
         KsAKmaj<T::BN, T::NW> br;
         ar.init(dZT, Bp, nullptr, tm * T::BM, Bp, (int)Mp, kt0 * 64);
         br.init(W, D, s_idx, tn * T::BN, D, kt1 * 64, kt0 * 64);
+#if KS_DX_IL
+        ks_a_mainloop_il<T, true, true, KS_IL_SPREAD>(ar, br, kt0, kt1, lds, acc);
+#else
         ks_a_mainloop<T, true, true>(ar, br, kt0, kt1, lds, acc);
+#endif
     }
     float *out = part + (int64_t)s * B * D;
     ks_a_foreach<T>(acc, [&](int m, int n, float v) {
@@ -1058,7 +1071,11 @@ __device__ __forceinline__ void dw_tile(uint16_t *lds, const uint16_t *__restric
     br.init(X, D, nullptr, tn * T::BN, D, B, 0);
     f32x16_t acc[T::FM][T::FN];
     ks_a_clear<T>(acc);
+#if KS_DW_IL
+    ks_a_mainloop_il<T, false, true, KS_IL_SPREAD>(ar, br, 0, Bp / 64, lds, acc);
+#else
     ks_a_mainloop<T, false, true>(ar, br, 0, Bp / 64, lds, acc);
+#endif
     // epilogue, row-wise through LDS: gradient rows out (if wanted) and, if asked for, the update of the master
     // rows and of their 16-bit copy.  Four rows per thread are in flight at a time.
     typedef KsASlab<T> SL;
