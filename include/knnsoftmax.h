@@ -171,6 +171,26 @@ int knn_softmax_fwd_bwd_update(float *W_master, uint16_t *W_bf16, const uint16_t
                                int32_t *target_pos, float *loss_per_sample, float *loss_mean, float *dX,
                                float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
+/* knn_softmax_fwd_bwd_update_selected -- the step without its first stage: the active list comes in as
+ * computed by an earlier knn_select_active (or knn_select_active_csr) call.  Algorithm 1 only reads the labels and
+ * the graph, so a training loop can run the selection of batch n + 1 on a second stream while the contractions of
+ * batch n run (Section 3.2.1 asks for the active classes to be fetched quickly: here the fetch leaves the
+ * critical path altogether).  Everything else as in knn_softmax_fwd_bwd_update, with the same results bit for bit.
+ *
+ *   active_idx [M], n_active [1], target_pos [B]     in (device): the outputs of the selection
+ *   W_master                                         may be NULL: no update (then dW_active is required)
+ * The list is validated on the device before use: ids outside [0, C) raise KS_DEV_BAD_INDEX, a count outside
+ * [0, M] KS_DEV_BAD_COUNT, target positions at or beyond the count KS_DEV_BAD_LABEL; the outputs are then
+ * unspecified, but every access stays in bounds.  Target positions must lie in [0, *n_active), as the selection
+ * on a GPU that owns all classes produces them (a node of a sharded layer uses the split-softmax calls below).
+ * Requires D % 32 == 0, B <= M. */
+size_t knn_softmax_selected_workspace(int64_t C, int D, int B, int M);
+int knn_softmax_fwd_bwd_update_selected(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16,
+                                        const int32_t *active_idx, const int32_t *n_active, const int32_t *target_pos,
+                                        int64_t C, int D, int B, int M, float scale, float grad_scale, float alpha,
+                                        uint32_t flags, float *loss_per_sample, float *loss_mean, float *dX,
+                                        float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
+
 /* Measurement aid: knn_softmax_fwd_bwd (W_master == NULL) or knn_softmax_fwd_bwd_update with one hipEvent_t
  * recorded on `stream` at each stage boundary, so that a caller can time the stages of a step without a profiler.
  * events[0..KS_N_PHASE_EVENTS) are created by the caller (hipEventCreate); event k is recorded: 0 at entry, 1
@@ -220,7 +240,7 @@ int apply_weight_grad(float *W_master, uint16_t *W_bf16, const int32_t *idx, con
 /* ------------------------------------------------------------------------------------------------------
  * The softmax split over the nodes of the model-parallel layer -- Section 3.1, steps 3 to 5: every node
  * computes the logits of its own classes for the whole (gathered) batch; the softmax needs each sample's maximum
- * and sum of exponentials over all nodes, which the nodes exchange (a tiny message, Section 3.4); then every node
+ * and sum of exponentials over all nodes, which the nodes exchange (a tiny message, Section 3.3.1); then every node
  * forms the gradient of its own logits, its weight gradient and its contribution to the feature gradient.
  * This is one node's half of it, in two calls around the exchange:
  *
@@ -324,7 +344,7 @@ int knn_select_active_csr(const int32_t *labels, const int32_t *counts, const in
                           int32_t *target_pos, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
 /* ------------------------------------------------------------------------------------------------------
- * Normalisation inside the layer -- Section 3.2.1: the graph and the softmax work on normalised W and X,
+ * Normalisation inside the layer -- Section 3.2.3 (GPU pipeline, step 2): the graph and the softmax work on normalised W and X,
  * and the normalisation itself runs on the GPU.  The layer keeps W un-normalised in fp32 (W_master), its
  * contractions read the normalised 16-bit copy W_hat = W / |W| (row-wise L2 norm; pass it wherever an entry
  * point above takes W_bf16, with KS_FLAG_UNIT_ROWS), and a gradient g with respect to a normalised row is
@@ -356,6 +376,19 @@ int apply_weight_grad_normalized(float *W_master, uint16_t *W_hat_bf16, float *i
                                  const int32_t *n, int n_max, const float *dW_hat, float alpha, int64_t C, int D,
                                  int idx_sorted_unique, void *ws, size_t ws_bytes, int32_t *dev_status,
                                  void *stream);
+
+/* ------------------------------------------------------------------------------------------------------
+ * Measurement aids for the roofline report: what the chip sustains on the two resources the kernels are priced
+ * against (the nominal peaks are 2.5 PFLOP/s of dense bf16 matrix work and 8 TB/s of HBM traffic).
+ *   ks_peak_mfma  launches a loop of independent 32x32x16 bf16 matrix instructions on registers only;
+ *                 *flops (host, may be NULL) receives the number of floating-point operations of the launch;
+ *                 out (device) needs workgroups * 256 floats
+ *   ks_peak_copy  launches a streaming copy of `bytes` (multiple of 16) from src to dst (device, 16-byte aligned);
+ *                 the traffic of the launch is 2 * bytes
+ * The caller times the launches with events on `stream` and divides.
+ * ---------------------------------------------------------------------------------------------------- */
+int ks_peak_mfma(float *out, int workgroups, int iters, double *flops, void *stream);
+int ks_peak_copy(const void *src, void *dst, size_t bytes, int workgroups, void *stream);
 
 #ifdef __cplusplus
 }

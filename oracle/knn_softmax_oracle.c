@@ -600,7 +600,7 @@ int orc_apply_weight_grad(float *Wm, uint16_t *Wb, const int32_t *idx, int n, co
 }
 
 /* ---------------------------------------------------------------------------------------------
- * Normalisation of the rows of W and X inside the layer (Section 3.2.1: the GPU pipeline normalises
+ * Normalisation of the rows of W and X inside the layer (Section 3.2.3: the GPU pipeline normalises
  * W and X; Section 3.2: "normalization strategy").  With v_hat = v / |v| the layer works on the
  * normalised rows; a gradient g with respect to v_hat becomes, with respect to v,
  *     dv = (g - v_hat <v_hat, g>) / |v|                (the Jacobian of v -> v / |v| is symmetric).
@@ -645,7 +645,7 @@ int orc_norm_backward(const float *V, const double *G, int64_t n, int D, double 
 }
 
 /* Weight update of the layer that keeps W un-normalised in fp32 and works on its normalised 16-bit copy
- * (Section 3.1 step 6 with the normalisation of Section 3.2.1 folded in).  dW_hat[p,:] is the gradient
+ * (Section 3.1 step 6 with the normalisation of Section 3.2.3 folded in).  dW_hat[p,:] is the gradient
  * with respect to the NORMALISED row of class idx[p].  For every class c that occurs in idx:
  *     g = sum of its rows of dW_hat (ascending p, fp64);  dw = (g - w_hat <w_hat, g>) / |w|  with the
  *     current master row;  W[c,:] += alpha * dw (stored fp32);  then, from the stored row,

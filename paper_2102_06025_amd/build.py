@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libknnsoftmax.so")
-SOURCES = ["ks_select.hip", "ks_softmax.hip", "ks_apply.hip", "ks_graph.hip", "ks_topk.hip"]
+SOURCES = ["ks_select.hip", "ks_softmax.hip", "ks_apply.hip", "ks_graph.hip", "ks_topk.hip", "ks_peaks.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -152,7 +152,7 @@ apply_segments_kernel(float *__restrict__ Wm, uint16_t *__restrict__ Wb, const u
 
 
 // ------------------------------------------------------------------------------------------------
-// Normalisation inside the layer (paper Section 3.2.1: W and X are normalised on the GPU): the layer keeps
+// Normalisation inside the layer (paper Section 3.2.3, GPU pipeline step 2: W and X are normalised on the GPU): the layer keeps
 // W un-normalised in fp32, its matrix kernels read the normalised 16-bit copy W_hat = W / |W| (row-wise), and
 // gradients with respect to normalised rows are brought back through
 //     dv = (g - v_hat <v_hat, g>) / |v|.

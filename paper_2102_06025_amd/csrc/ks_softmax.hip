@@ -635,7 +635,7 @@ sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
 // The reference only shifts the exponent range: results are the same function of the inputs as long as no
 // exponential overflows and not all of a sample's vanish, which the combine kernel checks.
 // ------------------------------------------------------------------------------------------------
-// The sweep runs on the eight-wavefront engine (ks_gemm_soe8.h): wavefront w owns samples [32 w, 32 w + 32) of the
+// The sweep runs on the eight-wavefront engine (ks_gemm_soe.h): wavefront w owns samples [32 w, 32 w + 32) of the
 // tile and two wavefronts share a SIMD, so the exponentials, the LDS writes and the copy-out of one overlap with
 // the MFMAs of the other (measured on the headline shape: 34 us against 40 us with four wavefronts of 64 samples).
 template <int KT>
@@ -1593,6 +1593,50 @@ extern "C" int knn_softmax_bwd_from_stats(const uint16_t *W_bf16, const uint16_t
     io.gtz = global_target_logit;
     return sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, s.act, s.n, s.tp, loss_per_sample, loss_mean, dX, dW_active,
                   s.w, flags, dev_status, st, nullptr, SM_IMPORT, io);
+}
+
+// The step on a selection computed earlier (possibly on another stream): sanitised copy of the list, then everything
+// after the selection.  The softmax buffers come first in the workspace, the copy of the list after them.
+static int sm_selected_check(int64_t C, int D, int B, int M) {
+    if (sm_check_dims(C, D, B) != KS_OK || M < 1 || B > M) return KS_INVALID_ARG;
+    return KS_OK;
+}
+extern "C" size_t knn_softmax_selected_workspace(int64_t C, int D, int B, int M) {
+    if (sm_selected_check(C, D, B, M) != KS_OK) return 0;
+    size_t total = 0;
+    sm_split_carve(nullptr, C, D, B, M, &total);
+    return total;
+}
+extern "C" int knn_softmax_fwd_bwd_update_selected(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16,
+                                                   const int32_t *active_idx, const int32_t *n_active,
+                                                   const int32_t *target_pos, int64_t C, int D, int B, int M, float scale,
+                                                   float grad_scale, float alpha, uint32_t flags, float *loss_per_sample,
+                                                   float *loss_mean, float *dX, float *dW_active, void *ws, size_t ws_bytes,
+                                                   int32_t *dev_status, void *stream) {
+    if (!W_bf16 || !X_bf16 || !active_idx || !n_active || !target_pos || !loss_per_sample || !loss_mean || !dX || !ws)
+        return KS_INVALID_ARG;
+    if (sm_selected_check(C, D, B, M) != KS_OK) return KS_INVALID_ARG;
+    if (flags & ~(uint32_t)KS_FLAG_UNIT_ROWS) return KS_INVALID_ARG;
+    const bool fast = D % 64 == 0;
+    if (!dW_active && !(W_master && fast)) return KS_INVALID_ARG;
+    size_t need = 0;
+    SmSplitWs s = sm_split_carve(ws, C, D, B, M, &need);
+    if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    const int nmax = M > B ? M : B;
+    hipLaunchKernelGGL(sm_sanitize_kernel, dim3((unsigned)ks_ceil_div(nmax, SM_NT)), dim3(SM_NT), 0, st, active_idx, n_active,
+                       target_pos, C, M, B, s.act, s.n, s.tp, dev_status);
+    DwUpdate up = DwUpdate();
+    if (W_master && fast) {
+        up.Wm = W_master;
+        up.Wb = W_bf16;
+        up.idx = s.act;
+        up.alpha = alpha;
+    }
+    int rc = sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, s.act, s.n, s.tp, loss_per_sample, loss_mean, dX, dW_active,
+                    s.w, flags, dev_status, st, nullptr, SM_WHOLE, SmSplitIO(), up);
+    if (rc != KS_OK || !W_master || fast) return rc;
+    return apply_weight_grad(W_master, W_bf16, s.act, s.n, M, dW_active, alpha, C, D, 1, ws, ws_bytes, dev_status, stream);
 }
 
 extern "C" size_t full_softmax_workspace(int64_t C, int D, int B) {

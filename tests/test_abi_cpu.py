@@ -23,7 +23,7 @@ def ks():
 def _declared_functions():
     src = open(HEADER).read() + open(os.path.join(ROOT, "include", "grad_topk.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(ks_version|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update|_stats|_profiled|_plan|_select|_static))\s*\(", src)))
+    return sorted(set(re.findall(r"\b(ks_version|ks_peak_mfma|ks_peak_copy|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update|_stats|_profiled|_plan|_select|_static|_selected))\s*\(", src)))
 
 
 def test_header_symbols_are_exported(ks):
@@ -272,3 +272,16 @@ def test_static_selection_rejects_sizes_beyond_its_scratch_array_before_any_laun
     assert sel(B=20_000, K=32) == ks.KS_UNSUPPORTED                          # staging array of 20,000 x 33 candidates
     assert sel(labels=null) == ks.KS_INVALID_ARG
     assert sel(B=40_000) == ks.KS_INVALID_ARG                                # B > M
+
+
+def test_bench_reads_the_traffic_figures_from_the_committed_profile():
+    """The `traffic` fields of the benchmark line come from profiles/bench_shard390k_hbm_traffic.txt at run time: the
+    parser finds the step's three contraction kernels there, and the figures are the file's own last column."""
+    import bench
+    t = bench.profiled_traffic()
+    assert set(t) == {"logits_gemm", "dx_gemm", "dw_gemm"}
+    text = open(bench.TRAFFIC_PROFILE).read()
+    for stage, kernel in bench.TRAFFIC_KERNEL.items():
+        line = [ln for ln in text.splitlines() if ln.startswith(kernel)][0]
+        assert t[stage] == float(line.split()[-1]) * 1e6 and 1e6 < t[stage] < 1e9
+    assert bench.profiled_traffic("/nonexistent/file") == {}

@@ -1,4 +1,4 @@
-"""GPU parity of the normalisation inside the layer (Section 3.2.1): row normalisation, the projection that brings
+"""GPU parity of the normalisation inside the layer (Section 3.2.3, GPU pipeline step 2): row normalisation, the projection that brings
 a gradient with respect to a normalised row back to the row itself, and the weight update through the
 normalisation, each against the CPU oracle; then one whole step of the layer that keeps un-normalised fp32
 weights (normalise X, forward/backward on the normalised copies, project dX, update W through the projection)

@@ -495,3 +495,60 @@ def test_one_call_step_on_a_shape_without_the_fused_update(ks, orc):
     b = ks.knn_softmax_fwd_bwd_update(Wm2, Wb2, Xb, yd, Gd, M, scale, 1.0, -0.1)
     torch.cuda.synchronize()
     assert b["dW_active"] is not None and torch.equal(Wm1, Wm2) and torch.equal(Wb1, Wb2) and torch.equal(a["dX"], b["dX"])
+
+
+# ------------------------------------------------------------------------------------------------
+# the step on a selection computed earlier (the selection of the next batch can run beside the current step)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,unit_rows", [("small", True), ("small", False), ("tiny", True)])
+def test_step_on_an_earlier_selection_equals_the_one_call_step(ks, orc, name, unit_rows):
+    """knn_select_active on a second stream, then knn_softmax_fwd_bwd_update_selected on the first: master weights,
+    16-bit copy, dX and losses equal the one-call step bit for bit; without W_master it returns the gradient rows of
+    knn_softmax_fwd_bwd."""
+    cfg = synth.CONFIGS[name]
+    C, D, B, K, M, scale = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"], cfg["scale"]
+    W, X = synth.make_WX(cfg)
+    W = synth.bf16_round(W)
+    y = synth.make_labels(cfg)
+    G = synth.graph_synthetic(cfg["seed"], C, K)
+    gs, alpha = 64.0, -0.03 / 64.0
+    Wb, Xb, yd, Gd = dev(W, torch.bfloat16), dev(synth.bf16_round(X), torch.bfloat16), dev(y), dev(G)
+    Wm1, Wb1 = dev(W), Wb.clone()
+    a = ks.knn_softmax_fwd_bwd_update(Wm1, Wb1, Xb, yd, Gd, M, scale, gs, alpha, unit_rows=unit_rows)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        act, n, tp, st = ks.knn_select_active(yd, Gd, C, M, stream=side)
+    done = torch.cuda.Event()
+    done.record(side)
+    torch.cuda.current_stream().wait_event(done)
+    Wm2, Wb2 = dev(W), Wb.clone()
+    b = ks.knn_softmax_fwd_bwd_update_selected(Wm2, Wb2, Xb, act, n, tp, scale, gs, alpha, unit_rows=unit_rows)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0 and int(a["dev_status"].item()) == 0 and int(b["dev_status"].item()) == 0
+    assert torch.equal(act, a["active_idx"]) and torch.equal(tp, a["target_pos"])
+    assert torch.equal(a["loss_per_sample"], b["loss_per_sample"]) and torch.equal(a["loss_mean"], b["loss_mean"])
+    assert torch.equal(a["dX"], b["dX"]) and torch.equal(Wm1, Wm2) and torch.equal(Wb1, Wb2)
+    assert not torch.equal(Wm2, dev(W))
+    # no update: the gradient rows of the plain forward/backward call
+    c = ks.knn_softmax_fwd_bwd(Wb, Xb, yd, Gd, M, scale, gs, unit_rows=unit_rows)
+    d = ks.knn_softmax_fwd_bwd_update_selected(None, Wb, Xb, act, n, tp, scale, gs, 0.0, unit_rows=unit_rows)
+    torch.cuda.synchronize()
+    A = int(n.item())
+    assert torch.equal(c["dW_active"][:A], d["dW_active"][:A]) and torch.equal(c["dX"], d["dX"])
+
+
+def test_step_on_a_broken_selection_is_flagged_and_stays_in_bounds(ks):
+    C, D, B, M = 1000, 128, 16, 64
+    W = torch.randn(C, D, device="cuda")
+    Wb = W.to(torch.bfloat16)
+    X = torch.randn(B, D, device="cuda").to(torch.bfloat16)
+    act = torch.arange(M, dtype=torch.int32, device="cuda")
+    act[3] = C + 5                                                # not a class
+    tp = torch.zeros(B, dtype=torch.int32, device="cuda")
+    tp[2] = 40                                                    # beyond the 32 valid entries
+    n = torch.tensor([32], dtype=torch.int32, device="cuda")
+    out = ks.knn_softmax_fwd_bwd_update_selected(W.clone(), Wb, X, act, n, tp, 10.0, 1.0, -0.01)
+    torch.cuda.synchronize()
+    stt = int(out["dev_status"].item())
+    assert stt & ks.KS_DEV_BAD_INDEX and stt & ks.KS_DEV_BAD_LABEL
