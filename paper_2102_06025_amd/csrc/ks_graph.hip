@@ -4,8 +4,8 @@
 //   prepare   bf16 copy of W when the input is fp32; row norms and their maximum (for the error bound)
 //   recall    each workgroup owns a block of 128 rows and sweeps all column blocks: bf16 MFMA tile of
 //             similarities; an element that beats its row's threshold is appended to that row's candidate
-//             buffer; a full buffer is cut back to its k' best by a wavefront-wide bitonic sort in
-//             registers, which also raises the threshold.  The C x C similarities are never stored.
+//             buffer; a full buffer is cut back to its k' best by a wavefront (a bitwise search for the
+//             k'-th largest key), which also raises the threshold.  The C x C similarities are never stored.
 //   re-rank   one wavefront per row: canonical fp64 similarity of the k' candidates, exact order
 //             (similarity descending, id ascending), first K written out.  The row is certified when
 //             the K-th exact similarity exceeds the recall threshold by more than the error bound of the
@@ -112,49 +112,25 @@ __global__ void gr_zero_kernel(uint32_t *maxnorm_bits, int32_t *fb_count) {
     *fb_count = 0;
 }
 
-// ------------------------------------------------------------------------------------------------
-// wavefront-wide bitonic sort, descending, of E*64 keys held as val[r] = element r*64 + lane
-// ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint64_t gr_shfl_xor64(uint64_t v, int mask) {
-    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
-    lo = __shfl_xor(lo, mask, 64);
-    hi = __shfl_xor(hi, mask, 64);
-    return ((uint64_t)hi << 32) | lo;
+// Cut the candidate buffer of one row back to its kprime best (in no particular order: the exact stage ranks them
+// anyway) and make the kprime-th best value the row's new threshold; updates cnt/thr in LDS.  One wavefront per row.
+// The kprime-th largest key is found by a bitwise search -- rounds of "how many keys are >= this prefix", each a
+// compare per key, a wavefront ballot and a population count -- which is an order of magnitude cheaper than sorting
+// the keys across the lanes (the keys are distinct: value bits above, inverted row id below; empty slots are 0).
+// The 32 value bits are searched first; the id bits only when several keys share the kprime-th value.
+// Requires kprime <= number of keys.
+template <int E> __device__ __forceinline__ int gr_count_hi_ge(const uint64_t (&val)[E], uint32_t t) {
+    int c = 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) c += __popcll(__ballot((uint32_t)(val[r] >> 32) >= t));
+    return c;
 }
-
-template <int E> __device__ __forceinline__ void gr_wave_sort_desc(uint64_t (&val)[E]) {
-    const int lane = threadIdx.x & 63;
+template <int E> __device__ __forceinline__ int gr_count_lo_ge(const uint64_t (&val)[E], uint32_t hi, uint32_t t) {
+    int c = 0;
 #pragma unroll
-    for (int k = 2; k <= E * 64; k <<= 1) {
-#pragma unroll
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            if (j >= 64) {
-                const int jr = j >> 6;
-#pragma unroll
-                for (int r = 0; r < E; ++r) {
-                    if ((r & jr) == 0) {
-                        const int idx = r * 64 + lane;
-                        const bool desc = (idx & k) == 0; // descending run: larger key to the lower index
-                        uint64_t a = val[r], b = val[r | jr];
-                        if ((a < b) == desc) { val[r] = b; val[r | jr] = a; }
-                    }
-                }
-            } else {
-#pragma unroll
-                for (int r = 0; r < E; ++r) {
-                    const int idx = r * 64 + lane;
-                    const bool desc = (idx & k) == 0;
-                    const bool lower = (lane & j) == 0;
-                    uint64_t me = val[r], other = gr_shfl_xor64(me, j);
-                    const bool want_max = (lower == desc);
-                    val[r] = want_max ? (me > other ? me : other) : (me < other ? me : other);
-                }
-            }
-        }
-    }
+    for (int r = 0; r < E; ++r) c += __popcll(__ballot((uint32_t)(val[r] >> 32) == hi && (uint32_t)val[r] >= t));
+    return c;
 }
-
-// cut the candidate buffer of one row back to its kprime best; returns nothing, updates cnt/thr in LDS
 template <int E>
 __device__ __forceinline__ void gr_compact_row(uint64_t *__restrict__ cand_row, int *cnt, uint32_t *thr, int kprime) {
     const int lane = threadIdx.x & 63;
@@ -163,24 +139,34 @@ __device__ __forceinline__ void gr_compact_row(uint64_t *__restrict__ cand_row, 
 #pragma unroll
     for (int r = 0; r < E; ++r) {
         int idx = r * 64 + lane;
-        val[r] = idx < n ? cand_row[idx] : 0ull; // 0 sorts below every real key
+        val[r] = idx < n ? cand_row[idx] : 0ull; // 0 is below every real key
     }
-    gr_wave_sort_desc<E>(val);
+    uint32_t t_hi = 0; // every decision below is uniform over the wavefront
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t c = t_hi | (1u << bit);
+        if (gr_count_hi_ge<E>(val, c) >= kprime) t_hi = c;
+    }
+    uint64_t t = (uint64_t)t_hi << 32;
+    if (gr_count_hi_ge<E>(val, t_hi) != kprime) { // keys of equal value straddle the cut: the ids decide
+        const int need = kprime - (t_hi == 0xFFFFFFFFu ? 0 : gr_count_hi_ge<E>(val, t_hi + 1u));
+        uint32_t t_lo = 0;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t c = t_lo | (1u << bit);
+            if (gr_count_lo_ge<E>(val, t_hi, c) >= need) t_lo = c;
+        }
+        t |= t_lo;
+    }
+    // t is the kprime-th largest key: exactly kprime keys are >= t; they move to the front of the buffer
+    int base = 0;
 #pragma unroll
     for (int r = 0; r < E; ++r) {
-        int idx = r * 64 + lane;
-        if (idx < kprime) cand_row[idx] = val[r];
+        const uint64_t m = __ballot(val[r] >= t);
+        if (val[r] >= t) cand_row[base + __popcll(m & ((1ull << lane) - 1ull))] = val[r];
+        base += __popcll(m);
     }
-    // key number kprime-1 is the new threshold
-    const int rk = (kprime - 1) >> 6, lk = (kprime - 1) & 63;
-    uint64_t kth = 0;
-#pragma unroll
-    for (int r = 0; r < E; ++r)
-        if (r == rk) kth = val[r];
-    uint32_t kth_hi = __shfl((uint32_t)(kth >> 32), lk, 64);
     if (lane == 0) {
         *cnt = kprime;
-        *thr = kth_hi;
+        *thr = (uint32_t)(t >> 32);
     }
 }
 
@@ -333,22 +319,24 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
     __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
     __shared__ int s_cnt[CFG::RES];
     __shared__ uint32_t s_thr[CFG::RES];
-    __shared__ int s_need;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t row0 = (int64_t)blockIdx.x * CFG::RES;
     for (int m = threadIdx.x; m < CFG::RES; m += CFG::NT) { s_cnt[m] = 0; s_thr[m] = 0u; }
-    if (threadIdx.x == 0) s_need = 0;
     __syncthreads();
     const int col = ks_soe_col();
     const int gi = (int)row0 + col; // C < 2^31
     const int Ci = (int)C;
     const int64_t self0 = row0 + pr.self; // streamed rows [self0, self0 + RES) are this workgroup's own rows
+    // A wavefront's accumulators hold 32 of the 256 rows (two lanes per row), so the candidate buffers, counters and
+    // thresholds of those rows are written by that wavefront alone: it also cuts them back itself, and the
+    // epilogue needs no workgroup barrier.
     auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM]) {
         // elements that need more than the threshold test: the tail of the last chunk, and the diagonal
         const bool special = rows_here < CFG::CH || ((int64_t)c0 < self0 + CFG::RES && (int64_t)c0 + CFG::CH > self0);
         const uint32_t th = s_thr[col];
         // 0 = nothing dropped yet: everything passes; rows beyond C never pass
         const float thf = gi >= Ci ? INFINITY : (th == 0u ? -INFINITY : gr_unorder(th));
+        bool full = false;
 #pragma unroll
         for (int fm = 0; fm < CFG::FM; ++fm) {
             float bm = acc[fm][0];
@@ -365,20 +353,18 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
                         const int slot = atomicAdd(&s_cnt[col], 1);
                         if (slot < CAP) // always true: a buffer is cut back before it can overflow
                             cand[(int64_t)gi * CAP + slot] = ((uint64_t)gr_orderable(v) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
-                        if (slot + 1 > CAP - CFG::CH) s_need = 1;
+                        full |= slot + 1 > CAP - CFG::CH;
                     }
                 }
             }
         }
-        __builtin_amdgcn_s_waitcnt(0xC07F); // LDS atomics done
-        ks_barrier_nofence();
-        if (s_need) { // some buffer could overflow in the next chunk: cut the full ones back
-            __syncthreads(); // the appended candidates are visible to the wavefront that sorts them
-            for (int m = wave; m < CFG::RES; m += CFG::NW) {
+        if (__any(full)) { // a buffer could overflow in the next chunk: cut this wavefront's full ones back
+            ks_wait_vmcnt<0>(); // the appended candidates have left this wavefront before it reads them back
+            asm volatile("" ::: "memory");
+            for (int m = wave * 32; m < wave * 32 + 32; ++m) {
                 if (s_cnt[m] > CAP - CFG::CH) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
             }
-            __syncthreads();
-            if (threadIdx.x == 0) s_need = 0;
+            asm volatile("" ::: "memory");
         }
     };
     ks_soe_sweep<CFG>(pr.R, D, (int)row0, (int)C, pr.S, D, nullptr, 0, (int)pr.Cs, (int)pr.Cs, lds, epi);
