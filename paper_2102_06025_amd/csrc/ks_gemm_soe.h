@@ -24,6 +24,7 @@
 // After every chunk (all KT k-tiles of CH streamed rows) the caller's epilogue functor gets the
 // accumulators; the loads of the next chunk are already in flight at that point.
 #pragma once
+#include <type_traits>
 #include "ks_gemm_async.h"
 
 template <int KT_, int CH_, int STAGES_, int KSUB_ = 1> struct KsSoe {
@@ -155,50 +156,74 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
     int stage = 0, done = 0;
     for (int c = 0; c < n_chunks; ++c) {
         const int rows_here = (s_end - (s_begin + c * CFG::CH)) < CFG::CH ? (s_end - (s_begin + c * CFG::CH)) : CFG::CH;
-        const int fm_cnt = (rows_here + 31) >> 5; // 32-row blocks of this chunk that hold real rows
         f32x16_t acc[FM];
+        // All k-tiles of one chunk.  FULL: the chunk has all CH rows -- the common case, compiled without a branch
+        // between the MFMAs (a branch ends the basic block, and the wait for the fragment reads that the compiler
+        // places at the start of the next one also waits for the reads issued ahead for the next k-step).
+        // Otherwise 32-row blocks that hold no real row are skipped.
+        auto chunk = [&](auto full) __attribute__((always_inline)) {
+            constexpr bool FULL = decltype(full)::value;
+            const int fm_cnt = (rows_here + 31) >> 5; // 32-row blocks of this chunk that hold real rows
+            if (!FULL) {
 #pragma unroll
-        for (int fm = 0; fm < FM; ++fm)
+                for (int fm = 0; fm < FM; ++fm)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[fm][r] = 0.f;
-#pragma unroll
-        for (int kt0 = 0; kt0 < KT; kt0 += CFG::KSUB) {
-            // stage `done` must have landed; the stages issued after it may still be in flight.  (Wavefronts that load
-            // nothing only have the stores of their epilogues outstanding, which this wait also covers.)
-            if (issued - done - 1 >= ST - 2) ks_wait_vmcnt<(ST - 2) * NI * CFG::KSUB>();
-            else ks_wait_vmcnt<0>();
-            ks_barrier_nofence();
-            if (issued < n_tiles) issue_one();
-            if (kt0 == 0 && c > 0) {
-                const int pc0 = s_begin + (c - 1) * CFG::CH;
-                post(pc0, (s_end - pc0) < CFG::CH ? (s_end - pc0) : CFG::CH);
+                    for (int r = 0; r < 16; ++r) acc[fm][r] = 0.f;
             }
 #pragma unroll
-            for (int u = 0; u < CFG::KSUB; ++u) {
-                const int kt = kt0 + u;
-                const uint16_t *st = lds + stage * CFG::STAGE_ELEMS + u * CFG::CH * 64;
-                bf16x8_t a0[FM], a1[FM];
+            for (int kt0 = 0; kt0 < KT; kt0 += CFG::KSUB) {
+                // stage `done` must have landed; the stages issued after it may still be in flight.  (Wavefronts that
+                // load nothing only have the stores of their epilogues outstanding, which this wait also covers.)
+                if (issued - done - 1 >= ST - 2) ks_wait_vmcnt<(ST - 2) * NI * CFG::KSUB>();
+                else ks_wait_vmcnt<0>();
+                ks_barrier_nofence();
+                if (issued < n_tiles) issue_one();
+                if (kt0 == 0 && c > 0) {
+                    const int pc0 = s_begin + (c - 1) * CFG::CH;
+                    post(pc0, (s_end - pc0) < CFG::CH ? (s_end - pc0) : CFG::CH);
+                }
 #pragma unroll
-                for (int fm = 0; fm < FM; ++fm) a0[fm] = *(const bf16x8_t *)(st + (fm * 32 + r31) * 64 + ((khalf ^ swz) * 8));
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    bf16x8_t(&cur)[FM] = (kk & 1) ? a1 : a0;
-                    bf16x8_t(&nxt)[FM] = (kk & 1) ? a0 : a1;
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (kk + 1 < 4) {
-#pragma unroll
-                        for (int fm = 0; fm < FM; ++fm)
-                            nxt[fm] = *(const bf16x8_t *)(st + (fm * 32 + r31) * 64 + ((((kk + 1) * 2 + khalf) ^ swz) * 8));
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+                for (int u = 0; u < CFG::KSUB; ++u) {
+                    const int kt = kt0 + u;
+                    const uint16_t *st = lds + stage * CFG::STAGE_ELEMS + u * CFG::CH * 64;
+                    bf16x8_t a0[FM], a1[FM];
 #pragma unroll
                     for (int fm = 0; fm < FM; ++fm)
-                        if (fm < fm_cnt) acc[fm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[fm], bres[kt * 4 + kk], acc[fm], 0, 0, 0);
+                        a0[fm] = *(const bf16x8_t *)(st + (fm * 32 + r31) * 64 + ((khalf ^ swz) * 8));
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) {
+                        bf16x8_t(&cur)[FM] = (kk & 1) ? a1 : a0;
+                        bf16x8_t(&nxt)[FM] = (kk & 1) ? a0 : a1;
+                        __builtin_amdgcn_sched_barrier(0);
+                        // The wait for this k-step's fragments goes HERE, before the next k-step's reads are issued:
+                        // placed at their first use, after those reads, it would wait for them as well.
+#pragma unroll
+                        for (int fm = 0; fm < FM; ++fm) asm volatile("" ::"v"(cur[fm]));
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (kk + 1 < 4) {
+#pragma unroll
+                            for (int fm = 0; fm < FM; ++fm)
+                                nxt[fm] = *(const bf16x8_t *)(st + (fm * 32 + r31) * 64 + ((((kk + 1) * 2 + khalf) ^ swz) * 8));
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int fm = 0; fm < FM; ++fm) {
+                            if (FULL) {
+                                const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                                acc[fm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[fm], bres[kt * 4 + kk],
+                                                                                   (kt == 0 && kk == 0) ? zero : acc[fm], 0, 0, 0);
+                            } else if (fm < fm_cnt) {
+                                acc[fm] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cur[fm], bres[kt * 4 + kk], acc[fm], 0, 0, 0);
+                            }
+                        }
+                    }
                 }
+                if (++stage == ST) stage = 0;
+                ++done;
             }
-            if (++stage == ST) stage = 0;
-            ++done;
-        }
+        };
+        if (rows_here == CFG::CH) chunk(std::true_type());
+        else chunk(std::false_type());
         // a chunk of a single stage has no barrier between post() of the previous chunk (which reads what epi() left
         // in LDS) and this chunk's epi(): a wavefront that runs ahead must not overwrite what another still reads
         if (KT / CFG::KSUB < 2 && KsSoeHasPost<Post>::value) ks_barrier_nofence();

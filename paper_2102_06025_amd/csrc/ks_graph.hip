@@ -309,75 +309,133 @@ gr_recall_async_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand
 // max operation; only 16-element blocks whose maximum beats the threshold are looked at one by one.
 // ------------------------------------------------------------------------------------------------
 #define GR_SOE_STAGES 6
+// Candidate buffers of the sweep kernel below.  Two lanes of a wavefront share a row of the graph (they hold
+// different streamed rows of it), so each appends to its own half of the row's buffer and counts in a register:
+// an append is a store and an increment, with no atomic operation and nothing to wait for.
+// Cuts the two halves (n0 and n1 keys) back to the kprime largest keys and returns the value bits of the smallest
+// key kept (0 when nothing was dropped); survivors go half and half to the two halves, or -- for the final call --
+// to the front of the buffer.  One wavefront per row.
+template <int E>
+__device__ __forceinline__ uint32_t gr_compact_halves(uint64_t *__restrict__ cand_row, int n0, int n1, int kprime,
+                                                       bool final_layout, int *n_kept) {
+    constexpr int HALF = E * 32;
+    const int lane = threadIdx.x & 63;
+    uint64_t val[E];
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        const int idx = r * 64 + lane;
+        const bool valid = idx < HALF ? idx < n0 : idx - HALF < n1;
+        val[r] = valid ? cand_row[idx] : 0ull; // 0 is below every real key
+    }
+    const int n = n0 + n1;
+    uint64_t t = 1ull; // keeps every real key
+    if (n > kprime) {
+        uint32_t t_hi = 0; // every decision below is uniform over the wavefront
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t c = t_hi | (1u << bit);
+            if (gr_count_hi_ge<E>(val, c) >= kprime) t_hi = c;
+        }
+        t = (uint64_t)t_hi << 32;
+        if (gr_count_hi_ge<E>(val, t_hi) != kprime) { // keys of equal value straddle the cut: the ids decide
+            const int need = kprime - (t_hi == 0xFFFFFFFFu ? 0 : gr_count_hi_ge<E>(val, t_hi + 1u));
+            uint32_t t_lo = 0;
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t c = t_lo | (1u << bit);
+                if (gr_count_lo_ge<E>(val, t_hi, c) >= need) t_lo = c;
+            }
+            t |= t_lo;
+        }
+    }
+    const int kept = n > kprime ? kprime : n;
+    const int first = final_layout ? kept : (kept + 1) / 2; // keys that go to the first half
+    int base = 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        const uint64_t m = __ballot(val[r] >= t);
+        if (val[r] >= t) {
+            const int q = base + __popcll(m & ((1ull << lane) - 1ull));
+            cand_row[q < first ? q : HALF + (q - first)] = val[r];
+        }
+        base += __popcll(m);
+    }
+    *n_kept = kept;
+    return n > kprime ? (uint32_t)(t >> 32) : 0u;
+}
+
 template <int KT, int E>
 __global__ void __launch_bounds__(512)
 gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, int32_t *__restrict__ cnt_out,
                       uint32_t *__restrict__ thr_out) {
     const int64_t C = pr.Cr;
     typedef KsSoe<KT, 96, GR_SOE_STAGES, 2> CFG;
-    constexpr int CAP = E * 64;
+    constexpr int CAP = E * 64, HALF = CAP / 2;
+    constexpr int LIMIT = HALF - CFG::FM * 16; // a lane appends at most FM * 16 keys per chunk
+    static_assert(LIMIT >= 64, "room for half of the largest kprime of this buffer size");
     __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
-    __shared__ int s_cnt[CFG::RES];
-    __shared__ uint32_t s_thr[CFG::RES];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t row0 = (int64_t)blockIdx.x * CFG::RES;
-    for (int m = threadIdx.x; m < CFG::RES; m += CFG::NT) { s_cnt[m] = 0; s_thr[m] = 0u; }
-    __syncthreads();
     const int col = ks_soe_col();
     const int gi = (int)row0 + col; // C < 2^31
     const int Ci = (int)C;
     const int64_t self0 = row0 + pr.self; // streamed rows [self0, self0 + RES) are this workgroup's own rows
-    // A wavefront's accumulators hold 32 of the 256 rows (two lanes per row), so the candidate buffers, counters and
-    // thresholds of those rows are written by that wavefront alone: it also cuts them back itself, and the
-    // epilogue needs no workgroup barrier.
+    // A wavefront's accumulators hold 32 of the 256 rows, two lanes per row (lane and lane + 32 hold different streamed
+    // rows), so the candidate buffers of those rows are written by that wavefront alone: it also cuts them back
+    // itself, the counts and the thresholds live in registers, and the epilogue needs no barrier and no atomics.
+    uint64_t *const my_half = cand + (int64_t)gi * CAP + (lane >> 5) * HALF;
+    int my_cnt = 0;
+    uint32_t th = 0u; // value bits of the row's threshold; 0 = nothing dropped yet: everything passes
+    float thf = gi >= Ci ? INFINITY : -INFINITY; // rows beyond C never pass
+    auto cut_back = [&](bool final_layout) {
+        ks_wait_vmcnt<0>(); // the appended candidates have left this wavefront before it reads them back
+        asm volatile("" ::: "memory");
+        for (int m = 0; m < 32; ++m) {
+            const int n0 = __builtin_amdgcn_readlane(my_cnt, m), n1 = __builtin_amdgcn_readlane(my_cnt, m + 32);
+            if (final_layout ? (row0 + wave * 32 + m < C) : (n0 > LIMIT || n1 > LIMIT)) {
+                int kept;
+                const uint32_t t = gr_compact_halves<E>(cand + (row0 + wave * 32 + m) * CAP, n0, n1, kprime, final_layout, &kept);
+                if ((lane & 31) == m) {
+                    my_cnt = final_layout ? kept : (lane < 32 ? (kept + 1) / 2 : kept / 2);
+                    if (t != 0u) { th = t; thf = gr_unorder(t); }
+                }
+            }
+        }
+        asm volatile("" ::: "memory");
+    };
     auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM]) {
         // elements that need more than the threshold test: the tail of the last chunk, and the diagonal
         const bool special = rows_here < CFG::CH || ((int64_t)c0 < self0 + CFG::RES && (int64_t)c0 + CFG::CH > self0);
-        const uint32_t th = s_thr[col];
-        // 0 = nothing dropped yet: everything passes; rows beyond C never pass
-        const float thf = gi >= Ci ? INFINITY : (th == 0u ? -INFINITY : gr_unorder(th));
-        bool full = false;
+#ifndef GR_GROUP
+#define GR_GROUP 4
+#endif
 #pragma unroll
         for (int fm = 0; fm < CFG::FM; ++fm) {
-            float bm = acc[fm][0];
 #pragma unroll
-            for (int r = 1; r < 16; ++r) bm = fmaxf(bm, acc[fm][r]);
-            if (bm > thf) {
+            for (int q = 0; q < 16 / GR_GROUP; ++q) { // GR_GROUP elements at a time: most groups have none that passes
+                float bm = acc[fm][q * GR_GROUP];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float v = acc[fm][r];
-                    if (v > thf) {
-                        const int lr = ks_soe_row(fm, r, lane);
-                        const int j = c0 + lr;
-                        if (special && (lr >= rows_here || (int64_t)j == (int64_t)gi + pr.self)) continue;
-                        const int slot = atomicAdd(&s_cnt[col], 1);
-                        if (slot < CAP) // always true: a buffer is cut back before it can overflow
-                            cand[(int64_t)gi * CAP + slot] = ((uint64_t)gr_orderable(v) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
-                        full |= slot + 1 > CAP - CFG::CH;
+                for (int e = 1; e < GR_GROUP; ++e) bm = fmaxf(bm, acc[fm][q * GR_GROUP + e]);
+                if (bm > thf) {
+#pragma unroll
+                    for (int e = 0; e < GR_GROUP; ++e) {
+                        const int r = q * GR_GROUP + e;
+                        const float v = acc[fm][r];
+                        if (v > thf) {
+                            const int lr = ks_soe_row(fm, r, lane);
+                            const int j = c0 + lr;
+                            if (special && (lr >= rows_here || (int64_t)j == (int64_t)gi + pr.self)) continue;
+                            if (my_cnt < HALF) // always true: a buffer is cut back before it can overflow
+                                my_half[my_cnt] = ((uint64_t)gr_orderable(v) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
+                            ++my_cnt;
+                        }
                     }
                 }
             }
         }
-        if (__any(full)) { // a buffer could overflow in the next chunk: cut this wavefront's full ones back
-            ks_wait_vmcnt<0>(); // the appended candidates have left this wavefront before it reads them back
-            asm volatile("" ::: "memory");
-            for (int m = wave * 32; m < wave * 32 + 32; ++m) {
-                if (s_cnt[m] > CAP - CFG::CH) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
-            }
-            asm volatile("" ::: "memory");
-        }
+        if (__any(my_cnt > LIMIT)) cut_back(false); // a buffer could overflow in the next chunk
     };
     ks_soe_sweep<CFG>(pr.R, D, (int)row0, (int)C, pr.S, D, nullptr, 0, (int)pr.Cs, (int)pr.Cs, lds, epi);
-    __syncthreads();
-    for (int m = wave; m < CFG::RES; m += CFG::NW) {
-        if (row0 + m < C) {
-            if (s_cnt[m] > kprime) gr_compact_row<E>(cand + (row0 + m) * CAP, &s_cnt[m], &s_thr[m], kprime);
-        }
-    }
-    __syncthreads();
-    for (int m = threadIdx.x; m < CFG::RES; m += CFG::NT) {
-        if (row0 + m < C) { cnt_out[row0 + m] = s_cnt[m]; thr_out[row0 + m] = s_thr[m]; }
-    }
+    cut_back(true); // at most kprime keys per row, at the front of its buffer
+    if (lane < 32 && gi < Ci) { cnt_out[gi] = my_cnt; thr_out[gi] = th; }
 }
 
 // ------------------------------------------------------------------------------------------------
