@@ -44,12 +44,17 @@ struct GrPair {
 };
 
 struct GrParams {
-    int kprime; // candidates kept per row by the recall pass (64, 128 or 256)
+    int kprime; // candidates kept per row by the recall pass (48, 64, 128 or 256)
     int cap;    // candidate buffer entries per row (256 or 512)
 };
-static GrParams gr_params(int K, int D) {
+// The recall pass keeps k' > K candidates so that the K-th exact similarity clears the recall threshold by more than
+// the error bound of the 16-bit pass.  With fp32 rows that bound is dominated by their rounding to bf16 (0.4 % of
+// |w_i||w_j|) and k' = 2 K gives the margin; with bf16 rows only the fp32 accumulation is left (D * 2^-23), orders
+// of magnitude below the spacing of neighbouring similarities, and k' = 1.5 K is kept: the number of candidates a
+// row collects during the sweep, and with it the epilogue's work, grows in proportion to k'.
+static GrParams gr_params(int K, int D, int dtype = KS_DTYPE_FP32) {
     GrParams p;
-    if (K <= 32) { p.kprime = 64; p.cap = 256; }
+    if (K <= 32) { p.kprime = dtype == KS_DTYPE_BF16 ? 48 : 64; p.cap = 256; }
     else if (K <= 64) { p.kprime = 128; p.cap = 256; }
     else { p.kprime = 256; p.cap = 512; }
     if (D % 64 == 0 && !(D == 128 || D == 256 || D == 512))
@@ -404,20 +409,18 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
     auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM]) {
         // elements that need more than the threshold test: the tail of the last chunk, and the diagonal
         const bool special = rows_here < CFG::CH || ((int64_t)c0 < self0 + CFG::RES && (int64_t)c0 + CFG::CH > self0);
-#ifndef GR_GROUP
-#define GR_GROUP 4
-#endif
+        constexpr int GROUP = 4; // elements per threshold test (2 .. 16 measured alike)
 #pragma unroll
         for (int fm = 0; fm < CFG::FM; ++fm) {
 #pragma unroll
-            for (int q = 0; q < 16 / GR_GROUP; ++q) { // GR_GROUP elements at a time: most groups have none that passes
-                float bm = acc[fm][q * GR_GROUP];
+            for (int q = 0; q < 16 / GROUP; ++q) { // GROUP elements at a time: most groups have none that passes
+                float bm = acc[fm][q * GROUP];
 #pragma unroll
-                for (int e = 1; e < GR_GROUP; ++e) bm = fmaxf(bm, acc[fm][q * GR_GROUP + e]);
+                for (int e = 1; e < GROUP; ++e) bm = fmaxf(bm, acc[fm][q * GROUP + e]);
                 if (bm > thf) {
 #pragma unroll
-                    for (int e = 0; e < GR_GROUP; ++e) {
-                        const int r = q * GR_GROUP + e;
+                    for (int e = 0; e < GROUP; ++e) {
+                        const int r = q * GROUP + e;
                         const float v = acc[fm][r];
                         if (v > thf) {
                             const int lr = ks_soe_row(fm, r, lane);
@@ -712,7 +715,7 @@ extern "C" int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K
     size_t need = 0;
     GrWs w = gr_carve(ws, C, D, K, dtype, &need);
     if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
-    const GrParams p = gr_params(K, D);
+    const GrParams p = gr_params(K, D, dtype);
     hipStream_t st = (hipStream_t)stream;
 
     hipLaunchKernelGGL(gr_zero_kernel, dim3(1), dim3(1), 0, st, w.maxnorm, w.fb_count);
@@ -999,7 +1002,7 @@ extern "C" int knn_graph_update(const void *W_local, const void *W_visit, int dt
     size_t need = 0;
     GrUpWs w = gr_up_carve(ws, C_loc, C_vis, D, K, dtype, &need);
     if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
-    const GrParams p = gr_params(K, D);
+    const GrParams p = gr_params(K, D, dtype);
     hipStream_t st = (hipStream_t)stream;
     hipLaunchKernelGGL(gr_zero_kernel, dim3(1), dim3(1), 0, st, w.maxnorm_l, w.fb_count);
     hipLaunchKernelGGL(gr_zero_kernel, dim3(1), dim3(1), 0, st, w.maxnorm_v, w.fb_count);
