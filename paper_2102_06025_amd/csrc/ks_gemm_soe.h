@@ -83,13 +83,25 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
         KsARows<CFG::RES, CFG::NW> rr;
         rr.init(R, ldr, nullptr, r_row0, r_limit);
         const int r31 = lane & 31, khalf = lane >> 5, swz = (lane >> 1) & 7;
-        rr.issue(0, lds);
+        // up to four k-tiles in flight (the stream stages hold that many 256-row tiles): one memory round trip for the
+        // first four instead of one per k-tile
+        constexpr int NS = CFG::LDS_ELEMS / (CFG::RES * 64) >= 4 ? 4 : 2;
+        constexpr int RNI = KsARows<CFG::RES, CFG::NW>::NI;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            if (s < KT) rr.issue(s * 64, lds + s * CFG::RES * 64);
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt) {
-            ks_wait_vmcnt<0>();
-            ks_barrier_nofence(); // k-tile kt is in LDS; everyone is done reading k-tile kt-1
-            if (kt + 1 < KT) rr.issue((kt + 1) * 64, lds + ((kt + 1) & 1) * CFG::RES * 64);
-            const uint16_t *st = lds + (kt & 1) * CFG::RES * 64;
+            const int issued_tiles = (NS + (kt > 0 ? kt - 1 : 0)) < KT ? (NS + (kt > 0 ? kt - 1 : 0)) : KT;
+            const int later = issued_tiles - (kt + 1); // k-tiles issued after this one (compile-time: the loop is unrolled)
+            if (later >= 3) ks_wait_vmcnt<3 * RNI>();
+            else if (later == 2) ks_wait_vmcnt<2 * RNI>();
+            else if (later == 1) ks_wait_vmcnt<1 * RNI>();
+            else ks_wait_vmcnt<0>();
+            __builtin_amdgcn_s_waitcnt(0xC07F); // the fragment reads of k-tile kt-1 have returned: its slot may be reused
+            ks_barrier_nofence();               // k-tile kt is in LDS
+            if (kt > 0 && kt - 1 + NS < KT) rr.issue((kt - 1 + NS) * 64, lds + ((kt - 1) % NS) * CFG::RES * 64);
+            const uint16_t *st = lds + (kt % NS) * CFG::RES * 64;
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
                 bres[kt * 4 + kk] = *(const bf16x8_t *)(st + (wave * 32 + r31) * 64 + (((kk * 2 + khalf) ^ swz) * 8));
