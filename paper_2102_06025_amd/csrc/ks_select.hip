@@ -788,6 +788,116 @@ gc_fill_kernel(const int32_t *__restrict__ graph, int64_t Cg, int K, int64_t c0,
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same two passes for list lengths that divide 64 (K = 32 and 64 in every workload): one lane per list ENTRY
+// instead of one lane per list.  The rows of a block are one contiguous run of GC_SEG * K entries, read with fully
+// coalesced loads; a list occupies K consecutive lanes, so its length is a population count over its part of a
+// wavefront ballot, and an entry's place in the compressed list is the count of the kept entries before it in
+// that part -- list order is preserved.
+// ------------------------------------------------------------------------------------------------
+#define GC_UNROLL 4
+
+__global__ void __launch_bounds__(GC_NT)
+gc_count_entries_kernel(const int32_t *__restrict__ graph, int64_t Cg, int K, int64_t c0, int64_t C_loc,
+                        int32_t *__restrict__ counts, int64_t *__restrict__ blk_sum, int32_t *dev_status) {
+    __shared__ int s_w[GC_NT / 64];
+    const int lane = threadIdx.x & 63;
+    const int64_t c1 = c0 + C_loc;
+    const int64_t e0 = (int64_t)blockIdx.x * GC_SEG * K, e_end = Cg * K; // entries of this block start at e0
+    const int n_it = GC_SEG * K / GC_NT;                               // (K divides 64, GC_SEG is a multiple of GC_NT)
+    const int lk = __builtin_ctz((unsigned)K);                          // K is a power of two here
+    const int sub = lane >> lk << lk;                                    // first lane of this lane's list
+    const uint64_t gmask = (K == 64 ? ~0ull : ((1ull << K) - 1ull)) << sub;
+    int local = 0;
+    bool bad = false;
+    for (int it = 0; it < n_it; it += GC_UNROLL) {
+        int32_t c[GC_UNROLL];
+#pragma unroll
+        for (int u = 0; u < GC_UNROLL; ++u) {
+            const int64_t e = e0 + (int64_t)(it + u) * GC_NT + threadIdx.x;
+            c[u] = (it + u < n_it && e < e_end) ? graph[e] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < GC_UNROLL; ++u) {
+            if (it + u >= n_it) break; // uniform
+            const int64_t e = e0 + (int64_t)(it + u) * GC_NT + threadIdx.x;
+            bad |= (c[u] < -1 || c[u] >= Cg);
+            const bool keep = c[u] >= c0 && c[u] < c1;
+            const uint64_t m = __ballot(keep);
+            if (lane == sub && e < e_end) counts[e >> lk] = __popcll(m & gmask);
+            local += keep ? 1 : 0;
+        }
+    }
+    if (bad) ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
+    local = ks_wave_sum_i(local);
+    if (lane == 0) s_w[threadIdx.x >> 6] = local;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int64_t t = 0;
+        for (int w = 0; w < GC_NT / 64; ++w) t += s_w[w];
+        blk_sum[blockIdx.x] = t;
+    }
+}
+
+__global__ void __launch_bounds__(GC_NT)
+gc_fill_entries_kernel(const int32_t *__restrict__ graph, int64_t Cg, int K, int64_t c0, int64_t C_loc,
+                       const int32_t *__restrict__ counts, const int64_t *__restrict__ blk_base, int64_t *__restrict__ offsets,
+                       int32_t *__restrict__ flat, int64_t flat_capacity) {
+    __shared__ int sh[GC_NT / 64 + 1];
+    __shared__ int s_off[GC_SEG + 1]; // start of every list of the block, relative to the block's first entry
+    const int lane = threadIdx.x & 63;
+    const int64_t base = blk_base[blockIdx.x];
+    const int64_t c1 = c0 + C_loc;
+    const int64_t g0 = (int64_t)blockIdx.x * GC_SEG;
+    {   // offsets of the block's lists: thread t owns lists 4 t .. 4 t + 3
+        int n[4], mine = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t g = g0 + threadIdx.x * 4 + q;
+            n[q] = g < Cg ? counts[g] : 0;
+            mine += n[q];
+        }
+        int tot;
+        int run = ks_block_escan<GC_NT>(mine, sh, &tot);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t g = g0 + threadIdx.x * 4 + q;
+            s_off[threadIdx.x * 4 + q] = run;
+            if (g < Cg) offsets[g] = base + run;
+            run += n[q];
+        }
+        if (threadIdx.x == GC_NT - 1) s_off[GC_SEG] = run;
+    }
+    __syncthreads();
+    if (!flat) return;
+    const int64_t e0 = g0 * K, e_end = Cg * K;
+    const int n_it = GC_SEG * K / GC_NT;
+    const int lk = __builtin_ctz((unsigned)K); // K is a power of two here
+    const int sub = lane >> lk << lk;
+    const uint64_t below = ((1ull << lane) - 1ull) & ((K == 64 ? ~0ull : ((1ull << K) - 1ull)) << sub); // earlier lanes of this list
+    for (int it = 0; it < n_it; it += GC_UNROLL) {
+        int32_t c[GC_UNROLL];
+#pragma unroll
+        for (int u = 0; u < GC_UNROLL; ++u) {
+            const int64_t e = e0 + (int64_t)(it + u) * GC_NT + threadIdx.x;
+            c[u] = (it + u < n_it && e < e_end) ? graph[e] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < GC_UNROLL; ++u) {
+            if (it + u >= n_it) break; // uniform
+            const int f = (it + u) * GC_NT + (int)threadIdx.x; // entry within the block
+            const bool keep = c[u] >= c0 && c[u] < c1;
+            const uint64_t m = __ballot(keep);
+            if (keep) {
+                const int row = f >> lk;
+                const int64_t off = base + s_off[row], end = base + s_off[row + 1];
+                // a list that does not fit the array is not written (the scan has flagged the short array)
+                if (end <= flat_capacity) flat[off + __popcll(m & below)] = (int32_t)(c[u] - c0);
+            }
+        }
+    }
+}
+
 extern "C" size_t knn_graph_compress_workspace(int64_t Cg, int K) {
     if (Cg < 1 || K < 0) return 0;
     return ks_align_up((size_t)ks_ceil_div(Cg, GC_SEG) * sizeof(int64_t), 256);
@@ -803,11 +913,20 @@ extern "C" int knn_graph_compress(const int32_t *graph, int64_t Cg, int K, int64
     const int nblk = (int)ks_ceil_div(Cg, GC_SEG);
     int64_t *blk = (int64_t *)ws;
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(gc_count_kernel, dim3(nblk), dim3(GC_NT), 0, st, graph, Cg, K, c0, C_loc, counts, blk, dev_status);
+    const bool by_entry = K <= 64 && 64 % K == 0; // a list is a whole number of lists per wavefront
+    if (by_entry)
+        hipLaunchKernelGGL(gc_count_entries_kernel, dim3(nblk), dim3(GC_NT), 0, st, graph, Cg, K, c0, C_loc, counts, blk,
+                           dev_status);
+    else
+        hipLaunchKernelGGL(gc_count_kernel, dim3(nblk), dim3(GC_NT), 0, st, graph, Cg, K, c0, C_loc, counts, blk, dev_status);
     hipLaunchKernelGGL(gc_scan_kernel, dim3(1), dim3(1024), 0, st, blk, nblk, offsets, Cg, flat_capacity, flat != nullptr,
                        dev_status);
-    hipLaunchKernelGGL(gc_fill_kernel, dim3(nblk), dim3(GC_NT), 0, st, graph, Cg, K, c0, C_loc, counts, blk, offsets, flat,
-                       flat_capacity);
+    if (by_entry)
+        hipLaunchKernelGGL(gc_fill_entries_kernel, dim3(nblk), dim3(GC_NT), 0, st, graph, Cg, K, c0, C_loc, counts, blk,
+                           offsets, flat, flat_capacity);
+    else
+        hipLaunchKernelGGL(gc_fill_kernel, dim3(nblk), dim3(GC_NT), 0, st, graph, Cg, K, c0, C_loc, counts, blk, offsets, flat,
+                           flat_capacity);
     KS_LAUNCH_CHECK();
     return KS_OK;
 }

@@ -42,7 +42,9 @@ def compress_both(ks, orc, G, c0, C_loc):
 
 
 @pytest.mark.parametrize("Cg,K,c0,C_loc,empty", [(37, 5, 10, 1, 0.2), (5000, 16, 0, 5000, 0.0), (5000, 16, 1250, 1250, 0.1),
-                                                  (100_000, 7, 99_000, 1000, 0.3), (1_200_000, 8, 200_000, 500_000, 0.0)])
+                                                  (100_000, 7, 99_000, 1000, 0.3), (1_200_000, 8, 200_000, 500_000, 0.0),
+                                                  (3001, 32, 700, 1500, 0.2), (2500, 64, 0, 1000, 0.1), (1030, 1, 5, 600, 0.3),
+                                                  (70_001, 2, 30_000, 20_000, 0.5), (9000, 4, 8999, 1, 0.0)])
 def test_graph_compress(ks, orc, Cg, K, c0, C_loc, empty):
     print(f"[csr] compress Cg={Cg} K={K} node=[{c0},{c0 + C_loc}) empty={empty}", flush=True)
     G = synth.graph_synthetic(1, Cg, K, locality=64, empty_frac=empty) if Cg <= 100_000 else arithmetic_graph(Cg, K)
