@@ -641,8 +641,8 @@ sm_grad_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ 
 template <int KT>
 __global__ void __launch_bounds__(512)
 sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, const int32_t *__restrict__ active_idx,
-                     const int32_t *__restrict__ n_active_p, int B, int Bp, int D, int M, int tiles_s, float scale,
-                     float *__restrict__ pl, uint16_t *__restrict__ dZT) {
+                     const int32_t *__restrict__ n_active_p, const int32_t *__restrict__ target_pos, int B, int Bp, int D, int M,
+                     int tiles_s, float scale, float *__restrict__ pl, float *__restrict__ pl_others, uint16_t *__restrict__ dZT) {
     typedef KsSoe<KT, 96, SOE_STAGES, 2> CFG;
     constexpr int STAGE_LD = CFG::RES + 8;
     constexpr int NT = CFG::NT;
@@ -663,8 +663,21 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
     for (int c = 0; c < 8; ++c) s_sum[c * NT + threadIdx.x] = 0.f;
     const float k1 = scale * 1.4426950408889634f; // exp(scale * acc - scale) = exp2(fma(acc, k1, -k1))
     const bool samples_ok = (ts + 1) * CFG::RES <= B;
+    // For the loss: this lane's sum of the UNROUNDED exponentials of its sample over its rows, the sample's own class
+    // left out (the combine step adds that one from an fp32 dot product).  The sums of the stored, rounded values
+    // (`pl`) are what the gradient columns must add up to; for the loss of a confident sample they would carry the
+    // bf16 rounding of its strongest competitor, 2^-9 relative.
+    float others = 0.f;
+    int my_tp = -1; // position of this lane's sample's class in the active list
+    {
+        const int i = ts * CFG::RES + ks_soe_col();
+        if (i < B) my_tp = target_pos[i];
+    }
     auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM]) {
         const bool plain = samples_ok && c0 + CFG::CH <= lim; // no row or column of this chunk needs masking
+        const int tl = my_tp - c0;                             // the own class's row in this chunk, if in [0, CH)
+        const bool own_here = __any(tl >= 0 && tl < CFG::CH);  // uniform: some sample of this wavefront has its class here
+        float csum = 0.f;
         // thread-index arithmetic is redone here behind a copy the compiler cannot see through, so that it does not
         // hoist the LDS addresses out of the sweep and spill them
         int tid = threadIdx.x;
@@ -673,26 +686,40 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
         const bool odd = lane & 1;
         const int col = (tid >> 6) * 32 + (tid & 31);
         const bool ok = ts * CFG::RES + col < B;
+        const int tq = tl - 4 * (lane >> 5); // the own class's accumulator element: fm * 32 + 8 * (r >> 2) + (r & 3) == tq
+        // the element loop, compiled twice: with and without the test for the own class (no branch inside the loop)
+        auto elements = [&](auto own) __attribute__((always_inline)) {
+            constexpr bool OWN = decltype(own)::value;
 #pragma unroll
-        for (int fm = 0; fm < CFG::FM; ++fm)
+            for (int fm = 0; fm < CFG::FM; ++fm)
 #pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                float d[2];
+                for (int r = 0; r < 16; r += 2) {
+                    float d[2];
 #pragma unroll
-                for (int e = 0; e < 2; ++e) d[e] = __builtin_amdgcn_exp2f(fmaf(acc[fm][r + e], k1, -k1));
-                if (!plain) {
+                    for (int e = 0; e < 2; ++e) d[e] = __builtin_amdgcn_exp2f(fmaf(acc[fm][r + e], k1, -k1));
+                    if (!plain) {
 #pragma unroll
-                    for (int e = 0; e < 2; ++e)
-                        if (!ok || c0 + ks_soe_row(fm, r + e, lane) >= lim) d[e] = 0.f;
+                        for (int e = 0; e < 2; ++e)
+                            if (!ok || c0 + ks_soe_row(fm, r + e, lane) >= lim) d[e] = 0.f;
+                    }
+                    if (OWN) {
+                        csum += (fm * 32 + 8 * (r >> 2) + (r & 3)) == tq ? 0.f : d[0];
+                        csum += (fm * 32 + 8 * ((r + 1) >> 2) + ((r + 1) & 3)) == tq ? 0.f : d[1];
+                    } else {
+                        csum += d[0] + d[1];
+                    }
+                    // neighbouring lanes (samples 2j, 2j+1) trade so that each holds two adjacent samples of one class
+                    // row: the even lane ends up with row r, the odd lane with row r+1
+                    const float send = odd ? d[0] : d[1];
+                    const float recv = __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0xB1, 0xF, 0xF, true));
+                    const uint32_t packed = odd ? ks_pack_bf2(recv, d[1]) : ks_pack_bf2(d[0], recv);
+                    const int row = ks_soe_row(fm, r + (odd ? 1 : 0), lane);
+                    *(uint32_t *)(stage + row * STAGE_LD + (col & ~1)) = packed;
                 }
-                // neighbouring lanes (samples 2j, 2j+1) trade so that each holds two adjacent samples of one class
-                // row: the even lane ends up with row r, the odd lane with row r+1
-                const float send = odd ? d[0] : d[1];
-                const float recv = __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(send), 0xB1, 0xF, 0xF, true));
-                const uint32_t packed = odd ? ks_pack_bf2(recv, d[1]) : ks_pack_bf2(d[0], recv);
-                const int row = ks_soe_row(fm, r + (odd ? 1 : 0), lane);
-                *(uint32_t *)(stage + row * STAGE_LD + (col & ~1)) = packed;
-            }
+        };
+        if (own_here) elements(std::true_type());
+        else elements(std::false_type());
+        others += csum;
         __builtin_amdgcn_s_waitcnt(0xC07F); // LDS writes done (lgkmcnt 0); loads in flight are left alone
     };
     // second half, one stage into the next chunk: copy the chunk out in 16-byte pieces; thread t always takes the
@@ -745,6 +772,11 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
         for (int grp = 0; grp < NT / (CFG::RES / 8); ++grp) sum += red[grp * CFG::RES + threadIdx.x];
         if (i < B) pl[(int64_t)slab * Bp + i] = sum;
     }
+    others += __shfl_xor(others, 32, 64); // the two lanes of a sample hold different rows
+    if ((threadIdx.x & 63) < 32) {
+        const int i = ts * CFG::RES + ks_soe_col();
+        if (i < B) pl_others[(int64_t)slab * Bp + i] = others;
+    }
 }
 
 // Combine step of the one-sweep variant.  A block owns 32 samples, eight threads per sample: sum of the slab
@@ -767,7 +799,7 @@ struct SmSplitIO {
     const float *gmax, *gsum, *gtz;       // SM_IMPORT
 };
 __global__ void __launch_bounds__(SM_CF_NT)
-sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict__ n_active_p,
+sm_combine_fused_kernel(const float *__restrict__ pl, const float *__restrict__ pl_others, const int32_t *__restrict__ n_active_p,
                         const int32_t *__restrict__ active_idx, const int32_t *__restrict__ target_pos,
                         const uint16_t *__restrict__ X, const uint16_t *__restrict__ W, int M, int slabs, int B, int Bp, int D,
                         float scale, float *__restrict__ inv_sum, float *__restrict__ loss_i, uint16_t *__restrict__ dZT,
@@ -775,7 +807,7 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
     // SM_CF_SPB samples per workgroup, SM_CF_PARTS threads per sample (each takes a share of the slab sums and of
     // the dot product): the kernel is a chain of dependent round trips, so it is spread over many compute units
     constexpr int SPB = SM_CF_SPB, PARTS = SM_CF_NT / SPB;
-    __shared__ float sh[SM_CF_NT], sh_dot[SM_CF_NT];
+    __shared__ float sh[SM_CF_NT], sh_dot[SM_CF_NT], sh_oth[SM_CF_NT];
     __shared__ float s_inv[SPB];
     const int n = sm_clamp_n(n_active_p, M);
     const int n64 = (n + 63) & ~63;
@@ -786,7 +818,7 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
     int tp = 0;
     bool owned = n > 0; // split over nodes: does this node hold the sample's class?  (one GPU: always)
     {
-        float part = 0.f, dot = 0.f;
+        float part = 0.f, dot = 0.f, oth = 0.f;
         if (i < B && n > 0) {
             // all loads of a batch are issued before the first use: these are dependent only through the
             // running sums, and one round trip to another L2 costs as much as everything else here
@@ -795,11 +827,17 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
             tp = tp < 0 ? 0 : (tp >= n ? n - 1 : tp); // stays in bounds whatever the selection flagged
             const int cls = active_idx[tp];
             for (int t0 = gq; mode != SM_IMPORT && t0 < nt; t0 += 4 * PARTS) {
-                float v[4];
+                float v[4], u[4];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) v[q] = (t0 + PARTS * q < nt) ? pl[(int64_t)(t0 + PARTS * q) * Bp + i] : 0.f;
+                for (int q = 0; q < 4; ++q) {
+                    v[q] = (t0 + PARTS * q < nt) ? pl[(int64_t)(t0 + PARTS * q) * Bp + i] : 0.f;
+                    u[q] = (t0 + PARTS * q < nt) ? pl_others[(int64_t)(t0 + PARTS * q) * Bp + i] : 0.f;
+                }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) part += v[q];
+                for (int q = 0; q < 4; ++q) {
+                    part += v[q];
+                    oth += u[q];
+                }
             }
             // this thread's share of the dot product: D / PARTS elements, in 8-byte pieces (D is 128, 256 or 512)
             const int per = D / PARTS;
@@ -826,15 +864,17 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
         }
         sh[threadIdx.x] = part;
         sh_dot[threadIdx.x] = dot;
+        sh_oth[threadIdx.x] = oth;
     }
     __syncthreads();
     if (threadIdx.x < SPB) {
         float inv = 0.f;
         if (i < B) {
-            float sum = 0.f, dot = 0.f;
+            float sum = 0.f, dot = 0.f, oth = 0.f;
             for (int q = 0; q < PARTS; ++q) { // a fixed order
                 sum += sh[q * SPB + j];
                 dot += sh_dot[q * SPB + j];
+                oth += sh_oth[q * SPB + j];
             }
             const float z_t = scale * dot;
             const float e_t = __expf(z_t - scale);
@@ -859,7 +899,10 @@ sm_combine_fused_kernel(const float *__restrict__ pl, const int32_t *__restrict_
                     io.tz_out[i] = owned ? z_t : 0.f;
                 } else {
                     if (!(sum > 0.f) || !(sum < INFINITY)) ks_flag(dev_status, KS_DEV_RANGE);
-                    loss_i[i] = (scale + __logf(sum)) - z_t;
+                    // loss = log(1 + (unrounded exponentials of the other classes) / E_t): no difference of nearly
+                    // equal numbers, and no bf16 rounding in it (a class list without the sample's class: plain form)
+                    const float ratio = oth / e_t;
+                    loss_i[i] = (owned && ratio < 1e30f) ? log1pf(ratio) : (scale + __logf(sum)) - z_t;
                     inv = 1.f / sum;
                     inv_sum[i] = inv;
                     *cell = (uint16_t)ks_f2bf(-others); // the column now holds (P - onehot) * sum
@@ -1310,8 +1353,8 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
         if (fused) {
             const int grid = SM_SOE_GRID / tiles_s * tiles_s, slabs = grid / tiles_s;
 #define SM_FUSED_LAUNCH(KT)                                                                                               \
-    hipLaunchKernelGGL(sm_fused_soe_kernel<KT>, dim3(grid), dim3(512), 0, st, X, W, active_idx, n_active, B, w.Bp, D, Mi,  \
-                       tiles_s, scale, w.pl, w.dZT)
+    hipLaunchKernelGGL(sm_fused_soe_kernel<KT>, dim3(grid), dim3(512), 0, st, X, W, active_idx, n_active, target_pos, B,   \
+                       w.Bp, D, Mi, tiles_s, scale, w.pl, w.pm, w.dZT)
             if (mode != SM_IMPORT) { // the first call of a split has left the exponentials in the workspace
                 if (D == 512) SM_FUSED_LAUNCH(8);
                 else if (D == 256) SM_FUSED_LAUNCH(4);
@@ -1320,7 +1363,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
 #undef SM_FUSED_LAUNCH
             mark(2);
             hipLaunchKernelGGL(sm_combine_fused_kernel, dim3((unsigned)ks_ceil_div(B, SM_CF_SPB)), dim3(SM_CF_NT), 0, st, w.pl,
-                               n_active, active_idx, target_pos, X, W, Mi, slabs, B, w.Bp, D, scale, w.inv, loss_per_sample,
+                               w.pm, n_active, active_idx, target_pos, X, W, Mi, slabs, B, w.Bp, D, scale, w.inv, loss_per_sample,
                                w.dZT, w.X2, dev_status, mode, io);
             mark(3);
             if (mode == SM_EXPORT) {

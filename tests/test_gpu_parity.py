@@ -164,6 +164,32 @@ def test_fwd_bwd_peaky_softmax_and_clustered_weights(ks, orc):
     assert (np.abs(li[big] - ref["loss_i"][big]) <= 5e-3 * ref["loss_i"][big] + 1e-3).all()
 
 
+@pytest.mark.parametrize("D,noise,sigma", [(128, 0.5, 0.2), (256, 0.5, 0.2), (512, 0.6, 0.3)])
+def test_one_sweep_loss_of_confident_samples_is_accurate_sample_by_sample(ks, orc, D, noise, sigma):
+    """Confident samples (the own class takes nearly all of the probability) among classes that come in pairs of
+    near twins, so that a single competitor holds nearly all of what is left: the one-sweep mode must not let the
+    bf16 rounding of that competitor's stored exponential (2^-9, above the 1e-3 bound) into the loss.  Checked
+    relatively, sample by sample."""
+    C, B, K, M = 12_000, 256, 16, 2_048
+    W = synth.clustered_rows(11, C, D, n_centres=C // 2, noise=noise, bf16=True)
+    y = synth.labels_zipf(11, B, C)
+    X = synth.features_near_labels(11, W, y, sigma=sigma, bf16=True)
+    rows = np.unique(y)
+    G = synth.graph_synthetic(11, C, K)
+    G[rows], _ = orc.graph_bruteforce(W, K, rows)
+    active, A, tpos = orc.select_active(y, G, C, M)
+    ref = orc.knn_softmax_fwd_bwd(W, X, active[:A], tpos, 30.0, 1.0)
+    out = ks.knn_softmax_fwd_bwd(dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(y), dev(G), M, 30.0, 1.0, unit_rows=True)
+    torch.cuda.synchronize()
+    assert int(out["dev_status"].item()) == 0
+    li, rl = out["loss_per_sample"].cpu().numpy().astype(np.float64), ref["loss_i"]
+    err = np.abs(li - rl) / (rl + 1e-6)
+    print(f"        D={D}: losses from {rl.min():.2e} to {rl.max():.2e}, median {np.median(rl):.2e}; "
+          f"worst relative error {err.max():.2e}", flush=True)
+    assert np.median(rl) < 0.05, "the case is meant to be confident"
+    assert err.max() <= 5e-4
+
+
 def test_knn_equals_full_softmax_when_lists_span_all_classes(ks, orc):
     C, D, B = 4_000, 128, 96
     W = synth.unit_rows(8, synth.TID_W, C, D, bf16=True)

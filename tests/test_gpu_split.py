@@ -152,7 +152,9 @@ def test_split_on_a_node_owning_everything_equals_the_one_call_path(ks, orc, uni
     torch.cuda.synchronize()
     assert int(s1["dev_status"].item()) == 0 and int(s2["dev_status"].item()) == 0
     A = int(one["n_active"].item())
-    assert torch.allclose(s2["loss_per_sample"], one["loss_per_sample"], rtol=1e-5, atol=1e-5)
+    # (one-sweep mode: the one-call path takes the loss from the unrounded exponentials, the split path from the sums
+    # the nodes exchange, which are those of the stored, rounded values: up to 2^-9 of the smaller of the two terms)
+    assert torch.allclose(s2["loss_per_sample"], one["loss_per_sample"], rtol=1e-3 if unit_rows else 1e-5, atol=1e-5)
     assert rel_fro(s2["dX"].cpu().numpy(), one["dX"].cpu().numpy()) <= 1e-3
     assert rel_fro(s2["dW_active"][:A].cpu().numpy(), one["dW_active"][:A].cpu().numpy()) <= 1e-3
 
