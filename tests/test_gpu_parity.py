@@ -415,6 +415,27 @@ def test_graph_clustered_rows_ragged_size(ks, orc):
     _check_graph(ks, orc, W, K, True, rows=rows, tag="clustered")
 
 
+@pytest.mark.parametrize("C,D,K,bf16,kind", [(3001, 128, 64, True, "unit"), (2500, 256, 100, True, "unit"),
+                                             (5003, 512, 32, False, "unit"), (4000, 128, 32, True, "integers"),
+                                             (3000, 256, 70, False, "integers"), (6000, 512, 16, True, "clustered")])
+def test_graph_sweep_kernel_buffer_sizes_and_ties(ks, orc, C, D, K, bf16, kind):
+    """The stationary-operand recall kernel (D = 128, 256, 512) with every candidate-buffer configuration (k' = 48, 64,
+    128 with 256-entry buffers; k' = 256 with 512-entry buffers), on rows with few distinct similarities (small integer
+    entries, twins: the cuts of the buffers meet many equal keys) and on clustered rows."""
+    if kind == "unit":
+        W = synth.unit_rows(9, synth.TID_W, C, D, bf16=bf16)
+    elif kind == "integers":
+        W = np.random.default_rng(C + D).integers(-1, 2, (C, D)).astype(np.float32)
+        W[C // 2] = W[3]
+        W[C - 1] = W[3]
+    else:
+        W = synth.clustered_rows(9, C, D, n_centres=97, bf16=bf16)
+    rows = np.sort(synth.class_permutation(9, C)[:200]).astype(np.int32)
+    rows[0] = 3
+    rows = np.unique(rows)
+    _check_graph(ks, orc, W, K, bf16, rows=rows, tag=f"sweep kernel {kind}")
+
+
 def test_graph_is_deterministic(ks, orc):
     W = synth.unit_rows(6, synth.TID_W, 6000, 128, bf16=True)
     g1, s1 = ks.knn_graph_build(dev(W, torch.bfloat16), 16, want_sims=True)
