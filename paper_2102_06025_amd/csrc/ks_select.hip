@@ -366,6 +366,7 @@ sel_finish_kernel(Src src, const int32_t *__restrict__ score, int B, int M, cons
 #define SEL1_NT 1024
 #define SEL1_GRID 32
 #define SEL1_MAX_WORDS SEL1_MAX_WORDS_HOST
+#define SEL1_FIRST_WORDS 257 /* one bit per sample of batches up to 8,192 (+ one word so that a clear loop may run over) */
 
 // Stage 1 (many workgroups, so that the scattered reads of the neighbour lists are spread over the chip):
 // validated candidates, list-position-major: cand[r * B + i] = class at position r of sample i's list
@@ -412,7 +413,26 @@ sel_single_kernel(const int32_t *__restrict__ cand, int64_t C, int B, int K, int
     // round trips to L2 are what this phase costs)
     const int64_t n_cand = (int64_t)B * (K + 1);
     const int64_t n_vec = n_cand >> 2; // the staging array is 256-byte aligned: whole 16-byte pieces, then a tail
-    for (int64_t t0 = 0; t0 < n_vec; t0 += (int64_t)SEL1_NT * 8) {
+    // Samples with the same label have the same list, and with skewed labels half of the batch are repeats: only the
+    // first sample of a label (whichever thread marks the label first) has its list marked.  s_first holds one bit
+    // per sample; for batch sizes that are a power of two, so that a 16-byte piece of the staging array holds four
+    // samples of one list position and the sample index is a mask away.
+    __shared__ uint32_t s_first[SEL1_FIRST_WORDS];
+    const bool dedup = B >= 4 && (B & (B - 1)) == 0 && B <= SEL1_FIRST_WORDS * 32;
+    int64_t v_begin = 0;
+    if (dedup) {
+        for (int w = tid; w < B / 32 + 1; w += SEL1_NT) s_first[w] = 0u;
+        __syncthreads();
+        for (int i = tid; i < B; i += SEL1_NT) {
+            const int32_t c = cand[i]; // list position 0: the label (or -1: a class of another node, whose list still counts)
+            bool first = true;
+            if (c >= 0) first = !(atomicOr(&bm[c >> 5], 1u << (c & 31)) & (1u << (c & 31)));
+            if (first) atomicOr(&s_first[i >> 5], 1u << (i & 31));
+        }
+        __syncthreads();
+        v_begin = B >> 2; // the labels are done
+    }
+    for (int64_t t0 = v_begin; t0 < n_vec; t0 += (int64_t)SEL1_NT * 8) {
         int4 c[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -421,10 +441,15 @@ sel_single_kernel(const int32_t *__restrict__ cand, int64_t C, int B, int K, int
         }
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            if (c[e].x >= 0) atomicOr(&bm[c[e].x >> 5], 1u << (c[e].x & 31));
-            if (c[e].y >= 0) atomicOr(&bm[c[e].y >> 5], 1u << (c[e].y & 31));
-            if (c[e].z >= 0) atomicOr(&bm[c[e].z >> 5], 1u << (c[e].z & 31));
-            if (c[e].w >= 0) atomicOr(&bm[c[e].w >> 5], 1u << (c[e].w & 31));
+            uint32_t f4 = 0xFu; // which of the four samples are the first of their label
+            if (dedup) {
+                const int i0 = (int)(((t0 + (int64_t)e * SEL1_NT + tid) << 2) & (B - 1));
+                f4 = s_first[i0 >> 5] >> (i0 & 31);
+            }
+            if (c[e].x >= 0 && (f4 & 1u)) atomicOr(&bm[c[e].x >> 5], 1u << (c[e].x & 31));
+            if (c[e].y >= 0 && (f4 & 2u)) atomicOr(&bm[c[e].y >> 5], 1u << (c[e].y & 31));
+            if (c[e].z >= 0 && (f4 & 4u)) atomicOr(&bm[c[e].z >> 5], 1u << (c[e].z & 31));
+            if (c[e].w >= 0 && (f4 & 8u)) atomicOr(&bm[c[e].w >> 5], 1u << (c[e].w & 31));
         }
     }
     for (int64_t t = n_vec * 4 + tid; t < n_cand; t += SEL1_NT) {
