@@ -19,7 +19,7 @@
 // MFMA orientation: streamed rows are the MFMA rows, resident rows the MFMA columns, so in the accumulator a
 // lane owns ONE resident row (column lane % 32) and 16 streamed rows per 32-row block: reductions along the
 // streamed rows for a fixed resident row (softmax statistics per sample, running thresholds per graph row) are
-// lane-local.  Streamed tiles are loaded by the first CH / 16 wavefronts (two 8-row instructions each).
+// lane-local.  Streamed tiles are loaded by wavefronts 0..3 (CH / 32 eight-row instructions each per k-tile).
 //
 // After every chunk (all KT k-tiles of CH streamed rows) the caller's epilogue functor gets the
 // accumulators; the loads of the next chunk are already in flight at that point.
@@ -31,8 +31,8 @@ template <int KT_, int CH_, int STAGES_, int KSUB_ = 1> struct KsSoe {
     static constexpr int KT = KT_, STAGES = STAGES_, KSUB = KSUB_;
     static constexpr int NW = 8, NT = 512, CH = CH_, RES = 256;
     static constexpr int FM = CH / 32;
-    static constexpr int LW = CH / 16; // wavefronts that issue the stream loads
-    static constexpr int NI = 2;       // load instructions per loading wavefront per k-tile
+    static constexpr int LW = 4;       // wavefronts that issue the stream loads: 0..3, one per SIMD (see the sweep)
+    static constexpr int NI = CH / 32; // load instructions per loading wavefront per k-tile (8 rows each)
     static constexpr int STAGE_ELEMS = KSUB * CH * 64;
     static constexpr int LDS_ELEMS = STAGES * STAGE_ELEMS;
     static_assert(KT >= 1 && KT <= 8 && KT % KSUB == 0 && STAGES >= 2 && (STAGES - 2) * NI * KSUB <= 63 && CH % 32 == 0 &&
@@ -189,7 +189,6 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
                 if (issued - done - 1 >= ST - 2) ks_wait_vmcnt<(ST - 2) * NI * CFG::KSUB>();
                 else ks_wait_vmcnt<0>();
                 ks_barrier_nofence();
-                if (issued < n_tiles) issue_one();
                 if (kt0 == 0 && c > 0) {
                     const int pc0 = s_begin + (c - 1) * CFG::CH;
                     post(pc0, (s_end - pc0) < CFG::CH ? (s_end - pc0) : CFG::CH);
@@ -230,6 +229,12 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
                         }
                     }
                 }
+                // The next stage's loads go out HERE, after this stage's MFMAs, not right after the barrier: issuing a
+                // load blocks a wavefront until the memory pipeline takes it (about 70 clocks each), and of the two
+                // wavefronts of a SIMD the lower one gets the matrix pipe first, is done half a stage before the
+                // other and would only wait at the next barrier -- the loading wavefronts 0..3 are those.  (The slot
+                // they fill held the previous stage, which every wavefront left before this stage's barrier.)
+                if (issued < n_tiles) issue_one();
                 if (++stage == ST) stage = 0;
                 ++done;
             }

@@ -25,8 +25,8 @@ typedef KsATile<256, 256, 2, 4, 2> TileRA;      // asynchronous recall tile (D %
 #define GR_MAX_D 4096     /* the exhaustive pass keeps one row in LDS as fp64 */
 
 __device__ __forceinline__ uint32_t gr_orderable(float f) {
-    uint32_t u = __float_as_uint(f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    const uint32_t u = __float_as_uint(f); // negative: all bits flipped; otherwise: the sign bit set
+    return u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
 }
 __device__ __forceinline__ float gr_unorder(uint32_t k) {
     return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
@@ -386,7 +386,10 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
     // A wavefront's accumulators hold 32 of the 256 rows, two lanes per row (lane and lane + 32 hold different streamed
     // rows), so the candidate buffers of those rows are written by that wavefront alone: it also cuts them back
     // itself, the counts and the thresholds live in registers, and the epilogue needs no barrier and no atomics.
-    uint64_t *const my_half = cand + (int64_t)gi * CAP + (lane >> 5) * HALF;
+    // an append is a store at a 32-bit slot number behind one base address of the workgroup: the count of the lane's
+    // half plus a constant of the lane
+    uint64_t *const wg_cand = cand + row0 * CAP;
+    const uint32_t my_base = (uint32_t)(col * CAP + (lane >> 5) * HALF);
     int my_cnt = 0;
     uint32_t th = 0u; // value bits of the row's threshold; 0 = nothing dropped yet: everything passes
     float thf = gi >= Ci ? INFINITY : -INFINITY; // rows beyond C never pass
@@ -410,30 +413,38 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
         // elements that need more than the threshold test: the tail of the last chunk, and the diagonal
         const bool special = rows_here < CFG::CH || ((int64_t)c0 < self0 + CFG::RES && (int64_t)c0 + CFG::CH > self0);
         constexpr int GROUP = 4; // elements per threshold test (2 .. 16 measured alike)
+        // compiled twice: nearly all chunks are plain (all rows real, none of them the row itself)
+        auto elements = [&](auto is_special) __attribute__((always_inline)) {
+            constexpr bool SPECIAL = decltype(is_special)::value;
 #pragma unroll
-        for (int fm = 0; fm < CFG::FM; ++fm) {
+            for (int fm = 0; fm < CFG::FM; ++fm) {
 #pragma unroll
-            for (int q = 0; q < 16 / GROUP; ++q) { // GROUP elements at a time: most groups have none that passes
-                float bm = acc[fm][q * GROUP];
+                for (int q = 0; q < 16 / GROUP; ++q) { // GROUP elements at a time: most groups have none that passes
+                    float bm = acc[fm][q * GROUP];
 #pragma unroll
-                for (int e = 1; e < GROUP; ++e) bm = fmaxf(bm, acc[fm][q * GROUP + e]);
-                if (bm > thf) {
+                    for (int e = 1; e < GROUP; ++e) bm = fmaxf(bm, acc[fm][q * GROUP + e]);
+                    if (bm > thf) {
 #pragma unroll
-                    for (int e = 0; e < GROUP; ++e) {
-                        const int r = q * GROUP + e;
-                        const float v = acc[fm][r];
-                        if (v > thf) {
-                            const int lr = ks_soe_row(fm, r, lane);
-                            const int j = c0 + lr;
-                            if (special && (lr >= rows_here || (int64_t)j == (int64_t)gi + pr.self)) continue;
-                            if (my_cnt < HALF) // always true: a buffer is cut back before it can overflow
-                                my_half[my_cnt] = ((uint64_t)gr_orderable(v) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
-                            ++my_cnt;
+                        for (int e = 0; e < GROUP; ++e) {
+                            const int r = q * GROUP + e;
+                            const float v = acc[fm][r];
+                            if (v > thf) {
+                                const int lr = ks_soe_row(fm, r, lane);
+                                const int j = c0 + lr;
+                                if (SPECIAL && (lr >= rows_here || (int64_t)j == (int64_t)gi + pr.self)) continue;
+                                // (my_cnt < HALF: a buffer is cut back before it can overflow; the mask keeps the
+                                // store inside the lane's half whatever happens)
+                                wg_cand[my_base + ((uint32_t)my_cnt & (uint32_t)(HALF - 1))] =
+                                    ((uint64_t)gr_orderable(v) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
+                                ++my_cnt;
+                            }
                         }
                     }
                 }
             }
-        }
+        };
+        if (special) elements(std::true_type());
+        else elements(std::false_type());
         if (__any(my_cnt > LIMIT)) cut_back(false); // a buffer could overflow in the next chunk
     };
     ks_soe_sweep<CFG>(pr.R, D, (int)row0, (int)C, pr.S, D, nullptr, 0, (int)pr.Cs, (int)pr.Cs, lds, epi);
