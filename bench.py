@@ -417,6 +417,77 @@ def main():
         log(f"[bench] stand-alone gather of the {A} active rows: {gather}")
         del g_out
 
+    # ---- the step when the selection is not on its critical path (Algorithm 1 needs only the labels): (a) the selection
+    # given -- made earlier, e.g. while the features of the batch were still being computed; (b) the selection of the
+    # NEXT batch on a second stream, one event dependency per step.  The headline figure is the serial one-call step.
+    selection_variants = None
+    if fused_update and not args.headline_only:
+        side = torch.cuda.Stream()
+        main_s = torch.cuda.current_stream()
+        sel_bufs = [dict(active_idx=torch.empty(M, dtype=torch.int32, device="cuda"),
+                         n_active=torch.empty(1, dtype=torch.int32, device="cuda"),
+                         target_pos=torch.empty(B, dtype=torch.int32, device="cuda"),
+                         ws=torch.empty(ks.knn_select_workspace(C, B, K, M), dtype=torch.uint8, device="cuda")) for _ in range(2)]
+        sel_st = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ws_sel = torch.empty(ks.knn_softmax_selected_workspace(C, D, B, M), dtype=torch.uint8, device="cuda")
+        e_sel = [torch.cuda.Event(), torch.cuda.Event()]
+        e_use = [torch.cuda.Event(), torch.cuda.Event()]
+        out_sel = None
+
+        def select_on(slot, stream):
+            b = sel_bufs[slot]
+            rc = ks.lib().knn_select_active(ct.c_void_p(labels.data_ptr()), ct.c_void_p(graph.data_ptr()), ct.c_int64(C),
+                                            ct.c_int(B), ct.c_int(K), ct.c_int(M), ct.c_void_p(b["active_idx"].data_ptr()),
+                                            ct.c_void_p(b["n_active"].data_ptr()), ct.c_void_p(b["target_pos"].data_ptr()),
+                                            ct.c_void_p(b["ws"].data_ptr()), ct.c_size_t(b["ws"].numel()),
+                                            ct.c_void_p(sel_st.data_ptr()), ct.c_void_p(stream.cuda_stream))
+            assert rc == 0, rc
+
+        def step_selected(slot):
+            nonlocal out_sel
+            b = sel_bufs[slot]
+            out_sel = ks.knn_softmax_fwd_bwd_update_selected(W_master, W_bf, X_bf, b["active_idx"], b["n_active"],
+                                                             b["target_pos"], cfg["scale"], grad_scale, alpha,
+                                                             out=out_sel, ws=ws_sel, unit_rows=unit_rows)
+
+        def pipelined(n):
+            select_on(0, side)
+            e_sel[0].record(side)
+            for s in range(n):
+                slot = s & 1
+                main_s.wait_event(e_sel[slot])
+                step_selected(slot)
+                e_use[slot].record(main_s)
+                if s + 1 < n:
+                    if s >= 1:
+                        side.wait_event(e_use[slot ^ 1])
+                    select_on(slot ^ 1, side)
+                    e_sel[slot ^ 1].record(side)
+
+        select_on(0, main_s)
+        for _ in range(args.warmup):
+            step_selected(0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_selected(0)
+        torch.cuda.synchronize()
+        ms_given = (time.perf_counter() - t0) * 1e3 / args.steps
+        pipelined(args.warmup)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        pipelined(args.steps)
+        torch.cuda.synchronize()
+        ms_piped = (time.perf_counter() - t0) * 1e3 / args.steps
+        assert int(out_sel["dev_status"].item()) == 0 and int(sel_st.item()) == 0
+        selection_variants = dict(serial_ms_per_step=round(ms_per_step, 4), selection_given_ms_per_step=round(ms_given, 4),
+                                  selection_of_next_batch_on_second_stream_ms_per_step=round(ms_piped, 4),
+                                  what="knn_select_active + knn_softmax_fwd_bwd_update_selected; the second-stream figure "
+                                       "includes one cross-stream event dependency per step")
+        log(f"[bench] selection off the path: given {ms_given:.4f} ms/step, next batch's on a second stream {ms_piped:.4f} "
+            f"ms/step (serial {ms_per_step:.4f})")
+        del sel_bufs, ws_sel
+
     # ---- the same step at the cap of the active set (uniform labels: about 32.3 k distinct candidates) ----------
     at_the_cap = None
     if args.workload == "shard390k" and not args.headline_only:
@@ -661,6 +732,7 @@ def main():
         "whole_step": whole_step,
         "phases": phases,
         "graph_build": graph_e,
+        "selection_variants": selection_variants,
         "at_the_cap": at_the_cap,
         "dense_contrast": dense_contrast,
         "gather_rows": gather,
