@@ -2,8 +2,8 @@
 // similarity; 16-bit matrix-core pass that recalls k' > K candidates, then an exact re-rank).
 //
 //   prepare   bf16 copy of W when the input is fp32; row norms and their maximum (for the error bound)
-//   recall    each workgroup owns a block of 128 rows and sweeps all column blocks: bf16 MFMA tile of
-//             similarities; an element that beats its row's threshold is appended to that row's candidate
+//   recall    each workgroup owns a block of rows (256 in the sweep kernel) and passes all rows of W by them: bf16
+//             MFMA tiles of similarities; an element that beats its row's threshold is appended to that row's candidate
 //             buffer; a full buffer is cut back to its k' best by a wavefront (a bitwise search for the
 //             k'-th largest key), which also raises the threshold.  The C x C similarities are never stored.
 //   re-rank   one wavefront per row: canonical fp64 similarity of the k' candidates, exact order
@@ -311,7 +311,7 @@ gr_recall_async_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand
 // recall pass as a stationary-operand sweep (D = 128, 256 or 512): a workgroup keeps the MFMA fragments
 // of its 256 rows in registers and streams every row of W past them, 96 rows at a time.  A lane owns one
 // of the 256 rows in the accumulators, so the row's threshold is a register and most elements cost one
-// max operation; only 16-element blocks whose maximum beats the threshold are looked at one by one.
+// max operation; only groups of four elements whose maximum beats the threshold are looked at one by one.
 // ------------------------------------------------------------------------------------------------
 #define GR_SOE_STAGES 6
 // Candidate buffers of the sweep kernel below.  Two lanes of a wavefront share a row of the graph (they hold
