@@ -687,9 +687,10 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
         const int col = (tid >> 6) * 32 + (tid & 31);
         const bool ok = ts * CFG::RES + col < B;
         const int tq = tl - 4 * (lane >> 5); // the own class's accumulator element: fm * 32 + 8 * (r >> 2) + (r & 3) == tq
-        // the element loop, compiled twice: with and without the test for the own class (no branch inside the loop)
-        auto elements = [&](auto own) __attribute__((always_inline)) {
-            constexpr bool OWN = decltype(own)::value;
+        // the element loop, compiled three times: plain chunks with and without the test for the own class, and chunks
+        // with rows or samples to mask (no branch inside the loop)
+        auto elements = [&](auto own, auto is_plain) __attribute__((always_inline)) {
+            constexpr bool OWN = decltype(own)::value, PLAIN = decltype(is_plain)::value;
 #pragma unroll
             for (int fm = 0; fm < CFG::FM; ++fm)
 #pragma unroll
@@ -697,7 +698,7 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
                     float d[2];
 #pragma unroll
                     for (int e = 0; e < 2; ++e) d[e] = __builtin_amdgcn_exp2f(fmaf(acc[fm][r + e], k1, -k1));
-                    if (!plain) {
+                    if (!PLAIN) {
 #pragma unroll
                         for (int e = 0; e < 2; ++e)
                             if (!ok || c0 + ks_soe_row(fm, r + e, lane) >= lim) d[e] = 0.f;
@@ -717,8 +718,12 @@ sm_fused_soe_kernel(const uint16_t *__restrict__ X, const uint16_t *__restrict__
                     *(uint32_t *)(stage + row * STAGE_LD + (col & ~1)) = packed;
                 }
         };
-        if (own_here) elements(std::true_type());
-        else elements(std::false_type());
+        if (plain) {
+            if (own_here) elements(std::true_type(), std::true_type());
+            else elements(std::false_type(), std::true_type());
+        } else {
+            elements(std::true_type(), std::false_type()); // (rare: the test for the own class is harmless where it is not needed)
+        }
         others += csum;
         __builtin_amdgcn_s_waitcnt(0xC07F); // LDS writes done (lgkmcnt 0); loads in flight are left alone
     };
