@@ -392,7 +392,10 @@ def main():
                                frac_of_measured_peak=roofline.get("frac_of_measured_peak"))
                 gbs = launch_bytes / (dur[dom] * 1e-6) / 1e9
                 roofline.update(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                                frac=round(gbs / PEAK_HBM_GBS, 4), algorithmic_bytes=launch_bytes, as_mfma=as_mfma)
+                                frac=round(gbs / PEAK_HBM_GBS, 4), algorithmic_bytes=launch_bytes, as_mfma=as_mfma,
+                                bound_reason=f"at the nominal peaks the launch's {launch_bytes / 1e6:.1f} MB take "
+                                             f"{launch_bytes / (PEAK_HBM_GBS * 1e9) * 1e6:.1f} us and its "
+                                             f"{model[dom]['flops'] / 1e9:.1f} GFLOP {model[dom]['flops'] / (PEAK_BF16_TFLOPS * 1e12) * 1e6:.1f} us")
                 if copy_peak:
                     roofline.update(measured_peak=copy_peak, frac_of_measured_peak=round(gbs / copy_peak, 4))
     else:
