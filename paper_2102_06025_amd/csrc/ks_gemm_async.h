@@ -111,16 +111,26 @@ template <int W, int NW> struct KsAKmaj {
     __device__ __forceinline__ void issue(int k0, uint16_t *lds) const {
         const int lane = threadIdx.x & 63;
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        // every source row first (the gather list is read from LDS in one batch, with one wait), then the loads
+        // back to back: a list read between two loads would cost its LDS latency once per load
+        int src[NI];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            int kg = k0 + kloc[j];
+            if (kg >= k_limit) kg = k_limit - 1;
+            src[j] = kg;
+        }
+        if (lidx) {
+#pragma unroll
+            for (int j = 0; j < NI; ++j) src[j] = lidx[src[j] - k_first];
+        }
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int k = kloc[j];
             // the slot this lane fills (lane % CPR) holds chunk slot ^ ((k & 3) << 2) of k-row k
             int col = col_base + (((lane % CPR) ^ ((k & 3) << 2)) * 8);
             if (col > col_lim8) col = col_lim8;
-            int kg = k0 + k;
-            if (kg >= k_limit) kg = k_limit - 1;
-            const int64_t src = lidx ? (int64_t)lidx[kg - k_first] : (int64_t)kg;
-            __builtin_amdgcn_global_load_lds(KS_GPTR(base + src * ld + col), KS_LPTR(lds + (j * NW + wave) * RPI * W), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(KS_GPTR(base + (int64_t)src[j] * ld + col), KS_LPTR(lds + (j * NW + wave) * RPI * W), 16, 0, 0);
         }
     }
     __device__ __forceinline__ void issue_one(int j, int k0, uint16_t *lds) const {

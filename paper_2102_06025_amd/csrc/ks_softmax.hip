@@ -1010,11 +1010,25 @@ dx_partial_async_kernel(const uint16_t *__restrict__ dZT, int Bp, int64_t Mp, co
         ks_a_mainloop<T, true, true>(ar, br, kt0, kt1, lds, acc);
 #endif
     }
+    // row-wise through LDS (the main loop has ended with a barrier): 16-byte pieces of whole rows, a quarter of the
+    // store instructions of an element-wise hand-out
     float *out = part + (int64_t)s * B * D;
-    ks_a_foreach<T>(acc, [&](int m, int n, float v) {
-        int i = tm * T::BM + m, d = tn * T::BN + n;
-        if (i < B && d < D) out[(int64_t)i * D + d] = v;
-    });
+    typedef KsASlab<T> SL;
+    float *st = (float *)lds;
+    for (int p = 0; p < T::WAVES_M; ++p) {
+        ks_a_stage_slab<T>(acc, st, p);
+        __syncthreads();
+        constexpr int PER = SL::ROWS * SL::QUADS / T::NT;
+        static_assert(SL::ROWS * SL::QUADS % T::NT == 0, "slab shape");
+#pragma unroll 4
+        for (int q0 = 0; q0 < PER; ++q0) {
+            const int q = q0 * T::NT + threadIdx.x;
+            const int row = q / SL::QUADS, quad = q % SL::QUADS;
+            const int i = tm * T::BM + p * SL::ROWS + row, d = tn * T::BN + quad * 4;
+            if (i < B && d < D) *(float4 *)(out + (int64_t)i * D + d) = ks_a_slab_quad<T>(st, row, quad); // D % 4 == 0
+        }
+        __syncthreads();
+    }
 }
 
 // dW_active[a][d] = scale * sum_i dZT[a][i] * X[i][d] on the asynchronous engine (X k-major, k = i).
