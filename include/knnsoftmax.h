@@ -80,6 +80,20 @@ size_t knn_graph_build_workspace(int64_t C, int D, int K, int dtype);
 int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K, int32_t *graph, float *sims,
                     void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
+/* knn_graph_build_plan -- how knn_graph_build divides the linear search of Section 3.2.2 when it computes every
+ * similarity once and uses it for both rows of the pair (large C; D = 128, 256 or 512; K <= 32).  Host-only, no GPU
+ * work; for tests and tools.
+ *   n_workgroups [1]   out (host): workgroups of that pass, 0 when this problem takes the plain pass
+ *   out          [12]  out (host), may be NULL: for `workgroup` in [0, *n_workgroups):
+ *                      [0] its block of 256 resident rows (rows 256 b .. 256 b + 255), or -1: none;
+ *                      [1 + 2 p], [2 + 2 p], p = 0..4: streamed rows [first, end) of its five ranges (end <= first:
+ *                      empty); range 0 is the 768-row super-block that holds its own block;
+ *                      [11] bit k set: inside range 0 it pairs its rows with block k of that super-block (its own
+ *                      block is always searched, for its own rows only)
+ * Every pair of different blocks is paired by exactly one workgroup: inside range 0 as [11] says, in ranges 1..4
+ * with every row.  Returns KS_OK, or KS_INVALID_ARG / KS_UNSUPPORTED as knn_graph_build would. */
+int knn_graph_build_plan(int64_t C, int D, int K, int dtype, int workgroup, int32_t *n_workgroups, int32_t *out);
+
 /* ------------------------------------------------------------------------------------------------------
  * knn_select_active -- Algorithm 1 without its random fill-up branch: the de-duplicated union of the
  * labels' neighbour lists, each list headed by the label itself; when more than M classes remain, the M

@@ -10,6 +10,6 @@ from .binding import (KS_DEV_RANGE, FLAG_UNIT_ROWS, FLAG_PAD_RANDOM, knn_graph_c
                       KS_DEV_IDX_NOT_SORTED, KS_INVALID_ARG, KS_OK, KS_UNSUPPORTED, KS_WORKSPACE_TOO_SMALL,
                       KsError, apply_weight_grad, apply_weight_grad_normalized, apply_weight_grad_normalized_workspace,
                       apply_weight_grad_workspace, knn_norm_backward_rows, knn_normalize_rows, full_softmax_fwd_bwd,
-                      full_softmax_workspace, knn_gather_rows, knn_graph_build, knn_graph_build_workspace,
+                      full_softmax_workspace, knn_gather_rows, knn_graph_build, knn_graph_build_plan, knn_graph_build_workspace,
                       knn_select_active, knn_select_active_static, knn_select_workspace, knn_softmax_fwd_bwd, knn_softmax_workspace,
                       ks_version, lib, lib_path, GradTopkPlan, grad_topk_plan, grad_topk_select)

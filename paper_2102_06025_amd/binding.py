@@ -17,7 +17,7 @@ _STATUS = {1: "KS_INVALID_ARG", 2: "KS_UNSUPPORTED", 3: "KS_WORKSPACE_TOO_SMALL"
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
-EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_select_workspace",
+EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_graph_build_plan", "knn_select_workspace",
            "knn_select_active", "knn_select_active_static", "knn_gather_rows", "knn_softmax_workspace", "knn_softmax_fwd_bwd",
            "full_softmax_workspace", "full_softmax_fwd_bwd", "apply_weight_grad_workspace", "apply_weight_grad",
            "knn_normalize_rows", "knn_norm_backward_rows", "apply_weight_grad_normalized_workspace",
@@ -100,6 +100,17 @@ def _status(device, dev_status):
 # ---------------------------------------------------------------------------------------------------
 def knn_graph_build_workspace(C, D, K, dtype) -> int:
     return int(lib().knn_graph_build_workspace(ct.c_int64(C), ct.c_int(D), ct.c_int(K), ct.c_int(dtype)))
+
+
+def knn_graph_build_plan(C, D, K, dtype, workgroup=None):
+    """Host-only.  -> (n_workgroups, plan) of the pass that computes every similarity once; n_workgroups == 0 when the
+    problem takes the plain pass; plan (12 ints, see the header) only when `workgroup` is given."""
+    n = ct.c_int32(0)
+    out = (ct.c_int32 * 12)() if workgroup is not None else None
+    rc = lib().knn_graph_build_plan(ct.c_int64(C), ct.c_int(D), ct.c_int(K), ct.c_int(dtype),
+                                    ct.c_int(0 if workgroup is None else workgroup), ct.byref(n), out)
+    _check("knn_graph_build_plan", rc)
+    return int(n.value), (list(out) if out is not None else None)
 
 
 def knn_graph_build(W, K, want_sims=False, graph=None, sims=None, ws=None, dev_status=None, stream=None):

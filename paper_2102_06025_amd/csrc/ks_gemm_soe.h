@@ -54,6 +54,9 @@ __device__ __forceinline__ int ks_soe_col() { return (threadIdx.x >> 6) * 32 + (
 // memory once per chunk, and waiting for that read means waiting for every stream load issued before it:
 // the wait counter of vector-memory instructions is shared.
 //
+// ctab / ctab_n: optional table of chunks (first streamed row, rows) that replaces the single range [s_begin, s_end):
+// the sweep then visits ctab_n chunks that may lie anywhere (the same table for all threads; no gather list with it).
+//
 // post(chunk_first_row, rows_in_chunk): optional second half of a chunk's epilogue, for global stores.  The
 // sweep tells that a stage has landed by counting outstanding vector-memory instructions, and stores count
 // too: stores issued at the end of a chunk make the very next wait sit out their round trip.  post() for
@@ -71,7 +74,8 @@ template <class CFG, class Epi, class Post = KsSoeNoPost>
 __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int64_t ldr, int r_row0, int r_limit,
                                               const uint16_t *__restrict__ S, int64_t lds_ld, const int32_t *__restrict__ gidx,
                                               int s_begin, int s_end, int s_clamp, uint16_t *lds, Epi &epi,
-                                              int32_t *lidx = nullptr, int lidx_cap = 0, Post post = Post()) {
+                                              int32_t *lidx = nullptr, int lidx_cap = 0, Post post = Post(),
+                                              const int2 *__restrict__ ctab = nullptr, int ctab_n = 0) {
     constexpr int KT = CFG::KT, ST = CFG::STAGES, NI = CFG::NI, FM = CFG::FM;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -109,7 +113,12 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
     }
 
     // ---- stream state ---------------------------------------------------------------------------------------
-    const int n_chunks = (s_end - s_begin + CFG::CH - 1) / CFG::CH;
+    const int n_chunks = ctab ? ctab_n : (s_end - s_begin + CFG::CH - 1) / CFG::CH;
+    auto chunk_first = [&](int c) __attribute__((always_inline)) { return ctab ? ctab[c].x : s_begin + c * CFG::CH; };
+    auto chunk_rows = [&](int c) __attribute__((always_inline)) {
+        if (ctab) return ctab[c].y;
+        return (s_end - (s_begin + c * CFG::CH)) < CFG::CH ? (s_end - (s_begin + c * CFG::CH)) : CFG::CH;
+    };
     const int n_tiles = n_chunks * (KT / CFG::KSUB); // pipeline stages in the whole sweep
     const bool use_lidx = gidx && lidx && n_chunks * CFG::CH <= lidx_cap;
     if (use_lidx) {
@@ -124,6 +133,7 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
     const bool loader = wave < CFG::LW;
     const uint16_t *ptr[NI]; // row pointers (k = 0, swizzled chunk) of the chunk being issued (loading wavefronts)
     auto chunk_ptrs = [&](int c) __attribute__((always_inline)) {
+        const int first = chunk_first(c);
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int row = (j * CFG::LW + wave) * 8 + (lane >> 3);
@@ -131,7 +141,7 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
             if (use_lidx) {
                 src = lidx[c * CFG::CH + row];
             } else {
-                int g = s_begin + c * CFG::CH + row;
+                int g = first + row;
                 if (g >= s_clamp) g = s_clamp - 1;
                 src = gidx ? (int64_t)gidx[g] : (int64_t)g;
             }
@@ -167,7 +177,7 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
     const int r31 = lane & 31, khalf = lane >> 5, swz = (lane >> 1) & 7;
     int stage = 0, done = 0;
     for (int c = 0; c < n_chunks; ++c) {
-        const int rows_here = (s_end - (s_begin + c * CFG::CH)) < CFG::CH ? (s_end - (s_begin + c * CFG::CH)) : CFG::CH;
+        const int rows_here = chunk_rows(c);
         f32x16_t acc[FM];
         // All k-tiles of one chunk.  FULL: the chunk has all CH rows -- the common case, compiled without a branch
         // between the MFMAs (a branch ends the basic block, and the wait for the fragment reads that the compiler
@@ -189,10 +199,7 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
                 if (issued - done - 1 >= ST - 2) ks_wait_vmcnt<(ST - 2) * NI * CFG::KSUB>();
                 else ks_wait_vmcnt<0>();
                 ks_barrier_nofence();
-                if (kt0 == 0 && c > 0) {
-                    const int pc0 = s_begin + (c - 1) * CFG::CH;
-                    post(pc0, (s_end - pc0) < CFG::CH ? (s_end - pc0) : CFG::CH);
-                }
+                if (kt0 == 0 && c > 0 && KsSoeHasPost<Post>::value) post(chunk_first(c - 1), chunk_rows(c - 1));
 #pragma unroll
                 for (int u = 0; u < CFG::KSUB; ++u) {
                     const int kt = kt0 + u;
@@ -244,11 +251,8 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
         // a chunk of a single stage has no barrier between post() of the previous chunk (which reads what epi() left
         // in LDS) and this chunk's epi(): a wavefront that runs ahead must not overwrite what another still reads
         if (KT / CFG::KSUB < 2 && KsSoeHasPost<Post>::value) ks_barrier_nofence();
-        epi(s_begin + c * CFG::CH, rows_here, acc);
+        epi(chunk_first(c), rows_here, acc);
     }
     ks_barrier_nofence();
-    if (n_chunks > 0) {
-        const int pc0 = s_begin + (n_chunks - 1) * CFG::CH;
-        post(pc0, s_end - pc0);
-    }
+    if (n_chunks > 0 && KsSoeHasPost<Post>::value) post(chunk_first(n_chunks - 1), chunk_rows(n_chunks - 1));
 }

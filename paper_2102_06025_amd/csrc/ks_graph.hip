@@ -6,6 +6,8 @@
 //             MFMA tiles of similarities; an element that beats its row's threshold is appended to that row's candidate
 //             buffer; a full buffer is cut back to its k' best by a wavefront (a bitwise search for the
 //             k'-th largest key), which also raises the threshold.  The C x C similarities are never stored.
+//             Large problems (D = 128, 256, 512, K <= 32) take the variant that computes every similarity once and
+//             uses it for both rows of the pair, with thresholds fixed beforehand from a sample of the rows (gr_sym_*).
 //   re-rank   one wavefront per row: canonical fp64 similarity of the k' candidates, exact order
 //             (similarity descending, id ascending), first K written out.  The row is certified when
 //             the K-th exact similarity exceeds the recall threshold by more than the error bound of the
@@ -453,6 +455,460 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
 }
 
 // ------------------------------------------------------------------------------------------------
+// recall pass that computes every similarity ONCE (W searched in W, D = 128, 256 or 512, k' <= 64).
+//
+// The similarity matrix is symmetric, so the tile of a workgroup's 256 resident rows against a streamed row j holds,
+// for every resident row i, a candidate for BOTH lists: j for row i (the "resident side", a lane's own row, as in the
+// kernel above) and i for row j (the "stream side").  Each unordered pair of 256-row blocks is given to exactly one
+// workgroup, which halves the MFMA work of the pass.  What it takes:
+//
+//  * thresholds known in advance.  A row that is streamed past hundreds of workgroups cannot keep a running
+//    threshold, so a first pass (the kernel above, on every `ratio`-th row of W only) finds for each row the
+//    (k'+1)-th largest similarity to that sample.  At least k' other rows are at or above it, so it is a valid lower
+//    bound of the row's k'-th best, and the number of rows above it in all of W is about (k'+1) * ratio whatever the
+//    distribution of the rows (it is an order statistic of a uniform sample).  Both sides test against these fixed
+//    thresholds and the buffers are sized for that count; nothing is cut back during the sweep.
+//  * who takes which pair.  Rows are cut into blocks of 256 (a workgroup's resident rows), super-blocks of 768 rows
+//    (three blocks = eight 96-row chunks, so that every streamed range starts on a chunk boundary) and groups of up
+//    to 10 super-blocks.  On each level the members form a ring and a member takes the following half of the ring
+//    (gr_sym_succ): a workgroup streams its own super-block (its own block for the resident side only, the blocks it
+//    takes there for both sides), then the super-blocks it takes inside its group, then all rows of the groups its
+//    group takes.  The 30 workgroups of a group sit on one XCD and stream the same long ranges at the same pace, so
+//    a streamed row is fetched from memory once per group.
+//  * the stream side's candidates.  A hit for streamed row j is a record (j, i, similarity): a wavefront collects them
+//    in LDS and appends them, with one atomic per batch, to the log of j's super-block; gr_sym_scatter_kernel (one
+//    workgroup per super-block, row counters in LDS) then moves them into the rows' buffers.  The fast test of the
+//    stream side compares a group of four accumulator elements with thresholds held in scalar registers: the two
+//    halves of a wavefront hold different streamed rows (j and j + 4), so the test uses the smaller of the two
+//    thresholds (gr_sym_prep_kernel stores these minima) and the exact ones only when some lane passes.
+//  * gr_sym_select_kernel cuts every row's candidates (two resident-side halves and the stream side) to the k' best,
+//    in the layout the re-rank expects.  A row whose buffers or log overflowed gets a threshold no similarity
+//    exceeds: its certificate fails and the exhaustive pass computes it.
+// ------------------------------------------------------------------------------------------------
+#define GR_SYM_CAP 2048          /* candidate slots per row: two resident-side halves, then the stream side */
+#define GR_SYM_Q 512             /* slots of each resident-side half */
+#define GR_SYM_SCAP 1024         /* slots of the stream side */
+#define GR_SYM_SB 768            /* rows of a super-block */
+#define GR_SYM_LOGCAP (768 * 640) /* records per super-block log (expected: 768 * (k'+1) * ratio / 2, about 300,000) */
+#define GR_SYM_STAGE 192         /* records a wavefront collects in LDS between two appends to a log */
+#define GR_SYM_MAX_GROUP 10      /* super-blocks per group at most: 30 workgroups, about the compute units of an XCD */
+
+// rows of W sampled by the first pass: one of every `ratio` consecutive rows, at a position that varies from one run
+// of `ratio` rows to the next
+__device__ __forceinline__ int64_t gr_sym_sample_row(int64_t s, int ratio, int64_t C) {
+    const int64_t r = s * ratio + (int64_t)(((uint32_t)s * 2654435761u) >> 16) % ratio;
+    return r < C ? r : C - 1;
+}
+// members of a ring of n that member x takes: the next gr_sym_succ(n, x) ones.  Every unordered pair is taken once:
+// for even n the opposite member is taken by the lower of the two.
+__host__ __device__ __forceinline__ int gr_sym_succ(int n, int x) {
+    return (n & 1) ? (n - 1) / 2 : (x < n / 2 ? n / 2 : n / 2 - 1);
+}
+__host__ __device__ __forceinline__ int gr_sym_group_sbs(int64_t C) { // super-blocks per group
+    const int nsb = (int)((C + GR_SYM_SB - 1) / GR_SYM_SB);
+    const int gs = nsb / 16;
+    return gs < 1 ? 1 : (gs > GR_SYM_MAX_GROUP ? GR_SYM_MAX_GROUP : gs);
+}
+
+__global__ void __launch_bounds__(GR_NT)
+gr_sym_sample_kernel(const uint16_t *__restrict__ W, int64_t C, int D, int ratio, int64_t n_sample,
+                     uint16_t *__restrict__ Ws) {
+    const int64_t s = (int64_t)blockIdx.x * (GR_NT / 64) + (threadIdx.x >> 6);
+    if (s >= n_sample) return;
+    const uint4 *src = (const uint4 *)(W + gr_sym_sample_row(s, ratio, C) * D);
+    uint4 *dst = (uint4 *)(Ws + s * D);
+    for (int q = threadIdx.x & 63; q < D / 8; q += 64) dst[q] = src[q];
+}
+
+// thr_sample[i]: value bits of the (k'+1)-th largest similarity of row i to the sample (0: the sample had fewer rows).
+// Row i takes every similarity at or above it: thf[i] is the next float below, and tbits[i] its key, so that "v > thf"
+// is the test and "key value <= tbits" holds for everything that fails it.  pm: minima over the row pairs (j, j + 4)
+// that share an accumulator register.  Rows at and beyond C never pass.  Also clears the counters of the logs.
+__global__ void __launch_bounds__(GR_NT)
+gr_sym_prep_kernel(const uint32_t *__restrict__ thr_sample, int64_t C, int64_t Cpad, float *__restrict__ thf,
+                   uint32_t *__restrict__ tbits, float *__restrict__ pm, int32_t *__restrict__ logcnt, int nsb) {
+    const int64_t i = (int64_t)blockIdx.x * GR_NT + threadIdx.x;
+    if (i < nsb) logcnt[i] = 0;
+    if (i >= Cpad) return;
+    auto bits_of = [&](int64_t r) -> uint32_t {
+        const uint32_t lowest = gr_orderable(-INFINITY);
+        const uint32_t t = thr_sample[r];
+        return t > lowest + 1u ? t - 1u : lowest;
+    };
+    const float mine = i < C ? gr_unorder(bits_of(i)) : INFINITY;
+    thf[i] = mine;
+    if (i < C) tbits[i] = bits_of(i);
+    if ((i & 4) == 0) {
+        const float other = i + 4 < C ? gr_unorder(bits_of(i + 4)) : INFINITY;
+        pm[(i >> 3) * 4 + (i & 3)] = fminf(mine, other);
+    }
+}
+
+// The plan of the sweep, made by a small kernel beforehand (the sweep kernel has no registers to spare for the
+// arithmetic).  Per workgroup GR_SYM_PLAN words: [0] the resident block or -1, [1] the block's place in the ring of its
+// super-block's blocks (place | members << 4 | members it takes << 8), [2] the number of chunks it streams; and a table
+// of those chunks (first row, rows): its own super-block, then the super-blocks it takes in its group (two ranges: the
+// ring wraps), then the groups its group takes (likewise).
+#define GR_SYM_PLAN 4
+struct GrSymRanges {
+    int block;          // resident block, or -1: the workgroup has none
+    int ring;           // place | members << 4 | members taken << 8 in the ring of its super-block's blocks
+    int first[5], end[5]; // streamed rows [first, end) of the five ranges; empty: end <= first
+};
+__host__ __device__ inline GrSymRanges gr_sym_ranges(int wg, int C, int GS) {
+    GrSymRanges out;
+    const int NB = (C + 255) / 256, NSB = (C + GR_SYM_SB - 1) / GR_SYM_SB, NG = (NSB + GS - 1) / GS;
+    const int BPG = GS * (GR_SYM_SB / 256); // blocks per group
+    // the workgroups of a group are those that one XCD receives in a row (workgroups are dealt to the eight XCDs in turn)
+    const int g = (wg >> 3) / BPG * 8 + (wg & 7);
+    const int block = g * BPG + (wg >> 3) % BPG;
+    out.block = -1;
+    out.ring = 0;
+    for (int part = 0; part < 5; ++part) out.first[part] = out.end[part] = 0;
+    if (g >= NG || block >= NB) return out;
+    const int sb = block * 256 / GR_SYM_SB, own0 = sb * GR_SYM_SB, own1 = own0 + GR_SYM_SB < C ? own0 + GR_SYM_SB : C;
+    const int kb = (block * 256 - own0) / 256, n_b = (own1 - own0 + 255) / 256;
+    const int gsb0 = g * GS, n_sb = (gsb0 + GS < NSB ? gsb0 + GS : NSB) - gsb0, s_loc = sb - gsb0;
+    const int succ_s = gr_sym_succ(n_sb, s_loc), succ_g = gr_sym_succ(NG, g);
+    out.block = block;
+    out.ring = kb | (n_b << 4) | (gr_sym_succ(n_b, kb) << 8);
+    for (int part = 0; part < 5; ++part) {
+        int b = 0, e = 0; // in super-blocks
+        if (part == 0) { b = sb; e = sb + 1; }
+        else if (part == 1) { b = sb + 1; e = gsb0 + (s_loc + succ_s < n_sb - 1 ? s_loc + succ_s : n_sb - 1) + 1; }
+        else if (part == 2) { b = gsb0; e = gsb0 + (s_loc + succ_s - n_sb) + 1; }
+        else if (part == 3) { b = (g + 1) * GS; e = ((g + succ_g < NG - 1 ? g + succ_g : NG - 1) + 1) * GS; }
+        else { b = 0; e = (g + succ_g - NG + 1) * GS; }
+        if (e > NSB) e = NSB;
+        if (e <= b) continue;
+        const long long e_row = (long long)e * GR_SYM_SB;
+        out.first[part] = b * GR_SYM_SB;
+        out.end[part] = e_row < C ? (int)e_row : C;
+    }
+    return out;
+}
+__global__ void __launch_bounds__(GR_NT)
+gr_sym_plan_kernel(int C, int GS, int32_t *__restrict__ plan, int2 *__restrict__ chunks, int chunks_stride) {
+    const int wg = blockIdx.x;
+    int32_t *out = plan + (int64_t)wg * GR_SYM_PLAN;
+    int2 *tab = chunks + (int64_t)wg * chunks_stride;
+    const GrSymRanges r = gr_sym_ranges(wg, C, GS);
+    int n_chunks = 0;
+    for (int part = 0; part < 5; ++part) {
+        if (r.end[part] <= r.first[part]) continue;
+        const int n = (r.end[part] - r.first[part] + 95) / 96;
+        for (int c = threadIdx.x; c < n; c += GR_NT) {
+            const int first = r.first[part] + c * 96;
+            if (n_chunks + c < chunks_stride) tab[n_chunks + c] = make_int2(first, r.end[part] - first < 96 ? r.end[part] - first : 96);
+        }
+        n_chunks += n;
+    }
+    if (threadIdx.x == 0) {
+        out[0] = r.block;
+        out[1] = r.ring;
+        out[2] = n_chunks < chunks_stride ? n_chunks : chunks_stride; // (the stride is sized for the longest plan)
+    }
+}
+
+// Element r (0 .. 15, different from lane to lane) of a lane's 16 accumulator values: a binary tree of selects on the
+// bits of r.  (As assembly: written as conditional expressions the compiler turns the tree into a table in scratch
+// memory that it indexes with r.  The s_nop after each compare: a select must not read a mask that one of the two
+// instructions before it has written.)
+__device__ __forceinline__ float gr_sym_pick16(const f32x16_t &a, int r) {
+    float b0, b1, b2, b3, b4, b5, b6, b7, c0, c1, c2, c3, d0, d1, v;
+    asm("v_and_b32 %8, 1, %25\n\tv_cmp_ne_u32 vcc, 0, %8\n\ts_nop 1\n\t"
+        "v_cndmask_b32 %0, %9, %10, vcc\n\tv_cndmask_b32 %1, %11, %12, vcc\n\t"
+        "v_cndmask_b32 %2, %13, %14, vcc\n\tv_cndmask_b32 %3, %15, %16, vcc\n\t"
+        "v_cndmask_b32 %4, %17, %18, vcc\n\tv_cndmask_b32 %5, %19, %20, vcc\n\t"
+        "v_cndmask_b32 %6, %21, %22, vcc\n\tv_cndmask_b32 %7, %23, %24, vcc"
+        : "=&v"(b0), "=&v"(b1), "=&v"(b2), "=&v"(b3), "=&v"(b4), "=&v"(b5), "=&v"(b6), "=&v"(b7), "=&v"(v)
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(a[8]), "v"(a[9]),
+          "v"(a[10]), "v"(a[11]), "v"(a[12]), "v"(a[13]), "v"(a[14]), "v"(a[15]), "v"(r)
+        : "vcc");
+    asm("v_and_b32 %4, 2, %13\n\tv_cmp_ne_u32 vcc, 0, %4\n\ts_nop 1\n\t"
+        "v_cndmask_b32 %0, %5, %6, vcc\n\tv_cndmask_b32 %1, %7, %8, vcc\n\t"
+        "v_cndmask_b32 %2, %9, %10, vcc\n\tv_cndmask_b32 %3, %11, %12, vcc"
+        : "=&v"(c0), "=&v"(c1), "=&v"(c2), "=&v"(c3), "=&v"(v)
+        : "v"(b0), "v"(b1), "v"(b2), "v"(b3), "v"(b4), "v"(b5), "v"(b6), "v"(b7), "v"(r)
+        : "vcc");
+    asm("v_and_b32 %2, 4, %7\n\tv_cmp_ne_u32 vcc, 0, %2\n\ts_nop 1\n\t"
+        "v_cndmask_b32 %0, %3, %4, vcc\n\tv_cndmask_b32 %1, %5, %6, vcc"
+        : "=&v"(d0), "=&v"(d1), "=&v"(v)
+        : "v"(c0), "v"(c1), "v"(c2), "v"(c3), "v"(r)
+        : "vcc");
+    asm("v_and_b32 %0, 8, %3\n\tv_cmp_ne_u32 vcc, 0, %0\n\ts_nop 1\n\tv_cndmask_b32 %0, %1, %2, vcc"
+        : "=&v"(v)
+        : "v"(d0), "v"(d1), "v"(r)
+        : "vcc");
+    return v;
+}
+
+// a stream-side hit: similarity v of streamed row j (its place in its super-block is kept) with resident row `other`
+__device__ __forceinline__ uint2 gr_sym_record(int j, int other, float v) {
+    return make_uint2(gr_orderable(v), ((uint32_t)other << 10) | (uint32_t)(j % GR_SYM_SB));
+}
+
+template <int KT>
+__global__ void __launch_bounds__(512)
+gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t *__restrict__ plan,
+                     const int2 *__restrict__ chunks, int chunks_stride, const float *__restrict__ thf_row,
+                     const float *__restrict__ pm, uint64_t *__restrict__ cand, int32_t *__restrict__ cnt_res,
+                     uint2 *__restrict__ log, int32_t *logcnt) {
+    typedef KsSoe<KT, 96, GR_SOE_STAGES, 2> CFG;
+    constexpr int CAP = GR_SYM_CAP, Q = GR_SYM_Q, SB = GR_SYM_SB;
+    static_assert(SB % CFG::CH == 0 && SB % CFG::RES == 0 && CFG::RES == 256, "super-blocks are whole chunks and whole blocks");
+    __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
+    __shared__ uint2 s_stage[CFG::NW][GR_SYM_STAGE];
+    const int lane = threadIdx.x & 63;
+    const int32_t *my_plan = plan + (int64_t)blockIdx.x * GR_SYM_PLAN;
+    const int block = my_plan[0];
+    if (block < 0) return;
+    const int row0 = block * CFG::RES;
+    const int sb_own = row0 / SB;
+    const int ring = my_plan[1];
+    const float thf = row0 + ks_soe_col() < C ? thf_row[row0 + ks_soe_col()] : INFINITY;
+    uint64_t *const wg_cand = cand + (int64_t)row0 * CAP;
+    int my_cnt = 0;
+    // stream side: records collected by this wavefront, and the super-block they belong to
+    int staged = 0, cur_sb = sb_own;
+    auto my_stage = [&]() __attribute__((always_inline)) { return s_stage[__builtin_amdgcn_readfirstlane(threadIdx.x >> 6)]; };
+    auto flush = [&]() {
+        if (staged > 0) {
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&logcnt[cur_sb], staged);
+            base = __builtin_amdgcn_readfirstlane(base);
+            uint2 *dst = log + (int64_t)cur_sb * GR_SYM_LOGCAP;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the records written by the other lanes are in LDS
+            for (int q = lane; q < staged; q += 64)
+                if (base + q < GR_SYM_LOGCAP) dst[base + q] = my_stage()[q];
+            asm volatile("" ::: "memory");
+            staged = 0;
+        }
+    };
+    // all lanes call it together with the ballot m of `hit`; the lanes that hit add the record (j, own row, v)
+    auto push = [&](uint64_t m, bool hit, int j, float v) __attribute__((always_inline)) {
+        const int n = __popcll(m);
+        if (staged + n > GR_SYM_STAGE) flush();
+        if (hit) my_stage()[staged + __popcll(m & ((1ull << lane) - 1ull))] = gr_sym_record(j, row0 + ks_soe_col(), v);
+        staged = __builtin_amdgcn_readfirstlane(staged + n);
+    };
+    auto append_res = [&](int j, float v) __attribute__((always_inline)) {
+        // (the mask keeps the store inside the lane's half; a count beyond Q marks the row as overflowed)
+        const uint32_t my_base = (uint32_t)(ks_soe_col() * CAP + (lane >> 5) * Q);
+        wg_cand[my_base + ((uint32_t)my_cnt & (uint32_t)(Q - 1))] = ((uint64_t)gr_orderable(v) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
+        ++my_cnt;
+    };
+    auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM]) {
+        const int sb = c0 / SB; // uniform; a chunk lies in one super-block
+        if (sb != cur_sb) { flush(); cur_sb = sb; }
+        if (rows_here == CFG::CH && sb != sb_own) {
+            // plain chunk: all rows real, both sides wanted for every element
+            const bool real_row = row0 + ks_soe_col() < C;
+#pragma unroll
+            for (int fm = 0; fm < CFG::FM; ++fm) {
+                const float *pmc = pm + ((c0 + fm * 32) >> 1); // 16 pair minima: rows 8 q + e and 8 q + 4 + e at 4 q + e
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float a0 = acc[fm][4 * q], a1 = acc[fm][4 * q + 1], a2 = acc[fm][4 * q + 2], a3 = acc[fm][4 * q + 3];
+                    if (fmaxf(fmaxf(a0, a1), fmaxf(a2, a3)) > thf) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float v = acc[fm][4 * q + e];
+                            if (v > thf) append_res(c0 + ks_soe_row(fm, 4 * q + e, lane), v);
+                        }
+                    }
+                }
+                // stream side: the two halves of the wavefront hold rows j and j + 4, the test is against the smaller of
+                // their two thresholds (the exact one is applied when the records are sorted into the rows' buffers).
+                // The hits of the 32 rows are counted first, so that room for them is made once; the code that runs
+                // for every chunk has to stay small (the instruction cache holds 64 KB).
+                // Every instruction here runs once per chunk and fragment, so there are few: a lane's hits become a bit
+                // mask with a compare and an add-with-carry per element (bit 15 - r for element r); nearly always no lane
+                // has more than one hit, and then a lane picks its element with a binary tree of selects and the slots
+                // come from one ballot.
+                uint32_t hm = 0u;
+#pragma unroll
+                for (int r = 0; r < 16; r += 4)
+                {
+                    // (the four compares first: a vector instruction must not read a mask that one of the two
+                    // instructions before it has written)
+                    uint64_t k0, k1, k2, k3;
+                    asm("v_cmp_lt_f32 %1, %5, %9\n\tv_cmp_lt_f32 %2, %6, %10\n\tv_cmp_lt_f32 %3, %7, %11\n\t"
+                        "v_cmp_lt_f32 %4, %8, %12\n\t"
+                        "v_addc_co_u32 %0, vcc, %0, %0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, %2\n\t"
+                        "v_addc_co_u32 %0, vcc, %0, %0, %3\n\tv_addc_co_u32 %0, vcc, %0, %0, %4"
+                        : "+v"(hm), "=&s"(k0), "=&s"(k1), "=&s"(k2), "=&s"(k3)
+                        : "s"(pmc[r]), "s"(pmc[r + 1]), "s"(pmc[r + 2]), "s"(pmc[r + 3]), "v"(acc[fm][r]), "v"(acc[fm][r + 1]),
+                          "v"(acc[fm][r + 2]), "v"(acc[fm][r + 3])
+                        : "vcc");
+                }
+                if (!real_row) hm = 0u;
+                const uint64_t any = __ballot(hm != 0u);
+                if (any != 0ull) {
+                    if (__ballot((hm & (hm - 1u)) != 0u) == 0ull) {
+                        const int n = __popcll(any);
+                        if (staged + n > GR_SYM_STAGE) flush();
+                        if (hm != 0u) {
+                            const int r = 15 - __builtin_ctz(hm);
+                            const float v = gr_sym_pick16(acc[fm], r);
+                            const int lr = fm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                            my_stage()[staged + __popcll(any & ((1ull << lane) - 1ull))] = gr_sym_record(c0 + lr, row0 + ks_soe_col(), v);
+                        }
+                        staged = __builtin_amdgcn_readfirstlane(staged + n);
+                    } else { // a lane with several hits: row by row
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            const bool hit = (hm >> (15 - r)) & 1u;
+                            const uint64_t m = __ballot(hit);
+                            if (m != 0ull) push(m, hit, c0 + ks_soe_row(fm, r, lane), acc[fm][r]);
+                        }
+                    }
+                }
+            }
+        } else {
+            // the workgroup's own super-block (which side is wanted depends on the streamed row's block) or a ragged end
+            // (the lane number goes through an opaque copy: otherwise the compiler computes the 48 row numbers and what
+            // follows from them once, before the sweep, and keeps them in registers that the sweep does not have)
+            int lane_here = lane;
+            asm volatile("" : "+v"(lane_here));
+            const int gi = row0 + (threadIdx.x >> 6) * 32 + (lane_here & 31);
+            const int own0 = sb_own * SB, kb = ring & 15, n_b = (ring >> 4) & 15, succ_b = ring >> 8;
+#pragma unroll
+            for (int fm = 0; fm < CFG::FM; ++fm) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int lr = ks_soe_row(fm, 4 * q + e, lane_here);
+                        const int j = c0 + lr;
+                        const float v = acc[fm][4 * q + e];
+                        bool res_side = lr < rows_here, str_side = lr < rows_here;
+                        if (sb == sb_own) {
+                            int dd = (j - own0) / CFG::RES - kb; // ring distance from this block to the streamed row's block
+                            if (dd < 0) dd += n_b;
+                            const bool taken = dd >= 1 && dd <= succ_b;
+                            res_side = res_side && ((dd == 0 && j != gi) || taken);
+                            str_side = str_side && taken;
+                        }
+                        if (res_side && v > thf) append_res(j, v);
+                        float t = INFINITY;
+                        if (str_side && gi < C) t = thf_row[j];
+                        const uint64_t m = __ballot(v > t);
+                        if (m != 0ull) push(m, v > t, j, v);
+                    }
+                    asm volatile("" ::: "memory"); // one group at a time: no pile of threshold loads in flight
+                }
+            }
+        }
+    };
+    ks_soe_sweep<CFG>(W, D, row0, C, W, D, nullptr, 0, 0, C, lds, epi, nullptr, 0, KsSoeNoPost(),
+                      chunks + (int64_t)blockIdx.x * chunks_stride, my_plan[2]);
+    flush();
+    if (row0 + ks_soe_col() < C) cnt_res[2 * (row0 + ks_soe_col()) + (lane >> 5)] = my_cnt;
+}
+
+// the stream-side records of a super-block go to the rows they belong to; one workgroup per super-block
+__global__ void __launch_bounds__(1024)
+gr_sym_scatter_kernel(const uint2 *__restrict__ log, const int32_t *__restrict__ logcnt, int C, const uint32_t *__restrict__ tbits,
+                      uint64_t *__restrict__ cand, int32_t *__restrict__ cnt_str) {
+    __shared__ int s_cnt[GR_SYM_SB];
+    __shared__ uint32_t s_tb[GR_SYM_SB];
+    const int sb = blockIdx.x, row0 = sb * GR_SYM_SB;
+    for (int r = threadIdx.x; r < GR_SYM_SB; r += 1024) {
+        s_cnt[r] = 0;
+        s_tb[r] = row0 + r < C ? tbits[row0 + r] : 0xFFFFFFFFu;
+    }
+    __syncthreads();
+    const int n_raw = logcnt[sb], n = n_raw < GR_SYM_LOGCAP ? n_raw : GR_SYM_LOGCAP;
+    const uint2 *src = log + (int64_t)sb * GR_SYM_LOGCAP;
+    for (int q = threadIdx.x; q < n; q += 1024) {
+        const uint2 rec = src[q];
+        const int jl = (int)(rec.y & 1023u); // (checked all the same: it becomes an address)
+        const uint32_t other = rec.y >> 10;
+        if (jl >= GR_SYM_SB || row0 + jl >= C || other >= (uint32_t)C) continue;
+        if (rec.x <= s_tb[jl]) continue;  // passed its neighbour's threshold in the sweep's test, not its own
+        const int slot = atomicAdd(&s_cnt[jl], 1);
+        if (slot < GR_SYM_SCAP)
+            cand[(int64_t)(row0 + jl) * GR_SYM_CAP + 2 * GR_SYM_Q + slot] = ((uint64_t)rec.x << 32) | (uint32_t)(0xFFFFFFFFu - other);
+    }
+    __syncthreads();
+    for (int r = threadIdx.x; r < GR_SYM_SB; r += 1024)
+        if (row0 + r < C) cnt_str[row0 + r] = n_raw > GR_SYM_LOGCAP ? 0x7FFFFFFF : s_cnt[r]; // a lost record: all rows overflow
+}
+
+// k' best of a row's candidates to the front of its buffer; one wavefront per row
+__global__ void __launch_bounds__(GR_NT)
+gr_sym_select_kernel(int64_t C, int kprime, uint64_t *__restrict__ cand, const int32_t *__restrict__ cnt_res,
+                     const int32_t *__restrict__ cnt_str, const uint32_t *__restrict__ tbits, int32_t *__restrict__ cnt_out,
+                     uint32_t *__restrict__ thr_out) {
+    constexpr int E = GR_SYM_CAP / 64, Q = GR_SYM_Q;
+    const int64_t i = (int64_t)blockIdx.x * (GR_NT / 64) + (threadIdx.x >> 6);
+    if (i >= C) return;
+    const int lane = threadIdx.x & 63;
+    uint64_t *row = cand + i * GR_SYM_CAP;
+    const int r0 = cnt_res[2 * i], r1 = cnt_res[2 * i + 1], rs = cnt_str[i];
+    const bool overflow = r0 > Q || r1 > Q || rs > GR_SYM_SCAP;
+    const int n0 = r0 < Q ? r0 : Q, n1 = r1 < Q ? r1 : Q, ns = rs < GR_SYM_SCAP ? rs : GR_SYM_SCAP;
+    const int n = n0 + n1 + ns, nreg = (n + 63) >> 6;
+    uint64_t val[E];
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        val[r] = 0ull; // below every real key
+        if (r < nreg) {
+            const int idx = r * 64 + lane;
+            if (idx < n) val[r] = row[idx < n0 ? idx : (idx < n0 + n1 ? Q + (idx - n0) : 2 * Q + (idx - n0 - n1))];
+        }
+    }
+    auto count_hi = [&](uint32_t t) {
+        int c = 0;
+#pragma unroll
+        for (int r = 0; r < E; ++r)
+            if (r < nreg) c += __popcll(__ballot((uint32_t)(val[r] >> 32) >= t));
+        return c;
+    };
+    auto count_lo = [&](uint32_t hi, uint32_t t) {
+        int c = 0;
+#pragma unroll
+        for (int r = 0; r < E; ++r)
+            if (r < nreg) c += __popcll(__ballot((uint32_t)(val[r] >> 32) == hi && (uint32_t)val[r] >= t));
+        return c;
+    };
+    uint64_t t = 1ull; // keeps every real key
+    if (n > kprime) {
+        uint32_t t_hi = 0;
+        for (int bit = 31; bit >= 0; --bit) {
+            const uint32_t c = t_hi | (1u << bit);
+            if (count_hi(c) >= kprime) t_hi = c;
+        }
+        t = (uint64_t)t_hi << 32;
+        if (count_hi(t_hi) != kprime) { // keys of equal value straddle the cut: the ids decide
+            const int need = kprime - (t_hi == 0xFFFFFFFFu ? 0 : count_hi(t_hi + 1u));
+            uint32_t t_lo = 0;
+            for (int bit = 31; bit >= 0; --bit) {
+                const uint32_t c = t_lo | (1u << bit);
+                if (count_lo(t_hi, c) >= need) t_lo = c;
+            }
+            t |= t_lo;
+        }
+    }
+    int base = 0;
+#pragma unroll
+    for (int r = 0; r < E; ++r) {
+        if (r < nreg) {
+            const uint64_t m = __ballot(val[r] >= t);
+            if (val[r] >= t) row[base + __popcll(m & ((1ull << lane) - 1ull))] = val[r];
+            base += __popcll(m);
+        }
+    }
+    if (lane == 0) {
+        cnt_out[i] = n > kprime ? kprime : n;
+        // what was left out is at or below the k'-th key if the cut dropped something, else at or below the row's
+        // fixed threshold; after an overflow nothing is known about it
+        thr_out[i] = overflow ? 0xFFFFFFFFu : (n > kprime ? (uint32_t)(t >> 32) : tbits[i]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // canonical similarity: sum over d ascending of (double)a_d * (double)b_d, one fused multiply-add per
 // term (the product of two fp32 or bf16 values is exact in fp64, so this equals multiply-then-add)
 // ------------------------------------------------------------------------------------------------
@@ -518,6 +974,7 @@ gr_rerank_kernel(const IN *__restrict__ W, int64_t C, int D, int K, int cap, con
     if (i >= C) return;
     const int lane = threadIdx.x & 63;
     const int n = cnt[i];
+    if (n < K && lane == 0) fb_rows[atomicAdd(fb_count, 1)] = (int32_t)i; // no K-th candidate to certify
     double s[4];
     int32_t id[4];
 #pragma unroll
@@ -636,21 +1093,60 @@ struct GrWs {
     int32_t *fb_count;
     int32_t *fb_rows;
     double *scratch;
+    // the pass that computes every similarity once (gr_sym_*), when it is used
+    uint16_t *Ws;      // sampled rows
+    float *thf, *pm;   // fixed thresholds, and their minima over row pairs
+    uint32_t *tbits;
+    int32_t *cnt_res, *cnt_str, *logcnt, *plan;
+    int2 *chunks;
+    uint2 *log;
 };
+
+// The pass that computes every similarity once needs a sample large enough for its thresholds to be tight (eight
+// times k'+1 rows) and buffers whose size grows with k'.
+static unsigned gr_sym_grid(int64_t C) { // workgroups of the sweep: whole groups, dealt to the eight XCDs
+    const int nsb = (int)ks_ceil_div(C, GR_SYM_SB), GS = gr_sym_group_sbs(C), NG = (nsb + GS - 1) / GS;
+    return (unsigned)((NG + 7) / 8) * (unsigned)(GS * 3) * 8u;
+}
+static int gr_sym_chunks_stride(int64_t C) { // chunks a workgroup streams at most: half of all groups, half of its own, a spare
+    const int64_t nsb = ks_ceil_div(C, GR_SYM_SB), GS = gr_sym_group_sbs(C), NG = ks_ceil_div(nsb, GS);
+    return (int)(((NG / 2) * GS + GS / 2 + 2) * (GR_SYM_SB / 96));
+}
+static int gr_sym_ratio(int kprime) { return kprime <= 48 ? 16 : 12; } // rows of W per sampled row: (k'+1) * ratio = 784
+static bool gr_use_sym(int64_t C, int D, const GrParams &p) {
+    return (D == 128 || D == 256 || D == 512) && p.kprime <= 64 && C / gr_sym_ratio(p.kprime) >= 8 * (p.kprime + 1) &&
+           C <= ((int64_t)1 << 22); // (a row id has 22 bits in the stream side's records)
+}
 
 static GrWs gr_carve(void *ws, int64_t C, int D, int K, int dtype, size_t *total) {
     KsArena ar(ws);
     GrParams p = gr_params(K, D);
+    const GrParams pd = gr_params(K, D, dtype);
+    const bool sym = gr_use_sym(C, D, pd);
     GrWs w;
     w.Wb = dtype == KS_DTYPE_FP32 ? ar.take<uint16_t>((size_t)C * D) : nullptr;
     w.norms = ar.take<float>((size_t)C);
     w.maxnorm = ar.take<uint32_t>(1);
-    w.cand = ar.take<uint64_t>((size_t)C * p.cap);
+    w.cand = ar.take<uint64_t>((size_t)C * (sym ? GR_SYM_CAP : p.cap));
     w.cnt = ar.take<int32_t>((size_t)C);
     w.thr = ar.take<uint32_t>((size_t)C);
     w.fb_count = ar.take<int32_t>(1);
     w.fb_rows = ar.take<int32_t>((size_t)C);
     w.scratch = ar.take<double>((size_t)GR_FB_BLOCKS * C);
+    w.Ws = nullptr; w.thf = w.pm = nullptr; w.tbits = nullptr; w.cnt_res = w.cnt_str = w.logcnt = w.plan = nullptr; w.chunks = nullptr; w.log = nullptr;
+    if (sym) {
+        const int64_t nsb = ks_ceil_div(C, GR_SYM_SB), Cpad = nsb * GR_SYM_SB + 96;
+        w.Ws = ar.take<uint16_t>((size_t)(C / gr_sym_ratio(pd.kprime)) * D);
+        w.thf = ar.take<float>((size_t)Cpad);
+        w.pm = ar.take<float>((size_t)Cpad / 2);
+        w.tbits = ar.take<uint32_t>((size_t)C);
+        w.cnt_res = ar.take<int32_t>((size_t)C * 2);
+        w.cnt_str = ar.take<int32_t>((size_t)C);
+        w.logcnt = ar.take<int32_t>((size_t)nsb);
+        w.plan = ar.take<int32_t>((size_t)gr_sym_grid(C) * GR_SYM_PLAN);
+        w.chunks = ar.take<int2>((size_t)gr_sym_grid(C) * gr_sym_chunks_stride(C));
+        w.log = ar.take<uint2>((size_t)nsb * GR_SYM_LOGCAP);
+    }
     if (total) *total = ar.off;
     return w;
 }
@@ -659,6 +1155,31 @@ static int gr_check(int64_t C, int D, int K, int dtype) {
     if (dtype != KS_DTYPE_BF16 && dtype != KS_DTYPE_FP32) return KS_INVALID_ARG;
     if (C < 2 || C >= (int64_t)1 << 31 || D < 32 || D % 32 != 0 || K < 1) return KS_INVALID_ARG;
     if (K > KS_MAX_GRAPH_K || K > C - 1 || D > GR_MAX_D) return KS_UNSUPPORTED;
+    return KS_OK;
+}
+
+extern "C" int knn_graph_build_plan(int64_t C, int D, int K, int dtype, int workgroup, int32_t *n_workgroups, int32_t *out) {
+    if (!n_workgroups) return KS_INVALID_ARG;
+    int rc = gr_check(C, D, K, dtype);
+    if (rc != KS_OK) return rc;
+    *n_workgroups = 0;
+    if (!gr_use_sym(C, D, gr_params(K, D, dtype))) return KS_OK;
+    *n_workgroups = (int32_t)gr_sym_grid(C);
+    if (!out) return KS_OK;
+    if (workgroup < 0 || workgroup >= *n_workgroups) return KS_INVALID_ARG;
+    const GrSymRanges r = gr_sym_ranges(workgroup, (int)C, gr_sym_group_sbs(C));
+    out[0] = r.block;
+    for (int part = 0; part < 5; ++part) { out[1 + 2 * part] = r.first[part]; out[2 + 2 * part] = r.end[part]; }
+    // which of the (up to three) 256-row blocks of its own super-block it pairs with: bit k = block k of that super-block
+    int mask = 0;
+    if (r.block >= 0) {
+        const int kb = r.ring & 15, n_b = (r.ring >> 4) & 15, succ_b = r.ring >> 8;
+        for (int k = 0; k < n_b; ++k) {
+            const int dd = (k - kb + n_b) % n_b;
+            if (dd >= 1 && dd <= succ_b) mask |= 1 << k;
+        }
+    }
+    out[11] = mask;
     return KS_OK;
 }
 
@@ -708,6 +1229,42 @@ static void gr_launch_recall(const GrPair &pr, int D, const GrParams &p, uint64_
     }
 }
 
+// W searched in W with every similarity computed once: thresholds from a sample, the sweep, the stream side's records
+// to their rows, the cut to k'
+static void gr_launch_recall_sym(const uint16_t *Wb, int64_t C, int D, const GrParams &p, const GrWs &w, hipStream_t st) {
+    const int ratio = gr_sym_ratio(p.kprime);
+    const int64_t n_sample = C / ratio;
+    const int nsb = (int)ks_ceil_div(C, GR_SYM_SB);
+    const int64_t Cpad = (int64_t)nsb * GR_SYM_SB + 96;
+    hipLaunchKernelGGL(gr_sym_sample_kernel, dim3((unsigned)ks_ceil_div(n_sample, GR_NT / 64)), dim3(GR_NT), 0, st, Wb, C, D, ratio,
+                       n_sample, w.Ws);
+    // the sample is searched with the kernel of the plain pass: k' + 1 kept, no row is "the row itself" (the sample
+    // may hold it: that is what the one extra is for)
+    GrParams ps = p;
+    ps.kprime = p.kprime + 1;
+    ps.cap = 256;
+    const GrPair pr{Wb, C, w.Ws, n_sample, -((int64_t)1 << 40)};
+    gr_launch_recall(pr, D, ps, w.cand, w.cnt, w.thr, st);
+    hipLaunchKernelGGL(gr_sym_prep_kernel, dim3((unsigned)ks_ceil_div(Cpad, GR_NT)), dim3(GR_NT), 0, st, w.thr, C, Cpad, w.thf,
+                       w.tbits, w.pm, w.logcnt, nsb);
+    const unsigned grid = gr_sym_grid(C);
+    const int stride = gr_sym_chunks_stride(C);
+    hipLaunchKernelGGL(gr_sym_plan_kernel, dim3(grid), dim3(GR_NT), 0, st, (int)C, gr_sym_group_sbs(C), w.plan, w.chunks, stride);
+    if (D == 512)
+        hipLaunchKernelGGL((gr_recall_sym_kernel<8>), dim3(grid), dim3(512), 0, st, Wb, (int)C, D, w.plan, w.chunks, stride, w.thf, w.pm,
+                           w.cand, w.cnt_res, w.log, w.logcnt);
+    else if (D == 256)
+        hipLaunchKernelGGL((gr_recall_sym_kernel<4>), dim3(grid), dim3(512), 0, st, Wb, (int)C, D, w.plan, w.chunks, stride, w.thf, w.pm,
+                           w.cand, w.cnt_res, w.log, w.logcnt);
+    else
+        hipLaunchKernelGGL((gr_recall_sym_kernel<2>), dim3(grid), dim3(512), 0, st, Wb, (int)C, D, w.plan, w.chunks, stride, w.thf, w.pm,
+                           w.cand, w.cnt_res, w.log, w.logcnt);
+    hipLaunchKernelGGL(gr_sym_scatter_kernel, dim3((unsigned)nsb), dim3(1024), 0, st, w.log, w.logcnt, (int)C, w.tbits, w.cand,
+                       w.cnt_str);
+    hipLaunchKernelGGL(gr_sym_select_kernel, dim3((unsigned)ks_ceil_div(C, GR_NT / 64)), dim3(GR_NT), 0, st, C, p.kprime, w.cand,
+                       w.cnt_res, w.cnt_str, w.tbits, w.cnt, w.thr);
+}
+
 // error bound of the recall pass relative to |w_i||w_j|: fp32 accumulation of D exact bf16 products
 // (2^-23 per addition allows for truncating adders), plus the bf16 rounding of both rows (2 * 2^-9,
 // rounded up to 2^-7.9) when the input is fp32; a small slack covers the fp32 norms themselves
@@ -741,11 +1298,17 @@ extern "C" int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K
                            (uint16_t *)nullptr, w.norms, w.maxnorm);
         Wb = (const uint16_t *)W;
     }
-    const GrPair pr{Wb, C, Wb, C, 0};
-    gr_launch_recall(pr, D, p, w.cand, w.cnt, w.thr, st);
+    GrParams pe = p; // what the exact stage reads
+    if (gr_use_sym(C, D, p)) {
+        gr_launch_recall_sym(Wb, C, D, p, w, st);
+        pe.cap = GR_SYM_CAP;
+    } else {
+        const GrPair pr{Wb, C, Wb, C, 0};
+        gr_launch_recall(pr, D, p, w.cand, w.cnt, w.thr, st);
+    }
     const float gamma = gr_gamma(D, dtype);
-    if (dtype == KS_DTYPE_FP32) gr_launch_exact<float>((const float *)W, C, D, K, p, w, gamma, graph, sims, st);
-    else gr_launch_exact<uint16_t>((const uint16_t *)W, C, D, K, p, w, gamma, graph, sims, st);
+    if (dtype == KS_DTYPE_FP32) gr_launch_exact<float>((const float *)W, C, D, K, pe, w, gamma, graph, sims, st);
+    else gr_launch_exact<uint16_t>((const uint16_t *)W, C, D, K, pe, w, gamma, graph, sims, st);
     KS_LAUNCH_CHECK();
     return KS_OK;
 }

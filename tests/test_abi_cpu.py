@@ -55,7 +55,7 @@ def test_workspace_sizes(ks):
     assert a < 1024 * 32768 * 4
     assert ks.knn_softmax_workspace(100, 33, 4, 2, 8) == 0          # D % 32 != 0
     assert ks.knn_graph_build_workspace(1000, 128, 200, 0) == 0     # K too large
-    assert ks.knn_graph_build_workspace(390625, 512, 32, 0) < 4 << 30
+    assert ks.knn_graph_build_workspace(390625, 512, 32, 0) < 10 << 30   # 2,048 candidate slots per row, and the logs
     assert ks.apply_weight_grad_workspace(1000, 128, 100, 1) <= 256
     assert ks.apply_weight_grad_workspace(1000, 128, 100, 0) >= 128 * 8
 
@@ -226,6 +226,82 @@ def test_topk_plan_layout(ks):
     assert nodes2[:7, 1].tolist() == [15] * 6 + [10] and nodes2[7:14, 1].tolist() == [1429] * 6 + [1426]
     _, p3 = _plan(ks, [5], [5], chunks=64)
     assert p3[32 + 2] == 5 and p3[2] == 6 and p3[6] == 2
+
+
+@pytest.mark.parametrize("C,D,K,dtype", [(6400, 128, 32, 0), (7000, 128, 8, 0), (8330, 256, 16, 1), (6913, 512, 32, 0),
+                                         (25_000, 128, 32, 0), (50_011, 128, 16, 0), (101_000, 256, 32, 0),
+                                         (390_625, 512, 32, 0), (393_216, 512, 32, 0), (399_000, 512, 32, 1)])
+def test_graph_plan_pairs_every_two_blocks_exactly_once(ks, C, D, K, dtype):
+    """The division of work of the graph build that computes every similarity once: every block of 256 rows is some
+    workgroup's, and for every two different blocks exactly one of the two workgroups streams the other's rows with both
+    sides of the similarity in use; a workgroup's own block is streamed by itself (for its own rows); ranges lie on
+    96-row chunk boundaries; the load is even."""
+    import numpy as np
+    n_wg, _ = ks.knn_graph_build_plan(C, D, K, dtype)
+    assert n_wg > 0
+    NB = -(-C // 256)
+    taken = np.zeros((NB, NB), dtype=np.uint8) if NB <= 512 else None
+    pairs = np.zeros(NB, dtype=np.int64)     # blocks paired by each resident block
+    seen = np.zeros(NB, dtype=np.int64)
+    rows_streamed = []
+    for wg in range(n_wg):
+        _, p = ks.knn_graph_build_plan(C, D, K, dtype, wg)
+        b = p[0]
+        if b < 0:
+            assert all(p[2 + 2 * q] <= p[1 + 2 * q] for q in range(5))
+            continue
+        seen[b] += 1
+        own_sb = b * 256 // 768
+        assert p[1] == own_sb * 768 and p[2] == min(p[1] + 768, C)         # range 0: its own super-block
+        n_own = -(-(p[2] - p[1]) // 256)
+        assert p[11] < (1 << n_own) and not (p[11] >> (b - own_sb * 3)) & 1
+        mine = [own_sb * 3 + k for k in range(n_own) if (p[11] >> k) & 1]
+        total = p[2] - p[1]
+        for q in range(1, 5):
+            first, end = p[1 + 2 * q], p[2 + 2 * q]
+            if end <= first:
+                continue
+            assert first % 768 == 0 and (end % 768 == 0 or end == C) and end <= C
+            assert not first <= b * 256 < end                                # never its own rows again
+            mine += list(range(first // 256, -(-end // 256)))
+            total += end - first
+        rows_streamed.append(total)
+        assert len(set(mine)) == len(mine)
+        pairs[b] = len(mine)
+        if taken is not None:
+            taken[b, mine] += 1
+    assert (seen == 1).all()
+    assert pairs.sum() == NB * (NB - 1) // 2                                  # as many pairs as there are
+    if taken is not None:
+        both = taken + taken.T
+        assert (both[~np.eye(NB, dtype=bool)] == 1).all() and (np.diag(taken) == 0).all()
+    else:   # large problems: the counts per block (every block is paired NB - 1 times in all) by sampling the relation
+        rng = np.random.default_rng(0)
+        sets = {}
+        for wg in range(n_wg):
+            _, p = ks.knn_graph_build_plan(C, D, K, dtype, wg)
+            if p[0] >= 0:
+                sets[p[0]] = p
+        def takes(a, b):
+            p = sets[a]
+            own_sb = a * 256 // 768
+            if b // 3 == own_sb:
+                return bool((p[11] >> (b - own_sb * 3)) & 1)
+            return any(p[1 + 2 * q] <= b * 256 < p[2 + 2 * q] for q in range(1, 5))
+        for a, b in rng.integers(0, NB, (20000, 2)):
+            if a != b:
+                assert takes(a, b) != takes(b, a)
+    # nobody streams much more than half of the rows
+    assert max(rows_streamed) <= C / 2 + 12 * 768 and max(rows_streamed) - min(rows_streamed) <= max(0.06 * C, 4 * 768)
+
+
+def test_graph_plan_is_absent_for_small_problems(ks):
+    for C, D, K, dtype in [(6000, 128, 32, 0), (390_625, 192, 32, 0), (390_625, 512, 64, 0), (6000, 256, 16, 1)]:
+        assert ks.knn_graph_build_plan(C, D, K, dtype)[0] == 0
+    with pytest.raises(ks.KsError):
+        ks.knn_graph_build_plan(1, 128, 32, 0)
+    with pytest.raises(ks.KsError):
+        ks.knn_graph_build_plan(390_625, 512, 32, 0, workgroup=10_000_000)
 
 
 def test_topk_argument_errors(ks):

@@ -436,6 +436,29 @@ def test_graph_sweep_kernel_buffer_sizes_and_ties(ks, orc, C, D, K, bf16, kind):
     _check_graph(ks, orc, W, K, bf16, rows=rows, tag=f"sweep kernel {kind}")
 
 
+@pytest.mark.parametrize("C,D,K,bf16,kind", [(6400, 128, 32, True, "unit"), (7000, 128, 8, True, "unit"),
+                                             (8330, 256, 16, False, "unit"), (6913, 512, 32, True, "clustered"),
+                                             (25_000, 128, 32, True, "unit"), (50_011, 128, 16, True, "clustered"),
+                                             (6400, 128, 32, True, "integers")])
+def test_graph_every_similarity_computed_once(ks, orc, C, D, K, bf16, kind):
+    """The recall pass that uses the symmetry of the similarities (D = 128, 256, 512, k' <= 64, a sample of at least
+    8 (k' + 1) rows): block, super-block and group counts that are odd, even and ragged (a last super-block of one, two
+    and three blocks; groups of one, two and four super-blocks), both values of k', clustered rows, and rows with so many
+    equal similarities that the fixed-size buffers overflow and the rows go to the exhaustive pass."""
+    if kind == "unit":
+        W = synth.unit_rows(11, synth.TID_W, C, D, bf16=bf16)
+    elif kind == "integers":
+        W = np.random.default_rng(C + D).integers(-1, 2, (C, D)).astype(np.float32)
+        W[C // 2] = W[3]
+        W[C - 1] = W[3]
+    else:
+        W = synth.clustered_rows(11, C, D, n_centres=97, bf16=bf16)
+    n_rows = 400 if C <= 10_000 else 160
+    rows = np.sort(synth.class_permutation(11, C)[:n_rows]).astype(np.int32)
+    rows = np.unique(np.concatenate([rows, [0, 3, 255, 256, 767, 768, C // 2, C - 257, C - 2, C - 1]])).astype(np.int32)
+    _check_graph(ks, orc, W, K, bf16, rows=rows, tag=f"symmetric recall {kind}")
+
+
 def test_graph_is_deterministic(ks, orc):
     W = synth.unit_rows(6, synth.TID_W, 6000, 128, bf16=True)
     g1, s1 = ks.knn_graph_build(dev(W, torch.bfloat16), 16, want_sims=True)
