@@ -132,8 +132,12 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
     __syncthreads();                    // (also publishes the gather list)
     const bool loader = wave < CFG::LW;
     const uint16_t *ptr[NI]; // row pointers (k = 0, swizzled chunk) of the chunk being issued (loading wavefronts)
+    // (table entries are read one chunk before they are needed, on the issue side and on the compute side: the wait for
+    // a scalar load at the point of use would sit in the middle of the stream)
+    int ahead_first = ctab && n_chunks > 0 ? ctab[0].x : 0; // first row of the next chunk whose loads will be set up
     auto chunk_ptrs = [&](int c) __attribute__((always_inline)) {
-        const int first = chunk_first(c);
+        const int first = ctab ? ahead_first : chunk_first(c);
+        if (ctab) ahead_first = ctab[c + 1 < n_chunks ? c + 1 : c].x;
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int row = (j * CFG::LW + wave) * 8 + (lane >> 3);
@@ -176,8 +180,11 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
     // ---- sweep -------------------------------------------------------------------------------------------
     const int r31 = lane & 31, khalf = lane >> 5, swz = (lane >> 1) & 7;
     int stage = 0, done = 0;
+    int2 ct_next = ctab && n_chunks > 0 ? ctab[0] : make_int2(0, 0);
     for (int c = 0; c < n_chunks; ++c) {
-        const int rows_here = chunk_rows(c);
+        const int2 ct = ct_next;
+        if (ctab) ct_next = ctab[c + 1 < n_chunks ? c + 1 : c];
+        const int rows_here = ctab ? ct.y : chunk_rows(c);
         f32x16_t acc[FM];
         // All k-tiles of one chunk.  FULL: the chunk has all CH rows -- the common case, compiled without a branch
         // between the MFMAs (a branch ends the basic block, and the wait for the fragment reads that the compiler
@@ -251,7 +258,7 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
         // a chunk of a single stage has no barrier between post() of the previous chunk (which reads what epi() left
         // in LDS) and this chunk's epi(): a wavefront that runs ahead must not overwrite what another still reads
         if (KT / CFG::KSUB < 2 && KsSoeHasPost<Post>::value) ks_barrier_nofence();
-        epi(chunk_first(c), rows_here, acc);
+        epi(ctab ? ct.x : chunk_first(c), rows_here, acc);
     }
     ks_barrier_nofence();
     if (n_chunks > 0 && KsSoeHasPost<Post>::value) post(chunk_first(n_chunks - 1), chunk_rows(n_chunks - 1));

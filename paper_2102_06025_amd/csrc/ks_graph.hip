@@ -463,11 +463,13 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
 // workgroup, which halves the MFMA work of the pass.  What it takes:
 //
 //  * thresholds known in advance.  A row that is streamed past hundreds of workgroups cannot keep a running
-//    threshold, so a first pass (the kernel above, on every `ratio`-th row of W only) finds for each row the
-//    (k'+1)-th largest similarity to that sample.  At least k' other rows are at or above it, so it is a valid lower
-//    bound of the row's k'-th best, and the number of rows above it in all of W is about (k'+1) * ratio whatever the
-//    distribution of the rows (it is an order statistic of a uniform sample).  Both sides test against these fixed
-//    thresholds and the buffers are sized for that count; nothing is cut back during the sweep.
+//    threshold, so a first pass (the kernel above, on every 32nd row of W only) finds for each row the 12th largest
+//    similarity to that sample.  The number of rows of all of W at or above it is 32 times a Gamma(12) variable
+//    whatever the distribution of the rows (it is an order statistic of a uniform sample): 384 on average, beyond
+//    1,100 or below k' (then 12 of the row's k' best would have to be in the sample) for less than one row in a
+//    million.  Both sides test against these fixed thresholds and the buffers are sized for those counts; nothing is
+//    cut back during the sweep.  A row that does end up with too many or too few candidates is caught by the
+//    re-rank's certificate like any other uncertain row.
 //  * who takes which pair.  Rows are cut into blocks of 256 (a workgroup's resident rows), super-blocks of 768 rows
 //    (three blocks = eight 96-row chunks, so that every streamed range starts on a chunk boundary) and groups of up
 //    to 10 super-blocks.  On each level the members form a ring and a member takes the following half of the ring
@@ -489,8 +491,10 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
 #define GR_SYM_Q 512             /* slots of each resident-side half */
 #define GR_SYM_SCAP 1024         /* slots of the stream side */
 #define GR_SYM_SB 768            /* rows of a super-block */
-#define GR_SYM_LOGCAP (768 * 640) /* records per super-block log (expected: 768 * (k'+1) * ratio / 2, about 300,000) */
+#define GR_SYM_LOGCAP (768 * 384) /* records per super-block log (expected: 768 rows * 192 stream-side hits, plus a tenth) */
 #define GR_SYM_STAGE 192         /* records a wavefront collects in LDS between two appends to a log */
+#define GR_SYM_RATIO 32          /* rows of W per sampled row */
+#define GR_SYM_RANK 12           /* the threshold of a row: its GR_SYM_RANK-th largest similarity to the sample */
 #define GR_SYM_MAX_GROUP 10      /* super-blocks per group at most: 30 workgroups, about the compute units of an XCD */
 
 // rows of W sampled by the first pass: one of every `ratio` consecutive rows, at a position that varies from one run
@@ -520,7 +524,7 @@ gr_sym_sample_kernel(const uint16_t *__restrict__ W, int64_t C, int D, int ratio
     for (int q = threadIdx.x & 63; q < D / 8; q += 64) dst[q] = src[q];
 }
 
-// thr_sample[i]: value bits of the (k'+1)-th largest similarity of row i to the sample (0: the sample had fewer rows).
+// thr_sample[i]: value bits of the GR_SYM_RANK-th largest similarity of row i to the sample (0: the sample had fewer rows).
 // Row i takes every similarity at or above it: thf[i] is the next float below, and tbits[i] its key, so that "v > thf"
 // is the test and "key value <= tbits" holds for everything that fails it.  pm: minima over the row pairs (j, j + 4)
 // that share an accumulator register.  Rows at and beyond C never pass.  Also clears the counters of the logs.
@@ -643,9 +647,9 @@ __device__ __forceinline__ float gr_sym_pick16(const f32x16_t &a, int r) {
     return v;
 }
 
-// a stream-side hit: similarity v of streamed row j (its place in its super-block is kept) with resident row `other`
-__device__ __forceinline__ uint2 gr_sym_record(int j, int other, float v) {
-    return make_uint2(gr_orderable(v), ((uint32_t)other << 10) | (uint32_t)(j % GR_SYM_SB));
+// a stream-side hit: similarity v of a streamed row (given by its place in its super-block) with resident row `other`
+__device__ __forceinline__ uint2 gr_sym_record(int j_in_sb, int other, float v) {
+    return make_uint2(gr_orderable(v), ((uint32_t)other << 10) | (uint32_t)j_in_sb);
 }
 
 template <int KT>
@@ -689,7 +693,7 @@ gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t
     auto push = [&](uint64_t m, bool hit, int j, float v) __attribute__((always_inline)) {
         const int n = __popcll(m);
         if (staged + n > GR_SYM_STAGE) flush();
-        if (hit) my_stage()[staged + __popcll(m & ((1ull << lane) - 1ull))] = gr_sym_record(j, row0 + ks_soe_col(), v);
+        if (hit) my_stage()[staged + __popcll(m & ((1ull << lane) - 1ull))] = gr_sym_record(j - cur_sb * SB, row0 + ks_soe_col(), v);
         staged = __builtin_amdgcn_readfirstlane(staged + n);
     };
     auto append_res = [&](int j, float v) __attribute__((always_inline)) {
@@ -706,7 +710,6 @@ gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t
             const bool real_row = row0 + ks_soe_col() < C;
 #pragma unroll
             for (int fm = 0; fm < CFG::FM; ++fm) {
-                const float *pmc = pm + ((c0 + fm * 32) >> 1); // 16 pair minima: rows 8 q + e and 8 q + 4 + e at 4 q + e
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const float a0 = acc[fm][4 * q], a1 = acc[fm][4 * q + 1], a2 = acc[fm][4 * q + 2], a3 = acc[fm][4 * q + 3];
@@ -718,10 +721,9 @@ gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t
                         }
                     }
                 }
+                const float *pmc = pm + ((c0 + fm * 32) >> 1); // 16 pair minima: rows 8 q + e and 8 q + 4 + e at 4 q + e
                 // stream side: the two halves of the wavefront hold rows j and j + 4, the test is against the smaller of
                 // their two thresholds (the exact one is applied when the records are sorted into the rows' buffers).
-                // The hits of the 32 rows are counted first, so that room for them is made once; the code that runs
-                // for every chunk has to stay small (the instruction cache holds 64 KB).
                 // Every instruction here runs once per chunk and fragment, so there are few: a lane's hits become a bit
                 // mask with a compare and an add-with-carry per element (bit 15 - r for element r); nearly always no lane
                 // has more than one hit, and then a lane picks its element with a binary tree of selects and the slots
@@ -752,7 +754,7 @@ gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t
                             const int r = 15 - __builtin_ctz(hm);
                             const float v = gr_sym_pick16(acc[fm], r);
                             const int lr = fm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                            my_stage()[staged + __popcll(any & ((1ull << lane) - 1ull))] = gr_sym_record(c0 + lr, row0 + ks_soe_col(), v);
+                            my_stage()[staged + __popcll(any & ((1ull << lane) - 1ull))] = gr_sym_record(c0 - sb * SB + lr, row0 + ks_soe_col(), v);
                         }
                         staged = __builtin_amdgcn_readfirstlane(staged + n);
                     } else { // a lane with several hits: row by row
@@ -821,15 +823,23 @@ gr_sym_scatter_kernel(const uint2 *__restrict__ log, const int32_t *__restrict__
     __syncthreads();
     const int n_raw = logcnt[sb], n = n_raw < GR_SYM_LOGCAP ? n_raw : GR_SYM_LOGCAP;
     const uint2 *src = log + (int64_t)sb * GR_SYM_LOGCAP;
-    for (int q = threadIdx.x; q < n; q += 1024) {
-        const uint2 rec = src[q];
-        const int jl = (int)(rec.y & 1023u); // (checked all the same: it becomes an address)
-        const uint32_t other = rec.y >> 10;
-        if (jl >= GR_SYM_SB || row0 + jl >= C || other >= (uint32_t)C) continue;
-        if (rec.x <= s_tb[jl]) continue;  // passed its neighbour's threshold in the sweep's test, not its own
-        const int slot = atomicAdd(&s_cnt[jl], 1);
-        if (slot < GR_SYM_SCAP)
-            cand[(int64_t)(row0 + jl) * GR_SYM_CAP + 2 * GR_SYM_Q + slot] = ((uint64_t)rec.x << 32) | (uint32_t)(0xFFFFFFFFu - other);
+    for (int q0 = 0; q0 < n; q0 += 4 * 1024) { // four records per thread in flight
+        uint2 rec[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int q = q0 + u * 1024 + (int)threadIdx.x;
+            rec[u] = q < n ? src[q] : make_uint2(0u, 0xFFFFFFFFu); // (place 1023 of a super-block: dropped below)
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int jl = (int)(rec[u].y & 1023u); // (checked all the same: it becomes an address)
+            const uint32_t other = rec[u].y >> 10;
+            if (jl >= GR_SYM_SB || row0 + jl >= C || other >= (uint32_t)C) continue;
+            if (rec[u].x <= s_tb[jl]) continue;  // passed its neighbour's threshold in the sweep's test, not its own
+            const int slot = atomicAdd(&s_cnt[jl], 1);
+            if (slot < GR_SYM_SCAP)
+                cand[(int64_t)(row0 + jl) * GR_SYM_CAP + 2 * GR_SYM_Q + slot] = ((uint64_t)rec[u].x << 32) | (uint32_t)(0xFFFFFFFFu - other);
+        }
     }
     __syncthreads();
     for (int r = threadIdx.x; r < GR_SYM_SB; r += 1024)
@@ -1102,8 +1112,6 @@ struct GrWs {
     uint2 *log;
 };
 
-// The pass that computes every similarity once needs a sample large enough for its thresholds to be tight (eight
-// times k'+1 rows) and buffers whose size grows with k'.
 static unsigned gr_sym_grid(int64_t C) { // workgroups of the sweep: whole groups, dealt to the eight XCDs
     const int nsb = (int)ks_ceil_div(C, GR_SYM_SB), GS = gr_sym_group_sbs(C), NG = (nsb + GS - 1) / GS;
     return (unsigned)((NG + 7) / 8) * (unsigned)(GS * 3) * 8u;
@@ -1112,10 +1120,10 @@ static int gr_sym_chunks_stride(int64_t C) { // chunks a workgroup streams at mo
     const int64_t nsb = ks_ceil_div(C, GR_SYM_SB), GS = gr_sym_group_sbs(C), NG = ks_ceil_div(nsb, GS);
     return (int)(((NG / 2) * GS + GS / 2 + 2) * (GR_SYM_SB / 96));
 }
-static int gr_sym_ratio(int kprime) { return kprime <= 48 ? 16 : 12; } // rows of W per sampled row: (k'+1) * ratio = 784
+// The pass that computes every similarity once pays off for problems of more than a few thousand rows; its buffers
+// are sized for k' <= 64 and a row id has 22 bits in the stream side's records.
 static bool gr_use_sym(int64_t C, int D, const GrParams &p) {
-    return (D == 128 || D == 256 || D == 512) && p.kprime <= 64 && C / gr_sym_ratio(p.kprime) >= 8 * (p.kprime + 1) &&
-           C <= ((int64_t)1 << 22); // (a row id has 22 bits in the stream side's records)
+    return (D == 128 || D == 256 || D == 512) && p.kprime <= 64 && C >= 6144 && C <= ((int64_t)1 << 22);
 }
 
 static GrWs gr_carve(void *ws, int64_t C, int D, int K, int dtype, size_t *total) {
@@ -1136,7 +1144,7 @@ static GrWs gr_carve(void *ws, int64_t C, int D, int K, int dtype, size_t *total
     w.Ws = nullptr; w.thf = w.pm = nullptr; w.tbits = nullptr; w.cnt_res = w.cnt_str = w.logcnt = w.plan = nullptr; w.chunks = nullptr; w.log = nullptr;
     if (sym) {
         const int64_t nsb = ks_ceil_div(C, GR_SYM_SB), Cpad = nsb * GR_SYM_SB + 96;
-        w.Ws = ar.take<uint16_t>((size_t)(C / gr_sym_ratio(pd.kprime)) * D);
+        w.Ws = ar.take<uint16_t>((size_t)(C / GR_SYM_RATIO) * D);
         w.thf = ar.take<float>((size_t)Cpad);
         w.pm = ar.take<float>((size_t)Cpad / 2);
         w.tbits = ar.take<uint32_t>((size_t)C);
@@ -1232,16 +1240,16 @@ static void gr_launch_recall(const GrPair &pr, int D, const GrParams &p, uint64_
 // W searched in W with every similarity computed once: thresholds from a sample, the sweep, the stream side's records
 // to their rows, the cut to k'
 static void gr_launch_recall_sym(const uint16_t *Wb, int64_t C, int D, const GrParams &p, const GrWs &w, hipStream_t st) {
-    const int ratio = gr_sym_ratio(p.kprime);
+    const int ratio = GR_SYM_RATIO;
     const int64_t n_sample = C / ratio;
     const int nsb = (int)ks_ceil_div(C, GR_SYM_SB);
     const int64_t Cpad = (int64_t)nsb * GR_SYM_SB + 96;
     hipLaunchKernelGGL(gr_sym_sample_kernel, dim3((unsigned)ks_ceil_div(n_sample, GR_NT / 64)), dim3(GR_NT), 0, st, Wb, C, D, ratio,
                        n_sample, w.Ws);
-    // the sample is searched with the kernel of the plain pass: k' + 1 kept, no row is "the row itself" (the sample
-    // may hold it: that is what the one extra is for)
+    // the sample is searched with the kernel of the plain pass: GR_SYM_RANK kept, no row is "the row itself" (the
+    // sample may hold it; it counts like any other row)
     GrParams ps = p;
-    ps.kprime = p.kprime + 1;
+    ps.kprime = GR_SYM_RANK;
     ps.cap = 256;
     const GrPair pr{Wb, C, w.Ws, n_sample, -((int64_t)1 << 40)};
     gr_launch_recall(pr, D, ps, w.cand, w.cnt, w.thr, st);
