@@ -372,7 +372,7 @@ __device__ __forceinline__ uint32_t gr_compact_halves(uint64_t *__restrict__ can
 template <int KT, int E>
 __global__ void __launch_bounds__(512)
 gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, int32_t *__restrict__ cnt_out,
-                      uint32_t *__restrict__ thr_out) {
+                      uint32_t *thr_out, const uint32_t *thr_init) {
     const int64_t C = pr.Cr;
     typedef KsSoe<KT, 96, GR_SOE_STAGES, 2> CFG;
     constexpr int CAP = E * 64, HALF = CAP / 2;
@@ -395,6 +395,10 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
     int my_cnt = 0;
     uint32_t th = 0u; // value bits of the row's threshold; 0 = nothing dropped yet: everything passes
     float thf = gi >= Ci ? INFINITY : -INFINITY; // rows beyond C never pass
+    if (thr_init && gi < Ci) { // the caller knows that nothing at or below this value is wanted (may be thr_out itself)
+        th = thr_init[gi];
+        if (th != 0u) thf = gr_unorder(th);
+    }
     auto cut_back = [&](bool final_layout) {
         ks_wait_vmcnt<0>(); // the appended candidates have left this wavefront before it reads them back
         asm volatile("" ::: "memory");
@@ -1207,17 +1211,21 @@ static void gr_launch_exact(const IN *W, int64_t C, int D, int K, const GrParams
                        w.scratch, graph, sims);
 }
 
+// thr_init (optional, honoured by the sweep kernel only, may be `thr`): per row the value bits of a similarity at or below
+// which no candidate is wanted
 static void gr_launch_recall(const GrPair &pr, int D, const GrParams &p, uint64_t *cand, int32_t *cnt, uint32_t *thr,
-                             hipStream_t st) {
+                             hipStream_t st, const uint32_t *thr_init = nullptr) {
     const int64_t C = pr.Cr;
     if (D == 128 || D == 256 || D == 512) {
         const unsigned nb = (unsigned)ks_ceil_div(C, 256);
 #define GR_SOE_LAUNCH(KT)                                                                                                   \
     do {                                                                                                                    \
         if (p.cap == 256)                                                                                                   \
-            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 4>), dim3(nb), dim3(512), 0, st, pr, D, p.kprime, cand, cnt, thr);  \
+            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 4>), dim3(nb), dim3(512), 0, st, pr, D, p.kprime, cand, cnt, thr,  \
+                               thr_init);                                                                                   \
         else                                                                                                                \
-            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 8>), dim3(nb), dim3(512), 0, st, pr, D, p.kprime, cand, cnt, thr);  \
+            hipLaunchKernelGGL((gr_recall_soe_kernel<KT, 8>), dim3(nb), dim3(512), 0, st, pr, D, p.kprime, cand, cnt, thr,  \
+                               thr_init);                                                                                   \
     } while (0)
         if (D == 512) GR_SOE_LAUNCH(8);
         else if (D == 256) GR_SOE_LAUNCH(4);
@@ -1424,6 +1432,27 @@ gr_merge_kernel(const IN *__restrict__ Wl, int64_t C_loc, const IN *__restrict__
     if (__ballot(!certified) != 0ull && lane == 0) fb_rows[atomicAdd(fb_count, 1)] = (int32_t)i;
 }
 
+// A row whose list is full needs no visiting row whose similarity cannot reach the list's last entry: the recall pass
+// starts from that entry's similarity, lowered by more than twice the recall's error bound (a visiting row that ties
+// the entry exactly is still recalled, and the certificate of the merge -- new K-th similarity above threshold + bound
+// -- holds when nothing new comes in).  0: no threshold (the list has empty slots).
+__global__ void __launch_bounds__(GR_NT)
+gr_hop_threshold_kernel(int64_t C_loc, int K, const int32_t *__restrict__ graph, const double *__restrict__ sims,
+                        const float *__restrict__ norms, const uint32_t *__restrict__ maxnorm_bits, float gamma,
+                        uint32_t *__restrict__ thr) {
+    const int64_t i = (int64_t)blockIdx.x * GR_NT + threadIdx.x;
+    if (i >= C_loc) return;
+    uint32_t t = 0u;
+    if (graph[i * K + K - 1] >= 0) {
+        const double eps = (double)gamma * (double)norms[i] * (double)__uint_as_float(*maxnorm_bits);
+        const double want = sims[i * K + K - 1] - 2.5 * eps;
+        float f = (float)want;
+        if ((double)f > want) f = nextafterf(f, -INFINITY); // rounded down
+        if (f == f && f > -INFINITY) t = gr_orderable(f);
+    }
+    thr[i] = t;
+}
+
 // rows on the list: every visiting row in canonical fp64 arithmetic, merged with the row's list
 template <typename IN>
 __global__ void __launch_bounds__(GR_NT)
@@ -1601,8 +1630,10 @@ extern "C" int knn_graph_update(const void *W_local, const void *W_visit, int dt
         Sv = (const uint16_t *)W_visit;
     }
     const GrPair pr{Rl, C_loc, Sv, C_vis, local_offset - visit_offset};
-    gr_launch_recall(pr, D, p, w.cand, w.cnt, w.thr, st);
     const float gamma = gr_gamma(D, dtype);
+    hipLaunchKernelGGL(gr_hop_threshold_kernel, dim3((unsigned)ks_ceil_div(C_loc, GR_NT)), dim3(GR_NT), 0, st, C_loc, K, graph, sims,
+                       w.norms_l, w.maxnorm_v, gamma, w.thr);
+    gr_launch_recall(pr, D, p, w.cand, w.cnt, w.thr, st, w.thr);
     if (dtype == KS_DTYPE_FP32)
         gr_up_exact<float>((const float *)W_local, C_loc, (const float *)W_visit, C_vis, D, K, p, w, gamma, local_offset,
                            visit_offset, graph, sims, st);
