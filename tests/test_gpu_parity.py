@@ -459,8 +459,9 @@ def test_graph_every_similarity_computed_once(ks, orc, C, D, K, bf16, kind):
     _check_graph(ks, orc, W, K, bf16, rows=rows, tag=f"symmetric recall {kind}")
 
 
-def test_graph_is_deterministic(ks, orc):
-    W = synth.unit_rows(6, synth.TID_W, 6000, 128, bf16=True)
+@pytest.mark.parametrize("C", [6000, 9000])   # the plain recall pass; the one that computes every similarity once
+def test_graph_is_deterministic(ks, orc, C):
+    W = synth.unit_rows(6, synth.TID_W, C, 128, bf16=True)
     g1, s1 = ks.knn_graph_build(dev(W, torch.bfloat16), 16, want_sims=True)
     g2, s2 = ks.knn_graph_build(dev(W, torch.bfloat16), 16, want_sims=True)
     torch.cuda.synchronize()
