@@ -1247,7 +1247,7 @@ static void gr_launch_recall(const GrPair &pr, int D, const GrParams &p, uint64_
 
 // W searched in W with every similarity computed once: thresholds from a sample, the sweep, the stream side's records
 // to their rows, the cut to k'
-static void gr_launch_recall_sym(const uint16_t *Wb, int64_t C, int D, const GrParams &p, const GrWs &w, hipStream_t st) {
+static void gr_launch_recall_sym(const uint16_t *Wb, int64_t C, int D, int K, const GrParams &p, const GrWs &w, hipStream_t st) {
     const int ratio = GR_SYM_RATIO;
     const int64_t n_sample = C / ratio;
     const int nsb = (int)ks_ceil_div(C, GR_SYM_SB);
@@ -1277,7 +1277,11 @@ static void gr_launch_recall_sym(const uint16_t *Wb, int64_t C, int D, const GrP
                            w.cand, w.cnt_res, w.log, w.logcnt);
     hipLaunchKernelGGL(gr_sym_scatter_kernel, dim3((unsigned)nsb), dim3(1024), 0, st, w.log, w.logcnt, (int)C, w.tbits, w.cand,
                        w.cnt_str);
-    hipLaunchKernelGGL(gr_sym_select_kernel, dim3((unsigned)ks_ceil_div(C, GR_NT / 64)), dim3(GR_NT), 0, st, C, p.kprime, w.cand,
+    // what the re-rank gets: the k' of the plain pass, where the number kept also sets the work of the sweep; here it
+    // only sets the re-rank's (k' candidate rows fetched per row), and with bf16 rows the certificate's margin is so
+    // small (D * 2^-23) that eight beyond K are plenty
+    const int kept = p.kprime == 48 && K + 8 < p.kprime ? K + 8 : p.kprime;
+    hipLaunchKernelGGL(gr_sym_select_kernel, dim3((unsigned)ks_ceil_div(C, GR_NT / 64)), dim3(GR_NT), 0, st, C, kept, w.cand,
                        w.cnt_res, w.cnt_str, w.tbits, w.cnt, w.thr);
 }
 
@@ -1316,7 +1320,7 @@ extern "C" int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K
     }
     GrParams pe = p; // what the exact stage reads
     if (gr_use_sym(C, D, p)) {
-        gr_launch_recall_sym(Wb, C, D, p, w, st);
+        gr_launch_recall_sym(Wb, C, D, K, p, w, st);
         pe.cap = GR_SYM_CAP;
     } else {
         const GrPair pr{Wb, C, Wb, C, 0};
