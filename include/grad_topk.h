@@ -42,11 +42,21 @@ extern "C" {
  * The paper's method has two steps (top-k of every chunk, then top-k of the M*k survivors).  Here one workgroup
  * performs one selection, and no selection gets more than 32,768 items: where M * k exceeds that, the survivors
  * are first reduced in groups of floor(32,768 / k) chunks, and so on -- a tree of exact selections with the
- * paper's two steps as its smallest case, one launch per level for the whole group of tensors.
+ * paper's two steps as its smallest case, one launch per level for the whole group of tensors ("plain tree").
+ * With chunks == 0, a tensor of several chunks whose k is small for its size goes a shorter way, in three steps
+ * whatever its size: (1) a threshold, the r-th largest magnitude of 4,096 evenly spaced elements, r >= 16 chosen so
+ * that about 4 k elements of the tensor are expected at or above it; (2) every chunk hands on its elements at or
+ * above the threshold (one pass, no selection: the chunks of the paper's first step hand on k elements each,
+ * whatever the rest of the tensor holds); (3) the final selection over what arrived.  The number that arrives is an
+ * order statistic's count (n / 4,096 times a Gamma(r) variable for any values), fewer than k for about one tensor in
+ * 100,000; it is checked in step (3), and if it is below k or beyond 32,768 (long runs of one magnitude), the
+ * workgroup of step (3) runs the tensor's plain tree itself.  The output is the same bits on every way.
  * Returns the number of int64 words of the plan (written only if plan != NULL and plan_capacity suffices), or
- * the negative of a ks_status for bad arguments.  Plan words a caller may read: [1] = T, [2] = selections
- * (workgroups) in all, [3] = survivors' buffer in 8-byte words, [4] = sum of k, [5] = elements in all,
- * [6] = levels (launches per call); per tensor t at [32 + 4 t]: n, k, chunks, levels.
+ * the negative of a ks_status for bad arguments.  Plan words a caller may read: [1] = T, [2] = steps launched
+ * (workgroups of 1,024 threads; a chunk of step (2) is four workgroups of 256), [3] = workspace in 8-byte words,
+ * [4] = sum of k, [5] = elements in all, [6] = levels (launches per call, plus one when [29] > 0), [7] = step records
+ * in all (the plain trees behind the shorter ways included), [29] = chunks that take step (2);
+ * per tensor t at [32 + 4 t]: n, k, chunks, steps.
  * ---------------------------------------------------------------------------------------------------- */
 int64_t grad_topk_plan(const int64_t *offsets, const int32_t *k, int T, int chunks, int64_t *plan, int64_t plan_capacity);
 
@@ -55,8 +65,9 @@ size_t grad_topk_workspace(const int64_t *plan_host);
 
 /* ------------------------------------------------------------------------------------------------------
  * grad_topk_select -- Section 3.3.2: the selection itself, one launch per level of the plan for the whole group
- * (first level: one workgroup per chunk of every tensor; last level of a tensor: one workgroup that writes its
- * output).
+ * (plain tree: first level one workgroup per chunk of a tensor, last level one workgroup that writes its output;
+ * the three steps described above: thresholds, then all chunks in a launch of their own, then the final steps,
+ * beside which the tensors of a single chunk run).
  *
  *   g          [offsets[T]]  the gradient tensors, fp32, back to back as planned (4-byte aligned is enough)
  *   plan_dev   the plan in device memory;  plan_host  HOST: the same words (launch geometry is read from it)

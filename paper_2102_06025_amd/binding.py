@@ -606,7 +606,8 @@ class GradTopkPlan:
         return [int(self.host[32 + 4 * t + 2]) for t in range(self.T)]
 
     def steps(self):
-        """Selection steps every tensor goes through (2 = the paper's chunks + final selection)."""
+        """Selection steps every tensor goes through (1 = a single chunk; 2 = the paper's chunks + final selection;
+        3 = threshold from a sample, filtered chunks, final selection, or a deeper tree of selections)."""
         return [int(self.host[32 + 4 * t + 3]) for t in range(self.T)]
 
 
@@ -629,7 +630,7 @@ def grad_topk_plan(offsets, k, chunks=0, device="cuda") -> GradTopkPlan:
 
 
 def grad_topk_select(g, plan: GradTopkPlan, out_idx=None, out_val=None, ws=None, stream=None):
-    """Top-k by magnitude of every tensor of the group (two launches).  Returns (idx int32 [sum k], val fp32 [sum k])."""
+    """Top-k by magnitude of every tensor of the group (one launch per level of the plan).  Returns (idx int32 [sum k], val fp32 [sum k])."""
     _need(g, torch.float32, "g")
     if out_idx is None:
         out_idx = torch.empty(plan.n_out, dtype=torch.int32, device=g.device)

@@ -24,6 +24,9 @@
 // a plan that cuts tensors so that no step has more than 32,768 items: a tensor of more than about 260,000
 // elements at k = 4,096 goes through more than the paper's two steps (a tree of selections instead of chunks +
 // one final selection), still without any approximation.
+// Tensors of several chunks whose k is small for their size take a shorter way (tk_threshold, tk_filter_kernel): a
+// threshold from a sample lets every chunk hand on only what can still matter, in one pass and without a selection of its
+// own; the plain tree of selections stays behind as what the final step falls back on when the sample misled.
 // Everything is integer work: the result is bit-exact and deterministic.
 #include <vector>
 #include "ks_common.h"
@@ -34,16 +37,25 @@
 #define TK_CAP 8192
 #define TK_LEAF 32768      /* largest chunk of a tensor */
 #define TK_NODE_CAP 32768  /* largest input of a later step */
-#define TK_MAX_LEVELS 12
+#define TK_MAX_LEVELS 10
 #define TK_MAGIC 0x6B706F74646172ll /* "gradtopk" cut to seven bytes */
-#define TK_HEADER (8 + 2 * TK_MAX_LEVELS)
+#define TK_HEADER 32        /* words before the tensor records: [0..7] see grad_topk.h, [8 + 2 l], [9 + 2 l] first node and nodes of level l,
+                               [28], [29] the sampled paths' filter steps (first node, count; they come first in level 1),
+                               [30], [31] their final steps (first in level 2) */
 #define TK_TENSOR 4        /* words per tensor record: n, k, chunks, steps */
-#define TK_NODE 8          /* words per step ("node") record */
+#define TK_NODE 12         /* words per step ("node") record */
+#define TK_SAMPLE 4096     /* elements of a tensor that its threshold is taken from (the sampled path, see tk_threshold) */
+#define TK_SAMPLE_RANK 16  /* the threshold is at least the TK_SAMPLE_RANK-th largest of the sample */
 
 // node record (int64 words)
-enum { TK_N_SRC = 0, TK_N_ITEMS, TK_N_K, TK_N_OUT, TK_N_FLAGS, TK_N_FIRST, TK_N_GBEGIN, TK_N_GN };
+enum { TK_N_SRC = 0, TK_N_ITEMS, TK_N_K, TK_N_OUT, TK_N_FLAGS, TK_N_FIRST, TK_N_GBEGIN, TK_N_GN, TK_N_AUX, TK_N_FB_FIRST, TK_N_FB_COUNT };
 #define TK_F_LEAF 1  /* reads gradients (src = element offset in g); otherwise items (src = offset in the workspace) */
 #define TK_F_FINAL 2 /* writes the tensor's output (out = offset in out_idx / out_val); otherwise items (workspace) */
+// The sampled path of a tensor of several chunks (three steps whatever its size):
+#define TK_F_THRESH 4   /* finds the tensor's threshold from a sample; aux = two workspace words: threshold, then count | overflow */
+#define TK_F_FILTER 8   /* a chunk: the items at or above the threshold go to the tensor's list (out), counted in aux + 1 */
+#define TK_F_COUNTED 16 /* final step over that list: its length is read from aux + 1; fb_first / fb_count = the steps of
+                           the tensor's plain tree (node indices), which this workgroup runs itself if the sample misled */
 
 struct TkShared {
     uint64_t sort[TK_CAP];
@@ -614,15 +626,140 @@ template <class List> __device__ __forceinline__ void tk_select(const List &list
     if (sorted) tk_order(k, sh);
 }
 
-// one step of the tree: one workgroup per node of the level
-__global__ void __launch_bounds__(TK_NT)
-tk_node_kernel(const float *__restrict__ g, const int64_t *__restrict__ plan, uint64_t *__restrict__ cand,
-               int32_t *__restrict__ out_idx, float *__restrict__ out_val, int first_node) {
-    __shared__ TkShared sh;
-    const int T = (int)plan[1];
-    const int64_t *rec = plan + TK_HEADER + (int64_t)T * TK_TENSOR + (int64_t)(first_node + blockIdx.x) * TK_NODE;
-    const int n = (int)rec[TK_N_ITEMS], k = (int)rec[TK_N_K];
+// ------------------------------------------------------------------------------------------------
+// The sampled path.  The paper's chunks hand on k items each, whatever the rest of the tensor looks like: 72 chunks of
+// the largest tensor pass 170,000 items for 2,359 places.  A threshold that is known to lie below the tensor's k-th
+// largest magnitude lets a chunk hand on only what can still matter, in ONE pass and without a selection of its own.
+// Such a threshold comes from a sample: the r-th largest of TK_SAMPLE evenly spaced elements, r chosen so that about
+// four times k elements of the tensor lie at or above it.  That count is n / TK_SAMPLE times a Gamma(r) variable
+// whatever the values are (an order statistic of a sample), r >= 16: fewer than k for one tensor in 100,000.  It is
+// not guaranteed, so it is checked: the final step sees how many items came, and if they are fewer than k, or more than
+// a step can take (long runs of one magnitude), its workgroup runs the tensor's plain tree of selections itself.  The
+// result is the same bits either way.
+// ------------------------------------------------------------------------------------------------
+__device__ void tk_threshold(const float *__restrict__ gt, uint32_t n, int r, uint64_t *aux, TkShared &sh) {
+    // The r-th largest of the sampled magnitudes, to 22 of their 31 bits (two histogram levels of 11 bits; the threshold is
+    // the lower edge of the bin it falls in, so a few more elements than r lie at or above it -- sorting the sample
+    // took five times as long as everything else in this step).
+    const int tid = threadIdx.x;
+    uint32_t key[TK_SAMPLE / TK_NT];
+#pragma unroll
+    for (int q = 0; q < TK_SAMPLE / TK_NT; ++q) {
+        const uint32_t idx = (uint32_t)(((uint64_t)(q * TK_NT + tid) * n) / TK_SAMPLE);
+        key[q] = __float_as_uint(gt[idx]) & 0x7FFFFFFFu;
+    }
+    for (int b = tid; b < TK_BINS; b += TK_NT) sh.hist[b] = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < TK_SAMPLE / TK_NT; ++q) atomicAdd(&sh.hist[key[q] >> 20], 1u);
+    __syncthreads();
+    uint32_t above, in_bin;
+    const uint32_t b1 = tk_find_bin(sh.hist, TK_BINS, (uint32_t)r, sh, &above, &in_bin);
+    for (int b = tid; b < TK_BINS; b += TK_NT) sh.hist[b] = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < TK_SAMPLE / TK_NT; ++q)
+        if ((key[q] >> 20) == b1) atomicAdd(&sh.hist[(key[q] >> 9) & (TK_BINS - 1)], 1u);
+    __syncthreads();
+    const uint32_t b2 = tk_find_bin(sh.hist, TK_BINS, (uint32_t)r - above, sh, &above, &in_bin);
+    if (tid == 0) {
+        aux[0] = (b1 << 20) | (b2 << 9);
+        aux[1] = 0ull; // items of the tensor's list so far (low word), overflow mark (high word)
+    }
+}
+
+// A chunk on the sampled path: its items with magnitude bits >= the tensor's threshold are appended to the tensor's
+// list.  One pass over memory and almost nothing to keep (about 130 of 32,768 elements), so what matters is how many
+// loads are in flight on a compute unit: four small workgroups per chunk, each with its whole piece requested at once.
+#define TK_FILTER_NT 256
+#define TK_FILTER_PIECES 4
+#define TK_FILTER_CAP 2048 /* items a piece may keep (its share of what a chunk's array would hold) */
+__global__ void __launch_bounds__(TK_FILTER_NT)
+tk_filter_kernel(const float *__restrict__ g, const int64_t *__restrict__ plan, uint64_t *cand, int first_node) {
+    __shared__ uint64_t kept[TK_FILTER_CAP];
+    __shared__ uint32_t s_cnt, s_base;
+    const int T_ = (int)plan[1];
+    const int64_t *rec = plan + TK_HEADER + (int64_t)T_ * TK_TENSOR + (int64_t)(first_node + (int)blockIdx.x / TK_FILTER_PIECES) * TK_NODE;
+    const int piece = (int)blockIdx.x % TK_FILTER_PIECES, tid = threadIdx.x;
+    const int n = (int)rec[TK_N_ITEMS];
+    const int per = ((n + TK_FILTER_PIECES - 1) / TK_FILTER_PIECES + 3) & ~3; // elements per piece, whole 16-byte vectors
+    const int begin = piece * per, end = begin + per < n ? begin + per : n;
+    uint64_t *aux = cand + rec[TK_N_AUX];
+    const uint32_t thr = (uint32_t)aux[0];
+    const float *p = g + rec[TK_N_SRC];
+    const uint32_t first = (uint32_t)rec[TK_N_FIRST];
+    if (tid == 0) s_cnt = 0u;
+    __syncthreads();
+    auto take = [&](uint32_t bits, int i) { // element i of the chunk
+        const uint32_t key = bits & 0x7FFFFFFFu;
+        if (key >= thr) {
+            const uint32_t slot = atomicAdd(&s_cnt, 1u);
+            if (slot < TK_FILTER_CAP) kept[slot] = ((uint64_t)key << 32) | (0xFFFFFFFFu - (first + (uint32_t)i));
+        }
+    };
+    if (begin < end) {
+        // elements before the first and after the last whole aligned vector one by one, the vectors eight per thread at once
+        const int mis = (int)(((uintptr_t)(p + begin) & 15u) >> 2);
+        int v0 = begin + ((4 - mis) & 3);
+        if (v0 > end) v0 = end;
+        const int nvec = (end - v0) >> 2, v1 = v0 + nvec * 4;
+        for (int i = begin + tid; i < v0; i += TK_FILTER_NT) take(__float_as_uint(p[i]), i);
+        for (int i = v1 + tid; i < end; i += TK_FILTER_NT) take(__float_as_uint(p[i]), i);
+        for (int q0 = 0; q0 < nvec; q0 += 8 * TK_FILTER_NT) {
+            uint4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int q = q0 + u * TK_FILTER_NT + tid;
+                v[u] = q < nvec ? *(const uint4 *)(p + v0 + 4 * q) : make_uint4(0u, 0u, 0u, 0u);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int q = q0 + u * TK_FILTER_NT + tid;
+                if (q < nvec) {
+                    take(v[u].x, v0 + 4 * q);
+                    take(v[u].y, v0 + 4 * q + 1);
+                    take(v[u].z, v0 + 4 * q + 2);
+                    take(v[u].w, v0 + 4 * q + 3);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const uint32_t cnt = s_cnt;
+    uint32_t *aux32 = (uint32_t *)(aux + 1); // [0] items of the tensor's list so far, [1] overflow mark
+    if (cnt > TK_FILTER_CAP) { // a run of one magnitude at the threshold: the final step will take the plain tree
+        if (tid == 0) atomicOr(&aux32[1], 1u);
+        return;
+    }
+    if (cnt == 0u) return;
+    if (tid == 0) s_base = atomicAdd(&aux32[0], cnt);
+    __syncthreads();
+    const uint32_t base = s_base;
+    if (base + cnt > TK_NODE_CAP) {
+        if (tid == 0) atomicOr(&aux32[1], 1u);
+        return;
+    }
+    uint64_t *region = cand + rec[TK_N_OUT];
+    for (uint32_t i = tid; i < cnt; i += TK_FILTER_NT) region[base + i] = kept[i];
+}
+
+// one step: a selection (from a chunk of gradients or from survivors), or the threshold of a sampled path
+// (returns true when it was the final step of a sampled path and the sample had misled: nothing is written then)
+__device__ __forceinline__ bool tk_run_node(const int64_t *__restrict__ rec, const float *__restrict__ g, uint64_t *cand,
+                                            int32_t *__restrict__ out_idx, float *__restrict__ out_val, TkShared &sh) {
     const int flags = (int)rec[TK_N_FLAGS];
+    if (flags & TK_F_THRESH) {
+        tk_threshold(g + rec[TK_N_GBEGIN], (uint32_t)rec[TK_N_GN], (int)rec[TK_N_K], cand + rec[TK_N_AUX], sh);
+        return false;
+    }
+    int n = (int)rec[TK_N_ITEMS];
+    const int k = (int)rec[TK_N_K];
+    if (flags & TK_F_COUNTED) {
+        uint32_t *aux32 = (uint32_t *)(cand + rec[TK_N_AUX] + 1);
+        const uint32_t cnt = aux32[0], overflow = aux32[1];
+        if (overflow != 0u || cnt < (uint32_t)k || cnt > (uint32_t)TK_NODE_CAP) return true; // the sample misled
+        n = (int)cnt;
+    }
     const bool final_step = flags & TK_F_FINAL;
     if (flags & TK_F_LEAF) {
         TkSrcGrad src;
@@ -651,6 +788,31 @@ tk_node_kernel(const float *__restrict__ g, const int64_t *__restrict__ plan, ui
     } else {
         for (int r = threadIdx.x; r < keep; r += TK_NT) cand[o + r] = sh.sort[r];
     }
+    return false;
+}
+
+// The plain tree of a tensor whose sample misled, run by the workgroup of the sampled path's final step: its steps one
+// after the other (each reads what the one before wrote).  Out of line: it is hardly ever run, and inlined its loop
+// costs the steps that are run their registers.
+__device__ __noinline__ void tk_plain_tree(const int64_t *nodes, const int64_t *fin, const float *g, uint64_t *cand, int32_t *out_idx,
+                                           float *out_val, TkShared &sh) {
+    const int64_t *rec = nodes + fin[TK_N_FB_FIRST] * TK_NODE;
+    for (int64_t s = 0; s < fin[TK_N_FB_COUNT]; ++s, rec += TK_NODE) {
+        tk_run_node(rec, g, cand, out_idx, out_val, sh);
+        __threadfence_block();
+        __syncthreads();
+    }
+}
+
+// one step of the tree: one workgroup per node of the level
+__global__ void __launch_bounds__(TK_NT)
+tk_node_kernel(const float *__restrict__ g, const int64_t *__restrict__ plan, uint64_t *cand, int32_t *__restrict__ out_idx,
+               float *__restrict__ out_val, int first_node) {
+    __shared__ TkShared sh;
+    const int T = (int)plan[1];
+    const int64_t *nodes = plan + TK_HEADER + (int64_t)T * TK_TENSOR;
+    const int64_t *rec = nodes + (int64_t)(first_node + blockIdx.x) * TK_NODE;
+    if (tk_run_node(rec, g, cand, out_idx, out_val, sh)) tk_plain_tree(nodes, rec, g, cand, out_idx, out_val, sh);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -658,7 +820,9 @@ tk_node_kernel(const float *__restrict__ g, const int64_t *__restrict__ plan, ui
 // ------------------------------------------------------------------------------------------------
 struct TkNode {
     int64_t src, items, k, out, flags, first, gbegin, gn;
-    int level;
+    int level;              // launch it belongs to; -1: a step of a plain tree that only a sampled path's final step may run
+    int64_t aux;            // sampled path: the tensor's two workspace words
+    int64_t fb_first, fb_count, tensor;
 };
 
 static int64_t tk_plan_build(const int64_t *offsets, const int32_t *k, int T, int chunks, int64_t *plan, int64_t plan_capacity);
@@ -673,6 +837,18 @@ extern "C" int64_t grad_topk_plan(const int64_t *offsets, const int32_t *k, int 
     }
 }
 
+// rank of the sampled path's threshold in the sample, or 0 when the tensor takes the plain tree: about four times k
+// elements of the tensor are then expected at or above the threshold, and three times that expectation must fit the
+// final step's input and, per chunk, the array a chunk's workgroup collects in
+static int tk_sample_rank(int64_t n, int64_t k, int64_t M, int chunks) {
+    if (chunks != 0 || M < 2 || n <= 8 * TK_SAMPLE) return 0;
+    int64_t r = (4 * k * TK_SAMPLE + n - 1) / n;
+    if (r < TK_SAMPLE_RANK) r = TK_SAMPLE_RANK;
+    const int64_t expect = r * n / TK_SAMPLE;
+    if (r > TK_SAMPLE / 8 || 3 * expect > TK_NODE_CAP || 3 * expect / M > TK_CAP) return 0;
+    return (int)r;
+}
+
 static int64_t tk_plan_build(const int64_t *offsets, const int32_t *k, int T, int chunks, int64_t *plan, int64_t plan_capacity) {
     std::vector<TkNode> nodes;
     std::vector<int64_t> tensors;
@@ -685,10 +861,12 @@ static int64_t tk_plan_build(const int64_t *offsets, const int32_t *k, int T, in
         int64_t M = chunks > 0 ? (chunks < n ? (int64_t)chunks : n) : (n + TK_LEAF - 1) / TK_LEAF;
         const int64_t chunk = (n + M - 1) / M;
         M = (n + chunk - 1) / chunk; // no empty chunks
-        // the lists of the current level: (offset, items) of each; level 0 = the chunks of the tensor
-        std::vector<TkNode> cur;
+        const int rank = tk_sample_rank(n, k[t], M, chunks);
+        // the plain tree.  The lists of the current level: (offset, items) of each; level 0 = the chunks of the tensor
+        std::vector<TkNode> cur, tree;
         for (int64_t j = 0; j < M; ++j) {
-            TkNode nd = {offsets[t] + j * chunk, (j + 1) * chunk < n ? chunk : n - j * chunk, k[t], 0, TK_F_LEAF, j * chunk, offsets[t], n, 0};
+            TkNode nd = {offsets[t] + j * chunk, (j + 1) * chunk < n ? chunk : n - j * chunk, k[t], 0, TK_F_LEAF, j * chunk, offsets[t], n, 0,
+                         0, 0, 0, t};
             cur.push_back(nd);
         }
         int level = 0;
@@ -696,7 +874,7 @@ static int64_t tk_plan_build(const int64_t *offsets, const int32_t *k, int T, in
             if (cur.size() == 1) { // the last step of the tensor
                 cur[0].flags |= TK_F_FINAL;
                 cur[0].out = out;
-                nodes.push_back(cur[0]);
+                tree.push_back(cur[0]);
                 break;
             }
             // the nodes of this level hand their survivors on, back to back in the workspace
@@ -704,7 +882,7 @@ static int64_t tk_plan_build(const int64_t *offsets, const int32_t *k, int T, in
             for (auto &nd : cur) {
                 nd.out = cand + total;
                 total += nd.items < nd.k ? nd.items : nd.k;
-                nodes.push_back(nd);
+                tree.push_back(nd);
             }
             // next level: as few steps as the input limit allows (at least two lists each)
             int64_t G = TK_NODE_CAP / k[t];
@@ -715,7 +893,7 @@ static int64_t tk_plan_build(const int64_t *offsets, const int32_t *k, int T, in
                 const size_t b = a + (size_t)G < cur.size() ? a + (size_t)G : cur.size();
                 int64_t items = 0;
                 for (size_t c = a; c < b; ++c) items += cur[c].items < cur[c].k ? cur[c].items : cur[c].k;
-                TkNode nd = {cur[a].out, items, k[t], 0, 0, 0, offsets[t], n, level + 1};
+                TkNode nd = {cur[a].out, items, k[t], 0, 0, 0, offsets[t], n, level + 1, 0, 0, 0, t};
                 next.push_back(nd);
             }
             cand += total;
@@ -723,13 +901,41 @@ static int64_t tk_plan_build(const int64_t *offsets, const int32_t *k, int T, in
             ++level;
             if (level >= TK_MAX_LEVELS) return -(int64_t)KS_UNSUPPORTED;
         }
-        if (level + 1 > n_levels) n_levels = level + 1;
+        int steps = level + 1;
+        if (rank > 0) {
+            // the sampled path in front: threshold, one filter per chunk, final step; the plain tree stays in the plan
+            // for the final step's workgroup to fall back on
+            for (auto &nd : tree) nd.level = -1;
+            const int64_t aux = cand, region = cand + 2;
+            cand += 2 + TK_NODE_CAP;
+            TkNode th = {0, n, rank, 0, TK_F_THRESH, 0, offsets[t], n, 0, aux, 0, 0, t};
+            nodes.push_back(th);
+            for (int64_t j = 0; j < M; ++j) {
+                TkNode nd = {offsets[t] + j * chunk, (j + 1) * chunk < n ? chunk : n - j * chunk, k[t], region, TK_F_LEAF | TK_F_FILTER,
+                             j * chunk, offsets[t], n, 1, aux, 0, 0, t};
+                nodes.push_back(nd);
+            }
+            TkNode fin = {region, TK_NODE_CAP, k[t], out, TK_F_FINAL | TK_F_COUNTED, 0, offsets[t], n, 2, aux, 0, (int64_t)tree.size(), t};
+            nodes.push_back(fin);
+            steps = 3;
+        }
+        for (auto &nd : tree) nodes.push_back(nd);
+        if (steps > n_levels) n_levels = steps;
         tensors.push_back(n);
         tensors.push_back(k[t]);
         tensors.push_back(M);
-        tensors.push_back(level + 1);
+        tensors.push_back(steps);
         out += k[t];
     }
+    // Tensors of one step are independent of everything else: with sampled paths in the plan they run beside those
+    // paths' final steps (the launch that otherwise has the fewest workgroups) instead of beside the thresholds.
+    bool sampled = false;
+    for (const TkNode &nd : nodes) sampled = sampled || (nd.flags & TK_F_THRESH);
+    if (sampled)
+        for (TkNode &nd : nodes)
+            if (nd.level == 0 && (nd.flags & TK_F_LEAF) && (nd.flags & TK_F_FINAL)) nd.level = n_levels - 1;
+    int64_t n_launched = 0;
+    for (const TkNode &nd : nodes) n_launched += nd.level >= 0;
     const int64_t n_nodes = (int64_t)nodes.size();
     if (n_nodes >= ((int64_t)1 << 31)) return -(int64_t)KS_UNSUPPORTED;
     const int64_t words = TK_HEADER + (int64_t)T * TK_TENSOR + n_nodes * TK_NODE;
@@ -737,36 +943,63 @@ static int64_t tk_plan_build(const int64_t *offsets, const int32_t *k, int T, in
     for (int64_t i = 0; i < TK_HEADER; ++i) plan[i] = 0;
     plan[0] = TK_MAGIC;
     plan[1] = T;
-    plan[2] = n_nodes;
+    plan[2] = n_launched;
     plan[3] = cand > 0 ? cand : 1;
     plan[4] = out;
     plan[5] = offsets[T] - offsets[0];
     plan[6] = n_levels;
+    plan[7] = n_nodes;
     for (size_t i = 0; i < tensors.size(); ++i) plan[TK_HEADER + (int64_t)i] = tensors[i];
     int64_t *nrec = plan + TK_HEADER + (int64_t)T * TK_TENSOR;
     int64_t w = 0;
-    for (int lev = 0; lev < n_levels; ++lev) { // nodes level by level, tensors in order inside a level
-        plan[8 + 2 * lev] = w;
-        for (const TkNode &nd : nodes) {
-            if (nd.level != lev) continue;
-            int64_t *r = nrec + w * TK_NODE;
-            r[TK_N_SRC] = nd.src;
-            r[TK_N_ITEMS] = nd.items;
-            r[TK_N_K] = nd.k;
-            r[TK_N_OUT] = nd.out;
-            r[TK_N_FLAGS] = nd.flags;
-            r[TK_N_FIRST] = nd.first;
-            r[TK_N_GBEGIN] = nd.gbegin;
-            r[TK_N_GN] = nd.gn;
-            ++w;
+    auto put = [&](const TkNode &nd) {
+        int64_t *r = nrec + w * TK_NODE;
+        for (int q = 0; q < TK_NODE; ++q) r[q] = 0;
+        r[TK_N_SRC] = nd.src;
+        r[TK_N_ITEMS] = nd.items;
+        r[TK_N_K] = nd.k;
+        r[TK_N_OUT] = nd.out;
+        r[TK_N_FLAGS] = nd.flags;
+        r[TK_N_FIRST] = nd.first;
+        r[TK_N_GBEGIN] = nd.gbegin;
+        r[TK_N_GN] = nd.gn;
+        r[TK_N_AUX] = nd.aux;
+        r[TK_N_FB_COUNT] = nd.fb_count;
+        ++w;
+    };
+    for (int lev = 0; lev < n_levels; ++lev) { // launched nodes level by level, tensors in order inside a level; the filter
+        plan[8 + 2 * lev] = w;                 // and final steps of the sampled paths first in theirs (kernels of their own)
+        const int64_t special = lev == 1 ? TK_F_FILTER : (lev == 2 ? TK_F_COUNTED : 0);
+        for (const TkNode &nd : nodes)
+            if (nd.level == lev && (nd.flags & special)) put(nd);
+        if (special) {
+            plan[lev == 1 ? 28 : 30] = plan[8 + 2 * lev];
+            plan[lev == 1 ? 29 : 31] = w - plan[8 + 2 * lev];
         }
+        for (const TkNode &nd : nodes)
+            if (nd.level == lev && !(nd.flags & special)) put(nd);
         plan[9 + 2 * lev] = w - plan[8 + 2 * lev];
+    }
+    // then the plain trees behind sampled paths, tensor by tensor, each in the order of its levels
+    std::vector<int64_t> fb_first((size_t)T, 0);
+    for (int t = 0; t < T; ++t) {
+        fb_first[(size_t)t] = w;
+        for (const TkNode &nd : nodes)
+            if (nd.level < 0 && nd.tensor == t) put(nd);
+    }
+    for (int64_t i = 0; i < n_launched; ++i) { // the final steps of the sampled paths learn where their trees are
+        int64_t *r = nrec + i * TK_NODE;
+        if (r[TK_N_FLAGS] & TK_F_COUNTED) {
+            for (int t = 0; t < T; ++t)
+                if (offsets[t] == r[TK_N_GBEGIN] && r[TK_N_GN] == offsets[t + 1] - offsets[t]) r[TK_N_FB_FIRST] = fb_first[(size_t)t];
+        }
     }
     return words;
 }
 
 static bool tk_plan_ok(const int64_t *p) {
-    return p && p[0] == TK_MAGIC && p[1] >= 1 && p[2] >= p[1] && p[3] >= 1 && p[4] >= 1 && p[6] >= 1 && p[6] <= TK_MAX_LEVELS;
+    return p && p[0] == TK_MAGIC && p[1] >= 1 && p[2] >= p[1] && p[3] >= 1 && p[4] >= 1 && p[6] >= 1 && p[6] <= TK_MAX_LEVELS &&
+           p[7] >= p[2] && p[29] >= 0 && p[31] >= 0 && p[29] <= p[2] && p[31] <= p[2];
 }
 
 extern "C" size_t grad_topk_workspace(const int64_t *plan_host) {
@@ -781,7 +1014,13 @@ extern "C" int grad_topk_select(const float *g, const int64_t *plan_dev, const i
     hipStream_t st = (hipStream_t)stream;
     uint64_t *cand = (uint64_t *)ws;
     for (int lev = 0; lev < (int)plan_host[6]; ++lev) {
-        const int64_t first = plan_host[8 + 2 * lev], count = plan_host[9 + 2 * lev];
+        int64_t first = plan_host[8 + 2 * lev], count = plan_host[9 + 2 * lev];
+        if (lev == 1 && plan_host[29] > 0) { // the chunks of the sampled paths
+            hipLaunchKernelGGL(tk_filter_kernel, dim3((unsigned)(plan_host[29] * TK_FILTER_PIECES)), dim3(TK_FILTER_NT), 0, st, g,
+                               plan_dev, cand, (int)first);
+            first += plan_host[29];
+            count -= plan_host[29];
+        }
         if (count < 1) continue;
         hipLaunchKernelGGL(tk_node_kernel, dim3((unsigned)count), dim3(TK_NT), 0, st, g, plan_dev, cand, out_idx, out_val,
                            (int)first);

@@ -185,6 +185,26 @@ def _plan(ks, sizes, k, chunks=0):
     return words, plan
 
 
+NODE = 12   # words of a step record: src, items, k, out, flags, first, tensor begin, tensor size, aux, tree first, tree steps
+F_LEAF, F_FINAL, F_THRESH, F_FILTER, F_COUNTED = 1, 2, 4, 8, 16
+
+
+def _check_plain_tree(np, nodes, n, k, out):
+    """nodes: the steps of one tensor's tree of selections, level by level.  Leaves tile the tensor, every inner step reads
+    whole lists that earlier steps wrote, no step takes more than 32,768 items, the last one writes the output."""
+    src, items, nk, o, flags = nodes.T[:5]
+    leaf, final = (flags & F_LEAF) == F_LEAF, (flags & F_FINAL) == F_FINAL
+    assert final.sum() == 1 and final[-1] and o[-1] == out and (nk == k).all() and not (flags & (F_THRESH | F_FILTER | F_COUNTED)).any()
+    assert (items <= 32768).all() and items[-1] >= k
+    ls = np.argsort(src[leaf], kind="stable")
+    assert (src[leaf][ls][1:] == (src[leaf] + items[leaf])[ls][:-1]).all() and items[leaf].sum() == n
+    keep = np.minimum(items, nk)
+    if len(nodes) > 1:
+        starts = set(o[~final].tolist())
+        assert all(int(x) in starts for x in src[~leaf]) and items[~leaf].sum() == keep[~final].sum()
+    return int(leaf.sum())
+
+
 def test_topk_plan_layout(ks):
     import numpy as np
     import synth
@@ -192,40 +212,65 @@ def test_topk_plan_layout(ks):
     k = synth.topk_counts(sizes)
     words, plan = _plan(ks, sizes, k)
     T = len(sizes)
+    offs = np.concatenate([[0], np.cumsum(sizes)])
     assert plan[1] == T and plan[4] == k.sum() and plan[5] == sum(sizes)
     n, kk, M, levels = plan[32:32 + 4 * T].reshape(T, 4).T
     assert (n == sizes).all() and (kk == k).all() and (M == -(-n // 32768)).all()
-    assert (levels[M == 1] == 1).all() and (levels[M > 1] >= 2).all() and plan[6] == levels.max()
+    # tensors of several chunks take the sampled path here (k is a thousandth of n): threshold, filters, final step
+    assert (levels[M == 1] == 1).all() and (levels[M > 1] == 3).all() and plan[6] == 3
+    n_launched, n_nodes = int(plan[2]), int(plan[7])
+    assert words == 32 + 4 * T + NODE * n_nodes and n_launched == (M == 1).sum() + (M[M > 1] + 2).sum()
+    nodes = plan[32 + 4 * T:].reshape(n_nodes, NODE)
+    src, items, nk, out, flags, first, gbegin, gn, aux, fb_first, fb_count = nodes.T[:11]
+    firsts, counts = plan[8:8 + 2 * 3:2], plan[9:9 + 2 * 3:2]
+    assert firsts[0] == 0 and (firsts[1:] == np.cumsum(counts)[:-1]).all() and counts.sum() == n_launched
+    lev = np.repeat(np.arange(3), counts)
+    L = nodes[:n_launched]
+    fl = L[:, 4]
+    # level 0: one threshold step per sampled tensor; level 1: its filters, first in the level; level 2: the final steps of
+    # the sampled paths first, then the tensors of a single step
+    assert ((fl[lev == 0] & F_THRESH) != 0).all() and counts[0] == (M > 1).sum()
+    assert ((fl[lev == 1] & F_FILTER) != 0).all() and plan[28] == firsts[1] and plan[29] == counts[1] == M[M > 1].sum()
+    assert plan[30] == firsts[2] and plan[31] == (M > 1).sum()
+    l2 = fl[lev == 2]
+    assert ((l2[:plan[31]] & F_COUNTED) != 0).all() and (l2[plan[31]:] == (F_LEAF | F_FINAL)).all()
+    # the filters of a tensor tile it; all final steps tile the output; the sampled paths' lists and words do not overlap
+    for t in np.nonzero(M > 1)[0]:
+        mine = L[(lev == 1) & (L[:, 6] == offs[t])]
+        o = np.argsort(mine[:, 0], kind="stable")
+        assert mine[o][0, 0] == offs[t] and (mine[o][1:, 0] == (mine[:, 0] + mine[:, 1])[o][:-1]).all() and mine[:, 1].sum() == n[t]
+        assert (mine[:, 5] == mine[:, 0] - offs[t]).all() and len(set(mine[:, 8])) == 1 and len(set(mine[:, 3])) == 1
+    fin = L[(fl & F_FINAL) != 0]
+    assert sorted(fin[:, 3].tolist()) == [0] + np.cumsum(k)[:-1].tolist()
+    counted = L[(fl & F_COUNTED) != 0]
+    regions = sorted((int(a), int(a) + 2 + 32768) for a in counted[:, 8])
+    assert all(b[0] >= a[1] for a, b in zip(regions, regions[1:])) and regions[-1][1] <= plan[3]
+    assert (counted[:, 0] == counted[:, 8] + 2).all() and (counted[:, 1] == 32768).all()
+    th = L[(fl & F_THRESH) != 0]
+    assert (th[:, 2] >= 16).all() and (th[:, 2] <= 512).all() and sorted(th[:, 8].tolist()) == sorted(counted[:, 8].tolist())
+    # behind the launched steps: the plain tree of every sampled tensor (what its final step falls back on)
+    assert n_nodes - n_launched == counted[:, 10].sum()
     big = n == 512 * 512 * 9   # 72 chunks x 2,359 survivors = 169,848 items: reduced in groups of 13 chunks first
-    assert (M[big] == 72).all() and (levels[big] == 3).all()
-    n_nodes = int(plan[2])
-    assert words == 32 + 4 * T + 8 * n_nodes
-    nodes = plan[32 + 4 * T:].reshape(n_nodes, 8)
-    src, items, nk, out, flags, first, gbegin = nodes.T[:7]
-    # levels are stored one after the other and cover all nodes
-    firsts, counts = plan[8:8 + 2 * int(plan[6]):2], plan[9:9 + 2 * int(plan[6]):2]
-    assert firsts[0] == 0 and (firsts[1:] == np.cumsum(counts)[:-1]).all() and counts.sum() == n_nodes
-    leaf, final = (flags & 1) == 1, (flags & 2) == 2
-    assert leaf[:counts[0]].all() and not leaf[counts[0]:].any() and final.sum() == T and leaf.sum() == M.sum()
-    assert (items <= 32768).all() and (items[final] >= nk[final]).all()
-    # the leaves tile the gradient array; the final nodes tile the output
-    order = np.argsort(src[leaf], kind="stable")
-    assert (src[leaf][order][1:] == (src[leaf] + items[leaf])[order][:-1]).all() and items[leaf].sum() == sum(sizes)
-    assert sorted(out[final].tolist()) == [0] + np.cumsum(k)[:-1].tolist()
-    # survivors of the other nodes lie back to back in the workspace, and every inner node reads whole lists
-    keep = np.minimum(items, nk)
-    o = np.argsort(out[~final], kind="stable")
-    assert (out[~final][o][1:] == (out[~final] + keep[~final])[o][:-1]).all() and plan[3] == keep[~final].sum()
-    starts = set(out[~final].tolist())
-    assert all(int(s) in starts for s in src[~leaf]) and items[~leaf].sum() == keep[~final].sum()
+    for c in counted:
+        t = int(np.nonzero(offs[:-1] == c[6])[0][0])
+        tree = nodes[c[9]:c[9] + c[10]]
+        assert c[9] >= n_launched and (tree[:, 6] == offs[t]).all()
+        leaves = _check_plain_tree(np, tree, n[t], k[t], c[3])
+        assert leaves == M[t] and (len(tree) == 72 + 6 + 1 if big[t] else len(tree) >= M[t] + 1)
     assert ks.lib().grad_topk_workspace(plan.ctypes.data_as(ct.c_void_p)) >= int(plan[3]) * 8
-    # forced chunk counts
+    # forced chunk counts: the paper's two steps (or a deeper tree), no sampled path
     _, p2 = _plan(ks, [100, 10_000], [5, 10], chunks=7)
-    assert p2[32 + 2] == 7 and p2[32 + 4 + 2] == 7 and p2[6] == 2
-    nodes2 = p2[32 + 8:].reshape(-1, 8)
+    assert p2[32 + 2] == 7 and p2[32 + 4 + 2] == 7 and p2[6] == 2 and p2[29] == 0 and p2[31] == 0 and p2[2] == p2[7]
+    nodes2 = p2[32 + 8:].reshape(-1, NODE)
     assert nodes2[:7, 1].tolist() == [15] * 6 + [10] and nodes2[7:14, 1].tolist() == [1429] * 6 + [1426]
+    _check_plain_tree(np, nodes2[(nodes2[:, 6] == 100)], 10_000, 10, 5)
     _, p3 = _plan(ks, [5], [5], chunks=64)
     assert p3[32 + 2] == 5 and p3[2] == 6 and p3[6] == 2
+    # a tensor whose k is large for its size keeps the plain tree even with several chunks
+    _, p4 = _plan(ks, [1_000_000], [2000])
+    assert p4[29] == 31 and p4[32 + 3] == 3 and p4[32 + 4 + 2] == 33   # threshold = 33rd of the sample: 8,000 items expected
+    _, p5 = _plan(ks, [300_000], [4096])
+    assert p5[29] == 0 and p5[31] == 0 and p5[32 + 3] >= 2             # three times 16,400 expected items are more than a step takes
 
 
 @pytest.mark.parametrize("C,D,K,dtype", [(6400, 128, 32, 0), (7000, 128, 8, 0), (8330, 256, 16, 1), (6913, 512, 32, 0),

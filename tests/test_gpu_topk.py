@@ -1,7 +1,8 @@
 """GPU parity of the layer-wise top-k selection (Section 3.3.2: divide-and-conquer top-k, grouped tensors): indices and
 values are compared bit for bit with the CPU oracle's definition (a full sort), over sizes that span one to many chunks
 with ragged tails, every path of the workgroup routine (the histogram bin fits; refinement by the lower bits; more equal
-magnitudes than the sort array holds), forced chunk counts, and the full gradient set of a ResNet-50."""
+magnitudes than the sort array holds), forced chunk counts (the paper's two steps and deeper trees), the sampled path of
+large tensors with samples that mislead in both directions, and the full gradient set of a ResNet-50."""
 import numpy as np
 import pytest
 import torch
@@ -98,6 +99,31 @@ def test_group_of_tensors_and_independence_of_the_chunk_count(ks, orc):
         if base is None:
             base = (idx, val)
         assert np.array_equal(idx, base[0]) and np.array_equal(val.view(np.uint32), base[1].view(np.uint32))
+
+
+def test_sampled_path_and_what_happens_when_the_sample_misleads(ks, orc):
+    """Tensors of several chunks take a threshold from 4,096 evenly spaced elements; the chunks then hand on what lies at
+    or above it and a final step selects.  The count that arrives is checked, so a sample that misleads costs time, not
+    correctness: here (a) gradient-like values, the path as planned; (b) all large values sit exactly on sampled
+    positions, so the threshold is far too high and fewer than k items arrive; (c) all large values sit between the
+    sampled positions and everything else is equal, so the threshold is the common value and every element passes;
+    (d) a tensor beside them that keeps its own path.  Bit-exact against the oracle in every case."""
+    n, k = 600_000, 600
+    pos = (np.arange(4096, dtype=np.int64) * n) // 4096
+    base = (synth.normal(21, synth.TID_GRAD_SET, 0, n) * 1e-3).astype(np.float32)
+    on_sample = (base * 1e-3).astype(np.float32)
+    on_sample[pos[::8]] = (1.0 + synth.uniform01(22, synth.TID_GRAD_SET, 0, 512)).astype(np.float32)   # 512 large values < k
+    off_sample = np.full(n, 0.5, dtype=np.float32)
+    between = np.setdiff1d(np.arange(n), pos)[::200][:2000]
+    off_sample[between] = (2.0 + synth.uniform01(23, synth.TID_GRAD_SET, 0, between.size)).astype(np.float32)
+    for name, g in (("gradient-like", base), ("large values on the sample", on_sample), ("large values off the sample", off_sample)):
+        print(f"case sampled path: {name}", flush=True)
+        plan = check(ks, orc, *one(g), np.array([k], dtype=np.int32))
+        assert plan.steps() == [3]
+    g_all = np.concatenate([base, on_sample, off_sample, base[:50_000]])
+    offs = np.array([0, n, 2 * n, 3 * n, 3 * n + 50_000], dtype=np.int64)
+    print("case sampled path: all of them in one group", flush=True)
+    check(ks, orc, g_all, offs, np.array([k, k, 2000, 50], dtype=np.int32))
 
 
 def test_resnet50_gradient_set(ks, orc):
