@@ -644,7 +644,8 @@ def main():
         us_topk = timed_events(lambda: ks.grad_topk_select(g_dev, plan, out_idx=t_idx, out_val=t_val, ws=t_ws), 20)
         bytes_topk = g_host.size * 4.0 + plan.n_out * 8.0  # algorithmic: every gradient read once, the selection written
         grad_topk = dict(problem=f"{len(sizes)} tensors, {g_host.size} gradients, k = 0.1 % per tensor ({plan.n_out} selected), "
-                                 f"{plan.n_workgroups} selection steps in {plan.n_levels} launches (at most {max(plan.chunks())} chunks per tensor)",
+                                 f"{plan.n_workgroups} steps in {plan.n_launches} launches ({plan.n_filtered_chunks} of them chunks filtered by a sampled "
+                                 f"threshold; at most {max(plan.chunks())} chunks per tensor)",
                          us_per_call=round(us_topk, 1), gradients_per_s=round(g_host.size / (us_topk * 1e-6), 1))
         grad_topk.update(hbm_entry(us_topk, bytes_topk))
         if not args.no_cpu_baseline:

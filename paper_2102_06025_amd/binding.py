@@ -598,7 +598,10 @@ class GradTopkPlan:
         self.T = int(host[1])
         self.n_workgroups = int(host[2])   # selection steps over all levels
         self.n_out = int(host[4])
-        self.n_levels = int(host[6])       # launches per call
+        self.n_levels = int(host[6])       # levels of the plan
+        self.n_filtered_chunks = int(host[29])  # chunks on the sampled path (a launch of their own)
+        self.n_launches = sum(1 for lev in range(self.n_levels)
+                              if int(host[9 + 2 * lev]) - (self.n_filtered_chunks if lev == 1 else 0) > 0) + (self.n_filtered_chunks > 0)
         self.ws_bytes = int(lib().grad_topk_workspace(host.ctypes.data_as(ct.c_void_p)))
 
     def chunks(self):
