@@ -72,6 +72,32 @@ def test_graph_sampled_rows_exact(ks, orc, shard):
     assert bool((S[:, 1:] <= S[:, :-1]).all())
 
 
+def test_graph_of_clustered_rows_sampled_rows_exact(ks, orc):
+    """The headline shard with clustered class weights (neighbour lists overlap heavily, some rows are in the lists of
+    hundreds of others): the graph build that computes every similarity once must neither lose a neighbour nor send
+    rows to its exhaustive pass in numbers that would show in the time."""
+    cfg = synth.CONFIGS["shard390k_clustered"]
+    print(f"[case] generating clustered rows C={cfg['C']} D={cfg['D']}", flush=True)
+    W, _ = synth.make_WX(cfg)
+    W_bf = torch.from_numpy(W).cuda().to(torch.bfloat16)
+    graph, sims = ks.knn_graph_build(W_bf, cfg["K"], want_sims=True)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    ks.knn_graph_build(W_bf, cfg["K"], graph=graph, sims=sims)
+    e1.record()
+    torch.cuda.synchronize()
+    print(f"[case] clustered graph build {e0.elapsed_time(e1):.1f} ms", flush=True)
+    assert e0.elapsed_time(e1) < 400.0   # (≈ 100 ms; a row in the exhaustive pass costs about a millisecond)
+    rng = np.random.default_rng(11)
+    rows = np.unique(np.concatenate([rng.integers(0, cfg["C"], 62), [0, cfg["C"] - 1]])).astype(np.int32)
+    print(f"[case] graph rows by brute force: {len(rows)} sampled rows", flush=True)
+    lists, ref = orc.graph_bruteforce(W, cfg["K"], rows)
+    sel = torch.from_numpy(rows.astype(np.int64)).cuda()
+    assert (graph[sel].cpu().numpy() == lists).all()
+    assert np.abs(sims[sel].cpu().numpy() - ref).max() <= 1e-6
+
+
 @pytest.mark.parametrize("name,unit_rows", [("shard390k", True), ("shard390k", False), ("shard390k_uniform", True)])
 def test_step_full_size(ks, orc, shard, name, unit_rows):
     cfg = synth.CONFIGS[name]
