@@ -483,10 +483,10 @@ gr_recall_soe_kernel(GrPair pr, int D, int kprime, uint64_t *__restrict__ cand, 
 //    a streamed row is fetched from memory once per group.
 //  * the stream side's candidates.  A hit for streamed row j is a record (j, i, similarity): a wavefront collects them
 //    in LDS and appends them, with one atomic per batch, to the log of j's super-block; gr_sym_scatter_kernel (one
-//    workgroup per super-block, row counters in LDS) then moves them into the rows' buffers.  The fast test of the
-//    stream side compares a group of four accumulator elements with thresholds held in scalar registers: the two
-//    halves of a wavefront hold different streamed rows (j and j + 4), so the test uses the smaller of the two
-//    thresholds (gr_sym_prep_kernel stores these minima) and the exact ones only when some lane passes.
+//    workgroup per super-block, row counters in LDS) then moves them into the rows' buffers.  In the sweep the
+//    thresholds of the streamed rows are scalar registers (an accumulator register holds one streamed row across the
+//    lanes); the two halves of a wavefront hold different rows (j and j + 4), so the test is against the smaller of
+//    the two thresholds (gr_sym_prep_kernel stores these minima) and the scatter kernel applies the row's own.
 //  * gr_sym_select_kernel cuts every row's candidates (two resident-side halves and the stream side) to the k' best,
 //    in the layout the re-rank expects.  A row whose buffers or log overflowed gets a threshold no similarity
 //    exceeds: its certificate fails and the exhaustive pass computes it.
