@@ -530,26 +530,23 @@ gr_sym_sample_kernel(const uint16_t *__restrict__ W, int64_t C, int D, int ratio
 
 // thr_sample[i]: value bits of the GR_SYM_RANK-th largest similarity of row i to the sample (0: the sample had fewer rows).
 // Row i takes every similarity at or above it: thf[i] is the next float below, and tbits[i] its key, so that "v > thf"
-// is the test and "key value <= tbits" holds for everything that fails it.  pm: minima over the row pairs (j, j + 4)
-// that share an accumulator register.  Rows at and beyond C never pass.  Also clears the counters of the logs.
+// is the test and "key value <= tbits" holds for everything that fails it.  Rows at and beyond C never pass.  Also
+// clears the counters of the logs and of the second-chance list.
 __global__ void __launch_bounds__(GR_NT)
 gr_sym_prep_kernel(const uint32_t *__restrict__ thr_sample, int64_t C, int64_t Cpad, float *__restrict__ thf,
-                   uint32_t *__restrict__ tbits, float *__restrict__ pm, int32_t *__restrict__ logcnt, int nsb) {
+                   uint32_t *__restrict__ tbits, int32_t *__restrict__ logcnt, int nsb, int32_t *second_count) {
     const int64_t i = (int64_t)blockIdx.x * GR_NT + threadIdx.x;
     if (i < nsb) logcnt[i] = 0;
+    if (i == 0) *second_count = 0;
     if (i >= Cpad) return;
-    auto bits_of = [&](int64_t r) -> uint32_t {
-        const uint32_t lowest = gr_orderable(-INFINITY);
-        const uint32_t t = thr_sample[r];
-        return t > lowest + 1u ? t - 1u : lowest;
-    };
-    const float mine = i < C ? gr_unorder(bits_of(i)) : INFINITY;
-    thf[i] = mine;
-    if (i < C) tbits[i] = bits_of(i);
-    if ((i & 4) == 0) {
-        const float other = i + 4 < C ? gr_unorder(bits_of(i + 4)) : INFINITY;
-        pm[(i >> 3) * 4 + (i & 3)] = fminf(mine, other);
+    if (i >= C) {
+        thf[i] = INFINITY;
+        return;
     }
+    const uint32_t lowest = gr_orderable(-INFINITY), t = thr_sample[i];
+    const uint32_t bits = t > lowest + 1u ? t - 1u : lowest;
+    thf[i] = gr_unorder(bits);
+    tbits[i] = bits;
 }
 
 // The plan of the sweep, made by a small kernel beforehand (the sweep kernel has no registers to spare for the
@@ -660,7 +657,7 @@ template <int KT>
 __global__ void __launch_bounds__(512)
 gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t *__restrict__ plan,
                      const int2 *__restrict__ chunks, int chunks_stride, const float *__restrict__ thf_row,
-                     const float *__restrict__ pm, uint64_t *__restrict__ cand, int32_t *__restrict__ cnt_res,
+                     uint64_t *__restrict__ cand, int32_t *__restrict__ cnt_res,
                      uint2 *__restrict__ log, int32_t *logcnt) {
     typedef KsSoe<KT, 96, GR_SOE_STAGES, 2> CFG;
     constexpr int CAP = GR_SYM_CAP, Q = GR_SYM_Q, SB = GR_SYM_SB;
@@ -725,17 +722,20 @@ gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t
                         }
                     }
                 }
-                const float *pmc = pm + ((c0 + fm * 32) >> 1); // 16 pair minima: rows 8 q + e and 8 q + 4 + e at 4 q + e
-                // stream side: the two halves of the wavefront hold rows j and j + 4, the test is against the smaller of
-                // their two thresholds (the exact one is applied when the records are sorted into the rows' buffers).
+                // Stream side.  An accumulator register holds ONE streamed row in the lanes 0..31 and the row four further
+                // on in the lanes 32..63, so a row's threshold is a scalar register -- but every element needs two of them.
+                // (Testing against the smaller of the two, and sorting out the surplus later, is half the work and was
+                // measured so; but then the number of records depends on how well neighbouring rows match: a tight cluster
+                // row beside a lone one got four times its share, the logs overflowed and every row went to the exhaustive
+                // pass.  With the exact test the counts depend on nothing but the sample.)
                 // Every instruction here runs once per chunk and fragment, so there are few: a lane's hits become a bit
-                // mask with a compare and an add-with-carry per element (bit 15 - r for element r); nearly always no lane
-                // has more than one hit, and then a lane picks its element with a binary tree of selects and the slots
-                // come from one ballot.
-                uint32_t hm = 0u;
+                // mask with a compare and an add-with-carry per element and half (bit 15 - r for element r); nearly always
+                // no lane has more than one hit, and then a lane picks its element with a binary tree of selects and the
+                // slots come from one ballot.
+                const float *tx = thf_row + c0 + fm * 32; // rows 8 q + e (lanes 0..31) and 8 q + 4 + e (lanes 32..63) of element 4 q + e
+                uint32_t hm_lo = 0u, hm_hi = 0u;
 #pragma unroll
-                for (int r = 0; r < 16; r += 4)
-                {
+                for (int q = 0; q < 4; ++q) {
                     // (the four compares first: a vector instruction must not read a mask that one of the two
                     // instructions before it has written)
                     uint64_t k0, k1, k2, k3;
@@ -743,11 +743,20 @@ gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t
                         "v_cmp_lt_f32 %4, %8, %12\n\t"
                         "v_addc_co_u32 %0, vcc, %0, %0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, %2\n\t"
                         "v_addc_co_u32 %0, vcc, %0, %0, %3\n\tv_addc_co_u32 %0, vcc, %0, %0, %4"
-                        : "+v"(hm), "=&s"(k0), "=&s"(k1), "=&s"(k2), "=&s"(k3)
-                        : "s"(pmc[r]), "s"(pmc[r + 1]), "s"(pmc[r + 2]), "s"(pmc[r + 3]), "v"(acc[fm][r]), "v"(acc[fm][r + 1]),
-                          "v"(acc[fm][r + 2]), "v"(acc[fm][r + 3])
+                        : "+v"(hm_lo), "=&s"(k0), "=&s"(k1), "=&s"(k2), "=&s"(k3)
+                        : "s"(tx[8 * q]), "s"(tx[8 * q + 1]), "s"(tx[8 * q + 2]), "s"(tx[8 * q + 3]), "v"(acc[fm][4 * q]),
+                          "v"(acc[fm][4 * q + 1]), "v"(acc[fm][4 * q + 2]), "v"(acc[fm][4 * q + 3])
+                        : "vcc");
+                    asm("v_cmp_lt_f32 %1, %5, %9\n\tv_cmp_lt_f32 %2, %6, %10\n\tv_cmp_lt_f32 %3, %7, %11\n\t"
+                        "v_cmp_lt_f32 %4, %8, %12\n\t"
+                        "v_addc_co_u32 %0, vcc, %0, %0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, %2\n\t"
+                        "v_addc_co_u32 %0, vcc, %0, %0, %3\n\tv_addc_co_u32 %0, vcc, %0, %0, %4"
+                        : "+v"(hm_hi), "=&s"(k0), "=&s"(k1), "=&s"(k2), "=&s"(k3)
+                        : "s"(tx[8 * q + 4]), "s"(tx[8 * q + 5]), "s"(tx[8 * q + 6]), "s"(tx[8 * q + 7]), "v"(acc[fm][4 * q]),
+                          "v"(acc[fm][4 * q + 1]), "v"(acc[fm][4 * q + 2]), "v"(acc[fm][4 * q + 3])
                         : "vcc");
                 }
+                uint32_t hm = (lane >> 5) ? hm_hi : hm_lo;
                 if (!real_row) hm = 0u;
                 const uint64_t any = __ballot(hm != 0u);
                 if (any != 0ull) {
@@ -854,7 +863,7 @@ gr_sym_scatter_kernel(const uint2 *__restrict__ log, const int32_t *__restrict__
 __global__ void __launch_bounds__(GR_NT)
 gr_sym_select_kernel(int64_t C, int kprime, uint64_t *__restrict__ cand, const int32_t *__restrict__ cnt_res,
                      const int32_t *__restrict__ cnt_str, const uint32_t *__restrict__ tbits, int32_t *__restrict__ cnt_out,
-                     uint32_t *__restrict__ thr_out) {
+                     uint32_t *__restrict__ thr_out, int32_t *__restrict__ cnt_all) {
     constexpr int E = GR_SYM_CAP / 64, Q = GR_SYM_Q;
     const int64_t i = (int64_t)blockIdx.x * (GR_NT / 64) + (threadIdx.x >> 6);
     if (i >= C) return;
@@ -905,17 +914,25 @@ gr_sym_select_kernel(int64_t C, int kprime, uint64_t *__restrict__ cand, const i
             t |= t_lo;
         }
     }
-    int base = 0;
+    // the k' best to the front, the other candidates behind them (gr_sym_second_kernel may need them: a row whose k'
+    // best do not certify its K-th neighbour is ranked again over everything the sweep found for it)
+    const int kept = n > kprime ? kprime : n;
+    int base = 0, rest = kept;
 #pragma unroll
     for (int r = 0; r < E; ++r) {
         if (r < nreg) {
-            const uint64_t m = __ballot(val[r] >= t);
-            if (val[r] >= t) row[base + __popcll(m & ((1ull << lane) - 1ull))] = val[r];
+            const bool real = r * 64 + lane < n, keep = real && val[r] >= t;
+            const uint64_t m = __ballot(keep), m2 = __ballot(real && !keep);
+            const uint64_t below = (1ull << lane) - 1ull;
+            if (keep) row[base + __popcll(m & below)] = val[r];
+            else if (real) row[rest + __popcll(m2 & below)] = val[r];
             base += __popcll(m);
+            rest += __popcll(m2);
         }
     }
     if (lane == 0) {
-        cnt_out[i] = n > kprime ? kprime : n;
+        cnt_all[i] = n;
+        cnt_out[i] = kept;
         // what was left out is at or below the k'-th key if the cut dropped something, else at or below the row's
         // fixed threshold; after an overflow nothing is known about it
         thr_out[i] = overflow ? 0xFFFFFFFFu : (n > kprime ? (uint32_t)(t >> 32) : tbits[i]);
@@ -1095,6 +1112,71 @@ gr_exhaustive_kernel(const IN *__restrict__ W, int64_t C, int D, int K, const in
 }
 
 // ------------------------------------------------------------------------------------------------
+// Second chance for rows that the re-rank could not certify, after the pass that computes every similarity once: that pass
+// leaves ALL rows above the row's fixed threshold in its buffer (some 400), not only the k' best, so the row is ranked
+// again over all of them, and the certificate is taken against the fixed threshold, which lies far below the K-th
+// neighbour.  It is what keeps tight clusters cheap: with hundreds of neighbours 2e-6 apart no k' of a few dozen
+// spans the error bound, and the exhaustive search costs such a row 30 ms.  One wavefront per row; rows that still
+// fail (a buffer overflowed; ties at the fixed threshold) go to the exhaustive list.
+// ------------------------------------------------------------------------------------------------
+template <typename IN>
+__global__ void __launch_bounds__(GR_NT)
+gr_sym_second_kernel(const IN *__restrict__ W, int64_t C, int D, int K, const uint64_t *__restrict__ cand,
+                     const int32_t *__restrict__ cnt_all, const uint32_t *__restrict__ thr, const uint32_t *__restrict__ tbits,
+                     const float *__restrict__ norms, const uint32_t *__restrict__ maxnorm_bits, float gamma,
+                     const int32_t *__restrict__ list_count, const int32_t *__restrict__ list_rows, int32_t *__restrict__ graph,
+                     float *__restrict__ sims, int32_t *fb_count, int32_t *__restrict__ fb_rows) {
+    __shared__ double s_s[GR_NT / 64][GR_SYM_CAP];
+    __shared__ int32_t s_id[GR_NT / 64][GR_SYM_CAP];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t n_list = *list_count;
+    if (n_list > C) n_list = C;
+    for (int64_t e0 = (int64_t)blockIdx.x * (GR_NT / 64); e0 < n_list; e0 += (int64_t)gridDim.x * (GR_NT / 64)) {
+        const int64_t e = e0 + wave;
+        const int64_t i = e < n_list ? list_rows[e] : -1;
+        const bool usable = i >= 0 && thr[i] != 0xFFFFFFFFu; // (an overflowed buffer does not hold everything above the threshold)
+        const int n = usable ? (cnt_all[i] < GR_SYM_CAP ? cnt_all[i] : GR_SYM_CAP) : 0;
+        int n_valid = 0;
+        for (int q0 = 0; q0 < n; q0 += 64) {
+            const int q = q0 + lane;
+            double sv = -INFINITY;
+            int32_t id = 0x7FFFFFFF;
+            if (q < n) {
+                const uint32_t j = 0xFFFFFFFFu - (uint32_t)cand[i * GR_SYM_CAP + q];
+                if (j < (uint32_t)C && (int64_t)j != i) { // always true for keys written by the recall pass
+                    id = (int32_t)j;
+                    sv = gr_canon(W + i * D, W + (int64_t)j * D, D);
+                }
+                s_s[wave][q] = sv;
+                s_id[wave][q] = id;
+            }
+            n_valid += __popcll(__ballot(id != 0x7FFFFFFF));
+        }
+        __syncthreads();
+        bool certified = usable && n_valid >= K;
+        if (certified) {
+            for (int q = lane; q < n; q += 64) {
+                const double sv = s_s[wave][q];
+                const int32_t id = s_id[wave][q];
+                if (id == 0x7FFFFFFF) continue;
+                int rank = 0;
+                for (int p = 0; p < n && rank < K; ++p) rank += gr_ranks_before(s_s[wave][p], s_id[wave][p], sv, id) ? 1 : 0;
+                if (rank < K) {
+                    graph[i * K + rank] = id;
+                    if (sims) sims[i * K + rank] = (float)sv;
+                    if (rank == K - 1) {
+                        const double eps = (double)gamma * (double)norms[i] * (double)__uint_as_float(*maxnorm_bits);
+                        if (!(sv > (double)gr_unorder(tbits[i]) + eps)) certified = false;
+                    }
+                }
+            }
+        }
+        if (i >= 0 && __ballot(!certified) != 0ull && lane == 0) fb_rows[atomicAdd(fb_count, 1)] = (int32_t)i;
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
 struct GrWs {
@@ -1109,9 +1191,10 @@ struct GrWs {
     double *scratch;
     // the pass that computes every similarity once (gr_sym_*), when it is used
     uint16_t *Ws;      // sampled rows
-    float *thf, *pm;   // fixed thresholds, and their minima over row pairs
+    float *thf;        // fixed thresholds
     uint32_t *tbits;
-    int32_t *cnt_res, *cnt_str, *logcnt, *plan;
+    int32_t *cnt_res, *cnt_str, *cnt_all, *logcnt, *plan;
+    int32_t *second_count, *second_rows; // rows for gr_sym_second_kernel
     int2 *chunks;
     uint2 *log;
 };
@@ -1145,15 +1228,17 @@ static GrWs gr_carve(void *ws, int64_t C, int D, int K, int dtype, size_t *total
     w.fb_count = ar.take<int32_t>(1);
     w.fb_rows = ar.take<int32_t>((size_t)C);
     w.scratch = ar.take<double>((size_t)GR_FB_BLOCKS * C);
-    w.Ws = nullptr; w.thf = w.pm = nullptr; w.tbits = nullptr; w.cnt_res = w.cnt_str = w.logcnt = w.plan = nullptr; w.chunks = nullptr; w.log = nullptr;
+    w.Ws = nullptr; w.thf = nullptr; w.tbits = nullptr; w.cnt_res = w.cnt_str = w.cnt_all = w.logcnt = w.plan = w.second_count = w.second_rows = nullptr; w.chunks = nullptr; w.log = nullptr;
     if (sym) {
         const int64_t nsb = ks_ceil_div(C, GR_SYM_SB), Cpad = nsb * GR_SYM_SB + 96;
         w.Ws = ar.take<uint16_t>((size_t)(C / GR_SYM_RATIO) * D);
         w.thf = ar.take<float>((size_t)Cpad);
-        w.pm = ar.take<float>((size_t)Cpad / 2);
         w.tbits = ar.take<uint32_t>((size_t)C);
         w.cnt_res = ar.take<int32_t>((size_t)C * 2);
         w.cnt_str = ar.take<int32_t>((size_t)C);
+        w.cnt_all = ar.take<int32_t>((size_t)C);
+        w.second_count = ar.take<int32_t>(1);
+        w.second_rows = ar.take<int32_t>((size_t)C);
         w.logcnt = ar.take<int32_t>((size_t)nsb);
         w.plan = ar.take<int32_t>((size_t)gr_sym_grid(C) * GR_SYM_PLAN);
         w.chunks = ar.take<int2>((size_t)gr_sym_grid(C) * gr_sym_chunks_stride(C));
@@ -1204,9 +1289,14 @@ extern "C" size_t knn_graph_build_workspace(int64_t C, int D, int K, int dtype) 
 
 template <typename IN>
 static void gr_launch_exact(const IN *W, int64_t C, int D, int K, const GrParams &p, const GrWs &w, float gamma,
-                            int32_t *graph, float *sims, hipStream_t st) {
+                            int32_t *graph, float *sims, hipStream_t st, bool second_chance) {
+    // (after the pass that computes every similarity once, uncertified rows get a second chance before the exhaustive list)
     hipLaunchKernelGGL(gr_rerank_kernel<IN>, dim3((unsigned)ks_ceil_div(C, GR_NT / 64)), dim3(GR_NT), 0, st, W, C, D, K, p.cap,
-                       w.cand, w.cnt, w.thr, w.norms, w.maxnorm, gamma, graph, sims, w.fb_count, w.fb_rows);
+                       w.cand, w.cnt, w.thr, w.norms, w.maxnorm, gamma, graph, sims, second_chance ? w.second_count : w.fb_count,
+                       second_chance ? w.second_rows : w.fb_rows);
+    if (second_chance)
+        hipLaunchKernelGGL(gr_sym_second_kernel<IN>, dim3(1024), dim3(GR_NT), 0, st, W, C, D, K, w.cand, w.cnt_all, w.thr, w.tbits,
+                           w.norms, w.maxnorm, gamma, w.second_count, w.second_rows, graph, sims, w.fb_count, w.fb_rows);
     hipLaunchKernelGGL(gr_exhaustive_kernel<IN>, dim3(GR_FB_BLOCKS), dim3(GR_NT), 0, st, W, C, D, K, w.fb_count, w.fb_rows,
                        w.scratch, graph, sims);
 }
@@ -1262,27 +1352,27 @@ static void gr_launch_recall_sym(const uint16_t *Wb, int64_t C, int D, int K, co
     const GrPair pr{Wb, C, w.Ws, n_sample, -((int64_t)1 << 40)};
     gr_launch_recall(pr, D, ps, w.cand, w.cnt, w.thr, st);
     hipLaunchKernelGGL(gr_sym_prep_kernel, dim3((unsigned)ks_ceil_div(Cpad, GR_NT)), dim3(GR_NT), 0, st, w.thr, C, Cpad, w.thf,
-                       w.tbits, w.pm, w.logcnt, nsb);
+                       w.tbits, w.logcnt, nsb, w.second_count);
     const unsigned grid = gr_sym_grid(C);
     const int stride = gr_sym_chunks_stride(C);
     hipLaunchKernelGGL(gr_sym_plan_kernel, dim3(grid), dim3(GR_NT), 0, st, (int)C, gr_sym_group_sbs(C), w.plan, w.chunks, stride);
     if (D == 512)
-        hipLaunchKernelGGL((gr_recall_sym_kernel<8>), dim3(grid), dim3(512), 0, st, Wb, (int)C, D, w.plan, w.chunks, stride, w.thf, w.pm,
-                           w.cand, w.cnt_res, w.log, w.logcnt);
+        hipLaunchKernelGGL((gr_recall_sym_kernel<8>), dim3(grid), dim3(512), 0, st, Wb, (int)C, D, w.plan, w.chunks, stride, w.thf, w.cand,
+                           w.cnt_res, w.log, w.logcnt);
     else if (D == 256)
-        hipLaunchKernelGGL((gr_recall_sym_kernel<4>), dim3(grid), dim3(512), 0, st, Wb, (int)C, D, w.plan, w.chunks, stride, w.thf, w.pm,
-                           w.cand, w.cnt_res, w.log, w.logcnt);
+        hipLaunchKernelGGL((gr_recall_sym_kernel<4>), dim3(grid), dim3(512), 0, st, Wb, (int)C, D, w.plan, w.chunks, stride, w.thf, w.cand,
+                           w.cnt_res, w.log, w.logcnt);
     else
-        hipLaunchKernelGGL((gr_recall_sym_kernel<2>), dim3(grid), dim3(512), 0, st, Wb, (int)C, D, w.plan, w.chunks, stride, w.thf, w.pm,
-                           w.cand, w.cnt_res, w.log, w.logcnt);
+        hipLaunchKernelGGL((gr_recall_sym_kernel<2>), dim3(grid), dim3(512), 0, st, Wb, (int)C, D, w.plan, w.chunks, stride, w.thf, w.cand,
+                           w.cnt_res, w.log, w.logcnt);
     hipLaunchKernelGGL(gr_sym_scatter_kernel, dim3((unsigned)nsb), dim3(1024), 0, st, w.log, w.logcnt, (int)C, w.tbits, w.cand,
                        w.cnt_str);
-    // what the re-rank gets: the k' of the plain pass, where the number kept also sets the work of the sweep; here it
-    // only sets the re-rank's (k' candidate rows fetched per row), and with bf16 rows the certificate's margin is so
-    // small (D * 2^-23) that eight beyond K are plenty
-    const int kept = p.kprime == 48 && K + 8 < p.kprime ? K + 8 : p.kprime;
+    // (Handing the re-rank only K + 8 candidates of bf16 rows saves it 0.6 of 5.2 ms at the headline size, and costs rows
+    // of tight clusters their certificate: with neighbours 2e-5 apart, eight of them span less than the error bound for
+    // four rows in ten, and an uncertified row costs a millisecond.)
+    const int kept = p.kprime;
     hipLaunchKernelGGL(gr_sym_select_kernel, dim3((unsigned)ks_ceil_div(C, GR_NT / 64)), dim3(GR_NT), 0, st, C, kept, w.cand,
-                       w.cnt_res, w.cnt_str, w.tbits, w.cnt, w.thr);
+                       w.cnt_res, w.cnt_str, w.tbits, w.cnt, w.thr, w.cnt_all);
 }
 
 // error bound of the recall pass relative to |w_i||w_j|: fp32 accumulation of D exact bf16 products
@@ -1319,7 +1409,8 @@ extern "C" int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K
         Wb = (const uint16_t *)W;
     }
     GrParams pe = p; // what the exact stage reads
-    if (gr_use_sym(C, D, p)) {
+    const bool sym = gr_use_sym(C, D, p);
+    if (sym) {
         gr_launch_recall_sym(Wb, C, D, K, p, w, st);
         pe.cap = GR_SYM_CAP;
     } else {
@@ -1327,8 +1418,8 @@ extern "C" int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K
         gr_launch_recall(pr, D, p, w.cand, w.cnt, w.thr, st);
     }
     const float gamma = gr_gamma(D, dtype);
-    if (dtype == KS_DTYPE_FP32) gr_launch_exact<float>((const float *)W, C, D, K, pe, w, gamma, graph, sims, st);
-    else gr_launch_exact<uint16_t>((const uint16_t *)W, C, D, K, pe, w, gamma, graph, sims, st);
+    if (dtype == KS_DTYPE_FP32) gr_launch_exact<float>((const float *)W, C, D, K, pe, w, gamma, graph, sims, st, sym);
+    else gr_launch_exact<uint16_t>((const uint16_t *)W, C, D, K, pe, w, gamma, graph, sims, st, sym);
     KS_LAUNCH_CHECK();
     return KS_OK;
 }

@@ -459,6 +459,32 @@ def test_graph_every_similarity_computed_once(ks, orc, C, D, K, bf16, kind):
     _check_graph(ks, orc, W, K, bf16, rows=rows, tag=f"symmetric recall {kind}")
 
 
+def test_graph_tight_clusters_beside_lone_rows(ks, orc):
+    """Rows that alternate, four by four, between tight clusters (hundreds of neighbours a few 1e-6 apart: no k' of a few
+    dozen certifies the K-th one) and random directions (rows four apart share accumulator registers in the sweep and have
+    nothing else in common).  The lists must be exact, and the build must not fall back on the exhaustive search for
+    more than a handful of rows: uncertified rows are ranked again over everything the sweep kept for them."""
+    C, D, K = 40_000, 128, 32
+    rnd = synth.unit_rows(13, synth.TID_W, C, D).astype(np.float64)
+    centres = synth.unit_rows(14, synth.TID_W, 64, D).astype(np.float64)
+    idx = np.arange(C)
+    W = np.where((((idx >> 2) & 1) == 0)[:, None], centres[idx % 64] + 0.1 * rnd, rnd)
+    W = synth.bf16_round((W / np.sqrt((W * W).sum(axis=1, keepdims=True))).astype(np.float32))
+    rows = np.unique(np.concatenate([np.sort(synth.class_permutation(13, C)[:150]), [0, 3, 4, 7, C - 1]])).astype(np.int32)
+    Wd = dev(W, torch.bfloat16)
+    ks.knn_graph_build(Wd, K)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    g, s = ks.knn_graph_build(Wd, K, want_sims=True)
+    e1.record()
+    torch.cuda.synchronize()
+    print(f"[graph] tight clusters beside lone rows: {e0.elapsed_time(e1):.1f} ms", flush=True)
+    assert e0.elapsed_time(e1) < 500.0   # (a few ms; with a thousand rows in the exhaustive search it would be seconds)
+    eg, es = orc.graph_bruteforce(W, K, rows)
+    assert (g.cpu().numpy()[rows] == eg).all() and (s.cpu().numpy()[rows] == es.astype(np.float32)).all()
+
+
 @pytest.mark.parametrize("C", [6000, 9000])   # the plain recall pass; the one that computes every similarity once
 def test_graph_is_deterministic(ks, orc, C):
     W = synth.unit_rows(6, synth.TID_W, C, 128, bf16=True)
