@@ -68,14 +68,20 @@ __device__ __forceinline__ int ks_soe_col() { return (threadIdx.x >> 6) * 32 + (
 struct KsSoeNoPost {
     __device__ __forceinline__ void operator()(int, int) const {}
 };
+// side(chunk_first_row, chunk_index): optional, called by wavefront 0 when the loads of a chunk begin to be requested (up
+// to two chunks before its epilogue): the place for a small asynchronous load of per-row data that the epilogue will
+// want in LDS (global_load_lds; it is older than the chunk's stream loads, so the waits that cover those cover it).
+struct KsSoeNoSide {
+    __device__ __forceinline__ void operator()(int, int) const {}
+};
 template <class P> struct KsSoeHasPost { static constexpr bool value = true; };
 template <> struct KsSoeHasPost<KsSoeNoPost> { static constexpr bool value = false; };
-template <class CFG, class Epi, class Post = KsSoeNoPost>
+template <class CFG, class Epi, class Post = KsSoeNoPost, class Side = KsSoeNoSide>
 __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int64_t ldr, int r_row0, int r_limit,
                                               const uint16_t *__restrict__ S, int64_t lds_ld, const int32_t *__restrict__ gidx,
                                               int s_begin, int s_end, int s_clamp, uint16_t *lds, Epi &epi,
                                               int32_t *lidx = nullptr, int lidx_cap = 0, Post post = Post(),
-                                              const int2 *__restrict__ ctab = nullptr, int ctab_n = 0) {
+                                              const int2 *__restrict__ ctab = nullptr, int ctab_n = 0, Side side = Side()) {
     constexpr int KT = CFG::KT, ST = CFG::STAGES, NI = CFG::NI, FM = CFG::FM;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -138,6 +144,7 @@ __device__ __forceinline__ void ks_soe_sweep(const uint16_t *__restrict__ R, int
     auto chunk_ptrs = [&](int c) __attribute__((always_inline)) {
         const int first = ctab ? ahead_first : chunk_first(c);
         if (ctab) ahead_first = ctab[c + 1 < n_chunks ? c + 1 : c].x;
+        if (wave == 0) side(first, c);
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int row = (j * CFG::LW + wave) * 8 + (lane >> 3);

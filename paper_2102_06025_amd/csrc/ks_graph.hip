@@ -664,6 +664,7 @@ gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t
     static_assert(SB % CFG::CH == 0 && SB % CFG::RES == 0 && CFG::RES == 256, "super-blocks are whole chunks and whole blocks");
     __shared__ __attribute__((aligned(16))) uint16_t lds[CFG::LDS_ELEMS];
     __shared__ uint2 s_stage[CFG::NW][GR_SYM_STAGE];
+    __shared__ __attribute__((aligned(16))) float s_thr[8][CFG::CH]; // the streamed rows' thresholds of the chunks in flight
     const int lane = threadIdx.x & 63;
     const int32_t *my_plan = plan + (int64_t)blockIdx.x * GR_SYM_PLAN;
     const int block = my_plan[0];
@@ -703,7 +704,19 @@ gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t
         wg_cand[my_base + ((uint32_t)my_cnt & (uint32_t)(Q - 1))] = ((uint64_t)gr_orderable(v) << 32) | (uint32_t)(0xFFFFFFFFu - (uint32_t)j);
         ++my_cnt;
     };
+    // The thresholds of a chunk's rows travel to LDS beside its rows: requested by wavefront 0 when the chunk's loads begin.
+    // The loads run up to STAGES - 1 pipeline stages ahead of the MFMAs and a chunk of D = 128 is a single stage, so up to
+    // seven chunks lie between the request and the epilogue that reads it: eight slots.
+    static_assert(GR_SOE_STAGES - 1 + 2 <= 8, "slots for the chunks in flight");
+    auto side = [&](int first, int c) __attribute__((always_inline)) {
+        static_assert(CFG::CH == 96, "64 + 32 lanes");
+        __builtin_amdgcn_global_load_lds(KS_GPTR(thf_row + first + lane), KS_LPTR(&s_thr[c & 7][0]), 4, 0, 0);
+        if (lane < 32) __builtin_amdgcn_global_load_lds(KS_GPTR(thf_row + first + 64 + lane), KS_LPTR(&s_thr[c & 7][64]), 4, 0, 0);
+    };
+    int epi_chunk = 0; // chunks seen by the epilogue: the slot of their thresholds
     auto epi = [&](int c0, int rows_here, f32x16_t (&acc)[CFG::FM]) {
+        const float *thr_chunk = s_thr[epi_chunk & 7];
+        ++epi_chunk;
         const int sb = c0 / SB; // uniform; a chunk lies in one super-block
         if (sb != cur_sb) { flush(); cur_sb = sb; }
         if (rows_here == CFG::CH && sb != sb_own) {
@@ -723,19 +736,21 @@ gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t
                     }
                 }
                 // Stream side.  An accumulator register holds ONE streamed row in the lanes 0..31 and the row four further
-                // on in the lanes 32..63, so a row's threshold is a scalar register -- but every element needs two of them.
-                // (Testing against the smaller of the two, and sorting out the surplus later, is half the work and was
-                // measured so; but then the number of records depends on how well neighbouring rows match: a tight cluster
-                // row beside a lone one got four times its share, the logs overflowed and every row went to the exhaustive
-                // pass.  With the exact test the counts depend on nothing but the sample.)
+                // on in the lanes 32..63.  (Testing against the smaller of the two thresholds, held in a scalar register,
+                // and sorting out the surplus later was tried: the number of records then depends on how well
+                // neighbouring rows match; a tight cluster row beside a lone one got four times its share, the logs
+                // overflowed and every row went to the exhaustive pass.  With the exact test the counts depend on
+                // nothing but the sample.)
                 // Every instruction here runs once per chunk and fragment, so there are few: a lane's hits become a bit
                 // mask with a compare and an add-with-carry per element and half (bit 15 - r for element r); nearly always
                 // no lane has more than one hit, and then a lane picks its element with a binary tree of selects and the
                 // slots come from one ballot.
-                const float *tx = thf_row + c0 + fm * 32; // rows 8 q + e (lanes 0..31) and 8 q + 4 + e (lanes 32..63) of element 4 q + e
-                uint32_t hm_lo = 0u, hm_hi = 0u;
+                // (a lane reads the four thresholds of its own rows from LDS: rows 8 q + e in the lanes 0..31, 8 q + 4 + e
+                // in the lanes 32..63)
+                uint32_t hm = 0u;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
+                    const f32x4_t t4 = *(const f32x4_t *)(thr_chunk + fm * 32 + 8 * q + 4 * (lane >> 5));
                     // (the four compares first: a vector instruction must not read a mask that one of the two
                     // instructions before it has written)
                     uint64_t k0, k1, k2, k3;
@@ -743,20 +758,11 @@ gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t
                         "v_cmp_lt_f32 %4, %8, %12\n\t"
                         "v_addc_co_u32 %0, vcc, %0, %0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, %2\n\t"
                         "v_addc_co_u32 %0, vcc, %0, %0, %3\n\tv_addc_co_u32 %0, vcc, %0, %0, %4"
-                        : "+v"(hm_lo), "=&s"(k0), "=&s"(k1), "=&s"(k2), "=&s"(k3)
-                        : "s"(tx[8 * q]), "s"(tx[8 * q + 1]), "s"(tx[8 * q + 2]), "s"(tx[8 * q + 3]), "v"(acc[fm][4 * q]),
-                          "v"(acc[fm][4 * q + 1]), "v"(acc[fm][4 * q + 2]), "v"(acc[fm][4 * q + 3])
-                        : "vcc");
-                    asm("v_cmp_lt_f32 %1, %5, %9\n\tv_cmp_lt_f32 %2, %6, %10\n\tv_cmp_lt_f32 %3, %7, %11\n\t"
-                        "v_cmp_lt_f32 %4, %8, %12\n\t"
-                        "v_addc_co_u32 %0, vcc, %0, %0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, %2\n\t"
-                        "v_addc_co_u32 %0, vcc, %0, %0, %3\n\tv_addc_co_u32 %0, vcc, %0, %0, %4"
-                        : "+v"(hm_hi), "=&s"(k0), "=&s"(k1), "=&s"(k2), "=&s"(k3)
-                        : "s"(tx[8 * q + 4]), "s"(tx[8 * q + 5]), "s"(tx[8 * q + 6]), "s"(tx[8 * q + 7]), "v"(acc[fm][4 * q]),
-                          "v"(acc[fm][4 * q + 1]), "v"(acc[fm][4 * q + 2]), "v"(acc[fm][4 * q + 3])
+                        : "+v"(hm), "=&s"(k0), "=&s"(k1), "=&s"(k2), "=&s"(k3)
+                        : "v"(t4[0]), "v"(t4[1]), "v"(t4[2]), "v"(t4[3]), "v"(acc[fm][4 * q]), "v"(acc[fm][4 * q + 1]),
+                          "v"(acc[fm][4 * q + 2]), "v"(acc[fm][4 * q + 3])
                         : "vcc");
                 }
-                uint32_t hm = (lane >> 5) ? hm_hi : hm_lo;
                 if (!real_row) hm = 0u;
                 const uint64_t any = __ballot(hm != 0u);
                 if (any != 0ull) {
@@ -817,7 +823,7 @@ gr_recall_sym_kernel(const uint16_t *__restrict__ W, int C, int D, const int32_t
         }
     };
     ks_soe_sweep<CFG>(W, D, row0, C, W, D, nullptr, 0, 0, C, lds, epi, nullptr, 0, KsSoeNoPost(),
-                      chunks + (int64_t)blockIdx.x * chunks_stride, my_plan[2]);
+                      chunks + (int64_t)blockIdx.x * chunks_stride, my_plan[2], side);
     flush();
     if (row0 + ks_soe_col() < C) cnt_res[2 * (row0 + ks_soe_col()) + (lane >> 5)] = my_cnt;
 }
