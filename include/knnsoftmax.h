@@ -81,7 +81,7 @@ int knn_graph_build(const void *W, int dtype, int64_t C, int D, int K, int32_t *
                     void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
 /* knn_graph_build_plan -- how knn_graph_build divides the linear search of Section 3.2.2 when it computes every
- * similarity once and uses it for both rows of the pair (large C; D = 128, 256 or 512; K <= 32).  Host-only, no GPU
+ * similarity once and uses it for both rows of the pair (large C; D = 128, 256 or 512; K <= 64).  Host-only, no GPU
  * work; for tests and tools.
  *   n_workgroups [1]   out (host): workgroups of that pass, 0 when this problem takes the plain pass
  *   out          [12]  out (host), may be NULL: for `workgroup` in [0, *n_workgroups):

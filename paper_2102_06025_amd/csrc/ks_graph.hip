@@ -6,7 +6,7 @@
 //             MFMA tiles of similarities; an element that beats its row's threshold is appended to that row's candidate
 //             buffer; a full buffer is cut back to its k' best by a wavefront (a bitwise search for the
 //             k'-th largest key), which also raises the threshold.  The C x C similarities are never stored.
-//             Large problems (D = 128, 256, 512, K <= 32) take the variant that computes every similarity once and
+//             Large problems (D = 128, 256, 512, K <= 64) take the variant that computes every similarity once and
 //             uses it for both rows of the pair, with thresholds fixed beforehand from a sample of the rows (gr_sym_*).
 //   re-rank   one wavefront per row: canonical fp64 similarity of the k' candidates, exact order
 //             (similarity descending, id ascending), first K written out.  The row is certified when
@@ -1213,10 +1213,12 @@ static int gr_sym_chunks_stride(int64_t C) { // chunks a workgroup streams at mo
     const int64_t nsb = ks_ceil_div(C, GR_SYM_SB), GS = gr_sym_group_sbs(C), NG = ks_ceil_div(nsb, GS);
     return (int)(((NG / 2) * GS + GS / 2 + 2) * (GR_SYM_SB / 96));
 }
-// The pass that computes every similarity once pays off for problems of more than a few thousand rows; its buffers
-// are sized for k' <= 64 and a row id has 22 bits in the stream side's records.
+// The pass that computes every similarity once pays off for problems of more than a few thousand rows.  A row's fixed
+// threshold leaves 32 * Gamma(12) candidates (384 on average, fewer than 64 for one row in 10^7), which serves K <= 64:
+// a row with fewer than k' candidates keeps them all and is certified against its fixed threshold.  A row id has 22
+// bits in the stream side's records.
 static bool gr_use_sym(int64_t C, int D, const GrParams &p) {
-    return (D == 128 || D == 256 || D == 512) && p.kprime <= 64 && C >= 6144 && C <= ((int64_t)1 << 22);
+    return (D == 128 || D == 256 || D == 512) && p.kprime <= 128 && C >= 6144 && C <= ((int64_t)1 << 22);
 }
 
 static GrWs gr_carve(void *ws, int64_t C, int D, int K, int dtype, size_t *total) {

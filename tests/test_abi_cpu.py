@@ -341,7 +341,7 @@ def test_graph_plan_pairs_every_two_blocks_exactly_once(ks, C, D, K, dtype):
 
 
 def test_graph_plan_is_absent_for_small_problems(ks):
-    for C, D, K, dtype in [(6000, 128, 32, 0), (390_625, 192, 32, 0), (390_625, 512, 64, 0), (6000, 256, 16, 1)]:
+    for C, D, K, dtype in [(6000, 128, 32, 0), (390_625, 192, 32, 0), (390_625, 512, 65, 0), (6000, 256, 16, 1)]:
         assert ks.knn_graph_build_plan(C, D, K, dtype)[0] == 0
     with pytest.raises(ks.KsError):
         ks.knn_graph_build_plan(1, 128, 32, 0)

@@ -439,12 +439,13 @@ def test_graph_sweep_kernel_buffer_sizes_and_ties(ks, orc, C, D, K, bf16, kind):
 @pytest.mark.parametrize("C,D,K,bf16,kind", [(6400, 128, 32, True, "unit"), (7000, 128, 8, True, "unit"),
                                              (8330, 256, 16, False, "unit"), (6913, 512, 32, True, "clustered"),
                                              (25_000, 128, 32, True, "unit"), (50_011, 128, 16, True, "clustered"),
-                                             (6400, 128, 32, True, "integers")])
+                                             (6400, 128, 32, True, "integers"), (9000, 256, 64, True, "unit"),
+                                             (12_345, 128, 40, False, "clustered"), (7000, 512, 64, True, "integers")])
 def test_graph_every_similarity_computed_once(ks, orc, C, D, K, bf16, kind):
-    """The recall pass that uses the symmetry of the similarities (D = 128, 256, 512, k' <= 64, a sample of at least
-    8 (k' + 1) rows): block, super-block and group counts that are odd, even and ragged (a last super-block of one, two
-    and three blocks; groups of one, two and four super-blocks), both values of k', clustered rows, and rows with so many
-    equal similarities that the fixed-size buffers overflow and the rows go to the exhaustive pass."""
+    """The recall pass that uses the symmetry of the similarities (D = 128, 256, 512, K <= 64): block, super-block and
+    group counts that are odd, even and ragged (a last super-block of one, two and three blocks; groups of one, two and
+    four super-blocks), all three values of k' (48, 64, 128), clustered rows, and rows with so many equal similarities
+    that the fixed-size buffers overflow and the rows go to the exhaustive pass."""
     if kind == "unit":
         W = synth.unit_rows(11, synth.TID_W, C, D, bf16=bf16)
     elif kind == "integers":
