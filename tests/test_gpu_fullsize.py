@@ -72,19 +72,21 @@ def test_graph_sampled_rows_exact(ks, orc, shard):
     assert bool((S[:, 1:] <= S[:, :-1]).all())
 
 
-def test_graph_of_clustered_rows_sampled_rows_exact(ks, orc):
+@pytest.mark.parametrize("K", [32, 64])
+def test_graph_of_clustered_rows_sampled_rows_exact(ks, orc, K):
     """The headline shard with clustered class weights (neighbour lists overlap heavily, some rows are in the lists of
     hundreds of others): the graph build that computes every similarity once must neither lose a neighbour nor send
-    rows to its exhaustive pass in numbers that would show in the time."""
+    rows to its exhaustive pass in numbers that would show in the time -- with the shard's K = 32 (k' = 48) and with
+    K = 64 (k' = 128)."""
     cfg = synth.CONFIGS["shard390k_clustered"]
-    print(f"[case] generating clustered rows C={cfg['C']} D={cfg['D']}", flush=True)
+    print(f"[case] generating clustered rows C={cfg['C']} D={cfg['D']}, K={K}", flush=True)
     W, _ = synth.make_WX(cfg)
     W_bf = torch.from_numpy(W).cuda().to(torch.bfloat16)
-    graph, sims = ks.knn_graph_build(W_bf, cfg["K"], want_sims=True)
+    graph, sims = ks.knn_graph_build(W_bf, K, want_sims=True)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    ks.knn_graph_build(W_bf, cfg["K"], graph=graph, sims=sims)
+    ks.knn_graph_build(W_bf, K, graph=graph, sims=sims)
     e1.record()
     torch.cuda.synchronize()
     print(f"[case] clustered graph build {e0.elapsed_time(e1):.1f} ms", flush=True)
@@ -92,7 +94,7 @@ def test_graph_of_clustered_rows_sampled_rows_exact(ks, orc):
     rng = np.random.default_rng(11)
     rows = np.unique(np.concatenate([rng.integers(0, cfg["C"], 62), [0, cfg["C"] - 1]])).astype(np.int32)
     print(f"[case] graph rows by brute force: {len(rows)} sampled rows", flush=True)
-    lists, ref = orc.graph_bruteforce(W, cfg["K"], rows)
+    lists, ref = orc.graph_bruteforce(W, K, rows)
     sel = torch.from_numpy(rows.astype(np.int64)).cuda()
     assert (graph[sel].cpu().numpy() == lists).all()
     assert np.abs(sims[sel].cpu().numpy() - ref).max() <= 1e-6
