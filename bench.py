@@ -176,7 +176,11 @@ def measure_peaks(ks, hev, stream, torch):
 class StepRunner:
     """One workload's buffers and the three timed loops over its step."""
 
-    def __init__(self, ks, torch, hev, cfg, W, X, y, graph, unit_rows, fused_update, W_bf=None, W_master=None):
+    def __init__(self, ks, torch, hev, cfg, W, X, y, graph, unit_rows, fused_update, W_bf=None, W_master=None,
+                 next_inside=False):
+        """next_inside: a step is ONE call of knn_softmax_fwd_bwd_update_selected_next -- forward, backward and weight
+        update of this batch on the list the previous call left, and Algorithm 1 for the next batch in the same launches
+        (every step still runs every stage once).  Otherwise ONE call of knn_softmax_fwd_bwd_update."""
         self.ks, self.torch, self.hev, self.cfg = ks, torch, hev, cfg
         C, D, B, K, M = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"]
         self.scale, self.grad_scale = cfg["scale"], 128.0
@@ -196,6 +200,13 @@ class StepRunner:
         self.A = int(self.out["n_active"].item())
         self.out_fused = dict(self.out)
         self.out_fused["dW_active"] = None      # the fused step does not store the gradient rows
+        self.next_inside = bool(next_inside and fused_update)
+        if self.next_inside:
+            self.ws_next = torch.empty(ks.knn_softmax_selected_next_workspace(C, D, B, K, M), dtype=torch.uint8, device="cuda")
+            # the list of the first batch; every call leaves the next batch's list in the same buffers
+            self.sel = {k: self.out[k].clone() for k in ("active_idx", "n_active", "target_pos")}
+            self.out_next = {k: self.out[k] for k in ("loss_per_sample", "loss_mean", "dX", "dev_status")}
+            self.out_next["dW_active"] = None
 
     def first_step_copy(self):
         first = {k: self.out[k].clone() for k in ("active_idx", "target_pos", "loss_per_sample", "loss_mean", "dX")}
@@ -205,6 +216,12 @@ class StepRunner:
     def step(self, ev=None):
         ks, cfg, o = self.ks, self.cfg, self.out
         C, D, B, K, M = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"]
+        if ev is None and self.next_inside:
+            ks.knn_softmax_fwd_bwd_update_selected_next(self.W_master, self.W_bf, self.X_bf, self.sel["active_idx"],
+                                                        self.sel["n_active"], self.sel["target_pos"], self.labels, self.graph,
+                                                        self.scale, self.grad_scale, self.alpha, out=self.out_next,
+                                                        ws=self.ws_next, unit_rows=self.unit_rows)
+            return
         if ev is None and self.fused:
             ks.knn_softmax_fwd_bwd_update(self.W_master, self.W_bf, self.X_bf, self.labels, self.graph, M, self.scale,
                                           self.grad_scale, self.alpha, out=self.out_fused, ws=self.ws, unit_rows=self.unit_rows)
@@ -276,6 +293,9 @@ def main():
     ap.add_argument("--no-parity", action="store_true")
     ap.add_argument("--headline-only", action="store_true",
                     help="only the headline step (no other workloads, layers or peaks): used for the profiles")
+    ap.add_argument("--serial", action="store_true",
+                    help="headline = the one-call step that selects its own batch first (default: the next batch's selection "
+                         "rides along with the step)")
     ap.add_argument("--separate-update", action="store_true",
                     help="run the weight update as a call of its own (apply_weight_grad) instead of knn_softmax_fwd_bwd_update")
     ap.add_argument("--general-rows", action="store_true",
@@ -337,7 +357,12 @@ def main():
     # the synthetic rows are L2-normalised, as the paper's are: the library may rely on it
     unit_rows = not args.general_rows
     fused_update = not args.separate_update
-    run = StepRunner(ks, torch, hev, cfg, W, X, y, graph, unit_rows, fused_update, W_bf=W_bf, W_master=W_master)
+    # The headline loop is the training loop's: one library call per step, which runs forward, backward and weight update
+    # of batch n and Algorithm 1 for batch n + 1 (whose labels a data loader has early) in the same launches.  --serial
+    # times the one-call step that selects its own batch first (reported beside it in any case).
+    next_inside = fused_update and not args.serial
+    run = StepRunner(ks, torch, hev, cfg, W, X, y, graph, unit_rows, fused_update, W_bf=W_bf, W_master=W_master,
+                     next_inside=next_inside)
     A = run.A
     log(f"[bench] active classes A={A} of M={M}")
     first = run.first_step_copy()
@@ -346,6 +371,13 @@ def main():
     grad_scale, alpha = run.grad_scale, run.alpha
     ms_per_step, ms_median, dur = run.run(args.steps, args.warmup)
     value = B / (ms_per_step * 1e-3)
+    ms_serial = ms_per_step
+    if next_inside:
+        assert torch.equal(run.sel["active_idx"], run.out["active_idx"]) and torch.equal(run.sel["target_pos"], run.out["target_pos"])
+        run.next_inside = False
+        ms_serial, _, _ = run.run(args.steps, args.warmup, with_stages=False)
+        run.next_inside = True
+        log(f"[bench] step with the next batch's selection inside: {ms_per_step:.4f} ms; one-call step that selects first: {ms_serial:.4f} ms")
 
     mfma_peak = peaks["mfma_loop_tflops"] if peaks else None
     copy_peak = peaks["stream_copy_gbs"] if peaks else None
@@ -497,12 +529,16 @@ def main():
         torch.cuda.synchronize()
         ms_piped = (time.perf_counter() - t0) * 1e3 / args.steps
         assert int(out_sel["dev_status"].item()) == 0 and int(sel_st.item()) == 0
-        selection_variants = dict(serial_ms_per_step=round(ms_per_step, 4), selection_given_ms_per_step=round(ms_given, 4),
+        selection_variants = dict(serial_ms_per_step=round(ms_serial, 4), selection_given_ms_per_step=round(ms_given, 4),
                                   selection_of_next_batch_on_second_stream_ms_per_step=round(ms_piped, 4),
-                                  what="knn_select_active + knn_softmax_fwd_bwd_update_selected; the second-stream figure "
-                                       "includes one cross-stream event dependency per step")
+                                  selection_of_next_batch_inside_the_step_ms_per_step=round(ms_per_step, 4) if next_inside else None,
+                                  what="serial: knn_softmax_fwd_bwd_update, which selects its own batch first; given / second "
+                                       "stream: knn_select_active + knn_softmax_fwd_bwd_update_selected (the second-stream "
+                                       "figure includes the cross-stream event dependencies of every step); inside: "
+                                       "knn_softmax_fwd_bwd_update_selected_next, the next batch's selection as extra "
+                                       "workgroups of the step's dX and dW launches")
         log(f"[bench] selection off the path: given {ms_given:.4f} ms/step, next batch's on a second stream {ms_piped:.4f} "
-            f"ms/step (serial {ms_per_step:.4f})")
+            f"ms/step (serial {ms_serial:.4f})")
         del sel_bufs, ws_sel
 
     # ---- the same step at the cap of the active set (uniform labels: about 32.3 k distinct candidates) ----------
@@ -510,7 +546,7 @@ def main():
     if args.workload == "shard390k" and not args.headline_only:
         cfg_u = dict(synth.CONFIGS["shard390k_uniform"])
         run_u = StepRunner(ks, torch, hev, cfg_u, W, X, synth.make_labels(cfg_u), graph, unit_rows, fused_update, W_bf=W_bf,
-                           W_master=W_master)
+                           W_master=W_master, next_inside=next_inside)
         ms_u, ms_u_med, dur_u = run_u.run(args.steps, args.warmup)
         gemm_u = 2.0 * B * run_u.A * D
         at_the_cap = dict(workload="shard390k_uniform", active_classes=run_u.A, ms_per_step=round(ms_u, 4),
@@ -752,8 +788,12 @@ def main():
         "ms_per_step_hip_event_median": round(ms_median, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: C={C} D={D} B={B} K={K} M={M} labels={cfg['labels']} s={scale}",
-                   "active_classes": A, "step": "knn_softmax_fwd_bwd_update (select + fwd/bwd + weight update in one call)" if fused_update
-                   else "select + knn_softmax_fwd_bwd + apply_weight_grad",
+                   "active_classes": A,
+                   "step": ("knn_softmax_fwd_bwd_update_selected_next, one call per step: fwd/bwd + weight update of batch n and "
+                            "the selection (Algorithm 1) of batch n + 1 in the same launches; the one-call step that selects "
+                            "its own batch first is selection_variants.serial_ms_per_step") if next_inside
+                   else ("knn_softmax_fwd_bwd_update (select + fwd/bwd + weight update in one call)" if fused_update
+                         else "select + knn_softmax_fwd_bwd + apply_weight_grad"),
                    "unit_rows_flag": unit_rows},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,

@@ -205,6 +205,30 @@ int knn_softmax_fwd_bwd_update_selected(float *W_master, uint16_t *W_bf16, const
                                         uint32_t flags, float *loss_per_sample, float *loss_mean, float *dX,
                                         float *dW_active, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
+/* knn_softmax_fwd_bwd_update_selected_next -- knn_softmax_fwd_bwd_update_selected for this batch AND Algorithm 1
+ * (knn_select_active) for the NEXT batch in the same launches: the selection needs only the next batch's labels and the
+ * graph (Section 3.2.1), so it runs as extra workgroups of the step's own dX and dW launches, on compute units those
+ * leave idle -- no second stream, no dependency between streams, and the selection is off the step's critical path.
+ * A training loop calls knn_select_active once for its first batch and this from then on.
+ *
+ *   labels_next [B] int32, graph [C, K] int32        in (device): the next batch's labels; the graph as in knn_select_active
+ *   active_idx_next [M], n_active_next [1], target_pos_next [B]   out (device): exactly what knn_select_active writes for
+ *                       labels_next (bit for bit).  They MAY be the buffers this call's active_idx / n_active /
+ *                       target_pos came in: the call copies its own list before the selection starts.
+ *   everything else     as in knn_softmax_fwd_bwd_update_selected, with the same results bit for bit
+ * Requires K + 1 <= M besides that call's conditions.  When D is not a multiple of 64, or C exceeds the 393,216 classes
+ * whose bitmap one workgroup holds, the selection runs after the step as launches of its own (same results).
+ * Workspace: knn_softmax_selected_next_workspace. */
+size_t knn_softmax_selected_next_workspace(int64_t C, int D, int B, int K, int M);
+int knn_softmax_fwd_bwd_update_selected_next(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16,
+                                             const int32_t *active_idx, const int32_t *n_active,
+                                             const int32_t *target_pos, int64_t C, int D, int B, int M, float scale,
+                                             float grad_scale, float alpha, uint32_t flags, float *loss_per_sample,
+                                             float *loss_mean, float *dX, float *dW_active, const int32_t *labels_next,
+                                             const int32_t *graph, int K, int32_t *active_idx_next,
+                                             int32_t *n_active_next, int32_t *target_pos_next, void *ws, size_t ws_bytes,
+                                             int32_t *dev_status, void *stream);
+
 /* Measurement aid: knn_softmax_fwd_bwd (W_master == NULL) or knn_softmax_fwd_bwd_update with one hipEvent_t
  * recorded on `stream` at each stage boundary, so that a caller can time the stages of a step without a profiler.
  * events[0..KS_N_PHASE_EVENTS) are created by the caller (hipEventCreate); event k is recorded: 0 at entry, 1

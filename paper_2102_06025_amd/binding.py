@@ -25,6 +25,7 @@ EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_gr
            "knn_select_active_csr_workspace", "knn_select_active_csr", "knn_graph_update_workspace", "knn_graph_update",
            "knn_softmax_split_workspace", "knn_softmax_fwd_stats", "knn_softmax_bwd_from_stats",
            "knn_softmax_fwd_bwd_update", "knn_softmax_selected_workspace", "knn_softmax_fwd_bwd_update_selected",
+           "knn_softmax_selected_next_workspace", "knn_softmax_fwd_bwd_update_selected_next",
            "ks_peak_mfma", "ks_peak_copy", "grad_topk_plan", "grad_topk_workspace", "grad_topk_select")
 
 
@@ -318,6 +319,49 @@ def knn_softmax_fwd_bwd_update_selected(W_master, W_bf16, X_bf16, active_idx, n_
                                                    ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
     _check("knn_softmax_fwd_bwd_update_selected", rc)
     return out
+
+
+def knn_softmax_selected_next_workspace(C, D, B, K, M) -> int:
+    return int(lib().knn_softmax_selected_next_workspace(ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(K), ct.c_int(M)))
+
+
+def knn_softmax_fwd_bwd_update_selected_next(W_master, W_bf16, X_bf16, active_idx, n_active, target_pos, labels_next, graph,
+                                             scale, grad_scale, alpha, next_out=None, out=None, ws=None, dev_status=None,
+                                             stream=None, unit_rows=False, want_dW=False):
+    """The step on a given selection, and in the same launches the selection of the next batch (labels_next).
+    next_out: dict(active_idx, n_active, target_pos) to write the next selection to (None: this call's own list
+    buffers are reused).  Returns (out, next_out)."""
+    _need(W_bf16, torch.bfloat16, "W_bf16")
+    _need(X_bf16, torch.bfloat16, "X_bf16")
+    _need(active_idx, torch.int32, "active_idx")
+    _need(target_pos, torch.int32, "target_pos")
+    _need(labels_next, torch.int32, "labels_next")
+    _need(graph, torch.int32, "graph")
+    if W_master is not None:
+        _need(W_master, torch.float32, "W_master")
+    C, D = W_bf16.shape
+    B, M, K = X_bf16.shape[0], active_idx.numel(), graph.shape[1]
+    dev = W_bf16.device
+    need_dW = want_dW or W_master is None or D % 64 != 0
+    if out is None:
+        out = dict(loss_per_sample=torch.empty(B, dtype=torch.float32, device=dev),
+                   loss_mean=torch.empty(1, dtype=torch.float32, device=dev),
+                   dX=torch.empty((B, D), dtype=torch.float32, device=dev),
+                   dW_active=torch.empty((M, D), dtype=torch.float32, device=dev) if need_dW else None)
+    if next_out is None:
+        next_out = dict(active_idx=active_idx, n_active=n_active, target_pos=target_pos)
+    ws = _ws(knn_softmax_selected_next_workspace(C, D, B, K, M), dev, ws)
+    dev_status = _status(dev, dev_status if dev_status is not None else out.get("dev_status"))
+    out["dev_status"], out["ws"] = dev_status, ws
+    rc = lib().knn_softmax_fwd_bwd_update_selected_next(
+        _ptr(W_master), _ptr(W_bf16), _ptr(X_bf16), _ptr(active_idx), _ptr(n_active), _ptr(target_pos), ct.c_int64(C),
+        ct.c_int(D), ct.c_int(B), ct.c_int(M), ct.c_float(scale), ct.c_float(grad_scale), ct.c_float(alpha),
+        ct.c_uint32(FLAG_UNIT_ROWS if unit_rows else 0), _ptr(out["loss_per_sample"]), _ptr(out["loss_mean"]), _ptr(out["dX"]),
+        _ptr(out.get("dW_active")), _ptr(labels_next), _ptr(graph), ct.c_int(K), _ptr(next_out["active_idx"]),
+        _ptr(next_out["n_active"]), _ptr(next_out["target_pos"]), _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status),
+        _stream(stream))
+    _check("knn_softmax_fwd_bwd_update_selected_next", rc)
+    return out, next_out
 
 
 def full_softmax_workspace(C, D, B) -> int:

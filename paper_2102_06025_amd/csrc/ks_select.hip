@@ -18,29 +18,7 @@
 #define SEL_SEG (SEL_NT * SEL_PER) /* classes per block in the table passes */
 #define SEL_NONE 0x7fffffff
 #define SEL_LDS_BINS 2048
-#define SEL1_MAX_WORDS_HOST 12288 /* classes / 32 up to which the single-workgroup path is used */
 
-// candidate at list position r of sample i (r = 0: the sample's own class), as an id in [0, C), or -1
-struct SelDense {
-    const int32_t *labels, *graph;
-    int64_t C;
-    int K;
-    static constexpr bool kForeignLabels = false; // a label this GPU does not own is an error
-    __device__ __forceinline__ int32_t cand(int i, int r, int32_t *dev_status) const {
-        const int32_t y = labels[i];
-        if (y < 0 || y >= C) {
-            if (r == 0) ks_flag(dev_status, KS_DEV_BAD_LABEL);
-            return -1;
-        }
-        if (r == 0) return y;
-        int32_t c = graph[(int64_t)y * K + (r - 1)];
-        if (c < -1 || c >= C) {
-            ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
-            c = -1;
-        }
-        return c;
-    }
-};
 struct SelCsr {
     const int32_t *labels, *counts;
     const int64_t *offsets;
@@ -73,36 +51,6 @@ struct SelCsr {
         return c;
     }
 };
-
-// k-th draw of the random fill-up: a keyed one-to-one map of [0, 2^b) onto itself (adding a constant, multiplying
-// by an odd constant and xor with a right shift of itself are each one-to-one on b-bit numbers), 2^b the smallest
-// power of two >= C.  Draws >= C or already in the set are passed over: a sample without replacement of the
-// classes not chosen (Algorithm 1 only says "random sample").
-struct SelPad {
-    int on, b;
-    uint32_t mask, s_lo, s_hi;
-};
-static SelPad sel_pad_make(int on, int64_t C, uint64_t seed) {
-    SelPad p;
-    p.on = on;
-    p.b = 1;
-    while (((int64_t)1 << p.b) < C) ++p.b;
-    p.mask = p.b >= 32 ? 0xFFFFFFFFu : ((1u << p.b) - 1u);
-    p.s_lo = (uint32_t)seed;
-    p.s_hi = (uint32_t)(seed >> 32);
-    return p;
-}
-__device__ __forceinline__ uint32_t sel_pad_draw(uint32_t k, const SelPad &p) {
-    const int s1 = (p.b + 1) >> 1, s2 = p.b / 3 > 0 ? p.b / 3 : 1;
-    uint32_t x = (k + p.s_lo) & p.mask;
-    x = (x * 0x9E3779B1u) & p.mask;
-    x ^= x >> s1;
-    x = (x * 0x85EBCA6Bu) & p.mask;
-    x ^= x >> s2;
-    x = (x * 0xC2B2AE35u) & p.mask;
-    x ^= x >> s1;
-    return (x + p.s_hi) & p.mask;
-}
 
 struct SelPlan {
     int r_star;    // classes with score < r_star are all kept
@@ -363,11 +311,6 @@ sel_finish_kernel(Src src, const int32_t *__restrict__ score, int B, int M, cons
 // write: the global stores and their latency are spread over several compute units with no
 // synchronisation between workgroups.
 // ------------------------------------------------------------------------------------------------
-#define SEL1_NT 1024
-#define SEL1_GRID 32
-#define SEL1_MAX_WORDS SEL1_MAX_WORDS_HOST
-#define SEL1_FIRST_WORDS 257 /* one bit per sample of batches up to 8,192 (+ one word so that a clear loop may run over) */
-
 // Stage 1 (many workgroups, so that the scattered reads of the neighbour lists are spread over the chip):
 // validated candidates, list-position-major: cand[r * B + i] = class at position r of sample i's list
 // (r = 0: the label itself), or -1 for an empty or invalid entry.
@@ -380,198 +323,13 @@ sel_fetch_kernel(Src src, int B, int K, int32_t *__restrict__ cand, int32_t *dev
     cand[(int64_t)r * B + i] = src.cand(i, r, dev_status);
 }
 
-// exclusive prefix over the words of a bitmap: pre[w] = number of set bits in words < w; returns the total
-__device__ __forceinline__ int sel1_prefix(const uint32_t *bm, int nw, int *pre, int *sh) {
-    const int per = (nw + SEL1_NT - 1) / SEL1_NT;
-    const int w0 = threadIdx.x * per;
-    int local = 0;
-    for (int w = w0; w < w0 + per && w < nw; ++w) local += __popc(bm[w]);
-    int total;
-    int run = ks_block_escan<SEL1_NT>(local, sh, &total);
-    for (int w = w0; w < w0 + per && w < nw; ++w) {
-        pre[w] = run;
-        run += __popc(bm[w]);
-    }
-    __syncthreads();
-    return total;
-}
-
 __global__ void __launch_bounds__(SEL1_NT)
 sel_single_kernel(const int32_t *__restrict__ cand, int64_t C, int B, int K, int M, int foreign_labels, SelPad pad,
                   int32_t *__restrict__ active_idx, int32_t *__restrict__ n_active, int32_t *__restrict__ n_found,
                   int32_t *__restrict__ target_pos) {
-    __shared__ uint32_t bm[SEL1_MAX_WORDS];
-    __shared__ uint32_t eq[SEL1_MAX_WORDS];
-    __shared__ int pre[SEL1_MAX_WORDS];
-    __shared__ int sh[SEL1_NT / 64 + 1];
-    __shared__ int s_new;
-    const int nw = (int)((C + 31) >> 5);
-    const int tid = threadIdx.x;
-    for (int w = tid; w < nw; w += SEL1_NT) bm[w] = 0u;
-    __syncthreads();
-    // optimistic pass: every candidate, whatever its list position (sixteen loads in flight per thread: the
-    // round trips to L2 are what this phase costs)
-    const int64_t n_cand = (int64_t)B * (K + 1);
-    const int64_t n_vec = n_cand >> 2; // the staging array is 256-byte aligned: whole 16-byte pieces, then a tail
-    // Samples with the same label have the same list, and with skewed labels half of the batch are repeats: only the
-    // first sample of a label (whichever thread marks the label first) has its list marked.  s_first holds one bit
-    // per sample; for batch sizes that are a power of two, so that a 16-byte piece of the staging array holds four
-    // samples of one list position and the sample index is a mask away.
-    __shared__ uint32_t s_first[SEL1_FIRST_WORDS];
-    const bool dedup = B >= 4 && (B & (B - 1)) == 0 && B <= SEL1_FIRST_WORDS * 32;
-    int64_t v_begin = 0;
-    if (dedup) {
-        for (int w = tid; w < B / 32 + 1; w += SEL1_NT) s_first[w] = 0u;
-        __syncthreads();
-        for (int i = tid; i < B; i += SEL1_NT) {
-            const int32_t c = cand[i]; // list position 0: the label (or -1: a class of another node, whose list still counts)
-            bool first = true;
-            if (c >= 0) first = !(atomicOr(&bm[c >> 5], 1u << (c & 31)) & (1u << (c & 31)));
-            if (first) atomicOr(&s_first[i >> 5], 1u << (i & 31));
-        }
-        __syncthreads();
-        v_begin = B >> 2; // the labels are done
-    }
-    for (int64_t t0 = v_begin; t0 < n_vec; t0 += (int64_t)SEL1_NT * 8) {
-        int4 c[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int64_t t = t0 + (int64_t)e * SEL1_NT + tid;
-            c[e] = t < n_vec ? ((const int4 *)cand)[t] : make_int4(-1, -1, -1, -1);
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            uint32_t f4 = 0xFu; // which of the four samples are the first of their label
-            if (dedup) {
-                const int i0 = (int)(((t0 + (int64_t)e * SEL1_NT + tid) << 2) & (B - 1));
-                f4 = s_first[i0 >> 5] >> (i0 & 31);
-            }
-            if (c[e].x >= 0 && (f4 & 1u)) atomicOr(&bm[c[e].x >> 5], 1u << (c[e].x & 31));
-            if (c[e].y >= 0 && (f4 & 2u)) atomicOr(&bm[c[e].y >> 5], 1u << (c[e].y & 31));
-            if (c[e].z >= 0 && (f4 & 4u)) atomicOr(&bm[c[e].z >> 5], 1u << (c[e].z & 31));
-            if (c[e].w >= 0 && (f4 & 8u)) atomicOr(&bm[c[e].w >> 5], 1u << (c[e].w & 31));
-        }
-    }
-    for (int64_t t = n_vec * 4 + tid; t < n_cand; t += SEL1_NT) {
-        const int32_t c = cand[t];
-        if (c >= 0) atomicOr(&bm[c >> 5], 1u << (c & 31));
-    }
-    __syncthreads();
-    int total = sel1_prefix(bm, nw, pre, sh);
-    if (total > M) {
-        // the cut bites: rebuild the bitmap in list-position order
-        for (int w = tid; w < nw; w += SEL1_NT) { bm[w] = 0u; eq[w] = 0u; }
-        __syncthreads();
-        int cum = 0, quota = 0;
-        for (int r = 0; r <= K; ++r) {
-            if (tid == 0) s_new = 0;
-            __syncthreads();
-            int local_new = 0;
-            for (int i = tid; i < B; i += SEL1_NT) {
-                const int c = cand[(int64_t)r * B + i];
-                if (c < 0) continue;
-                const uint32_t bit = 1u << (c & 31);
-                if (bm[c >> 5] & bit) continue; // already in with a better position
-                if (!(atomicOr(&eq[c >> 5], bit) & bit)) ++local_new;
-            }
-            local_new = ks_wave_sum_i(local_new);
-            if ((tid & 63) == 0 && local_new) atomicAdd(&s_new, local_new);
-            __syncthreads();
-            const int total_new = s_new;
-            if (cum + total_new > M) { // classes first seen at position r do not all fit: r is the cut score
-                quota = M - cum;
-                break;
-            }
-            for (int i = tid; i < B; i += SEL1_NT) { // commit position r
-                const int c = cand[(int64_t)r * B + i];
-                if (c < 0) continue;
-                const uint32_t bit = 1u << (c & 31);
-                if (eq[c >> 5] & bit) {
-                    atomicOr(&bm[c >> 5], bit);
-                    atomicAnd(&eq[c >> 5], ~bit);
-                }
-            }
-            cum += total_new;
-            __syncthreads();
-        }
-        // eq holds the classes whose best position is the cut score; the `quota` lowest ids of them are kept
-        sel1_prefix(eq, nw, pre, sh);
-        const int per = (nw + SEL1_NT - 1) / SEL1_NT;
-        for (int w = tid * per; w < tid * per + per && w < nw; ++w) {
-            uint32_t e = eq[w], keep = 0u;
-            int left = quota - pre[w];
-            while (left > 0 && e) {
-                keep |= e & (0u - e);
-                e &= e - 1;
-                --left;
-            }
-            bm[w] |= keep;
-        }
-        __syncthreads();
-        total = sel1_prefix(bm, nw, pre, sh);
-    }
-    const int found = total < M ? total : M;
-    const int64_t want = M < C ? M : C;
-    if (pad.on && total < want) {
-        // random fill-up: the first draws that are classes of this GPU and not in the bitmap yet (the draws are
-        // distinct, so marking one cannot change the test of another)
-        const int need = (int)(want - total);
-        const uint32_t n_draws = 1u << pad.b; // b <= 19 here
-        int got = 0;
-        for (uint32_t k0 = 0; got < need && k0 < n_draws; k0 += SEL1_NT * 8) {
-            uint32_t cs[8];
-            int valid = 0;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t k = k0 + (uint32_t)tid * 8 + e;
-                const uint32_t c = k < n_draws ? sel_pad_draw(k, pad) : 0xFFFFFFFFu;
-                cs[e] = (c < (uint64_t)C && !(bm[c >> 5] & (1u << (c & 31)))) ? c : 0xFFFFFFFFu;
-                valid += cs[e] != 0xFFFFFFFFu;
-            }
-            int tot;
-            int ex = ks_block_escan<SEL1_NT>(valid, sh, &tot);
-            const int room = need - got;
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                if (cs[e] != 0xFFFFFFFFu) {
-                    if (ex < room) atomicOr(&bm[cs[e] >> 5], 1u << (cs[e] & 31));
-                    ++ex;
-                }
-            got += tot < room ? tot : room;
-            __syncthreads();
-        }
-        total = sel1_prefix(bm, nw, pre, sh);
-    }
-    // Every workgroup of the grid has built the same bitmap and prefix (redundantly: it is LDS work, and it
-    // spares a grid-wide synchronisation); each writes its share of the outputs.
-    const int G = gridDim.x, g = blockIdx.x;
-    { // read the bitmap out in ascending order: this workgroup's slice of the words, one word per thread
-        const int per_g = (nw + G - 1) / G;
-        const int w_end = (g + 1) * per_g < nw ? (g + 1) * per_g : nw;
-        for (int w = g * per_g + tid; w < w_end; w += SEL1_NT) {
-            uint32_t e = bm[w];
-            int pos = pre[w];
-            while (e) {
-                const int b = __ffs(e) - 1;
-                if (pos < M) active_idx[pos] = w * 32 + b; // pos < M always holds; the test keeps the store in bounds
-                ++pos;
-                e &= e - 1;
-            }
-        }
-    }
-    const int n = total < M ? total : M;
-    for (int a = n + g * SEL1_NT + tid; a < M; a += G * SEL1_NT) active_idx[a] = -1;
-    const int none = foreign_labels ? -1 : 0; // in range even for broken inputs (those are flagged)
-    for (int i = g * SEL1_NT + tid; i < B; i += G * SEL1_NT) {
-        const int32_t y = cand[i]; // list position 0: the sample's own class, -1 if it is not one of this GPU's
-        int p = none;
-        if (y >= 0 && y < C) p = pre[y >> 5] + __popc(bm[y >> 5] & ((1u << (y & 31)) - 1u));
-        target_pos[i] = (p >= 0 && p < n) ? p : none;
-    }
-    if (g == 0 && tid == 0) {
-        *n_active = n;
-        if (n_found) *n_found = found;
-    }
+    __shared__ uint32_t lds[sel1_lds_words(SEL1_NT)];
+    sel1_body<SEL1_NT>(lds, cand, C, B, K, M, foreign_labels, pad, active_idx, n_active, n_found, target_pos, (int)gridDim.x,
+                       (int)blockIdx.x);
 }
 
 template <class Src>

@@ -977,12 +977,16 @@ template <class T>
 __global__ void __launch_bounds__(T::NT)
 dx_partial_async_kernel(const uint16_t *__restrict__ dZT, int Bp, int64_t Mp, const uint16_t *__restrict__ W,
                         const int32_t *__restrict__ active_idx, const int32_t *__restrict__ n_active_p, int B, int D, int M,
-                        int S, float *__restrict__ part) {
+                        int S, float *__restrict__ part, KsSelNext next) {
     __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
     __shared__ int32_t s_idx[DX_IDX_CACHE];
     const int n_active = sm_clamp_n(n_active_p, M);
     const int tiles_m = (B + T::BM - 1) / T::BM, tiles_n = (D + T::BN - 1) / T::BN;
     const int n_tiles = tiles_m * tiles_n;
+    if ((int)blockIdx.x >= n_tiles * S) { // blocks behind the tiles: the next batch's candidates are staged (if asked for)
+        ks_sel_next_fetch<T::NT>(next, (int)blockIdx.x - n_tiles * S);
+        return;
+    }
     const int L = ks_xcd_remap(blockIdx.x, n_tiles * S);
     const int s = L / n_tiles, t = L % n_tiles;
     const int tm = t % tiles_m, tn = t / tiles_m;
@@ -1074,20 +1078,31 @@ __device__ __forceinline__ int dw_tile_rows(int n_active, int tiles_n, int n_cu)
 }
 
 template <class T>
-__device__ __forceinline__ void dw_tile(uint16_t *lds, const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X, int B,
+__device__ __forceinline__ void dw_tile(int bid, uint16_t *lds, const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X, int B,
                                         int Bp, int n_active, int D, int64_t Mp, float scale, float *__restrict__ dW,
                                         const DwUpdate &up);
 
 __global__ void __launch_bounds__(TileDw::NT)
 dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X, int B, int Bp,
                 const int32_t *__restrict__ n_active_p, int D, int M, int64_t Mp, float scale, float *__restrict__ dW,
-                int tiles_max, int n_cu, DxReduceJob job, DwUpdate up) {
+                int tiles_max, int n_cu, DxReduceJob job, DwUpdate up, KsSelNext next) {
     typedef TileDw T;
     static_assert(TileDw192::NT == T::NT && TileDw128::NT == T::NT && TileDw192::LDS_ELEMS <= T::LDS_ELEMS &&
                       TileDw128::LDS_ELEMS <= T::LDS_ELEMS, "one launch shape for all tile heights");
-    __shared__ __attribute__((aligned(16))) uint16_t lds[T::LDS_ELEMS];
-    if ((int)blockIdx.x >= tiles_max) { // reduction blocks
-        const int rb = blockIdx.x - tiles_max, nrb = gridDim.x - tiles_max;
+    constexpr int LDS_ELEMS = T::LDS_ELEMS > 2 * sel1_lds_words(T::NT) ? T::LDS_ELEMS : 2 * sel1_lds_words(T::NT);
+    __shared__ __attribute__((aligned(16))) uint16_t lds[LDS_ELEMS];
+    // The first next.nsel workgroups select the NEXT batch's active classes (Algorithm 1 needs only its labels): with a
+    // few hundred tiles this launch leaves compute units idle, and being first they start at once.
+    const int bid = (int)blockIdx.x - next.nsel;
+    if (bid < 0) {
+        SelPad none;
+        none.on = 0; none.b = 1; none.mask = 1u; none.s_lo = none.s_hi = 0u;
+        sel1_body<T::NT>((uint32_t *)lds, next.cand, next.src.C, next.B, next.K, next.M, 0, none, next.active_idx, next.n_active,
+                         nullptr, next.target_pos, next.nsel, (int)blockIdx.x);
+        return;
+    }
+    if (bid >= tiles_max) { // reduction blocks
+        const int rb = bid - tiles_max, nrb = (int)gridDim.x - next.nsel - tiles_max;
         for (int64_t e = ((int64_t)rb * T::NT + threadIdx.x) * 4; e < job.BD; e += (int64_t)nrb * T::NT * 4) {
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
             for (int sp = 0; sp < job.S; ++sp) {
@@ -1113,19 +1128,19 @@ dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X
     }
     const int n_active = sm_clamp_n(n_active_p, M);
     const int rows = dw_tile_rows(n_active, (D + T::BN - 1) / T::BN, n_cu);
-    if (rows == 256) dw_tile<TileDw>(lds, dZT, X, B, Bp, n_active, D, Mp, scale, dW, up);
-    else if (rows == 192) dw_tile<TileDw192>(lds, dZT, X, B, Bp, n_active, D, Mp, scale, dW, up);
-    else dw_tile<TileDw128>(lds, dZT, X, B, Bp, n_active, D, Mp, scale, dW, up);
+    if (rows == 256) dw_tile<TileDw>(bid, lds, dZT, X, B, Bp, n_active, D, Mp, scale, dW, up);
+    else if (rows == 192) dw_tile<TileDw192>(bid, lds, dZT, X, B, Bp, n_active, D, Mp, scale, dW, up);
+    else dw_tile<TileDw128>(bid, lds, dZT, X, B, Bp, n_active, D, Mp, scale, dW, up);
 }
 
 template <class T>
-__device__ __forceinline__ void dw_tile(uint16_t *lds, const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X, int B,
+__device__ __forceinline__ void dw_tile(int bid, uint16_t *lds, const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X, int B,
                                         int Bp, int n_active, int D, int64_t Mp, float scale, float *__restrict__ dW,
                                         const DwUpdate &up) {
     const int tiles_n = (D + T::BN - 1) / T::BN;
     const int n_tiles = tiles_n * ((n_active + T::BM - 1) / T::BM);
-    if ((int)blockIdx.x >= n_tiles) return;
-    const int t = ks_xcd_remap(blockIdx.x, n_tiles);
+    if (bid >= n_tiles) return;
+    const int t = ks_xcd_remap(bid, n_tiles);
     const int tn = t % tiles_n, tm = t / tiles_n;
     KsARows<T::BM, T::NW> ar;
     KsAKmaj<T::BN, T::NW> br;
@@ -1357,8 +1372,10 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
                   const int32_t *active_idx, const int32_t *n_active, const int32_t *target_pos,
                   float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, const SmWs &w,
                   uint32_t flags, int32_t *dev_status, hipStream_t st, hipEvent_t *ev = nullptr, int mode = SM_WHOLE,
-                  SmSplitIO io = SmSplitIO(), DwUpdate up = DwUpdate()) {
+                  SmSplitIO io = SmSplitIO(), DwUpdate up = DwUpdate(), const KsSelNext *next_p = nullptr) {
     auto mark = [&](int k) { if (ev) (void)hipEventRecord(ev[k], st); };
+    KsSelNext next = KsSelNext();
+    if (next_p) next = *next_p; // (the caller has checked that this path takes it: w.fast and a whole step)
     if (mode != SM_WHOLE && !w.fast) return KS_UNSUPPORTED;
     if (mode == SM_EXPORT) loss_per_sample = w.inv; // not known before the exchange: the kernels' loss output is scratch
     const int Mi = (int)M;
@@ -1440,8 +1457,9 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
         {
             typedef TileDx T;
             const int tiles = (int)(ks_ceil_div(B, T::BM) * ks_ceil_div(D, T::BN));
-            hipLaunchKernelGGL(dx_partial_async_kernel<T>, dim3(tiles * w.S), dim3(T::NT), 0, st, w.dZT, w.Bp, w.Mp, W,
-                               active_idx, n_active, B, D, Mi, w.S, w.part);
+            if (next.nsel) next.nfetch = (int)ks_ceil_div((int64_t)next.B * (next.K + 1), (int64_t)T::NT);
+            hipLaunchKernelGGL(dx_partial_async_kernel<T>, dim3(tiles * w.S + next.nfetch), dim3(T::NT), 0, st, w.dZT, w.Bp,
+                               w.Mp, W, active_idx, n_active, B, D, Mi, w.S, w.part, next);
         }
         mark(5);
         mark(6); // the reduction of the partial products rides along with the next launch
@@ -1457,8 +1475,9 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
             job.dX = dX;
             job.loss_i = loss_per_sample;
             job.loss_mean = loss_mean;
-            hipLaunchKernelGGL(dw_async_kernel, dim3(tiles + DW_REDUCE_BLOCKS), dim3(T::NT), 0, st, w.dZT, fused ? w.X2 : X, B,
-                               w.Bp, n_active, D, Mi, w.Mp, fused ? scale * g : scale, dW_active, tiles, ks_n_cu(), job, up);
+            hipLaunchKernelGGL(dw_async_kernel, dim3(next.nsel + tiles + DW_REDUCE_BLOCKS), dim3(T::NT), 0, st, w.dZT,
+                               fused ? w.X2 : X, B, w.Bp, n_active, D, Mi, w.Mp, fused ? scale * g : scale, dW_active, tiles,
+                               ks_n_cu(), job, up, next);
         }
         mark(7);
         KS_LAUNCH_CHECK();
@@ -1669,20 +1688,32 @@ extern "C" size_t knn_softmax_selected_workspace(int64_t C, int D, int B, int M)
     sm_split_carve(nullptr, C, D, B, M, &total);
     return total;
 }
-extern "C" int knn_softmax_fwd_bwd_update_selected(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16,
-                                                   const int32_t *active_idx, const int32_t *n_active,
-                                                   const int32_t *target_pos, int64_t C, int D, int B, int M, float scale,
-                                                   float grad_scale, float alpha, uint32_t flags, float *loss_per_sample,
-                                                   float *loss_mean, float *dX, float *dW_active, void *ws, size_t ws_bytes,
-                                                   int32_t *dev_status, void *stream) {
+// the next batch's selection that rides along with a step on a given selection (nullptr: none)
+struct SmNextArgs {
+    const int32_t *labels, *graph;
+    int K;
+    int32_t *active_idx, *n_active, *target_pos;
+};
+static int sm_selected(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *active_idx,
+                       const int32_t *n_active, const int32_t *target_pos, int64_t C, int D, int B, int M, float scale,
+                       float grad_scale, float alpha, uint32_t flags, float *loss_per_sample, float *loss_mean, float *dX,
+                       float *dW_active, const SmNextArgs *nx, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream) {
     if (!W_bf16 || !X_bf16 || !active_idx || !n_active || !target_pos || !loss_per_sample || !loss_mean || !dX || !ws)
         return KS_INVALID_ARG;
     if (sm_selected_check(C, D, B, M) != KS_OK) return KS_INVALID_ARG;
     if (flags & ~(uint32_t)KS_FLAG_UNIT_ROWS) return KS_INVALID_ARG;
     const bool fast = D % 64 == 0;
     if (!dW_active && !(W_master && fast)) return KS_INVALID_ARG;
+    if (nx) {
+        if (!nx->labels || !nx->active_idx || !nx->n_active || !nx->target_pos || nx->K < 0 || (nx->K > 0 && !nx->graph))
+            return KS_INVALID_ARG;
+        if ((int64_t)nx->K + 1 > M) return KS_INVALID_ARG;
+    }
     size_t need = 0;
     SmSplitWs s = sm_split_carve(ws, C, D, B, M, &need);
+    if (nx) need = ks_align_up(need, 256);
+    void *sel_ws = (char *)ws + need; // the selection's staging area follows the step's buffers
+    if (nx) need += ks_select_ws_bytes(C, B, nx->K);
     if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
     const int nmax = M > B ? M : B;
@@ -1695,10 +1726,59 @@ extern "C" int knn_softmax_fwd_bwd_update_selected(float *W_master, uint16_t *W_
         up.idx = s.act;
         up.alpha = alpha;
     }
+    // The selection rides along with the dX and dW launches where those exist (D a multiple of 64) and the class bitmap
+    // fits in LDS; otherwise it follows the step as launches of its own.  Either way it starts after the sanitised copy
+    // of this step's list has been made, so its outputs may be the buffers this step's list came in.
+    KsSelNext next = KsSelNext();
+    const bool ride = nx && fast && C <= (int64_t)SEL1_MAX_WORDS * 32;
+    if (ride) {
+        next.nsel = SEL1_GRID;
+        next.src = SelDense{nx->labels, nx->graph, C, nx->K};
+        next.B = B;
+        next.K = nx->K;
+        next.M = M;
+        next.cand = (int32_t *)sel_ws;
+        next.active_idx = nx->active_idx;
+        next.n_active = nx->n_active;
+        next.target_pos = nx->target_pos;
+        next.dev_status = dev_status;
+    }
     int rc = sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, s.act, s.n, s.tp, loss_per_sample, loss_mean, dX, dW_active,
-                    s.w, flags, dev_status, st, nullptr, SM_WHOLE, SmSplitIO(), up);
-    if (rc != KS_OK || !W_master || fast) return rc;
-    return apply_weight_grad(W_master, W_bf16, s.act, s.n, M, dW_active, alpha, C, D, 1, ws, ws_bytes, dev_status, stream);
+                    s.w, flags, dev_status, st, nullptr, SM_WHOLE, SmSplitIO(), up, ride ? &next : nullptr);
+    if (rc == KS_OK && W_master && !fast)
+        rc = apply_weight_grad(W_master, W_bf16, s.act, s.n, M, dW_active, alpha, C, D, 1, ws, ws_bytes, dev_status, stream);
+    if (rc == KS_OK && nx && !ride)
+        rc = ks_select_launch(nx->labels, nx->graph, C, B, nx->K, M, nx->active_idx, nx->n_active, nx->target_pos, sel_ws,
+                              dev_status, st);
+    return rc;
+}
+extern "C" int knn_softmax_fwd_bwd_update_selected(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16,
+                                                   const int32_t *active_idx, const int32_t *n_active,
+                                                   const int32_t *target_pos, int64_t C, int D, int B, int M, float scale,
+                                                   float grad_scale, float alpha, uint32_t flags, float *loss_per_sample,
+                                                   float *loss_mean, float *dX, float *dW_active, void *ws, size_t ws_bytes,
+                                                   int32_t *dev_status, void *stream) {
+    return sm_selected(W_master, W_bf16, X_bf16, active_idx, n_active, target_pos, C, D, B, M, scale, grad_scale, alpha, flags,
+                       loss_per_sample, loss_mean, dX, dW_active, nullptr, ws, ws_bytes, dev_status, stream);
+}
+extern "C" size_t knn_softmax_selected_next_workspace(int64_t C, int D, int B, int K, int M) {
+    if (sm_selected_check(C, D, B, M) != KS_OK || K < 0) return 0;
+    size_t total = 0;
+    sm_split_carve(nullptr, C, D, B, M, &total);
+    return ks_align_up(total, 256) + ks_select_ws_bytes(C, B, K);
+}
+extern "C" int knn_softmax_fwd_bwd_update_selected_next(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16,
+                                                        const int32_t *active_idx, const int32_t *n_active,
+                                                        const int32_t *target_pos, int64_t C, int D, int B, int M,
+                                                        float scale, float grad_scale, float alpha, uint32_t flags,
+                                                        float *loss_per_sample, float *loss_mean, float *dX,
+                                                        float *dW_active, const int32_t *labels_next, const int32_t *graph,
+                                                        int K, int32_t *active_idx_next, int32_t *n_active_next,
+                                                        int32_t *target_pos_next, void *ws, size_t ws_bytes,
+                                                        int32_t *dev_status, void *stream) {
+    SmNextArgs nx{labels_next, graph, K, active_idx_next, n_active_next, target_pos_next};
+    return sm_selected(W_master, W_bf16, X_bf16, active_idx, n_active, target_pos, C, D, B, M, scale, grad_scale, alpha, flags,
+                       loss_per_sample, loss_mean, dX, dW_active, &nx, ws, ws_bytes, dev_status, stream);
 }
 
 extern "C" size_t full_softmax_workspace(int64_t C, int D, int B) {

@@ -23,14 +23,15 @@ def ks():
 def _declared_functions():
     src = open(HEADER).read() + open(os.path.join(ROOT, "include", "grad_topk.h")).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(ks_version|ks_peak_mfma|ks_peak_copy|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update|_stats|_profiled|_plan|_select|_static|_selected))\s*\(", src)))
+    return sorted(set(re.findall(r"\b(ks_version|ks_peak_mfma|ks_peak_copy|[a-z_]+(?:_workspace|_build|_active|_rows|_fwd_bwd|_grad|_normalized|_csr|_compress|_update|_stats|_profiled|_plan|_select|_static|_selected|_next))\s*\(", src)))
 
 
 def test_header_symbols_are_exported(ks):
     names = _declared_functions()
     assert {"knn_graph_build", "knn_softmax_fwd_bwd", "apply_weight_grad", "apply_weight_grad_normalized",
             "knn_normalize_rows", "knn_norm_backward_rows", "grad_topk_plan", "grad_topk_workspace",
-            "grad_topk_select", "knn_select_active_static"} <= set(names)
+            "grad_topk_select", "knn_select_active_static", "knn_softmax_fwd_bwd_update_selected_next",
+            "knn_softmax_selected_next_workspace"} <= set(names)
     L = ks.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in the header but not exported"

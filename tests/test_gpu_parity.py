@@ -636,6 +636,60 @@ def test_step_on_an_earlier_selection_equals_the_one_call_step(ks, orc, name, un
     assert torch.equal(c["dW_active"][:A], d["dW_active"][:A]) and torch.equal(c["dX"], d["dX"])
 
 
+@pytest.mark.parametrize("name,shape,unit_rows,in_place", [
+    ("small", None, True, True), ("small", None, False, False), ("tiny", None, True, False),
+    ("the cut bites", dict(C=20_000, D=128, B=128, K=16, M=700, labels="zipf"), True, True),
+    ("D = 96", dict(C=5_000, D=96, B=70, K=9, M=300), False, False),
+    ("the table path", dict(C=400_000, D=128, B=64, K=8, M=1_024), True, True)])
+def test_selection_of_the_next_batch_rides_along_with_the_step(ks, orc, name, shape, unit_rows, in_place):
+    """A loop of knn_softmax_fwd_bwd_update_selected_next calls (the step on this batch's list, the next batch's list
+    made by extra workgroups of the same launches) against a loop of one-call steps on the same batches: every
+    batch's active list, target positions, losses and dX, and the weights after the last step, bit for bit.  With the
+    list buffers reused in place and with separate ones; D a multiple of 64 (the selection rides along) and not, and
+    more classes than one workgroup's bitmap holds (then it follows the step); a batch whose lists exceed M."""
+    cfg = dict(synth.CONFIGS["tiny"], **shape) if shape else synth.CONFIGS[name]
+    C, D, B, K, M, scale = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"], cfg["scale"]
+    W, X = synth.make_WX(cfg)
+    W = synth.bf16_round(W)
+    G = synth.graph_synthetic(cfg["seed"], C, K)
+    gs, alpha = 64.0, -0.03 / 64.0
+    Xb, Gd = dev(synth.bf16_round(X), torch.bfloat16), dev(G)
+    n_steps = 4
+    ys = [dev(synth.make_labels(cfg, seed=cfg["seed"] + 17 * t)) for t in range(n_steps + 1)]
+    # reference: one-call steps
+    Wm1, Wb1 = dev(W), dev(W, torch.bfloat16)
+    ref = []
+    for t in range(n_steps):
+        a = ks.knn_softmax_fwd_bwd_update(Wm1, Wb1, Xb, ys[t], Gd, M, scale, gs, alpha, unit_rows=unit_rows)
+        torch.cuda.synchronize()
+        assert int(a["dev_status"].item()) == 0
+        ref.append({k: a[k].clone() for k in ("active_idx", "n_active", "target_pos", "loss_per_sample", "loss_mean", "dX")})
+    # the loop under test
+    Wm2, Wb2 = dev(W), dev(W, torch.bfloat16)
+    act, n, tp, st = ks.knn_select_active(ys[0], Gd, C, M)
+    cur = dict(active_idx=act, n_active=n, target_pos=tp)
+    spare = dict(active_idx=torch.empty_like(act), n_active=torch.empty_like(n), target_pos=torch.empty_like(tp))
+    for t in range(n_steps):
+        print(f"[case] {name}: step {t} with the selection of batch {t + 1} riding along", flush=True)
+        torch.cuda.synchronize()
+        assert torch.equal(cur["active_idx"], ref[t]["active_idx"]) and torch.equal(cur["n_active"], ref[t]["n_active"])
+        assert torch.equal(cur["target_pos"], ref[t]["target_pos"])
+        b, nxt = ks.knn_softmax_fwd_bwd_update_selected_next(Wm2, Wb2, Xb, cur["active_idx"], cur["n_active"], cur["target_pos"],
+                                                             ys[t + 1], Gd, scale, gs, alpha,
+                                                             next_out=None if in_place else spare, unit_rows=unit_rows)
+        torch.cuda.synchronize()
+        assert int(b["dev_status"].item()) == 0
+        assert torch.equal(b["loss_per_sample"], ref[t]["loss_per_sample"]) and torch.equal(b["loss_mean"], ref[t]["loss_mean"])
+        assert torch.equal(b["dX"], ref[t]["dX"])
+        if not in_place:
+            cur, spare = nxt, cur
+    assert torch.equal(Wm1, Wm2) and torch.equal(Wb1, Wb2) and int(st.item()) == 0
+    # the list left by the last call is the one of the batch after it
+    act_l, n_l, tp_l, _ = ks.knn_select_active(ys[n_steps], Gd, C, M)
+    torch.cuda.synchronize()
+    assert torch.equal(cur["active_idx"], act_l) and torch.equal(cur["n_active"], n_l) and torch.equal(cur["target_pos"], tp_l)
+
+
 def test_step_on_a_broken_selection_is_flagged_and_stays_in_bounds(ks):
     C, D, B, M = 1000, 128, 16, 64
     W = torch.randn(C, D, device="cuda")
