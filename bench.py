@@ -203,8 +203,10 @@ class StepRunner:
         self.next_inside = bool(next_inside and fused_update)
         if self.next_inside:
             self.ws_next = torch.empty(ks.knn_softmax_selected_next_workspace(C, D, B, K, M), dtype=torch.uint8, device="cuda")
-            # the list of the first batch; every call leaves the next batch's list in the same buffers
+            # the list of the first batch; every call reads one set of buffers in place (they are the library's own
+            # output: KS_FLAG_TRUSTED_LIST) and leaves the next batch's list in the other
             self.sel = {k: self.out[k].clone() for k in ("active_idx", "n_active", "target_pos")}
+            self.sel_other = {k: self.out[k].clone() for k in ("active_idx", "n_active", "target_pos")}
             self.out_next = {k: self.out[k] for k in ("loss_per_sample", "loss_mean", "dX", "dev_status")}
             self.out_next["dW_active"] = None
 
@@ -219,8 +221,10 @@ class StepRunner:
         if ev is None and self.next_inside:
             ks.knn_softmax_fwd_bwd_update_selected_next(self.W_master, self.W_bf, self.X_bf, self.sel["active_idx"],
                                                         self.sel["n_active"], self.sel["target_pos"], self.labels, self.graph,
-                                                        self.scale, self.grad_scale, self.alpha, out=self.out_next,
-                                                        ws=self.ws_next, unit_rows=self.unit_rows)
+                                                        self.scale, self.grad_scale, self.alpha, next_out=self.sel_other,
+                                                        out=self.out_next, ws=self.ws_next, unit_rows=self.unit_rows,
+                                                        trusted_list=True)
+            self.sel, self.sel_other = self.sel_other, self.sel
             return
         if ev is None and self.fused:
             ks.knn_softmax_fwd_bwd_update(self.W_master, self.W_bf, self.X_bf, self.labels, self.graph, M, self.scale,
@@ -790,7 +794,8 @@ def main():
         "config": {"workload": f"{args.workload}: C={C} D={D} B={B} K={K} M={M} labels={cfg['labels']} s={scale}",
                    "active_classes": A,
                    "step": ("knn_softmax_fwd_bwd_update_selected_next, one call per step: fwd/bwd + weight update of batch n and "
-                            "the selection (Algorithm 1) of batch n + 1 in the same launches; the one-call step that selects "
+                            "the selection (Algorithm 1) of batch n + 1 in the same launches, the list read in place from the "
+                            "buffers the previous call wrote (KS_FLAG_TRUSTED_LIST); the one-call step that selects "
                             "its own batch first is selection_variants.serial_ms_per_step") if next_inside
                    else ("knn_softmax_fwd_bwd_update (select + fwd/bwd + weight update in one call)" if fused_update
                          else "select + knn_softmax_fwd_bwd + apply_weight_grad"),

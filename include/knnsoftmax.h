@@ -51,6 +51,9 @@ typedef enum {
 /* bits of the `flags` argument of the softmax entry points */
 #define KS_FLAG_UNIT_ROWS 1u        /* every row of W_bf16 and X_bf16 has L2 norm <= 1 (up to rounding) */
 #define KS_FLAG_PAD_RANDOM 2u       /* knn_select_active_csr: fill the active list up to M with randomly drawn classes */
+#define KS_FLAG_TRUSTED_LIST 4u     /* knn_softmax_fwd_bwd_update_selected(_next): the list is the unmodified output of this
+                                       library's selection for the same C and M; it is used where it lies, without the
+                                       validating copy (a broken promise may read outside W) */
 
 #define KS_DTYPE_BF16 0
 #define KS_DTYPE_FP32 1
@@ -197,6 +200,9 @@ int knn_softmax_fwd_bwd_update(float *W_master, uint16_t *W_bf16, const uint16_t
  * [0, M] KS_DEV_BAD_COUNT, target positions at or beyond the count KS_DEV_BAD_LABEL; the outputs are then
  * unspecified, but every access stays in bounds.  Target positions must lie in [0, *n_active), as the selection
  * on a GPU that owns all classes produces them (a node of a sharded layer uses the split-softmax calls below).
+ * With KS_FLAG_TRUSTED_LIST the caller promises that the three arrays are what knn_select_active (or the _next call
+ * below) wrote for this C and M, unmodified: they are then read in place, nothing is validated or copied (one small
+ * launch less), and ids out of range would be read out of bounds.
  * Requires D % 32 == 0, B <= M. */
 size_t knn_softmax_selected_workspace(int64_t C, int D, int B, int M);
 int knn_softmax_fwd_bwd_update_selected(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16,
@@ -214,7 +220,9 @@ int knn_softmax_fwd_bwd_update_selected(float *W_master, uint16_t *W_bf16, const
  *   labels_next [B] int32, graph [C, K] int32        in (device): the next batch's labels; the graph as in knn_select_active
  *   active_idx_next [M], n_active_next [1], target_pos_next [B]   out (device): exactly what knn_select_active writes for
  *                       labels_next (bit for bit).  They MAY be the buffers this call's active_idx / n_active /
- *                       target_pos came in: the call copies its own list before the selection starts.
+ *                       target_pos came in: the call copies its own list before the selection starts (not with
+ *                       KS_FLAG_TRUSTED_LIST, which reads the list in place: then they must be other buffers, else
+ *                       KS_INVALID_ARG -- a loop alternates between two sets).
  *   everything else     as in knn_softmax_fwd_bwd_update_selected, with the same results bit for bit
  * Requires K + 1 <= M besides that call's conditions.  When D is not a multiple of 64, or C exceeds the 393,216 classes
  * whose bitmap one workgroup holds, the selection runs after the step as launches of its own (same results).

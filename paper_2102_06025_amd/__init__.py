@@ -2,7 +2,7 @@
 C-ABI library `libknnsoftmax.so` (hand-written HIP for gfx950).  See include/knnsoftmax.h for the contract
 of every call; this package only marshals arguments (torch tensors provide device memory and streams)."""
 from . import binding  # noqa: F401
-from .binding import (KS_DEV_RANGE, FLAG_UNIT_ROWS, FLAG_PAD_RANDOM, knn_graph_compress, knn_select_active_csr, knn_graph_update,
+from .binding import (KS_DEV_RANGE, FLAG_UNIT_ROWS, FLAG_PAD_RANDOM, FLAG_TRUSTED_LIST, knn_graph_compress, knn_select_active_csr, knn_graph_update,
                       knn_graph_update_workspace, knn_softmax_bwd_from_stats, knn_softmax_fwd_stats, knn_softmax_fwd_bwd_update,
                       knn_softmax_fwd_bwd_update_selected, knn_softmax_selected_workspace,
                       knn_softmax_fwd_bwd_update_selected_next, knn_softmax_selected_next_workspace,

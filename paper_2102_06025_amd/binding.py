@@ -207,6 +207,7 @@ def knn_softmax_workspace(C, D, B, K, M) -> int:
 
 
 FLAG_UNIT_ROWS = 1  # KS_FLAG_UNIT_ROWS
+FLAG_TRUSTED_LIST = 4  # KS_FLAG_TRUSTED_LIST
 
 
 def knn_softmax_fwd_bwd(W_bf16, X_bf16, labels, graph, M, scale, grad_scale=1.0, out=None, ws=None,
@@ -290,7 +291,8 @@ def knn_softmax_selected_workspace(C, D, B, M) -> int:
 
 
 def knn_softmax_fwd_bwd_update_selected(W_master, W_bf16, X_bf16, active_idx, n_active, target_pos, scale, grad_scale, alpha,
-                                        out=None, ws=None, dev_status=None, stream=None, unit_rows=False, want_dW=False):
+                                        out=None, ws=None, dev_status=None, stream=None, unit_rows=False, want_dW=False,
+                                        trusted_list=False):
     """The step on a selection computed earlier by knn_select_active (W_master may be None: no update, dW_active is
     then returned).  Returns dict(loss_per_sample, loss_mean, dX, dW_active or None, dev_status, ws)."""
     _need(W_bf16, torch.bfloat16, "W_bf16")
@@ -314,7 +316,8 @@ def knn_softmax_fwd_bwd_update_selected(W_master, W_bf16, X_bf16, active_idx, n_
     rc = lib().knn_softmax_fwd_bwd_update_selected(_ptr(W_master), _ptr(W_bf16), _ptr(X_bf16), _ptr(active_idx), _ptr(n_active),
                                                    _ptr(target_pos), ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(M),
                                                    ct.c_float(scale), ct.c_float(grad_scale), ct.c_float(alpha),
-                                                   ct.c_uint32(FLAG_UNIT_ROWS if unit_rows else 0), _ptr(out["loss_per_sample"]),
+                                                   ct.c_uint32((FLAG_UNIT_ROWS if unit_rows else 0) | (FLAG_TRUSTED_LIST if trusted_list else 0)),
+                                                   _ptr(out["loss_per_sample"]),
                                                    _ptr(out["loss_mean"]), _ptr(out["dX"]), _ptr(out.get("dW_active")), _ptr(ws),
                                                    ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
     _check("knn_softmax_fwd_bwd_update_selected", rc)
@@ -327,10 +330,10 @@ def knn_softmax_selected_next_workspace(C, D, B, K, M) -> int:
 
 def knn_softmax_fwd_bwd_update_selected_next(W_master, W_bf16, X_bf16, active_idx, n_active, target_pos, labels_next, graph,
                                              scale, grad_scale, alpha, next_out=None, out=None, ws=None, dev_status=None,
-                                             stream=None, unit_rows=False, want_dW=False):
+                                             stream=None, unit_rows=False, want_dW=False, trusted_list=False):
     """The step on a given selection, and in the same launches the selection of the next batch (labels_next).
     next_out: dict(active_idx, n_active, target_pos) to write the next selection to (None: this call's own list
-    buffers are reused).  Returns (out, next_out)."""
+    buffers are reused; not with trusted_list, which reads the list in place).  Returns (out, next_out)."""
     _need(W_bf16, torch.bfloat16, "W_bf16")
     _need(X_bf16, torch.bfloat16, "X_bf16")
     _need(active_idx, torch.int32, "active_idx")
@@ -356,7 +359,8 @@ def knn_softmax_fwd_bwd_update_selected_next(W_master, W_bf16, X_bf16, active_id
     rc = lib().knn_softmax_fwd_bwd_update_selected_next(
         _ptr(W_master), _ptr(W_bf16), _ptr(X_bf16), _ptr(active_idx), _ptr(n_active), _ptr(target_pos), ct.c_int64(C),
         ct.c_int(D), ct.c_int(B), ct.c_int(M), ct.c_float(scale), ct.c_float(grad_scale), ct.c_float(alpha),
-        ct.c_uint32(FLAG_UNIT_ROWS if unit_rows else 0), _ptr(out["loss_per_sample"]), _ptr(out["loss_mean"]), _ptr(out["dX"]),
+        ct.c_uint32((FLAG_UNIT_ROWS if unit_rows else 0) | (FLAG_TRUSTED_LIST if trusted_list else 0)),
+        _ptr(out["loss_per_sample"]), _ptr(out["loss_mean"]), _ptr(out["dX"]),
         _ptr(out.get("dW_active")), _ptr(labels_next), _ptr(graph), ct.c_int(K), _ptr(next_out["active_idx"]),
         _ptr(next_out["n_active"]), _ptr(next_out["target_pos"]), _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status),
         _stream(stream))

@@ -1701,9 +1701,13 @@ static int sm_selected(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16
     if (!W_bf16 || !X_bf16 || !active_idx || !n_active || !target_pos || !loss_per_sample || !loss_mean || !dX || !ws)
         return KS_INVALID_ARG;
     if (sm_selected_check(C, D, B, M) != KS_OK) return KS_INVALID_ARG;
-    if (flags & ~(uint32_t)KS_FLAG_UNIT_ROWS) return KS_INVALID_ARG;
+    if (flags & ~(uint32_t)(KS_FLAG_UNIT_ROWS | KS_FLAG_TRUSTED_LIST)) return KS_INVALID_ARG;
     const bool fast = D % 64 == 0;
+    const bool trusted = (flags & KS_FLAG_TRUSTED_LIST) != 0;
     if (!dW_active && !(W_master && fast)) return KS_INVALID_ARG;
+    // a trusted list is read where it lies, until the end of the call: the next batch's list needs buffers of its own
+    if (nx && trusted && (nx->active_idx == active_idx || nx->n_active == n_active || nx->target_pos == target_pos))
+        return KS_INVALID_ARG;
     if (nx) {
         if (!nx->labels || !nx->active_idx || !nx->n_active || !nx->target_pos || nx->K < 0 || (nx->K > 0 && !nx->graph))
             return KS_INVALID_ARG;
@@ -1717,13 +1721,19 @@ static int sm_selected(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16
     if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
     const int nmax = M > B ? M : B;
-    hipLaunchKernelGGL(sm_sanitize_kernel, dim3((unsigned)ks_ceil_div(nmax, SM_NT)), dim3(SM_NT), 0, st, active_idx, n_active,
-                       target_pos, C, M, B, s.act, s.n, s.tp, dev_status);
+    const int32_t *act = active_idx, *n_act = n_active, *tp = target_pos;
+    if (!trusted) { // the validated copy (which also lets the next batch's list be written where this one came in)
+        hipLaunchKernelGGL(sm_sanitize_kernel, dim3((unsigned)ks_ceil_div(nmax, SM_NT)), dim3(SM_NT), 0, st, active_idx,
+                           n_active, target_pos, C, M, B, s.act, s.n, s.tp, dev_status);
+        act = s.act;
+        n_act = s.n;
+        tp = s.tp;
+    }
     DwUpdate up = DwUpdate();
     if (W_master && fast) {
         up.Wm = W_master;
         up.Wb = W_bf16;
-        up.idx = s.act;
+        up.idx = act;
         up.alpha = alpha;
     }
     // The selection rides along with the dX and dW launches where those exist (D a multiple of 64) and the class bitmap
@@ -1743,10 +1753,10 @@ static int sm_selected(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16
         next.target_pos = nx->target_pos;
         next.dev_status = dev_status;
     }
-    int rc = sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, s.act, s.n, s.tp, loss_per_sample, loss_mean, dX, dW_active,
-                    s.w, flags, dev_status, st, nullptr, SM_WHOLE, SmSplitIO(), up, ride ? &next : nullptr);
+    int rc = sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, act, n_act, tp, loss_per_sample, loss_mean, dX, dW_active,
+                    s.w, flags & KS_FLAG_UNIT_ROWS, dev_status, st, nullptr, SM_WHOLE, SmSplitIO(), up, ride ? &next : nullptr);
     if (rc == KS_OK && W_master && !fast)
-        rc = apply_weight_grad(W_master, W_bf16, s.act, s.n, M, dW_active, alpha, C, D, 1, ws, ws_bytes, dev_status, stream);
+        rc = apply_weight_grad(W_master, W_bf16, act, n_act, M, dW_active, alpha, C, D, 1, ws, ws_bytes, dev_status, stream);
     if (rc == KS_OK && nx && !ride)
         rc = ks_select_launch(nx->labels, nx->graph, C, B, nx->K, M, nx->active_idx, nx->n_active, nx->target_pos, sel_ws,
                               dev_status, st);

@@ -636,17 +636,21 @@ def test_step_on_an_earlier_selection_equals_the_one_call_step(ks, orc, name, un
     assert torch.equal(c["dW_active"][:A], d["dW_active"][:A]) and torch.equal(c["dX"], d["dX"])
 
 
-@pytest.mark.parametrize("name,shape,unit_rows,in_place", [
-    ("small", None, True, True), ("small", None, False, False), ("tiny", None, True, False),
-    ("the cut bites", dict(C=20_000, D=128, B=128, K=16, M=700, labels="zipf"), True, True),
-    ("D = 96", dict(C=5_000, D=96, B=70, K=9, M=300), False, False),
-    ("the table path", dict(C=400_000, D=128, B=64, K=8, M=1_024), True, True)])
-def test_selection_of_the_next_batch_rides_along_with_the_step(ks, orc, name, shape, unit_rows, in_place):
+@pytest.mark.parametrize("name,shape,unit_rows,in_place,trusted", [
+    ("small", None, True, True, False), ("small", None, False, False, False), ("tiny", None, True, False, False),
+    ("small", None, True, False, True), ("tiny", None, False, False, True),
+    ("the cut bites", dict(C=20_000, D=128, B=128, K=16, M=700, labels="zipf"), True, True, False),
+    ("the cut bites", dict(C=20_000, D=128, B=128, K=16, M=700, labels="zipf"), True, False, True),
+    ("D = 96", dict(C=5_000, D=96, B=70, K=9, M=300), False, False, False),
+    ("D = 96", dict(C=5_000, D=96, B=70, K=9, M=300), False, False, True),
+    ("the table path", dict(C=400_000, D=128, B=64, K=8, M=1_024), True, True, False)])
+def test_selection_of_the_next_batch_rides_along_with_the_step(ks, orc, name, shape, unit_rows, in_place, trusted):
     """A loop of knn_softmax_fwd_bwd_update_selected_next calls (the step on this batch's list, the next batch's list
     made by extra workgroups of the same launches) against a loop of one-call steps on the same batches: every
     batch's active list, target positions, losses and dX, and the weights after the last step, bit for bit.  With the
     list buffers reused in place and with separate ones; D a multiple of 64 (the selection rides along) and not, and
-    more classes than one workgroup's bitmap holds (then it follows the step); a batch whose lists exceed M."""
+    more classes than one workgroup's bitmap holds (then it follows the step); a batch whose lists exceed M; and with
+    the list declared trusted (read in place, no validating copy: separate buffers are then required)."""
     cfg = dict(synth.CONFIGS["tiny"], **shape) if shape else synth.CONFIGS[name]
     C, D, B, K, M, scale = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"], cfg["scale"]
     W, X = synth.make_WX(cfg)
@@ -676,7 +680,8 @@ def test_selection_of_the_next_batch_rides_along_with_the_step(ks, orc, name, sh
         assert torch.equal(cur["target_pos"], ref[t]["target_pos"])
         b, nxt = ks.knn_softmax_fwd_bwd_update_selected_next(Wm2, Wb2, Xb, cur["active_idx"], cur["n_active"], cur["target_pos"],
                                                              ys[t + 1], Gd, scale, gs, alpha,
-                                                             next_out=None if in_place else spare, unit_rows=unit_rows)
+                                                             next_out=None if in_place else spare, unit_rows=unit_rows,
+                                                             trusted_list=trusted)
         torch.cuda.synchronize()
         assert int(b["dev_status"].item()) == 0
         assert torch.equal(b["loss_per_sample"], ref[t]["loss_per_sample"]) and torch.equal(b["loss_mean"], ref[t]["loss_mean"])
@@ -688,6 +693,21 @@ def test_selection_of_the_next_batch_rides_along_with_the_step(ks, orc, name, sh
     act_l, n_l, tp_l, _ = ks.knn_select_active(ys[n_steps], Gd, C, M)
     torch.cuda.synchronize()
     assert torch.equal(cur["active_idx"], act_l) and torch.equal(cur["n_active"], n_l) and torch.equal(cur["target_pos"], tp_l)
+
+
+def test_trusted_list_needs_buffers_of_its_own_for_the_next_list(ks):
+    C, D, B, K, M = 2000, 128, 16, 4, 64
+    W = torch.randn(C, D, device="cuda")
+    Wb, X = W.to(torch.bfloat16), torch.randn(B, D, device="cuda").to(torch.bfloat16)
+    y = torch.arange(B, dtype=torch.int32, device="cuda")
+    G = torch.from_numpy(synth.graph_synthetic(0, C, K)).cuda()
+    act, n, tp, _ = ks.knn_select_active(y, G, C, M)
+    with pytest.raises(ks.KsError):
+        ks.knn_softmax_fwd_bwd_update_selected_next(W, Wb, X, act, n, tp, y, G, 10.0, 1.0, -0.01, trusted_list=True)
+    a, _ = ks.knn_softmax_fwd_bwd_update_selected_next(W.clone(), Wb.clone(), X, act, n, tp, y, G, 10.0, 1.0, -0.01)
+    b = ks.knn_softmax_fwd_bwd_update_selected(W.clone(), Wb.clone(), X, act, n, tp, 10.0, 1.0, -0.01, trusted_list=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a["dX"], b["dX"]) and torch.equal(a["loss_per_sample"], b["loss_per_sample"])
 
 
 def test_step_on_a_broken_selection_is_flagged_and_stays_in_bounds(ks):
