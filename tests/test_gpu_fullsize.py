@@ -214,3 +214,44 @@ def test_step_dense1m(ks, orc):
                          scale, grad_scale, tag=f"dense1m unit_rows={unit_rows}")
         assert bool((out["dW_active"][A_ref:] == SENTINEL).all()), "rows beyond n_active were written"
         del out
+
+
+@pytest.mark.parametrize("name", ["shard390k", "shard390k_uniform"])
+def test_headline_loop_full_size_equals_the_one_call_step(ks, shard, name):
+    """The loop `bench.py` times -- one knn_softmax_fwd_bwd_update_selected_next call per step, the list read in place
+    (KS_FLAG_TRUSTED_LIST), the next batch's selection inside the step's launches -- against one-call steps on the same
+    three batches (those are the calls the oracle checks above): lists, losses, dX of every step and the weights at the
+    end, bit for bit, at the headline size (Zipf labels: 182 dW tiles beside the 32 selection workgroups; uniform
+    labels: the cap, 512 tiles)."""
+    cfg = synth.CONFIGS[name]
+    C, D, B, K, M, scale = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"], cfg["scale"]
+    W_bf, graph = shard["W_bf"], shard["graph"]
+    X_bf = torch.from_numpy(shard["X"]).cuda().to(torch.bfloat16)
+    gs, alpha = 128.0, -0.05 / 128.0
+    ys = [torch.from_numpy(synth.make_labels(cfg, seed=cfg["seed"] + 31 * t)).cuda() for t in range(4)]
+    Wm1, Wb1 = W_bf.float(), W_bf.clone()
+    ref = []
+    for t in range(3):
+        a = ks.knn_softmax_fwd_bwd_update(Wm1, Wb1, X_bf, ys[t], graph, M, scale, gs, alpha, unit_rows=True)
+        torch.cuda.synchronize()
+        assert int(a["dev_status"].item()) == 0
+        ref.append({k: a[k].clone() for k in ("active_idx", "n_active", "target_pos", "loss_per_sample", "loss_mean", "dX")})
+    Wm2, Wb2 = W_bf.float(), W_bf.clone()
+    act, n, tp, st = ks.knn_select_active(ys[0], graph, C, M)
+    cur = dict(active_idx=act, n_active=n, target_pos=tp)
+    other = {k: torch.empty_like(v) for k, v in cur.items()}
+    for t in range(3):
+        print(f"[case] {name}: step {t} of the headline loop, A={int(ref[t]['n_active'].item())}", flush=True)
+        b, _ = ks.knn_softmax_fwd_bwd_update_selected_next(Wm2, Wb2, X_bf, cur["active_idx"], cur["n_active"], cur["target_pos"],
+                                                           ys[t + 1], graph, scale, gs, alpha, next_out=other, unit_rows=True,
+                                                           trusted_list=True)
+        torch.cuda.synchronize()
+        assert int(b["dev_status"].item()) == 0
+        assert torch.equal(cur["active_idx"], ref[t]["active_idx"]) and torch.equal(cur["target_pos"], ref[t]["target_pos"])
+        assert torch.equal(b["loss_per_sample"], ref[t]["loss_per_sample"]) and torch.equal(b["dX"], ref[t]["dX"])
+        assert torch.equal(b["loss_mean"], ref[t]["loss_mean"])
+        cur, other = other, cur
+    assert torch.equal(Wm1, Wm2) and torch.equal(Wb1, Wb2)
+    act3, n3, tp3, _ = ks.knn_select_active(ys[3], graph, C, M)
+    torch.cuda.synchronize()
+    assert torch.equal(cur["active_idx"], act3) and torch.equal(cur["n_active"], n3) and torch.equal(cur["target_pos"], tp3)
