@@ -397,6 +397,9 @@ def main():
             e["gbs"] = round(m["bytes"] / (dur[p] * 1e-6) / 1e9, 1)
             e.update(fracs(e["gbs"], PEAK_HBM_GBS, copy_peak))
         phases[p] = e
+    if next_inside:
+        phases["select"]["note"] = ("stage times are those of the one-call step; in the headline loop the selection (of the next "
+                                    "batch) runs inside the dx_gemm and dw_gemm launches and adds nothing to the step")
     log("[bench] stage times (us, medians): " + ", ".join(f"{p}={phases[p]['us']}" for p in PHASES))
     traffic_all = profiled_traffic() if (unit_rows and fused_update and args.workload == "shard390k") else {}
     dom = max((p for p in PHASES if model[p]["bound"] in ("mfma", "hbm")), key=lambda p: dur[p])
