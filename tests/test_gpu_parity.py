@@ -643,7 +643,10 @@ def test_step_on_an_earlier_selection_equals_the_one_call_step(ks, orc, name, un
     ("the cut bites", dict(C=20_000, D=128, B=128, K=16, M=700, labels="zipf"), True, False, True),
     ("D = 96", dict(C=5_000, D=96, B=70, K=9, M=300), False, False, False),
     ("D = 96", dict(C=5_000, D=96, B=70, K=9, M=300), False, False, True),
-    ("the table path", dict(C=400_000, D=128, B=64, K=8, M=1_024), True, True, False)])
+    ("the table path", dict(C=400_000, D=128, B=64, K=8, M=1_024), True, True, False),
+    ("one sample", dict(C=300, D=64, B=1, K=3, M=4), False, True, False),
+    ("lists as long as M allows", dict(C=3_000, D=128, B=5, K=7, M=8), True, False, True),
+    ("batch not a power of two, 393,216 classes", dict(C=393_216, D=64, B=100, K=5, M=600), True, False, True)])
 def test_selection_of_the_next_batch_rides_along_with_the_step(ks, orc, name, shape, unit_rows, in_place, trusted):
     """A loop of knn_softmax_fwd_bwd_update_selected_next calls (the step on this batch's list, the next batch's list
     made by extra workgroups of the same launches) against a loop of one-call steps on the same batches: every
