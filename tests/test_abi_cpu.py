@@ -158,6 +158,24 @@ def test_argument_errors_are_reported_before_any_launch(ks):
     assert L.knn_select_active(one, one, i64(100), i(8), i(4), i(4), one, one, one, one, sz(1 << 20), null,
                                null) == ks.KS_INVALID_ARG  # B > M
 
+    two = ct.c_void_p(512)
+
+    def nxt(labels_next=one, K=4, M=64, flags=0, act_next=two, n_next=two, tp_next=two, ws_bytes=1 << 30, graph=one):
+        return L.knn_softmax_fwd_bwd_update_selected_next(one, one, one, one, one, one, i64(1000), i(128), i(8), i(M), f(30.0),
+                                                          f(1.0), f(-0.01), ct.c_uint32(flags), one, one, one, null,
+                                                          labels_next, graph, i(K), act_next, n_next, tp_next, one,
+                                                          sz(ws_bytes), null, null)
+
+    assert nxt(labels_next=null) == ks.KS_INVALID_ARG
+    assert nxt(graph=null) == ks.KS_INVALID_ARG
+    assert nxt(act_next=null) == ks.KS_INVALID_ARG
+    assert nxt(K=64) == ks.KS_INVALID_ARG              # K + 1 > M
+    assert nxt(flags=2) == ks.KS_INVALID_ARG           # not a flag of this call
+    assert nxt(flags=4, act_next=one) == ks.KS_INVALID_ARG   # a trusted list is read in place: the next one needs its own buffers
+    assert nxt(ws_bytes=1024) == ks.KS_WORKSPACE_TOO_SMALL
+    assert ks.knn_softmax_selected_next_workspace(1000, 128, 8, 4, 64) >= ks.knn_softmax_selected_workspace(1000, 128, 8, 64) + 8 * 5 * 4
+    assert ks.knn_softmax_selected_next_workspace(1000, 100, 8, 4, 64) == 0
+
 
 def test_product_never_imports_the_oracle():
     pkg = os.path.join(ROOT, "paper_2102_06025_amd")
