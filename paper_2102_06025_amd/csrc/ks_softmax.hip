@@ -1265,6 +1265,9 @@ sm_sanitize_kernel(const int32_t *__restrict__ active_idx, const int32_t *__rest
                    const int32_t *__restrict__ target_pos, int64_t C, int M, int B, int32_t *__restrict__ act_safe,
                    int32_t *__restrict__ n_safe, int32_t *__restrict__ tp_safe, int32_t *dev_status) {
     const int t = blockIdx.x * SM_NT + threadIdx.x;
+    // (all three loads are issued before the count is looked at: the kernel is one round trip to memory long)
+    const int32_t a_in = t < M ? active_idx[t] : -1;
+    const int32_t tp_in = t < B ? target_pos[t] : -1;
     int n = *n_active_p;
     if (n < 0 || n > M) {
         if (t == 0) ks_flag(dev_status, KS_DEV_BAD_COUNT);
@@ -1274,7 +1277,7 @@ sm_sanitize_kernel(const int32_t *__restrict__ active_idx, const int32_t *__rest
     if (t < M) {
         int32_t a = -1;
         if (t < n) {
-            a = active_idx[t];
+            a = a_in;
             if (a < 0 || a >= C) {
                 ks_flag(dev_status, KS_DEV_BAD_INDEX);
                 a = 0;
@@ -1283,7 +1286,7 @@ sm_sanitize_kernel(const int32_t *__restrict__ active_idx, const int32_t *__rest
         act_safe[t] = a;
     }
     if (t < B) {
-        int32_t tp = target_pos[t];
+        int32_t tp = tp_in;
         if (tp >= n) {
             ks_flag(dev_status, KS_DEV_BAD_LABEL);
             tp = -1;
