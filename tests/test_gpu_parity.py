@@ -698,6 +698,68 @@ def test_selection_of_the_next_batch_rides_along_with_the_step(ks, orc, name, sh
     assert torch.equal(cur["active_idx"], act_l) and torch.equal(cur["n_active"], n_l) and torch.equal(cur["target_pos"], tp_l)
 
 
+def test_headline_loop_replayed_from_a_hip_graph(ks):
+    """The library allocates nothing, clears nothing with memset and never synchronises, so a training loop can capture
+    its calls: two steps of the headline loop (list A -> list B -> list A) captured once and replayed three times, the
+    labels of the coming batches copied into fixed buffers and other eager work done between the replays; weights, 16-bit
+    copy and the last list against six eager one-call steps, bit for bit, after every replay."""
+    cfg = synth.CONFIGS["small"]
+    C, D, B, K, M, scale = cfg["C"], cfg["D"], cfg["B"], cfg["K"], cfg["M"], cfg["scale"]
+    W, X = synth.make_WX(cfg)
+    W = synth.bf16_round(W)
+    G = synth.graph_synthetic(cfg["seed"], C, K)
+    gs, alpha = 64.0, -0.03 / 64.0
+    Xb, Gd = dev(synth.bf16_round(X), torch.bfloat16), dev(G)
+    ys = [dev(synth.make_labels(cfg, seed=cfg["seed"] + 5 * t)) for t in range(7)]
+    Wm1, Wb1 = dev(W), dev(W, torch.bfloat16)
+    ref_W = []
+    for t in range(6):
+        a = ks.knn_softmax_fwd_bwd_update(Wm1, Wb1, Xb, ys[t], Gd, M, scale, gs, alpha, unit_rows=True)
+        if t % 2 == 1:
+            torch.cuda.synchronize()
+            ref_W.append((Wm1.clone(), Wb1.clone()))
+    assert int(a["dev_status"].item()) == 0
+    Wm2, Wb2 = dev(W), dev(W, torch.bfloat16)
+    act, n, tp, _ = ks.knn_select_active(ys[0], Gd, C, M)
+    L0 = dict(active_idx=act, n_active=n, target_pos=tp)
+    L1 = {k: torch.empty_like(v) for k, v in L0.items()}
+    Ya, Yb = torch.empty_like(ys[0]), torch.empty_like(ys[0])
+    out = dict(loss_per_sample=torch.empty(B, dtype=torch.float32, device="cuda"),
+               loss_mean=torch.empty(1, dtype=torch.float32, device="cuda"),
+               dX=torch.empty((B, D), dtype=torch.float32, device="cuda"), dW_active=None,
+               dev_status=torch.zeros(1, dtype=torch.int32, device="cuda"))
+    ws = torch.empty(ks.knn_softmax_selected_next_workspace(C, D, B, K, M), dtype=torch.uint8, device="cuda")
+
+    def two_steps():
+        ks.knn_softmax_fwd_bwd_update_selected_next(Wm2, Wb2, Xb, L0["active_idx"], L0["n_active"], L0["target_pos"], Ya, Gd, scale,
+                                                    gs, alpha, next_out=L1, out=out, ws=ws, unit_rows=True, trusted_list=True)
+        ks.knn_softmax_fwd_bwd_update_selected_next(Wm2, Wb2, Xb, L1["active_idx"], L1["n_active"], L1["target_pos"], Yb, Gd, scale,
+                                                    gs, alpha, next_out=L0, out=out, ws=ws, unit_rows=True, trusted_list=True)
+
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    Wm_keep, Wb_keep, L0_keep = Wm2.clone(), Wb2.clone(), {k: v.clone() for k, v in L0.items()}
+    Ya.copy_(ys[1]); Yb.copy_(ys[2])
+    print("[case] capturing two steps of the headline loop", flush=True)
+    with torch.cuda.graph(graph):
+        two_steps()
+    # (capture runs nothing; the buffers are as before)
+    Wm2.copy_(Wm_keep); Wb2.copy_(Wb_keep)
+    for k in L0:
+        L0[k].copy_(L0_keep[k])
+    for r in range(3):
+        Ya.copy_(ys[2 * r + 1]); Yb.copy_(ys[2 * r + 2])
+        scratch = torch.randn(1 << 20, device="cuda").sum()      # eager work between the replays
+        print(f"[case] replay {r}", flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(out["dev_status"].item()) == 0 and bool(torch.isfinite(scratch))
+        assert torch.equal(Wm2, ref_W[r][0]) and torch.equal(Wb2, ref_W[r][1]), f"replay {r}"
+    act6, n6, tp6, _ = ks.knn_select_active(ys[6], Gd, C, M)
+    torch.cuda.synchronize()
+    assert torch.equal(L0["active_idx"], act6) and torch.equal(L0["n_active"], n6) and torch.equal(L0["target_pos"], tp6)
+
+
 def test_trusted_list_needs_buffers_of_its_own_for_the_next_list(ks):
     C, D, B, K, M = 2000, 128, 16, 4, 64
     W = torch.randn(C, D, device="cuda")
