@@ -643,6 +643,29 @@ def main():
                                             alpha, idx_sorted_unique=True, ws=ws, dev_status=st4)
             return sel
 
+        # the same step as a training loop runs it: the next batch's selection inside the second call's launches, the
+        # list read in place from the buffers the previous step wrote (two sets in turn)
+        spn_ws = torch.empty(ks.knn_softmax_split_next_workspace(C, D, B, K, M), dtype=torch.uint8, device="cuda")
+        node_lists = {}
+
+        def node_step_next(pad):
+            if pad not in node_lists:
+                o = ks.knn_select_active_csr(y4, counts, offsets, flat, c0, C, K, M, pad_random=pad, pad_seed=7, ws=s_ws,
+                                             dev_status=st4)
+                first = {k_: o[k_] for k_ in ("active_idx", "n_active", "n_found", "target_pos")}
+                node_lists[pad] = [first, {k_: torch.empty_like(v) for k_, v in first.items()}]
+            a, b = node_lists[pad]
+            s1 = ks.knn_softmax_fwd_stats(W_bf, X_bf, a["active_idx"], a["n_active"], a["target_pos"], scale, unit_rows=True,
+                                          ws=spn_ws, dev_status=st4, trusted_list=True)
+            s1["row_sumexp"].mul_(4.0)
+            s2, _ = ks.knn_softmax_bwd_from_stats_next(W_bf, X_bf, a["active_idx"], a["n_active"], a["target_pos"], s1["row_max"],
+                                                       s1["row_sumexp"], s1["target_logit"], scale, grad_scale, spn_ws, y4, counts,
+                                                       offsets, flat, c0, K, next_out=b, pad_random=pad, pad_seed=7,
+                                                       unit_rows=True, trusted_list=True, dev_status=st4)
+            ks.apply_weight_grad_normalized(W_master, W_bf, inv_norm, a["active_idx"], a["n_active"], s2["dW_active"], alpha,
+                                            idx_sorted_unique=True, ws=ws, dev_status=st4)
+            node_lists[pad] = [b, a]
+
         def wall(fn, reps):
             for _ in range(3):
                 fn()
@@ -655,6 +678,8 @@ def main():
 
         ms_node = wall(lambda: node_step(False), args.steps)
         ms_node_pad = wall(lambda: node_step(True), args.steps)
+        ms_node_next = wall(lambda: node_step_next(False), args.steps)
+        ms_node_next_pad = wall(lambda: node_step_next(True), args.steps)
         n_act4 = int(node_step(False)["n_active"].item())
         torch.cuda.synchronize()
         assert int(st4.item()) == 0
@@ -667,10 +692,17 @@ def main():
                             node_step=dict(what="select_csr + fwd_stats + exchange stand-in + bwd_from_stats + "
                                                 "apply_weight_grad_normalized, one-sweep softmax",
                                            ms_per_step=round(ms_node, 4), active_classes=n_act4,
-                                           ms_per_step_filled_to_M=round(ms_node_pad, 4)))
+                                           ms_per_step_filled_to_M=round(ms_node_pad, 4),
+                                           next_selection_inside=dict(
+                                               what="fwd_stats + exchange stand-in + knn_softmax_bwd_from_stats_next (the next "
+                                                    "batch's select_csr inside its launches, lists read in place) + "
+                                                    "apply_weight_grad_normalized",
+                                               ms_per_step=round(ms_node_next, 4),
+                                               ms_per_step_filled_to_M=round(ms_node_next_pad, 4))))
         log(f"[bench] one node of four: compress {us_compress:.0f} us, select {us_sel:.1f} us, with fill-up {us_sel_pad:.1f} us; "
-            f"node step {ms_node:.4f} ms (A={n_act4}), filled to M {ms_node_pad:.4f} ms")
-        del G4, sp_ws, c_ws, counts, offsets, flat
+            f"node step {ms_node:.4f} ms (A={n_act4}), filled to M {ms_node_pad:.4f} ms; with the next selection inside "
+            f"{ms_node_next:.4f} / {ms_node_next_pad:.4f} ms")
+        del G4, sp_ws, spn_ws, node_lists, c_ws, counts, offsets, flat
 
     # ---- second workload (Section 3.3.2): layer-wise top-k selection over the gradient set of a ResNet-50, 99.9 %
     # sparsity, all 161 tensors in one call; HBM-bound by its algorithmic bytes: every gradient is read once

@@ -51,7 +51,7 @@ typedef enum {
 /* bits of the `flags` argument of the softmax entry points */
 #define KS_FLAG_UNIT_ROWS 1u        /* every row of W_bf16 and X_bf16 has L2 norm <= 1 (up to rounding) */
 #define KS_FLAG_PAD_RANDOM 2u       /* knn_select_active_csr: fill the active list up to M with randomly drawn classes */
-#define KS_FLAG_TRUSTED_LIST 4u     /* knn_softmax_fwd_bwd_update_selected(_next): the list is the unmodified output of this
+#define KS_FLAG_TRUSTED_LIST 4u     /* the calls that take a selection made earlier: the list is the unmodified output of this
                                        library's selection for the same C and M; it is used where it lies, without the
                                        validating copy (a broken promise may read outside W) */
 
@@ -311,6 +311,16 @@ int apply_weight_grad(float *W_master, uint16_t *W_bf16, const int32_t *idx, con
  * B is the gathered batch (the mean and grad_scale / B refer to it).  An active_idx entry outside [0, C) sets
  * KS_DEV_BAD_INDEX (and is replaced by row 0), a target_pos >= n_active sets KS_DEV_BAD_LABEL (treated as -1).
  * Requires D % 64 == 0 (KS_UNSUPPORTED otherwise), B <= M not required.  Tolerances as knn_softmax_fwd_bwd.
+ * Both calls take KS_FLAG_TRUSTED_LIST (the list is the unmodified output of this library's selection: read in place, no
+ * validating copy).
+ *
+ * knn_softmax_bwd_from_stats_next: the same second call, and in its launches knn_select_active_csr for the NEXT batch
+ * (labels_next .. target_pos_next: that call's arguments, select_flags = its flags; C is its C_loc) -- the selection needs
+ * only the next batch's labels and the node's compressed graph, so it runs as extra workgroups of the dX and dW launches
+ * and leaves the node's critical path (Section 3.2.1).  Outputs exactly as knn_select_active_csr writes them; they may be
+ * the buffers this call's list came in, except with KS_FLAG_TRUSTED_LIST.  Requires B <= M and K_max + 1 <= M.  Nodes of
+ * more than 393,216 classes run the selection after the step instead.  Workspace: knn_softmax_split_next_workspace,
+ * passed to both calls of a step.
  * ---------------------------------------------------------------------------------------------------- */
 size_t knn_softmax_split_workspace(int64_t C, int D, int B, int M);
 int knn_softmax_fwd_stats(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *active_idx,
@@ -323,6 +333,16 @@ int knn_softmax_bwd_from_stats(const uint16_t *W_bf16, const uint16_t *X_bf16, c
                                int M, float scale, float grad_scale, uint32_t flags, float *loss_per_sample,
                                float *loss_mean, float *dX, float *dW_active, void *ws, size_t ws_bytes,
                                int32_t *dev_status, void *stream);
+size_t knn_softmax_split_next_workspace(int64_t C, int D, int B, int K_max, int M);
+int knn_softmax_bwd_from_stats_next(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *active_idx,
+                                    const int32_t *n_active, const int32_t *target_pos, const float *global_max,
+                                    const float *global_sumexp, const float *global_target_logit, int64_t C, int D, int B,
+                                    int M, float scale, float grad_scale, uint32_t flags, float *loss_per_sample,
+                                    float *loss_mean, float *dX, float *dW_active, const int32_t *labels_next,
+                                    const int32_t *counts, const int64_t *offsets, const int32_t *flat, int64_t flat_len,
+                                    int64_t Cg, int64_t c0, int K_max, uint32_t select_flags, uint64_t pad_seed,
+                                    int32_t *active_idx_next, int32_t *n_active_next, int32_t *n_found_next,
+                                    int32_t *target_pos_next, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream);
 
 /* ------------------------------------------------------------------------------------------------------
  * knn_graph_update -- one hop of the distributed graph build of Section 3.2.2 (the shards of W travel from

@@ -6,6 +6,7 @@ from .binding import (KS_DEV_RANGE, FLAG_UNIT_ROWS, FLAG_PAD_RANDOM, FLAG_TRUSTE
                       knn_graph_update_workspace, knn_softmax_bwd_from_stats, knn_softmax_fwd_stats, knn_softmax_fwd_bwd_update,
                       knn_softmax_fwd_bwd_update_selected, knn_softmax_selected_workspace,
                       knn_softmax_fwd_bwd_update_selected_next, knn_softmax_selected_next_workspace,
+                      knn_softmax_bwd_from_stats_next, knn_softmax_split_next_workspace,
                       knn_softmax_split_workspace,
                       knn_select_active_csr_workspace, KS_DEV_BAD_COUNT, KS_DEV_BAD_GRAPH_ID, KS_DEV_BAD_INDEX, KS_DEV_BAD_LABEL,  # noqa: F401
                       KS_DEV_IDX_NOT_SORTED, KS_INVALID_ARG, KS_OK, KS_UNSUPPORTED, KS_WORKSPACE_TOO_SMALL,

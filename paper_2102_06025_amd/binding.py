@@ -26,6 +26,7 @@ EXPORTS = ("ks_version", "knn_graph_build_workspace", "knn_graph_build", "knn_gr
            "knn_softmax_split_workspace", "knn_softmax_fwd_stats", "knn_softmax_bwd_from_stats",
            "knn_softmax_fwd_bwd_update", "knn_softmax_selected_workspace", "knn_softmax_fwd_bwd_update_selected",
            "knn_softmax_selected_next_workspace", "knn_softmax_fwd_bwd_update_selected_next",
+           "knn_softmax_split_next_workspace", "knn_softmax_bwd_from_stats_next",
            "ks_peak_mfma", "ks_peak_copy", "grad_topk_plan", "grad_topk_workspace", "grad_topk_select")
 
 
@@ -586,7 +587,7 @@ def knn_softmax_split_workspace(C, D, B, M) -> int:
 
 
 def knn_softmax_fwd_stats(W_bf16, X_bf16, active_idx, n_active, target_pos, scale, unit_rows=False, ws=None,
-                          dev_status=None, stream=None):
+                          dev_status=None, stream=None, trusted_list=False, out=None):
     """First call of the softmax split over nodes.  Returns dict(row_max, row_sumexp, target_logit [B] fp32, ws,
     dev_status); pass the same `ws` to knn_softmax_bwd_from_stats."""
     _need(W_bf16, torch.bfloat16, "W_bf16")
@@ -595,23 +596,67 @@ def knn_softmax_fwd_stats(W_bf16, X_bf16, active_idx, n_active, target_pos, scal
     _need(target_pos, torch.int32, "target_pos")
     (C, D), B, M = W_bf16.shape, X_bf16.shape[0], active_idx.numel()
     dev = W_bf16.device
-    out = dict(row_max=torch.empty(B, dtype=torch.float32, device=dev),
-               row_sumexp=torch.empty(B, dtype=torch.float32, device=dev),
-               target_logit=torch.empty(B, dtype=torch.float32, device=dev))
+    if out is None:
+        out = dict(row_max=torch.empty(B, dtype=torch.float32, device=dev),
+                   row_sumexp=torch.empty(B, dtype=torch.float32, device=dev),
+                   target_logit=torch.empty(B, dtype=torch.float32, device=dev))
     ws = _ws(knn_softmax_split_workspace(C, D, B, M), dev, ws)
     dev_status = _status(dev, dev_status)
     out["ws"], out["dev_status"] = ws, dev_status
     rc = lib().knn_softmax_fwd_stats(_ptr(W_bf16), _ptr(X_bf16), _ptr(active_idx), _ptr(n_active), _ptr(target_pos),
                                      ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(M), ct.c_float(scale),
-                                     ct.c_uint32(FLAG_UNIT_ROWS if unit_rows else 0), _ptr(out["row_max"]),
+                                     ct.c_uint32((FLAG_UNIT_ROWS if unit_rows else 0) | (FLAG_TRUSTED_LIST if trusted_list else 0)),
+                                     _ptr(out["row_max"]),
                                      _ptr(out["row_sumexp"]), _ptr(out["target_logit"]), _ptr(ws), ct.c_size_t(ws.numel()),
                                      _ptr(dev_status), _stream(stream))
     _check("knn_softmax_fwd_stats", rc)
     return out
 
 
+def knn_softmax_split_next_workspace(C, D, B, K_max, M) -> int:
+    return int(lib().knn_softmax_split_next_workspace(ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(K_max), ct.c_int(M)))
+
+
+def knn_softmax_bwd_from_stats_next(W_bf16, X_bf16, active_idx, n_active, target_pos, global_max, global_sumexp,
+                                    global_target_logit, scale, grad_scale, ws, labels_next, counts, offsets, flat, c0, K_max,
+                                    next_out=None, pad_random=False, pad_seed=0, unit_rows=False, trusted_list=False,
+                                    dev_status=None, stream=None, out=None):
+    """knn_softmax_bwd_from_stats, and in the same launches knn_select_active_csr for the next batch (labels_next).
+    `ws` (knn_softmax_split_next_workspace) is the first call's.  next_out: dict(active_idx, n_active, n_found,
+    target_pos) for the next list (None: this call's own list buffers, not with trusted_list).  Returns (out, next_out)."""
+    for t, name in ((global_max, "global_max"), (global_sumexp, "global_sumexp"), (global_target_logit, "global_target_logit")):
+        _need(t, torch.float32, name)
+    _need(labels_next, torch.int32, "labels_next")
+    _need(counts, torch.int32, "counts")
+    _need(offsets, torch.int64, "offsets")
+    _need(flat, torch.int32, "flat")
+    (C, D), B, M = W_bf16.shape, X_bf16.shape[0], active_idx.numel()
+    dev = W_bf16.device
+    if out is None:
+        out = dict(loss_per_sample=torch.empty(B, dtype=torch.float32, device=dev),
+                   loss_mean=torch.empty(1, dtype=torch.float32, device=dev),
+                   dX=torch.empty((B, D), dtype=torch.float32, device=dev),
+                   dW_active=torch.empty((M, D), dtype=torch.float32, device=dev))
+    if next_out is None:
+        next_out = dict(active_idx=active_idx, n_active=n_active, n_found=None, target_pos=target_pos)
+    dev_status = _status(dev, dev_status if dev_status is not None else out.get("dev_status"))
+    out["dev_status"] = dev_status
+    flags = (FLAG_UNIT_ROWS if unit_rows else 0) | (FLAG_TRUSTED_LIST if trusted_list else 0)
+    rc = lib().knn_softmax_bwd_from_stats_next(
+        _ptr(W_bf16), _ptr(X_bf16), _ptr(active_idx), _ptr(n_active), _ptr(target_pos), _ptr(global_max), _ptr(global_sumexp),
+        _ptr(global_target_logit), ct.c_int64(C), ct.c_int(D), ct.c_int(B), ct.c_int(M), ct.c_float(scale), ct.c_float(grad_scale),
+        ct.c_uint32(flags), _ptr(out["loss_per_sample"]), _ptr(out["loss_mean"]), _ptr(out["dX"]), _ptr(out["dW_active"]),
+        _ptr(labels_next), _ptr(counts), _ptr(offsets), _ptr(flat), ct.c_int64(flat.numel()), ct.c_int64(counts.numel()),
+        ct.c_int64(c0), ct.c_int(K_max), ct.c_uint32(FLAG_PAD_RANDOM if pad_random else 0), ct.c_uint64(pad_seed),
+        _ptr(next_out["active_idx"]), _ptr(next_out["n_active"]), _ptr(next_out.get("n_found")), _ptr(next_out["target_pos"]),
+        _ptr(ws), ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
+    _check("knn_softmax_bwd_from_stats_next", rc)
+    return out, next_out
+
+
 def knn_softmax_bwd_from_stats(W_bf16, X_bf16, active_idx, n_active, target_pos, global_max, global_sumexp,
-                               global_target_logit, scale, grad_scale, ws, unit_rows=False, dev_status=None, stream=None):
+                               global_target_logit, scale, grad_scale, ws, unit_rows=False, dev_status=None, stream=None,
+                               trusted_list=False):
     """Second call of the softmax split over nodes (`ws` is the first call's).  Returns dict(loss_per_sample,
     loss_mean, dX (this node's contribution), dW_active, dev_status)."""
     for t, name in ((global_max, "global_max"), (global_sumexp, "global_sumexp"), (global_target_logit, "global_target_logit")):
@@ -627,7 +672,8 @@ def knn_softmax_bwd_from_stats(W_bf16, X_bf16, active_idx, n_active, target_pos,
     rc = lib().knn_softmax_bwd_from_stats(_ptr(W_bf16), _ptr(X_bf16), _ptr(active_idx), _ptr(n_active), _ptr(target_pos),
                                           _ptr(global_max), _ptr(global_sumexp), _ptr(global_target_logit), ct.c_int64(C),
                                           ct.c_int(D), ct.c_int(B), ct.c_int(M), ct.c_float(scale), ct.c_float(grad_scale),
-                                          ct.c_uint32(FLAG_UNIT_ROWS if unit_rows else 0), _ptr(out["loss_per_sample"]),
+                                          ct.c_uint32((FLAG_UNIT_ROWS if unit_rows else 0) | (FLAG_TRUSTED_LIST if trusted_list else 0)),
+                                          _ptr(out["loss_per_sample"]),
                                           _ptr(out["loss_mean"]), _ptr(out["dX"]), _ptr(out["dW_active"]), _ptr(ws),
                                           ct.c_size_t(ws.numel()), _ptr(dev_status), _stream(stream))
     _check("knn_softmax_bwd_from_stats", rc)

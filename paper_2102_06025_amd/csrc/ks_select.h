@@ -39,6 +39,39 @@ struct SelDense {
         return c;
     }
 };
+struct SelCsr {
+    const int32_t *labels, *counts;
+    const int64_t *offsets;
+    const int32_t *flat;
+    int64_t Cg, c0, C, flat_len; // classes of the whole problem; first class and number of classes of this node
+    int K;                       // upper bound of the list lengths
+    static constexpr bool kForeignLabels = true; // labels of other nodes' classes have no target here
+    __device__ __forceinline__ int32_t cand(int i, int r, int32_t *dev_status) const {
+        const int32_t y = labels[i];
+        if (y < 0 || y >= Cg) {
+            if (r == 0) ks_flag(dev_status, KS_DEV_BAD_LABEL);
+            return -1;
+        }
+        if (r == 0) {
+            const int64_t l = (int64_t)y - c0;
+            return (l >= 0 && l < C) ? (int32_t)l : -1;
+        }
+        const int32_t n = counts[y];
+        if (r - 1 >= n) return -1;
+        const int64_t off = offsets[y];
+        if (n > K || off < 0 || off + n > flat_len) { // a list longer than promised or outside the array: not read
+            if (r == 1) ks_flag(dev_status, KS_DEV_BAD_COUNT);
+            return -1;
+        }
+        int32_t c = flat[off + (r - 1)];
+        if (c < -1 || c >= C) {
+            ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
+            c = -1;
+        }
+        return c;
+    }
+};
+
 // k-th draw of the random fill-up: a keyed one-to-one map of [0, 2^b) onto itself (adding a constant, multiplying
 // by an odd constant and xor with a right shift of itself are each one-to-one on b-bit numbers), 2^b the smallest
 // power of two >= C.  Draws >= C or already in the set are passed over: a sample without replacement of the
@@ -270,18 +303,27 @@ __device__ __forceinline__ void sel1_body(uint32_t *lds, const int32_t *__restri
 
 // The selection of the NEXT batch as extra workgroups of the step's launches (nsel == 0: none): `nfetch` blocks of
 // `fetch_nt` threads stage the candidates (they ride along with the dX launch), `nsel` workgroups select (with the dW
-// launch, which leaves compute units idle).
+// launch, which leaves compute units idle).  The candidates come from the dense graph of a GPU that owns all classes
+// or from the compressed graph of one node (csr_source), then with that selection's fill-up if asked for.
 struct KsSelNext {
     int nsel, nfetch;
-    SelDense src;
+    int csr_source;
+    SelDense dense;
+    SelCsr csr;
+    SelPad pad;
+    int64_t C; // classes the bitmap covers (all classes, or the node's)
     int B, K, M;
     int32_t *cand;
-    int32_t *active_idx, *n_active, *target_pos;
+    int32_t *active_idx, *n_active, *n_found, *target_pos;
     int32_t *dev_status;
 };
 template <int NT> __device__ __forceinline__ void ks_sel_next_fetch(const KsSelNext &s, int block) {
     const int64_t t = (int64_t)block * NT + threadIdx.x;
     if (t >= (int64_t)s.B * (s.K + 1)) return;
     const int i = (int)(t / (s.K + 1)), r = (int)(t % (s.K + 1));
-    s.cand[(int64_t)r * s.B + i] = s.src.cand(i, r, s.dev_status);
+    s.cand[(int64_t)r * s.B + i] = s.csr_source ? s.csr.cand(i, r, s.dev_status) : s.dense.cand(i, r, s.dev_status);
+}
+template <int NT> __device__ __forceinline__ void ks_sel_next_select(const KsSelNext &s, uint32_t *lds, int g) {
+    sel1_body<NT>(lds, s.cand, s.C, s.B, s.K, s.M, s.csr_source, s.pad, s.active_idx, s.n_active, s.n_found, s.target_pos,
+                  s.nsel, g);
 }

@@ -19,39 +19,6 @@
 #define SEL_NONE 0x7fffffff
 #define SEL_LDS_BINS 2048
 
-struct SelCsr {
-    const int32_t *labels, *counts;
-    const int64_t *offsets;
-    const int32_t *flat;
-    int64_t Cg, c0, C, flat_len; // classes of the whole problem; first class and number of classes of this node
-    int K;                       // upper bound of the list lengths
-    static constexpr bool kForeignLabels = true; // labels of other nodes' classes have no target here
-    __device__ __forceinline__ int32_t cand(int i, int r, int32_t *dev_status) const {
-        const int32_t y = labels[i];
-        if (y < 0 || y >= Cg) {
-            if (r == 0) ks_flag(dev_status, KS_DEV_BAD_LABEL);
-            return -1;
-        }
-        if (r == 0) {
-            const int64_t l = (int64_t)y - c0;
-            return (l >= 0 && l < C) ? (int32_t)l : -1;
-        }
-        const int32_t n = counts[y];
-        if (r - 1 >= n) return -1;
-        const int64_t off = offsets[y];
-        if (n > K || off < 0 || off + n > flat_len) { // a list longer than promised or outside the array: not read
-            if (r == 1) ks_flag(dev_status, KS_DEV_BAD_COUNT);
-            return -1;
-        }
-        int32_t c = flat[off + (r - 1)];
-        if (c < -1 || c >= C) {
-            ks_flag(dev_status, KS_DEV_BAD_GRAPH_ID);
-            c = -1;
-        }
-        return c;
-    }
-};
-
 struct SelPlan {
     int r_star;    // classes with score < r_star are all kept
     int quota;     // number of classes with score == r_star that are kept (lowest ids)

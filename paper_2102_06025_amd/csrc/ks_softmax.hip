@@ -1095,10 +1095,7 @@ dw_async_kernel(const uint16_t *__restrict__ dZT, const uint16_t *__restrict__ X
     // few hundred tiles this launch leaves compute units idle, and being first they start at once.
     const int bid = (int)blockIdx.x - next.nsel;
     if (bid < 0) {
-        SelPad none;
-        none.on = 0; none.b = 1; none.mask = 1u; none.s_lo = none.s_hi = 0u;
-        sel1_body<T::NT>((uint32_t *)lds, next.cand, next.src.C, next.B, next.K, next.M, 0, none, next.active_idx, next.n_active,
-                         nullptr, next.target_pos, next.nsel, (int)blockIdx.x);
+        ks_sel_next_select<T::NT>(next, (uint32_t *)lds, (int)blockIdx.x);
         return;
     }
     if (bid >= tiles_max) { // reduction blocks
@@ -1635,6 +1632,8 @@ extern "C" int knn_softmax_fwd_stats(const uint16_t *W_bf16, const uint16_t *X_b
                                      void *ws, size_t ws_bytes, int32_t *dev_status, void *stream) {
     if (!W_bf16 || !X_bf16 || !active_idx || !n_active || !target_pos || !row_max || !row_sumexp || !target_logit || !ws)
         return KS_INVALID_ARG;
+    const bool trusted = (flags & KS_FLAG_TRUSTED_LIST) != 0;
+    flags &= ~(uint32_t)KS_FLAG_TRUSTED_LIST;
     int rc = sm_split_check(C, D, B, M, scale, flags);
     if (rc != KS_OK) return rc;
     size_t need = 0;
@@ -1642,41 +1641,130 @@ extern "C" int knn_softmax_fwd_stats(const uint16_t *W_bf16, const uint16_t *X_b
     if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
     const int nmax = M > B ? M : B;
-    hipLaunchKernelGGL(sm_sanitize_kernel, dim3((unsigned)ks_ceil_div(nmax, SM_NT)), dim3(SM_NT), 0, st, active_idx, n_active,
-                       target_pos, C, M, B, s.act, s.n, s.tp, dev_status);
+    if (!trusted) {
+        hipLaunchKernelGGL(sm_sanitize_kernel, dim3((unsigned)ks_ceil_div(nmax, SM_NT)), dim3(SM_NT), 0, st, active_idx,
+                           n_active, target_pos, C, M, B, s.act, s.n, s.tp, dev_status);
+        active_idx = s.act;
+        n_active = s.n;
+        target_pos = s.tp;
+    }
     SmSplitIO io = SmSplitIO();
     io.row_max = row_max;
     io.row_sum = row_sumexp;
     io.tz_out = target_logit;
-    return sm_run(W_bf16, X_bf16, D, B, M, scale, 1.f, s.act, s.n, s.tp, nullptr, nullptr, nullptr, nullptr, s.w, flags,
-                  dev_status, st, nullptr, SM_EXPORT, io);
+    return sm_run(W_bf16, X_bf16, D, B, M, scale, 1.f, active_idx, n_active, target_pos, nullptr, nullptr, nullptr, nullptr, s.w,
+                  flags, dev_status, st, nullptr, SM_EXPORT, io);
 }
 
+// the next batch's selection on the node's compressed graph that rides along with the second call of a split (nullptr: none)
+struct SmNextCsr {
+    const int32_t *labels, *counts;
+    const int64_t *offsets;
+    const int32_t *flat;
+    int64_t flat_len, Cg, c0;
+    int K_max;
+    uint32_t sel_flags;
+    uint64_t pad_seed;
+    int32_t *active_idx, *n_active, *n_found, *target_pos;
+};
+static int sm_bwd_from_stats(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *active_idx, const int32_t *n_active,
+                             const int32_t *target_pos, const float *global_max, const float *global_sumexp,
+                             const float *global_target_logit, int64_t C, int D, int B, int M, float scale, float grad_scale,
+                             uint32_t flags, float *loss_per_sample, float *loss_mean, float *dX, float *dW_active,
+                             const SmNextCsr *nx, void *ws, size_t ws_bytes, int32_t *dev_status, void *stream) {
+    if (!W_bf16 || !X_bf16 || !active_idx || !n_active || !target_pos || !global_max || !global_sumexp ||
+        !global_target_logit || !loss_per_sample || !loss_mean || !dX || !dW_active || !ws)
+        return KS_INVALID_ARG;
+    const bool trusted = (flags & KS_FLAG_TRUSTED_LIST) != 0;
+    flags &= ~(uint32_t)KS_FLAG_TRUSTED_LIST;
+    int rc = sm_split_check(C, D, B, M, scale, flags);
+    if (rc != KS_OK) return rc;
+    if (!(grad_scale > 0.f)) return KS_INVALID_ARG;
+    if (nx) { // the conditions of knn_select_active_csr
+        if (!nx->labels || !nx->counts || !nx->offsets || !nx->active_idx || !nx->n_active || !nx->target_pos) return KS_INVALID_ARG;
+        if (nx->Cg < 1 || nx->Cg >= (int64_t)1 << 31 || nx->c0 < 0 || nx->c0 + C > nx->Cg) return KS_INVALID_ARG;
+        if (nx->K_max < 0 || nx->flat_len < 0 || (nx->flat_len > 0 && !nx->flat)) return KS_INVALID_ARG;
+        if (B > M || (int64_t)nx->K_max + 1 > M) return KS_INVALID_ARG;
+        if (nx->sel_flags & ~(uint32_t)KS_FLAG_PAD_RANDOM) return KS_INVALID_ARG;
+        if (trusted && (nx->active_idx == active_idx || nx->n_active == n_active || nx->target_pos == target_pos))
+            return KS_INVALID_ARG; // a trusted list is read in place: the next one needs buffers of its own
+    }
+    size_t need = 0;
+    SmSplitWs s = sm_split_carve(ws, C, D, B, M, &need);
+    if (nx) need = ks_align_up(need, 256);
+    void *sel_ws = (char *)ws + need;
+    if (nx) need += ks_select_ws_bytes(C, B, nx->K_max);
+    if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    const int nmax = M > B ? M : B;
+    if (!trusted) {
+        hipLaunchKernelGGL(sm_sanitize_kernel, dim3((unsigned)ks_ceil_div(nmax, SM_NT)), dim3(SM_NT), 0, st, active_idx,
+                           n_active, target_pos, C, M, B, s.act, s.n, s.tp, dev_status);
+        active_idx = s.act;
+        n_active = s.n;
+        target_pos = s.tp;
+    }
+    SmSplitIO io = SmSplitIO();
+    io.gmax = global_max;
+    io.gsum = global_sumexp;
+    io.gtz = global_target_logit;
+    KsSelNext next = KsSelNext();
+    const bool ride = nx && C <= (int64_t)SEL1_MAX_WORDS * 32;
+    if (ride) {
+        next.nsel = SEL1_GRID;
+        next.csr_source = 1;
+        next.csr = SelCsr{nx->labels, nx->counts, nx->offsets, nx->flat, nx->Cg, nx->c0, C, nx->flat_len, nx->K_max};
+        next.pad = sel_pad_make((nx->sel_flags & KS_FLAG_PAD_RANDOM) != 0, C, nx->pad_seed);
+        next.C = C;
+        next.B = B;
+        next.K = nx->K_max;
+        next.M = M;
+        next.cand = (int32_t *)sel_ws;
+        next.active_idx = nx->active_idx;
+        next.n_active = nx->n_active;
+        next.n_found = nx->n_found;
+        next.target_pos = nx->target_pos;
+        next.dev_status = dev_status;
+    }
+    rc = sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, active_idx, n_active, target_pos, loss_per_sample, loss_mean, dX,
+                dW_active, s.w, flags, dev_status, st, nullptr, SM_IMPORT, io, DwUpdate(), ride ? &next : nullptr);
+    if (rc == KS_OK && nx && !ride)
+        rc = knn_select_active_csr(nx->labels, nx->counts, nx->offsets, nx->flat, nx->flat_len, nx->Cg, nx->c0, C, B, nx->K_max, M,
+                                   nx->sel_flags, nx->pad_seed, nx->active_idx, nx->n_active, nx->n_found, nx->target_pos, sel_ws,
+                                   ks_select_ws_bytes(C, B, nx->K_max), dev_status, stream);
+    return rc;
+}
 extern "C" int knn_softmax_bwd_from_stats(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *active_idx,
                                           const int32_t *n_active, const int32_t *target_pos, const float *global_max,
                                           const float *global_sumexp, const float *global_target_logit, int64_t C, int D,
                                           int B, int M, float scale, float grad_scale, uint32_t flags,
                                           float *loss_per_sample, float *loss_mean, float *dX, float *dW_active, void *ws,
                                           size_t ws_bytes, int32_t *dev_status, void *stream) {
-    if (!W_bf16 || !X_bf16 || !active_idx || !n_active || !target_pos || !global_max || !global_sumexp ||
-        !global_target_logit || !loss_per_sample || !loss_mean || !dX || !dW_active || !ws)
-        return KS_INVALID_ARG;
-    int rc = sm_split_check(C, D, B, M, scale, flags);
-    if (rc != KS_OK) return rc;
-    if (!(grad_scale > 0.f)) return KS_INVALID_ARG;
-    size_t need = 0;
-    SmSplitWs s = sm_split_carve(ws, C, D, B, M, &need);
-    if (ws_bytes < need) return KS_WORKSPACE_TOO_SMALL;
-    hipStream_t st = (hipStream_t)stream;
-    const int nmax = M > B ? M : B;
-    hipLaunchKernelGGL(sm_sanitize_kernel, dim3((unsigned)ks_ceil_div(nmax, SM_NT)), dim3(SM_NT), 0, st, active_idx, n_active,
-                       target_pos, C, M, B, s.act, s.n, s.tp, dev_status);
-    SmSplitIO io = SmSplitIO();
-    io.gmax = global_max;
-    io.gsum = global_sumexp;
-    io.gtz = global_target_logit;
-    return sm_run(W_bf16, X_bf16, D, B, M, scale, grad_scale, s.act, s.n, s.tp, loss_per_sample, loss_mean, dX, dW_active,
-                  s.w, flags, dev_status, st, nullptr, SM_IMPORT, io);
+    return sm_bwd_from_stats(W_bf16, X_bf16, active_idx, n_active, target_pos, global_max, global_sumexp, global_target_logit,
+                             C, D, B, M, scale, grad_scale, flags, loss_per_sample, loss_mean, dX, dW_active, nullptr, ws,
+                             ws_bytes, dev_status, stream);
+}
+extern "C" size_t knn_softmax_split_next_workspace(int64_t C, int D, int B, int K_max, int M) {
+    if (sm_split_check(C, D, B, M, 1.f, 0) != KS_OK || K_max < 0) return 0;
+    size_t total = 0;
+    sm_split_carve(nullptr, C, D, B, M, &total);
+    return ks_align_up(total, 256) + ks_select_ws_bytes(C, B, K_max);
+}
+extern "C" int knn_softmax_bwd_from_stats_next(const uint16_t *W_bf16, const uint16_t *X_bf16, const int32_t *active_idx,
+                                               const int32_t *n_active, const int32_t *target_pos, const float *global_max,
+                                               const float *global_sumexp, const float *global_target_logit, int64_t C, int D,
+                                               int B, int M, float scale, float grad_scale, uint32_t flags,
+                                               float *loss_per_sample, float *loss_mean, float *dX, float *dW_active,
+                                               const int32_t *labels_next, const int32_t *counts, const int64_t *offsets,
+                                               const int32_t *flat, int64_t flat_len, int64_t Cg, int64_t c0, int K_max,
+                                               uint32_t select_flags, uint64_t pad_seed, int32_t *active_idx_next,
+                                               int32_t *n_active_next, int32_t *n_found_next, int32_t *target_pos_next,
+                                               void *ws, size_t ws_bytes, int32_t *dev_status, void *stream) {
+    SmNextCsr nx{labels_next, counts, offsets, flat, flat_len, Cg, c0, K_max, select_flags, pad_seed, active_idx_next,
+                 n_active_next, n_found_next, target_pos_next};
+    return sm_bwd_from_stats(W_bf16, X_bf16, active_idx, n_active, target_pos, global_max, global_sumexp, global_target_logit,
+                             C, D, B, M, scale, grad_scale, flags, loss_per_sample, loss_mean, dX, dW_active, &nx, ws, ws_bytes,
+                             dev_status, stream);
 }
 
 // The step on a selection computed earlier (possibly on another stream): sanitised copy of the list, then everything
@@ -1746,7 +1834,9 @@ static int sm_selected(float *W_master, uint16_t *W_bf16, const uint16_t *X_bf16
     const bool ride = nx && fast && C <= (int64_t)SEL1_MAX_WORDS * 32;
     if (ride) {
         next.nsel = SEL1_GRID;
-        next.src = SelDense{nx->labels, nx->graph, C, nx->K};
+        next.dense = SelDense{nx->labels, nx->graph, C, nx->K};
+        next.pad = sel_pad_make(0, C, 0);
+        next.C = C;
         next.B = B;
         next.K = nx->K;
         next.M = M;

@@ -31,7 +31,7 @@ def test_header_symbols_are_exported(ks):
     assert {"knn_graph_build", "knn_softmax_fwd_bwd", "apply_weight_grad", "apply_weight_grad_normalized",
             "knn_normalize_rows", "knn_norm_backward_rows", "grad_topk_plan", "grad_topk_workspace",
             "grad_topk_select", "knn_select_active_static", "knn_softmax_fwd_bwd_update_selected_next",
-            "knn_softmax_selected_next_workspace"} <= set(names)
+            "knn_softmax_selected_next_workspace", "knn_softmax_bwd_from_stats_next", "knn_softmax_split_next_workspace"} <= set(names)
     L = ks.lib()
     for n in names:
         assert hasattr(L, n), f"{n} declared in the header but not exported"
@@ -175,6 +175,23 @@ def test_argument_errors_are_reported_before_any_launch(ks):
     assert nxt(ws_bytes=1024) == ks.KS_WORKSPACE_TOO_SMALL
     assert ks.knn_softmax_selected_next_workspace(1000, 128, 8, 4, 64) >= ks.knn_softmax_selected_workspace(1000, 128, 8, 64) + 8 * 5 * 4
     assert ks.knn_softmax_selected_next_workspace(1000, 100, 8, 4, 64) == 0
+
+    def split_next(labels_next=one, counts=one, K_max=4, c0=100, Cg=2000, sel_flags=0, flags=0, act_next=two, ws_bytes=1 << 30,
+                   D=128):
+        return L.knn_softmax_bwd_from_stats_next(one, one, one, one, one, one, one, one, i64(1000), i(D), i(8), i(64), f(30.0),
+                                                 f(1.0), ct.c_uint32(flags), one, one, one, one, labels_next, counts, one, one,
+                                                 i64(10), i64(Cg), i64(c0), i(K_max), ct.c_uint32(sel_flags), ct.c_uint64(1),
+                                                 act_next, two, null, two, one, sz(ws_bytes), null, null)
+
+    assert split_next(labels_next=null) == ks.KS_INVALID_ARG
+    assert split_next(counts=null) == ks.KS_INVALID_ARG
+    assert split_next(c0=1500) == ks.KS_INVALID_ARG          # the node's range sticks out of the problem
+    assert split_next(K_max=64) == ks.KS_INVALID_ARG         # K_max + 1 > M
+    assert split_next(sel_flags=1) == ks.KS_INVALID_ARG      # only the fill-up flag belongs to the selection
+    assert split_next(flags=4, act_next=one) == ks.KS_INVALID_ARG   # trusted list: the next one needs its own buffers
+    assert split_next(D=96) == ks.KS_UNSUPPORTED
+    assert split_next(ws_bytes=1024) == ks.KS_WORKSPACE_TOO_SMALL
+    assert ks.knn_softmax_split_next_workspace(1000, 128, 8, 4, 64) >= ks.knn_softmax_split_workspace(1000, 128, 8, 64) + 8 * 5 * 4
 
 
 def test_product_never_imports_the_oracle():

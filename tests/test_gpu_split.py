@@ -229,3 +229,68 @@ def test_split_node_of_the_headline_shard_size(ks, orc):
     ref["lse"] = oM.astype(np.float32).astype(np.float64) + np.log(oS.astype(np.float32).astype(np.float64))
     check_step_grads(s2["dX"].cpu().numpy(), s2["dW_active"][:n].cpu().numpy(), ref, W[a[:n]], X, t, scale, gs,
                      tag="headline node")
+
+
+@pytest.mark.parametrize("Cg,D,K,B,M,P,pad,trusted,unit_rows", [
+    (40_000, 128, 16, 128, 2048, 4, False, False, True), (40_000, 128, 16, 128, 2048, 4, True, True, True),
+    (9_000, 256, 8, 64, 400, 3, True, False, False), (1_600_000, 64, 8, 96, 1024, 4, False, True, True)])
+def test_node_loop_with_the_next_selection_inside_the_second_call(ks, Cg, D, K, B, M, P, pad, trusted, unit_rows):
+    """One node of a P-node layer over three batches: knn_softmax_fwd_stats + knn_softmax_bwd_from_stats_next (the next
+    batch's selection on the compressed graph inside the second call's launches, with and without the fill-up, the
+    list in place or trusted and alternating) against knn_select_active_csr + the two plain calls: lists, counts,
+    losses, dX and dW_active bit for bit.  The last case is a node of 400,000 classes (the selection follows the step)."""
+    rng = np.random.default_rng(Cg + D)
+    c0, C_loc = Cg // P, Cg // P
+    W = synth.unit_rows(3, synth.TID_W, C_loc, D, bf16=True)
+    X = synth.unit_rows(3, synth.TID_X, B, D, bf16=True)
+    c = np.arange(Cg, dtype=np.int64)[:, None]
+    k = np.arange(K, dtype=np.int64)[None, :]
+    G = ((c + 1 + (c * 2654435761 + k * 40503) % (Cg - 1)) % Cg).astype(np.int32)
+    Wd, Xd, Gd = dev(W, torch.bfloat16), dev(X, torch.bfloat16), dev(G)
+    counts, offsets, flat, st = ks.knn_graph_compress(Gd, c0, C_loc)
+    ys = [dev(rng.integers(0, Cg, B).astype(np.int32)) for _ in range(4)]
+    scale, gs = 30.0, 16.0
+
+    def exchange(s1):  # stand-in for the all-reduce: the same on both sides
+        return s1["row_max"].clone(), s1["row_sumexp"] * 4.0, s1["target_logit"].clone()
+
+    ref = []
+    for t in range(3):
+        sel = ks.knn_select_active_csr(ys[t], counts, offsets, flat, c0, C_loc, K, M, pad_random=pad, pad_seed=100 + t)
+        s1 = ks.knn_softmax_fwd_stats(Wd, Xd, sel["active_idx"], sel["n_active"], sel["target_pos"], scale, unit_rows=unit_rows)
+        gm, gsum, gtz = exchange(s1)
+        s2 = ks.knn_softmax_bwd_from_stats(Wd, Xd, sel["active_idx"], sel["n_active"], sel["target_pos"], gm, gsum, gtz, scale, gs,
+                                           s1["ws"], unit_rows=unit_rows)
+        torch.cuda.synchronize()
+        assert int(sel["dev_status"].item()) == 0 and int(s2["dev_status"].item()) == 0
+        ref.append((sel, s2))
+    sel3 = ks.knn_select_active_csr(ys[3], counts, offsets, flat, c0, C_loc, K, M, pad_random=pad, pad_seed=103)
+    first = ks.knn_select_active_csr(ys[0], counts, offsets, flat, c0, C_loc, K, M, pad_random=pad, pad_seed=100)
+    cur = dict(active_idx=first["active_idx"], n_active=first["n_active"], n_found=first["n_found"].clone(),
+               target_pos=first["target_pos"])
+    other = {k_: torch.empty_like(v) for k_, v in cur.items()}
+    ws = torch.empty(ks.knn_softmax_split_next_workspace(C_loc, D, B, K, M), dtype=torch.uint8, device="cuda")
+    for t in range(3):
+        print(f"[case] node step {t}: Cg={Cg} D={D} pad={pad} trusted={trusted}", flush=True)
+        sel_ref, s2_ref = ref[t]
+        torch.cuda.synchronize()
+        assert torch.equal(cur["active_idx"], sel_ref["active_idx"]) and torch.equal(cur["n_active"], sel_ref["n_active"])
+        assert torch.equal(cur["target_pos"], sel_ref["target_pos"]) and torch.equal(cur["n_found"], sel_ref["n_found"])
+        s1 = ks.knn_softmax_fwd_stats(Wd, Xd, cur["active_idx"], cur["n_active"], cur["target_pos"], scale, unit_rows=unit_rows,
+                                      ws=ws, trusted_list=trusted)
+        gm, gsum, gtz = exchange(s1)
+        nxt = other if trusted else cur
+        s2, _ = ks.knn_softmax_bwd_from_stats_next(Wd, Xd, cur["active_idx"], cur["n_active"], cur["target_pos"], gm, gsum, gtz, scale,
+                                                   gs, ws, ys[t + 1], counts, offsets, flat, c0, K, next_out=nxt, pad_random=pad,
+                                                   pad_seed=100 + t + 1, unit_rows=unit_rows, trusted_list=trusted)
+        torch.cuda.synchronize()
+        assert int(s2["dev_status"].item()) == 0
+        n = int(sel_ref["n_active"].item())
+        assert torch.equal(s2["loss_per_sample"], s2_ref["loss_per_sample"]) and torch.equal(s2["dX"], s2_ref["dX"])
+        assert torch.equal(s2["dW_active"][:n], s2_ref["dW_active"][:n])
+        if trusted:
+            cur, other = other, cur
+    torch.cuda.synchronize()
+    assert torch.equal(cur["active_idx"], sel3["active_idx"]) and torch.equal(cur["n_active"], sel3["n_active"])
+    assert torch.equal(cur["target_pos"], sel3["target_pos"]) and torch.equal(cur["n_found"], sel3["n_found"])
+    assert int(st.item()) == 0
