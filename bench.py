@@ -589,14 +589,45 @@ def main():
             step_normalized()
         torch.cuda.synchronize()
         ms_norm_step = (time.perf_counter() - t0) * 1e3 / args.steps
+        # the same as a training loop runs it: the next batch's selection inside the softmax call (W_master = NULL: the
+        # gradient rows are stored for the update through the normalisation), lists read in place, two sets in turn
+        nl = [{k_: out[k_].clone() for k_ in ("active_idx", "n_active", "target_pos")} for _ in range(2)]
+        nl_ws = torch.empty(ks.knn_softmax_selected_next_workspace(C, D, B, K, M), dtype=torch.uint8, device="cuda")
+        nl_out = {k_: out[k_] for k_ in ("loss_per_sample", "loss_mean", "dX", "dW_active", "dev_status")}
+
+        def step_normalized_next():
+            a, b = nl
+            ks.knn_normalize_rows(X_raw, want_inv_norm=False, out_bf16=X_bf)
+            ks.knn_softmax_fwd_bwd_update_selected_next(None, W_bf, X_bf, a["active_idx"], a["n_active"], a["target_pos"], labels,
+                                                        graph, scale, grad_scale, 0.0, next_out=b, out=nl_out, ws=nl_ws,
+                                                        unit_rows=True, trusted_list=True)
+            ks.knn_norm_backward_rows(X_raw, out["dX"], out=dX_raw)
+            ks.apply_weight_grad_normalized(W_master, W_bf, inv_norm, a["active_idx"], a["n_active"], out["dW_active"], alpha,
+                                            idx_sorted_unique=True, ws=ws, dev_status=out["dev_status"])
+            nl.reverse()
+
+        for _ in range(args.warmup):
+            step_normalized_next()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            step_normalized_next()
+        torch.cuda.synchronize()
+        ms_norm_next = (time.perf_counter() - t0) * 1e3 / args.steps
+        del nl_ws
         us_apply_n = timed_events(lambda: ks.apply_weight_grad_normalized(
             W_master, W_bf, inv_norm, out["active_idx"], out["n_active"], out["dW_active"], alpha, idx_sorted_unique=True,
             ws=ws, dev_status=out["dev_status"]), args.steps, warm=0)
         assert int(out["dev_status"].item()) == 0
         normalized_layer = dict(ms_per_step=round(ms_norm_step, 4), samples_per_s=round(B / (ms_norm_step * 1e-3), 1),
                                 step="normalize X + select + knn_softmax_fwd_bwd + project dX + apply_weight_grad_normalized",
+                                ms_per_step_next_selection_inside=round(ms_norm_next, 4),
+                                step_next_selection_inside="normalize X + knn_softmax_fwd_bwd_update_selected_next without update "
+                                                           "(selects the next batch inside) + project dX + "
+                                                           "apply_weight_grad_normalized",
                                 apply_normalized=hbm_entry(us_apply_n, A * (D * (4.0 + 4.0 + 4.0 + 2.0) + 4.0)))
-        log(f"[bench] layer with normalisation inside: {ms_norm_step:.4f} ms/step, apply_normalized {us_apply_n:.1f} us")
+        log(f"[bench] layer with normalisation inside: {ms_norm_step:.4f} ms/step ({ms_norm_next:.4f} with the next selection "
+            f"inside), apply_normalized {us_apply_n:.1f} us")
 
     # ---- this GPU as one node of four (Section 3.2.3): graph compression and selection on the compressed graph,
     # with and without the random fill-up to M (Algorithm 1); integer work, bit-exact against the oracle in the tests
