@@ -1375,7 +1375,7 @@ static int sm_run(const uint16_t *W, const uint16_t *X, int D, int B, int64_t M,
                   SmSplitIO io = SmSplitIO(), DwUpdate up = DwUpdate(), const KsSelNext *next_p = nullptr) {
     auto mark = [&](int k) { if (ev) (void)hipEventRecord(ev[k], st); };
     KsSelNext next = KsSelNext();
-    if (next_p) next = *next_p; // (the caller has checked that this path takes it: w.fast and a whole step)
+    if (next_p) next = *next_p; // (the caller has checked that this path takes it: w.fast, and the dX and dW launches are made)
     if (mode != SM_WHOLE && !w.fast) return KS_UNSUPPORTED;
     if (mode == SM_EXPORT) loss_per_sample = w.inv; // not known before the exchange: the kernels' loss output is scratch
     const int Mi = (int)M;
