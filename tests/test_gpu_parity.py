@@ -646,7 +646,9 @@ def test_step_on_an_earlier_selection_equals_the_one_call_step(ks, orc, name, un
     ("the table path", dict(C=400_000, D=128, B=64, K=8, M=1_024), True, True, False),
     ("one sample", dict(C=300, D=64, B=1, K=3, M=4), False, True, False),
     ("lists as long as M allows", dict(C=3_000, D=128, B=5, K=7, M=8), True, False, True),
-    ("batch not a power of two, 393,216 classes", dict(C=393_216, D=64, B=100, K=5, M=600), True, False, True)])
+    ("batch not a power of two, 393,216 classes", dict(C=393_216, D=64, B=100, K=5, M=600), True, False, True),
+    ("a large batch", dict(C=200_000, D=128, B=3000, K=32, M=65_536, labels="zipf"), True, False, True),
+    ("a large batch, the cut bites", dict(C=200_000, D=128, B=4096, K=32, M=20_000), True, True, False)])
 def test_selection_of_the_next_batch_rides_along_with_the_step(ks, orc, name, shape, unit_rows, in_place, trusted):
     """A loop of knn_softmax_fwd_bwd_update_selected_next calls (the step on this batch's list, the next batch's list
     made by extra workgroups of the same launches) against a loop of one-call steps on the same batches: every
